@@ -1,0 +1,196 @@
+/*
+ * hif8.h -- C ABI of libhif8: HiFloat8 (HiF8) conversion kernels for AMD MI355X (gfx950).
+ *
+ * The format and the rounding methods are those of "Ascend HiFloat8 Format for
+ * Deep Learning" (arXiv 2409.16626):
+ *   Sec. 2.1, Tables 1-3   field layout: sign | dot (prefix code) | exponent Em | mantissa
+ *   Eq. (1), Eq. (2)       value of normal / denormal codes; Zero, NaN, +-Inf patterns
+ *   Sec. 3.1               rounding half away from zero (TA)
+ *   Sec. 3.2, Eq. (3)      hybrid rounding (HR): TA if |E| < 4, else simplified stochastic
+ *                          rounding (SR14 for FP32 sources, SR2 for 16-bit sources)
+ *   Sec. 3 (options)       saturation on overflow, NaN to zero
+ *   Sec. 5 (PTS)           per-tensor amax, scale factor, scale before / descale after
+ *
+ * General conventions (apply to every entry point unless stated otherwise)
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *     allocates nothing and frees nothing.  The only state it keeps is a set of
+ *     small read-only lookup tables in static device memory, written once per
+ *     device by hif8_init().
+ *   - Calls only enqueue work on `stream` and return; they never synchronise
+ *     (exception: the first call on a device, see hif8_init) and never read
+ *     results back to the host.
+ *   - Element counts are size_t; kernels index with 64 bits.
+ *   - bfloat16 tensors are passed as raw uint16_t bit patterns.
+ *   - Any pointer alignment and any n are accepted.  The fast path needs the
+ *     source 16-byte aligned and the destination(s) aligned to their per-lane
+ *     store width (4 B for u8 codes of an FP32 source, 8 B for u8 codes of a
+ *     BF16 source, 16 B for FP32 / BF16 outputs); otherwise a slower
+ *     element-per-lane kernel computes the same result.
+ *   - n == 0 is valid and enqueues nothing (hif8_amax_* still writes 0).
+ *   - Return value: HIF8_OK, or a negative hif8_status.  On error nothing has
+ *     been enqueued.
+ *   - Semantics, with fl32() = IEEE binary32 round-to-nearest-even and Q() the
+ *     HiF8 rounding selected by `mode`:
+ *         encode      dst[i] = code( Q( fl32( widen(src[i]) * scale ) ) )
+ *         decode      dst[i] = narrow( fl32( value(src[i]) * fl32(1/scale) ) )
+ *         fake_quant  dst[i] = decode(encode(src[i])) with the same scale
+ *     narrow() to BF16 is round-to-nearest-even.  value(NaN code) is the quiet
+ *     NaN 0x7FC00000 (BF16 0x7FC0), value(Inf codes) is +-Inf, value(0x00) is
+ *     +0.0.  scale = 1 gives the paper's plain cast.
+ *   - `scale` must be finite and > 0, and 1/scale must be finite and > 0,
+ *     else HIF8_ERR_SCALE.
+ */
+#ifndef HIF8_H_
+#define HIF8_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* opaque HIP stream handle (hipStream_t); 0 / NULL is the default stream */
+typedef void* hif8_stream_t;
+
+typedef int hif8_status;
+enum {
+  HIF8_OK = 0,
+  HIF8_ERR_NULL = -1,  /* a required pointer is NULL                      */
+  HIF8_ERR_MODE = -2,  /* unknown rounding method or unknown flag bits    */
+  HIF8_ERR_SCALE = -3, /* scale (or 1/scale) not finite and positive      */
+  HIF8_ERR_HIP = -4,   /* a HIP call failed; see hif8_last_hip_error()    */
+  HIF8_ERR_ARG = -5    /* any other invalid argument                      */
+};
+
+/* rounding_mode bit-field */
+#define HIF8_RM_TA 0u            /* Sec. 3.1: round half away from zero                        */
+#define HIF8_RM_HR 1u            /* Eq. (3): TA if |E| < 4, else SR14 (FP32 src) / SR2 (BF16) */
+#define HIF8_RM_MASK 0xFu        /* values 2..15 reserved                                      */
+#define HIF8_FLAG_SAT 0x10u      /* overflow and +-Inf input -> +-2^15 instead of +-Inf        */
+#define HIF8_FLAG_NAN2ZERO 0x20u /* NaN input -> 0x00 instead of 0x80                          */
+
+/* Largest finite HiF8 magnitude (Table 4: max positive normal = 2^15). */
+#define HIF8_MAX_FINITE 32768.0f
+
+/* Library version, major*10000 + minor*100 + patch. */
+int hif8_version(void);
+
+/* Raw hipError_t of the most recent failing HIP call on this thread (0 if none). */
+int hif8_last_hip_error(void);
+
+/*
+ * Writes the read-only lookup tables (FP32 pattern -> code for TA, code -> value)
+ * into static device memory of the CURRENT device and waits for that to finish.
+ * Idempotent and thread-safe.  Every other entry point calls it lazily on first
+ * use of a device (that one call synchronises `stream`); callers that must not
+ * synchronise later -- e.g. under HIP graph capture -- call hif8_init() once per
+ * device beforehand.
+ */
+hif8_status hif8_init(void);
+
+/*
+ * Per-tensor amax (Sec. 5, per-tensor scaling): *d_amax = max_i |src[i]|.
+ * The maximum is taken over the magnitude bit patterns as unsigned integers, so
+ * Inf dominates finite values and any NaN dominates Inf (the result is then a NaN).
+ * d_amax: one device float, overwritten (the call clears it on the stream first).
+ */
+hif8_status hif8_amax_f32(const float* src, size_t n, float* d_amax, hif8_stream_t stream);
+hif8_status hif8_amax_bf16(const uint16_t* src, size_t n, float* d_amax, hif8_stream_t stream);
+
+/*
+ * Scale factor from a device-resident amax, without a host round trip
+ * (Sec. 5: scale each tensor "to a better range that can be represented by HiF8";
+ * power-of-two factors avoid extra rounding error).
+ *   d_scale2[0] = scale = fl32(target / amax), or with pow2 != 0 the largest power
+ *                 of two not above it; amax zero, Inf or NaN (or a quotient that
+ *                 is not finite and positive) gives scale = 1.
+ *   d_scale2[1] = fl32(1 / scale).
+ * d_amax: one device float (input).  d_scale2: two device floats (output).
+ */
+hif8_status hif8_scale_from_amax(const float* d_amax, float* d_scale2, float target, int pow2,
+                                 hif8_stream_t stream);
+
+/*
+ * Encode (Sec. 3; Tables 1-3): n source values -> n packed u8 HiF8 codes.
+ * src and dst must not overlap.
+ */
+hif8_status hif8_encode_f32(const float* src, uint8_t* dst, size_t n, float scale,
+                            uint32_t rounding_mode, hif8_stream_t stream);
+hif8_status hif8_encode_bf16(const uint16_t* src, uint8_t* dst, size_t n, float scale,
+                             uint32_t rounding_mode, hif8_stream_t stream);
+
+/*
+ * Decode (Eq. (1), Eq. (2), special patterns): n u8 codes -> n values, descaled.
+ * src and dst must not overlap.
+ */
+hif8_status hif8_decode_f32(const uint8_t* src, float* dst, size_t n, float scale,
+                            hif8_stream_t stream);
+hif8_status hif8_decode_bf16(const uint8_t* src, uint16_t* dst, size_t n, float scale,
+                             hif8_stream_t stream);
+
+/*
+ * Fake quantisation (Sec. 4: tensors "converted ... to only those [values] that
+ * could be represented in HiF8"): encode and decode fused in registers.
+ * dst may equal src (in place).  codes_or_null, if not NULL, also receives the
+ * n u8 codes and must not overlap src or dst.
+ */
+hif8_status hif8_fake_quant_f32(const float* src, float* dst, uint8_t* codes_or_null, size_t n,
+                                float scale, uint32_t rounding_mode, hif8_stream_t stream);
+hif8_status hif8_fake_quant_bf16(const uint16_t* src, uint16_t* dst, uint8_t* codes_or_null,
+                                 size_t n, float scale, uint32_t rounding_mode,
+                                 hif8_stream_t stream);
+
+/*
+ * Device-scale ("_ds") variants: identical to the calls above except that the
+ * scale pair is read by the kernel from d_scale2 = {scale, fl32(1/scale)} in
+ * device memory, as written by hif8_scale_from_amax on the same stream.  The
+ * values are not validated (the host never sees them).
+ */
+hif8_status hif8_encode_f32_ds(const float* src, uint8_t* dst, size_t n, const float* d_scale2,
+                               uint32_t rounding_mode, hif8_stream_t stream);
+hif8_status hif8_encode_bf16_ds(const uint16_t* src, uint8_t* dst, size_t n,
+                                const float* d_scale2, uint32_t rounding_mode,
+                                hif8_stream_t stream);
+hif8_status hif8_decode_f32_ds(const uint8_t* src, float* dst, size_t n, const float* d_scale2,
+                               hif8_stream_t stream);
+hif8_status hif8_decode_bf16_ds(const uint8_t* src, uint16_t* dst, size_t n,
+                                const float* d_scale2, hif8_stream_t stream);
+hif8_status hif8_fake_quant_f32_ds(const float* src, float* dst, uint8_t* codes_or_null, size_t n,
+                                   const float* d_scale2, uint32_t rounding_mode,
+                                   hif8_stream_t stream);
+hif8_status hif8_fake_quant_bf16_ds(const uint16_t* src, uint16_t* dst, uint8_t* codes_or_null,
+                                    size_t n, const float* d_scale2, uint32_t rounding_mode,
+                                    hif8_stream_t stream);
+
+/*
+ * Launch-shape tuning knobs (process-wide; for benchmarking and profiling).
+ *   HIF8_TUNE_BLOCK     threads per workgroup of the streaming kernels (64..1024, multiple of 64)
+ *   HIF8_TUNE_WG_PER_CU persistent workgroups launched per compute unit (1..32)
+ *   HIF8_TUNE_UNROLL    16-byte loads in flight per lane (1, 2, 4 or 8)
+ *   HIF8_TUNE_TA_IMPL   0 = TA encode through the LDS lookup table, 1 = TA encode in ALU only
+ * Returns HIF8_ERR_ARG for an unknown key or a value outside the stated range.
+ */
+enum {
+  HIF8_TUNE_BLOCK = 0,
+  HIF8_TUNE_WG_PER_CU = 1,
+  HIF8_TUNE_UNROLL = 2,
+  HIF8_TUNE_TA_IMPL = 3
+};
+hif8_status hif8_set_tuning(int key, int value);
+int hif8_get_tuning(int key); /* -1 for an unknown key */
+
+/*
+ * Diagnostic stream kernel with the same read:write mix as a conversion
+ * (read in_bytes_per_lane = 16 per lane, write out_bytes_per_lane in {4, 8, 16}),
+ * used by the benchmark as the practical bandwidth ceiling of the machine.
+ * Copies the low bytes of each 16-byte group: dst group g = first out_bytes of src group g.
+ * n_groups 16-byte groups are read.  src 16-byte aligned, dst aligned to out_bytes.
+ */
+hif8_status hif8_diag_stream(const void* src, void* dst, size_t n_groups, int out_bytes_per_lane,
+                             hif8_stream_t stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HIF8_H_ */
