@@ -1,0 +1,232 @@
+"""Benchmark of the HiF8 conversion hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-extra] [--no-cpu]
+
+Headline (the one JSON line on stdout): config 2 of the baseline, the dynamic-range sweep --
+67,108,864 FP32 values encoded to u8 HiF8 codes, scale = 1, rounding half away from zero.
+One step = one hif8_encode_f32 pass over one such tensor; steps rotate over several
+distinct resident tensors so that no pass is served from the 256 MB last-level cache.
+value = algorithmic bytes (4 B read + 1 B written per element) * steps / wall time.
+
+The same line carries
+  roofline      algorithmic bytes per launch / average launch duration (HIP events on the
+                launch stream over the timed region) against the 8 TB/s HBM peak;
+  cpu_baseline  the CPU oracle (oracle/, untouched) timed on the host cores on the same input;
+  extra         the other rows of the hot path (amax, decode, fused fake-quant pipeline,
+                gradient tensor TA / HR, LLM weight cast, same-mix stream ceiling).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def timed(fn, steps, warmup):
+    """Runs fn(i) warmup + steps times; returns (wall ms per step, event ms per step)."""
+    import torch
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(steps):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+
+def rate(bytes_per_step, ms):
+    gbs = bytes_per_step / (ms * 1e-3) / 1e9
+    return {"ms": round(ms, 5), "GB/s": round(gbs, 1), "frac_of_8TBs": round(gbs / HBM_PEAK_GBS, 4)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-extra", action="store_true", help="skip the secondary workloads")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--buffers", type=int, default=6, help="distinct resident input tensors to rotate over")
+    ap.add_argument("--tune", type=str, default="", help="block,wg_per_cu,unroll,ta_impl")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
+                 "(no collectives, sharding or rank code exist here)" % args.gpus)
+
+    import numpy as np
+    import torch
+    from paper_2409_16626_amd import hif8, workloads
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    hif8.hif8_init()
+    if args.tune:
+        for k, v in enumerate(int(t) for t in args.tune.split(",")):
+            hif8.hif8_set_tuning(k, v)
+    tune = [hif8.hif8_get_tuning(k) for k in range(4)]
+
+    # ---------------- headline: C2 encode_f32, TA, scale 1 ----------------
+    n = 1 << 26
+    x0 = workloads.dynamic_range_sweep(n, dev)
+    xs = [x0] + [torch.roll(x0, 1009 * (i + 1)) for i in range(args.buffers - 1)]
+    outs = [torch.empty(n, dtype=torch.uint8, device=dev) for _ in range(args.buffers)]
+    R = args.buffers
+
+    def step(i):
+        hif8.hif8_encode_f32(xs[i % R], outs[i % R], n, 1.0, hif8.RM_TA)
+
+    wall_ms, ev_ms = timed(step, args.steps, args.warmup)
+    bytes_step = 5 * n
+    value = bytes_step / (wall_ms * 1e-3) / 1e9
+    achieved = bytes_step / (ev_ms * 1e-3) / 1e9
+    log("C2 encode_f32 TA: wall %.4f ms/step, events %.4f ms/launch, %.1f GB/s" % (wall_ms, ev_ms, achieved))
+
+    result = {
+        "metric": "HiF8 encode GB/s (FP32 -> u8 codes, TA, algorithmic 5 B/element) on 1 MI355X",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u8",
+        "data": "synthetic",
+        "config": {"workload": "C2 dynamic-range sweep: 67,108,864 FP32 = +-2^U[-30,20] with 1% short-mantissa ties, "
+                               "hif8_encode_f32, scale=1, rounding half away from zero",
+                   "elements": n, "elements_per_s": round(n / (wall_ms * 1e-3), 0),
+                   "rotating_buffers": R, "tuning_block_wgpercu_unroll_impl": tune},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "k_encode_f32<U,TA_LUT>", "bytes_per_launch": bytes_step,
+                     "avg_launch_ms": round(ev_ms, 5)},
+    }
+
+    # ---------------- CPU oracle baseline on the same input ----------------
+    if not args.no_cpu:
+        from oracle import hif8_oracle as orc
+        sample = x0.cpu().numpy()
+        orc.encode_f32(sample[:1 << 20], 1.0, orc.RM_TA)  # warm up threads / table
+        t0 = time.perf_counter()
+        want = orc.encode_f32(sample, 1.0, orc.RM_TA)
+        dt = time.perf_counter() - t0
+        got = outs[0].cpu().numpy() if (args.steps + args.warmup) >= 1 else None
+        hif8.hif8_encode_f32(xs[0], outs[0], n, 1.0, hif8.RM_TA)
+        torch.cuda.synchronize()
+        mism = int(np.count_nonzero(outs[0].cpu().numpy() != want))
+        result["cpu_baseline"] = {"value": round(5 * n / dt / 1e9, 3), "unit": "GB/s", "cores": orc.threads_used(),
+                                  "kind": "oracle", "sample": "the whole C2 tensor (67,108,864 elements), %.2f s wall" % dt,
+                                  "elements_per_s": round(n / dt, 0), "gpu_vs_oracle_mismatches": mism}
+        log("oracle: %.2f s on %d threads; mismatches vs GPU: %d" % (dt, orc.threads_used(), mism))
+        del sample, want
+
+    # ---------------- the other rows of the hot path ----------------
+    if not args.no_extra:
+        extra = {}
+        K, W = max(20, args.steps // 4), 5
+
+        # same-mix stream ceiling (read 16 B, write 4 B per lane)
+        w_ms, e_ms = timed(lambda i: hif8.hif8_diag_stream(xs[i % R], outs[i % R], n // 4, 4), K, W)
+        extra["stream_r16_w4 (ceiling for FP32 encode)"] = rate(5 * n, e_ms)
+
+        # amax FP32 (read only)
+        am = torch.zeros(1, dtype=torch.float32, device=dev)
+        w_ms, e_ms = timed(lambda i: hif8.hif8_amax_f32(xs[i % R], n, am), K, W)
+        extra["amax_f32 C2 (4 B/elem)"] = rate(4 * n, e_ms)
+
+        # decode to FP32 (1 B in, 4 B out)
+        dec = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(2)]
+        w_ms, e_ms = timed(lambda i: hif8.hif8_decode_f32(outs[i % R], dec[i % 2], n, 1.0), K, W)
+        extra["decode_f32 C2 codes (5 B/elem)"] = rate(5 * n, e_ms)
+        del dec
+
+        # HR on the C2 tensor
+        w_ms, e_ms = timed(lambda i: hif8.hif8_encode_f32(xs[i % R], outs[i % R], n, 1.0, hif8.RM_HR), K, W)
+        extra["encode_f32 HR C2 (5 B/elem)"] = rate(5 * n, e_ms)
+        del xs, outs, x0
+        torch.cuda.empty_cache()
+
+        # C3: BF16 activation, amax -> scale -> fused fake-quant with codes
+        a0 = workloads.activation_bf16(8192, 8192, dev).view(-1)
+        m = a0.numel()
+        acts = [a0] + [torch.roll(a0, 4099 * (i + 1)) for i in range(R - 1)]
+        fq = [torch.empty_like(a0) for _ in range(R)]
+        cds = [torch.empty(m, dtype=torch.uint8, device=dev) for _ in range(R)]
+        sc = torch.zeros(2, dtype=torch.float32, device=dev)
+
+        def c3(i):
+            j = i % R
+            hif8.hif8_amax_bf16(acts[j], m, am)
+            hif8.hif8_scale_from_amax(am, sc, hif8.MAX_FINITE, 0)
+            hif8.hif8_fake_quant_bf16_ds(acts[j], fq[j], cds[j], m, sc, hif8.RM_TA)
+
+        w_ms, e_ms = timed(c3, K, W)
+        extra["C3 amax+scale+fake_quant_bf16 (5 B/elem primary)"] = rate(5 * m, e_ms)
+        extra["C3 amax+scale+fake_quant_bf16 (7 B/elem with amax pass)"] = rate(7 * m, e_ms)
+        w_ms, e_ms = timed(lambda i: hif8.hif8_fake_quant_bf16_ds(acts[i % R], fq[i % R], cds[i % R], m, sc, hif8.RM_TA), K, W)
+        extra["fake_quant_bf16 alone (5 B/elem)"] = rate(5 * m, e_ms)
+        w_ms, e_ms = timed(lambda i: hif8.hif8_amax_bf16(acts[i % R], m, am), K, W)
+        extra["amax_bf16 (2 B/elem)"] = rate(2 * m, e_ms)
+        w_ms, e_ms = timed(lambda i: hif8.hif8_encode_bf16_ds(acts[i % R], cds[i % R], m, sc, hif8.RM_TA), K, W)
+        extra["encode_bf16 (3 B/elem)"] = rate(3 * m, e_ms)
+        w_ms, e_ms = timed(lambda i: hif8.hif8_diag_stream(acts[i % R], cds[i % R], m // 8, 8), K, W)
+        extra["stream_r16_w8 (ceiling for BF16 encode)"] = rate(3 * m, e_ms)
+        del acts, fq, cds, a0
+        torch.cuda.empty_cache()
+
+        # C4: gradient tensor, 2^30 FP32, TA and HR
+        g = workloads.gradient_f32(1 << 30, dev)
+        gc = torch.empty(g.numel(), dtype=torch.uint8, device=dev)
+        for name, mode in (("TA", hif8.RM_TA), ("HR", hif8.RM_HR)):
+            w_ms, e_ms = timed(lambda i: hif8.hif8_encode_f32(g, gc, g.numel(), 1.0, mode), 10, 2)
+            extra["C4 encode_f32 %s 2^30 (5 B/elem)" % name] = rate(5 * g.numel(), e_ms)
+        del g, gc
+        torch.cuda.empty_cache()
+
+        # C5: LLM weight cast, 225 BF16 tensors, amax -> scale -> encode back to back
+        arena, index = workloads.llm_weights_bf16(dev)
+        wc = torch.empty(arena.numel(), dtype=torch.uint8, device=dev)
+        ams = torch.zeros(len(index), dtype=torch.float32, device=dev)
+        scs = torch.zeros(len(index), 2, dtype=torch.float32, device=dev)
+        ap, cp, amp, scp = arena.data_ptr(), wc.data_ptr(), ams.data_ptr(), scs.data_ptr()
+
+        def c5(i):
+            for t, (_, off, cnt) in enumerate(index):
+                hif8.hif8_amax_bf16(ap + 2 * off, cnt, amp + 4 * t)
+                hif8.hif8_scale_from_amax(amp + 4 * t, scp + 8 * t, hif8.MAX_FINITE, 0)
+                hif8.hif8_encode_bf16_ds(ap + 2 * off, cp + off, cnt, scp + 8 * t, hif8.RM_TA)
+
+        w_ms, e_ms = timed(c5, 5, 1)
+        tot = arena.numel()
+        extra["C5 225-tensor amax+scale+encode_bf16 (3 B/elem primary)"] = rate(3 * tot, e_ms)
+        extra["C5 225-tensor amax+scale+encode_bf16 (5 B/elem with amax pass)"] = rate(5 * tot, e_ms)
+        extra["C5 wall ms per cast of all weights"] = round(w_ms, 3)
+        result["extra"] = extra
+        for k, v in extra.items():
+            log("%-64s %s" % (k, v))
+
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

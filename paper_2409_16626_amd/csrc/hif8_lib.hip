@@ -1,0 +1,828 @@
+// libhif8: HiF8 (HiFloat8, arXiv 2409.16626) conversion kernels for MI355X (gfx950) and the
+// C ABI declared in include/hif8.h.
+//
+// All kernels are HBM-streaming scans: every lane moves 16 bytes per load, a persistent
+// grid (a few workgroups per compute unit) strides over the tensor, U independent loads
+// are in flight per lane.  There is no contraction anywhere, hence no MFMA.
+//
+//   encode, TA   : the TA code of a non-NaN binary32 value depends only on its top 13 bits
+//                  (sign, exponent, 3 kept + 1 rounding mantissa bit), so the hot loop is one
+//                  shift and one byte lookup in an 8 KiB table staged in LDS.  The table
+//                  itself is produced on the device, once, by the integer encoder below.
+//   encode, HR   : integer rounding in registers (round_mag), then the same byte lookup.
+//   decode       : 256-entry binary32 table staged in LDS, one multiply by 1/scale.
+//   fake-quant   : encode and decode fused; the value never leaves registers.
+//   amax         : unsigned max of magnitude patterns; DPP reduction inside a wavefront,
+//                  LDS across wavefronts, one atomic max per workgroup.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <mutex>
+
+#include "hif8.h"
+#include "hif8_device.hpp"
+
+using namespace hif8dev;
+
+// ------------------------------------------------------------------------------------
+// static device tables (written once per device by k_build_tables)
+// ------------------------------------------------------------------------------------
+static __device__ __attribute__((aligned(16))) uint8_t g_enc_lut[2][8192];  // [sat][pattern >> 19]
+static __device__ __attribute__((aligned(16))) uint32_t g_dec_lut[256];     // code -> binary32 bits
+
+__global__ void k_build_tables() {
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < 8192u) {
+    g_enc_lut[0][i] = (uint8_t)encode_alu<false, false>(i << 19, 0u);
+    g_enc_lut[1][i] = (uint8_t)encode_alu<false, false>(i << 19, kFlagSat);
+  }
+  if (i < 256u) g_dec_lut[i] = decode_bits(i);
+}
+
+// ------------------------------------------------------------------------------------
+// small device helpers
+// ------------------------------------------------------------------------------------
+enum : int { IMPL_TA_LUT = 0, IMPL_TA_ALU = 1, IMPL_HR = 2 };
+
+__device__ __forceinline__ void stage_enc_lut(uint8_t* lut, uint32_t mode) {
+  const uint4* g = reinterpret_cast<const uint4*>(g_enc_lut[(mode & kFlagSat) ? 1 : 0]);
+  uint4* l = reinterpret_cast<uint4*>(lut);
+  for (uint32_t i = threadIdx.x; i < 8192u / 16u; i += blockDim.x) l[i] = g[i];
+}
+__device__ __forceinline__ void stage_dec_lut(uint32_t* lut) {
+  for (uint32_t i = threadIdx.x; i < 256u; i += blockDim.x) lut[i] = g_dec_lut[i];
+}
+
+// One element: scaled pattern -> code.  `lut` is the staged TA table (unused for IMPL_TA_ALU).
+template <int IMPL, bool SRC16>
+__device__ __forceinline__ uint32_t encode_one(uint32_t ybits, const uint8_t* lut, uint32_t mode) {
+  if (IMPL == IMPL_TA_LUT) {
+    uint32_t c = lut[ybits >> 19];
+    // NaNs whose payload sits only in the low 19 bits index the Inf entry; fix them here.
+    if ((ybits & 0x7FFFFFFFu) > 0x7F800000u) c = nan_code(mode);
+    return c;
+  } else if (IMPL == IMPL_TA_ALU) {
+    return encode_alu<false, SRC16>(ybits, mode);
+  } else {
+    // HR: integer rounding, then the byte of the (now representable) pattern from the table
+    const uint32_t a = ybits & 0x7FFFFFFFu;
+    const uint32_t r = round_mag<true, SRC16>(a > 0x7F800000u ? 0u : a, ybits);
+    uint32_t c = lut[(r | (ybits & 0x80000000u)) >> 19];
+    if (a > 0x7F800000u) c = nan_code(mode);
+    return c;
+  }
+}
+
+__device__ __forceinline__ uint32_t scaled_bits(uint32_t xbits, float scale) {
+  return __float_as_uint(__fmul_rn(__uint_as_float(xbits), scale));
+}
+
+template <int IMPL>
+__device__ __forceinline__ uint32_t encode4_f32(const uint4& v, float scale, const uint8_t* lut,
+                                               uint32_t mode) {
+  const uint32_t c0 = encode_one<IMPL, false>(scaled_bits(v.x, scale), lut, mode);
+  const uint32_t c1 = encode_one<IMPL, false>(scaled_bits(v.y, scale), lut, mode);
+  const uint32_t c2 = encode_one<IMPL, false>(scaled_bits(v.z, scale), lut, mode);
+  const uint32_t c3 = encode_one<IMPL, false>(scaled_bits(v.w, scale), lut, mode);
+  return c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
+}
+
+// two bfloat16 in one dword -> two codes in the low 16 bits
+template <int IMPL>
+__device__ __forceinline__ uint32_t encode2_bf16(uint32_t w, float scale, const uint8_t* lut,
+                                                uint32_t mode) {
+  const uint32_t c0 = encode_one<IMPL, true>(scaled_bits(w << 16, scale), lut, mode);
+  const uint32_t c1 = encode_one<IMPL, true>(scaled_bits(w & 0xFFFF0000u, scale), lut, mode);
+  return c0 | (c1 << 8);
+}
+
+template <int IMPL>
+__device__ __forceinline__ uint2 encode8_bf16(const uint4& v, float scale, const uint8_t* lut,
+                                              uint32_t mode) {
+  uint2 o;
+  o.x = encode2_bf16<IMPL>(v.x, scale, lut, mode) | (encode2_bf16<IMPL>(v.y, scale, lut, mode) << 16);
+  o.y = encode2_bf16<IMPL>(v.z, scale, lut, mode) | (encode2_bf16<IMPL>(v.w, scale, lut, mode) << 16);
+  return o;
+}
+
+__device__ __forceinline__ uint32_t descale_bits(uint32_t code, const uint32_t* dec, float inv) {
+  return __float_as_uint(__fmul_rn(__uint_as_float(dec[code & 0xFFu]), inv));
+}
+
+__device__ __forceinline__ uint32_t descale2_bf16(uint32_t c0, uint32_t c1, const uint32_t* dec,
+                                                  float inv) {
+  return narrow_bf16(descale_bits(c0, dec, inv)) | (narrow_bf16(descale_bits(c1, dec, inv)) << 16);
+}
+
+// ------------------------------------------------------------------------------------
+// streaming kernels.  Vector unit = one 16-byte source load per lane (decode: one lane's
+// worth of codes).  A tile is blockDim.x * U vector units; blocks stride over tiles.
+// The ragged tail (n modulo the vector width) is done element-wise by block 0.
+// ------------------------------------------------------------------------------------
+template <int U, typename V, typename LoadF, typename StoreF>
+__device__ __forceinline__ void tile_loop(size_t nvec, LoadF load, StoreF store) {
+  const size_t tile = (size_t)blockDim.x * U;
+  for (size_t base = (size_t)blockIdx.x * tile; base < nvec; base += (size_t)gridDim.x * tile) {
+    V v[U];
+    const size_t first = base + threadIdx.x;
+    if (base + tile <= nvec) {  // full tile: U independent loads in flight, then U stores
+#pragma unroll
+      for (int j = 0; j < U; ++j) v[j] = load(first + (size_t)j * blockDim.x);
+#pragma unroll
+      for (int j = 0; j < U; ++j) store(first + (size_t)j * blockDim.x, v[j]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < U; ++j) {
+        const size_t idx = first + (size_t)j * blockDim.x;
+        if (idx < nvec) v[j] = load(idx);
+      }
+#pragma unroll
+      for (int j = 0; j < U; ++j) {
+        const size_t idx = first + (size_t)j * blockDim.x;
+        if (idx < nvec) store(idx, v[j]);
+      }
+    }
+  }
+}
+
+template <int U, int IMPL>
+__global__ void __launch_bounds__(1024)
+k_encode_f32(const float* __restrict__ src, uint8_t* __restrict__ dst, size_t n, float scale_arg,
+             const float* __restrict__ d_scale2, uint32_t mode) {
+  __shared__ __attribute__((aligned(16))) uint8_t lut[IMPL == IMPL_TA_ALU ? 16 : 8192];
+  const float scale = d_scale2 ? d_scale2[0] : scale_arg;
+  if (IMPL != IMPL_TA_ALU) {
+    stage_enc_lut(lut, mode);
+    __syncthreads();
+  }
+  const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(src);
+  uint32_t* __restrict__ dst4 = reinterpret_cast<uint32_t*>(dst);
+  const size_t nvec = n >> 2;
+  tile_loop<U, uint4>(
+      nvec, [&](size_t idx) { return src4[idx]; },
+      [&](size_t idx, const uint4& v) { dst4[idx] = encode4_f32<IMPL>(v, scale, lut, mode); });
+  const size_t t = (nvec << 2) + threadIdx.x;
+  if (blockIdx.x == 0 && t < n)
+    dst[t] = (uint8_t)encode_one<IMPL, false>(scaled_bits(__float_as_uint(src[t]), scale), lut, mode);
+}
+
+template <int U, int IMPL>
+__global__ void __launch_bounds__(1024)
+k_encode_bf16(const uint16_t* __restrict__ src, uint8_t* __restrict__ dst, size_t n,
+              float scale_arg, const float* __restrict__ d_scale2, uint32_t mode) {
+  __shared__ __attribute__((aligned(16))) uint8_t lut[IMPL == IMPL_TA_ALU ? 16 : 8192];
+  const float scale = d_scale2 ? d_scale2[0] : scale_arg;
+  if (IMPL != IMPL_TA_ALU) {
+    stage_enc_lut(lut, mode);
+    __syncthreads();
+  }
+  const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(src);
+  uint2* __restrict__ dst8 = reinterpret_cast<uint2*>(dst);
+  const size_t nvec = n >> 3;
+  tile_loop<U, uint4>(
+      nvec, [&](size_t idx) { return src4[idx]; },
+      [&](size_t idx, const uint4& v) { dst8[idx] = encode8_bf16<IMPL>(v, scale, lut, mode); });
+  const size_t t = (nvec << 3) + threadIdx.x;
+  if (blockIdx.x == 0 && t < n)
+    dst[t] = (uint8_t)encode_one<IMPL, true>(scaled_bits((uint32_t)src[t] << 16, scale), lut, mode);
+}
+
+template <int U>
+__global__ void __launch_bounds__(1024)
+k_decode_f32(const uint8_t* __restrict__ src, float* __restrict__ dst, size_t n, float inv_arg,
+             const float* __restrict__ d_scale2) {
+  __shared__ uint32_t dec[256];
+  const float inv = d_scale2 ? d_scale2[1] : inv_arg;  // fl32(1/scale), computed by the host
+  stage_dec_lut(dec);
+  __syncthreads();
+  const uint32_t* __restrict__ src4 = reinterpret_cast<const uint32_t*>(src);
+  uint4* __restrict__ dst4 = reinterpret_cast<uint4*>(dst);
+  const size_t nvec = n >> 2;
+  tile_loop<U, uint32_t>(
+      nvec, [&](size_t idx) { return src4[idx]; },
+      [&](size_t idx, uint32_t w) {
+        uint4 o;
+        o.x = descale_bits(w, dec, inv);
+        o.y = descale_bits(w >> 8, dec, inv);
+        o.z = descale_bits(w >> 16, dec, inv);
+        o.w = descale_bits(w >> 24, dec, inv);
+        dst4[idx] = o;
+      });
+  const size_t t = (nvec << 2) + threadIdx.x;
+  if (blockIdx.x == 0 && t < n) dst[t] = __uint_as_float(descale_bits(src[t], dec, inv));
+}
+
+template <int U>
+__global__ void __launch_bounds__(1024)
+k_decode_bf16(const uint8_t* __restrict__ src, uint16_t* __restrict__ dst, size_t n,
+              float inv_arg, const float* __restrict__ d_scale2) {
+  __shared__ uint32_t dec[256];
+  const float inv = d_scale2 ? d_scale2[1] : inv_arg;
+  stage_dec_lut(dec);
+  __syncthreads();
+  const uint2* __restrict__ src8 = reinterpret_cast<const uint2*>(src);
+  uint4* __restrict__ dst16 = reinterpret_cast<uint4*>(dst);
+  const size_t nvec = n >> 3;
+  tile_loop<U, uint2>(
+      nvec, [&](size_t idx) { return src8[idx]; },
+      [&](size_t idx, const uint2& w) {
+        uint4 o;
+        o.x = descale2_bf16(w.x, w.x >> 8, dec, inv);
+        o.y = descale2_bf16(w.x >> 16, w.x >> 24, dec, inv);
+        o.z = descale2_bf16(w.y, w.y >> 8, dec, inv);
+        o.w = descale2_bf16(w.y >> 16, w.y >> 24, dec, inv);
+        dst16[idx] = o;
+      });
+  const size_t t = (nvec << 3) + threadIdx.x;
+  if (blockIdx.x == 0 && t < n) dst[t] = (uint16_t)narrow_bf16(descale_bits(src[t], dec, inv));
+}
+
+// fake-quant: src and dst may alias (each lane reads its own vectors before it writes them)
+template <int U, int IMPL, bool CODES>
+__global__ void __launch_bounds__(1024)
+k_fake_quant_f32(const float* src, float* dst, uint8_t* codes, size_t n, float scale_arg,
+                 float inv_arg, const float* __restrict__ d_scale2, uint32_t mode) {
+  __shared__ __attribute__((aligned(16))) uint8_t lut[IMPL == IMPL_TA_ALU ? 16 : 8192];
+  __shared__ uint32_t dec[256];
+  const float scale = d_scale2 ? d_scale2[0] : scale_arg;
+  const float inv = d_scale2 ? d_scale2[1] : inv_arg;
+  if (IMPL != IMPL_TA_ALU) stage_enc_lut(lut, mode);
+  stage_dec_lut(dec);
+  __syncthreads();
+  const uint4* src4 = reinterpret_cast<const uint4*>(src);
+  uint4* dst4 = reinterpret_cast<uint4*>(dst);
+  uint32_t* codes4 = reinterpret_cast<uint32_t*>(codes);
+  const size_t nvec = n >> 2;
+  tile_loop<U, uint4>(
+      nvec, [&](size_t idx) { return src4[idx]; },
+      [&](size_t idx, const uint4& v) {
+        const uint32_t w = encode4_f32<IMPL>(v, scale, lut, mode);
+        uint4 o;
+        o.x = descale_bits(w, dec, inv);
+        o.y = descale_bits(w >> 8, dec, inv);
+        o.z = descale_bits(w >> 16, dec, inv);
+        o.w = descale_bits(w >> 24, dec, inv);
+        dst4[idx] = o;
+        if (CODES) codes4[idx] = w;
+      });
+  const size_t t = (nvec << 2) + threadIdx.x;
+  if (blockIdx.x == 0 && t < n) {
+    const uint32_t c = encode_one<IMPL, false>(scaled_bits(__float_as_uint(src[t]), scale), lut, mode);
+    dst[t] = __uint_as_float(descale_bits(c, dec, inv));
+    if (CODES) codes[t] = (uint8_t)c;
+  }
+}
+
+template <int U, int IMPL, bool CODES>
+__global__ void __launch_bounds__(1024)
+k_fake_quant_bf16(const uint16_t* src, uint16_t* dst, uint8_t* codes, size_t n, float scale_arg,
+                  float inv_arg, const float* __restrict__ d_scale2, uint32_t mode) {
+  __shared__ __attribute__((aligned(16))) uint8_t lut[IMPL == IMPL_TA_ALU ? 16 : 8192];
+  __shared__ uint32_t dec[256];
+  const float scale = d_scale2 ? d_scale2[0] : scale_arg;
+  const float inv = d_scale2 ? d_scale2[1] : inv_arg;
+  if (IMPL != IMPL_TA_ALU) stage_enc_lut(lut, mode);
+  stage_dec_lut(dec);
+  __syncthreads();
+  const uint4* src4 = reinterpret_cast<const uint4*>(src);
+  uint4* dst4 = reinterpret_cast<uint4*>(dst);
+  uint2* codes8 = reinterpret_cast<uint2*>(codes);
+  const size_t nvec = n >> 3;
+  tile_loop<U, uint4>(
+      nvec, [&](size_t idx) { return src4[idx]; },
+      [&](size_t idx, const uint4& v) {
+        const uint2 w = encode8_bf16<IMPL>(v, scale, lut, mode);
+        uint4 o;
+        o.x = descale2_bf16(w.x, w.x >> 8, dec, inv);
+        o.y = descale2_bf16(w.x >> 16, w.x >> 24, dec, inv);
+        o.z = descale2_bf16(w.y, w.y >> 8, dec, inv);
+        o.w = descale2_bf16(w.y >> 16, w.y >> 24, dec, inv);
+        dst4[idx] = o;
+        if (CODES) codes8[idx] = w;
+      });
+  const size_t t = (nvec << 3) + threadIdx.x;
+  if (blockIdx.x == 0 && t < n) {
+    const uint32_t c = encode_one<IMPL, true>(scaled_bits((uint32_t)src[t] << 16, scale), lut, mode);
+    dst[t] = (uint16_t)narrow_bf16(descale_bits(c, dec, inv));
+    if (CODES) codes[t] = (uint8_t)c;
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// element-per-lane kernels for pointers that do not meet the fast path's alignment
+// ------------------------------------------------------------------------------------
+template <bool SRC16>
+__device__ __forceinline__ uint32_t load_scaled(const void* src, size_t i, float scale) {
+  const uint32_t xb = SRC16 ? ((uint32_t) reinterpret_cast<const uint16_t*>(src)[i] << 16)
+                            : __float_as_uint(reinterpret_cast<const float*>(src)[i]);
+  return scaled_bits(xb, scale);
+}
+template <bool SRC16>
+__device__ __forceinline__ uint32_t encode_any(uint32_t yb, uint32_t mode) {
+  return ((mode & 0xFu) == HIF8_RM_HR) ? encode_alu<true, SRC16>(yb, mode)
+                                       : encode_alu<false, SRC16>(yb, mode);
+}
+
+template <bool SRC16>
+__global__ void __launch_bounds__(256)
+k_encode_elem(const void* src, uint8_t* dst, size_t n, float scale_arg, const float* d_scale2,
+              uint32_t mode) {
+  const float scale = d_scale2 ? d_scale2[0] : scale_arg;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = (uint8_t)encode_any<SRC16>(load_scaled<SRC16>(src, i, scale), mode);
+}
+
+template <bool DST16>
+__global__ void __launch_bounds__(256)
+k_decode_elem(const uint8_t* src, void* dst, size_t n, float inv_arg, const float* d_scale2) {
+  const float inv = d_scale2 ? d_scale2[1] : inv_arg;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x) {
+    const uint32_t b = __float_as_uint(__fmul_rn(__uint_as_float(decode_bits(src[i])), inv));
+    if (DST16) reinterpret_cast<uint16_t*>(dst)[i] = (uint16_t)narrow_bf16(b);
+    else reinterpret_cast<uint32_t*>(dst)[i] = b;
+  }
+}
+
+template <bool T16>
+__global__ void __launch_bounds__(256)
+k_fake_quant_elem(const void* src, void* dst, uint8_t* codes, size_t n, float scale_arg,
+                  float inv_arg, const float* d_scale2, uint32_t mode) {
+  const float scale = d_scale2 ? d_scale2[0] : scale_arg;
+  const float inv = d_scale2 ? d_scale2[1] : inv_arg;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x) {
+    const uint32_t c = encode_any<T16>(load_scaled<T16>(src, i, scale), mode);
+    const uint32_t b = __float_as_uint(__fmul_rn(__uint_as_float(decode_bits(c)), inv));
+    if (T16) reinterpret_cast<uint16_t*>(dst)[i] = (uint16_t)narrow_bf16(b);
+    else reinterpret_cast<uint32_t*>(dst)[i] = b;
+    if (codes) codes[i] = (uint8_t)c;
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// amax
+// ------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+
+// Maximum over the 64 lanes of a wavefront with DPP row shifts and row broadcasts; the
+// result is valid in lane 63 and returned to every lane through a scalar read of that lane.
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+  v = umax(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x111, 0xF, 0xF, false));  // row_shr:1
+  v = umax(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x112, 0xF, 0xF, false));  // row_shr:2
+  v = umax(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x114, 0xF, 0xF, false));  // row_shr:4
+  v = umax(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x118, 0xF, 0xF, false));  // row_shr:8
+  v = umax(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x142, 0xF, 0xF, false));  // row_bcast:15
+  v = umax(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x143, 0xF, 0xF, false));  // row_bcast:31
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
+__device__ __forceinline__ void block_max_to_global(uint32_t m, uint32_t* out) {
+  __shared__ uint32_t wave_m[16];
+  m = wave_max_u32(m);
+  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  if (lane == 0) wave_m[wave] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const uint32_t nw = (blockDim.x + 63u) >> 6;
+    uint32_t r = wave_m[0];
+    for (uint32_t w = 1; w < nw; ++w) r = umax(r, wave_m[w]);
+    if (r) atomicMax(out, r);
+  }
+}
+
+__global__ void k_fill_u32(uint32_t* p, uint32_t v, uint32_t count) {
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) p[i] = v;
+}
+
+// magnitude patterns as binary32 bits: FP32 -> bits & 0x7FFFFFFF; BF16 -> (bits & 0x7FFF) << 16
+template <int U, bool SRC16>
+__global__ void __launch_bounds__(1024)
+k_amax(const void* __restrict__ src, size_t n, uint32_t* __restrict__ out) {
+  const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(src);
+  const size_t nvec = SRC16 ? (n >> 3) : (n >> 2);
+  uint32_t m = 0;  // FP32: magnitude pattern; BF16: two 15-bit magnitudes, one per half
+  tile_loop<U, uint4>(
+      nvec, [&](size_t idx) { return src4[idx]; },
+      [&](size_t, const uint4& v) {
+        if (SRC16) {
+          typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+          u16x2 mm = __builtin_bit_cast(u16x2, m);
+          mm = __builtin_elementwise_max(mm, __builtin_bit_cast(u16x2, v.x & 0x7FFF7FFFu));
+          mm = __builtin_elementwise_max(mm, __builtin_bit_cast(u16x2, v.y & 0x7FFF7FFFu));
+          mm = __builtin_elementwise_max(mm, __builtin_bit_cast(u16x2, v.z & 0x7FFF7FFFu));
+          mm = __builtin_elementwise_max(mm, __builtin_bit_cast(u16x2, v.w & 0x7FFF7FFFu));
+          m = __builtin_bit_cast(uint32_t, mm);
+        } else {
+          m = umax(m, umax(umax(v.x & 0x7FFFFFFFu, v.y & 0x7FFFFFFFu),
+                           umax(v.z & 0x7FFFFFFFu, v.w & 0x7FFFFFFFu)));
+        }
+      });
+  if (SRC16) m = umax(m & 0xFFFFu, m >> 16) << 16;
+  const size_t t = (SRC16 ? (nvec << 3) : (nvec << 2)) + threadIdx.x;
+  if (blockIdx.x == 0 && t < n) {
+    const uint32_t a = SRC16 ? (((uint32_t) reinterpret_cast<const uint16_t*>(src)[t] & 0x7FFFu) << 16)
+                             : (__float_as_uint(reinterpret_cast<const float*>(src)[t]) & 0x7FFFFFFFu);
+    m = umax(m, a);
+  }
+  block_max_to_global(m, out);
+}
+
+template <bool SRC16>
+__global__ void __launch_bounds__(256)
+k_amax_elem(const void* __restrict__ src, size_t n, uint32_t* __restrict__ out) {
+  uint32_t m = 0;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x) {
+    const uint32_t a = SRC16 ? (((uint32_t) reinterpret_cast<const uint16_t*>(src)[i] & 0x7FFFu) << 16)
+                             : (__float_as_uint(reinterpret_cast<const float*>(src)[i]) & 0x7FFFFFFFu);
+    m = umax(m, a);
+  }
+  block_max_to_global(m, out);
+}
+
+// scale = fl32(target / amax) (optionally floored to a power of two), inverse = fl32(1 / scale)
+__global__ void k_scale_from_amax(const float* d_amax, float* d_scale2, float target, int pow2) {
+  if (blockIdx.x != 0 || threadIdx.x != 0) return;
+  const float amax = *d_amax;
+  const uint32_t ab = __float_as_uint(amax);
+  float s = 1.0f;
+  if (ab != 0u && ab < 0x7F800000u) {  // positive, finite, non-zero
+    const float q = target / amax;     // correctly rounded divide
+    const uint32_t qb = __float_as_uint(q);
+    if (qb != 0u && qb < 0x7F800000u) {
+      s = q;
+      if (pow2) {
+        if ((qb >> 23) != 0u) s = __uint_as_float(qb & 0x7F800000u);
+        else s = __uint_as_float(1u << (31 - __clz((int)qb)));  // subnormal quotient
+      }
+    }
+  }
+  d_scale2[0] = s;
+  d_scale2[1] = 1.0f / s;
+}
+
+// diagnostic stream kernel: read 16 B per lane, write the first OUT bytes of it
+template <int U, int OUT>
+__global__ void __launch_bounds__(1024)
+k_diag_stream(const uint4* __restrict__ src, void* __restrict__ dst, size_t nvec) {
+  tile_loop<U, uint4>(
+      nvec, [&](size_t idx) { return src[idx]; },
+      [&](size_t idx, const uint4& v) {
+        if (OUT == 4) reinterpret_cast<uint32_t*>(dst)[idx] = v.x;
+        else if (OUT == 8) reinterpret_cast<uint2*>(dst)[idx] = make_uint2(v.x, v.y);
+        else reinterpret_cast<uint4*>(dst)[idx] = v;
+      });
+}
+
+// ====================================================================================
+// host side: C ABI
+// ====================================================================================
+namespace {
+
+thread_local int t_last_hip_error = 0;
+
+struct Tuning {
+  int block = 512;
+  int wg_per_cu = 4;
+  int unroll = 4;
+  int ta_impl = 0;
+};
+Tuning g_tune;
+
+constexpr int kMaxDevices = 64;
+std::mutex g_init_mutex;
+bool g_inited[kMaxDevices] = {};
+int g_cu_count[kMaxDevices] = {};
+
+bool hip_ok(hipError_t e) {
+  if (e == hipSuccess) return true;
+  t_last_hip_error = (int)e;
+  return false;
+}
+
+hif8_status ensure_init(int* cu_count_out) {
+  int dev = 0;
+  if (!hip_ok(hipGetDevice(&dev))) return HIF8_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return HIF8_ERR_ARG;
+  std::lock_guard<std::mutex> lock(g_init_mutex);
+  if (!g_inited[dev]) {
+    int cus = 0;
+    if (!hip_ok(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)))
+      return HIF8_ERR_HIP;
+    if (cus <= 0) cus = 256;
+    hipLaunchKernelGGL(k_build_tables, dim3(8192 / 256), dim3(256), 0, (hipStream_t)0);
+    if (!hip_ok(hipGetLastError())) return HIF8_ERR_HIP;
+    // the null stream synchronises with every blocking stream; wait on the host as well so
+    // that non-blocking streams also see the tables
+    if (!hip_ok(hipStreamSynchronize((hipStream_t)0))) return HIF8_ERR_HIP;
+    g_cu_count[dev] = cus;
+    g_inited[dev] = true;
+  }
+  if (cu_count_out) *cu_count_out = g_cu_count[dev];
+  return HIF8_OK;
+}
+
+bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+bool valid_mode(uint32_t mode) {
+  if ((mode & ~(HIF8_RM_MASK | HIF8_FLAG_SAT | HIF8_FLAG_NAN2ZERO)) != 0) return false;
+  const uint32_t rm = mode & HIF8_RM_MASK;
+  return rm == HIF8_RM_TA || rm == HIF8_RM_HR;
+}
+
+// scale and fl32(1/scale) both finite and positive
+bool valid_scale(float scale, float* inv_out) {
+  if (!(scale > 0.0f) || std::isinf(scale)) return false;
+  volatile float inv = 1.0f / scale;
+  if (!(inv > 0.0f) || std::isinf((float)inv)) return false;
+  *inv_out = inv;
+  return true;
+}
+
+unsigned grid_for(size_t nvec, int cus) {
+  const size_t tile = (size_t)g_tune.block * (size_t)g_tune.unroll;
+  size_t tiles = (nvec + tile - 1) / tile;
+  if (tiles == 0) tiles = 1;  // block 0 still handles a ragged tail
+  const size_t cap = (size_t)cus * (size_t)g_tune.wg_per_cu;
+  return (unsigned)(tiles < cap ? tiles : cap);
+}
+
+unsigned grid_elem(size_t n, int cus) {
+  size_t blocks = (n + 255) / 256;
+  const size_t cap = (size_t)cus * 16;
+  if (blocks == 0) blocks = 1;
+  return (unsigned)(blocks < cap ? blocks : cap);
+}
+
+int impl_for(uint32_t mode) {
+  if ((mode & HIF8_RM_MASK) == HIF8_RM_HR) return IMPL_HR;
+  return g_tune.ta_impl ? IMPL_TA_ALU : IMPL_TA_LUT;
+}
+
+#define HIF8_DISPATCH_U(CALL)             \
+  switch (g_tune.unroll) {                \
+    case 1: { constexpr int U = 1; CALL; } break; \
+    case 2: { constexpr int U = 2; CALL; } break; \
+    case 8: { constexpr int U = 8; CALL; } break; \
+    default: { constexpr int U = 4; CALL; } break; \
+  }
+
+#define HIF8_DISPATCH_IMPL(IMPLV, CALL)                                   \
+  switch (IMPLV) {                                                        \
+    case IMPL_TA_ALU: { constexpr int IMPL = IMPL_TA_ALU; CALL; } break;  \
+    case IMPL_HR: { constexpr int IMPL = IMPL_HR; CALL; } break;          \
+    default: { constexpr int IMPL = IMPL_TA_LUT; CALL; } break;           \
+  }
+
+hif8_status finish_launch() { return hip_ok(hipGetLastError()) ? HIF8_OK : HIF8_ERR_HIP; }
+
+// ---- common implementations (scale either by value or from device memory) ----
+template <bool SRC16>
+hif8_status do_encode(const void* src, uint8_t* dst, size_t n, float scale, const float* d_scale2,
+                      uint32_t mode, hipStream_t st) {
+  if (!src || !dst) return HIF8_ERR_NULL;
+  if (!valid_mode(mode)) return HIF8_ERR_MODE;
+  float inv = 1.0f;
+  if (!d_scale2 && !valid_scale(scale, &inv)) return HIF8_ERR_SCALE;
+  if (n == 0) return HIF8_OK;
+  int cus = 0;
+  hif8_status s = ensure_init(&cus);
+  if (s != HIF8_OK) return s;
+  const bool fast = aligned_to(src, 16) && aligned_to(dst, SRC16 ? 8 : 4);
+  if (!fast) {
+    hipLaunchKernelGGL(k_encode_elem<SRC16>, dim3(grid_elem(n, cus)), dim3(256), 0, st, src, dst, n,
+                       scale, d_scale2, mode);
+    return finish_launch();
+  }
+  const size_t nvec = SRC16 ? (n >> 3) : (n >> 2);
+  const dim3 grid(grid_for(nvec, cus)), block(g_tune.block);
+  const int impl = impl_for(mode);
+  if (SRC16) {
+    HIF8_DISPATCH_U(HIF8_DISPATCH_IMPL(impl, hipLaunchKernelGGL((k_encode_bf16<U, IMPL>), grid, block, 0, st,
+        reinterpret_cast<const uint16_t*>(src), dst, n, scale, d_scale2, mode)))
+  } else {
+    HIF8_DISPATCH_U(HIF8_DISPATCH_IMPL(impl, hipLaunchKernelGGL((k_encode_f32<U, IMPL>), grid, block, 0, st,
+        reinterpret_cast<const float*>(src), dst, n, scale, d_scale2, mode)))
+  }
+  return finish_launch();
+}
+
+template <bool DST16>
+hif8_status do_decode(const uint8_t* src, void* dst, size_t n, float scale, const float* d_scale2,
+                      hipStream_t st) {
+  if (!src || !dst) return HIF8_ERR_NULL;
+  float inv = 1.0f;
+  if (!d_scale2 && !valid_scale(scale, &inv)) return HIF8_ERR_SCALE;
+  if (n == 0) return HIF8_OK;
+  int cus = 0;
+  hif8_status s = ensure_init(&cus);
+  if (s != HIF8_OK) return s;
+  const bool fast = aligned_to(src, DST16 ? 8 : 4) && aligned_to(dst, 16);
+  if (!fast) {
+    hipLaunchKernelGGL(k_decode_elem<DST16>, dim3(grid_elem(n, cus)), dim3(256), 0, st, src, dst, n,
+                       inv, d_scale2);
+    return finish_launch();
+  }
+  const size_t nvec = DST16 ? (n >> 3) : (n >> 2);
+  const dim3 grid(grid_for(nvec, cus)), block(g_tune.block);
+  if (DST16) {
+    HIF8_DISPATCH_U(hipLaunchKernelGGL((k_decode_bf16<U>), grid, block, 0, st, src,
+                                       reinterpret_cast<uint16_t*>(dst), n, inv, d_scale2))
+  } else {
+    HIF8_DISPATCH_U(hipLaunchKernelGGL((k_decode_f32<U>), grid, block, 0, st, src,
+                                       reinterpret_cast<float*>(dst), n, inv, d_scale2))
+  }
+  return finish_launch();
+}
+
+template <bool T16>
+hif8_status do_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, float scale,
+                          const float* d_scale2, uint32_t mode, hipStream_t st) {
+  if (!src || !dst) return HIF8_ERR_NULL;
+  if (!valid_mode(mode)) return HIF8_ERR_MODE;
+  float inv = 1.0f;
+  if (!d_scale2 && !valid_scale(scale, &inv)) return HIF8_ERR_SCALE;
+  if (n == 0) return HIF8_OK;
+  int cus = 0;
+  hif8_status s = ensure_init(&cus);
+  if (s != HIF8_OK) return s;
+  const bool fast = aligned_to(src, 16) && aligned_to(dst, 16) && (!codes || aligned_to(codes, T16 ? 8 : 4));
+  if (!fast) {
+    hipLaunchKernelGGL(k_fake_quant_elem<T16>, dim3(grid_elem(n, cus)), dim3(256), 0, st, src, dst,
+                       codes, n, scale, inv, d_scale2, mode);
+    return finish_launch();
+  }
+  const size_t nvec = T16 ? (n >> 3) : (n >> 2);
+  const dim3 grid(grid_for(nvec, cus)), block(g_tune.block);
+  const int impl = impl_for(mode);
+#define HIF8_FQ_LAUNCH(KERNEL, TS, TD, CODESV)                                                        \
+  HIF8_DISPATCH_U(HIF8_DISPATCH_IMPL(impl, hipLaunchKernelGGL((KERNEL<U, IMPL, CODESV>), grid, block, \
+      0, st, reinterpret_cast<TS>(src), reinterpret_cast<TD>(dst), codes, n, scale, inv, d_scale2, mode)))
+  if (T16) {
+    if (codes) { HIF8_FQ_LAUNCH(k_fake_quant_bf16, const uint16_t*, uint16_t*, true) }
+    else { HIF8_FQ_LAUNCH(k_fake_quant_bf16, const uint16_t*, uint16_t*, false) }
+  } else {
+    if (codes) { HIF8_FQ_LAUNCH(k_fake_quant_f32, const float*, float*, true) }
+    else { HIF8_FQ_LAUNCH(k_fake_quant_f32, const float*, float*, false) }
+  }
+#undef HIF8_FQ_LAUNCH
+  return finish_launch();
+}
+
+template <bool SRC16>
+hif8_status do_amax(const void* src, size_t n, float* d_amax, hipStream_t st) {
+  if (!d_amax || (!src && n != 0)) return HIF8_ERR_NULL;
+  int cus = 0;
+  hif8_status s = ensure_init(&cus);
+  if (s != HIF8_OK) return s;
+  uint32_t* out = reinterpret_cast<uint32_t*>(d_amax);
+  hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, out, 0u, 1u);
+  if (!hip_ok(hipGetLastError())) return HIF8_ERR_HIP;
+  if (n == 0) return HIF8_OK;
+  if (!aligned_to(src, 16)) {
+    hipLaunchKernelGGL(k_amax_elem<SRC16>, dim3(grid_elem(n, cus)), dim3(256), 0, st, src, n, out);
+    return finish_launch();
+  }
+  const size_t nvec = SRC16 ? (n >> 3) : (n >> 2);
+  const dim3 grid(grid_for(nvec, cus)), block(g_tune.block);
+  HIF8_DISPATCH_U(hipLaunchKernelGGL((k_amax<U, SRC16>), grid, block, 0, st, src, n, out))
+  return finish_launch();
+}
+
+}  // namespace
+
+extern "C" {
+
+int hif8_version(void) { return 100; }
+int hif8_last_hip_error(void) { return t_last_hip_error; }
+hif8_status hif8_init(void) { return ensure_init(nullptr); }
+
+hif8_status hif8_set_tuning(int key, int value) {
+  switch (key) {
+    case HIF8_TUNE_BLOCK:
+      if (value < 64 || value > 1024 || (value % 64) != 0) return HIF8_ERR_ARG;
+      g_tune.block = value;
+      return HIF8_OK;
+    case HIF8_TUNE_WG_PER_CU:
+      if (value < 1 || value > 32) return HIF8_ERR_ARG;
+      g_tune.wg_per_cu = value;
+      return HIF8_OK;
+    case HIF8_TUNE_UNROLL:
+      if (value != 1 && value != 2 && value != 4 && value != 8) return HIF8_ERR_ARG;
+      g_tune.unroll = value;
+      return HIF8_OK;
+    case HIF8_TUNE_TA_IMPL:
+      if (value != 0 && value != 1) return HIF8_ERR_ARG;
+      g_tune.ta_impl = value;
+      return HIF8_OK;
+    default:
+      return HIF8_ERR_ARG;
+  }
+}
+
+int hif8_get_tuning(int key) {
+  switch (key) {
+    case HIF8_TUNE_BLOCK: return g_tune.block;
+    case HIF8_TUNE_WG_PER_CU: return g_tune.wg_per_cu;
+    case HIF8_TUNE_UNROLL: return g_tune.unroll;
+    case HIF8_TUNE_TA_IMPL: return g_tune.ta_impl;
+    default: return -1;
+  }
+}
+
+hif8_status hif8_amax_f32(const float* src, size_t n, float* d_amax, hif8_stream_t stream) {
+  return do_amax<false>(src, n, d_amax, (hipStream_t)stream);
+}
+hif8_status hif8_amax_bf16(const uint16_t* src, size_t n, float* d_amax, hif8_stream_t stream) {
+  return do_amax<true>(src, n, d_amax, (hipStream_t)stream);
+}
+
+hif8_status hif8_scale_from_amax(const float* d_amax, float* d_scale2, float target, int pow2,
+                                 hif8_stream_t stream) {
+  if (!d_amax || !d_scale2) return HIF8_ERR_NULL;
+  if (!(target > 0.0f) || std::isinf(target)) return HIF8_ERR_ARG;
+  hipLaunchKernelGGL(k_scale_from_amax, dim3(1), dim3(64), 0, (hipStream_t)stream, d_amax, d_scale2,
+                     target, pow2);
+  return finish_launch();
+}
+
+hif8_status hif8_encode_f32(const float* src, uint8_t* dst, size_t n, float scale, uint32_t mode,
+                            hif8_stream_t stream) {
+  return do_encode<false>(src, dst, n, scale, nullptr, mode, (hipStream_t)stream);
+}
+hif8_status hif8_encode_bf16(const uint16_t* src, uint8_t* dst, size_t n, float scale,
+                             uint32_t mode, hif8_stream_t stream) {
+  return do_encode<true>(src, dst, n, scale, nullptr, mode, (hipStream_t)stream);
+}
+hif8_status hif8_decode_f32(const uint8_t* src, float* dst, size_t n, float scale,
+                            hif8_stream_t stream) {
+  return do_decode<false>(src, dst, n, scale, nullptr, (hipStream_t)stream);
+}
+hif8_status hif8_decode_bf16(const uint8_t* src, uint16_t* dst, size_t n, float scale,
+                             hif8_stream_t stream) {
+  return do_decode<true>(src, dst, n, scale, nullptr, (hipStream_t)stream);
+}
+hif8_status hif8_fake_quant_f32(const float* src, float* dst, uint8_t* codes, size_t n, float scale,
+                                uint32_t mode, hif8_stream_t stream) {
+  return do_fake_quant<false>(src, dst, codes, n, scale, nullptr, mode, (hipStream_t)stream);
+}
+hif8_status hif8_fake_quant_bf16(const uint16_t* src, uint16_t* dst, uint8_t* codes, size_t n,
+                                 float scale, uint32_t mode, hif8_stream_t stream) {
+  return do_fake_quant<true>(src, dst, codes, n, scale, nullptr, mode, (hipStream_t)stream);
+}
+
+hif8_status hif8_encode_f32_ds(const float* src, uint8_t* dst, size_t n, const float* d_scale2,
+                               uint32_t mode, hif8_stream_t stream) {
+  if (!d_scale2) return HIF8_ERR_NULL;
+  return do_encode<false>(src, dst, n, 1.0f, d_scale2, mode, (hipStream_t)stream);
+}
+hif8_status hif8_encode_bf16_ds(const uint16_t* src, uint8_t* dst, size_t n, const float* d_scale2,
+                                uint32_t mode, hif8_stream_t stream) {
+  if (!d_scale2) return HIF8_ERR_NULL;
+  return do_encode<true>(src, dst, n, 1.0f, d_scale2, mode, (hipStream_t)stream);
+}
+hif8_status hif8_decode_f32_ds(const uint8_t* src, float* dst, size_t n, const float* d_scale2,
+                               hif8_stream_t stream) {
+  if (!d_scale2) return HIF8_ERR_NULL;
+  return do_decode<false>(src, dst, n, 1.0f, d_scale2, (hipStream_t)stream);
+}
+hif8_status hif8_decode_bf16_ds(const uint8_t* src, uint16_t* dst, size_t n, const float* d_scale2,
+                                hif8_stream_t stream) {
+  if (!d_scale2) return HIF8_ERR_NULL;
+  return do_decode<true>(src, dst, n, 1.0f, d_scale2, (hipStream_t)stream);
+}
+hif8_status hif8_fake_quant_f32_ds(const float* src, float* dst, uint8_t* codes, size_t n,
+                                   const float* d_scale2, uint32_t mode, hif8_stream_t stream) {
+  if (!d_scale2) return HIF8_ERR_NULL;
+  return do_fake_quant<false>(src, dst, codes, n, 1.0f, d_scale2, mode, (hipStream_t)stream);
+}
+hif8_status hif8_fake_quant_bf16_ds(const uint16_t* src, uint16_t* dst, uint8_t* codes, size_t n,
+                                    const float* d_scale2, uint32_t mode, hif8_stream_t stream) {
+  if (!d_scale2) return HIF8_ERR_NULL;
+  return do_fake_quant<true>(src, dst, codes, n, 1.0f, d_scale2, mode, (hipStream_t)stream);
+}
+
+hif8_status hif8_diag_stream(const void* src, void* dst, size_t n_groups, int out_bytes,
+                             hif8_stream_t stream) {
+  if (!src || !dst) return HIF8_ERR_NULL;
+  if (out_bytes != 4 && out_bytes != 8 && out_bytes != 16) return HIF8_ERR_ARG;
+  if (!aligned_to(src, 16) || !aligned_to(dst, (size_t)out_bytes)) return HIF8_ERR_ARG;
+  if (n_groups == 0) return HIF8_OK;
+  int cus = 0;
+  hif8_status s = ensure_init(&cus);
+  if (s != HIF8_OK) return s;
+  const dim3 grid(grid_for(n_groups, cus)), block(g_tune.block);
+  const uint4* s4 = reinterpret_cast<const uint4*>(src);
+  hipStream_t st = (hipStream_t)stream;
+  if (out_bytes == 4) { HIF8_DISPATCH_U(hipLaunchKernelGGL((k_diag_stream<U, 4>), grid, block, 0, st, s4, dst, n_groups)) }
+  else if (out_bytes == 8) { HIF8_DISPATCH_U(hipLaunchKernelGGL((k_diag_stream<U, 8>), grid, block, 0, st, s4, dst, n_groups)) }
+  else { HIF8_DISPATCH_U(hipLaunchKernelGGL((k_diag_stream<U, 16>), grid, block, 0, st, s4, dst, n_groups)) }
+  return finish_launch();
+}
+
+}  // extern "C"

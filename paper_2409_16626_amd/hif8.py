@@ -1,0 +1,189 @@
+"""Thin ctypes binding over libhif8.so: same names as the C ABI in include/hif8.h.
+
+Argument marshalling only -- every step of the conversion runs in the HIP kernels.
+Data arguments are torch tensors living on the GPU (or raw integer device pointers);
+bfloat16 tensors may be passed as torch.bfloat16 or as int16/uint16 views.  The HIP
+stream defaults to torch's current stream.  There is no CPU fallback: if the library
+is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+import torch
+
+from . import build as _build
+
+RM_TA = 0
+RM_HR = 1
+FLAG_SAT = 0x10
+FLAG_NAN2ZERO = 0x20
+MAX_FINITE = 32768.0
+
+TUNE_BLOCK, TUNE_WG_PER_CU, TUNE_UNROLL, TUNE_TA_IMPL = 0, 1, 2, 3
+
+_STATUS = {0: "HIF8_OK", -1: "HIF8_ERR_NULL", -2: "HIF8_ERR_MODE", -3: "HIF8_ERR_SCALE",
+           -4: "HIF8_ERR_HIP", -5: "HIF8_ERR_ARG"}
+
+
+class Hif8Error(RuntimeError):
+    def __init__(self, status, hip_error=0):
+        self.status = status
+        self.hip_error = hip_error
+        super().__init__("%s (status %d, hipError %d)" % (_STATUS.get(status, "?"), status, hip_error))
+
+
+def _load():
+    path = _build.LIB
+    if not os.path.exists(path):
+        # nothing built yet: build once (hipcc cross-compiles without a GPU); never fall back
+        _build.build(force=True)
+    return ctypes.CDLL(path)
+
+
+lib = _load()
+
+_vp, _sz, _f, _u32, _i = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float, ctypes.c_uint32, ctypes.c_int
+
+_SIGS = {
+    "hif8_version": ([], _i),
+    "hif8_last_hip_error": ([], _i),
+    "hif8_init": ([], _i),
+    "hif8_amax_f32": ([_vp, _sz, _vp, _vp], _i),
+    "hif8_amax_bf16": ([_vp, _sz, _vp, _vp], _i),
+    "hif8_scale_from_amax": ([_vp, _vp, _f, _i, _vp], _i),
+    "hif8_encode_f32": ([_vp, _vp, _sz, _f, _u32, _vp], _i),
+    "hif8_encode_bf16": ([_vp, _vp, _sz, _f, _u32, _vp], _i),
+    "hif8_decode_f32": ([_vp, _vp, _sz, _f, _vp], _i),
+    "hif8_decode_bf16": ([_vp, _vp, _sz, _f, _vp], _i),
+    "hif8_fake_quant_f32": ([_vp, _vp, _vp, _sz, _f, _u32, _vp], _i),
+    "hif8_fake_quant_bf16": ([_vp, _vp, _vp, _sz, _f, _u32, _vp], _i),
+    "hif8_encode_f32_ds": ([_vp, _vp, _sz, _vp, _u32, _vp], _i),
+    "hif8_encode_bf16_ds": ([_vp, _vp, _sz, _vp, _u32, _vp], _i),
+    "hif8_decode_f32_ds": ([_vp, _vp, _sz, _vp, _vp], _i),
+    "hif8_decode_bf16_ds": ([_vp, _vp, _sz, _vp, _vp], _i),
+    "hif8_fake_quant_f32_ds": ([_vp, _vp, _vp, _sz, _vp, _u32, _vp], _i),
+    "hif8_fake_quant_bf16_ds": ([_vp, _vp, _vp, _sz, _vp, _u32, _vp], _i),
+    "hif8_set_tuning": ([_i, _i], _i),
+    "hif8_get_tuning": ([_i], _i),
+    "hif8_diag_stream": ([_vp, _vp, _sz, _i, _vp], _i),
+}
+for _name, (_args, _res) in _SIGS.items():
+    _fn = getattr(lib, _name)
+    _fn.argtypes = _args
+    _fn.restype = _res
+
+EXPORTED_SYMBOLS = tuple(_SIGS)
+
+
+def _ptr(t):
+    """Device pointer of a tensor (or pass an int / None through)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_cuda:
+        raise ValueError("libhif8 takes device pointers; got a tensor on %s" % t.device)
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _check(status):
+    if status != 0:
+        raise Hif8Error(status, lib.hif8_last_hip_error())
+
+
+def hif8_version():
+    return lib.hif8_version()
+
+
+def hif8_last_hip_error():
+    return lib.hif8_last_hip_error()
+
+
+def hif8_init():
+    _check(lib.hif8_init())
+
+
+def hif8_amax_f32(src, n, d_amax, stream=None):
+    _check(lib.hif8_amax_f32(_ptr(src), n, _ptr(d_amax), _stream(stream)))
+
+
+def hif8_amax_bf16(src, n, d_amax, stream=None):
+    _check(lib.hif8_amax_bf16(_ptr(src), n, _ptr(d_amax), _stream(stream)))
+
+
+def hif8_scale_from_amax(d_amax, d_scale2, target=MAX_FINITE, pow2=0, stream=None):
+    _check(lib.hif8_scale_from_amax(_ptr(d_amax), _ptr(d_scale2), target, int(pow2), _stream(stream)))
+
+
+def hif8_encode_f32(src, dst, n, scale=1.0, rounding_mode=RM_TA, stream=None):
+    _check(lib.hif8_encode_f32(_ptr(src), _ptr(dst), n, scale, rounding_mode, _stream(stream)))
+
+
+def hif8_encode_bf16(src, dst, n, scale=1.0, rounding_mode=RM_TA, stream=None):
+    _check(lib.hif8_encode_bf16(_ptr(src), _ptr(dst), n, scale, rounding_mode, _stream(stream)))
+
+
+def hif8_decode_f32(src, dst, n, scale=1.0, stream=None):
+    _check(lib.hif8_decode_f32(_ptr(src), _ptr(dst), n, scale, _stream(stream)))
+
+
+def hif8_decode_bf16(src, dst, n, scale=1.0, stream=None):
+    _check(lib.hif8_decode_bf16(_ptr(src), _ptr(dst), n, scale, _stream(stream)))
+
+
+def hif8_fake_quant_f32(src, dst, codes_or_none, n, scale=1.0, rounding_mode=RM_TA, stream=None):
+    _check(lib.hif8_fake_quant_f32(_ptr(src), _ptr(dst), _ptr(codes_or_none), n, scale, rounding_mode,
+                                   _stream(stream)))
+
+
+def hif8_fake_quant_bf16(src, dst, codes_or_none, n, scale=1.0, rounding_mode=RM_TA, stream=None):
+    _check(lib.hif8_fake_quant_bf16(_ptr(src), _ptr(dst), _ptr(codes_or_none), n, scale, rounding_mode,
+                                    _stream(stream)))
+
+
+def hif8_encode_f32_ds(src, dst, n, d_scale2, rounding_mode=RM_TA, stream=None):
+    _check(lib.hif8_encode_f32_ds(_ptr(src), _ptr(dst), n, _ptr(d_scale2), rounding_mode, _stream(stream)))
+
+
+def hif8_encode_bf16_ds(src, dst, n, d_scale2, rounding_mode=RM_TA, stream=None):
+    _check(lib.hif8_encode_bf16_ds(_ptr(src), _ptr(dst), n, _ptr(d_scale2), rounding_mode, _stream(stream)))
+
+
+def hif8_decode_f32_ds(src, dst, n, d_scale2, stream=None):
+    _check(lib.hif8_decode_f32_ds(_ptr(src), _ptr(dst), n, _ptr(d_scale2), _stream(stream)))
+
+
+def hif8_decode_bf16_ds(src, dst, n, d_scale2, stream=None):
+    _check(lib.hif8_decode_bf16_ds(_ptr(src), _ptr(dst), n, _ptr(d_scale2), _stream(stream)))
+
+
+def hif8_fake_quant_f32_ds(src, dst, codes_or_none, n, d_scale2, rounding_mode=RM_TA, stream=None):
+    _check(lib.hif8_fake_quant_f32_ds(_ptr(src), _ptr(dst), _ptr(codes_or_none), n, _ptr(d_scale2),
+                                      rounding_mode, _stream(stream)))
+
+
+def hif8_fake_quant_bf16_ds(src, dst, codes_or_none, n, d_scale2, rounding_mode=RM_TA, stream=None):
+    _check(lib.hif8_fake_quant_bf16_ds(_ptr(src), _ptr(dst), _ptr(codes_or_none), n, _ptr(d_scale2),
+                                       rounding_mode, _stream(stream)))
+
+
+def hif8_set_tuning(key, value):
+    _check(lib.hif8_set_tuning(key, value))
+
+
+def hif8_get_tuning(key):
+    return lib.hif8_get_tuning(key)
+
+
+def hif8_diag_stream(src, dst, n_groups, out_bytes_per_lane, stream=None):
+    _check(lib.hif8_diag_stream(_ptr(src), _ptr(dst), n_groups, out_bytes_per_lane, _stream(stream)))

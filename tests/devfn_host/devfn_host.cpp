@@ -1,0 +1,29 @@
+// CPU build of the HIP library's device-side bit logic (hif8_device.hpp), for tests that
+// run where there is no GPU.  Test infrastructure: it lets the encode / decode bit
+// manipulation be compared with the oracle on the CPU before (and besides) the GPU parity
+// tests.  Not part of the product and never loaded by it.
+#include <stdint.h>
+#include <stddef.h>
+#define HIF8_DEVICE_HOST_SHIM 1
+#define __device__
+#define __forceinline__ inline
+static inline int __clz(int x) { return x == 0 ? 32 : __builtin_clz((unsigned)x); }
+#include "../../paper_2409_16626_amd/csrc/hif8_device.hpp"
+
+extern "C" {
+void devfn_encode_bits(const uint32_t* ybits, uint8_t* dst, size_t n, uint32_t mode, int src16) {
+  const bool hr = (mode & 0xF) == 1;
+  for (size_t i = 0; i < n; ++i) {
+    uint32_t c;
+    if (hr) c = src16 ? hif8dev::encode_alu<true, true>(ybits[i], mode) : hif8dev::encode_alu<true, false>(ybits[i], mode);
+    else c = src16 ? hif8dev::encode_alu<false, true>(ybits[i], mode) : hif8dev::encode_alu<false, false>(ybits[i], mode);
+    dst[i] = (uint8_t)c;
+  }
+}
+void devfn_decode_bits(const uint8_t* codes, uint32_t* dst, size_t n) {
+  for (size_t i = 0; i < n; ++i) dst[i] = hif8dev::decode_bits(codes[i]);
+}
+void devfn_narrow_bf16(const uint32_t* bits, uint16_t* dst, size_t n) {
+  for (size_t i = 0; i < n; ++i) dst[i] = (uint16_t)hif8dev::narrow_bf16(bits[i]);
+}
+}

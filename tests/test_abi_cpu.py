@@ -1,0 +1,61 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared symbol, and
+rejects bad arguments before touching a device (no compute calls here)."""
+import os
+import re
+
+from conftest import ROOT
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "hif8.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hif8_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2409_16626_amd import hif8
+    names = declared_symbols()
+    assert len(names) >= 20
+    for n in names:
+        assert hasattr(hif8.lib, n), n
+        assert n in hif8.EXPORTED_SYMBOLS, "binding has no wrapper for " + n
+        assert callable(getattr(hif8, n)), n
+    assert hif8.hif8_version() >= 100
+
+
+def test_argument_validation_happens_on_the_host():
+    from paper_2409_16626_amd import hif8
+    L = hif8.lib
+    OK, NULL, MODE, SCALE, ARG = 0, -1, -2, -3, -5
+    p = 0x1000  # never dereferenced: every call below fails validation or has n == 0
+    assert L.hif8_encode_f32(None, p, 16, 1.0, 0, None) == NULL
+    assert L.hif8_encode_f32(p, None, 16, 1.0, 0, None) == NULL
+    assert L.hif8_encode_bf16(p, p, 16, 1.0, 2, None) == MODE
+    assert L.hif8_encode_bf16(p, p, 16, 1.0, 0x40, None) == MODE
+    for bad in (0.0, -1.0, float("inf"), float("nan"), 1e-45, 3e38 * 10):
+        assert L.hif8_encode_f32(p, p, 16, bad, 0, None) == SCALE, bad
+        assert L.hif8_decode_f32(p, p, 16, bad, None) == SCALE
+        assert L.hif8_fake_quant_bf16(p, p, None, 16, bad, 0, None) == SCALE
+    assert L.hif8_encode_f32(p, p, 0, 1.0, 0x31, None) == OK          # n == 0 is a no-op
+    assert L.hif8_decode_bf16(p, p, 0, 2.0, None) == OK
+    assert L.hif8_fake_quant_f32(p, p, None, 0, 2.0, 1, None) == OK
+    assert L.hif8_fake_quant_f32(None, p, None, 4, 2.0, 1, None) == NULL
+    assert L.hif8_encode_f32_ds(p, p, 16, None, 0, None) == NULL
+    assert L.hif8_amax_f32(p, 16, None, None) == NULL
+    assert L.hif8_scale_from_amax(None, p, 1.0, 0, None) == NULL
+    assert L.hif8_scale_from_amax(p, p, -1.0, 0, None) == ARG
+    assert L.hif8_diag_stream(p, p, 16, 5, None) == ARG
+    assert L.hif8_diag_stream(p + 4, p, 16, 4, None) == ARG
+
+
+def test_tuning_knobs():
+    from paper_2409_16626_amd import hif8
+    L = hif8.lib
+    saved = [L.hif8_get_tuning(k) for k in range(4)]
+    assert L.hif8_set_tuning(0, 100) == -5 and L.hif8_set_tuning(0, 2048) == -5
+    assert L.hif8_set_tuning(1, 0) == -5 and L.hif8_set_tuning(2, 3) == -5
+    assert L.hif8_set_tuning(3, 2) == -5 and L.hif8_set_tuning(9, 1) == -5
+    assert L.hif8_get_tuning(9) == -1
+    assert L.hif8_set_tuning(0, 256) == 0 and L.hif8_get_tuning(0) == 256
+    for k, v in enumerate(saved):
+        assert L.hif8_set_tuning(k, v) == 0

@@ -1,0 +1,89 @@
+"""CPU build of the HIP library's device bit logic, checked against the oracle (no GPU).
+
+The header with the device functions is compiled for the host with g++ through a small
+shim (tests/devfn_host).  This is not the parity test proper (that one runs the kernels
+on the GPU through the C ABI); it checks the integer encode / decode logic the kernels
+are built from on every binary32 top-13-bit pattern, every 16-bit source pattern and
+random patterns, under every rounding method and option.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+from oracle import hif8_oracle as orc
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(HERE, "devfn_host", "devfn_host.cpp")
+HDR = os.path.join(HERE, "..", "paper_2409_16626_amd", "csrc", "hif8_device.hpp")
+LIB = os.path.join(HERE, "devfn_host", "libdevfn_host.so")
+
+
+@pytest.fixture(scope="module")
+def dev():
+    newest = max(os.path.getmtime(SRC), os.path.getmtime(HDR))
+    if not os.path.exists(LIB) or os.path.getmtime(LIB) < newest:
+        subprocess.run(["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-o", LIB, SRC], check=True)
+    lib = ctypes.CDLL(LIB)
+    return lib
+
+
+def _enc(lib, ybits, mode, src16):
+    ybits = np.ascontiguousarray(ybits, np.uint32)
+    out = np.empty(ybits.shape, np.uint8)
+    lib.devfn_encode_bits(ybits.ctypes.data_as(ctypes.c_void_p), out.ctypes.data_as(ctypes.c_void_p),
+                          ctypes.c_size_t(ybits.size), ctypes.c_uint32(mode), ctypes.c_int(src16))
+    return out
+
+
+MODES = [orc.RM_TA, orc.RM_HR, orc.RM_TA | orc.FLAG_SAT, orc.RM_HR | orc.FLAG_SAT,
+         orc.RM_TA | orc.FLAG_NAN2ZERO, orc.RM_HR | orc.FLAG_SAT | orc.FLAG_NAN2ZERO]
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_device_encode_logic_f32(dev, mode):
+    rng = np.random.default_rng(21)
+    top = np.arange(1 << 13, dtype=np.uint32) << 19
+    parts = [top, top | np.uint32(0x7FFFF), top | np.uint32(1), top | np.uint32(0x2000),
+             top | rng.integers(0, 1 << 19, size=top.size).astype(np.uint32)]
+    yb = rng.integers(0, 2 ** 32, size=1 << 20, dtype=np.uint64).astype(np.uint32)
+    ex = rng.integers(127 - 40, 127 + 18, size=yb.size).astype(np.uint32)
+    yb[::2] = (yb[::2] & np.uint32(0x807FFFFF)) | (ex[::2] << 23)
+    yb[::8] &= np.uint32(0xFFFFC000)
+    h = np.arange(65536, dtype=np.uint16).view(np.float16).astype(np.float32).view(np.uint32)
+    allb = np.concatenate(parts + [yb, h])
+    want = orc.encode_f32(allb.view(np.float32), 1.0, mode)
+    got = _enc(dev, allb, mode, 0)
+    bad = np.nonzero(want != got)[0]
+    assert bad.size == 0, [(hex(allb[i]), hex(want[i]), hex(got[i])) for i in bad[:8]]
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_device_encode_logic_bf16(dev, mode):
+    b = np.arange(65536, dtype=np.uint16)
+    for scale in (np.float32(1.0), np.float32(0.37), np.float32(1311.7), np.float32(2.0 ** -20)):
+        prod = ((b.astype(np.uint32) << 16).view(np.float32) * scale).astype(np.float32)
+        want = orc.encode_bf16(b, scale, mode)
+        got = _enc(dev, prod.view(np.uint32), mode, 1)
+        bad = np.nonzero(want != got)[0]
+        assert bad.size == 0, [(hex(b[i]), hex(want[i]), hex(got[i])) for i in bad[:8]]
+
+
+def test_device_decode_logic(dev):
+    codes = np.arange(256, dtype=np.uint8)
+    out = np.empty(256, np.uint32)
+    dev.devfn_decode_bits(codes.ctypes.data_as(ctypes.c_void_p), out.ctypes.data_as(ctypes.c_void_p),
+                          ctypes.c_size_t(256))
+    assert np.array_equal(out, orc.decode_f32(codes, 1.0).view(np.uint32))
+
+
+def test_device_narrow_logic(dev):
+    rng = np.random.default_rng(22)
+    u = rng.integers(0, 2 ** 32, size=1 << 18, dtype=np.uint64).astype(np.uint32)
+    u[::7] = (u[::7] & np.uint32(0xFFFF0000)) | np.uint32(0x8000)
+    out = np.empty(u.shape, np.uint16)
+    dev.devfn_narrow_bf16(u.ctypes.data_as(ctypes.c_void_p), out.ctypes.data_as(ctypes.c_void_p),
+                          ctypes.c_size_t(u.size))
+    assert np.array_equal(out, orc.narrow_bf16(u.view(np.float32)))

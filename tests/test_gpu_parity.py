@@ -1,0 +1,357 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bars: u8 codes bit-exact; FP32 / BF16 outputs compared as raw bit patterns (0 ulp).
+Sizes span several tiles, a ragged tail, and the element-per-lane path for unaligned
+pointers.  Inputs come from the seeded generators in paper_2409_16626_amd.workloads.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import hif8_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+TA, HR, SAT, N2Z = orc.RM_TA, orc.RM_HR, orc.FLAG_SAT, orc.FLAG_NAN2ZERO
+ALL_MODES = [TA, HR, TA | SAT, HR | SAT, TA | N2Z, HR | N2Z, TA | SAT | N2Z, HR | SAT | N2Z]
+
+
+@pytest.fixture(scope="module")
+def h():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2409_16626_amd import hif8
+    hif8.hif8_init()
+    return hif8
+
+
+from gpu_util import assert_same_bytes, bf16_bits, dev, f32_bits, to_gpu  # noqa: E402
+
+
+def gpu_encode_f32(h, x, scale, mode):
+    dst = torch.empty(x.numel(), dtype=torch.uint8, device=dev())
+    h.hif8_encode_f32(x, dst, x.numel(), scale, mode)
+    torch.cuda.synchronize()
+    return dst.cpu().numpy()
+
+
+def gpu_encode_bf16(h, x, scale, mode):
+    dst = torch.empty(x.numel(), dtype=torch.uint8, device=dev())
+    h.hif8_encode_bf16(x, dst, x.numel(), scale, mode)
+    torch.cuda.synchronize()
+    return dst.cpu().numpy()
+
+
+# ------------------------------------------------------------------ config 1: exhaustive tiny
+@pytest.mark.parametrize("scale", [1.0, 4.0, 0.37, 1311.7])
+def test_c1_decode_all_codes(h, scale):
+    from paper_2409_16626_amd import workloads
+    codes = workloads.all_codes(dev())
+    out32 = torch.empty(256, dtype=torch.float32, device=dev())
+    out16 = torch.empty(256, dtype=torch.bfloat16, device=dev())
+    h.hif8_decode_f32(codes, out32, 256, scale)
+    h.hif8_decode_bf16(codes, out16, 256, scale)
+    torch.cuda.synchronize()
+    c = codes.cpu().numpy()
+    assert_same_bytes(f32_bits(out32), orc.decode_f32(c, scale).view(np.uint32), "decode_f32")
+    assert_same_bytes(bf16_bits(out16), orc.decode_bf16(c, scale), "decode_bf16")
+
+
+@pytest.mark.parametrize("mode", ALL_MODES)
+def test_c1_encode_all_fp16_patterns(h, mode):
+    from paper_2409_16626_amd import workloads
+    x = workloads.all_fp16_as_f32(dev())
+    got = gpu_encode_f32(h, x, 1.0, mode)
+    assert_same_bytes(got, orc.encode_f32(x.cpu().numpy(), 1.0, mode), "fp16 patterns mode %#x" % mode)
+
+
+@pytest.mark.parametrize("mode", ALL_MODES)
+@pytest.mark.parametrize("scale", [1.0, 0.37, 2.0 ** -9, 1311.7])
+def test_c1_encode_all_bf16_patterns(h, mode, scale):
+    from paper_2409_16626_amd import workloads
+    x = workloads.all_bf16(dev())
+    got = gpu_encode_bf16(h, x, scale, mode)
+    assert_same_bytes(got, orc.encode_bf16(bf16_bits(x), scale, mode), "bf16 patterns")
+
+
+@pytest.mark.parametrize("mode", [TA, HR, TA | SAT, HR | N2Z])
+def test_c1_encode_normal_1m(h, mode):
+    from paper_2409_16626_amd import workloads
+    x = workloads.normal_f32(1 << 20, dev())
+    got = gpu_encode_f32(h, x, 1.0, mode)
+    assert_same_bytes(got, orc.encode_f32(x.cpu().numpy(), 1.0, mode), "N(0,1)")
+
+
+@pytest.mark.parametrize("mode", ALL_MODES)
+def test_c1_decode_encode_round_trip(h, mode):
+    from paper_2409_16626_amd import workloads
+    codes = workloads.all_codes(dev())
+    v = torch.empty(256, dtype=torch.float32, device=dev())
+    h.hif8_decode_f32(codes, v, 256, 1.0)
+    got = gpu_encode_f32(h, v, 1.0, mode)
+    want = np.arange(256, dtype=np.uint8)
+    if mode & N2Z:
+        want[0x80] = 0
+    if mode & SAT:
+        want[0x6F], want[0xEF] = 0x6E, 0xEE
+    assert_same_bytes(got, want, "round trip")
+    vb = torch.empty(256, dtype=torch.bfloat16, device=dev())
+    h.hif8_decode_bf16(codes, vb, 256, 1.0)
+    assert_same_bytes(gpu_encode_bf16(h, vb, 1.0, mode), want, "round trip bf16")
+
+
+def test_top13_bit_patterns_with_fillers(h):
+    rng = np.random.default_rng(31)
+    top = np.arange(1 << 13, dtype=np.uint32) << 19
+    parts = [top, top | np.uint32(0x7FFFF), top | np.uint32(1),
+             top | rng.integers(0, 1 << 19, size=top.size).astype(np.uint32)]
+    yb = np.concatenate(parts)
+    x = to_gpu(yb).view(torch.float32)
+    for mode in (TA, HR, TA | SAT | N2Z):
+        got = gpu_encode_f32(h, x, 1.0, mode)
+        assert_same_bytes(got, orc.encode_f32(yb.view(np.float32), 1.0, mode), "top13 %#x" % mode)
+
+
+# ------------------------------------------------------------------ ragged sizes / alignment
+@pytest.mark.parametrize("n", [0, 1, 3, 4, 5, 7, 8, 9, 63, 64, 65, 1000, 4097, 8191, (1 << 18) + 13])
+def test_ragged_sizes_all_entry_points(h, n):
+    from paper_2409_16626_amd import workloads
+    big = workloads.dynamic_range_sweep(1 << 19, dev())
+    x = big[:n].contiguous()
+    xb = big[:n].to(torch.bfloat16).contiguous()
+    xn, xbn = x.cpu().numpy(), bf16_bits(xb)
+    for mode in (TA, HR):
+        for scale in (1.0, 3.3):
+            assert_same_bytes(gpu_encode_f32(h, x, scale, mode), orc.encode_f32(xn, scale, mode), "enc f32")
+            assert_same_bytes(gpu_encode_bf16(h, xb, scale, mode), orc.encode_bf16(xbn, scale, mode), "enc bf16")
+            o = torch.empty_like(x)
+            c = torch.empty(n, dtype=torch.uint8, device=dev())
+            h.hif8_fake_quant_f32(x, o, c, n, scale, mode)
+            ob = torch.empty_like(xb)
+            cb = torch.empty(n, dtype=torch.uint8, device=dev())
+            h.hif8_fake_quant_bf16(xb, ob, cb, n, scale, mode)
+            torch.cuda.synchronize()
+            wo, wc = orc.fake_quant_f32(xn, scale, mode)
+            assert_same_bytes(f32_bits(o), wo.view(np.uint32), "fq f32")
+            assert_same_bytes(c.cpu().numpy(), wc, "fq f32 codes")
+            wob, wcb = orc.fake_quant_bf16(xbn, scale, mode)
+            assert_same_bytes(bf16_bits(ob), wob, "fq bf16")
+            assert_same_bytes(cb.cpu().numpy(), wcb, "fq bf16 codes")
+    codes = torch.randint(0, 256, (n,), dtype=torch.int32, device=dev(),
+                          generator=torch.Generator(device=dev()).manual_seed(5)).to(torch.uint8)
+    o = torch.empty(n, dtype=torch.float32, device=dev())
+    ob = torch.empty(n, dtype=torch.bfloat16, device=dev())
+    h.hif8_decode_f32(codes, o, n, 2.5)
+    h.hif8_decode_bf16(codes, ob, n, 2.5)
+    torch.cuda.synchronize()
+    assert_same_bytes(f32_bits(o), orc.decode_f32(codes.cpu().numpy(), 2.5).view(np.uint32), "dec f32")
+    assert_same_bytes(bf16_bits(ob), orc.decode_bf16(codes.cpu().numpy(), 2.5), "dec bf16")
+    am = torch.full((1,), 7.0, dtype=torch.float32, device=dev())
+    h.hif8_amax_f32(x, n, am)
+    assert f32_bits(am)[0] == np.float32(orc.amax_f32(xn)).view(np.uint32)
+    h.hif8_amax_bf16(xb, n, am)
+    assert f32_bits(am)[0] == np.float32(orc.amax_bf16(xbn)).view(np.uint32)
+
+
+@pytest.mark.parametrize("off", [1, 2, 3])
+def test_unaligned_pointers_use_element_path(h, off):
+    from paper_2409_16626_amd import workloads
+    n = 10007
+    big = workloads.dynamic_range_sweep(1 << 15, dev())
+    x = big[off:off + n]                       # 4*off bytes off a 16-byte boundary
+    xb_all = big.to(torch.bfloat16)
+    xb = xb_all[off:off + n]
+    xn, xbn = x.cpu().numpy(), bf16_bits(xb.contiguous())
+    dst_all = torch.zeros(n + 8, dtype=torch.uint8, device=dev())
+    for mode in (TA, HR | SAT):
+        dst = dst_all[off:off + n]
+        h.hif8_encode_f32(x.data_ptr(), dst.data_ptr(), n, 1.7, mode)
+        torch.cuda.synchronize()
+        assert_same_bytes(dst.cpu().numpy(), orc.encode_f32(xn, 1.7, mode), "unaligned enc f32")
+        h.hif8_encode_bf16(xb.data_ptr(), dst.data_ptr(), n, 1.7, mode)
+        torch.cuda.synchronize()
+        assert_same_bytes(dst.cpu().numpy(), orc.encode_bf16(xbn, 1.7, mode), "unaligned enc bf16")
+        # destination only misaligned
+        x0 = big[:n]
+        h.hif8_encode_f32(x0.data_ptr(), dst.data_ptr(), n, 1.0, mode)
+        torch.cuda.synchronize()
+        assert_same_bytes(dst.cpu().numpy(), orc.encode_f32(x0.cpu().numpy(), 1.0, mode), "unaligned dst")
+        o_all = torch.zeros(n + 8, dtype=torch.float32, device=dev())
+        o = o_all[off:off + n]
+        h.hif8_fake_quant_f32(x.data_ptr(), o.data_ptr(), dst.data_ptr(), n, 1.7, mode)
+        torch.cuda.synchronize()
+        wo, wc = orc.fake_quant_f32(xn, 1.7, mode)
+        assert_same_bytes(f32_bits(o.contiguous()), wo.view(np.uint32), "unaligned fq")
+        assert_same_bytes(dst.cpu().numpy(), wc, "unaligned fq codes")
+        ob_all = torch.zeros(n + 8, dtype=torch.bfloat16, device=dev())
+        ob = ob_all[off:off + n]
+        h.hif8_fake_quant_bf16(xb.data_ptr(), ob.data_ptr(), None, n, 1.7, mode)
+        torch.cuda.synchronize()
+        wob, _ = orc.fake_quant_bf16(xbn, 1.7, mode)
+        assert_same_bytes(bf16_bits(ob.contiguous()), wob, "unaligned fq bf16")
+    codes = dst_all[off:off + n]
+    o = torch.zeros(n + 8, dtype=torch.float32, device=dev())[off:off + n]
+    h.hif8_decode_f32(codes.data_ptr(), o.data_ptr(), n, 0.7)
+    torch.cuda.synchronize()
+    assert_same_bytes(f32_bits(o.contiguous()), orc.decode_f32(codes.cpu().numpy(), 0.7).view(np.uint32), "unaligned dec")
+    am = torch.zeros(1, dtype=torch.float32, device=dev())
+    h.hif8_amax_f32(x.data_ptr(), n, am)
+    assert f32_bits(am)[0] == np.float32(orc.amax_f32(xn)).view(np.uint32)
+    h.hif8_amax_bf16(xb.data_ptr(), n, am)
+    assert f32_bits(am)[0] == np.float32(orc.amax_bf16(xbn)).view(np.uint32)
+
+
+def test_fake_quant_in_place(h):
+    from paper_2409_16626_amd import workloads
+    x = workloads.dynamic_range_sweep((1 << 20) + 5, dev())
+    xn = x.cpu().numpy()
+    h.hif8_fake_quant_f32(x, x, None, x.numel(), 2.0, TA)
+    torch.cuda.synchronize()
+    wo, _ = orc.fake_quant_f32(xn, 2.0, TA)
+    assert_same_bytes(f32_bits(x), wo.view(np.uint32), "in place f32")
+    xb = workloads.activation_bf16(512, 1024, dev()).view(-1)
+    xbn = bf16_bits(xb)
+    h.hif8_fake_quant_bf16(xb, xb, None, xb.numel(), 5.0, HR)
+    torch.cuda.synchronize()
+    wob, _ = orc.fake_quant_bf16(xbn, 5.0, HR)
+    assert_same_bytes(bf16_bits(xb), wob, "in place bf16")
+
+
+# ------------------------------------------------------------------ reduced-size configs 2-5
+@pytest.mark.parametrize("mode", [TA, TA | SAT, HR])
+def test_c2_dynamic_range_sweep_small(h, mode):
+    from paper_2409_16626_amd import workloads
+    x = workloads.dynamic_range_sweep((1 << 22) + 3, dev())
+    got = gpu_encode_f32(h, x, 1.0, mode)
+    assert_same_bytes(got, orc.encode_f32(x.cpu().numpy(), 1.0, mode), "C2 small")
+
+
+def test_c3_activation_pipeline_small(h):
+    """amax -> scale (2^15 / amax, device resident) -> fused fake-quant with codes."""
+    from paper_2409_16626_amd import workloads
+    x = workloads.activation_bf16(1024, 2048 + 8, dev()).view(-1)
+    n = x.numel()
+    xb = bf16_bits(x)
+    am = torch.zeros(1, dtype=torch.float32, device=dev())
+    sc = torch.zeros(2, dtype=torch.float32, device=dev())
+    out = torch.empty_like(x)
+    codes = torch.empty(n, dtype=torch.uint8, device=dev())
+    for pow2 in (0, 1):
+        h.hif8_amax_bf16(x, n, am)
+        h.hif8_scale_from_amax(am, sc, 32768.0, pow2)
+        h.hif8_fake_quant_bf16_ds(x, out, codes, n, sc, TA)
+        torch.cuda.synchronize()
+        w_am = orc.amax_bf16(xb)
+        assert f32_bits(am)[0] == np.float32(w_am).view(np.uint32)
+        w_s = orc.scale_from_amax(w_am, 32768.0, bool(pow2))
+        s2 = sc.cpu().numpy()
+        assert s2[0] == w_s and s2[1] == np.float32(1.0) / w_s
+        wo, wc = orc.fake_quant_bf16(xb, w_s, TA)
+        assert_same_bytes(codes.cpu().numpy(), wc, "C3 codes")
+        assert_same_bytes(bf16_bits(out), wo, "C3 bf16 out")
+        assert wc.max() >= 0x6C or (wc & 0x7F).max() >= 0x6C  # scaling uses the top of the range
+        # separate encode_ds / decode_ds agree with the fused call
+        c2 = torch.empty_like(codes)
+        o2 = torch.empty_like(out)
+        h.hif8_encode_bf16_ds(x, c2, n, sc, TA)
+        h.hif8_decode_bf16_ds(c2, o2, n, sc)
+        torch.cuda.synchronize()
+        assert torch.equal(c2, codes) and torch.equal(o2.view(torch.int16), out.view(torch.int16))
+
+
+@pytest.mark.parametrize("mode", [TA, HR])
+def test_c4_gradient_small(h, mode):
+    from paper_2409_16626_amd import workloads
+    x = workloads.gradient_f32((1 << 22) + 1, dev(), chunk=1 << 20)
+    got = gpu_encode_f32(h, x, 1.0, mode)
+    want = orc.encode_f32(x.cpu().numpy(), 1.0, mode)
+    assert_same_bytes(got, want, "C4 small")
+    frac_dml = np.mean(((want & 0x7F) >= 1) & ((want & 0x7F) <= 7))
+    assert frac_dml > 0.2      # the bulk of this workload lives in the denormal binades
+
+
+def test_c5_weight_cast_small(h):
+    from paper_2409_16626_amd import workloads
+    arena, index = workloads.llm_weights_bf16(dev(), layers=2, hidden=256, ffn=688, vocab=2000)
+    codes = torch.empty(arena.numel(), dtype=torch.uint8, device=dev())
+    am = torch.zeros(len(index), dtype=torch.float32, device=dev())
+    sc = torch.zeros(len(index), 2, dtype=torch.float32, device=dev())
+    for i, (_, off, m) in enumerate(index):
+        h.hif8_amax_bf16(arena[off:off + m].data_ptr(), m, am[i:i + 1].data_ptr())
+        h.hif8_scale_from_amax(am[i:i + 1].data_ptr(), sc[i].data_ptr(), 32768.0, 0)
+        h.hif8_encode_bf16_ds(arena[off:off + m].data_ptr(), codes[off:off + m].data_ptr(), m,
+                              sc[i].data_ptr(), TA)
+    torch.cuda.synchronize()
+    ab = bf16_bits(arena)
+    cg = codes.cpu().numpy()
+    for i, (_, off, m) in enumerate(index):
+        w_am = orc.amax_bf16(ab[off:off + m])
+        w_s = orc.scale_from_amax(w_am, 32768.0, False)
+        assert sc[i, 0].item() == w_s
+        assert_same_bytes(cg[off:off + m], orc.encode_bf16(ab[off:off + m], w_s, TA), "C5 tensor %d" % i)
+
+
+# ------------------------------------------------------------------ amax semantics, tuning, graphs
+def test_amax_special_values(h):
+    x = torch.randn(100003, device=dev())
+    am = torch.zeros(1, dtype=torch.float32, device=dev())
+    x[77777] = -float("inf")
+    h.hif8_amax_f32(x, x.numel(), am)
+    assert f32_bits(am)[0] == 0x7F800000
+    x[5] = float("nan")
+    h.hif8_amax_f32(x, x.numel(), am)
+    assert np.isnan(am.cpu().numpy()[0])
+    z = torch.zeros(4096, device=dev())
+    h.hif8_amax_f32(z, z.numel(), am)
+    assert f32_bits(am)[0] == 0
+    z[4095] = -0.0
+    h.hif8_amax_f32(z, z.numel(), am)
+    assert f32_bits(am)[0] == 0
+    # scale from a degenerate amax is 1
+    sc = torch.zeros(2, dtype=torch.float32, device=dev())
+    for v in (0.0, float("inf"), float("nan")):
+        am.fill_(v)
+        h.hif8_scale_from_amax(am, sc, 32768.0, 0)
+        assert sc.cpu().tolist() == [1.0, 1.0]
+
+
+@pytest.mark.parametrize("block,wg,unroll,impl", [(64, 1, 1, 0), (256, 8, 2, 0), (1024, 2, 8, 0),
+                                                  (512, 4, 4, 1), (128, 16, 8, 1), (320, 3, 2, 0)])
+def test_launch_shapes_and_alu_variant(h, block, wg, unroll, impl):
+    from paper_2409_16626_amd import workloads
+    saved = [h.hif8_get_tuning(k) for k in range(4)]
+    try:
+        h.hif8_set_tuning(h.TUNE_BLOCK, block)
+        h.hif8_set_tuning(h.TUNE_WG_PER_CU, wg)
+        h.hif8_set_tuning(h.TUNE_UNROLL, unroll)
+        h.hif8_set_tuning(h.TUNE_TA_IMPL, impl)
+        x = workloads.dynamic_range_sweep((1 << 21) + 77, dev())
+        xn = x.cpu().numpy()
+        for mode in (TA, HR, TA | SAT | N2Z):
+            assert_same_bytes(gpu_encode_f32(h, x, 1.0, mode), orc.encode_f32(xn, 1.0, mode), "tuned enc")
+        xb = x.to(torch.bfloat16)
+        xbn = bf16_bits(xb)
+        o = torch.empty_like(xb)
+        c = torch.empty(xb.numel(), dtype=torch.uint8, device=dev())
+        h.hif8_fake_quant_bf16(xb, o, c, xb.numel(), 0.9, TA)
+        torch.cuda.synchronize()
+        wo, wc = orc.fake_quant_bf16(xbn, 0.9, TA)
+        assert_same_bytes(c.cpu().numpy(), wc, "tuned fq codes")
+        assert_same_bytes(bf16_bits(o), wo, "tuned fq out")
+        am = torch.zeros(1, dtype=torch.float32, device=dev())
+        h.hif8_amax_f32(x, x.numel(), am)
+        assert f32_bits(am)[0] == np.float32(orc.amax_f32(xn)).view(np.uint32)
+    finally:
+        for k, v in enumerate(saved):
+            h.hif8_set_tuning(k, v)
+
+
+def test_non_default_stream(h):
+    from paper_2409_16626_amd import workloads
+    x = workloads.normal_f32(1 << 18, dev())
+    s = torch.cuda.Stream()
+    dst = torch.empty(x.numel(), dtype=torch.uint8, device=dev())
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        h.hif8_encode_f32(x, dst, x.numel(), 1.0, TA)
+    s.synchronize()
+    assert_same_bytes(dst.cpu().numpy(), orc.encode_f32(x.cpu().numpy(), 1.0, TA), "stream")
