@@ -26,7 +26,8 @@
  *     store width (4 B for u8 codes of an FP32 source, 8 B for u8 codes of a
  *     BF16 source, 16 B for FP32 / BF16 outputs); otherwise a slower
  *     element-per-lane kernel computes the same result.
- *   - n == 0 is valid and enqueues nothing (hif8_amax_* still writes 0).
+ *   - n == 0 is valid and enqueues nothing (hif8_amax_* still writes 0); data pointers
+ *     may then be NULL.  Mode and scale are validated first in every case.
  *   - Return value: HIF8_OK, or a negative hif8_status.  On error nothing has
  *     been enqueued.
  *   - Semantics, with fl32() = IEEE binary32 round-to-nearest-even and Q() the
@@ -100,8 +101,8 @@ hif8_status hif8_amax_bf16(const uint16_t* src, size_t n, float* d_amax, hif8_st
 
 /*
  * Scale factor from a device-resident amax, without a host round trip
- * (Sec. 5: scale each tensor "to a better range that can be represented by HiF8";
- * power-of-two factors avoid extra rounding error).
+ * (Sec. 5, per-tensor scaling: each GEMM input is multiplied by its own factor so that
+ * it sits well inside the HiF8 range; power-of-two factors add no rounding error).
  *   d_scale2[0] = scale = fl32(target / amax), or with pow2 != 0 the largest power
  *                 of two not above it; amax zero, Inf or NaN (or a quotient that
  *                 is not finite and positive) gives scale = 1.
@@ -130,8 +131,9 @@ hif8_status hif8_decode_bf16(const uint8_t* src, uint16_t* dst, size_t n, float 
                              hif8_stream_t stream);
 
 /*
- * Fake quantisation (Sec. 4: tensors "converted ... to only those [values] that
- * could be represented in HiF8"): encode and decode fused in registers.
+ * Fake quantisation (Sec. 4: the paper's simulated HiF8 -- every tensor value is
+ * replaced by the HiF8-representable value it rounds to, kept in the source data type):
+ * encode and decode fused in registers.
  * dst may equal src (in place).  codes_or_null, if not NULL, also receives the
  * n u8 codes and must not overlap src or dst.
  */

@@ -585,11 +585,11 @@ hif8_status finish_launch() { return hip_ok(hipGetLastError()) ? HIF8_OK : HIF8_
 template <bool SRC16>
 hif8_status do_encode(const void* src, uint8_t* dst, size_t n, float scale, const float* d_scale2,
                       uint32_t mode, hipStream_t st) {
-  if (!src || !dst) return HIF8_ERR_NULL;
   if (!valid_mode(mode)) return HIF8_ERR_MODE;
   float inv = 1.0f;
   if (!d_scale2 && !valid_scale(scale, &inv)) return HIF8_ERR_SCALE;
   if (n == 0) return HIF8_OK;
+  if (!src || !dst) return HIF8_ERR_NULL;
   int cus = 0;
   hif8_status s = ensure_init(&cus);
   if (s != HIF8_OK) return s;
@@ -615,10 +615,10 @@ hif8_status do_encode(const void* src, uint8_t* dst, size_t n, float scale, cons
 template <bool DST16>
 hif8_status do_decode(const uint8_t* src, void* dst, size_t n, float scale, const float* d_scale2,
                       hipStream_t st) {
-  if (!src || !dst) return HIF8_ERR_NULL;
   float inv = 1.0f;
   if (!d_scale2 && !valid_scale(scale, &inv)) return HIF8_ERR_SCALE;
   if (n == 0) return HIF8_OK;
+  if (!src || !dst) return HIF8_ERR_NULL;
   int cus = 0;
   hif8_status s = ensure_init(&cus);
   if (s != HIF8_OK) return s;
@@ -643,11 +643,11 @@ hif8_status do_decode(const uint8_t* src, void* dst, size_t n, float scale, cons
 template <bool T16>
 hif8_status do_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, float scale,
                           const float* d_scale2, uint32_t mode, hipStream_t st) {
-  if (!src || !dst) return HIF8_ERR_NULL;
   if (!valid_mode(mode)) return HIF8_ERR_MODE;
   float inv = 1.0f;
   if (!d_scale2 && !valid_scale(scale, &inv)) return HIF8_ERR_SCALE;
   if (n == 0) return HIF8_OK;
+  if (!src || !dst) return HIF8_ERR_NULL;
   int cus = 0;
   hif8_status s = ensure_init(&cus);
   if (s != HIF8_OK) return s;
