@@ -63,7 +63,7 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--buffers", type=int, default=6, help="distinct resident input tensors to rotate over")
-    ap.add_argument("--tune", type=str, default="", help="block,wg_per_cu,unroll,ta_impl")
+    ap.add_argument("--tune", type=str, default="", help="block,wg_per_cu,unroll,ta_impl,tiles_per_wg,amax_nt (prefix allowed)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
@@ -81,7 +81,7 @@ def main():
     if args.tune:
         for k, v in enumerate(int(t) for t in args.tune.split(",")):
             hif8.hif8_set_tuning(k, v)
-    tune = [hif8.hif8_get_tuning(k) for k in range(4)]
+    tune = [hif8.hif8_get_tuning(k) for k in range(hif8.N_TUNE_KEYS)]
 
     # ---------------- headline: C2 encode_f32, TA, scale 1 ----------------
     n = 1 << 26
@@ -115,7 +115,7 @@ def main():
         "config": {"workload": "C2 dynamic-range sweep: 67,108,864 FP32 = +-2^U[-30,20] with 1% short-mantissa ties, "
                                "hif8_encode_f32, scale=1, rounding half away from zero",
                    "elements": n, "elements_per_s": round(n / (wall_ms * 1e-3), 0),
-                   "rotating_buffers": R, "tuning_block_wgpercu_unroll_impl": tune},
+                   "rotating_buffers": R, "tuning_block_wgpercu_unroll_impl_tilesperwg_amaxnt": tune},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                      "kernel": "k_encode_f32<U,TA_LUT>", "bytes_per_launch": bytes_step,

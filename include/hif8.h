@@ -166,18 +166,25 @@ hif8_status hif8_fake_quant_bf16_ds(const uint16_t* src, uint16_t* dst, uint8_t*
                                     hif8_stream_t stream);
 
 /*
- * Launch-shape tuning knobs (process-wide; for benchmarking and profiling).
- *   HIF8_TUNE_BLOCK     threads per workgroup of the streaming kernels (64..1024, multiple of 64)
- *   HIF8_TUNE_WG_PER_CU persistent workgroups launched per compute unit (1..32)
- *   HIF8_TUNE_UNROLL    16-byte loads in flight per lane (1, 2, 4 or 8)
- *   HIF8_TUNE_TA_IMPL   0 = TA encode through the LDS lookup table, 1 = TA encode in ALU only
+ * Launch-shape tuning knobs (process-wide; for benchmarking and profiling).  The first,
+ * second, third and fifth default to -1 = "use the built-in shape of each kernel family".
+ *   HIF8_TUNE_BLOCK        threads per workgroup of the streaming kernels (64..1024, multiple of 64)
+ *   HIF8_TUNE_WG_PER_CU    persistent mode: workgroups launched per compute unit (1..64)
+ *   HIF8_TUNE_UNROLL       16-byte loads in flight per lane (1, 2, 4 or 8); a tile is
+ *                          block * unroll lanes' worth of data
+ *   HIF8_TUNE_TA_IMPL      0 = TA encode through the LDS lookup table, 1 = TA encode in ALU only
+ *   HIF8_TUNE_TILES_PER_WG 0 = persistent grid (grid-stride over tiles); k >= 1 = one-shot grid in
+ *                          which every workgroup handles k consecutive tiles (0..4096)
+ *   HIF8_TUNE_AMAX_NT      1 = amax reads with non-temporal loads, 0 = ordinary loads
  * Returns HIF8_ERR_ARG for an unknown key or a value outside the stated range.
  */
 enum {
   HIF8_TUNE_BLOCK = 0,
   HIF8_TUNE_WG_PER_CU = 1,
   HIF8_TUNE_UNROLL = 2,
-  HIF8_TUNE_TA_IMPL = 3
+  HIF8_TUNE_TA_IMPL = 3,
+  HIF8_TUNE_TILES_PER_WG = 4,
+  HIF8_TUNE_AMAX_NT = 5
 };
 hif8_status hif8_set_tuning(int key, int value);
 int hif8_get_tuning(int key); /* -1 for an unknown key */

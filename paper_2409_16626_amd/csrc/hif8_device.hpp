@@ -122,6 +122,86 @@ __device__ __forceinline__ uint32_t encode_alu(uint32_t ybits, uint32_t mode) {
   return c ? (c | ((ybits >> 24) & 0x80u)) : 0u;
 }
 
+// ------------------------------------------------------------------------------------
+// Hybrid rounding, table-driven form for the streaming kernels.
+//
+// For a value in the binade of biased exponent e the HiF8 grid step is ulp = 2^(E-k)
+// (2^-22 below 2^-22).  Multiplying |y| by c = 2^14 / ulp (exact: a power of two) and
+// truncating to an integer gives Q = n * 2^14 + F with n the kept digits and F the top 14
+// bits of the discarded fraction, which is what both SR14 and SR2 compare with a threshold
+// (SR2's two-bit test F2 >= T2 is F >= T2 * 2^12).  The carry is added as
+// Q - T + 2^14 (bit 14 and up then hold n or n + 1), and n' * ulp is rebuilt by one
+// integer->float conversion and one multiply by 1/c.  Per exponent the table also holds
+// the clamp range of the threshold: [1, 2^14 - 1] where Eq. (3) asks for simplified SR
+// (F = 0 never carries), [2^13, 2^13] where it asks for TA (|E| < 4: carry iff F >= half).
+// ------------------------------------------------------------------------------------
+struct HrExp {
+  float c;         // 2^14 / ulp (a power of two; its reciprocal is rebuilt from the bits)
+  uint32_t tpack;  // threshold clamp: low bound in bits [15:0], high bound in bits [31:16]
+};
+
+__device__ __forceinline__ float pow2f(int x) {  // 2^x for x in [-126, 127]
+  union { uint32_t u; float f; } v;
+  v.u = (uint32_t)(x + 127) << 23;
+  return v.f;
+}
+
+__device__ __forceinline__ HrExp hr_exp_entry(uint32_t e) {
+  HrExp h;
+  if (e <= 104u) {  // |y| < 2^-22: one step from 0 to 2^-22
+    h.c = pow2f(36);
+    h.tpack = 1u | (0x3FFFu << 16);
+    return h;
+  }
+  const int E = (int)e - 127;
+  const int k = (int)kept_bits(e);
+  h.c = pow2f(14 - E + k);
+  h.tpack = (k == 3) ? (0x2000u | (0x2000u << 16)) : (1u | (0x3FFFu << 16));
+  // Inf: the product saturates the integer conversion to 2^32 - 1; a threshold of 2^14
+  // never carries, so Q stays saturated instead of wrapping, and n' * ulp overflows to Inf
+  if (e == 255u) h.tpack = 0x4000u | (0x4000u << 16);
+  return h;
+}
+
+#ifdef HIF8_DEVICE_HOST_SHIM
+// host stand-ins for two hardware instructions (used by the CPU test build only)
+__device__ __forceinline__ uint32_t cvt_u32_trunc_sat(float x) {  // NaN -> 0, saturating
+  if (!(x > 0.0f)) return 0u;
+  if (x >= 4294967296.0f) return 0xFFFFFFFFu;
+  return (uint32_t)x;
+}
+__device__ __forceinline__ uint32_t med3_u32(uint32_t a, uint32_t lo, uint32_t hi) {
+  return a < lo ? lo : (a > hi ? hi : a);
+}
+#else
+__device__ __forceinline__ uint32_t cvt_u32_trunc_sat(float x) {
+  uint32_t q;
+  asm("v_cvt_u32_f32 %0, %1" : "=v"(q) : "v"(x));  // truncates; saturates; NaN -> 0
+  return q;
+}
+__device__ __forceinline__ uint32_t med3_u32(uint32_t a, uint32_t lo, uint32_t hi) {
+  uint32_t r;
+  asm("v_med3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(lo), "v"(hi));
+  return r;
+}
+#endif
+
+// Rounded binary32 pattern (sign kept) of non-NaN pattern ybits under HR; p = table entry
+// of ybits' exponent.  The result is on the HiF8 grid (or at/above 1.5 * 2^15: overflow).
+template <bool SRC16>
+__device__ __forceinline__ uint32_t hr_round_bits(uint32_t ybits, const HrExp& p) {
+  union { uint32_t u; float f; } y, r, c, inv;
+  y.u = ybits & 0x7FFFFFFFu;
+  c.f = p.c;
+  inv.u = 0x7F000000u - c.u;  // 1/c for c = 2^x: exponent field 127 - x
+  const uint32_t q = cvt_u32_trunc_sat(y.f * c.f);
+  uint32_t T = SRC16 ? (((ybits >> 3) & 0x2000u) | 0x1000u) : (ybits & 0x3FFFu);
+  T = med3_u32(T, p.tpack & 0xFFFFu, p.tpack >> 16);
+  const uint32_t qq = (q - T + 0x4000u) & 0xFFFFC000u;
+  r.f = (float)qq * inv.f;
+  return r.u | (ybits & 0x80000000u);
+}
+
 // binary32 pattern of the value of a code (Eq. (1), Eq. (2), special patterns).
 __device__ __forceinline__ uint32_t decode_bits(uint32_t code) {
   const uint32_t s = (code & 0x80u) << 24;

@@ -51,13 +51,17 @@ __device__ __forceinline__ void stage_enc_lut(uint8_t* lut, uint32_t mode) {
   uint4* l = reinterpret_cast<uint4*>(lut);
   for (uint32_t i = threadIdx.x; i < 8192u / 16u; i += blockDim.x) l[i] = g[i];
 }
+__device__ __forceinline__ void stage_hr_table(HrExp* hrt) {
+  for (uint32_t i = threadIdx.x; i < 256u; i += blockDim.x) hrt[i] = hr_exp_entry(i);
+}
 __device__ __forceinline__ void stage_dec_lut(uint32_t* lut) {
   for (uint32_t i = threadIdx.x; i < 256u; i += blockDim.x) lut[i] = g_dec_lut[i];
 }
 
 // One element: scaled pattern -> code.  `lut` is the staged TA table (unused for IMPL_TA_ALU).
 template <int IMPL, bool SRC16>
-__device__ __forceinline__ uint32_t encode_one(uint32_t ybits, const uint8_t* lut, uint32_t mode) {
+__device__ __forceinline__ uint32_t encode_one(uint32_t ybits, const uint8_t* lut, const HrExp* hrt,
+                                              uint32_t mode) {
   if (IMPL == IMPL_TA_LUT) {
     uint32_t c = lut[ybits >> 19];
     // NaNs whose payload sits only in the low 19 bits index the Inf entry; fix them here.
@@ -66,11 +70,11 @@ __device__ __forceinline__ uint32_t encode_one(uint32_t ybits, const uint8_t* lu
   } else if (IMPL == IMPL_TA_ALU) {
     return encode_alu<false, SRC16>(ybits, mode);
   } else {
-    // HR: integer rounding, then the byte of the (now representable) pattern from the table
-    const uint32_t a = ybits & 0x7FFFFFFFu;
-    const uint32_t r = round_mag<true, SRC16>(a > 0x7F800000u ? 0u : a, ybits);
-    uint32_t c = lut[(r | (ybits & 0x80000000u)) >> 19];
-    if (a > 0x7F800000u) c = nan_code(mode);
+    // HR: table-driven rounding to the grid, then the byte of the (now representable)
+    // pattern from the TA table
+    const uint32_t r = hr_round_bits<SRC16>(ybits, hrt[(ybits >> 23) & 0xFFu]);
+    uint32_t c = lut[r >> 19];
+    if ((ybits & 0x7FFFFFFFu) > 0x7F800000u) c = nan_code(mode);
     return c;
   }
 }
@@ -81,29 +85,29 @@ __device__ __forceinline__ uint32_t scaled_bits(uint32_t xbits, float scale) {
 
 template <int IMPL>
 __device__ __forceinline__ uint32_t encode4_f32(const uint4& v, float scale, const uint8_t* lut,
-                                               uint32_t mode) {
-  const uint32_t c0 = encode_one<IMPL, false>(scaled_bits(v.x, scale), lut, mode);
-  const uint32_t c1 = encode_one<IMPL, false>(scaled_bits(v.y, scale), lut, mode);
-  const uint32_t c2 = encode_one<IMPL, false>(scaled_bits(v.z, scale), lut, mode);
-  const uint32_t c3 = encode_one<IMPL, false>(scaled_bits(v.w, scale), lut, mode);
+                                               const HrExp* hrt, uint32_t mode) {
+  const uint32_t c0 = encode_one<IMPL, false>(scaled_bits(v.x, scale), lut, hrt, mode);
+  const uint32_t c1 = encode_one<IMPL, false>(scaled_bits(v.y, scale), lut, hrt, mode);
+  const uint32_t c2 = encode_one<IMPL, false>(scaled_bits(v.z, scale), lut, hrt, mode);
+  const uint32_t c3 = encode_one<IMPL, false>(scaled_bits(v.w, scale), lut, hrt, mode);
   return c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
 }
 
 // two bfloat16 in one dword -> two codes in the low 16 bits
 template <int IMPL>
 __device__ __forceinline__ uint32_t encode2_bf16(uint32_t w, float scale, const uint8_t* lut,
-                                                uint32_t mode) {
-  const uint32_t c0 = encode_one<IMPL, true>(scaled_bits(w << 16, scale), lut, mode);
-  const uint32_t c1 = encode_one<IMPL, true>(scaled_bits(w & 0xFFFF0000u, scale), lut, mode);
+                                                const HrExp* hrt, uint32_t mode) {
+  const uint32_t c0 = encode_one<IMPL, true>(scaled_bits(w << 16, scale), lut, hrt, mode);
+  const uint32_t c1 = encode_one<IMPL, true>(scaled_bits(w & 0xFFFF0000u, scale), lut, hrt, mode);
   return c0 | (c1 << 8);
 }
 
 template <int IMPL>
 __device__ __forceinline__ uint2 encode8_bf16(const uint4& v, float scale, const uint8_t* lut,
-                                              uint32_t mode) {
+                                              const HrExp* hrt, uint32_t mode) {
   uint2 o;
-  o.x = encode2_bf16<IMPL>(v.x, scale, lut, mode) | (encode2_bf16<IMPL>(v.y, scale, lut, mode) << 16);
-  o.y = encode2_bf16<IMPL>(v.z, scale, lut, mode) | (encode2_bf16<IMPL>(v.w, scale, lut, mode) << 16);
+  o.x = encode2_bf16<IMPL>(v.x, scale, lut, hrt, mode) | (encode2_bf16<IMPL>(v.y, scale, lut, hrt, mode) << 16);
+  o.y = encode2_bf16<IMPL>(v.z, scale, lut, hrt, mode) | (encode2_bf16<IMPL>(v.w, scale, lut, hrt, mode) << 16);
   return o;
 }
 
@@ -111,9 +115,15 @@ __device__ __forceinline__ uint32_t descale_bits(uint32_t code, const uint32_t* 
   return __float_as_uint(__fmul_rn(__uint_as_float(dec[code & 0xFFu]), inv));
 }
 
+// two codes -> two descaled bfloat16 in one dword; the narrowing is the hardware's packed
+// round-to-nearest-even conversion (v_cvt_pk_bf16_f32)
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t descale2_bf16(uint32_t c0, uint32_t c1, const uint32_t* dec,
                                                   float inv) {
-  return narrow_bf16(descale_bits(c0, dec, inv)) | (narrow_bf16(descale_bits(c1, dec, inv)) << 16);
+  const f32x2_t f = {__uint_as_float(descale_bits(c0, dec, inv)),
+                     __uint_as_float(descale_bits(c1, dec, inv))};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
 }
 
 // ------------------------------------------------------------------------------------
@@ -121,94 +131,155 @@ __device__ __forceinline__ uint32_t descale2_bf16(uint32_t c0, uint32_t c1, cons
 // worth of codes).  A tile is blockDim.x * U vector units; blocks stride over tiles.
 // The ragged tail (n modulo the vector width) is done element-wise by block 0.
 // ------------------------------------------------------------------------------------
-template <int U, typename V, typename LoadF, typename StoreF>
-__device__ __forceinline__ void tile_loop(size_t nvec, LoadF load, StoreF store) {
+// How a workgroup walks the tiles of a tensor (tile t = vector units [t*tile, (t+1)*tile)):
+// workgroup b visits tiles b*first_mul + i*stride for i in [0, count).
+//   persistent grid : first_mul = 1, stride = gridDim.x, count = ceil(tiles / gridDim.x)
+//   one-shot chunks : first_mul = count = tiles per workgroup, stride = 1; the hardware
+//                     dispatcher hands out chunks in address order as workgroups retire, which
+//                     keeps the set of DRAM pages being streamed compact.
+struct Walk {
+  uint32_t first_mul;
+  uint32_t stride;
+  uint32_t count;
+};
+
+// Streaming (non-temporal) 16 / 8 / 4-byte accesses: the data is touched once.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint4 ld_stream(const uint4* p) {
+  const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ uint2 ld_stream(const uint2* p) {
+  const u32x2 t = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+  return make_uint2(t.x, t.y);
+}
+__device__ __forceinline__ uint32_t ld_stream(const uint32_t* p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ void st_stream(uint4* p, const uint4& v) {
+  const u32x4 t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, reinterpret_cast<u32x4*>(p));
+}
+__device__ __forceinline__ void st_stream(uint2* p, const uint2& v) {
+  const u32x2 t = {v.x, v.y};
+  __builtin_nontemporal_store(t, reinterpret_cast<u32x2*>(p));
+}
+__device__ __forceinline__ void st_stream(uint32_t* p, uint32_t v) { __builtin_nontemporal_store(v, p); }
+
+// The first tile's loads are issued before `prologue` (table staging + barrier) runs, so the
+// staging latency overlaps with the first HBM round trip.
+template <int U, typename V, typename LoadF, typename StoreF, typename PrologueF>
+__device__ __forceinline__ void tile_loop(size_t nvec, const Walk w, LoadF load, StoreF store,
+                                          PrologueF prologue) {
   const size_t tile = (size_t)blockDim.x * U;
-  for (size_t base = (size_t)blockIdx.x * tile; base < nvec; base += (size_t)gridDim.x * tile) {
-    V v[U];
-    const size_t first = base + threadIdx.x;
-    if (base + tile <= nvec) {  // full tile: U independent loads in flight, then U stores
+  size_t base = (size_t)blockIdx.x * w.first_mul * tile;
+  V v[U];
+  auto load_tile = [&](size_t b) {
+    const size_t first = b + threadIdx.x;
+    if (b + tile <= nvec) {
 #pragma unroll
       for (int j = 0; j < U; ++j) v[j] = load(first + (size_t)j * blockDim.x);
-#pragma unroll
-      for (int j = 0; j < U; ++j) store(first + (size_t)j * blockDim.x, v[j]);
     } else {
 #pragma unroll
       for (int j = 0; j < U; ++j) {
         const size_t idx = first + (size_t)j * blockDim.x;
         if (idx < nvec) v[j] = load(idx);
       }
+    }
+  };
+  auto store_tile = [&](size_t b) {
+    const size_t first = b + threadIdx.x;
+    if (b + tile <= nvec) {
+#pragma unroll
+      for (int j = 0; j < U; ++j) store(first + (size_t)j * blockDim.x, v[j]);
+    } else {
 #pragma unroll
       for (int j = 0; j < U; ++j) {
         const size_t idx = first + (size_t)j * blockDim.x;
         if (idx < nvec) store(idx, v[j]);
       }
     }
+  };
+  if (w.count > 0 && base < nvec) load_tile(base);
+  prologue();
+  for (uint32_t i = 0; i < w.count && base < nvec; ++i) {
+    store_tile(base);
+    base += (size_t)w.stride * tile;
+    if (i + 1 < w.count && base < nvec) load_tile(base);
   }
 }
 
 template <int U, int IMPL>
 __global__ void __launch_bounds__(1024)
 k_encode_f32(const float* __restrict__ src, uint8_t* __restrict__ dst, size_t n, float scale_arg,
-             const float* __restrict__ d_scale2, uint32_t mode) {
+             const float* __restrict__ d_scale2, uint32_t mode, Walk walk) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[IMPL == IMPL_TA_ALU ? 16 : 8192];
+  __shared__ __attribute__((aligned(8))) HrExp hrt[IMPL == IMPL_HR ? 256 : 1];
   const float scale = d_scale2 ? d_scale2[0] : scale_arg;
-  if (IMPL != IMPL_TA_ALU) {
-    stage_enc_lut(lut, mode);
-    __syncthreads();
-  }
   const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(src);
   uint32_t* __restrict__ dst4 = reinterpret_cast<uint32_t*>(dst);
   const size_t nvec = n >> 2;
   tile_loop<U, uint4>(
-      nvec, [&](size_t idx) { return src4[idx]; },
-      [&](size_t idx, const uint4& v) { dst4[idx] = encode4_f32<IMPL>(v, scale, lut, mode); });
+      nvec, walk, [&](size_t idx) { return ld_stream(src4 + idx); },
+      [&](size_t idx, const uint4& v) { st_stream(dst4 + idx, encode4_f32<IMPL>(v, scale, lut, hrt, mode)); },
+      [&]() {
+        if (IMPL != IMPL_TA_ALU) {
+          stage_enc_lut(lut, mode);
+          if (IMPL == IMPL_HR) stage_hr_table(hrt);
+          __syncthreads();
+        }
+      });
   const size_t t = (nvec << 2) + threadIdx.x;
   if (blockIdx.x == 0 && t < n)
-    dst[t] = (uint8_t)encode_one<IMPL, false>(scaled_bits(__float_as_uint(src[t]), scale), lut, mode);
+    dst[t] = (uint8_t)encode_one<IMPL, false>(scaled_bits(__float_as_uint(src[t]), scale), lut, hrt, mode);
 }
 
 template <int U, int IMPL>
 __global__ void __launch_bounds__(1024)
 k_encode_bf16(const uint16_t* __restrict__ src, uint8_t* __restrict__ dst, size_t n,
-              float scale_arg, const float* __restrict__ d_scale2, uint32_t mode) {
+              float scale_arg, const float* __restrict__ d_scale2, uint32_t mode, Walk walk) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[IMPL == IMPL_TA_ALU ? 16 : 8192];
+  __shared__ __attribute__((aligned(8))) HrExp hrt[IMPL == IMPL_HR ? 256 : 1];
   const float scale = d_scale2 ? d_scale2[0] : scale_arg;
-  if (IMPL != IMPL_TA_ALU) {
-    stage_enc_lut(lut, mode);
-    __syncthreads();
-  }
   const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(src);
   uint2* __restrict__ dst8 = reinterpret_cast<uint2*>(dst);
   const size_t nvec = n >> 3;
   tile_loop<U, uint4>(
-      nvec, [&](size_t idx) { return src4[idx]; },
-      [&](size_t idx, const uint4& v) { dst8[idx] = encode8_bf16<IMPL>(v, scale, lut, mode); });
+      nvec, walk, [&](size_t idx) { return ld_stream(src4 + idx); },
+      [&](size_t idx, const uint4& v) { st_stream(dst8 + idx, encode8_bf16<IMPL>(v, scale, lut, hrt, mode)); },
+      [&]() {
+        if (IMPL != IMPL_TA_ALU) {
+          stage_enc_lut(lut, mode);
+          if (IMPL == IMPL_HR) stage_hr_table(hrt);
+          __syncthreads();
+        }
+      });
   const size_t t = (nvec << 3) + threadIdx.x;
   if (blockIdx.x == 0 && t < n)
-    dst[t] = (uint8_t)encode_one<IMPL, true>(scaled_bits((uint32_t)src[t] << 16, scale), lut, mode);
+    dst[t] = (uint8_t)encode_one<IMPL, true>(scaled_bits((uint32_t)src[t] << 16, scale), lut, hrt, mode);
 }
 
 template <int U>
 __global__ void __launch_bounds__(1024)
 k_decode_f32(const uint8_t* __restrict__ src, float* __restrict__ dst, size_t n, float inv_arg,
-             const float* __restrict__ d_scale2) {
+             const float* __restrict__ d_scale2, Walk walk) {
   __shared__ uint32_t dec[256];
   const float inv = d_scale2 ? d_scale2[1] : inv_arg;  // fl32(1/scale), computed by the host
-  stage_dec_lut(dec);
-  __syncthreads();
   const uint32_t* __restrict__ src4 = reinterpret_cast<const uint32_t*>(src);
   uint4* __restrict__ dst4 = reinterpret_cast<uint4*>(dst);
   const size_t nvec = n >> 2;
   tile_loop<U, uint32_t>(
-      nvec, [&](size_t idx) { return src4[idx]; },
+      nvec, walk, [&](size_t idx) { return ld_stream(src4 + idx); },
       [&](size_t idx, uint32_t w) {
         uint4 o;
         o.x = descale_bits(w, dec, inv);
         o.y = descale_bits(w >> 8, dec, inv);
         o.z = descale_bits(w >> 16, dec, inv);
         o.w = descale_bits(w >> 24, dec, inv);
-        dst4[idx] = o;
+        st_stream(dst4 + idx, o);
+      },
+      [&]() {
+        stage_dec_lut(dec);
+        __syncthreads();
       });
   const size_t t = (nvec << 2) + threadIdx.x;
   if (blockIdx.x == 0 && t < n) dst[t] = __uint_as_float(descale_bits(src[t], dec, inv));
@@ -217,23 +288,25 @@ k_decode_f32(const uint8_t* __restrict__ src, float* __restrict__ dst, size_t n,
 template <int U>
 __global__ void __launch_bounds__(1024)
 k_decode_bf16(const uint8_t* __restrict__ src, uint16_t* __restrict__ dst, size_t n,
-              float inv_arg, const float* __restrict__ d_scale2) {
+              float inv_arg, const float* __restrict__ d_scale2, Walk walk) {
   __shared__ uint32_t dec[256];
   const float inv = d_scale2 ? d_scale2[1] : inv_arg;
-  stage_dec_lut(dec);
-  __syncthreads();
   const uint2* __restrict__ src8 = reinterpret_cast<const uint2*>(src);
   uint4* __restrict__ dst16 = reinterpret_cast<uint4*>(dst);
   const size_t nvec = n >> 3;
   tile_loop<U, uint2>(
-      nvec, [&](size_t idx) { return src8[idx]; },
+      nvec, walk, [&](size_t idx) { return ld_stream(src8 + idx); },
       [&](size_t idx, const uint2& w) {
         uint4 o;
         o.x = descale2_bf16(w.x, w.x >> 8, dec, inv);
         o.y = descale2_bf16(w.x >> 16, w.x >> 24, dec, inv);
         o.z = descale2_bf16(w.y, w.y >> 8, dec, inv);
         o.w = descale2_bf16(w.y >> 16, w.y >> 24, dec, inv);
-        dst16[idx] = o;
+        st_stream(dst16 + idx, o);
+      },
+      [&]() {
+        stage_dec_lut(dec);
+        __syncthreads();
       });
   const size_t t = (nvec << 3) + threadIdx.x;
   if (blockIdx.x == 0 && t < n) dst[t] = (uint16_t)narrow_bf16(descale_bits(src[t], dec, inv));
@@ -243,33 +316,38 @@ k_decode_bf16(const uint8_t* __restrict__ src, uint16_t* __restrict__ dst, size_
 template <int U, int IMPL, bool CODES>
 __global__ void __launch_bounds__(1024)
 k_fake_quant_f32(const float* src, float* dst, uint8_t* codes, size_t n, float scale_arg,
-                 float inv_arg, const float* __restrict__ d_scale2, uint32_t mode) {
+                 float inv_arg, const float* __restrict__ d_scale2, uint32_t mode, Walk walk) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[IMPL == IMPL_TA_ALU ? 16 : 8192];
+  __shared__ __attribute__((aligned(8))) HrExp hrt[IMPL == IMPL_HR ? 256 : 1];
   __shared__ uint32_t dec[256];
   const float scale = d_scale2 ? d_scale2[0] : scale_arg;
   const float inv = d_scale2 ? d_scale2[1] : inv_arg;
-  if (IMPL != IMPL_TA_ALU) stage_enc_lut(lut, mode);
-  stage_dec_lut(dec);
-  __syncthreads();
+  auto prologue = [&]() {
+    if (IMPL != IMPL_TA_ALU) stage_enc_lut(lut, mode);
+    if (IMPL == IMPL_HR) stage_hr_table(hrt);
+    stage_dec_lut(dec);
+    __syncthreads();
+  };
   const uint4* src4 = reinterpret_cast<const uint4*>(src);
   uint4* dst4 = reinterpret_cast<uint4*>(dst);
   uint32_t* codes4 = reinterpret_cast<uint32_t*>(codes);
   const size_t nvec = n >> 2;
   tile_loop<U, uint4>(
-      nvec, [&](size_t idx) { return src4[idx]; },
+      nvec, walk, [&](size_t idx) { return ld_stream(src4 + idx); },
       [&](size_t idx, const uint4& v) {
-        const uint32_t w = encode4_f32<IMPL>(v, scale, lut, mode);
+        const uint32_t w = encode4_f32<IMPL>(v, scale, lut, hrt, mode);
         uint4 o;
         o.x = descale_bits(w, dec, inv);
         o.y = descale_bits(w >> 8, dec, inv);
         o.z = descale_bits(w >> 16, dec, inv);
         o.w = descale_bits(w >> 24, dec, inv);
-        dst4[idx] = o;
-        if (CODES) codes4[idx] = w;
-      });
+        st_stream(dst4 + idx, o);
+        if (CODES) st_stream(codes4 + idx, w);
+      },
+      prologue);
   const size_t t = (nvec << 2) + threadIdx.x;
   if (blockIdx.x == 0 && t < n) {
-    const uint32_t c = encode_one<IMPL, false>(scaled_bits(__float_as_uint(src[t]), scale), lut, mode);
+    const uint32_t c = encode_one<IMPL, false>(scaled_bits(__float_as_uint(src[t]), scale), lut, hrt, mode);
     dst[t] = __uint_as_float(descale_bits(c, dec, inv));
     if (CODES) codes[t] = (uint8_t)c;
   }
@@ -278,33 +356,38 @@ k_fake_quant_f32(const float* src, float* dst, uint8_t* codes, size_t n, float s
 template <int U, int IMPL, bool CODES>
 __global__ void __launch_bounds__(1024)
 k_fake_quant_bf16(const uint16_t* src, uint16_t* dst, uint8_t* codes, size_t n, float scale_arg,
-                  float inv_arg, const float* __restrict__ d_scale2, uint32_t mode) {
+                  float inv_arg, const float* __restrict__ d_scale2, uint32_t mode, Walk walk) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[IMPL == IMPL_TA_ALU ? 16 : 8192];
+  __shared__ __attribute__((aligned(8))) HrExp hrt[IMPL == IMPL_HR ? 256 : 1];
   __shared__ uint32_t dec[256];
   const float scale = d_scale2 ? d_scale2[0] : scale_arg;
   const float inv = d_scale2 ? d_scale2[1] : inv_arg;
-  if (IMPL != IMPL_TA_ALU) stage_enc_lut(lut, mode);
-  stage_dec_lut(dec);
-  __syncthreads();
+  auto prologue = [&]() {
+    if (IMPL != IMPL_TA_ALU) stage_enc_lut(lut, mode);
+    if (IMPL == IMPL_HR) stage_hr_table(hrt);
+    stage_dec_lut(dec);
+    __syncthreads();
+  };
   const uint4* src4 = reinterpret_cast<const uint4*>(src);
   uint4* dst4 = reinterpret_cast<uint4*>(dst);
   uint2* codes8 = reinterpret_cast<uint2*>(codes);
   const size_t nvec = n >> 3;
   tile_loop<U, uint4>(
-      nvec, [&](size_t idx) { return src4[idx]; },
+      nvec, walk, [&](size_t idx) { return ld_stream(src4 + idx); },
       [&](size_t idx, const uint4& v) {
-        const uint2 w = encode8_bf16<IMPL>(v, scale, lut, mode);
+        const uint2 w = encode8_bf16<IMPL>(v, scale, lut, hrt, mode);
         uint4 o;
         o.x = descale2_bf16(w.x, w.x >> 8, dec, inv);
         o.y = descale2_bf16(w.x >> 16, w.x >> 24, dec, inv);
         o.z = descale2_bf16(w.y, w.y >> 8, dec, inv);
         o.w = descale2_bf16(w.y >> 16, w.y >> 24, dec, inv);
-        dst4[idx] = o;
-        if (CODES) codes8[idx] = w;
-      });
+        st_stream(dst4 + idx, o);
+        if (CODES) st_stream(codes8 + idx, w);
+      },
+      prologue);
   const size_t t = (nvec << 3) + threadIdx.x;
   if (blockIdx.x == 0 && t < n) {
-    const uint32_t c = encode_one<IMPL, true>(scaled_bits((uint32_t)src[t] << 16, scale), lut, mode);
+    const uint32_t c = encode_one<IMPL, true>(scaled_bits((uint32_t)src[t] << 16, scale), lut, hrt, mode);
     dst[t] = (uint16_t)narrow_bf16(descale_bits(c, dec, inv));
     if (CODES) codes[t] = (uint8_t)c;
   }
@@ -400,14 +483,14 @@ __global__ void k_fill_u32(uint32_t* p, uint32_t v, uint32_t count) {
 }
 
 // magnitude patterns as binary32 bits: FP32 -> bits & 0x7FFFFFFF; BF16 -> (bits & 0x7FFF) << 16
-template <int U, bool SRC16>
+template <int U, bool SRC16, bool NT>
 __global__ void __launch_bounds__(1024)
-k_amax(const void* __restrict__ src, size_t n, uint32_t* __restrict__ out) {
+k_amax(const void* __restrict__ src, size_t n, uint32_t* __restrict__ out, Walk walk) {
   const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(src);
   const size_t nvec = SRC16 ? (n >> 3) : (n >> 2);
   uint32_t m = 0;  // FP32: magnitude pattern; BF16: two 15-bit magnitudes, one per half
   tile_loop<U, uint4>(
-      nvec, [&](size_t idx) { return src4[idx]; },
+      nvec, walk, [&](size_t idx) { return NT ? ld_stream(src4 + idx) : src4[idx]; },
       [&](size_t, const uint4& v) {
         if (SRC16) {
           typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
@@ -421,7 +504,8 @@ k_amax(const void* __restrict__ src, size_t n, uint32_t* __restrict__ out) {
           m = umax(m, umax(umax(v.x & 0x7FFFFFFFu, v.y & 0x7FFFFFFFu),
                            umax(v.z & 0x7FFFFFFFu, v.w & 0x7FFFFFFFu)));
         }
-      });
+      },
+      []() {});
   if (SRC16) m = umax(m & 0xFFFFu, m >> 16) << 16;
   const size_t t = (SRC16 ? (nvec << 3) : (nvec << 2)) + threadIdx.x;
   if (blockIdx.x == 0 && t < n) {
@@ -469,14 +553,15 @@ __global__ void k_scale_from_amax(const float* d_amax, float* d_scale2, float ta
 // diagnostic stream kernel: read 16 B per lane, write the first OUT bytes of it
 template <int U, int OUT>
 __global__ void __launch_bounds__(1024)
-k_diag_stream(const uint4* __restrict__ src, void* __restrict__ dst, size_t nvec) {
+k_diag_stream(const uint4* __restrict__ src, void* __restrict__ dst, size_t nvec, Walk walk) {
   tile_loop<U, uint4>(
-      nvec, [&](size_t idx) { return src[idx]; },
+      nvec, walk, [&](size_t idx) { return ld_stream(src + idx); },
       [&](size_t idx, const uint4& v) {
-        if (OUT == 4) reinterpret_cast<uint32_t*>(dst)[idx] = v.x;
-        else if (OUT == 8) reinterpret_cast<uint2*>(dst)[idx] = make_uint2(v.x, v.y);
-        else reinterpret_cast<uint4*>(dst)[idx] = v;
-      });
+        if (OUT == 4) st_stream(reinterpret_cast<uint32_t*>(dst) + idx, v.x);
+        else if (OUT == 8) st_stream(reinterpret_cast<uint2*>(dst) + idx, make_uint2(v.x, v.y));
+        else st_stream(reinterpret_cast<uint4*>(dst) + idx, v);
+      },
+      []() {});
 }
 
 // ====================================================================================
@@ -486,13 +571,46 @@ namespace {
 
 thread_local int t_last_hip_error = 0;
 
+// Launch shape of one kernel family.  tiles_per_wg == 0 selects the persistent grid.
+struct Shape {
+  int block;
+  int unroll;
+  int tiles_per_wg;
+  int wg_per_cu;
+};
+enum Family { FAM_ENC32_TA, FAM_ENC32_HR, FAM_ENC16, FAM_FQ, FAM_DEC, FAM_AMAX, FAM_DIAG, FAM_COUNT };
+// Defaults from a sweep on MI355X (block x unroll x tiles-per-workgroup / persistent) with
+// 64 Mi-element tensors: one-shot grids of small chunks win for the read+write kernels,
+// a persistent grid of one large workgroup per CU wins for the read-only reduction.
+const Shape kDefaultShape[FAM_COUNT] = {
+    {256, 4, 1, 4},  // FP32 encode, TA
+    {512, 4, 1, 4},  // FP32 encode, HR
+    {512, 2, 2, 4},  // BF16 encode
+    {512, 2, 2, 4},  // fake-quant
+    {256, 2, 1, 4},  // decode
+    {512, 4, 0, 1},  // amax
+    {512, 1, 2, 4},  // diagnostic stream
+};
+
+// user overrides; -1 = use the family default
 struct Tuning {
-  int block = 512;
-  int wg_per_cu = 4;
-  int unroll = 4;
+  int block = -1;
+  int wg_per_cu = -1;
+  int unroll = -1;
   int ta_impl = 0;
+  int tiles_per_wg = -1;
+  int amax_nt = 1;
 };
 Tuning g_tune;
+
+Shape shape_for(Family f) {
+  Shape s = kDefaultShape[f];
+  if (g_tune.block >= 0) s.block = g_tune.block;
+  if (g_tune.unroll >= 0) s.unroll = g_tune.unroll;
+  if (g_tune.tiles_per_wg >= 0) s.tiles_per_wg = g_tune.tiles_per_wg;
+  if (g_tune.wg_per_cu >= 0) s.wg_per_cu = g_tune.wg_per_cu;
+  return s;
+}
 
 constexpr int kMaxDevices = 64;
 std::mutex g_init_mutex;
@@ -544,12 +662,22 @@ bool valid_scale(float scale, float* inv_out) {
   return true;
 }
 
-unsigned grid_for(size_t nvec, int cus) {
-  const size_t tile = (size_t)g_tune.block * (size_t)g_tune.unroll;
+// grid size and tile walk for nvec vector units under the current tuning
+unsigned grid_for(size_t nvec, int cus, const Shape& sh, Walk* walk) {
+  const size_t tile = (size_t)sh.block * (size_t)sh.unroll;
   size_t tiles = (nvec + tile - 1) / tile;
   if (tiles == 0) tiles = 1;  // block 0 still handles a ragged tail
-  const size_t cap = (size_t)cus * (size_t)g_tune.wg_per_cu;
-  return (unsigned)(tiles < cap ? tiles : cap);
+  size_t grid;
+  if (sh.tiles_per_wg > 0) {
+    const size_t tpw = (size_t)sh.tiles_per_wg;
+    grid = (tiles + tpw - 1) / tpw;
+    *walk = Walk{(uint32_t)tpw, 1u, (uint32_t)tpw};
+  } else {
+    const size_t cap = (size_t)cus * (size_t)sh.wg_per_cu;
+    grid = tiles < cap ? tiles : cap;
+    *walk = Walk{1u, (uint32_t)grid, (uint32_t)((tiles + grid - 1) / grid)};
+  }
+  return (unsigned)grid;
 }
 
 unsigned grid_elem(size_t n, int cus) {
@@ -565,7 +693,7 @@ int impl_for(uint32_t mode) {
 }
 
 #define HIF8_DISPATCH_U(CALL)             \
-  switch (g_tune.unroll) {                \
+  switch (shape.unroll) {                 \
     case 1: { constexpr int U = 1; CALL; } break; \
     case 2: { constexpr int U = 2; CALL; } break; \
     case 8: { constexpr int U = 8; CALL; } break; \
@@ -600,14 +728,16 @@ hif8_status do_encode(const void* src, uint8_t* dst, size_t n, float scale, cons
     return finish_launch();
   }
   const size_t nvec = SRC16 ? (n >> 3) : (n >> 2);
-  const dim3 grid(grid_for(nvec, cus)), block(g_tune.block);
   const int impl = impl_for(mode);
+  const Shape shape = shape_for(SRC16 ? FAM_ENC16 : (impl == IMPL_HR ? FAM_ENC32_HR : FAM_ENC32_TA));
+  Walk walk;
+  const dim3 grid(grid_for(nvec, cus, shape, &walk)), block(shape.block);
   if (SRC16) {
     HIF8_DISPATCH_U(HIF8_DISPATCH_IMPL(impl, hipLaunchKernelGGL((k_encode_bf16<U, IMPL>), grid, block, 0, st,
-        reinterpret_cast<const uint16_t*>(src), dst, n, scale, d_scale2, mode)))
+        reinterpret_cast<const uint16_t*>(src), dst, n, scale, d_scale2, mode, walk)))
   } else {
     HIF8_DISPATCH_U(HIF8_DISPATCH_IMPL(impl, hipLaunchKernelGGL((k_encode_f32<U, IMPL>), grid, block, 0, st,
-        reinterpret_cast<const float*>(src), dst, n, scale, d_scale2, mode)))
+        reinterpret_cast<const float*>(src), dst, n, scale, d_scale2, mode, walk)))
   }
   return finish_launch();
 }
@@ -629,13 +759,15 @@ hif8_status do_decode(const uint8_t* src, void* dst, size_t n, float scale, cons
     return finish_launch();
   }
   const size_t nvec = DST16 ? (n >> 3) : (n >> 2);
-  const dim3 grid(grid_for(nvec, cus)), block(g_tune.block);
+  const Shape shape = shape_for(FAM_DEC);
+  Walk walk;
+  const dim3 grid(grid_for(nvec, cus, shape, &walk)), block(shape.block);
   if (DST16) {
     HIF8_DISPATCH_U(hipLaunchKernelGGL((k_decode_bf16<U>), grid, block, 0, st, src,
-                                       reinterpret_cast<uint16_t*>(dst), n, inv, d_scale2))
+                                       reinterpret_cast<uint16_t*>(dst), n, inv, d_scale2, walk))
   } else {
     HIF8_DISPATCH_U(hipLaunchKernelGGL((k_decode_f32<U>), grid, block, 0, st, src,
-                                       reinterpret_cast<float*>(dst), n, inv, d_scale2))
+                                       reinterpret_cast<float*>(dst), n, inv, d_scale2, walk))
   }
   return finish_launch();
 }
@@ -658,11 +790,13 @@ hif8_status do_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, 
     return finish_launch();
   }
   const size_t nvec = T16 ? (n >> 3) : (n >> 2);
-  const dim3 grid(grid_for(nvec, cus)), block(g_tune.block);
+  const Shape shape = shape_for(FAM_FQ);
+  Walk walk;
+  const dim3 grid(grid_for(nvec, cus, shape, &walk)), block(shape.block);
   const int impl = impl_for(mode);
 #define HIF8_FQ_LAUNCH(KERNEL, TS, TD, CODESV)                                                        \
   HIF8_DISPATCH_U(HIF8_DISPATCH_IMPL(impl, hipLaunchKernelGGL((KERNEL<U, IMPL, CODESV>), grid, block, \
-      0, st, reinterpret_cast<TS>(src), reinterpret_cast<TD>(dst), codes, n, scale, inv, d_scale2, mode)))
+      0, st, reinterpret_cast<TS>(src), reinterpret_cast<TD>(dst), codes, n, scale, inv, d_scale2, mode, walk)))
   if (T16) {
     if (codes) { HIF8_FQ_LAUNCH(k_fake_quant_bf16, const uint16_t*, uint16_t*, true) }
     else { HIF8_FQ_LAUNCH(k_fake_quant_bf16, const uint16_t*, uint16_t*, false) }
@@ -689,8 +823,11 @@ hif8_status do_amax(const void* src, size_t n, float* d_amax, hipStream_t st) {
     return finish_launch();
   }
   const size_t nvec = SRC16 ? (n >> 3) : (n >> 2);
-  const dim3 grid(grid_for(nvec, cus)), block(g_tune.block);
-  HIF8_DISPATCH_U(hipLaunchKernelGGL((k_amax<U, SRC16>), grid, block, 0, st, src, n, out))
+  const Shape shape = shape_for(FAM_AMAX);
+  Walk walk;
+  const dim3 grid(grid_for(nvec, cus, shape, &walk)), block(shape.block);
+  if (g_tune.amax_nt) { HIF8_DISPATCH_U(hipLaunchKernelGGL((k_amax<U, SRC16, true>), grid, block, 0, st, src, n, out, walk)) }
+  else { HIF8_DISPATCH_U(hipLaunchKernelGGL((k_amax<U, SRC16, false>), grid, block, 0, st, src, n, out, walk)) }
   return finish_launch();
 }
 
@@ -705,20 +842,28 @@ hif8_status hif8_init(void) { return ensure_init(nullptr); }
 hif8_status hif8_set_tuning(int key, int value) {
   switch (key) {
     case HIF8_TUNE_BLOCK:
-      if (value < 64 || value > 1024 || (value % 64) != 0) return HIF8_ERR_ARG;
+      if (value != -1 && (value < 64 || value > 1024 || (value % 64) != 0)) return HIF8_ERR_ARG;
       g_tune.block = value;
       return HIF8_OK;
     case HIF8_TUNE_WG_PER_CU:
-      if (value < 1 || value > 32) return HIF8_ERR_ARG;
+      if (value != -1 && (value < 1 || value > 64)) return HIF8_ERR_ARG;
       g_tune.wg_per_cu = value;
       return HIF8_OK;
     case HIF8_TUNE_UNROLL:
-      if (value != 1 && value != 2 && value != 4 && value != 8) return HIF8_ERR_ARG;
+      if (value != -1 && value != 1 && value != 2 && value != 4 && value != 8) return HIF8_ERR_ARG;
       g_tune.unroll = value;
       return HIF8_OK;
     case HIF8_TUNE_TA_IMPL:
       if (value != 0 && value != 1) return HIF8_ERR_ARG;
       g_tune.ta_impl = value;
+      return HIF8_OK;
+    case HIF8_TUNE_TILES_PER_WG:
+      if (value < -1 || value > 4096) return HIF8_ERR_ARG;
+      g_tune.tiles_per_wg = value;
+      return HIF8_OK;
+    case HIF8_TUNE_AMAX_NT:
+      if (value != 0 && value != 1) return HIF8_ERR_ARG;
+      g_tune.amax_nt = value;
       return HIF8_OK;
     default:
       return HIF8_ERR_ARG;
@@ -731,6 +876,8 @@ int hif8_get_tuning(int key) {
     case HIF8_TUNE_WG_PER_CU: return g_tune.wg_per_cu;
     case HIF8_TUNE_UNROLL: return g_tune.unroll;
     case HIF8_TUNE_TA_IMPL: return g_tune.ta_impl;
+    case HIF8_TUNE_TILES_PER_WG: return g_tune.tiles_per_wg;
+    case HIF8_TUNE_AMAX_NT: return g_tune.amax_nt;
     default: return -1;
   }
 }
@@ -816,12 +963,14 @@ hif8_status hif8_diag_stream(const void* src, void* dst, size_t n_groups, int ou
   int cus = 0;
   hif8_status s = ensure_init(&cus);
   if (s != HIF8_OK) return s;
-  const dim3 grid(grid_for(n_groups, cus)), block(g_tune.block);
+  const Shape shape = shape_for(FAM_DIAG);
+  Walk walk;
+  const dim3 grid(grid_for(n_groups, cus, shape, &walk)), block(shape.block);
   const uint4* s4 = reinterpret_cast<const uint4*>(src);
   hipStream_t st = (hipStream_t)stream;
-  if (out_bytes == 4) { HIF8_DISPATCH_U(hipLaunchKernelGGL((k_diag_stream<U, 4>), grid, block, 0, st, s4, dst, n_groups)) }
-  else if (out_bytes == 8) { HIF8_DISPATCH_U(hipLaunchKernelGGL((k_diag_stream<U, 8>), grid, block, 0, st, s4, dst, n_groups)) }
-  else { HIF8_DISPATCH_U(hipLaunchKernelGGL((k_diag_stream<U, 16>), grid, block, 0, st, s4, dst, n_groups)) }
+  if (out_bytes == 4) { HIF8_DISPATCH_U(hipLaunchKernelGGL((k_diag_stream<U, 4>), grid, block, 0, st, s4, dst, n_groups, walk)) }
+  else if (out_bytes == 8) { HIF8_DISPATCH_U(hipLaunchKernelGGL((k_diag_stream<U, 8>), grid, block, 0, st, s4, dst, n_groups, walk)) }
+  else { HIF8_DISPATCH_U(hipLaunchKernelGGL((k_diag_stream<U, 16>), grid, block, 0, st, s4, dst, n_groups, walk)) }
   return finish_launch();
 }
 

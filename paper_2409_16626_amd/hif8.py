@@ -19,7 +19,8 @@ FLAG_SAT = 0x10
 FLAG_NAN2ZERO = 0x20
 MAX_FINITE = 32768.0
 
-TUNE_BLOCK, TUNE_WG_PER_CU, TUNE_UNROLL, TUNE_TA_IMPL = 0, 1, 2, 3
+TUNE_BLOCK, TUNE_WG_PER_CU, TUNE_UNROLL, TUNE_TA_IMPL, TUNE_TILES_PER_WG, TUNE_AMAX_NT = 0, 1, 2, 3, 4, 5
+N_TUNE_KEYS = 6
 
 _STATUS = {0: "HIF8_OK", -1: "HIF8_ERR_NULL", -2: "HIF8_ERR_MODE", -3: "HIF8_ERR_SCALE",
            -4: "HIF8_ERR_HIP", -5: "HIF8_ERR_ARG"}

@@ -20,6 +20,16 @@ void devfn_encode_bits(const uint32_t* ybits, uint8_t* dst, size_t n, uint32_t m
     dst[i] = (uint8_t)c;
   }
 }
+// table-driven hybrid rounding, then the TA code of the (representable) result
+void devfn_encode_bits_hr_table(const uint32_t* ybits, uint8_t* dst, size_t n, uint32_t mode, int src16) {
+  for (size_t i = 0; i < n; ++i) {
+    const uint32_t y = ybits[i];
+    if ((y & 0x7FFFFFFFu) > 0x7F800000u) { dst[i] = (uint8_t)hif8dev::nan_code(mode); continue; }
+    const hif8dev::HrExp p = hif8dev::hr_exp_entry((y >> 23) & 0xFFu);
+    const uint32_t r = src16 ? hif8dev::hr_round_bits<true>(y, p) : hif8dev::hr_round_bits<false>(y, p);
+    dst[i] = (uint8_t)hif8dev::encode_alu<false, false>(r & 0xFFF80000u, mode);
+  }
+}
 void devfn_decode_bits(const uint8_t* codes, uint32_t* dst, size_t n) {
   for (size_t i = 0; i < n; ++i) dst[i] = hif8dev::decode_bits(codes[i]);
 }

@@ -51,10 +51,11 @@ def test_argument_validation_happens_on_the_host():
 def test_tuning_knobs():
     from paper_2409_16626_amd import hif8
     L = hif8.lib
-    saved = [L.hif8_get_tuning(k) for k in range(4)]
+    saved = [L.hif8_get_tuning(k) for k in range(hif8.N_TUNE_KEYS)]
     assert L.hif8_set_tuning(0, 100) == -5 and L.hif8_set_tuning(0, 2048) == -5
     assert L.hif8_set_tuning(1, 0) == -5 and L.hif8_set_tuning(2, 3) == -5
     assert L.hif8_set_tuning(3, 2) == -5 and L.hif8_set_tuning(9, 1) == -5
+    assert L.hif8_set_tuning(4, -2) == -5 and L.hif8_set_tuning(4, 5000) == -5 and L.hif8_set_tuning(5, 2) == -5
     assert L.hif8_get_tuning(9) == -1
     assert L.hif8_set_tuning(0, 256) == 0 and L.hif8_get_tuning(0) == 256
     for k, v in enumerate(saved):

@@ -33,6 +33,16 @@ def dev():
 def _enc(lib, ybits, mode, src16):
     ybits = np.ascontiguousarray(ybits, np.uint32)
     out = np.empty(ybits.shape, np.uint8)
+    if (mode & 0xF) == orc.RM_HR:
+        # the streaming kernels' table-driven form must agree with the generic form
+        out2 = np.empty(ybits.shape, np.uint8)
+        lib.devfn_encode_bits_hr_table(ybits.ctypes.data_as(ctypes.c_void_p), out2.ctypes.data_as(ctypes.c_void_p),
+                                       ctypes.c_size_t(ybits.size), ctypes.c_uint32(mode), ctypes.c_int(src16))
+        lib.devfn_encode_bits(ybits.ctypes.data_as(ctypes.c_void_p), out.ctypes.data_as(ctypes.c_void_p),
+                              ctypes.c_size_t(ybits.size), ctypes.c_uint32(mode), ctypes.c_int(src16))
+        bad = np.nonzero(out != out2)[0]
+        assert bad.size == 0, [(hex(ybits[i]), hex(out[i]), hex(out2[i])) for i in bad[:8]]
+        return out2
     lib.devfn_encode_bits(ybits.ctypes.data_as(ctypes.c_void_p), out.ctypes.data_as(ctypes.c_void_p),
                           ctypes.c_size_t(ybits.size), ctypes.c_uint32(mode), ctypes.c_int(src16))
     return out

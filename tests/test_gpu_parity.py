@@ -56,6 +56,31 @@ def test_c1_decode_all_codes(h, scale):
     assert_same_bytes(bf16_bits(out16), orc.decode_bf16(c, scale), "decode_bf16")
 
 
+@pytest.mark.parametrize("scale", [2.0 ** 110, 2.0 ** 120, 2.0 ** -100, 3.0e37, 1.7e-38])
+def test_decode_and_fake_quant_extreme_scales(h, scale):
+    """Descaled outputs that are binary32 / bfloat16 subnormals, or overflow to Inf."""
+    from paper_2409_16626_amd import workloads
+    codes = workloads.all_codes(dev()).repeat(5)[:1275]
+    n = codes.numel()
+    out32 = torch.empty(n, dtype=torch.float32, device=dev())
+    out16 = torch.empty(n, dtype=torch.bfloat16, device=dev())
+    h.hif8_decode_f32(codes, out32, n, scale)
+    h.hif8_decode_bf16(codes, out16, n, scale)
+    torch.cuda.synchronize()
+    c = codes.cpu().numpy()
+    assert_same_bytes(f32_bits(out32), orc.decode_f32(c, scale).view(np.uint32), "decode_f32 extreme")
+    assert_same_bytes(bf16_bits(out16), orc.decode_bf16(c, scale), "decode_bf16 extreme")
+    x = (workloads.normal_f32(1 << 12, dev()) / scale).to(torch.float32)
+    xn = x.cpu().numpy()
+    o = torch.empty_like(x)
+    cc = torch.empty(x.numel(), dtype=torch.uint8, device=dev())
+    h.hif8_fake_quant_f32(x, o, cc, x.numel(), scale, HR)
+    torch.cuda.synchronize()
+    wo, wc = orc.fake_quant_f32(xn, scale, HR)
+    assert_same_bytes(cc.cpu().numpy(), wc, "fq extreme codes")
+    assert_same_bytes(f32_bits(o), wo.view(np.uint32), "fq extreme out")
+
+
 @pytest.mark.parametrize("mode", ALL_MODES)
 def test_c1_encode_all_fp16_patterns(h, mode):
     from paper_2409_16626_amd import workloads
@@ -314,16 +339,21 @@ def test_amax_special_values(h):
         assert sc.cpu().tolist() == [1.0, 1.0]
 
 
-@pytest.mark.parametrize("block,wg,unroll,impl", [(64, 1, 1, 0), (256, 8, 2, 0), (1024, 2, 8, 0),
-                                                  (512, 4, 4, 1), (128, 16, 8, 1), (320, 3, 2, 0)])
-def test_launch_shapes_and_alu_variant(h, block, wg, unroll, impl):
+@pytest.mark.parametrize("block,wg,unroll,impl,tpw,amax_nt",
+                         [(64, 1, 1, 0, 0, 1), (256, 8, 2, 0, 0, 0), (1024, 2, 8, 0, 0, 1),
+                          (512, 4, 4, 1, 0, 1), (128, 16, 8, 1, 1, 0), (320, 3, 2, 0, 3, 1),
+                          (256, 4, 2, 0, 1, 1), (512, 4, 1, 0, 7, 0), (1024, 4, 4, 1, 16, 1),
+                          (64, 4, 1, 0, 4096, 1)])
+def test_launch_shapes_and_alu_variant(h, block, wg, unroll, impl, tpw, amax_nt):
     from paper_2409_16626_amd import workloads
-    saved = [h.hif8_get_tuning(k) for k in range(4)]
+    saved = [h.hif8_get_tuning(k) for k in range(h.N_TUNE_KEYS)]
     try:
         h.hif8_set_tuning(h.TUNE_BLOCK, block)
         h.hif8_set_tuning(h.TUNE_WG_PER_CU, wg)
         h.hif8_set_tuning(h.TUNE_UNROLL, unroll)
         h.hif8_set_tuning(h.TUNE_TA_IMPL, impl)
+        h.hif8_set_tuning(h.TUNE_TILES_PER_WG, tpw)
+        h.hif8_set_tuning(h.TUNE_AMAX_NT, amax_nt)
         x = workloads.dynamic_range_sweep((1 << 21) + 77, dev())
         xn = x.cpu().numpy()
         for mode in (TA, HR, TA | SAT | N2Z):
@@ -340,6 +370,15 @@ def test_launch_shapes_and_alu_variant(h, block, wg, unroll, impl):
         am = torch.zeros(1, dtype=torch.float32, device=dev())
         h.hif8_amax_f32(x, x.numel(), am)
         assert f32_bits(am)[0] == np.float32(orc.amax_f32(xn)).view(np.uint32)
+        h.hif8_amax_bf16(xb, xb.numel(), am)
+        assert f32_bits(am)[0] == np.float32(orc.amax_bf16(xbn)).view(np.uint32)
+        codes = c
+        o32 = torch.empty(codes.numel(), dtype=torch.float32, device=dev())
+        h.hif8_decode_f32(codes, o32, codes.numel(), 0.9)
+        h.hif8_decode_bf16(codes, o, codes.numel(), 0.9)
+        torch.cuda.synchronize()
+        assert_same_bytes(f32_bits(o32), orc.decode_f32(wc, 0.9).view(np.uint32), "tuned dec f32")
+        assert_same_bytes(bf16_bits(o), orc.decode_bf16(wc, 0.9), "tuned dec bf16")
     finally:
         for k, v in enumerate(saved):
             h.hif8_set_tuning(k, v)
