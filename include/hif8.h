@@ -166,6 +166,41 @@ hif8_status hif8_fake_quant_bf16_ds(const uint16_t* src, uint16_t* dst, uint8_t*
                                     hif8_stream_t stream);
 
 /*
+ * Multi-tensor cast: per-tensor amax, scale and encode for a whole list of tensors in four
+ * launches (clear, amax, scale, encode) instead of four per tensor -- the per-tensor scaling
+ * recipe of Sec. 5 applied to every weight (or activation) tensor of a model at once.
+ *
+ *   hif8_cast_item   one tensor: src (device, BF16 or FP32, 16-byte aligned), dst (device, n
+ *                    u8 codes, 8-byte aligned for BF16 sources, 4-byte for FP32), n elements,
+ *                    first_tile (filled by hif8_multi_plan).
+ *   hif8_multi_plan  HOST-side helper: validates a HOST array of items, fills first_tile and
+ *                    returns the total tile count.  The caller then copies the array to
+ *                    device memory (it may be reused for any number of casts).
+ *   hif8_multi_cast_{bf16,f32}
+ *                    d_items: the planned array in DEVICE memory; d_amax: count device floats
+ *                    (output, amax per tensor); d_scale2: 2*count device floats (output,
+ *                    {scale, 1/scale} per tensor, as hif8_scale_from_amax); target, pow2 as in
+ *                    hif8_scale_from_amax.  Results equal the per-tensor sequence
+ *                    hif8_amax_* -> hif8_scale_from_amax -> hif8_encode_*_ds.
+ * Misaligned items make hif8_multi_plan return HIF8_ERR_ARG (use the per-tensor calls).
+ */
+typedef struct hif8_cast_item {
+  const void* src;
+  uint8_t* dst;
+  uint64_t n;
+  uint64_t first_tile;
+} hif8_cast_item;
+
+hif8_status hif8_multi_plan(hif8_cast_item* host_items, size_t count, int src_is_bf16,
+                            uint64_t* total_tiles_out);
+hif8_status hif8_multi_cast_bf16(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
+                                 float* d_amax, float* d_scale2, float target, int pow2,
+                                 uint32_t rounding_mode, hif8_stream_t stream);
+hif8_status hif8_multi_cast_f32(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
+                                float* d_amax, float* d_scale2, float target, int pow2,
+                                uint32_t rounding_mode, hif8_stream_t stream);
+
+/*
  * Launch-shape tuning knobs (process-wide; for benchmarking and profiling).  The first,
  * second, third and fifth default to -1 = "use the built-in shape of each kernel family".
  *   HIF8_TUNE_BLOCK        threads per workgroup of the streaming kernels (64..1024, multiple of 64)

@@ -530,8 +530,12 @@ k_amax_elem(const void* __restrict__ src, size_t n, uint32_t* __restrict__ out) 
 }
 
 // scale = fl32(target / amax) (optionally floored to a power of two), inverse = fl32(1 / scale)
-__global__ void k_scale_from_amax(const float* d_amax, float* d_scale2, float target, int pow2) {
-  if (blockIdx.x != 0 || threadIdx.x != 0) return;
+__global__ void k_scale_from_amax(const float* d_amax, float* d_scale2, uint32_t count, float target,
+                                  int pow2) {
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= count) return;
+  d_amax += i;
+  d_scale2 += 2 * i;
   const float amax = *d_amax;
   const uint32_t ab = __float_as_uint(amax);
   float s = 1.0f;
@@ -548,6 +552,138 @@ __global__ void k_scale_from_amax(const float* d_amax, float* d_scale2, float ta
   }
   d_scale2[0] = s;
   d_scale2[1] = 1.0f / s;
+}
+
+// ------------------------------------------------------------------------------------
+// multi-tensor cast: many tensors per launch (amax, then scale, then encode), so that a
+// list of small tensors is not bound by launch gaps.  All tensors share one global tile
+// index space; items[i].first_tile is the prefix sum of tile counts.  A tile is
+// kMultiBlock * kMultiUnroll vector units of one tensor.
+// ------------------------------------------------------------------------------------
+constexpr int kMultiBlock = 512;
+constexpr int kMultiUnroll = 2;
+constexpr uint32_t kMultiTileVec = kMultiBlock * kMultiUnroll;
+constexpr uint32_t kMultiTpwEncode = 2;
+constexpr uint32_t kMultiTpwAmax = 8;
+
+// largest i with items[i].first_tile <= tile (zero-size items are skipped by construction)
+__device__ __forceinline__ uint32_t multi_find_item(const hif8_cast_item* __restrict__ items,
+                                                    uint32_t count, uint64_t tile) {
+  uint32_t lo = 0, hi = count;
+  while (hi - lo > 1u) {
+    const uint32_t mid = (lo + hi) >> 1;
+    if (items[mid].first_tile <= tile) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+template <bool SRC16>
+__device__ __forceinline__ uint64_t multi_item_tiles(uint64_t n) {
+  const uint64_t nvec = SRC16 ? (n >> 3) : (n >> 2);
+  const uint64_t t = (nvec + kMultiTileVec - 1) / kMultiTileVec;
+  return (t == 0 && n != 0) ? 1 : t;
+}
+
+template <bool SRC16>
+__global__ void __launch_bounds__(kMultiBlock)
+k_multi_amax(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_t total_tiles,
+             uint32_t* __restrict__ amax_out) {
+  uint32_t m = 0;
+  uint32_t cur = 0xFFFFFFFFu;
+  for (uint32_t i = 0; i < kMultiTpwAmax; ++i) {
+    const uint64_t tile = (uint64_t)blockIdx.x * kMultiTpwAmax + i;
+    if (tile >= total_tiles) break;
+    const uint32_t it = multi_find_item(items, count, tile);
+    if (it != cur) {
+      if (cur != 0xFFFFFFFFu) {
+        block_max_to_global(SRC16 ? (umax(m & 0xFFFFu, m >> 16) << 16) : m, amax_out + cur);
+        __syncthreads();
+      }
+      cur = it;
+      m = 0;
+    }
+    const uint64_t n = items[it].n;
+    const uint64_t nvec = SRC16 ? (n >> 3) : (n >> 2);
+    const uint64_t local = tile - items[it].first_tile;
+    const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(items[it].src);
+    const uint64_t first = local * kMultiTileVec + threadIdx.x;
+    uint4 v[kMultiUnroll];
+#pragma unroll
+    for (int j = 0; j < kMultiUnroll; ++j) {
+      const uint64_t idx = first + (uint64_t)j * kMultiBlock;
+      v[j] = (idx < nvec) ? ld_stream(src4 + idx) : make_uint4(0u, 0u, 0u, 0u);
+    }
+#pragma unroll
+    for (int j = 0; j < kMultiUnroll; ++j) {
+      if (SRC16) {
+        typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+        u16x2 mm = __builtin_bit_cast(u16x2, m);
+        mm = __builtin_elementwise_max(mm, __builtin_bit_cast(u16x2, v[j].x & 0x7FFF7FFFu));
+        mm = __builtin_elementwise_max(mm, __builtin_bit_cast(u16x2, v[j].y & 0x7FFF7FFFu));
+        mm = __builtin_elementwise_max(mm, __builtin_bit_cast(u16x2, v[j].z & 0x7FFF7FFFu));
+        mm = __builtin_elementwise_max(mm, __builtin_bit_cast(u16x2, v[j].w & 0x7FFF7FFFu));
+        m = __builtin_bit_cast(uint32_t, mm);
+      } else {
+        m = umax(m, umax(umax(v[j].x & 0x7FFFFFFFu, v[j].y & 0x7FFFFFFFu),
+                         umax(v[j].z & 0x7FFFFFFFu, v[j].w & 0x7FFFFFFFu)));
+      }
+    }
+    // ragged tail of the tensor, done with its last tile
+    if (local + 1 == multi_item_tiles<SRC16>(n)) {
+      const uint64_t t = (SRC16 ? (nvec << 3) : (nvec << 2)) + threadIdx.x;
+      if (t < n) {
+        // BF16: m holds two 15-bit running maxima; a 15-bit value can join either half
+        if (SRC16) m = (m & 0xFFFF0000u) | umax(m & 0xFFFFu, (uint32_t) reinterpret_cast<const uint16_t*>(items[it].src)[t] & 0x7FFFu);
+        else m = umax(m, __float_as_uint(reinterpret_cast<const float*>(items[it].src)[t]) & 0x7FFFFFFFu);
+      }
+    }
+  }
+  if (cur != 0xFFFFFFFFu) block_max_to_global(SRC16 ? (umax(m & 0xFFFFu, m >> 16) << 16) : m, amax_out + cur);
+}
+
+template <int IMPL, bool SRC16>
+__global__ void __launch_bounds__(kMultiBlock)
+k_multi_encode(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_t total_tiles,
+               const float* __restrict__ d_scale2, uint32_t mode) {
+  __shared__ __attribute__((aligned(16))) uint8_t lut[8192];
+  __shared__ __attribute__((aligned(8))) HrExp hrt[IMPL == IMPL_HR ? 256 : 1];
+  stage_enc_lut(lut, mode);
+  if (IMPL == IMPL_HR) stage_hr_table(hrt);
+  __syncthreads();
+  for (uint32_t i = 0; i < kMultiTpwEncode; ++i) {
+    const uint64_t tile = (uint64_t)blockIdx.x * kMultiTpwEncode + i;
+    if (tile >= total_tiles) break;
+    const uint32_t it = multi_find_item(items, count, tile);
+    const uint64_t n = items[it].n;
+    const uint64_t nvec = SRC16 ? (n >> 3) : (n >> 2);
+    const uint64_t local = tile - items[it].first_tile;
+    const float scale = d_scale2 ? d_scale2[2 * it] : 1.0f;
+    const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(items[it].src);
+    uint8_t* __restrict__ dst = items[it].dst;
+    const uint64_t first = local * kMultiTileVec + threadIdx.x;
+    uint4 v[kMultiUnroll];
+#pragma unroll
+    for (int j = 0; j < kMultiUnroll; ++j) {
+      const uint64_t idx = first + (uint64_t)j * kMultiBlock;
+      if (idx < nvec) v[j] = ld_stream(src4 + idx);
+    }
+#pragma unroll
+    for (int j = 0; j < kMultiUnroll; ++j) {
+      const uint64_t idx = first + (uint64_t)j * kMultiBlock;
+      if (idx < nvec) {
+        if (SRC16) st_stream(reinterpret_cast<uint2*>(dst) + idx, encode8_bf16<IMPL>(v[j], scale, lut, hrt, mode));
+        else st_stream(reinterpret_cast<uint32_t*>(dst) + idx, encode4_f32<IMPL>(v[j], scale, lut, hrt, mode));
+      }
+    }
+    if (local + 1 == multi_item_tiles<SRC16>(n)) {
+      const uint64_t t = (SRC16 ? (nvec << 3) : (nvec << 2)) + threadIdx.x;
+      if (t < n) {
+        const uint32_t xb = SRC16 ? ((uint32_t) reinterpret_cast<const uint16_t*>(items[it].src)[t] << 16)
+                                  : __float_as_uint(reinterpret_cast<const float*>(items[it].src)[t]);
+        dst[t] = (uint8_t)encode_one<IMPL, SRC16>(scaled_bits(xb, scale), lut, hrt, mode);
+      }
+    }
+  }
 }
 
 // diagnostic stream kernel: read 16 B per lane, write the first OUT bytes of it
@@ -894,7 +1030,7 @@ hif8_status hif8_scale_from_amax(const float* d_amax, float* d_scale2, float tar
   if (!d_amax || !d_scale2) return HIF8_ERR_NULL;
   if (!(target > 0.0f) || std::isinf(target)) return HIF8_ERR_ARG;
   hipLaunchKernelGGL(k_scale_from_amax, dim3(1), dim3(64), 0, (hipStream_t)stream, d_amax, d_scale2,
-                     target, pow2);
+                     1u, target, pow2);
   return finish_launch();
 }
 
@@ -952,6 +1088,72 @@ hif8_status hif8_fake_quant_bf16_ds(const uint16_t* src, uint16_t* dst, uint8_t*
                                     const float* d_scale2, uint32_t mode, hif8_stream_t stream) {
   if (!d_scale2) return HIF8_ERR_NULL;
   return do_fake_quant<true>(src, dst, codes, n, 1.0f, d_scale2, mode, (hipStream_t)stream);
+}
+
+hif8_status hif8_multi_plan(hif8_cast_item* host_items, size_t count, int src_is_bf16,
+                            uint64_t* total_tiles_out) {
+  if (!total_tiles_out || (!host_items && count != 0)) return HIF8_ERR_NULL;
+  if (count > 0xFFFFFFu) return HIF8_ERR_ARG;
+  uint64_t tiles = 0;
+  for (size_t i = 0; i < count; ++i) {
+    hif8_cast_item& it = host_items[i];
+    if (it.n != 0 && (!it.src || !it.dst)) return HIF8_ERR_NULL;
+    if (!aligned_to(it.src, 16) || !aligned_to(it.dst, src_is_bf16 ? 8 : 4)) return HIF8_ERR_ARG;
+    it.first_tile = tiles;
+    const uint64_t nvec = src_is_bf16 ? (it.n >> 3) : (it.n >> 2);
+    uint64_t t = (nvec + kMultiTileVec - 1) / kMultiTileVec;
+    if (t == 0 && it.n != 0) t = 1;
+    tiles += t;
+  }
+  *total_tiles_out = tiles;
+  return HIF8_OK;
+}
+
+static hif8_status multi_cast(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
+                              float* d_amax, float* d_scale2, float target, int pow2, uint32_t mode,
+                              bool bf16, hipStream_t st) {
+  if (!valid_mode(mode)) return HIF8_ERR_MODE;
+  if (!(target > 0.0f) || std::isinf(target)) return HIF8_ERR_ARG;
+  if (count == 0) return HIF8_OK;
+  if (!d_items || !d_amax || !d_scale2) return HIF8_ERR_NULL;
+  if (count > 0xFFFFFFu) return HIF8_ERR_ARG;
+  hif8_status s = ensure_init(nullptr);
+  if (s != HIF8_OK) return s;
+  const uint32_t cnt = (uint32_t)count;
+  uint32_t* am = reinterpret_cast<uint32_t*>(d_amax);
+  hipLaunchKernelGGL(k_fill_u32, dim3((cnt + 255) / 256), dim3(256), 0, st, am, 0u, cnt);
+  if (total_tiles != 0) {
+    const unsigned g1 = (unsigned)((total_tiles + kMultiTpwAmax - 1) / kMultiTpwAmax);
+    if (bf16) hipLaunchKernelGGL(k_multi_amax<true>, dim3(g1), dim3(kMultiBlock), 0, st, d_items, cnt, total_tiles, am);
+    else hipLaunchKernelGGL(k_multi_amax<false>, dim3(g1), dim3(kMultiBlock), 0, st, d_items, cnt, total_tiles, am);
+  }
+  hipLaunchKernelGGL(k_scale_from_amax, dim3((cnt + 255) / 256), dim3(256), 0, st, d_amax, d_scale2, cnt,
+                     target, pow2);
+  if (total_tiles != 0) {
+    const unsigned g2 = (unsigned)((total_tiles + kMultiTpwEncode - 1) / kMultiTpwEncode);
+    const bool hr = (mode & HIF8_RM_MASK) == HIF8_RM_HR;
+    if (bf16) {
+      if (hr) hipLaunchKernelGGL((k_multi_encode<IMPL_HR, true>), dim3(g2), dim3(kMultiBlock), 0, st, d_items, cnt, total_tiles, d_scale2, mode);
+      else hipLaunchKernelGGL((k_multi_encode<IMPL_TA_LUT, true>), dim3(g2), dim3(kMultiBlock), 0, st, d_items, cnt, total_tiles, d_scale2, mode);
+    } else {
+      if (hr) hipLaunchKernelGGL((k_multi_encode<IMPL_HR, false>), dim3(g2), dim3(kMultiBlock), 0, st, d_items, cnt, total_tiles, d_scale2, mode);
+      else hipLaunchKernelGGL((k_multi_encode<IMPL_TA_LUT, false>), dim3(g2), dim3(kMultiBlock), 0, st, d_items, cnt, total_tiles, d_scale2, mode);
+    }
+  }
+  return finish_launch();
+}
+
+hif8_status hif8_multi_cast_bf16(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
+                                 float* d_amax, float* d_scale2, float target, int pow2,
+                                 uint32_t mode, hif8_stream_t stream) {
+  return multi_cast(d_items, count, total_tiles, d_amax, d_scale2, target, pow2, mode, true,
+                    (hipStream_t)stream);
+}
+hif8_status hif8_multi_cast_f32(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
+                                float* d_amax, float* d_scale2, float target, int pow2,
+                                uint32_t mode, hif8_stream_t stream) {
+  return multi_cast(d_items, count, total_tiles, d_amax, d_scale2, target, pow2, mode, false,
+                    (hipStream_t)stream);
 }
 
 hif8_status hif8_diag_stream(const void* src, void* dst, size_t n_groups, int out_bytes,

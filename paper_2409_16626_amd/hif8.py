@@ -64,6 +64,9 @@ _SIGS = {
     "hif8_decode_bf16_ds": ([_vp, _vp, _sz, _vp, _vp], _i),
     "hif8_fake_quant_f32_ds": ([_vp, _vp, _vp, _sz, _vp, _u32, _vp], _i),
     "hif8_fake_quant_bf16_ds": ([_vp, _vp, _vp, _sz, _vp, _u32, _vp], _i),
+    "hif8_multi_plan": ([_vp, _sz, _i, _vp], _i),
+    "hif8_multi_cast_bf16": ([_vp, _sz, ctypes.c_uint64, _vp, _vp, _f, _i, _u32, _vp], _i),
+    "hif8_multi_cast_f32": ([_vp, _sz, ctypes.c_uint64, _vp, _vp, _f, _i, _u32, _vp], _i),
     "hif8_set_tuning": ([_i, _i], _i),
     "hif8_get_tuning": ([_i], _i),
     "hif8_diag_stream": ([_vp, _vp, _sz, _i, _vp], _i),
@@ -176,6 +179,41 @@ def hif8_fake_quant_f32_ds(src, dst, codes_or_none, n, d_scale2, rounding_mode=R
 def hif8_fake_quant_bf16_ds(src, dst, codes_or_none, n, d_scale2, rounding_mode=RM_TA, stream=None):
     _check(lib.hif8_fake_quant_bf16_ds(_ptr(src), _ptr(dst), _ptr(codes_or_none), n, _ptr(d_scale2),
                                        rounding_mode, _stream(stream)))
+
+
+class CastItem(ctypes.Structure):
+    """Mirror of hif8_cast_item."""
+    _fields_ = [("src", ctypes.c_void_p), ("dst", ctypes.c_void_p), ("n", ctypes.c_uint64),
+                ("first_tile", ctypes.c_uint64)]
+
+
+def hif8_multi_plan(items, src_is_bf16=True):
+    """items: list of (src_ptr_or_tensor, dst_ptr_or_tensor, n).  Returns (device uint8 tensor
+    holding the planned hif8_cast_item array, count, total_tiles)."""
+    count = len(items)
+    arr = (CastItem * max(count, 1))()
+    for i, (src, dst, n) in enumerate(items):
+        arr[i].src = _ptr(src)
+        arr[i].dst = _ptr(dst)
+        arr[i].n = n
+    total = ctypes.c_uint64(0)
+    _check(lib.hif8_multi_plan(ctypes.cast(arr, ctypes.c_void_p), count, int(src_is_bf16),
+                               ctypes.cast(ctypes.byref(total), ctypes.c_void_p)))
+    raw = bytes(arr)[:count * ctypes.sizeof(CastItem)]
+    d_items = torch.frombuffer(bytearray(raw), dtype=torch.uint8).cuda() if count else torch.empty(0, dtype=torch.uint8, device="cuda")
+    return d_items, count, total.value
+
+
+def hif8_multi_cast_bf16(d_items, count, total_tiles, d_amax, d_scale2, target=MAX_FINITE, pow2=0,
+                         rounding_mode=RM_TA, stream=None):
+    _check(lib.hif8_multi_cast_bf16(_ptr(d_items), count, total_tiles, _ptr(d_amax), _ptr(d_scale2), target,
+                                    int(pow2), rounding_mode, _stream(stream)))
+
+
+def hif8_multi_cast_f32(d_items, count, total_tiles, d_amax, d_scale2, target=MAX_FINITE, pow2=0,
+                        rounding_mode=RM_TA, stream=None):
+    _check(lib.hif8_multi_cast_f32(_ptr(d_items), count, total_tiles, _ptr(d_amax), _ptr(d_scale2), target,
+                                   int(pow2), rounding_mode, _stream(stream)))
 
 
 def hif8_set_tuning(key, value):

@@ -48,6 +48,27 @@ def test_argument_validation_happens_on_the_host():
     assert L.hif8_diag_stream(p + 4, p, 16, 4, None) == ARG
 
 
+def test_multi_plan_is_host_only():
+    import ctypes
+    from paper_2409_16626_amd import hif8
+    arr = (hif8.CastItem * 3)()
+    for i, n in enumerate((8192 * 2 + 1, 0, 5)):
+        arr[i].src, arr[i].dst, arr[i].n = 0x10000 * (i + 1), 0x20000 * (i + 1), n
+    total = ctypes.c_uint64(0)
+    p = ctypes.cast(arr, ctypes.c_void_p)
+    tp = ctypes.cast(ctypes.byref(total), ctypes.c_void_p)
+    assert hif8.lib.hif8_multi_plan(p, 3, 1, tp) == 0
+    assert [arr[i].first_tile for i in range(3)] == [0, 2, 2] and total.value == 3
+    assert hif8.lib.hif8_multi_plan(p, 3, 0, tp) == 0
+    assert [arr[i].first_tile for i in range(3)] == [0, 4, 4] and total.value == 5
+    arr[2].src = 0x30004
+    assert hif8.lib.hif8_multi_plan(p, 3, 1, tp) == -5
+    arr[2].src = None
+    assert hif8.lib.hif8_multi_plan(p, 3, 1, tp) == -1
+    assert hif8.lib.hif8_multi_cast_bf16(p, 0, 0, None, None, 32768.0, 0, 0, None) == 0
+    assert hif8.lib.hif8_multi_cast_bf16(p, 3, 4, None, None, 32768.0, 0, 9, None) == -2
+
+
 def test_tuning_knobs():
     from paper_2409_16626_amd import hif8
     L = hif8.lib

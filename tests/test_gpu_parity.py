@@ -315,6 +315,42 @@ def test_c5_weight_cast_small(h):
         assert_same_bytes(cg[off:off + m], orc.encode_bf16(ab[off:off + m], w_s, TA), "C5 tensor %d" % i)
 
 
+@pytest.mark.parametrize("mode", [TA, HR | SAT])
+@pytest.mark.parametrize("pow2", [0, 1])
+def test_multi_tensor_cast_matches_per_tensor_oracle(h, mode, pow2):
+    """Tensor list with ragged, tiny and empty members: four launches for the whole list."""
+    rng = np.random.default_rng(41)
+    sizes = [8192 * 3, 0, 1, 7, 8, 8200, 12345, 8192, 100003, 16, 0, 65536 + 24]
+    for bf16 in (True, False):
+        offs, total = [], 0
+        for m in sizes:
+            offs.append(total)
+            total += (m + 15) // 16 * 16          # keep every slice 16-byte aligned
+        xf = torch.from_numpy((rng.standard_normal(total) * np.exp2(rng.uniform(-12, 3, total))).astype(np.float32)).to(dev())
+        x = xf.to(torch.bfloat16) if bf16 else xf
+        codes = torch.zeros(total, dtype=torch.uint8, device=dev())
+        items = [(x[o:o + m].data_ptr() if m else 0, codes[o:o + m].data_ptr() if m else 0, m) for o, m in zip(offs, sizes)]
+        d_items, count, tiles = h.hif8_multi_plan(items, src_is_bf16=bf16)
+        am = torch.full((count,), 3.0, dtype=torch.float32, device=dev())
+        sc = torch.zeros(count, 2, dtype=torch.float32, device=dev())
+        fn = h.hif8_multi_cast_bf16 if bf16 else h.hif8_multi_cast_f32
+        fn(d_items, count, tiles, am, sc, 32768.0, pow2, mode)
+        torch.cuda.synchronize()
+        xn = bf16_bits(x) if bf16 else x.cpu().numpy()
+        cg, amg, scg = codes.cpu().numpy(), am.cpu().numpy(), sc.cpu().numpy()
+        for i, (o, m) in enumerate(zip(offs, sizes)):
+            part = xn[o:o + m]
+            w_am = orc.amax_bf16(part) if bf16 else orc.amax_f32(part)
+            w_s = orc.scale_from_amax(w_am, 32768.0, bool(pow2))
+            assert amg[i] == w_am and scg[i, 0] == w_s and scg[i, 1] == np.float32(1.0) / w_s, (i, m)
+            want = orc.encode_bf16(part, w_s, mode) if bf16 else orc.encode_f32(part, w_s, mode)
+            assert_same_bytes(cg[o:o + m], want, "multi item %d (n=%d, bf16=%s)" % (i, m, bf16))
+        # bytes between the slices were not touched
+        for o, m in zip(offs, sizes):
+            pad = (m + 15) // 16 * 16
+            assert not cg[o + m:o + pad].any()
+
+
 # ------------------------------------------------------------------ amax semantics, tuning, graphs
 def test_amax_special_values(h):
     x = torch.randn(100003, device=dev())
