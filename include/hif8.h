@@ -144,26 +144,33 @@ hif8_status hif8_fake_quant_bf16(const uint16_t* src, uint16_t* dst, uint8_t* co
                                  hif8_stream_t stream);
 
 /*
- * Device-scale ("_ds") variants: identical to the calls above except that the
- * scale pair is read by the kernel from d_scale2 = {scale, fl32(1/scale)} in
- * device memory, as written by hif8_scale_from_amax on the same stream.  The
- * values are not validated (the host never sees them).
+ * Device-state ("_ds") variants: identical to the calls above except that
+ *   - the scale pair is read by the kernel from d_scale2 = {scale, fl32(1/scale)} in device
+ *     memory, as written by hif8_scale_from_amax on the same stream (not validated: the host
+ *     never sees the values);
+ *   - encode and fake_quant take d_amax_accum_or_null: if not NULL, the same pass also
+ *     accumulates max_i |src[i]| of the UNSCALED input into that device float with an atomic
+ *     max on its bit pattern (same ordering as hif8_amax_*).  This is the delayed scaling of
+ *     Sec. 5 (amax gathered every few iterations feeds the scale of later ones) at no extra
+ *     memory pass.  The call does not clear the accumulator: the caller starts a window by
+ *     writing 0 to it (hif8_amax_* with n = 0 does that on the stream).
  */
 hif8_status hif8_encode_f32_ds(const float* src, uint8_t* dst, size_t n, const float* d_scale2,
-                               uint32_t rounding_mode, hif8_stream_t stream);
+                               float* d_amax_accum_or_null, uint32_t rounding_mode,
+                               hif8_stream_t stream);
 hif8_status hif8_encode_bf16_ds(const uint16_t* src, uint8_t* dst, size_t n,
-                                const float* d_scale2, uint32_t rounding_mode,
-                                hif8_stream_t stream);
+                                const float* d_scale2, float* d_amax_accum_or_null,
+                                uint32_t rounding_mode, hif8_stream_t stream);
 hif8_status hif8_decode_f32_ds(const uint8_t* src, float* dst, size_t n, const float* d_scale2,
                                hif8_stream_t stream);
 hif8_status hif8_decode_bf16_ds(const uint8_t* src, uint16_t* dst, size_t n,
                                 const float* d_scale2, hif8_stream_t stream);
 hif8_status hif8_fake_quant_f32_ds(const float* src, float* dst, uint8_t* codes_or_null, size_t n,
-                                   const float* d_scale2, uint32_t rounding_mode,
-                                   hif8_stream_t stream);
+                                   const float* d_scale2, float* d_amax_accum_or_null,
+                                   uint32_t rounding_mode, hif8_stream_t stream);
 hif8_status hif8_fake_quant_bf16_ds(const uint16_t* src, uint16_t* dst, uint8_t* codes_or_null,
-                                    size_t n, const float* d_scale2, uint32_t rounding_mode,
-                                    hif8_stream_t stream);
+                                    size_t n, const float* d_scale2, float* d_amax_accum_or_null,
+                                    uint32_t rounding_mode, hif8_stream_t stream);
 
 /*
  * Multi-tensor cast: per-tensor amax, scale and encode for a whole list of tensors in four

@@ -131,6 +131,51 @@ __device__ __forceinline__ uint32_t descale2_bf16(uint32_t c0, uint32_t c1, cons
 // worth of codes).  A tile is blockDim.x * U vector units; blocks stride over tiles.
 // The ragged tail (n modulo the vector width) is done element-wise by block 0.
 // ------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+
+// Maximum over the 64 lanes of a wavefront with DPP row shifts and row broadcasts; the
+// result is valid in lane 63 and returned to every lane through a scalar read of that lane.
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+  v = umax(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x111, 0xF, 0xF, false));  // row_shr:1
+  v = umax(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x112, 0xF, 0xF, false));  // row_shr:2
+  v = umax(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x114, 0xF, 0xF, false));  // row_shr:4
+  v = umax(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x118, 0xF, 0xF, false));  // row_shr:8
+  v = umax(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x142, 0xF, 0xF, false));  // row_bcast:15
+  v = umax(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x143, 0xF, 0xF, false));  // row_bcast:31
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
+__device__ __forceinline__ void block_max_to_global(uint32_t m, uint32_t* out) {
+  __shared__ uint32_t wave_m[16];
+  m = wave_max_u32(m);
+  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  if (lane == 0) wave_m[wave] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const uint32_t nw = (blockDim.x + 63u) >> 6;
+    uint32_t r = wave_m[0];
+    for (uint32_t w = 1; w < nw; ++w) r = umax(r, wave_m[w]);
+    if (r) atomicMax(out, r);
+  }
+}
+
+// running magnitude maximum of one 16-byte vector: FP32 -> binary32 magnitude pattern;
+// BF16 -> two 15-bit magnitudes, one per 16-bit half (folded by fold_amax_bf16 at the end)
+typedef uint16_t u16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t vec_amax_f32(uint32_t m, const uint4& v) {
+  return umax(m, umax(umax(v.x & 0x7FFFFFFFu, v.y & 0x7FFFFFFFu),
+                      umax(v.z & 0x7FFFFFFFu, v.w & 0x7FFFFFFFu)));
+}
+__device__ __forceinline__ uint32_t vec_amax_bf16(uint32_t m, const uint4& v) {
+  u16x2_t mm = __builtin_bit_cast(u16x2_t, m);
+  mm = __builtin_elementwise_max(mm, __builtin_bit_cast(u16x2_t, v.x & 0x7FFF7FFFu));
+  mm = __builtin_elementwise_max(mm, __builtin_bit_cast(u16x2_t, v.y & 0x7FFF7FFFu));
+  mm = __builtin_elementwise_max(mm, __builtin_bit_cast(u16x2_t, v.z & 0x7FFF7FFFu));
+  mm = __builtin_elementwise_max(mm, __builtin_bit_cast(u16x2_t, v.w & 0x7FFF7FFFu));
+  return __builtin_bit_cast(uint32_t, mm);
+}
+__device__ __forceinline__ uint32_t fold_amax_bf16(uint32_t m) { return umax(m & 0xFFFFu, m >> 16) << 16; }
+
 // How a workgroup walks the tiles of a tensor (tile t = vector units [t*tile, (t+1)*tile)):
 // workgroup b visits tiles b*first_mul + i*stride for i in [0, count).
 //   persistent grid : first_mul = 1, stride = gridDim.x, count = ceil(tiles / gridDim.x)
@@ -211,16 +256,21 @@ __device__ __forceinline__ void tile_loop(size_t nvec, const Walk w, LoadF load,
 template <int U, int IMPL>
 __global__ void __launch_bounds__(1024)
 k_encode_f32(const float* __restrict__ src, uint8_t* __restrict__ dst, size_t n, float scale_arg,
-             const float* __restrict__ d_scale2, uint32_t mode, Walk walk) {
+             const float* __restrict__ d_scale2, uint32_t* __restrict__ amax_acc, uint32_t mode,
+             Walk walk) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[IMPL == IMPL_TA_ALU ? 16 : 8192];
   __shared__ __attribute__((aligned(8))) HrExp hrt[IMPL == IMPL_HR ? 256 : 1];
   const float scale = d_scale2 ? d_scale2[0] : scale_arg;
   const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(src);
   uint32_t* __restrict__ dst4 = reinterpret_cast<uint32_t*>(dst);
   const size_t nvec = n >> 2;
+  uint32_t m = 0;  // amax of the unscaled input, only tracked when amax_acc != nullptr
   tile_loop<U, uint4>(
       nvec, walk, [&](size_t idx) { return ld_stream(src4 + idx); },
-      [&](size_t idx, const uint4& v) { st_stream(dst4 + idx, encode4_f32<IMPL>(v, scale, lut, hrt, mode)); },
+      [&](size_t idx, const uint4& v) {
+        if (amax_acc) m = vec_amax_f32(m, v);
+        st_stream(dst4 + idx, encode4_f32<IMPL>(v, scale, lut, hrt, mode));
+      },
       [&]() {
         if (IMPL != IMPL_TA_ALU) {
           stage_enc_lut(lut, mode);
@@ -229,23 +279,32 @@ k_encode_f32(const float* __restrict__ src, uint8_t* __restrict__ dst, size_t n,
         }
       });
   const size_t t = (nvec << 2) + threadIdx.x;
-  if (blockIdx.x == 0 && t < n)
-    dst[t] = (uint8_t)encode_one<IMPL, false>(scaled_bits(__float_as_uint(src[t]), scale), lut, hrt, mode);
+  if (blockIdx.x == 0 && t < n) {
+    const uint32_t xb = __float_as_uint(src[t]);
+    m = umax(m, xb & 0x7FFFFFFFu);
+    dst[t] = (uint8_t)encode_one<IMPL, false>(scaled_bits(xb, scale), lut, hrt, mode);
+  }
+  if (amax_acc) block_max_to_global(m, amax_acc);
 }
 
 template <int U, int IMPL>
 __global__ void __launch_bounds__(1024)
 k_encode_bf16(const uint16_t* __restrict__ src, uint8_t* __restrict__ dst, size_t n,
-              float scale_arg, const float* __restrict__ d_scale2, uint32_t mode, Walk walk) {
+              float scale_arg, const float* __restrict__ d_scale2,
+              uint32_t* __restrict__ amax_acc, uint32_t mode, Walk walk) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[IMPL == IMPL_TA_ALU ? 16 : 8192];
   __shared__ __attribute__((aligned(8))) HrExp hrt[IMPL == IMPL_HR ? 256 : 1];
   const float scale = d_scale2 ? d_scale2[0] : scale_arg;
   const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(src);
   uint2* __restrict__ dst8 = reinterpret_cast<uint2*>(dst);
   const size_t nvec = n >> 3;
+  uint32_t m = 0;
   tile_loop<U, uint4>(
       nvec, walk, [&](size_t idx) { return ld_stream(src4 + idx); },
-      [&](size_t idx, const uint4& v) { st_stream(dst8 + idx, encode8_bf16<IMPL>(v, scale, lut, hrt, mode)); },
+      [&](size_t idx, const uint4& v) {
+        if (amax_acc) m = vec_amax_bf16(m, v);
+        st_stream(dst8 + idx, encode8_bf16<IMPL>(v, scale, lut, hrt, mode));
+      },
       [&]() {
         if (IMPL != IMPL_TA_ALU) {
           stage_enc_lut(lut, mode);
@@ -254,8 +313,13 @@ k_encode_bf16(const uint16_t* __restrict__ src, uint8_t* __restrict__ dst, size_
         }
       });
   const size_t t = (nvec << 3) + threadIdx.x;
-  if (blockIdx.x == 0 && t < n)
-    dst[t] = (uint8_t)encode_one<IMPL, true>(scaled_bits((uint32_t)src[t] << 16, scale), lut, hrt, mode);
+  m = fold_amax_bf16(m);
+  if (blockIdx.x == 0 && t < n) {
+    const uint32_t xb = (uint32_t)src[t] << 16;
+    m = umax(m, xb & 0x7FFFFFFFu);
+    dst[t] = (uint8_t)encode_one<IMPL, true>(scaled_bits(xb, scale), lut, hrt, mode);
+  }
+  if (amax_acc) block_max_to_global(m, amax_acc);
 }
 
 template <int U>
@@ -316,7 +380,8 @@ k_decode_bf16(const uint8_t* __restrict__ src, uint16_t* __restrict__ dst, size_
 template <int U, int IMPL, bool CODES>
 __global__ void __launch_bounds__(1024)
 k_fake_quant_f32(const float* src, float* dst, uint8_t* codes, size_t n, float scale_arg,
-                 float inv_arg, const float* __restrict__ d_scale2, uint32_t mode, Walk walk) {
+                 float inv_arg, const float* __restrict__ d_scale2, uint32_t* amax_acc,
+                  uint32_t mode, Walk walk) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[IMPL == IMPL_TA_ALU ? 16 : 8192];
   __shared__ __attribute__((aligned(8))) HrExp hrt[IMPL == IMPL_HR ? 256 : 1];
   __shared__ uint32_t dec[256];
@@ -332,9 +397,11 @@ k_fake_quant_f32(const float* src, float* dst, uint8_t* codes, size_t n, float s
   uint4* dst4 = reinterpret_cast<uint4*>(dst);
   uint32_t* codes4 = reinterpret_cast<uint32_t*>(codes);
   const size_t nvec = n >> 2;
+  uint32_t m = 0;
   tile_loop<U, uint4>(
       nvec, walk, [&](size_t idx) { return ld_stream(src4 + idx); },
       [&](size_t idx, const uint4& v) {
+        if (amax_acc) m = vec_amax_f32(m, v);
         const uint32_t w = encode4_f32<IMPL>(v, scale, lut, hrt, mode);
         uint4 o;
         o.x = descale_bits(w, dec, inv);
@@ -347,16 +414,20 @@ k_fake_quant_f32(const float* src, float* dst, uint8_t* codes, size_t n, float s
       prologue);
   const size_t t = (nvec << 2) + threadIdx.x;
   if (blockIdx.x == 0 && t < n) {
-    const uint32_t c = encode_one<IMPL, false>(scaled_bits(__float_as_uint(src[t]), scale), lut, hrt, mode);
+    const uint32_t xb = __float_as_uint(src[t]);
+    m = umax(m, xb & 0x7FFFFFFFu);
+    const uint32_t c = encode_one<IMPL, false>(scaled_bits(xb, scale), lut, hrt, mode);
     dst[t] = __uint_as_float(descale_bits(c, dec, inv));
     if (CODES) codes[t] = (uint8_t)c;
   }
+  if (amax_acc) block_max_to_global(m, amax_acc);
 }
 
 template <int U, int IMPL, bool CODES>
 __global__ void __launch_bounds__(1024)
 k_fake_quant_bf16(const uint16_t* src, uint16_t* dst, uint8_t* codes, size_t n, float scale_arg,
-                  float inv_arg, const float* __restrict__ d_scale2, uint32_t mode, Walk walk) {
+                  float inv_arg, const float* __restrict__ d_scale2, uint32_t* amax_acc,
+                  uint32_t mode, Walk walk) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[IMPL == IMPL_TA_ALU ? 16 : 8192];
   __shared__ __attribute__((aligned(8))) HrExp hrt[IMPL == IMPL_HR ? 256 : 1];
   __shared__ uint32_t dec[256];
@@ -372,9 +443,11 @@ k_fake_quant_bf16(const uint16_t* src, uint16_t* dst, uint8_t* codes, size_t n, 
   uint4* dst4 = reinterpret_cast<uint4*>(dst);
   uint2* codes8 = reinterpret_cast<uint2*>(codes);
   const size_t nvec = n >> 3;
+  uint32_t m = 0;
   tile_loop<U, uint4>(
       nvec, walk, [&](size_t idx) { return ld_stream(src4 + idx); },
       [&](size_t idx, const uint4& v) {
+        if (amax_acc) m = vec_amax_bf16(m, v);
         const uint2 w = encode8_bf16<IMPL>(v, scale, lut, hrt, mode);
         uint4 o;
         o.x = descale2_bf16(w.x, w.x >> 8, dec, inv);
@@ -386,21 +459,24 @@ k_fake_quant_bf16(const uint16_t* src, uint16_t* dst, uint8_t* codes, size_t n, 
       },
       prologue);
   const size_t t = (nvec << 3) + threadIdx.x;
+  m = fold_amax_bf16(m);
   if (blockIdx.x == 0 && t < n) {
-    const uint32_t c = encode_one<IMPL, true>(scaled_bits((uint32_t)src[t] << 16, scale), lut, hrt, mode);
+    const uint32_t xb = (uint32_t)src[t] << 16;
+    m = umax(m, xb & 0x7FFFFFFFu);
+    const uint32_t c = encode_one<IMPL, true>(scaled_bits(xb, scale), lut, hrt, mode);
     dst[t] = (uint16_t)narrow_bf16(descale_bits(c, dec, inv));
     if (CODES) codes[t] = (uint8_t)c;
   }
+  if (amax_acc) block_max_to_global(m, amax_acc);
 }
 
 // ------------------------------------------------------------------------------------
 // element-per-lane kernels for pointers that do not meet the fast path's alignment
 // ------------------------------------------------------------------------------------
 template <bool SRC16>
-__device__ __forceinline__ uint32_t load_scaled(const void* src, size_t i, float scale) {
-  const uint32_t xb = SRC16 ? ((uint32_t) reinterpret_cast<const uint16_t*>(src)[i] << 16)
-                            : __float_as_uint(reinterpret_cast<const float*>(src)[i]);
-  return scaled_bits(xb, scale);
+__device__ __forceinline__ uint32_t load_bits(const void* src, size_t i) {
+  return SRC16 ? ((uint32_t) reinterpret_cast<const uint16_t*>(src)[i] << 16)
+               : __float_as_uint(reinterpret_cast<const float*>(src)[i]);
 }
 template <bool SRC16>
 __device__ __forceinline__ uint32_t encode_any(uint32_t yb, uint32_t mode) {
@@ -411,11 +487,16 @@ __device__ __forceinline__ uint32_t encode_any(uint32_t yb, uint32_t mode) {
 template <bool SRC16>
 __global__ void __launch_bounds__(256)
 k_encode_elem(const void* src, uint8_t* dst, size_t n, float scale_arg, const float* d_scale2,
-              uint32_t mode) {
+              uint32_t* amax_acc, uint32_t mode) {
   const float scale = d_scale2 ? d_scale2[0] : scale_arg;
+  uint32_t m = 0;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
-       i += (size_t)gridDim.x * blockDim.x)
-    dst[i] = (uint8_t)encode_any<SRC16>(load_scaled<SRC16>(src, i, scale), mode);
+       i += (size_t)gridDim.x * blockDim.x) {
+    const uint32_t xb = load_bits<SRC16>(src, i);
+    m = umax(m, xb & 0x7FFFFFFFu);
+    dst[i] = (uint8_t)encode_any<SRC16>(scaled_bits(xb, scale), mode);
+  }
+  if (amax_acc) block_max_to_global(m, amax_acc);
 }
 
 template <bool DST16>
@@ -433,50 +514,26 @@ k_decode_elem(const uint8_t* src, void* dst, size_t n, float inv_arg, const floa
 template <bool T16>
 __global__ void __launch_bounds__(256)
 k_fake_quant_elem(const void* src, void* dst, uint8_t* codes, size_t n, float scale_arg,
-                  float inv_arg, const float* d_scale2, uint32_t mode) {
+                  float inv_arg, const float* d_scale2, uint32_t* amax_acc, uint32_t mode) {
   const float scale = d_scale2 ? d_scale2[0] : scale_arg;
   const float inv = d_scale2 ? d_scale2[1] : inv_arg;
+  uint32_t m = 0;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
        i += (size_t)gridDim.x * blockDim.x) {
-    const uint32_t c = encode_any<T16>(load_scaled<T16>(src, i, scale), mode);
+    const uint32_t xb = load_bits<T16>(src, i);
+    m = umax(m, xb & 0x7FFFFFFFu);
+    const uint32_t c = encode_any<T16>(scaled_bits(xb, scale), mode);
     const uint32_t b = __float_as_uint(__fmul_rn(__uint_as_float(decode_bits(c)), inv));
     if (T16) reinterpret_cast<uint16_t*>(dst)[i] = (uint16_t)narrow_bf16(b);
     else reinterpret_cast<uint32_t*>(dst)[i] = b;
     if (codes) codes[i] = (uint8_t)c;
   }
+  if (amax_acc) block_max_to_global(m, amax_acc);
 }
 
 // ------------------------------------------------------------------------------------
 // amax
 // ------------------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
-
-// Maximum over the 64 lanes of a wavefront with DPP row shifts and row broadcasts; the
-// result is valid in lane 63 and returned to every lane through a scalar read of that lane.
-__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
-  v = umax(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x111, 0xF, 0xF, false));  // row_shr:1
-  v = umax(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x112, 0xF, 0xF, false));  // row_shr:2
-  v = umax(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x114, 0xF, 0xF, false));  // row_shr:4
-  v = umax(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x118, 0xF, 0xF, false));  // row_shr:8
-  v = umax(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x142, 0xF, 0xF, false));  // row_bcast:15
-  v = umax(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x143, 0xF, 0xF, false));  // row_bcast:31
-  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
-}
-
-__device__ __forceinline__ void block_max_to_global(uint32_t m, uint32_t* out) {
-  __shared__ uint32_t wave_m[16];
-  m = wave_max_u32(m);
-  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-  if (lane == 0) wave_m[wave] = m;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    const uint32_t nw = (blockDim.x + 63u) >> 6;
-    uint32_t r = wave_m[0];
-    for (uint32_t w = 1; w < nw; ++w) r = umax(r, wave_m[w]);
-    if (r) atomicMax(out, r);
-  }
-}
-
 __global__ void k_fill_u32(uint32_t* p, uint32_t v, uint32_t count) {
   const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < count) p[i] = v;
@@ -491,22 +548,9 @@ k_amax(const void* __restrict__ src, size_t n, uint32_t* __restrict__ out, Walk 
   uint32_t m = 0;  // FP32: magnitude pattern; BF16: two 15-bit magnitudes, one per half
   tile_loop<U, uint4>(
       nvec, walk, [&](size_t idx) { return NT ? ld_stream(src4 + idx) : src4[idx]; },
-      [&](size_t, const uint4& v) {
-        if (SRC16) {
-          typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
-          u16x2 mm = __builtin_bit_cast(u16x2, m);
-          mm = __builtin_elementwise_max(mm, __builtin_bit_cast(u16x2, v.x & 0x7FFF7FFFu));
-          mm = __builtin_elementwise_max(mm, __builtin_bit_cast(u16x2, v.y & 0x7FFF7FFFu));
-          mm = __builtin_elementwise_max(mm, __builtin_bit_cast(u16x2, v.z & 0x7FFF7FFFu));
-          mm = __builtin_elementwise_max(mm, __builtin_bit_cast(u16x2, v.w & 0x7FFF7FFFu));
-          m = __builtin_bit_cast(uint32_t, mm);
-        } else {
-          m = umax(m, umax(umax(v.x & 0x7FFFFFFFu, v.y & 0x7FFFFFFFu),
-                           umax(v.z & 0x7FFFFFFFu, v.w & 0x7FFFFFFFu)));
-        }
-      },
+      [&](size_t, const uint4& v) { m = SRC16 ? vec_amax_bf16(m, v) : vec_amax_f32(m, v); },
       []() {});
-  if (SRC16) m = umax(m & 0xFFFFu, m >> 16) << 16;
+  if (SRC16) m = fold_amax_bf16(m);
   const size_t t = (SRC16 ? (nvec << 3) : (nvec << 2)) + threadIdx.x;
   if (blockIdx.x == 0 && t < n) {
     const uint32_t a = SRC16 ? (((uint32_t) reinterpret_cast<const uint16_t*>(src)[t] & 0x7FFFu) << 16)
@@ -848,7 +892,8 @@ hif8_status finish_launch() { return hip_ok(hipGetLastError()) ? HIF8_OK : HIF8_
 // ---- common implementations (scale either by value or from device memory) ----
 template <bool SRC16>
 hif8_status do_encode(const void* src, uint8_t* dst, size_t n, float scale, const float* d_scale2,
-                      uint32_t mode, hipStream_t st) {
+                      float* d_amax_acc, uint32_t mode, hipStream_t st) {
+  uint32_t* amax_acc = reinterpret_cast<uint32_t*>(d_amax_acc);
   if (!valid_mode(mode)) return HIF8_ERR_MODE;
   float inv = 1.0f;
   if (!d_scale2 && !valid_scale(scale, &inv)) return HIF8_ERR_SCALE;
@@ -860,7 +905,7 @@ hif8_status do_encode(const void* src, uint8_t* dst, size_t n, float scale, cons
   const bool fast = aligned_to(src, 16) && aligned_to(dst, SRC16 ? 8 : 4);
   if (!fast) {
     hipLaunchKernelGGL(k_encode_elem<SRC16>, dim3(grid_elem(n, cus)), dim3(256), 0, st, src, dst, n,
-                       scale, d_scale2, mode);
+                       scale, d_scale2, amax_acc, mode);
     return finish_launch();
   }
   const size_t nvec = SRC16 ? (n >> 3) : (n >> 2);
@@ -870,10 +915,10 @@ hif8_status do_encode(const void* src, uint8_t* dst, size_t n, float scale, cons
   const dim3 grid(grid_for(nvec, cus, shape, &walk)), block(shape.block);
   if (SRC16) {
     HIF8_DISPATCH_U(HIF8_DISPATCH_IMPL(impl, hipLaunchKernelGGL((k_encode_bf16<U, IMPL>), grid, block, 0, st,
-        reinterpret_cast<const uint16_t*>(src), dst, n, scale, d_scale2, mode, walk)))
+        reinterpret_cast<const uint16_t*>(src), dst, n, scale, d_scale2, amax_acc, mode, walk)))
   } else {
     HIF8_DISPATCH_U(HIF8_DISPATCH_IMPL(impl, hipLaunchKernelGGL((k_encode_f32<U, IMPL>), grid, block, 0, st,
-        reinterpret_cast<const float*>(src), dst, n, scale, d_scale2, mode, walk)))
+        reinterpret_cast<const float*>(src), dst, n, scale, d_scale2, amax_acc, mode, walk)))
   }
   return finish_launch();
 }
@@ -910,7 +955,8 @@ hif8_status do_decode(const uint8_t* src, void* dst, size_t n, float scale, cons
 
 template <bool T16>
 hif8_status do_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, float scale,
-                          const float* d_scale2, uint32_t mode, hipStream_t st) {
+                          const float* d_scale2, float* d_amax_acc, uint32_t mode, hipStream_t st) {
+  uint32_t* amax_acc = reinterpret_cast<uint32_t*>(d_amax_acc);
   if (!valid_mode(mode)) return HIF8_ERR_MODE;
   float inv = 1.0f;
   if (!d_scale2 && !valid_scale(scale, &inv)) return HIF8_ERR_SCALE;
@@ -922,7 +968,7 @@ hif8_status do_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, 
   const bool fast = aligned_to(src, 16) && aligned_to(dst, 16) && (!codes || aligned_to(codes, T16 ? 8 : 4));
   if (!fast) {
     hipLaunchKernelGGL(k_fake_quant_elem<T16>, dim3(grid_elem(n, cus)), dim3(256), 0, st, src, dst,
-                       codes, n, scale, inv, d_scale2, mode);
+                       codes, n, scale, inv, d_scale2, amax_acc, mode);
     return finish_launch();
   }
   const size_t nvec = T16 ? (n >> 3) : (n >> 2);
@@ -932,7 +978,7 @@ hif8_status do_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, 
   const int impl = impl_for(mode);
 #define HIF8_FQ_LAUNCH(KERNEL, TS, TD, CODESV)                                                        \
   HIF8_DISPATCH_U(HIF8_DISPATCH_IMPL(impl, hipLaunchKernelGGL((KERNEL<U, IMPL, CODESV>), grid, block, \
-      0, st, reinterpret_cast<TS>(src), reinterpret_cast<TD>(dst), codes, n, scale, inv, d_scale2, mode, walk)))
+      0, st, reinterpret_cast<TS>(src), reinterpret_cast<TD>(dst), codes, n, scale, inv, d_scale2, amax_acc, mode, walk)))
   if (T16) {
     if (codes) { HIF8_FQ_LAUNCH(k_fake_quant_bf16, const uint16_t*, uint16_t*, true) }
     else { HIF8_FQ_LAUNCH(k_fake_quant_bf16, const uint16_t*, uint16_t*, false) }
@@ -1036,11 +1082,11 @@ hif8_status hif8_scale_from_amax(const float* d_amax, float* d_scale2, float tar
 
 hif8_status hif8_encode_f32(const float* src, uint8_t* dst, size_t n, float scale, uint32_t mode,
                             hif8_stream_t stream) {
-  return do_encode<false>(src, dst, n, scale, nullptr, mode, (hipStream_t)stream);
+  return do_encode<false>(src, dst, n, scale, nullptr, nullptr, mode, (hipStream_t)stream);
 }
 hif8_status hif8_encode_bf16(const uint16_t* src, uint8_t* dst, size_t n, float scale,
                              uint32_t mode, hif8_stream_t stream) {
-  return do_encode<true>(src, dst, n, scale, nullptr, mode, (hipStream_t)stream);
+  return do_encode<true>(src, dst, n, scale, nullptr, nullptr, mode, (hipStream_t)stream);
 }
 hif8_status hif8_decode_f32(const uint8_t* src, float* dst, size_t n, float scale,
                             hif8_stream_t stream) {
@@ -1052,22 +1098,22 @@ hif8_status hif8_decode_bf16(const uint8_t* src, uint16_t* dst, size_t n, float 
 }
 hif8_status hif8_fake_quant_f32(const float* src, float* dst, uint8_t* codes, size_t n, float scale,
                                 uint32_t mode, hif8_stream_t stream) {
-  return do_fake_quant<false>(src, dst, codes, n, scale, nullptr, mode, (hipStream_t)stream);
+  return do_fake_quant<false>(src, dst, codes, n, scale, nullptr, nullptr, mode, (hipStream_t)stream);
 }
 hif8_status hif8_fake_quant_bf16(const uint16_t* src, uint16_t* dst, uint8_t* codes, size_t n,
                                  float scale, uint32_t mode, hif8_stream_t stream) {
-  return do_fake_quant<true>(src, dst, codes, n, scale, nullptr, mode, (hipStream_t)stream);
+  return do_fake_quant<true>(src, dst, codes, n, scale, nullptr, nullptr, mode, (hipStream_t)stream);
 }
 
 hif8_status hif8_encode_f32_ds(const float* src, uint8_t* dst, size_t n, const float* d_scale2,
-                               uint32_t mode, hif8_stream_t stream) {
+                               float* d_amax_acc, uint32_t mode, hif8_stream_t stream) {
   if (!d_scale2) return HIF8_ERR_NULL;
-  return do_encode<false>(src, dst, n, 1.0f, d_scale2, mode, (hipStream_t)stream);
+  return do_encode<false>(src, dst, n, 1.0f, d_scale2, d_amax_acc, mode, (hipStream_t)stream);
 }
 hif8_status hif8_encode_bf16_ds(const uint16_t* src, uint8_t* dst, size_t n, const float* d_scale2,
-                                uint32_t mode, hif8_stream_t stream) {
+                                float* d_amax_acc, uint32_t mode, hif8_stream_t stream) {
   if (!d_scale2) return HIF8_ERR_NULL;
-  return do_encode<true>(src, dst, n, 1.0f, d_scale2, mode, (hipStream_t)stream);
+  return do_encode<true>(src, dst, n, 1.0f, d_scale2, d_amax_acc, mode, (hipStream_t)stream);
 }
 hif8_status hif8_decode_f32_ds(const uint8_t* src, float* dst, size_t n, const float* d_scale2,
                                hif8_stream_t stream) {
@@ -1080,14 +1126,16 @@ hif8_status hif8_decode_bf16_ds(const uint8_t* src, uint16_t* dst, size_t n, con
   return do_decode<true>(src, dst, n, 1.0f, d_scale2, (hipStream_t)stream);
 }
 hif8_status hif8_fake_quant_f32_ds(const float* src, float* dst, uint8_t* codes, size_t n,
-                                   const float* d_scale2, uint32_t mode, hif8_stream_t stream) {
+                                   const float* d_scale2, float* d_amax_acc, uint32_t mode,
+                                   hif8_stream_t stream) {
   if (!d_scale2) return HIF8_ERR_NULL;
-  return do_fake_quant<false>(src, dst, codes, n, 1.0f, d_scale2, mode, (hipStream_t)stream);
+  return do_fake_quant<false>(src, dst, codes, n, 1.0f, d_scale2, d_amax_acc, mode, (hipStream_t)stream);
 }
 hif8_status hif8_fake_quant_bf16_ds(const uint16_t* src, uint16_t* dst, uint8_t* codes, size_t n,
-                                    const float* d_scale2, uint32_t mode, hif8_stream_t stream) {
+                                    const float* d_scale2, float* d_amax_acc, uint32_t mode,
+                                    hif8_stream_t stream) {
   if (!d_scale2) return HIF8_ERR_NULL;
-  return do_fake_quant<true>(src, dst, codes, n, 1.0f, d_scale2, mode, (hipStream_t)stream);
+  return do_fake_quant<true>(src, dst, codes, n, 1.0f, d_scale2, d_amax_acc, mode, (hipStream_t)stream);
 }
 
 hif8_status hif8_multi_plan(hif8_cast_item* host_items, size_t count, int src_is_bf16,

@@ -58,12 +58,12 @@ _SIGS = {
     "hif8_decode_bf16": ([_vp, _vp, _sz, _f, _vp], _i),
     "hif8_fake_quant_f32": ([_vp, _vp, _vp, _sz, _f, _u32, _vp], _i),
     "hif8_fake_quant_bf16": ([_vp, _vp, _vp, _sz, _f, _u32, _vp], _i),
-    "hif8_encode_f32_ds": ([_vp, _vp, _sz, _vp, _u32, _vp], _i),
-    "hif8_encode_bf16_ds": ([_vp, _vp, _sz, _vp, _u32, _vp], _i),
+    "hif8_encode_f32_ds": ([_vp, _vp, _sz, _vp, _vp, _u32, _vp], _i),
+    "hif8_encode_bf16_ds": ([_vp, _vp, _sz, _vp, _vp, _u32, _vp], _i),
     "hif8_decode_f32_ds": ([_vp, _vp, _sz, _vp, _vp], _i),
     "hif8_decode_bf16_ds": ([_vp, _vp, _sz, _vp, _vp], _i),
-    "hif8_fake_quant_f32_ds": ([_vp, _vp, _vp, _sz, _vp, _u32, _vp], _i),
-    "hif8_fake_quant_bf16_ds": ([_vp, _vp, _vp, _sz, _vp, _u32, _vp], _i),
+    "hif8_fake_quant_f32_ds": ([_vp, _vp, _vp, _sz, _vp, _vp, _u32, _vp], _i),
+    "hif8_fake_quant_bf16_ds": ([_vp, _vp, _vp, _sz, _vp, _vp, _u32, _vp], _i),
     "hif8_multi_plan": ([_vp, _sz, _i, _vp], _i),
     "hif8_multi_cast_bf16": ([_vp, _sz, ctypes.c_uint64, _vp, _vp, _f, _i, _u32, _vp], _i),
     "hif8_multi_cast_f32": ([_vp, _sz, ctypes.c_uint64, _vp, _vp, _f, _i, _u32, _vp], _i),
@@ -155,12 +155,14 @@ def hif8_fake_quant_bf16(src, dst, codes_or_none, n, scale=1.0, rounding_mode=RM
                                     _stream(stream)))
 
 
-def hif8_encode_f32_ds(src, dst, n, d_scale2, rounding_mode=RM_TA, stream=None):
-    _check(lib.hif8_encode_f32_ds(_ptr(src), _ptr(dst), n, _ptr(d_scale2), rounding_mode, _stream(stream)))
+def hif8_encode_f32_ds(src, dst, n, d_scale2, rounding_mode=RM_TA, stream=None, d_amax_accum=None):
+    _check(lib.hif8_encode_f32_ds(_ptr(src), _ptr(dst), n, _ptr(d_scale2), _ptr(d_amax_accum), rounding_mode,
+                                  _stream(stream)))
 
 
-def hif8_encode_bf16_ds(src, dst, n, d_scale2, rounding_mode=RM_TA, stream=None):
-    _check(lib.hif8_encode_bf16_ds(_ptr(src), _ptr(dst), n, _ptr(d_scale2), rounding_mode, _stream(stream)))
+def hif8_encode_bf16_ds(src, dst, n, d_scale2, rounding_mode=RM_TA, stream=None, d_amax_accum=None):
+    _check(lib.hif8_encode_bf16_ds(_ptr(src), _ptr(dst), n, _ptr(d_scale2), _ptr(d_amax_accum), rounding_mode,
+                                   _stream(stream)))
 
 
 def hif8_decode_f32_ds(src, dst, n, d_scale2, stream=None):
@@ -171,14 +173,16 @@ def hif8_decode_bf16_ds(src, dst, n, d_scale2, stream=None):
     _check(lib.hif8_decode_bf16_ds(_ptr(src), _ptr(dst), n, _ptr(d_scale2), _stream(stream)))
 
 
-def hif8_fake_quant_f32_ds(src, dst, codes_or_none, n, d_scale2, rounding_mode=RM_TA, stream=None):
+def hif8_fake_quant_f32_ds(src, dst, codes_or_none, n, d_scale2, rounding_mode=RM_TA, stream=None,
+                           d_amax_accum=None):
     _check(lib.hif8_fake_quant_f32_ds(_ptr(src), _ptr(dst), _ptr(codes_or_none), n, _ptr(d_scale2),
-                                      rounding_mode, _stream(stream)))
+                                      _ptr(d_amax_accum), rounding_mode, _stream(stream)))
 
 
-def hif8_fake_quant_bf16_ds(src, dst, codes_or_none, n, d_scale2, rounding_mode=RM_TA, stream=None):
+def hif8_fake_quant_bf16_ds(src, dst, codes_or_none, n, d_scale2, rounding_mode=RM_TA, stream=None,
+                            d_amax_accum=None):
     _check(lib.hif8_fake_quant_bf16_ds(_ptr(src), _ptr(dst), _ptr(codes_or_none), n, _ptr(d_scale2),
-                                       rounding_mode, _stream(stream)))
+                                       _ptr(d_amax_accum), rounding_mode, _stream(stream)))
 
 
 class CastItem(ctypes.Structure):

@@ -40,7 +40,8 @@ def test_argument_validation_happens_on_the_host():
     assert L.hif8_decode_bf16(p, p, 0, 2.0, None) == OK
     assert L.hif8_fake_quant_f32(p, p, None, 0, 2.0, 1, None) == OK
     assert L.hif8_fake_quant_f32(None, p, None, 4, 2.0, 1, None) == NULL
-    assert L.hif8_encode_f32_ds(p, p, 16, None, 0, None) == NULL
+    assert L.hif8_encode_f32_ds(p, p, 16, None, None, 0, None) == NULL
+    assert L.hif8_fake_quant_bf16_ds(p, p, None, 16, None, p, 0, None) == NULL
     assert L.hif8_amax_f32(p, 16, None, None) == NULL
     assert L.hif8_scale_from_amax(None, p, 1.0, 0, None) == NULL
     assert L.hif8_scale_from_amax(p, p, -1.0, 0, None) == ARG

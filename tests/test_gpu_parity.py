@@ -420,6 +420,98 @@ def test_launch_shapes_and_alu_variant(h, block, wg, unroll, impl, tpw, amax_nt)
             h.hif8_set_tuning(k, v)
 
 
+@pytest.mark.parametrize("n,off", [(1 << 20, 0), ((1 << 18) + 5, 0), (10007, 1), (3, 0)])
+def test_delayed_scaling_amax_accumulates_in_the_cast_pass(h, n, off):
+    """_ds encode / fake-quant with an amax accumulator: codes as usual, plus the amax of the
+    unscaled input; the accumulator keeps the maximum over consecutive calls."""
+    from paper_2409_16626_amd import workloads
+    big = workloads.dynamic_range_sweep((1 << 20) + 64, dev())
+    x = big[off:off + n]
+    y = (big[off + 8:off + 8 + n] * 0.01)
+    xb_all = big.to(torch.bfloat16)
+    xb = xb_all[off:off + n]
+    sc = torch.tensor([0.75, 1.0 / 0.75], dtype=torch.float32, device=dev())
+    acc = torch.zeros(1, dtype=torch.float32, device=dev())
+    codes = torch.empty(n + 8, dtype=torch.uint8, device=dev())[off:off + n]
+    xn, yn, xbn = x.cpu().numpy(), y.contiguous().cpu().numpy(), bf16_bits(xb.contiguous())
+    s = np.float32(0.75)
+    for mode in (TA, HR):
+        h.hif8_amax_f32(0, 0, acc)                      # start a window: writes 0
+        h.hif8_encode_f32_ds(x.data_ptr(), codes.data_ptr(), n, sc, mode, d_amax_accum=acc)
+        torch.cuda.synchronize()
+        assert_same_bytes(codes.cpu().numpy(), orc.encode_f32(xn, s, mode), "ds enc f32")
+        assert f32_bits(acc)[0] == np.float32(orc.amax_f32(xn)).view(np.uint32)
+        yc = y.contiguous()
+        h.hif8_encode_f32_ds(yc, codes.data_ptr(), n, sc, mode, d_amax_accum=acc)   # smaller values: max stays
+        torch.cuda.synchronize()
+        assert f32_bits(acc)[0] == np.float32(max(orc.amax_f32(xn), orc.amax_f32(yn))).view(np.uint32)
+        h.hif8_amax_f32(0, 0, acc)
+        h.hif8_encode_bf16_ds(xb.data_ptr(), codes.data_ptr(), n, sc, mode, d_amax_accum=acc)
+        torch.cuda.synchronize()
+        assert_same_bytes(codes.cpu().numpy(), orc.encode_bf16(xbn, s, mode), "ds enc bf16")
+        assert f32_bits(acc)[0] == np.float32(orc.amax_bf16(xbn)).view(np.uint32)
+        o = torch.empty(n + 8, dtype=torch.float32, device=dev())[off:off + n]
+        h.hif8_amax_f32(0, 0, acc)
+        h.hif8_fake_quant_f32_ds(x.data_ptr(), o.data_ptr(), codes.data_ptr(), n, sc, mode, d_amax_accum=acc)
+        torch.cuda.synchronize()
+        wo, wc = orc.fake_quant_f32(xn, s, mode)
+        assert_same_bytes(f32_bits(o.contiguous()), wo.view(np.uint32), "ds fq f32")
+        assert f32_bits(acc)[0] == np.float32(orc.amax_f32(xn)).view(np.uint32)
+        ob = torch.empty(n + 8, dtype=torch.bfloat16, device=dev())[off:off + n]
+        h.hif8_amax_f32(0, 0, acc)
+        h.hif8_fake_quant_bf16_ds(xb.data_ptr(), ob.data_ptr(), None, n, sc, mode, d_amax_accum=acc)
+        torch.cuda.synchronize()
+        wob, _ = orc.fake_quant_bf16(xbn, s, mode)
+        assert_same_bytes(bf16_bits(ob.contiguous()), wob, "ds fq bf16")
+        assert f32_bits(acc)[0] == np.float32(orc.amax_bf16(xbn)).view(np.uint32)
+
+
+def test_hip_graph_replays_match_eager(h):
+    """amax -> scale -> fused fake-quant captured in a HIP graph; every replay is checked against
+    the eager result, with other eager work and synchronisations between replays."""
+    from paper_2409_16626_amd import workloads
+    x = workloads.activation_bf16(1024, 1024 + 8, dev()).view(-1)
+    n = x.numel()
+    am = torch.zeros(1, dtype=torch.float32, device=dev())
+    sc = torch.zeros(2, dtype=torch.float32, device=dev())
+    out = torch.empty_like(x)
+    codes = torch.empty(n, dtype=torch.uint8, device=dev())
+
+    def run():
+        h.hif8_amax_bf16(x, n, am)
+        h.hif8_scale_from_amax(am, sc, 32768.0, 0)
+        h.hif8_fake_quant_bf16_ds(x, out, codes, n, sc, TA)
+
+    run()
+    torch.cuda.synchronize()
+    ref_codes, ref_out, ref_sc = codes.clone(), out.clone(), sc.clone()
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g, stream=s):
+            run()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        codes.zero_()
+        out.zero_()
+        sc.zero_()
+        am.fill_(123.0)
+        if rep == 2:                                   # new input between replays
+            x.mul_(0.5)
+            run()
+            torch.cuda.synchronize()
+            ref_codes, ref_out, ref_sc = codes.clone(), out.clone(), sc.clone()
+            codes.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(codes, ref_codes) and torch.equal(out.view(torch.int16), ref_out.view(torch.int16))
+        assert torch.equal(sc, ref_sc)
+    wo, wc = orc.fake_quant_bf16(bf16_bits(x), np.float32(sc[0].item()), TA)
+    assert_same_bytes(codes.cpu().numpy(), wc, "graph codes vs oracle")
+
+
 def test_non_default_stream(h):
     from paper_2409_16626_amd import workloads
     x = workloads.normal_f32(1 << 18, dev())
