@@ -58,8 +58,9 @@ def rate(bytes_per_step, ms):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=300,
+                    help="untimed launches first; the launch duration settles only after ~150 back-to-back launches")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--buffers", type=int, default=6, help="distinct resident input tensors to rotate over")
@@ -167,7 +168,7 @@ def main():
     # ---------------- the other rows of the hot path ----------------
     if not args.no_extra:
         extra = {}
-        K, W = max(20, args.steps // 4), 5
+        K, W = max(20, args.steps // 3), max(5, args.warmup // 3)
 
         # same-mix stream ceiling (read 16 B, write 4 B per lane)
         w_ms, e_ms = timed(lambda i: hif8.hif8_diag_stream(xs[i % R], outs[i % R], n // 4, 4), K, W)

@@ -759,17 +759,18 @@ struct Shape {
   int wg_per_cu;
 };
 enum Family { FAM_ENC32_TA, FAM_ENC32_HR, FAM_ENC16, FAM_FQ, FAM_DEC, FAM_AMAX, FAM_DIAG, FAM_COUNT };
-// Defaults from a sweep on MI355X (block x unroll x tiles-per-workgroup / persistent) with
-// 64 Mi-element tensors: one-shot grids of small chunks win for the read+write kernels,
-// a persistent grid of one large workgroup per CU wins for the read-only reduction.
+// Defaults from a sweep on MI355X under sustained load (hundreds of back-to-back launches on
+// 64 Mi-element tensors; short bursts rank the shapes differently): one-shot grids of
+// 512-lane workgroups with 16-32 KiB of source per staged table win for the read+write
+// kernels, a persistent grid of one 1024-lane workgroup per CU wins for the read-only reduction.
 const Shape kDefaultShape[FAM_COUNT] = {
-    {256, 4, 1, 4},  // FP32 encode, TA
-    {512, 4, 1, 4},  // FP32 encode, HR
-    {512, 2, 2, 4},  // BF16 encode
-    {512, 2, 2, 4},  // fake-quant
-    {256, 2, 1, 4},  // decode
-    {512, 4, 0, 1},  // amax
-    {512, 1, 2, 4},  // diagnostic stream
+    {512, 2, 2, 4},   // FP32 encode, TA
+    {512, 4, 1, 4},   // FP32 encode, HR
+    {512, 2, 2, 4},   // BF16 encode
+    {512, 2, 2, 4},   // fake-quant
+    {512, 2, 1, 4},   // decode
+    {1024, 2, 0, 1},  // amax
+    {512, 1, 2, 4},   // diagnostic stream
 };
 
 // user overrides; -1 = use the family default
