@@ -51,6 +51,23 @@
  *     integers (so Inf dominates finite values and any NaN dominates Inf).
  *   - scale from amax: fl32(target / amax); with pow2 the largest power of
  *     two not above it; amax zero, Inf or NaN gives scale 1.
+ *   - Comparison modes (not adopted by the format; kept so that the paper's TA/TE/SR/HR
+ *     comparisons can be repeated):
+ *     TE  "even" means the neighbour that is an even multiple of the local step
+ *         hi - lo (IEEE-style).  In the denormal range the steps are powers of
+ *         two, so lo = 1 * step is odd and a tie goes up; at the underflow edge
+ *         lo = 0 is even and the tie 2^-23 goes to zero; at the overflow edge
+ *         lo = 2^15 = 2 * step is even and the tie 1.25 * 2^15 stays finite.
+ *         (PARITY UNPINNED outside the normal bands.)
+ *     SSR the simplified SR rule of HR applied in every binade, also |E| < 4.
+ *     SR  carry iff T < F with T = t32 / 2^32, t32 a 32-bit threshold drawn per
+ *         element from a counter-based generator (below); strict "<" makes the
+ *         carry probability exactly F for a discrete uniform T and keeps
+ *         representable inputs fixed (the paper writes F >= T for a real-valued T).
+ *         Threshold of element i under seed s: two rounds of the 32-bit finaliser
+ *         of MurmurHash3 over (low words of i and s), then (high words).
+ *   - FP16 sources use SR2 with the FP16 LSB (bit 13 of the binary32 pattern
+ *     being converted, so that, as for BF16, a scaled product is handled too).
  *
  * Arithmetic is fp64 throughout except where the method itself fixes binary32
  * (the scale multiply and the descale multiply).  Every fp64 quantity used in
@@ -72,7 +89,16 @@
  * public header of the HIP library, typed in again here on purpose). */
 #define ORM_TA 0u
 #define ORM_HR 1u
+#define ORM_TE 2u  /* rounding half to even: described in Sec. 3.1, not adopted by the format */
+#define ORM_SSR 3u /* simplified SR (SR14 / SR2) in every binade, Sec. 3.2                   */
+#define ORM_SR 4u  /* standard SR, Sec. 3.2, threshold from a counter-based generator        */
 #define ORM_MASK 0xFu
+
+/* source kinds: which simplified SR applies (Sec. 3.2: SR14 for FP32, SR2 for FP16 and BF16)
+ * and where the source format's LSB sits in the binary32 pattern being converted */
+#define OSRC_F32 0
+#define OSRC_BF16 1 /* LSB = bit 16 */
+#define OSRC_F16 2  /* LSB = bit 13 */
 #define OFLAG_SAT 0x10u
 #define OFLAG_NAN2ZERO 0x20u
 
@@ -206,7 +232,26 @@ static float bits_f32(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
  * Encode one binary32 value y (already scaled).  src_bf16 selects which
  * simplified SR the hybrid mode uses (SR2 for 16-bit sources, SR14 for FP32).
  * ---------------------------------------------------------------------- */
-uint8_t hif8o_encode_one(float y, uint32_t mode, int src_bf16) {
+/* counter-based threshold generator for standard SR (see header) */
+static uint32_t fmix32(uint32_t x) {
+  x ^= x >> 16; x *= 0x85EBCA6Bu; x ^= x >> 13; x *= 0xC2B2AE35u; x ^= x >> 16;
+  return x;
+}
+uint32_t hif8o_sr_threshold(uint64_t seed, uint64_t index) {
+  uint32_t x = fmix32((uint32_t)index ^ (uint32_t)seed);
+  x += (uint32_t)(index >> 32) * 0x9E3779B9u + (uint32_t)(seed >> 32);
+  return fmix32(x);
+}
+static uint64_t g_sr_seed = 0;
+void hif8o_set_sr_seed(uint64_t seed) { g_sr_seed = seed; }
+
+uint8_t hif8o_encode_one_t(float y, uint32_t mode, int src_kind, uint32_t t32);
+uint8_t hif8o_encode_one(float y, uint32_t mode, int src_kind) {
+  return hif8o_encode_one_t(y, mode, src_kind, 0u);
+}
+
+/* t32: the 32-bit threshold of this element (used by ORM_SR only) */
+uint8_t hif8o_encode_one_t(float y, uint32_t mode, int src_kind, uint32_t t32) {
   build_value_table();
   const uint32_t rm = mode & ORM_MASK;
   const int sat = (mode & OFLAG_SAT) != 0;
@@ -229,14 +274,23 @@ uint8_t hif8o_encode_one(float y, uint32_t mode, int src_bf16) {
   const double hi = (i + 1 < g_nval) ? g_val[i + 1] : V_OVERFLOW;
 
   int up;
-  int use_sr = 0;
+  int use_sr = (rm == ORM_SSR);
   if (rm == ORM_HR) {
     int ex;
     (void)frexp(a, &ex);       /* a = f * 2^ex, f in [0.5, 1) */
     const int E = ex - 1;      /* floor(log2 a) */
     use_sr = (E <= -4 || E >= 4); /* Eq. (3) */
   }
-  if (!use_sr) {
+  if (rm == ORM_TE) {
+    /* Sec. 3.1, TE: nearest, exact half goes to the even multiple of the step */
+    const double mid = 0.5 * (lo + hi);
+    if (a != mid) up = (a > mid);
+    else up = (fmod(lo / (hi - lo), 2.0) != 0.0); /* lo = n * step, n odd -> go up */
+  } else if (rm == ORM_SR) {
+    /* Sec. 3.2, standard SR: carry iff T < F, T = t32 / 2^32 */
+    const double frac = (a - lo) / (hi - lo);
+    up = ((double)t32 / 4294967296.0 < frac);
+  } else if (!use_sr) {
     /* Sec. 3.1, TA: nearest, exact half goes away from zero */
     const double mid = 0.5 * (lo + hi);
     up = (a >= mid);
@@ -245,9 +299,10 @@ uint8_t hif8o_encode_one(float y, uint32_t mode, int src_bf16) {
     const uint32_t ybits = f32_bits(y);
     const double frac = (a - lo) / (hi - lo); /* in [0, 1), exact */
     uint32_t F, T;
-    if (src_bf16) {
+    if (src_kind == OSRC_BF16 || src_kind == OSRC_F16) {
+      const int lsb_pos = (src_kind == OSRC_BF16) ? 16 : 13;
       F = (uint32_t)floor(frac * 4.0);
-      T = 2u * ((ybits >> 16) & 1u) + 1u;
+      T = 2u * ((ybits >> lsb_pos) & 1u) + 1u;
     } else {
       F = (uint32_t)floor(frac * 16384.0);
       T = ybits & 0x3FFFu;
@@ -311,6 +366,51 @@ static float decode_descaled(uint8_t code, float inv_scale) {
 }
 
 /* ------------------------------------------------------------------------
+ * Helpers for IEEE binary16 (1 sign, 5 exponent, 10 mantissa bits).
+ * ---------------------------------------------------------------------- */
+static float f16_to_f32(uint16_t h) {
+  const int s = h >> 15, e = (h >> 10) & 0x1F, m = h & 0x3FF;
+  double v;
+  if (e == 0x1F) {
+    if (m) return bits_f32(0x7FC00000u | ((uint32_t)s << 31) | ((uint32_t)m << 13));
+    v = INFINITY;
+  } else if (e == 0) {
+    v = ldexp((double)m, -24);                 /* subnormal: m * 2^-24 */
+  } else {
+    v = ldexp(1.0 + (double)m / 1024.0, e - 15);
+  }
+  return (float)(s ? -v : v);                  /* every binary16 value is exact in binary32 */
+}
+
+/* binary32 -> binary16, round to nearest even; NaN -> 0x7E00 */
+static uint16_t f32_to_f16_rne(float f) {
+  if (isnan(f)) return 0x7E00;
+  const uint16_t s = signbit(f) ? 0x8000 : 0;
+  double x = fabs((double)f);
+  if (isinf(f)) return (uint16_t)(s | 0x7C00);
+  if (x == 0.0) return s;
+  int ex;
+  (void)frexp(x, &ex);
+  int E = ex - 1;                              /* floor(log2 x) */
+  if (E < -14) E = -14;                        /* subnormal range shares the quantum 2^-24 */
+  const double q = ldexp(1.0, E - 10);         /* spacing of binary16 values near x */
+  const double r = rint(x / q) * q;            /* default rounding mode: nearest even; exact in fp64 */
+  if (r >= 65536.0) return (uint16_t)(s | 0x7C00); /* rounds past the largest finite 65504 */
+  if (r < ldexp(1.0, -14)) return (uint16_t)(s | (uint16_t)(r / ldexp(1.0, -24)));
+  (void)frexp(r, &ex);
+  const int Er = ex - 1;
+  const double frac = r / ldexp(1.0, Er) - 1.0; /* in [0, 1) */
+  return (uint16_t)(s | ((Er + 15) << 10) | (uint16_t)(frac * 1024.0));
+}
+
+void hif8o_widen_f16(const uint16_t *src, float *dst, size_t n) {
+  for (size_t i = 0; i < n; ++i) dst[i] = f16_to_f32(src[i]);
+}
+void hif8o_narrow_f16(const float *src, uint16_t *dst, size_t n) {
+  for (size_t i = 0; i < n; ++i) dst[i] = f32_to_f16_rne(src[i]);
+}
+
+/* ------------------------------------------------------------------------
  * Array entry points (what the tests and the CPU baseline call).
  * ---------------------------------------------------------------------- */
 static int g_threads_used = 1;
@@ -329,7 +429,7 @@ void hif8o_encode_f32(const float *src, uint8_t *dst, size_t n, float scale, uin
 #pragma omp parallel for schedule(static)
   for (ptrdiff_t i = 0; i < (ptrdiff_t)n; ++i) {
     volatile float y = src[i] * scale;
-    dst[i] = hif8o_encode_one(y, mode, 0);
+    dst[i] = hif8o_encode_one_t(y, mode, OSRC_F32, hif8o_sr_threshold(g_sr_seed, (uint64_t)i));
   }
 }
 
@@ -338,7 +438,16 @@ void hif8o_encode_bf16(const uint16_t *src, uint8_t *dst, size_t n, float scale,
 #pragma omp parallel for schedule(static)
   for (ptrdiff_t i = 0; i < (ptrdiff_t)n; ++i) {
     volatile float y = bf16_to_f32(src[i]) * scale;
-    dst[i] = hif8o_encode_one(y, mode, 1);
+    dst[i] = hif8o_encode_one_t(y, mode, OSRC_BF16, hif8o_sr_threshold(g_sr_seed, (uint64_t)i));
+  }
+}
+
+void hif8o_encode_f16(const uint16_t *src, uint8_t *dst, size_t n, float scale, uint32_t mode) {
+  build_value_table(); note_threads();
+#pragma omp parallel for schedule(static)
+  for (ptrdiff_t i = 0; i < (ptrdiff_t)n; ++i) {
+    volatile float y = f16_to_f32(src[i]) * scale;
+    dst[i] = hif8o_encode_one_t(y, mode, OSRC_F16, hif8o_sr_threshold(g_sr_seed, (uint64_t)i));
   }
 }
 
@@ -364,7 +473,7 @@ void hif8o_fake_quant_f32(const float *src, float *dst, uint8_t *codes_or_null, 
 #pragma omp parallel for schedule(static)
   for (ptrdiff_t i = 0; i < (ptrdiff_t)n; ++i) {
     volatile float y = src[i] * scale;
-    uint8_t c = hif8o_encode_one(y, mode, 0);
+    uint8_t c = hif8o_encode_one_t(y, mode, OSRC_F32, hif8o_sr_threshold(g_sr_seed, (uint64_t)i));
     if (codes_or_null) codes_or_null[i] = c;
     dst[i] = decode_descaled(c, inv);
   }
@@ -377,10 +486,40 @@ void hif8o_fake_quant_bf16(const uint16_t *src, uint16_t *dst, uint8_t *codes_or
 #pragma omp parallel for schedule(static)
   for (ptrdiff_t i = 0; i < (ptrdiff_t)n; ++i) {
     volatile float y = bf16_to_f32(src[i]) * scale;
-    uint8_t c = hif8o_encode_one(y, mode, 1);
+    uint8_t c = hif8o_encode_one_t(y, mode, OSRC_BF16, hif8o_sr_threshold(g_sr_seed, (uint64_t)i));
     if (codes_or_null) codes_or_null[i] = c;
     dst[i] = f32_to_bf16_rne(decode_descaled(c, inv));
   }
+}
+
+void hif8o_fake_quant_f16(const uint16_t *src, uint16_t *dst, uint8_t *codes_or_null, size_t n,
+                          float scale, uint32_t mode) {
+  build_value_table(); note_threads();
+  volatile float inv = 1.0f / scale;
+#pragma omp parallel for schedule(static)
+  for (ptrdiff_t i = 0; i < (ptrdiff_t)n; ++i) {
+    volatile float y = f16_to_f32(src[i]) * scale;
+    uint8_t c = hif8o_encode_one_t(y, mode, OSRC_F16, hif8o_sr_threshold(g_sr_seed, (uint64_t)i));
+    if (codes_or_null) codes_or_null[i] = c;
+    dst[i] = f32_to_f16_rne(decode_descaled(c, inv));
+  }
+}
+
+void hif8o_decode_f16(const uint8_t *src, uint16_t *dst, size_t n, float scale) {
+  note_threads();
+  volatile float inv = 1.0f / scale;
+#pragma omp parallel for schedule(static)
+  for (ptrdiff_t i = 0; i < (ptrdiff_t)n; ++i)
+    dst[i] = f32_to_f16_rne(decode_descaled(src[i], inv));
+}
+
+float hif8o_amax_f16(const uint16_t *src, size_t n) {
+  uint16_t m = 0;                     /* magnitude patterns of binary16 order like the values */
+  for (size_t i = 0; i < n; ++i) {
+    uint16_t a = src[i] & 0x7FFF;
+    if (a > m) m = a;
+  }
+  return f16_to_f32(m);
 }
 
 /* amax: maximum magnitude pattern, compared as unsigned integers */

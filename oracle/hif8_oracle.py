@@ -13,6 +13,10 @@ from . import build as _build
 
 RM_TA = 0
 RM_HR = 1
+RM_TE = 2
+RM_SSR = 3
+RM_SR = 4
+SRC_F32, SRC_BF16, SRC_F16 = 0, 1, 2
 FLAG_SAT = 0x10
 FLAG_NAN2ZERO = 0x20
 
@@ -32,6 +36,18 @@ _lib.hif8o_value_table.restype = ctypes.c_int
 _lib.hif8o_value_table.argtypes = [_f64p, _u8p]
 _lib.hif8o_encode_one.restype = ctypes.c_uint8
 _lib.hif8o_encode_one.argtypes = [ctypes.c_float, ctypes.c_uint32, ctypes.c_int]
+_lib.hif8o_encode_one_t.restype = ctypes.c_uint8
+_lib.hif8o_encode_one_t.argtypes = [ctypes.c_float, ctypes.c_uint32, ctypes.c_int, ctypes.c_uint32]
+_lib.hif8o_sr_threshold.restype = ctypes.c_uint32
+_lib.hif8o_sr_threshold.argtypes = [ctypes.c_uint64, ctypes.c_uint64]
+_lib.hif8o_set_sr_seed.argtypes = [ctypes.c_uint64]
+_lib.hif8o_widen_f16.argtypes = [_u16p, _f32p, ctypes.c_size_t]
+_lib.hif8o_narrow_f16.argtypes = [_f32p, _u16p, ctypes.c_size_t]
+_lib.hif8o_encode_f16.argtypes = [_u16p, _u8p, ctypes.c_size_t, ctypes.c_float, ctypes.c_uint32]
+_lib.hif8o_decode_f16.argtypes = [_u8p, _u16p, ctypes.c_size_t, ctypes.c_float]
+_lib.hif8o_fake_quant_f16.argtypes = [_u16p, _u16p, _u8p, ctypes.c_size_t, ctypes.c_float, ctypes.c_uint32]
+_lib.hif8o_amax_f16.restype = ctypes.c_float
+_lib.hif8o_amax_f16.argtypes = [_u16p, ctypes.c_size_t]
 _lib.hif8o_set_literal_sr_zero.argtypes = [ctypes.c_int]
 _lib.hif8o_threads_used.restype = ctypes.c_int
 _lib.hif8o_encode_f32.argtypes = [_f32p, _u8p, ctypes.c_size_t, ctypes.c_float, ctypes.c_uint32]
@@ -83,8 +99,62 @@ def value_table():
     return vals[:n].copy(), codes[:n].copy()
 
 
-def encode_one(y: float, mode: int = RM_TA, src_bf16: bool = False) -> int:
-    return _lib.hif8o_encode_one(np.float32(y), mode, int(src_bf16))
+def encode_one(y: float, mode: int = RM_TA, src_bf16=False, t32: int = 0) -> int:
+    """src_bf16: False / SRC_F32, True / SRC_BF16, or SRC_F16; t32: threshold for RM_SR."""
+    return _lib.hif8o_encode_one_t(np.float32(y), mode, int(src_bf16), t32)
+
+
+def sr_threshold(seed: int, index: int) -> int:
+    return _lib.hif8o_sr_threshold(seed, index)
+
+
+def set_sr_seed(seed: int) -> None:
+    """Seed of the standard-SR threshold generator used by the array functions."""
+    _lib.hif8o_set_sr_seed(seed)
+
+
+def widen_f16(src):
+    src = _arr(src, np.uint16)
+    dst = np.empty(src.shape, np.float32)
+    _lib.hif8o_widen_f16(_ptr(src, ctypes.c_uint16), _ptr(dst, ctypes.c_float), src.size)
+    return dst
+
+
+def narrow_f16(src):
+    src = _arr(src, np.float32)
+    dst = np.empty(src.shape, np.uint16)
+    _lib.hif8o_narrow_f16(_ptr(src, ctypes.c_float), _ptr(dst, ctypes.c_uint16), src.size)
+    return dst
+
+
+def encode_f16(src, scale=1.0, mode=RM_TA):
+    src = _arr(src, np.uint16)
+    dst = np.empty(src.shape, np.uint8)
+    _lib.hif8o_encode_f16(_ptr(src, ctypes.c_uint16), _ptr(dst, ctypes.c_uint8), src.size,
+                          np.float32(scale), mode)
+    return dst
+
+
+def decode_f16(codes, scale=1.0):
+    codes = _arr(codes, np.uint8)
+    dst = np.empty(codes.shape, np.uint16)
+    _lib.hif8o_decode_f16(_ptr(codes, ctypes.c_uint8), _ptr(dst, ctypes.c_uint16), codes.size,
+                          np.float32(scale))
+    return dst
+
+
+def fake_quant_f16(src, scale=1.0, mode=RM_TA):
+    src = _arr(src, np.uint16)
+    dst = np.empty(src.shape, np.uint16)
+    codes = np.empty(src.shape, np.uint8)
+    _lib.hif8o_fake_quant_f16(_ptr(src, ctypes.c_uint16), _ptr(dst, ctypes.c_uint16),
+                              _ptr(codes, ctypes.c_uint8), src.size, np.float32(scale), mode)
+    return dst, codes
+
+
+def amax_f16(src) -> np.float32:
+    src = _arr(src, np.uint16)
+    return np.float32(_lib.hif8o_amax_f16(_ptr(src, ctypes.c_uint16), src.size))
 
 
 def set_literal_sr_zero(on: bool) -> None:

@@ -21,6 +21,7 @@ from conftest import golden_lines
 from oracle import hif8_oracle as orc
 
 TA, HR = orc.RM_TA, orc.RM_HR
+TE, SSR, SR = orc.RM_TE, orc.RM_SSR, orc.RM_SR
 SAT, N2Z = orc.FLAG_SAT, orc.FLAG_NAN2ZERO
 
 
@@ -53,13 +54,18 @@ def kept_bits_of_exponent(E):
     return k
 
 
-def closed_form_round(ybits, rm, src_bf16):
+def closed_form_round(ybits, rm, src_bf16, t32=None):
     """Bit-level rounding of binary32 patterns (non-NaN) to HiF8 *values* (float64;
     +-inf on overflow, 0 on underflow), written from the prose of Sec. 3: keep k(E)
     mantissa bits, look only at the discarded bits.  TA: carry iff the top discarded bit
     is 1.  SR: carry iff F >= T (F top 14 / 2 discarded bits; T the 14 LSBs of the pattern
-    / {LSB of the BF16 pattern, 1}), no carry when F = T = 0.  Below 2^-22 the discarded
-    fraction is the fixed-point fraction of one 2^-22 step."""
+    / {LSB of the 16-bit source pattern, 1}), no carry when F = T = 0.  Below 2^-22 the discarded
+    fraction is the fixed-point fraction of one 2^-22 step.
+    src_bf16: False/0 = FP32 source, True/1 = BF16 (LSB at bit 16), 2 = FP16 (LSB at bit 13).
+    Comparison modes: TE carries iff the discarded part is above half, or exactly half with an
+    odd kept significand; SSR is the SR rule in every binade; SR carries iff the threshold
+    t32 / 2^32 is below the discarded fraction."""
+    src_kind = int(src_bf16)
     ybits = np.asarray(ybits, np.uint32)
     sign = np.where(ybits >> 31, -1.0, 1.0)
     a = (ybits & 0x7FFFFFFF).astype(np.int64)
@@ -75,11 +81,12 @@ def closed_form_round(ybits, rm, src_bf16):
     under = (val < 2.0 ** -22)
     # f * 2^24 as an exact integer when possible: floor() of a float64 is exact here
     f = np.where(under, val, 0.0) * 2.0 ** 22
-    if src_bf16:
+    if src_kind:
         F_u = np.floor(f * 4).astype(np.int64)
     else:
         F_u = np.floor(f * 16384).astype(np.int64)
     ta_up_u = f >= 0.5
+    te_up_u = f > 0.5                      # the tie f = 1/2 sits next to lo = 0, an even multiple
 
     # --- regular region
     k = kept_bits_of_exponent(E)
@@ -89,13 +96,13 @@ def closed_form_round(ybits, rm, src_bf16):
     disc = m & ((1 << d) - 1)
     keep = m >> d
     top = (disc >> (d - 1)) & 1
-    if src_bf16:
+    if src_kind:
         F_r = disc >> (d - 2)
     else:
         F_r = disc >> (d - 14)
 
-    if src_bf16:
-        T = 2 * ((a >> 16) & 1) + 1
+    if src_kind:
+        T = 2 * ((a >> (16 if src_kind == 1 else 13)) & 1) + 1
     else:
         T = a & 0x3FFF
     F = np.where(under, F_u, F_r)
@@ -103,6 +110,18 @@ def closed_form_round(ybits, rm, src_bf16):
     ta_up = np.where(under, ta_up_u, top == 1)
     if rm == TA:
         up = ta_up
+    elif rm == TE:
+        half = np.int64(1) << (d - 1)
+        n_odd = np.where(k > 0, keep & 1, 1)
+        te_up = (disc > half) | ((disc == half) & (n_odd == 1))
+        up = np.where(under, te_up_u, te_up)
+    elif rm == SSR:
+        up = sr_up
+    elif rm == SR:
+        t = np.asarray(t32, np.uint32).astype(np.int64)
+        up_r = (t >> (32 - d)) < disc
+        up_u = (t.astype(np.float64) / 2.0 ** 32) < f
+        up = np.where(under, up_u, up_r)
     else:
         use_sr = (np.abs(E) >= 4)
         up = np.where(use_sr, sr_up, ta_up)
