@@ -26,9 +26,20 @@ constexpr uint32_t kCodeNaN = 0x80u;  // 1 0000 000
 constexpr uint32_t kBitsOverflow = 0x47400000u;  // binary32 pattern of 1.5 * 2^15
 constexpr uint32_t kBitsTwoM22 = 105u << 23;     // binary32 pattern of 2^-22 (smallest denormal code)
 
-// rounding_mode flag bits as seen by kernels
+// rounding_mode bit-field as seen by kernels
+constexpr uint32_t kRmTA = 0u;   // rounding half away from zero (Sec. 3.1)
+constexpr uint32_t kRmHR = 1u;   // hybrid rounding (Eq. (3))
+constexpr uint32_t kRmTE = 2u;   // rounding half to even (Sec. 3.1; comparison mode)
+constexpr uint32_t kRmSSR = 3u;  // simplified SR in every binade (Sec. 3.2; comparison mode)
+constexpr uint32_t kRmSR = 4u;   // standard SR with a counter-based threshold (Sec. 3.2; comparison mode)
 constexpr uint32_t kFlagSat = 0x10u;
 constexpr uint32_t kFlagNan2Zero = 0x20u;
+
+// source kinds: which simplified SR applies and where the source format's LSB sits in the
+// binary32 pattern being converted (Sec. 3.2: SR14 for FP32, SR2 for FP16 and BF16)
+constexpr int kSrcF32 = 0;
+constexpr int kSrcBF16 = 1;  // LSB = bit 16
+constexpr int kSrcF16 = 2;   // LSB = bit 13
 
 __device__ __forceinline__ uint32_t overflow_code(uint32_t mode) {
   return (mode & kFlagSat) ? kCodeMax : kCodeInf;
@@ -61,7 +72,7 @@ __device__ __forceinline__ uint32_t kept_bits(uint32_t e) {
 //     F = top 14 (FP32 source) or top 2 (16-bit source) discarded bits, T = low 14 bits of
 //     the pattern, or {bit 16, 1}.  F = 0 never carries (T is raised to at least 1), which
 //     keeps representable inputs fixed.
-template <bool HR, bool SRC16>
+template <bool HR, int SRCK>
 __device__ __forceinline__ uint32_t round_mag(uint32_t a, uint32_t ybits) {
   uint32_t ap = a;
   {
@@ -73,9 +84,9 @@ __device__ __forceinline__ uint32_t round_mag(uint32_t a, uint32_t ybits) {
   const uint32_t k = kept_bits(ap >> 23);
   const uint32_t sh = 23u - k;
   uint32_t F, T;
-  if (SRC16) {
+  if (SRCK != kSrcF32) {
     F = (ap >> (sh - 2u)) & 3u;
-    T = 2u * ((ybits >> 16) & 1u) + 1u;
+    T = 2u * ((ybits >> (SRCK == kSrcBF16 ? 16 : 13)) & 1u) + 1u;
     if (!HR || k == 3u) T = 2u;
   } else {
     F = (ap >> (sh - 14u)) & 0x3FFFu;
@@ -114,11 +125,101 @@ __device__ __forceinline__ uint32_t pack_mag(uint32_t r, uint32_t ovf_code) {
 }
 
 // Full ALU encode of one binary32 pattern (already scaled).
-template <bool HR, bool SRC16>
+template <bool HR, int SRCK>
 __device__ __forceinline__ uint32_t encode_alu(uint32_t ybits, uint32_t mode) {
   const uint32_t a = ybits & 0x7FFFFFFFu;
   if (a > 0x7F800000u) return nan_code(mode);
-  const uint32_t c = pack_mag(round_mag<HR, SRC16>(a, ybits), overflow_code(mode));
+  const uint32_t c = pack_mag(round_mag<HR, SRCK>(a, ybits), overflow_code(mode));
+  return c ? (c | ((ybits >> 24) & 0x80u)) : 0u;
+}
+
+// ------------------------------------------------------------------------------------
+// Comparison modes (Sec. 3.1 TE; Sec. 3.2 simplified SR everywhere, standard SR), written
+// for clarity: these are not on the throughput path.
+// ------------------------------------------------------------------------------------
+
+// 32-bit threshold of element `index` under `seed`: two rounds of MurmurHash3's 32-bit
+// finaliser, first over the low words, then folding in the high words.
+__device__ __forceinline__ uint32_t fmix32(uint32_t x) {
+  x ^= x >> 16; x *= 0x85EBCA6Bu; x ^= x >> 13; x *= 0xC2B2AE35u; x ^= x >> 16;
+  return x;
+}
+__device__ __forceinline__ uint32_t sr_threshold(uint64_t seed, uint64_t index) {
+  uint32_t x = fmix32((uint32_t)index ^ (uint32_t)seed);
+  x += (uint32_t)(index >> 32) * 0x9E3779B9u + (uint32_t)(seed >> 32);
+  return fmix32(x);
+}
+
+// Rounded pattern of magnitude `a` (not NaN) under rounding method rm (any of the five), in
+// the convention of round_mag(): exponent 103 reads as zero and 104 as 2^-22 in pack_mag().
+//   TE : carry iff the discarded part is above half, or exactly half and the kept
+//        significand is odd (with no kept mantissa bits the significand is 1: odd).
+//        Below 2^-22 the lower neighbour is 0 (even), so only strictly more than half carries.
+//   SR : carry iff t32 / 2^32 < discarded fraction.  With d discarded bits that is
+//        (t32 >> (32 - d)) < discarded, exactly.  Below 2^-22 the fraction is sig / 2^s,
+//        s = 128 - e >= 24.
+//   TA / HR / SSR: the F >= T rule of round_mag(), SSR without the |E| < 4 exception.
+template <int SRCK>
+__device__ __forceinline__ uint32_t round_mag_any(uint32_t rm, uint32_t a, uint32_t ybits, uint32_t t32) {
+  if (rm == kRmTA) return round_mag<false, SRCK>(a, ybits);
+  if (rm == kRmHR) return round_mag<true, SRCK>(a, ybits);
+  const uint32_t e = a >> 23;
+  if (a < kBitsTwoM22) {
+    // value = sig * 2^(e - 150) (subnormal binary32: sig = mantissa, e taken as 1)
+    const uint32_t sig = e ? ((a & 0x7FFFFFu) | 0x800000u) : a;
+    const uint32_t s = 128u - (e ? e : 1u);  // fraction of the 2^-22 step = sig / 2^s, s in [24, 127]
+    bool carry;
+    if (rm == kRmTE) {
+      carry = (s == 24u) && (sig > 0x800000u);  // more than half of the step
+    } else if (rm == kRmSR) {
+      if (s < 32u) carry = t32 < (sig << (32u - s));
+      else if (s < 56u) carry = t32 < ((sig + (1u << (s - 32u)) - 1u) >> (s - 32u));  // ceil(sig / 2^(s-32))
+      else carry = (t32 == 0u) && (sig != 0u);
+    } else {  // SSR: top 14 (or 2) bits of the fraction against the threshold bits
+      uint32_t F, T;
+      if (SRCK != kSrcF32) {
+        F = (s - 2u < 32u) ? (sig >> (s - 2u)) : 0u;
+        T = 2u * ((ybits >> (SRCK == kSrcBF16 ? 16 : 13)) & 1u) + 1u;
+      } else {
+        F = (s - 14u < 32u) ? (sig >> (s - 14u)) : 0u;
+        T = ybits & 0x3FFFu;
+        T = T < 1u ? 1u : T;
+      }
+      carry = F >= T;
+    }
+    return (carry ? 104u : 103u) << 23;
+  }
+  const uint32_t k = kept_bits(e);
+  const uint32_t d = 23u - k;
+  const uint32_t disc = a & ((1u << d) - 1u);
+  bool carry;
+  if (rm == kRmTE) {
+    const uint32_t half = 1u << (d - 1u);
+    const uint32_t n_odd = k ? ((a >> d) & 1u) : 1u;
+    carry = disc > half || (disc == half && n_odd);
+  } else if (rm == kRmSR) {
+    carry = (t32 >> (32u - d)) < disc;
+  } else {
+    uint32_t F, T;
+    if (SRCK != kSrcF32) {
+      F = disc >> (d - 2u);
+      T = 2u * ((ybits >> (SRCK == kSrcBF16 ? 16 : 13)) & 1u) + 1u;
+    } else {
+      F = disc >> (d - 14u);
+      T = ybits & 0x3FFFu;
+      T = T < 1u ? 1u : T;
+    }
+    carry = F >= T;
+  }
+  return ((a >> d) + (carry ? 1u : 0u)) << d;
+}
+
+// Full encode of one binary32 pattern under any rounding method (element-wise paths).
+template <int SRCK>
+__device__ __forceinline__ uint32_t encode_any(uint32_t ybits, uint32_t mode, uint32_t t32) {
+  const uint32_t a = ybits & 0x7FFFFFFFu;
+  if (a > 0x7F800000u) return nan_code(mode);
+  const uint32_t c = pack_mag(round_mag_any<SRCK>(mode & 0xFu, a, ybits, t32), overflow_code(mode));
   return c ? (c | ((ybits >> 24) & 0x80u)) : 0u;
 }
 
@@ -146,7 +247,8 @@ __device__ __forceinline__ float pow2f(int x) {  // 2^x for x in [-126, 127]
   return v.f;
 }
 
-__device__ __forceinline__ HrExp hr_exp_entry(uint32_t e) {
+// ssr: simplified SR in every binade (no TA exception for |E| < 4)
+__device__ __forceinline__ HrExp hr_exp_entry(uint32_t e, bool ssr = false) {
   HrExp h;
   if (e <= 104u) {  // |y| < 2^-22: one step from 0 to 2^-22
     h.c = pow2f(36);
@@ -156,7 +258,7 @@ __device__ __forceinline__ HrExp hr_exp_entry(uint32_t e) {
   const int E = (int)e - 127;
   const int k = (int)kept_bits(e);
   h.c = pow2f(14 - E + k);
-  h.tpack = (k == 3) ? (0x2000u | (0x2000u << 16)) : (1u | (0x3FFFu << 16));
+  h.tpack = (k == 3 && !ssr) ? (0x2000u | (0x2000u << 16)) : (1u | (0x3FFFu << 16));
   // Inf: the product saturates the integer conversion to 2^32 - 1; a threshold of 2^14
   // never carries, so Q stays saturated instead of wrapping, and n' * ulp overflows to Inf
   if (e == 255u) h.tpack = 0x4000u | (0x4000u << 16);
@@ -188,14 +290,17 @@ __device__ __forceinline__ uint32_t med3_u32(uint32_t a, uint32_t lo, uint32_t h
 
 // Rounded binary32 pattern (sign kept) of non-NaN pattern ybits under HR; p = table entry
 // of ybits' exponent.  The result is on the HiF8 grid (or at/above 1.5 * 2^15: overflow).
-template <bool SRC16>
+template <int SRCK>
 __device__ __forceinline__ uint32_t hr_round_bits(uint32_t ybits, const HrExp& p) {
   union { uint32_t u; float f; } y, r, c, inv;
   y.u = ybits & 0x7FFFFFFFu;
   c.f = p.c;
   inv.u = 0x7F000000u - c.u;  // 1/c for c = 2^x: exponent field 127 - x
   const uint32_t q = cvt_u32_trunc_sat(y.f * c.f);
-  uint32_t T = SRC16 ? (((ybits >> 3) & 0x2000u) | 0x1000u) : (ybits & 0x3FFFu);
+  // SR2: T2 = {source LSB, 1} against the top two fraction bits == T2 * 2^12 against F14
+  uint32_t T = (SRCK == kSrcBF16) ? (((ybits >> 3) & 0x2000u) | 0x1000u)
+             : (SRCK == kSrcF16)  ? ((ybits & 0x2000u) | 0x1000u)
+                                  : (ybits & 0x3FFFu);
   T = med3_u32(T, p.tpack & 0xFFFFu, p.tpack >> 16);
   const uint32_t qq = (q - T + 0x4000u) & 0xFFFFC000u;
   r.f = (float)qq * inv.f;

@@ -11,23 +11,31 @@ static inline int __clz(int x) { return x == 0 ? 32 : __builtin_clz((unsigned)x)
 #include "../../paper_2409_16626_amd/csrc/hif8_device.hpp"
 
 extern "C" {
-void devfn_encode_bits(const uint32_t* ybits, uint8_t* dst, size_t n, uint32_t mode, int src16) {
-  const bool hr = (mode & 0xF) == 1;
+// generic element-wise form (any rounding method, any source kind)
+void devfn_encode_bits(const uint32_t* ybits, uint8_t* dst, size_t n, uint32_t mode, int srck,
+                       uint64_t seed) {
   for (size_t i = 0; i < n; ++i) {
+    const uint32_t t = hif8dev::sr_threshold(seed, (uint64_t)i);
     uint32_t c;
-    if (hr) c = src16 ? hif8dev::encode_alu<true, true>(ybits[i], mode) : hif8dev::encode_alu<true, false>(ybits[i], mode);
-    else c = src16 ? hif8dev::encode_alu<false, true>(ybits[i], mode) : hif8dev::encode_alu<false, false>(ybits[i], mode);
+    if (srck == 0) c = hif8dev::encode_any<0>(ybits[i], mode, t);
+    else if (srck == 1) c = hif8dev::encode_any<1>(ybits[i], mode, t);
+    else c = hif8dev::encode_any<2>(ybits[i], mode, t);
     dst[i] = (uint8_t)c;
   }
 }
-// table-driven hybrid rounding, then the TA code of the (representable) result
-void devfn_encode_bits_hr_table(const uint32_t* ybits, uint8_t* dst, size_t n, uint32_t mode, int src16) {
+// table-driven hybrid rounding (or simplified SR everywhere), then the TA code of the
+// (representable) result
+void devfn_encode_bits_hr_table(const uint32_t* ybits, uint8_t* dst, size_t n, uint32_t mode, int srck) {
+  const bool ssr = (mode & 0xF) == hif8dev::kRmSSR;
   for (size_t i = 0; i < n; ++i) {
     const uint32_t y = ybits[i];
     if ((y & 0x7FFFFFFFu) > 0x7F800000u) { dst[i] = (uint8_t)hif8dev::nan_code(mode); continue; }
-    const hif8dev::HrExp p = hif8dev::hr_exp_entry((y >> 23) & 0xFFu);
-    const uint32_t r = src16 ? hif8dev::hr_round_bits<true>(y, p) : hif8dev::hr_round_bits<false>(y, p);
-    dst[i] = (uint8_t)hif8dev::encode_alu<false, false>(r & 0xFFF80000u, mode);
+    const hif8dev::HrExp p = hif8dev::hr_exp_entry((y >> 23) & 0xFFu, ssr);
+    uint32_t r;
+    if (srck == 0) r = hif8dev::hr_round_bits<0>(y, p);
+    else if (srck == 1) r = hif8dev::hr_round_bits<1>(y, p);
+    else r = hif8dev::hr_round_bits<2>(y, p);
+    dst[i] = (uint8_t)hif8dev::encode_alu<false, 0>(r & 0xFFF80000u, mode);
   }
 }
 void devfn_decode_bits(const uint8_t* codes, uint32_t* dst, size_t n) {

@@ -30,26 +30,25 @@ def dev():
     return lib
 
 
-def _enc(lib, ybits, mode, src16):
+def _enc(lib, ybits, mode, srck, seed=0):
     ybits = np.ascontiguousarray(ybits, np.uint32)
     out = np.empty(ybits.shape, np.uint8)
-    if (mode & 0xF) == orc.RM_HR:
+    lib.devfn_encode_bits(ybits.ctypes.data_as(ctypes.c_void_p), out.ctypes.data_as(ctypes.c_void_p),
+                          ctypes.c_size_t(ybits.size), ctypes.c_uint32(mode), ctypes.c_int(srck),
+                          ctypes.c_uint64(seed))
+    if (mode & 0xF) in (orc.RM_HR, orc.RM_SSR):
         # the streaming kernels' table-driven form must agree with the generic form
         out2 = np.empty(ybits.shape, np.uint8)
         lib.devfn_encode_bits_hr_table(ybits.ctypes.data_as(ctypes.c_void_p), out2.ctypes.data_as(ctypes.c_void_p),
-                                       ctypes.c_size_t(ybits.size), ctypes.c_uint32(mode), ctypes.c_int(src16))
-        lib.devfn_encode_bits(ybits.ctypes.data_as(ctypes.c_void_p), out.ctypes.data_as(ctypes.c_void_p),
-                              ctypes.c_size_t(ybits.size), ctypes.c_uint32(mode), ctypes.c_int(src16))
+                                       ctypes.c_size_t(ybits.size), ctypes.c_uint32(mode), ctypes.c_int(srck))
         bad = np.nonzero(out != out2)[0]
         assert bad.size == 0, [(hex(ybits[i]), hex(out[i]), hex(out2[i])) for i in bad[:8]]
-        return out2
-    lib.devfn_encode_bits(ybits.ctypes.data_as(ctypes.c_void_p), out.ctypes.data_as(ctypes.c_void_p),
-                          ctypes.c_size_t(ybits.size), ctypes.c_uint32(mode), ctypes.c_int(src16))
     return out
 
 
 MODES = [orc.RM_TA, orc.RM_HR, orc.RM_TA | orc.FLAG_SAT, orc.RM_HR | orc.FLAG_SAT,
-         orc.RM_TA | orc.FLAG_NAN2ZERO, orc.RM_HR | orc.FLAG_SAT | orc.FLAG_NAN2ZERO]
+         orc.RM_TA | orc.FLAG_NAN2ZERO, orc.RM_HR | orc.FLAG_SAT | orc.FLAG_NAN2ZERO,
+         orc.RM_TE, orc.RM_SSR, orc.RM_SR, orc.RM_TE | orc.FLAG_SAT, orc.RM_SR | orc.FLAG_SAT | orc.FLAG_NAN2ZERO]
 
 
 @pytest.mark.parametrize("mode", MODES)
@@ -64,8 +63,13 @@ def test_device_encode_logic_f32(dev, mode):
     yb[::8] &= np.uint32(0xFFFFC000)
     h = np.arange(65536, dtype=np.uint16).view(np.float16).astype(np.float32).view(np.uint32)
     allb = np.concatenate(parts + [yb, h])
-    want = orc.encode_f32(allb.view(np.float32), 1.0, mode)
-    got = _enc(dev, allb, mode, 0)
+    allb[5::16] &= np.uint32(0xFFF80000)      # exact ties and representable values for TE
+    orc.set_sr_seed(0xABCDEF0123)
+    try:
+        want = orc.encode_f32(allb.view(np.float32), 1.0, mode)
+    finally:
+        orc.set_sr_seed(0)
+    got = _enc(dev, allb, mode, 0, 0xABCDEF0123)
     bad = np.nonzero(want != got)[0]
     assert bad.size == 0, [(hex(allb[i]), hex(want[i]), hex(got[i])) for i in bad[:8]]
 
@@ -79,6 +83,17 @@ def test_device_encode_logic_bf16(dev, mode):
         got = _enc(dev, prod.view(np.uint32), mode, 1)
         bad = np.nonzero(want != got)[0]
         assert bad.size == 0, [(hex(b[i]), hex(want[i]), hex(got[i])) for i in bad[:8]]
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_device_encode_logic_f16(dev, mode):
+    h = np.arange(65536, dtype=np.uint16)
+    for scale in (np.float32(1.0), np.float32(0.37), np.float32(2.0 ** -9)):
+        prod = (h.view(np.float16).astype(np.float32) * scale).astype(np.float32)
+        want = orc.encode_f16(h, scale, mode)
+        got = _enc(dev, prod.view(np.uint32), mode, 2)
+        bad = np.nonzero(want != got)[0]
+        assert bad.size == 0, [(hex(h[i]), hex(want[i]), hex(got[i])) for i in bad[:8]]
 
 
 def test_device_decode_logic(dev):
