@@ -246,7 +246,7 @@ def main():
         extra["C5 per-tensor calls, 225 x (amax, scale, encode_bf16) (3 B/elem primary)"] = rate(3 * tot, e_ms)
         extra["C5 per-tensor calls (5 B/elem with amax pass)"] = rate(5 * tot, e_ms)
         items = [(ap + 2 * off, cp + off, cnt) for _, off, cnt in index]
-        d_items, count, tiles = hif8.hif8_multi_plan(items, src_is_bf16=True)
+        d_items, count, tiles = hif8.hif8_multi_plan(items, src_is_16bit=True)
         w_ms, e_ms = timed(lambda i: hif8.hif8_multi_cast_bf16(d_items, count, tiles, ams, scs, hif8.MAX_FINITE, 0, hif8.RM_TA), 5, 1)
         extra["C5 multi-tensor cast, 4 launches (3 B/elem primary)"] = rate(3 * tot, e_ms)
         extra["C5 multi-tensor cast, 4 launches (5 B/elem with amax pass)"] = rate(5 * tot, e_ms)

@@ -8,6 +8,8 @@
  *   Sec. 3.1               rounding half away from zero (TA)
  *   Sec. 3.2, Eq. (3)      hybrid rounding (HR): TA if |E| < 4, else simplified stochastic
  *                          rounding (SR14 for FP32 sources, SR2 for 16-bit sources)
+ *   Sec. 3.1, Sec. 3.2     the methods the paper compares these with: rounding half to even
+ *                          (TE), simplified SR in every binade, standard SR
  *   Sec. 3 (options)       saturation on overflow, NaN to zero
  *   Sec. 5 (PTS)           per-tensor amax, scale factor, scale before / descale after
  *
@@ -20,11 +22,12 @@
  *     (exception: the first call on a device, see hif8_init) and never read
  *     results back to the host.
  *   - Element counts are size_t; kernels index with 64 bits.
- *   - bfloat16 tensors are passed as raw uint16_t bit patterns.
+ *   - bfloat16 (_bf16 entry points) and IEEE binary16 (_f16 entry points) tensors are
+ *     passed as raw uint16_t bit patterns.
  *   - Any pointer alignment and any n are accepted.  The fast path needs the
  *     source 16-byte aligned and the destination(s) aligned to their per-lane
  *     store width (4 B for u8 codes of an FP32 source, 8 B for u8 codes of a
- *     BF16 source, 16 B for FP32 / BF16 outputs); otherwise a slower
+ *     16-bit source, 16 B for FP32 / BF16 / FP16 outputs); otherwise a slower
  *     element-per-lane kernel computes the same result.
  *   - n == 0 is valid and enqueues nothing (hif8_amax_* still writes 0); data pointers
  *     may then be NULL.  Mode and scale are validated first in every case.
@@ -35,8 +38,8 @@
  *         encode      dst[i] = code( Q( fl32( widen(src[i]) * scale ) ) )
  *         decode      dst[i] = narrow( fl32( value(src[i]) * fl32(1/scale) ) )
  *         fake_quant  dst[i] = decode(encode(src[i])) with the same scale
- *     narrow() to BF16 is round-to-nearest-even.  value(NaN code) is the quiet
- *     NaN 0x7FC00000 (BF16 0x7FC0), value(Inf codes) is +-Inf, value(0x00) is
+ *     narrow() to BF16 / FP16 is round-to-nearest-even.  value(NaN code) is the quiet
+ *     NaN 0x7FC00000 (BF16 0x7FC0, FP16 0x7E00), value(Inf codes) is +-Inf, value(0x00) is
  *     +0.0.  scale = 1 gives the paper's plain cast.
  *   - `scale` must be finite and > 0, and 1/scale must be finite and > 0,
  *     else HIF8_ERR_SCALE.
@@ -65,9 +68,16 @@ enum {
 };
 
 /* rounding_mode bit-field */
-#define HIF8_RM_TA 0u            /* Sec. 3.1: round half away from zero                        */
-#define HIF8_RM_HR 1u            /* Eq. (3): TA if |E| < 4, else SR14 (FP32 src) / SR2 (BF16) */
-#define HIF8_RM_MASK 0xFu        /* values 2..15 reserved                                      */
+#define HIF8_RM_TA 0u            /* Sec. 3.1: round half away from zero                          */
+#define HIF8_RM_HR 1u            /* Eq. (3): TA if |E| < 4, else SR14 (FP32 src) / SR2 (16-bit)  */
+/* Comparison modes: described by the paper, not adopted by the format. */
+#define HIF8_RM_TE 2u            /* Sec. 3.1: round half to even (a tie goes to the neighbour that
+                                    is an even multiple of the local step; 0 counts as even)     */
+#define HIF8_RM_SSR 3u           /* Sec. 3.2: simplified SR (SR14 / SR2) in every binade         */
+#define HIF8_RM_SR 4u            /* Sec. 3.2: standard SR; element i carries iff t_i / 2^32 is
+                                    below its discarded fraction, t_i = hif8_sr_threshold(seed, i)
+                                    with the seed set by hif8_set_sr_seed                        */
+#define HIF8_RM_MASK 0xFu        /* values 5..15 reserved                                        */
 #define HIF8_FLAG_SAT 0x10u      /* overflow and +-Inf input -> +-2^15 instead of +-Inf        */
 #define HIF8_FLAG_NAN2ZERO 0x20u /* NaN input -> 0x00 instead of 0x80                          */
 
@@ -91,13 +101,28 @@ int hif8_last_hip_error(void);
 hif8_status hif8_init(void);
 
 /*
+ * Seed of the threshold generator of HIF8_RM_SR (process-wide; default 0).  A call uses the
+ * seed in effect when it is enqueued.  The 32-bit threshold of element i (index within the
+ * tensor of the call) is two rounds of the 32-bit MurmurHash3 finaliser
+ *     fmix(x): x ^= x >> 16; x *= 0x85EBCA6B; x ^= x >> 13; x *= 0xC2B2AE35; x ^= x >> 16
+ *     t = fmix( fmix(lo32(i) ^ lo32(seed)) + hi32(i) * 0x9E3779B9 + hi32(seed) )
+ * so results are reproducible and independent of the launch shape.  Sec. 3.2 notes that
+ * standard SR needs a random number per element; a counter-based hash supplies it here.
+ */
+hif8_status hif8_set_sr_seed(uint64_t seed);
+uint64_t hif8_get_sr_seed(void);
+uint32_t hif8_sr_threshold(uint64_t seed, uint64_t index); /* host-side evaluation of t */
+
+/*
  * Per-tensor amax (Sec. 5, per-tensor scaling): *d_amax = max_i |src[i]|.
  * The maximum is taken over the magnitude bit patterns as unsigned integers, so
  * Inf dominates finite values and any NaN dominates Inf (the result is then a NaN).
+ * For FP16 sources the payload of a NaN result is unspecified.
  * d_amax: one device float, overwritten (the call clears it on the stream first).
  */
 hif8_status hif8_amax_f32(const float* src, size_t n, float* d_amax, hif8_stream_t stream);
 hif8_status hif8_amax_bf16(const uint16_t* src, size_t n, float* d_amax, hif8_stream_t stream);
+hif8_status hif8_amax_f16(const uint16_t* src, size_t n, float* d_amax, hif8_stream_t stream);
 
 /*
  * Scale factor from a device-resident amax, without a host round trip
@@ -120,6 +145,8 @@ hif8_status hif8_encode_f32(const float* src, uint8_t* dst, size_t n, float scal
                             uint32_t rounding_mode, hif8_stream_t stream);
 hif8_status hif8_encode_bf16(const uint16_t* src, uint8_t* dst, size_t n, float scale,
                              uint32_t rounding_mode, hif8_stream_t stream);
+hif8_status hif8_encode_f16(const uint16_t* src, uint8_t* dst, size_t n, float scale,
+                            uint32_t rounding_mode, hif8_stream_t stream);
 
 /*
  * Decode (Eq. (1), Eq. (2), special patterns): n u8 codes -> n values, descaled.
@@ -129,6 +156,8 @@ hif8_status hif8_decode_f32(const uint8_t* src, float* dst, size_t n, float scal
                             hif8_stream_t stream);
 hif8_status hif8_decode_bf16(const uint8_t* src, uint16_t* dst, size_t n, float scale,
                              hif8_stream_t stream);
+hif8_status hif8_decode_f16(const uint8_t* src, uint16_t* dst, size_t n, float scale,
+                            hif8_stream_t stream);
 
 /*
  * Fake quantisation (Sec. 4: the paper's simulated HiF8 -- every tensor value is
@@ -142,6 +171,9 @@ hif8_status hif8_fake_quant_f32(const float* src, float* dst, uint8_t* codes_or_
 hif8_status hif8_fake_quant_bf16(const uint16_t* src, uint16_t* dst, uint8_t* codes_or_null,
                                  size_t n, float scale, uint32_t rounding_mode,
                                  hif8_stream_t stream);
+hif8_status hif8_fake_quant_f16(const uint16_t* src, uint16_t* dst, uint8_t* codes_or_null,
+                                size_t n, float scale, uint32_t rounding_mode,
+                                hif8_stream_t stream);
 
 /*
  * Device-state ("_ds") variants: identical to the calls above except that
@@ -161,29 +193,38 @@ hif8_status hif8_encode_f32_ds(const float* src, uint8_t* dst, size_t n, const f
 hif8_status hif8_encode_bf16_ds(const uint16_t* src, uint8_t* dst, size_t n,
                                 const float* d_scale2, float* d_amax_accum_or_null,
                                 uint32_t rounding_mode, hif8_stream_t stream);
+hif8_status hif8_encode_f16_ds(const uint16_t* src, uint8_t* dst, size_t n,
+                               const float* d_scale2, float* d_amax_accum_or_null,
+                               uint32_t rounding_mode, hif8_stream_t stream);
 hif8_status hif8_decode_f32_ds(const uint8_t* src, float* dst, size_t n, const float* d_scale2,
                                hif8_stream_t stream);
 hif8_status hif8_decode_bf16_ds(const uint8_t* src, uint16_t* dst, size_t n,
                                 const float* d_scale2, hif8_stream_t stream);
+hif8_status hif8_decode_f16_ds(const uint8_t* src, uint16_t* dst, size_t n,
+                               const float* d_scale2, hif8_stream_t stream);
 hif8_status hif8_fake_quant_f32_ds(const float* src, float* dst, uint8_t* codes_or_null, size_t n,
                                    const float* d_scale2, float* d_amax_accum_or_null,
                                    uint32_t rounding_mode, hif8_stream_t stream);
 hif8_status hif8_fake_quant_bf16_ds(const uint16_t* src, uint16_t* dst, uint8_t* codes_or_null,
                                     size_t n, const float* d_scale2, float* d_amax_accum_or_null,
                                     uint32_t rounding_mode, hif8_stream_t stream);
+hif8_status hif8_fake_quant_f16_ds(const uint16_t* src, uint16_t* dst, uint8_t* codes_or_null,
+                                   size_t n, const float* d_scale2, float* d_amax_accum_or_null,
+                                   uint32_t rounding_mode, hif8_stream_t stream);
 
 /*
  * Multi-tensor cast: per-tensor amax, scale and encode for a whole list of tensors in four
  * launches (clear, amax, scale, encode) instead of four per tensor -- the per-tensor scaling
  * recipe of Sec. 5 applied to every weight (or activation) tensor of a model at once.
  *
- *   hif8_cast_item   one tensor: src (device, BF16 or FP32, 16-byte aligned), dst (device, n
- *                    u8 codes, 8-byte aligned for BF16 sources, 4-byte for FP32), n elements,
+ *   hif8_cast_item   one tensor: src (device, 16-byte aligned; all items of a list have the
+ *                    same type), dst (device, n u8 codes, 8-byte aligned for BF16 / FP16
+ *                    sources, 4-byte for FP32), n elements,
  *                    first_tile (filled by hif8_multi_plan).
  *   hif8_multi_plan  HOST-side helper: validates a HOST array of items, fills first_tile and
  *                    returns the total tile count.  The caller then copies the array to
  *                    device memory (it may be reused for any number of casts).
- *   hif8_multi_cast_{bf16,f32}
+ *   hif8_multi_cast_{bf16,f16,f32}
  *                    d_items: the planned array in DEVICE memory; d_amax: count device floats
  *                    (output, amax per tensor); d_scale2: 2*count device floats (output,
  *                    {scale, 1/scale} per tensor, as hif8_scale_from_amax); target, pow2 as in
@@ -198,12 +239,15 @@ typedef struct hif8_cast_item {
   uint64_t first_tile;
 } hif8_cast_item;
 
-hif8_status hif8_multi_plan(hif8_cast_item* host_items, size_t count, int src_is_bf16,
+hif8_status hif8_multi_plan(hif8_cast_item* host_items, size_t count, int src_is_16bit,
                             uint64_t* total_tiles_out);
 hif8_status hif8_multi_cast_bf16(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
                                  float* d_amax, float* d_scale2, float target, int pow2,
                                  uint32_t rounding_mode, hif8_stream_t stream);
 hif8_status hif8_multi_cast_f32(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
+                                float* d_amax, float* d_scale2, float target, int pow2,
+                                uint32_t rounding_mode, hif8_stream_t stream);
+hif8_status hif8_multi_cast_f16(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
                                 float* d_amax, float* d_scale2, float target, int pow2,
                                 uint32_t rounding_mode, hif8_stream_t stream);
 

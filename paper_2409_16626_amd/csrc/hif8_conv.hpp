@@ -1,0 +1,747 @@
+// Conversion kernels of libhif8 (HiF8, arXiv 2409.16626) for gfx950, templated on the kind of
+// the high-precision tensor (binary32, bfloat16, binary16), and their host launchers.
+//
+// All kernels are HBM-streaming scans: every lane moves 16 bytes per load, U independent
+// loads are in flight per lane, nothing is read twice.  There is no contraction, hence no MFMA.
+//
+//   encode, TA   : the TA code of a non-NaN binary32 value depends only on its top 13 bits
+//                  (sign, exponent, 3 kept + 1 rounding mantissa bit), so the hot loop is one
+//                  shift and one byte lookup in an 8 KiB table staged in LDS.  The table
+//                  itself is produced on the device, once, by the integer encoder.
+//   encode, HR   : table-driven rounding to the grid (hr_round_bits), then the same byte lookup.
+//                  Simplified SR in every binade is the same kernel with another threshold clamp.
+//   encode, TE   : differs from TA only at exact ties, which need the low 19 bits to be zero;
+//                  a second 8 KiB table holds the TE code of those patterns.
+//   encode, SR   : standard SR (comparison mode): integer encoder with a hashed threshold per element.
+//   decode       : 256-entry binary32 table staged in LDS, one multiply by 1/scale.
+//   fake-quant   : encode and decode fused; the value never leaves registers.
+//   amax         : unsigned max of magnitude patterns; DPP reduction inside a wavefront,
+//                  LDS across wavefronts, one atomic max per workgroup.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+
+#include "hif8.h"
+#include "hif8_conv_api.hpp"
+#include "hif8_device.hpp"
+#include "hif8_host.hpp"
+#include "hif8_stream.hpp"
+
+namespace hif8conv {
+
+using namespace hif8dev;
+using namespace hif8host;
+
+enum : int { IMPL_TA_LUT = 0, IMPL_TA_ALU = 1, IMPL_HR = 2, IMPL_TE = 3, IMPL_SR = 4 };
+
+template <int IMPL>
+constexpr uint32_t lut_bytes() {
+  return IMPL == IMPL_TE ? 16384u : (IMPL == IMPL_TA_ALU || IMPL == IMPL_SR) ? 16u : 8192u;
+}
+template <int SRCK>
+constexpr int vec_elems() { return SRCK == kSrcF32 ? 4 : 8; }  // elements per 16-byte source vector
+template <int SRCK>
+constexpr int vec_shift() { return SRCK == kSrcF32 ? 2 : 3; }
+
+// ------------------------------------------------------------------------------------
+// small device helpers
+// ------------------------------------------------------------------------------------
+struct EncCtx {
+  const uint8_t* lut;  // staged table(s) in LDS
+  const HrExp* hrt;    // staged per-exponent parameters in LDS (IMPL_HR)
+  uint32_t mode;
+  uint64_t seed;       // IMPL_SR
+};
+
+template <int IMPL>
+__device__ __forceinline__ void stage_enc_lut(uint8_t* lut, const uint8_t* __restrict__ g_lut, uint32_t mode) {
+  if (lut_bytes<IMPL>() < 8192u) return;
+  const uint4* g = reinterpret_cast<const uint4*>(g_lut + ((mode & kFlagSat) ? 16384u : 0u));
+  uint4* l = reinterpret_cast<uint4*>(lut);
+  for (uint32_t i = threadIdx.x; i < lut_bytes<IMPL>() / 16u; i += blockDim.x) l[i] = g[i];
+}
+__device__ __forceinline__ void stage_hr_table(HrExp* hrt, uint32_t mode) {
+  const bool ssr = (mode & 0xFu) == kRmSSR;
+  for (uint32_t i = threadIdx.x; i < 256u; i += blockDim.x) hrt[i] = hr_exp_entry(i, ssr);
+}
+__device__ __forceinline__ void stage_dec_lut(uint32_t* lut, const uint32_t* __restrict__ g_dec) {
+  for (uint32_t i = threadIdx.x; i < 256u; i += blockDim.x) lut[i] = g_dec[i];
+}
+
+// One element: scaled pattern -> code.  `elem` is the element's index in the tensor (it
+// selects the threshold of standard SR and is unused otherwise).
+template <int IMPL, int SRCK>
+__device__ __forceinline__ uint32_t encode_one(uint32_t ybits, const EncCtx& c, uint64_t elem) {
+  if constexpr (IMPL == IMPL_TA_ALU) {
+    return encode_alu<false, SRCK>(ybits, c.mode);
+  } else if constexpr (IMPL == IMPL_SR) {
+    return encode_any<SRCK>(ybits, c.mode, sr_threshold(c.seed, elem));
+  } else {
+    uint32_t code;
+    if constexpr (IMPL == IMPL_TA_LUT) {
+      code = c.lut[ybits >> 19];
+    } else if constexpr (IMPL == IMPL_TE) {
+      // a tie needs every bit below the rounding bit to be zero; otherwise TE rounds as TA
+      code = c.lut[(ybits >> 19) + ((ybits & 0x7FFFFu) ? 0u : 8192u)];
+    } else {
+      // HR / SSR: rounding to the grid, then the byte of the (now representable) pattern
+      const uint32_t r = hr_round_bits<SRCK>(ybits, c.hrt[(ybits >> 23) & 0xFFu]);
+      code = c.lut[r >> 19];
+    }
+    // NaNs whose payload sits only in the low 19 bits index the Inf entry; fix them here.
+    if ((ybits & 0x7FFFFFFFu) > 0x7F800000u) code = nan_code(c.mode);
+    return code;
+  }
+}
+
+__device__ __forceinline__ uint32_t scaled_bits(uint32_t xbits, float scale) {
+  return __float_as_uint(__fmul_rn(__uint_as_float(xbits), scale));
+}
+
+// binary32 pattern of the low / high 16-bit half of a dword holding two 16-bit floats
+template <int SRCK>
+__device__ __forceinline__ uint32_t widen_lo(uint32_t w) {
+  if constexpr (SRCK == kSrcBF16) return w << 16;
+  else return __float_as_uint((float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xFFFFu)));
+}
+template <int SRCK>
+__device__ __forceinline__ uint32_t widen_hi(uint32_t w) {
+  if constexpr (SRCK == kSrcBF16) return w & 0xFFFF0000u;
+  else return __float_as_uint((float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16)));
+}
+
+// element i of a tensor as a binary32 pattern
+template <int SRCK>
+__device__ __forceinline__ uint32_t load_bits(const void* src, size_t i) {
+  if constexpr (SRCK == kSrcF32) return __float_as_uint(reinterpret_cast<const float*>(src)[i]);
+  else return widen_lo<SRCK>(reinterpret_cast<const uint16_t*>(src)[i]);
+}
+
+template <int IMPL>
+__device__ __forceinline__ uint32_t encode4_f32(const uint4& v, float scale, const EncCtx& c, uint64_t e0) {
+  const uint32_t c0 = encode_one<IMPL, kSrcF32>(scaled_bits(v.x, scale), c, e0);
+  const uint32_t c1 = encode_one<IMPL, kSrcF32>(scaled_bits(v.y, scale), c, e0 + 1);
+  const uint32_t c2 = encode_one<IMPL, kSrcF32>(scaled_bits(v.z, scale), c, e0 + 2);
+  const uint32_t c3 = encode_one<IMPL, kSrcF32>(scaled_bits(v.w, scale), c, e0 + 3);
+  return c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
+}
+
+// two 16-bit floats in one dword -> two codes in the low 16 bits
+template <int IMPL, int SRCK>
+__device__ __forceinline__ uint32_t encode2_16(uint32_t w, float scale, const EncCtx& c, uint64_t e0) {
+  const uint32_t c0 = encode_one<IMPL, SRCK>(scaled_bits(widen_lo<SRCK>(w), scale), c, e0);
+  const uint32_t c1 = encode_one<IMPL, SRCK>(scaled_bits(widen_hi<SRCK>(w), scale), c, e0 + 1);
+  return c0 | (c1 << 8);
+}
+template <int IMPL, int SRCK>
+__device__ __forceinline__ uint2 encode8_16(const uint4& v, float scale, const EncCtx& c, uint64_t e0) {
+  uint2 o;
+  o.x = encode2_16<IMPL, SRCK>(v.x, scale, c, e0) | (encode2_16<IMPL, SRCK>(v.y, scale, c, e0 + 2) << 16);
+  o.y = encode2_16<IMPL, SRCK>(v.z, scale, c, e0 + 4) | (encode2_16<IMPL, SRCK>(v.w, scale, c, e0 + 6) << 16);
+  return o;
+}
+
+__device__ __forceinline__ uint32_t descale_bits(uint32_t code, const uint32_t* dec, float inv) {
+  return __float_as_uint(__fmul_rn(__uint_as_float(dec[code & 0xFFu]), inv));
+}
+
+// binary32 pattern(s) -> 16-bit float pattern(s), round to nearest even (hardware conversions:
+// v_cvt_pk_bf16_f32 / v_cvt_f16_f32); NaN -> 0x7FC0 / 0x7E00 for the quiet NaN decode produces
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+template <int DSTK>
+__device__ __forceinline__ uint32_t narrow2(uint32_t b0, uint32_t b1) {
+  const f32x2_t f = {__uint_as_float(b0), __uint_as_float(b1)};
+  if constexpr (DSTK == kSrcBF16) return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
+  else return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, f16x2_t));
+}
+template <int DSTK>
+__device__ __forceinline__ uint32_t narrow1(uint32_t b) {
+  if constexpr (DSTK == kSrcBF16) return narrow_bf16(b);
+  else return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)__uint_as_float(b));
+}
+template <int DSTK>
+__device__ __forceinline__ uint32_t descale2_16(uint32_t c0, uint32_t c1, const uint32_t* dec, float inv) {
+  return narrow2<DSTK>(descale_bits(c0, dec, inv), descale_bits(c1, dec, inv));
+}
+template <int DSTK>
+__device__ __forceinline__ uint4 descale8_16(const uint2& w, const uint32_t* dec, float inv) {
+  uint4 o;
+  o.x = descale2_16<DSTK>(w.x, w.x >> 8, dec, inv);
+  o.y = descale2_16<DSTK>(w.x >> 16, w.x >> 24, dec, inv);
+  o.z = descale2_16<DSTK>(w.y, w.y >> 8, dec, inv);
+  o.w = descale2_16<DSTK>(w.y >> 16, w.y >> 24, dec, inv);
+  return o;
+}
+__device__ __forceinline__ uint4 descale4_f32(uint32_t w, const uint32_t* dec, float inv) {
+  uint4 o;
+  o.x = descale_bits(w, dec, inv);
+  o.y = descale_bits(w >> 8, dec, inv);
+  o.z = descale_bits(w >> 16, dec, inv);
+  o.w = descale_bits(w >> 24, dec, inv);
+  return o;
+}
+
+// running magnitude maximum of one 16-byte vector: binary32 -> magnitude pattern; 16-bit
+// floats -> two 15-bit magnitudes, one per 16-bit half (folded by fold_amax at the end; the
+// magnitude patterns of bfloat16 and of binary16 both order like the values)
+typedef uint16_t u16x2_t __attribute__((ext_vector_type(2)));
+template <int SRCK>
+__device__ __forceinline__ uint32_t vec_amax(uint32_t m, const uint4& v) {
+  if constexpr (SRCK == kSrcF32) {
+    return umax(m, umax(umax(v.x & 0x7FFFFFFFu, v.y & 0x7FFFFFFFu),
+                        umax(v.z & 0x7FFFFFFFu, v.w & 0x7FFFFFFFu)));
+  } else {
+    u16x2_t mm = __builtin_bit_cast(u16x2_t, m);
+    mm = __builtin_elementwise_max(mm, __builtin_bit_cast(u16x2_t, v.x & 0x7FFF7FFFu));
+    mm = __builtin_elementwise_max(mm, __builtin_bit_cast(u16x2_t, v.y & 0x7FFF7FFFu));
+    mm = __builtin_elementwise_max(mm, __builtin_bit_cast(u16x2_t, v.z & 0x7FFF7FFFu));
+    mm = __builtin_elementwise_max(mm, __builtin_bit_cast(u16x2_t, v.w & 0x7FFF7FFFu));
+    return __builtin_bit_cast(uint32_t, mm);
+  }
+}
+// running maximum -> binary32 magnitude pattern
+template <int SRCK>
+__device__ __forceinline__ uint32_t fold_amax(uint32_t m) {
+  if constexpr (SRCK == kSrcF32) return m;
+  else return widen_lo<SRCK>(umax(m & 0xFFFFu, m >> 16));
+}
+
+// ------------------------------------------------------------------------------------
+// streaming kernels.  The ragged tail (n modulo the vector width) is done element-wise by
+// workgroup 0.
+// ------------------------------------------------------------------------------------
+template <int U, int IMPL, int SRCK>
+__global__ void __launch_bounds__(1024)
+k_encode(const void* __restrict__ src, uint8_t* __restrict__ dst, size_t n, float scale_arg,
+         const float* __restrict__ d_scale2, uint32_t* __restrict__ amax_acc, uint32_t mode,
+         uint64_t seed, const uint8_t* __restrict__ g_lut, Walk walk) {
+  __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
+  __shared__ __attribute__((aligned(8))) HrExp hrt[IMPL == IMPL_HR ? 256 : 1];
+  const EncCtx ctx{lut, hrt, mode, seed};
+  const float scale = d_scale2 ? d_scale2[0] : scale_arg;
+  const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(src);
+  constexpr int VE = vec_elems<SRCK>();
+  const size_t nvec = n >> vec_shift<SRCK>();
+  uint32_t m = 0;  // amax of the unscaled input, only tracked when amax_acc != nullptr
+  tile_loop<U, uint4>(
+      nvec, walk, [&](size_t idx) { return ld_stream(src4 + idx); },
+      [&](size_t idx, const uint4& v) {
+        if (amax_acc) m = vec_amax<SRCK>(m, v);
+        if constexpr (SRCK == kSrcF32)
+          st_stream(reinterpret_cast<uint32_t*>(dst) + idx, encode4_f32<IMPL>(v, scale, ctx, idx * VE));
+        else
+          st_stream(reinterpret_cast<uint2*>(dst) + idx, encode8_16<IMPL, SRCK>(v, scale, ctx, idx * VE));
+      },
+      [&]() {
+        if (IMPL != IMPL_TA_ALU && IMPL != IMPL_SR) {
+          stage_enc_lut<IMPL>(lut, g_lut, mode);
+          if (IMPL == IMPL_HR) stage_hr_table(hrt, mode);
+          __syncthreads();
+        }
+      });
+  const size_t t = nvec * VE + threadIdx.x;
+  m = fold_amax<SRCK>(m);
+  if (blockIdx.x == 0 && t < n) {
+    const uint32_t xb = load_bits<SRCK>(src, t);
+    m = umax(m, xb & 0x7FFFFFFFu);
+    dst[t] = (uint8_t)encode_one<IMPL, SRCK>(scaled_bits(xb, scale), ctx, t);
+  }
+  if (amax_acc) block_max_to_global(m, amax_acc);
+}
+
+template <int U, int DSTK>
+__global__ void __launch_bounds__(1024)
+k_decode(const uint8_t* __restrict__ src, void* __restrict__ dst, size_t n, float inv_arg,
+         const float* __restrict__ d_scale2, const uint32_t* __restrict__ g_dec, Walk walk) {
+  __shared__ uint32_t dec[256];
+  const float inv = d_scale2 ? d_scale2[1] : inv_arg;  // fl32(1/scale)
+  constexpr int VE = vec_elems<DSTK>();
+  const size_t nvec = n >> vec_shift<DSTK>();
+  uint4* __restrict__ dst4 = reinterpret_cast<uint4*>(dst);
+  auto prologue = [&]() {
+    stage_dec_lut(dec, g_dec);
+    __syncthreads();
+  };
+  if constexpr (DSTK == kSrcF32) {
+    const uint32_t* __restrict__ s4 = reinterpret_cast<const uint32_t*>(src);
+    tile_loop<U, uint32_t>(
+        nvec, walk, [&](size_t idx) { return ld_stream(s4 + idx); },
+        [&](size_t idx, uint32_t w) { st_stream(dst4 + idx, descale4_f32(w, dec, inv)); }, prologue);
+  } else {
+    const uint2* __restrict__ s8 = reinterpret_cast<const uint2*>(src);
+    tile_loop<U, uint2>(
+        nvec, walk, [&](size_t idx) { return ld_stream(s8 + idx); },
+        [&](size_t idx, const uint2& w) { st_stream(dst4 + idx, descale8_16<DSTK>(w, dec, inv)); }, prologue);
+  }
+  const size_t t = nvec * VE + threadIdx.x;
+  if (blockIdx.x == 0 && t < n) {
+    const uint32_t b = descale_bits(src[t], dec, inv);
+    if constexpr (DSTK == kSrcF32) reinterpret_cast<uint32_t*>(dst)[t] = b;
+    else reinterpret_cast<uint16_t*>(dst)[t] = (uint16_t)narrow1<DSTK>(b);
+  }
+}
+
+// fake-quant: src and dst may alias (each lane reads its own vectors before it writes them)
+template <int U, int IMPL, bool CODES, int SRCK>
+__global__ void __launch_bounds__(1024)
+k_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, float scale_arg, float inv_arg,
+             const float* __restrict__ d_scale2, uint32_t* amax_acc, uint32_t mode, uint64_t seed,
+             const uint8_t* __restrict__ g_lut, const uint32_t* __restrict__ g_dec, Walk walk) {
+  __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
+  __shared__ __attribute__((aligned(8))) HrExp hrt[IMPL == IMPL_HR ? 256 : 1];
+  __shared__ uint32_t dec[256];
+  const EncCtx ctx{lut, hrt, mode, seed};
+  const float scale = d_scale2 ? d_scale2[0] : scale_arg;
+  const float inv = d_scale2 ? d_scale2[1] : inv_arg;
+  auto prologue = [&]() {
+    stage_enc_lut<IMPL>(lut, g_lut, mode);
+    if (IMPL == IMPL_HR) stage_hr_table(hrt, mode);
+    stage_dec_lut(dec, g_dec);
+    __syncthreads();
+  };
+  const uint4* src4 = reinterpret_cast<const uint4*>(src);
+  uint4* dst4 = reinterpret_cast<uint4*>(dst);
+  constexpr int VE = vec_elems<SRCK>();
+  const size_t nvec = n >> vec_shift<SRCK>();
+  uint32_t m = 0;
+  tile_loop<U, uint4>(
+      nvec, walk, [&](size_t idx) { return ld_stream(src4 + idx); },
+      [&](size_t idx, const uint4& v) {
+        if (amax_acc) m = vec_amax<SRCK>(m, v);
+        if constexpr (SRCK == kSrcF32) {
+          const uint32_t w = encode4_f32<IMPL>(v, scale, ctx, idx * VE);
+          st_stream(dst4 + idx, descale4_f32(w, dec, inv));
+          if (CODES) st_stream(reinterpret_cast<uint32_t*>(codes) + idx, w);
+        } else {
+          const uint2 w = encode8_16<IMPL, SRCK>(v, scale, ctx, idx * VE);
+          st_stream(dst4 + idx, descale8_16<SRCK>(w, dec, inv));
+          if (CODES) st_stream(reinterpret_cast<uint2*>(codes) + idx, w);
+        }
+      },
+      prologue);
+  const size_t t = nvec * VE + threadIdx.x;
+  m = fold_amax<SRCK>(m);
+  if (blockIdx.x == 0 && t < n) {
+    const uint32_t xb = load_bits<SRCK>(src, t);
+    m = umax(m, xb & 0x7FFFFFFFu);
+    const uint32_t c = encode_one<IMPL, SRCK>(scaled_bits(xb, scale), ctx, t);
+    const uint32_t b = descale_bits(c, dec, inv);
+    if constexpr (SRCK == kSrcF32) reinterpret_cast<uint32_t*>(dst)[t] = b;
+    else reinterpret_cast<uint16_t*>(dst)[t] = (uint16_t)narrow1<SRCK>(b);
+    if (CODES) codes[t] = (uint8_t)c;
+  }
+  if (amax_acc) block_max_to_global(m, amax_acc);
+}
+
+// ------------------------------------------------------------------------------------
+// element-per-lane kernels for pointers that do not meet the fast path's alignment
+// (integer encoder, any rounding method)
+// ------------------------------------------------------------------------------------
+template <int SRCK>
+__global__ void __launch_bounds__(256)
+k_encode_elem(const void* src, uint8_t* dst, size_t n, float scale_arg, const float* d_scale2,
+              uint32_t* amax_acc, uint32_t mode, uint64_t seed) {
+  const float scale = d_scale2 ? d_scale2[0] : scale_arg;
+  uint32_t m = 0;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x) {
+    const uint32_t xb = load_bits<SRCK>(src, i);
+    m = umax(m, xb & 0x7FFFFFFFu);
+    dst[i] = (uint8_t)encode_any<SRCK>(scaled_bits(xb, scale), mode, sr_threshold(seed, i));
+  }
+  if (amax_acc) block_max_to_global(m, amax_acc);
+}
+
+template <int DSTK>
+__global__ void __launch_bounds__(256)
+k_decode_elem(const uint8_t* src, void* dst, size_t n, float inv_arg, const float* d_scale2) {
+  const float inv = d_scale2 ? d_scale2[1] : inv_arg;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x) {
+    const uint32_t b = __float_as_uint(__fmul_rn(__uint_as_float(decode_bits(src[i])), inv));
+    if constexpr (DSTK == kSrcF32) reinterpret_cast<uint32_t*>(dst)[i] = b;
+    else reinterpret_cast<uint16_t*>(dst)[i] = (uint16_t)narrow1<DSTK>(b);
+  }
+}
+
+template <int SRCK>
+__global__ void __launch_bounds__(256)
+k_fake_quant_elem(const void* src, void* dst, uint8_t* codes, size_t n, float scale_arg,
+                  float inv_arg, const float* d_scale2, uint32_t* amax_acc, uint32_t mode,
+                  uint64_t seed) {
+  const float scale = d_scale2 ? d_scale2[0] : scale_arg;
+  const float inv = d_scale2 ? d_scale2[1] : inv_arg;
+  uint32_t m = 0;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x) {
+    const uint32_t xb = load_bits<SRCK>(src, i);
+    m = umax(m, xb & 0x7FFFFFFFu);
+    const uint32_t c = encode_any<SRCK>(scaled_bits(xb, scale), mode, sr_threshold(seed, i));
+    const uint32_t b = __float_as_uint(__fmul_rn(__uint_as_float(decode_bits(c)), inv));
+    if constexpr (SRCK == kSrcF32) reinterpret_cast<uint32_t*>(dst)[i] = b;
+    else reinterpret_cast<uint16_t*>(dst)[i] = (uint16_t)narrow1<SRCK>(b);
+    if (codes) codes[i] = (uint8_t)c;
+  }
+  if (amax_acc) block_max_to_global(m, amax_acc);
+}
+
+// ------------------------------------------------------------------------------------
+// amax (magnitude patterns as binary32 bits)
+// ------------------------------------------------------------------------------------
+template <int U, int SRCK, bool NT>
+__global__ void __launch_bounds__(1024)
+k_amax(const void* __restrict__ src, size_t n, uint32_t* __restrict__ out, Walk walk) {
+  const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(src);
+  const size_t nvec = n >> vec_shift<SRCK>();
+  uint32_t m = 0;
+  tile_loop<U, uint4>(
+      nvec, walk, [&](size_t idx) { return NT ? ld_stream(src4 + idx) : src4[idx]; },
+      [&](size_t, const uint4& v) { m = vec_amax<SRCK>(m, v); }, []() {});
+  m = fold_amax<SRCK>(m);
+  const size_t t = nvec * vec_elems<SRCK>() + threadIdx.x;
+  if (blockIdx.x == 0 && t < n) m = umax(m, load_bits<SRCK>(src, t) & 0x7FFFFFFFu);
+  block_max_to_global(m, out);
+}
+
+template <int SRCK>
+__global__ void __launch_bounds__(256)
+k_amax_elem(const void* __restrict__ src, size_t n, uint32_t* __restrict__ out) {
+  uint32_t m = 0;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x)
+    m = umax(m, load_bits<SRCK>(src, i) & 0x7FFFFFFFu);
+  block_max_to_global(m, out);
+}
+
+// ------------------------------------------------------------------------------------
+// multi-tensor cast: many tensors per launch (amax, then scale, then encode), so that a
+// list of small tensors is not bound by launch gaps.  All tensors share one global tile
+// index space; items[i].first_tile is the prefix sum of tile counts.  A tile is
+// kMultiBlock * kMultiUnroll vector units of one tensor.
+// ------------------------------------------------------------------------------------
+constexpr uint32_t kMultiTpwEncode = 2;
+constexpr uint32_t kMultiTpwAmax = 8;
+
+// largest i with items[i].first_tile <= tile (zero-size items are skipped by construction)
+__device__ __forceinline__ uint32_t multi_find_item(const hif8_cast_item* __restrict__ items,
+                                                    uint32_t count, uint64_t tile) {
+  uint32_t lo = 0, hi = count;
+  while (hi - lo > 1u) {
+    const uint32_t mid = (lo + hi) >> 1;
+    if (items[mid].first_tile <= tile) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+template <int SRCK>
+__device__ __forceinline__ uint64_t multi_item_tiles(uint64_t n) {
+  const uint64_t nvec = n >> vec_shift<SRCK>();
+  const uint64_t t = (nvec + kMultiTileVec - 1) / kMultiTileVec;
+  return (t == 0 && n != 0) ? 1 : t;
+}
+
+template <int SRCK>
+__global__ void __launch_bounds__(kMultiBlock)
+k_multi_amax(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_t total_tiles,
+             uint32_t* __restrict__ amax_out) {
+  uint32_t m = 0;     // vector part, in the packed form of vec_amax
+  uint32_t mt = 0;    // ragged-tail part, binary32 magnitude pattern
+  uint32_t cur = 0xFFFFFFFFu;
+  for (uint32_t i = 0; i < kMultiTpwAmax; ++i) {
+    const uint64_t tile = (uint64_t)blockIdx.x * kMultiTpwAmax + i;
+    if (tile >= total_tiles) break;
+    const uint32_t it = multi_find_item(items, count, tile);
+    if (it != cur) {
+      if (cur != 0xFFFFFFFFu) {
+        block_max_to_global(umax(fold_amax<SRCK>(m), mt), amax_out + cur);
+        __syncthreads();
+      }
+      cur = it;
+      m = 0;
+      mt = 0;
+    }
+    const uint64_t n = items[it].n;
+    const uint64_t nvec = n >> vec_shift<SRCK>();
+    const uint64_t local = tile - items[it].first_tile;
+    const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(items[it].src);
+    const uint64_t first = local * kMultiTileVec + threadIdx.x;
+    uint4 v[kMultiUnroll];
+#pragma unroll
+    for (int j = 0; j < kMultiUnroll; ++j) {
+      const uint64_t idx = first + (uint64_t)j * kMultiBlock;
+      v[j] = (idx < nvec) ? ld_stream(src4 + idx) : make_uint4(0u, 0u, 0u, 0u);
+    }
+#pragma unroll
+    for (int j = 0; j < kMultiUnroll; ++j) m = vec_amax<SRCK>(m, v[j]);
+    // ragged tail of the tensor, done with its last tile
+    if (local + 1 == multi_item_tiles<SRCK>(n)) {
+      const uint64_t t = nvec * vec_elems<SRCK>() + threadIdx.x;
+      if (t < n) mt = umax(mt, load_bits<SRCK>(items[it].src, t) & 0x7FFFFFFFu);
+    }
+  }
+  if (cur != 0xFFFFFFFFu) block_max_to_global(umax(fold_amax<SRCK>(m), mt), amax_out + cur);
+}
+
+template <int IMPL, int SRCK>
+__global__ void __launch_bounds__(kMultiBlock)
+k_multi_encode(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_t total_tiles,
+               const float* __restrict__ d_scale2, uint32_t mode, uint64_t seed,
+               const uint8_t* __restrict__ g_lut) {
+  __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
+  __shared__ __attribute__((aligned(8))) HrExp hrt[IMPL == IMPL_HR ? 256 : 1];
+  const EncCtx ctx{lut, hrt, mode, seed};
+  stage_enc_lut<IMPL>(lut, g_lut, mode);
+  if (IMPL == IMPL_HR) stage_hr_table(hrt, mode);
+  __syncthreads();
+  constexpr int VE = vec_elems<SRCK>();
+  for (uint32_t i = 0; i < kMultiTpwEncode; ++i) {
+    const uint64_t tile = (uint64_t)blockIdx.x * kMultiTpwEncode + i;
+    if (tile >= total_tiles) break;
+    const uint32_t it = multi_find_item(items, count, tile);
+    const uint64_t n = items[it].n;
+    const uint64_t nvec = n >> vec_shift<SRCK>();
+    const uint64_t local = tile - items[it].first_tile;
+    const float scale = d_scale2[2 * it];
+    const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(items[it].src);
+    uint8_t* __restrict__ dst = items[it].dst;
+    const uint64_t first = local * kMultiTileVec + threadIdx.x;
+    uint4 v[kMultiUnroll];
+#pragma unroll
+    for (int j = 0; j < kMultiUnroll; ++j) {
+      const uint64_t idx = first + (uint64_t)j * kMultiBlock;
+      if (idx < nvec) v[j] = ld_stream(src4 + idx);
+    }
+#pragma unroll
+    for (int j = 0; j < kMultiUnroll; ++j) {
+      const uint64_t idx = first + (uint64_t)j * kMultiBlock;
+      if (idx < nvec) {
+        if constexpr (SRCK == kSrcF32)
+          st_stream(reinterpret_cast<uint32_t*>(dst) + idx, encode4_f32<IMPL>(v[j], scale, ctx, idx * VE));
+        else
+          st_stream(reinterpret_cast<uint2*>(dst) + idx, encode8_16<IMPL, SRCK>(v[j], scale, ctx, idx * VE));
+      }
+    }
+    if (local + 1 == multi_item_tiles<SRCK>(n)) {
+      const uint64_t t = nvec * VE + threadIdx.x;
+      if (t < n)
+        dst[t] = (uint8_t)encode_one<IMPL, SRCK>(scaled_bits(load_bits<SRCK>(items[it].src, t), scale), ctx, t);
+    }
+  }
+}
+
+// ====================================================================================
+// host side
+// ====================================================================================
+inline int impl_for(uint32_t mode) {
+  switch (mode & HIF8_RM_MASK) {
+    case HIF8_RM_HR:
+    case HIF8_RM_SSR: return IMPL_HR;
+    case HIF8_RM_TE: return IMPL_TE;
+    case HIF8_RM_SR: return IMPL_SR;
+    default: return tune_ta_impl() ? IMPL_TA_ALU : IMPL_TA_LUT;
+  }
+}
+
+// Calls f(integral_constant IMPL, integral_constant U).  The comparison modes TE and SR are
+// built for one unroll factor only.
+template <typename F>
+inline void dispatch_impl(int impl, int unroll, F&& f) {
+  using std::integral_constant;
+  switch (impl) {
+    case IMPL_TA_ALU: dispatch_unroll(unroll, [&](auto u) { f(integral_constant<int, IMPL_TA_ALU>{}, u); }); break;
+    case IMPL_HR: dispatch_unroll(unroll, [&](auto u) { f(integral_constant<int, IMPL_HR>{}, u); }); break;
+    case IMPL_TE: f(integral_constant<int, IMPL_TE>{}, integral_constant<int, 2>{}); break;
+    case IMPL_SR: f(integral_constant<int, IMPL_SR>{}, integral_constant<int, 2>{}); break;
+    default: dispatch_unroll(unroll, [&](auto u) { f(integral_constant<int, IMPL_TA_LUT>{}, u); }); break;
+  }
+}
+
+template <int SRCK>
+hif8_status conv_encode(const void* src, uint8_t* dst, size_t n, float scale, const float* d_scale2,
+                        float* d_amax_acc, uint32_t mode, hipStream_t st) {
+  uint32_t* amax_acc = reinterpret_cast<uint32_t*>(d_amax_acc);
+  if (!valid_mode(mode)) return HIF8_ERR_MODE;
+  float inv = 1.0f;
+  if (!d_scale2 && !valid_scale(scale, &inv)) return HIF8_ERR_SCALE;
+  if (n == 0) return HIF8_OK;
+  if (!src || !dst) return HIF8_ERR_NULL;
+  int cus = 0;
+  DevTables tb;
+  hif8_status s = ensure_init(&cus, &tb);
+  if (s != HIF8_OK) return s;
+  const uint64_t seed = sr_seed();
+  const bool fast = aligned_to(src, 16) && aligned_to(dst, SRCK == kSrcF32 ? 4 : 8);
+  if (!fast) {
+    hipLaunchKernelGGL(k_encode_elem<SRCK>, dim3(grid_elem(n, cus)), dim3(256), 0, st, src, dst, n,
+                       scale, d_scale2, amax_acc, mode, seed);
+    return finish_launch();
+  }
+  const size_t nvec = n >> vec_shift<SRCK>();
+  const int impl = impl_for(mode);
+  Shape shape = shape_for(SRCK != kSrcF32 ? FAM_ENC16 : (impl == IMPL_HR ? FAM_ENC32_HR : FAM_ENC32_TA));
+  if (impl == IMPL_TE || impl == IMPL_SR) shape.unroll = 2;
+  Walk walk;
+  const dim3 grid(grid_for(nvec, cus, shape, &walk)), block(shape.block);
+  dispatch_impl(impl, shape.unroll, [&](auto impl_c, auto u_c) {
+    hipLaunchKernelGGL((k_encode<decltype(u_c)::value, decltype(impl_c)::value, SRCK>), grid, block, 0, st, src,
+                       dst, n, scale, d_scale2, amax_acc, mode, seed, tb.enc_lut, walk);
+  });
+  return finish_launch();
+}
+
+template <int DSTK>
+hif8_status conv_decode(const uint8_t* src, void* dst, size_t n, float scale, const float* d_scale2,
+                        hipStream_t st) {
+  float inv = 1.0f;
+  if (!d_scale2 && !valid_scale(scale, &inv)) return HIF8_ERR_SCALE;
+  if (n == 0) return HIF8_OK;
+  if (!src || !dst) return HIF8_ERR_NULL;
+  int cus = 0;
+  DevTables tb;
+  hif8_status s = ensure_init(&cus, &tb);
+  if (s != HIF8_OK) return s;
+  const bool fast = aligned_to(src, DSTK == kSrcF32 ? 4 : 8) && aligned_to(dst, 16);
+  if (!fast) {
+    hipLaunchKernelGGL(k_decode_elem<DSTK>, dim3(grid_elem(n, cus)), dim3(256), 0, st, src, dst, n,
+                       inv, d_scale2);
+    return finish_launch();
+  }
+  const size_t nvec = n >> vec_shift<DSTK>();
+  const Shape shape = shape_for(FAM_DEC);
+  Walk walk;
+  const dim3 grid(grid_for(nvec, cus, shape, &walk)), block(shape.block);
+  dispatch_unroll(shape.unroll, [&](auto u_c) {
+    hipLaunchKernelGGL((k_decode<decltype(u_c)::value, DSTK>), grid, block, 0, st, src, dst, n, inv, d_scale2,
+                       tb.dec_lut, walk);
+  });
+  return finish_launch();
+}
+
+template <int SRCK>
+hif8_status conv_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, float scale,
+                            const float* d_scale2, float* d_amax_acc, uint32_t mode, hipStream_t st) {
+  uint32_t* amax_acc = reinterpret_cast<uint32_t*>(d_amax_acc);
+  if (!valid_mode(mode)) return HIF8_ERR_MODE;
+  float inv = 1.0f;
+  if (!d_scale2 && !valid_scale(scale, &inv)) return HIF8_ERR_SCALE;
+  if (n == 0) return HIF8_OK;
+  if (!src || !dst) return HIF8_ERR_NULL;
+  int cus = 0;
+  DevTables tb;
+  hif8_status s = ensure_init(&cus, &tb);
+  if (s != HIF8_OK) return s;
+  const uint64_t seed = sr_seed();
+  const bool fast = aligned_to(src, 16) && aligned_to(dst, 16) &&
+                    (!codes || aligned_to(codes, SRCK == kSrcF32 ? 4 : 8));
+  if (!fast) {
+    hipLaunchKernelGGL(k_fake_quant_elem<SRCK>, dim3(grid_elem(n, cus)), dim3(256), 0, st, src, dst,
+                       codes, n, scale, inv, d_scale2, amax_acc, mode, seed);
+    return finish_launch();
+  }
+  const size_t nvec = n >> vec_shift<SRCK>();
+  const int impl = impl_for(mode);
+  Shape shape = shape_for(FAM_FQ);
+  if (impl == IMPL_TE || impl == IMPL_SR) shape.unroll = 2;
+  Walk walk;
+  const dim3 grid(grid_for(nvec, cus, shape, &walk)), block(shape.block);
+  dispatch_impl(impl, shape.unroll, [&](auto impl_c, auto u_c) {
+    constexpr int U = decltype(u_c)::value, IMPL = decltype(impl_c)::value;
+    if (codes)
+      hipLaunchKernelGGL((k_fake_quant<U, IMPL, true, SRCK>), grid, block, 0, st, src, dst, codes, n, scale, inv,
+                         d_scale2, amax_acc, mode, seed, tb.enc_lut, tb.dec_lut, walk);
+    else
+      hipLaunchKernelGGL((k_fake_quant<U, IMPL, false, SRCK>), grid, block, 0, st, src, dst, codes, n, scale, inv,
+                         d_scale2, amax_acc, mode, seed, tb.enc_lut, tb.dec_lut, walk);
+  });
+  return finish_launch();
+}
+
+template <int SRCK>
+hif8_status conv_amax(const void* src, size_t n, float* d_amax, hipStream_t st) {
+  if (!d_amax || (!src && n != 0)) return HIF8_ERR_NULL;
+  int cus = 0;
+  hif8_status s = ensure_init(&cus, nullptr);
+  if (s != HIF8_OK) return s;
+  uint32_t* out = reinterpret_cast<uint32_t*>(d_amax);
+  s = launch_fill_u32(out, 0u, 1u, st);
+  if (s != HIF8_OK) return s;
+  if (n == 0) return HIF8_OK;
+  if (!aligned_to(src, 16)) {
+    hipLaunchKernelGGL(k_amax_elem<SRCK>, dim3(grid_elem(n, cus)), dim3(256), 0, st, src, n, out);
+    return finish_launch();
+  }
+  const size_t nvec = n >> vec_shift<SRCK>();
+  const Shape shape = shape_for(FAM_AMAX);
+  Walk walk;
+  const dim3 grid(grid_for(nvec, cus, shape, &walk)), block(shape.block);
+  const bool nt = tune_amax_nt() != 0;
+  dispatch_unroll(shape.unroll, [&](auto u_c) {
+    constexpr int U = decltype(u_c)::value;
+    if (nt) hipLaunchKernelGGL((k_amax<U, SRCK, true>), grid, block, 0, st, src, n, out, walk);
+    else hipLaunchKernelGGL((k_amax<U, SRCK, false>), grid, block, 0, st, src, n, out, walk);
+  });
+  return finish_launch();
+}
+
+template <int SRCK>
+hif8_status conv_multi_cast(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
+                            float* d_amax, float* d_scale2, float target, int pow2, uint32_t mode,
+                            hipStream_t st) {
+  if (!valid_mode(mode)) return HIF8_ERR_MODE;
+  if (!(target > 0.0f) || std::isinf(target)) return HIF8_ERR_ARG;
+  if (count == 0) return HIF8_OK;
+  if (!d_items || !d_amax || !d_scale2) return HIF8_ERR_NULL;
+  if (count > 0xFFFFFFu) return HIF8_ERR_ARG;
+  DevTables tb;
+  hif8_status s = ensure_init(nullptr, &tb);
+  if (s != HIF8_OK) return s;
+  const uint64_t seed = sr_seed();
+  const uint32_t cnt = (uint32_t)count;
+  uint32_t* am = reinterpret_cast<uint32_t*>(d_amax);
+  s = launch_fill_u32(am, 0u, cnt, st);
+  if (s != HIF8_OK) return s;
+  if (total_tiles != 0) {
+    const unsigned g1 = (unsigned)((total_tiles + kMultiTpwAmax - 1) / kMultiTpwAmax);
+    hipLaunchKernelGGL(k_multi_amax<SRCK>, dim3(g1), dim3(kMultiBlock), 0, st, d_items, cnt, total_tiles, am);
+  }
+  s = launch_scale_from_amax(d_amax, d_scale2, cnt, target, pow2, st);
+  if (s != HIF8_OK) return s;
+  if (total_tiles != 0) {
+    const dim3 g2((unsigned)((total_tiles + kMultiTpwEncode - 1) / kMultiTpwEncode)), blk(kMultiBlock);
+    switch (impl_for(mode)) {
+      case IMPL_HR:
+        hipLaunchKernelGGL((k_multi_encode<IMPL_HR, SRCK>), g2, blk, 0, st, d_items, cnt, total_tiles, d_scale2, mode, seed, tb.enc_lut);
+        break;
+      case IMPL_TE:
+        hipLaunchKernelGGL((k_multi_encode<IMPL_TE, SRCK>), g2, blk, 0, st, d_items, cnt, total_tiles, d_scale2, mode, seed, tb.enc_lut);
+        break;
+      case IMPL_SR:
+        hipLaunchKernelGGL((k_multi_encode<IMPL_SR, SRCK>), g2, blk, 0, st, d_items, cnt, total_tiles, d_scale2, mode, seed, tb.enc_lut);
+        break;
+      default:
+        hipLaunchKernelGGL((k_multi_encode<IMPL_TA_LUT, SRCK>), g2, blk, 0, st, d_items, cnt, total_tiles, d_scale2, mode, seed, tb.enc_lut);
+        break;
+    }
+  }
+  return finish_launch();
+}
+
+}  // namespace hif8conv
+
+// explicit instantiation of every host entry point for one kind
+#define HIF8_INSTANTIATE_CONV(K)                                                                         \
+  namespace hif8conv {                                                                                   \
+  template hif8_status conv_encode<K>(const void*, uint8_t*, size_t, float, const float*, float*,        \
+                                      uint32_t, hipStream_t);                                            \
+  template hif8_status conv_decode<K>(const uint8_t*, void*, size_t, float, const float*, hipStream_t);  \
+  template hif8_status conv_fake_quant<K>(const void*, void*, uint8_t*, size_t, float, const float*,     \
+                                          float*, uint32_t, hipStream_t);                                \
+  template hif8_status conv_amax<K>(const void*, size_t, float*, hipStream_t);                           \
+  template hif8_status conv_multi_cast<K>(const hif8_cast_item*, size_t, uint64_t, float*, float*,       \
+                                          float, int, uint32_t, hipStream_t);                            \
+  }

@@ -1,0 +1,36 @@
+// Host entry points of the conversion kernels, one instantiation per source / destination
+// kind (hif8dev::kSrcF32, kSrcBF16, kSrcF16).  Defined in hif8_conv.hpp and instantiated in
+// hif8_conv_f32.hip, hif8_conv_bf16.hip and hif8_conv_f16.hip; called by the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "hif8.h"
+
+namespace hif8conv {
+
+// scale by value (d_scale2 == nullptr) or from device memory {scale, 1/scale}
+template <int SRCK>
+hif8_status conv_encode(const void* src, uint8_t* dst, size_t n, float scale, const float* d_scale2,
+                        float* d_amax_acc, uint32_t mode, hipStream_t st);
+template <int DSTK>
+hif8_status conv_decode(const uint8_t* src, void* dst, size_t n, float scale, const float* d_scale2,
+                        hipStream_t st);
+template <int SRCK>
+hif8_status conv_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, float scale,
+                            const float* d_scale2, float* d_amax_acc, uint32_t mode, hipStream_t st);
+template <int SRCK>
+hif8_status conv_amax(const void* src, size_t n, float* d_amax, hipStream_t st);
+template <int SRCK>
+hif8_status conv_multi_cast(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
+                            float* d_amax, float* d_scale2, float target, int pow2, uint32_t mode,
+                            hipStream_t st);
+
+// vector units per tile of the multi-tensor kernels (shared with hif8_multi_plan)
+constexpr int kMultiBlock = 512;
+constexpr int kMultiUnroll = 2;
+constexpr uint32_t kMultiTileVec = kMultiBlock * kMultiUnroll;
+
+}  // namespace hif8conv

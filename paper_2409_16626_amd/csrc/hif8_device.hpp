@@ -140,11 +140,11 @@ __device__ __forceinline__ uint32_t encode_alu(uint32_t ybits, uint32_t mode) {
 
 // 32-bit threshold of element `index` under `seed`: two rounds of MurmurHash3's 32-bit
 // finaliser, first over the low words, then folding in the high words.
-__device__ __forceinline__ uint32_t fmix32(uint32_t x) {
+__host__ __device__ __forceinline__ uint32_t fmix32(uint32_t x) {
   x ^= x >> 16; x *= 0x85EBCA6Bu; x ^= x >> 13; x *= 0xC2B2AE35u; x ^= x >> 16;
   return x;
 }
-__device__ __forceinline__ uint32_t sr_threshold(uint64_t seed, uint64_t index) {
+__host__ __device__ __forceinline__ uint32_t sr_threshold(uint64_t seed, uint64_t index) {
   uint32_t x = fmix32((uint32_t)index ^ (uint32_t)seed);
   x += (uint32_t)(index >> 32) * 0x9E3779B9u + (uint32_t)(seed >> 32);
   return fmix32(x);

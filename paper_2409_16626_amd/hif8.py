@@ -2,7 +2,7 @@
 
 Argument marshalling only -- every step of the conversion runs in the HIP kernels.
 Data arguments are torch tensors living on the GPU (or raw integer device pointers);
-bfloat16 tensors may be passed as torch.bfloat16 or as int16/uint16 views.  The HIP
+bfloat16 / float16 tensors may be passed as such or as int16/uint16 views.  The HIP
 stream defaults to torch's current stream.  There is no CPU fallback: if the library
 is missing or a call fails, an exception is raised.
 """
@@ -15,6 +15,9 @@ from . import build as _build
 
 RM_TA = 0
 RM_HR = 1
+RM_TE = 2    # comparison modes (described by the paper, not adopted by the format)
+RM_SSR = 3
+RM_SR = 4
 FLAG_SAT = 0x10
 FLAG_NAN2ZERO = 0x20
 MAX_FINITE = 32768.0
@@ -44,11 +47,23 @@ def _load():
 lib = _load()
 
 _vp, _sz, _f, _u32, _i = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float, ctypes.c_uint32, ctypes.c_int
+_u64 = ctypes.c_uint64
 
 _SIGS = {
     "hif8_version": ([], _i),
     "hif8_last_hip_error": ([], _i),
     "hif8_init": ([], _i),
+    "hif8_set_sr_seed": ([_u64], _i),
+    "hif8_get_sr_seed": ([], _u64),
+    "hif8_sr_threshold": ([_u64, _u64], _u32),
+    "hif8_amax_f16": ([_vp, _sz, _vp, _vp], _i),
+    "hif8_encode_f16": ([_vp, _vp, _sz, _f, _u32, _vp], _i),
+    "hif8_decode_f16": ([_vp, _vp, _sz, _f, _vp], _i),
+    "hif8_fake_quant_f16": ([_vp, _vp, _vp, _sz, _f, _u32, _vp], _i),
+    "hif8_encode_f16_ds": ([_vp, _vp, _sz, _vp, _vp, _u32, _vp], _i),
+    "hif8_decode_f16_ds": ([_vp, _vp, _sz, _vp, _vp], _i),
+    "hif8_fake_quant_f16_ds": ([_vp, _vp, _vp, _sz, _vp, _vp, _u32, _vp], _i),
+    "hif8_multi_cast_f16": ([_vp, _sz, ctypes.c_uint64, _vp, _vp, _f, _i, _u32, _vp], _i),
     "hif8_amax_f32": ([_vp, _sz, _vp, _vp], _i),
     "hif8_amax_bf16": ([_vp, _sz, _vp, _vp], _i),
     "hif8_scale_from_amax": ([_vp, _vp, _f, _i, _vp], _i),
@@ -115,6 +130,56 @@ def hif8_last_hip_error():
 
 def hif8_init():
     _check(lib.hif8_init())
+
+
+def hif8_set_sr_seed(seed):
+    _check(lib.hif8_set_sr_seed(seed))
+
+
+def hif8_get_sr_seed():
+    return lib.hif8_get_sr_seed()
+
+
+def hif8_sr_threshold(seed, index):
+    return lib.hif8_sr_threshold(seed, index)
+
+
+def hif8_amax_f16(src, n, d_amax, stream=None):
+    _check(lib.hif8_amax_f16(_ptr(src), n, _ptr(d_amax), _stream(stream)))
+
+
+def hif8_encode_f16(src, dst, n, scale=1.0, rounding_mode=RM_TA, stream=None):
+    _check(lib.hif8_encode_f16(_ptr(src), _ptr(dst), n, scale, rounding_mode, _stream(stream)))
+
+
+def hif8_decode_f16(src, dst, n, scale=1.0, stream=None):
+    _check(lib.hif8_decode_f16(_ptr(src), _ptr(dst), n, scale, _stream(stream)))
+
+
+def hif8_fake_quant_f16(src, dst, codes_or_none, n, scale=1.0, rounding_mode=RM_TA, stream=None):
+    _check(lib.hif8_fake_quant_f16(_ptr(src), _ptr(dst), _ptr(codes_or_none), n, scale, rounding_mode,
+                                   _stream(stream)))
+
+
+def hif8_encode_f16_ds(src, dst, n, d_scale2, rounding_mode=RM_TA, stream=None, d_amax_accum=None):
+    _check(lib.hif8_encode_f16_ds(_ptr(src), _ptr(dst), n, _ptr(d_scale2), _ptr(d_amax_accum), rounding_mode,
+                                  _stream(stream)))
+
+
+def hif8_decode_f16_ds(src, dst, n, d_scale2, stream=None):
+    _check(lib.hif8_decode_f16_ds(_ptr(src), _ptr(dst), n, _ptr(d_scale2), _stream(stream)))
+
+
+def hif8_fake_quant_f16_ds(src, dst, codes_or_none, n, d_scale2, rounding_mode=RM_TA, stream=None,
+                           d_amax_accum=None):
+    _check(lib.hif8_fake_quant_f16_ds(_ptr(src), _ptr(dst), _ptr(codes_or_none), n, _ptr(d_scale2),
+                                      _ptr(d_amax_accum), rounding_mode, _stream(stream)))
+
+
+def hif8_multi_cast_f16(d_items, count, total_tiles, d_amax, d_scale2, target=MAX_FINITE, pow2=0,
+                        rounding_mode=RM_TA, stream=None):
+    _check(lib.hif8_multi_cast_f16(_ptr(d_items), count, total_tiles, _ptr(d_amax), _ptr(d_scale2), target,
+                                   int(pow2), rounding_mode, _stream(stream)))
 
 
 def hif8_amax_f32(src, n, d_amax, stream=None):
@@ -191,7 +256,7 @@ class CastItem(ctypes.Structure):
                 ("first_tile", ctypes.c_uint64)]
 
 
-def hif8_multi_plan(items, src_is_bf16=True):
+def hif8_multi_plan(items, src_is_16bit=True):
     """items: list of (src_ptr_or_tensor, dst_ptr_or_tensor, n).  Returns (device uint8 tensor
     holding the planned hif8_cast_item array, count, total_tiles)."""
     count = len(items)
@@ -201,7 +266,7 @@ def hif8_multi_plan(items, src_is_bf16=True):
         arr[i].dst = _ptr(dst)
         arr[i].n = n
     total = ctypes.c_uint64(0)
-    _check(lib.hif8_multi_plan(ctypes.cast(arr, ctypes.c_void_p), count, int(src_is_bf16),
+    _check(lib.hif8_multi_plan(ctypes.cast(arr, ctypes.c_void_p), count, int(src_is_16bit),
                                ctypes.cast(ctypes.byref(total), ctypes.c_void_p)))
     raw = bytes(arr)[:count * ctypes.sizeof(CastItem)]
     d_items = torch.frombuffer(bytearray(raw), dtype=torch.uint8).cuda() if count else torch.empty(0, dtype=torch.uint8, device="cuda")

@@ -6,6 +6,7 @@
 #include <stddef.h>
 #define HIF8_DEVICE_HOST_SHIM 1
 #define __device__
+#define __host__
 #define __forceinline__ inline
 static inline int __clz(int x) { return x == 0 ? 32 : __builtin_clz((unsigned)x); }
 #include "../../paper_2409_16626_amd/csrc/hif8_device.hpp"

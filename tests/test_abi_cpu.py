@@ -30,7 +30,8 @@ def test_argument_validation_happens_on_the_host():
     p = 0x1000  # never dereferenced: every call below fails validation or has n == 0
     assert L.hif8_encode_f32(None, p, 16, 1.0, 0, None) == NULL
     assert L.hif8_encode_f32(p, None, 16, 1.0, 0, None) == NULL
-    assert L.hif8_encode_bf16(p, p, 16, 1.0, 2, None) == MODE
+    assert L.hif8_encode_bf16(p, p, 16, 1.0, 5, None) == MODE
+    assert L.hif8_encode_f16(p, p, 16, 1.0, 0xF, None) == MODE
     assert L.hif8_encode_bf16(p, p, 16, 1.0, 0x40, None) == MODE
     for bad in (0.0, -1.0, float("inf"), float("nan"), 1e-45, 3e38 * 10):
         assert L.hif8_encode_f32(p, p, 16, bad, 0, None) == SCALE, bad

@@ -127,7 +127,7 @@ def test_c5_full(h):
     assert len(index) == 225 and arena.numel() == 6607077376
     codes = torch.empty(arena.numel(), dtype=torch.uint8, device=dev())
     items = [(arena.data_ptr() + 2 * off, codes.data_ptr() + off, m) for _, off, m in index]
-    d_items, count, tiles = h.hif8_multi_plan(items, src_is_bf16=True)
+    d_items, count, tiles = h.hif8_multi_plan(items, src_is_16bit=True)
     am = torch.zeros(count, dtype=torch.float32, device=dev())
     sc = torch.zeros(count, 2, dtype=torch.float32, device=dev())
     h.hif8_multi_cast_bf16(d_items, count, tiles, am, sc, 32768.0, 0, TA)

@@ -330,7 +330,7 @@ def test_multi_tensor_cast_matches_per_tensor_oracle(h, mode, pow2):
         x = xf.to(torch.bfloat16) if bf16 else xf
         codes = torch.zeros(total, dtype=torch.uint8, device=dev())
         items = [(x[o:o + m].data_ptr() if m else 0, codes[o:o + m].data_ptr() if m else 0, m) for o, m in zip(offs, sizes)]
-        d_items, count, tiles = h.hif8_multi_plan(items, src_is_bf16=bf16)
+        d_items, count, tiles = h.hif8_multi_plan(items, src_is_16bit=bf16)
         am = torch.full((count,), 3.0, dtype=torch.float32, device=dev())
         sc = torch.zeros(count, 2, dtype=torch.float32, device=dev())
         fn = h.hif8_multi_cast_bf16 if bf16 else h.hif8_multi_cast_f32
