@@ -139,7 +139,7 @@ def main():
                    "rotating_buffers": R, "tuning_block_wgpercu_unroll_impl_tilesperwg_amaxnt": tune},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                     "kernel": "k_encode_f32<U,TA_LUT>", "bytes_per_launch": bytes_step,
+                     "kernel": "k_encode<U, TA table, binary32 source>", "bytes_per_launch": bytes_step,
                      "avg_launch_ms": round(ev_ms, 5)},
     }
 
@@ -188,6 +188,11 @@ def main():
         # HR on the C2 tensor
         w_ms, e_ms = timed(lambda i: hif8.hif8_encode_f32(xs[i % R], outs[i % R], n, 1.0, hif8.RM_HR), K, W)
         extra["encode_f32 HR C2 (5 B/elem)"] = rate(5 * n, e_ms)
+
+        # comparison modes on the C2 tensor: TE (tie table), simplified SR everywhere, standard SR
+        for name, mode in (("TE", hif8.RM_TE), ("SSR", hif8.RM_SSR), ("SR", hif8.RM_SR)):
+            w_ms, e_ms = timed(lambda i: hif8.hif8_encode_f32(xs[i % R], outs[i % R], n, 1.0, mode), K, W)
+            extra["encode_f32 %s C2 (5 B/elem, comparison mode)" % name] = rate(5 * n, e_ms)
         del xs, outs, x0
         torch.cuda.empty_cache()
 
@@ -214,6 +219,12 @@ def main():
         extra["amax_bf16 (2 B/elem)"] = rate(2 * m, e_ms)
         w_ms, e_ms = timed(lambda i: hif8.hif8_encode_bf16_ds(acts[i % R], cds[i % R], m, sc, hif8.RM_TA), K, W)
         extra["encode_bf16 (3 B/elem)"] = rate(3 * m, e_ms)
+        h16 = [a.float().to(torch.float16) for a in acts[:2]]
+        w_ms, e_ms = timed(lambda i: hif8.hif8_encode_f16(h16[i % 2], cds[i % R], m, 1.0, hif8.RM_TA), K, W)
+        extra["encode_f16 (3 B/elem)"] = rate(3 * m, e_ms)
+        w_ms, e_ms = timed(lambda i: hif8.hif8_fake_quant_f16(h16[i % 2], fq[i % R], cds[i % R], m, 1.0, hif8.RM_HR), K, W)
+        extra["fake_quant_f16 HR with codes (5 B/elem)"] = rate(5 * m, e_ms)
+        del h16
         w_ms, e_ms = timed(lambda i: hif8.hif8_diag_stream(acts[i % R], cds[i % R], m // 8, 8), K, W)
         extra["stream_r16_w8 (ceiling for BF16 encode)"] = rate(3 * m, e_ms)
         del acts, fq, cds, a0
