@@ -556,3 +556,90 @@ float hif8o_scale_from_amax(float amax, float target, int pow2) {
   }
   return s;
 }
+
+/* ------------------------------------------------------------------------
+ * Scale sweep (the cast-and-score step of Algorithm 1, applied to one tensor):
+ * for each exponent e = e_lo .. e_lo + count - 1 the tensor is scaled by 2^e,
+ * cast to HiF8, restored by 2^-e, and the squared error against the original is
+ * summed:  err[k] = sum_i ( x_i - value(Q(fl32(x_i * 2^e))) * 2^-e )^2.
+ * Sums are fp64 (each term is exact in fp64: the difference of two binary32
+ * values that is itself a binary32-sized quantity, squared).  IEEE semantics for
+ * non-finite terms: a cast that overflows to Infinity makes the sum +Inf, a NaN
+ * element makes it NaN.  Algorithm 1 scores the MSE of the layer output; this is
+ * the same score taken on the tensor itself (MSE = err / n).
+ * src_kind: OSRC_F32 (x points to float), OSRC_BF16 / OSRC_F16 (uint16_t patterns).
+ * ---------------------------------------------------------------------- */
+static float load_as_f32(const void *x, size_t i, int src_kind) {
+  if (src_kind == OSRC_F32) return ((const float *)x)[i];
+  if (src_kind == OSRC_BF16) return bf16_to_f32(((const uint16_t *)x)[i]);
+  return f16_to_f32(((const uint16_t *)x)[i]);
+}
+
+void hif8o_scale_sweep(const void *x, size_t n, int src_kind, int e_lo, int count,
+                       uint32_t mode, double *err_out) {
+  build_value_table(); note_threads();
+  for (int k = 0; k < count; ++k) {
+    const float s = (float)ldexp(1.0, e_lo + k);
+    volatile float inv = 1.0f / s;
+    double acc = 0.0;
+#pragma omp parallel for schedule(static) reduction(+ : acc)
+    for (ptrdiff_t i = 0; i < (ptrdiff_t)n; ++i) {
+      const float xi = load_as_f32(x, (size_t)i, src_kind);
+      volatile float y = xi * s;
+      const uint8_t c = hif8o_encode_one_t(y, mode, src_kind, hif8o_sr_threshold(g_sr_seed, (uint64_t)i));
+      const double q = (double)decode_descaled(c, inv);
+      const double d = (double)xi - q;
+      acc += d * d;
+    }
+    err_out[k] = acc;
+  }
+}
+
+/* ------------------------------------------------------------------------
+ * Per-channel scaling (Sec. 4.2 suggests per-channel scaling for weights as a
+ * further method): a row-major [rows, cols] matrix with one amax / scale per
+ * row (axis = 0: the channel index is the row) or per column (axis = 1).
+ * ---------------------------------------------------------------------- */
+void hif8o_amax_axis(const void *x, size_t rows, size_t cols, int src_kind, int axis, float *amax_out) {
+  const size_t nch = axis == 0 ? rows : cols;
+  for (size_t c = 0; c < nch; ++c) {
+    uint32_t m = 0;
+    const size_t len = axis == 0 ? cols : rows;
+    for (size_t j = 0; j < len; ++j) {
+      const size_t idx = axis == 0 ? c * cols + j : j * cols + c;
+      uint32_t a = f32_bits(load_as_f32(x, idx, src_kind)) & 0x7FFFFFFFu;
+      if (a > m) m = a;
+    }
+    amax_out[c] = bits_f32(m);
+  }
+}
+
+/* codes[r, c] = code(Q(fl32(x[r, c] * scale[channel]))); standard-SR thresholds are indexed
+ * by the flat element index r * cols + c */
+void hif8o_encode_axis(const void *x, uint8_t *dst, size_t rows, size_t cols, int src_kind, int axis,
+                       const float *scale, uint32_t mode) {
+  build_value_table(); note_threads();
+#pragma omp parallel for schedule(static)
+  for (ptrdiff_t r = 0; r < (ptrdiff_t)rows; ++r) {
+    for (size_t c = 0; c < cols; ++c) {
+      const size_t idx = (size_t)r * cols + c;
+      volatile float y = load_as_f32(x, idx, src_kind) * scale[axis == 0 ? (size_t)r : c];
+      dst[idx] = hif8o_encode_one_t(y, mode, src_kind, hif8o_sr_threshold(g_sr_seed, (uint64_t)idx));
+    }
+  }
+}
+
+/* dst[r, c] = narrow(fl32(value(codes[r, c]) * fl32(1 / scale[channel]))) */
+void hif8o_decode_axis(const uint8_t *codes, void *dst, size_t rows, size_t cols, int dst_kind, int axis,
+                       const float *scale) {
+  for (size_t r = 0; r < rows; ++r) {
+    for (size_t c = 0; c < cols; ++c) {
+      const size_t idx = r * cols + c;
+      volatile float inv = 1.0f / scale[axis == 0 ? r : c];
+      const float v = decode_descaled(codes[idx], inv);
+      if (dst_kind == OSRC_F32) ((float *)dst)[idx] = v;
+      else if (dst_kind == OSRC_BF16) ((uint16_t *)dst)[idx] = f32_to_bf16_rne(v);
+      else ((uint16_t *)dst)[idx] = f32_to_f16_rne(v);
+    }
+  }
+}

@@ -61,6 +61,11 @@ _lib.hif8o_amax_f32.restype = ctypes.c_float
 _lib.hif8o_amax_f32.argtypes = [_f32p, ctypes.c_size_t]
 _lib.hif8o_amax_bf16.restype = ctypes.c_float
 _lib.hif8o_amax_bf16.argtypes = [_u16p, ctypes.c_size_t]
+_vp = ctypes.c_void_p
+_lib.hif8o_scale_sweep.argtypes = [_vp, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_uint32, _f64p]
+_lib.hif8o_amax_axis.argtypes = [_vp, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, _f32p]
+_lib.hif8o_encode_axis.argtypes = [_vp, _u8p, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, _f32p, ctypes.c_uint32]
+_lib.hif8o_decode_axis.argtypes = [_u8p, _vp, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, _f32p]
 _lib.hif8o_scale_from_amax.restype = ctypes.c_float
 _lib.hif8o_scale_from_amax.argtypes = [ctypes.c_float, ctypes.c_float, ctypes.c_int]
 
@@ -235,3 +240,47 @@ def amax_bf16(src) -> np.float32:
 
 def scale_from_amax(amax, target=32768.0, pow2=False) -> np.float32:
     return np.float32(_lib.hif8o_scale_from_amax(np.float32(amax), np.float32(target), int(pow2)))
+
+
+def _kind_dtype(kind):
+    return np.float32 if kind == SRC_F32 else np.uint16
+
+
+def scale_sweep(src, kind=SRC_F32, e_lo=-4, count=10, mode=RM_TA):
+    """Sum of squared cast errors of one tensor at the scales 2^e_lo .. 2^(e_lo+count-1)
+    (fp64 array of `count` sums; divide by the element count for the MSE)."""
+    src = _arr(src, _kind_dtype(kind))
+    err = np.zeros(count, np.float64)
+    _lib.hif8o_scale_sweep(src.ctypes.data_as(ctypes.c_void_p), src.size, kind, e_lo, count, mode,
+                           _ptr(err, ctypes.c_double))
+    return err
+
+
+def amax_axis(src, kind=SRC_F32, axis=0):
+    src = _arr(src, _kind_dtype(kind))
+    rows, cols = src.shape
+    out = np.zeros(rows if axis == 0 else cols, np.float32)
+    _lib.hif8o_amax_axis(src.ctypes.data_as(ctypes.c_void_p), rows, cols, kind, axis, _ptr(out, ctypes.c_float))
+    return out
+
+
+def encode_axis(src, scale, kind=SRC_F32, axis=0, mode=RM_TA):
+    src = _arr(src, _kind_dtype(kind))
+    scale = _arr(scale, np.float32)
+    rows, cols = src.shape
+    assert scale.size == (rows if axis == 0 else cols)
+    dst = np.empty(src.shape, np.uint8)
+    _lib.hif8o_encode_axis(src.ctypes.data_as(ctypes.c_void_p), _ptr(dst, ctypes.c_uint8), rows, cols, kind, axis,
+                           _ptr(scale, ctypes.c_float), mode)
+    return dst
+
+
+def decode_axis(codes, scale, kind=SRC_F32, axis=0):
+    codes = _arr(codes, np.uint8)
+    scale = _arr(scale, np.float32)
+    rows, cols = codes.shape
+    assert scale.size == (rows if axis == 0 else cols)
+    dst = np.empty(codes.shape, _kind_dtype(kind))
+    _lib.hif8o_decode_axis(_ptr(codes, ctypes.c_uint8), dst.ctypes.data_as(ctypes.c_void_p), rows, cols, kind, axis,
+                           _ptr(scale, ctypes.c_float))
+    return dst
