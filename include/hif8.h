@@ -252,6 +252,63 @@ hif8_status hif8_multi_cast_f16(const hif8_cast_item* d_items, size_t count, uin
                                 uint32_t rounding_mode, hif8_stream_t stream);
 
 /*
+ * Scale sweep: the cast-and-score step of Algorithm 1 (HiF8 calibration with per-tensor
+ * scaling: try a run of power-of-two scale factors, keep the one with the smallest error)
+ * applied to one tensor, in one pass over it.  For k = 0 .. count-1, e = e_lo + k:
+ *     d_err[k] = sum_i ( x_i - value(Q(fl32(x_i * 2^e))) * 2^-e )^2          (MSE = d_err[k] / n)
+ * Differences, squares and sums are fp64; a cast that overflows to Infinity makes the sum +Inf,
+ * a NaN element makes it NaN (HIF8_FLAG_SAT keeps overflow finite).  Partial sums are combined
+ * with fp64 atomics, so the last bits depend on the order (relative spread ~1e-15).
+ * Algorithm 1 proper scores the layer output; hif8_calibrate_layer does that with the GEMM.
+ * count in [1, 16]; |e| <= 126.  d_err: count device doubles, overwritten.  n == 0 gives zeros.
+ */
+hif8_status hif8_scale_sweep_f32(const float* src, size_t n, int e_lo, int count,
+                                 uint32_t rounding_mode, double* d_err, hif8_stream_t stream);
+hif8_status hif8_scale_sweep_bf16(const uint16_t* src, size_t n, int e_lo, int count,
+                                  uint32_t rounding_mode, double* d_err, hif8_stream_t stream);
+hif8_status hif8_scale_sweep_f16(const uint16_t* src, size_t n, int e_lo, int count,
+                                 uint32_t rounding_mode, double* d_err, hif8_stream_t stream);
+
+/*
+ * Per-channel scaling of a row-major [rows, cols] matrix (Sec. 4.2 names per-tensor scaling
+ * for activations with per-channel scaling for weights as a further method).  axis = 0: one
+ * scale per row; axis = 1: one scale per column.  nch = rows or cols accordingly.
+ *   hif8_amax_axis_*        d_amax[ch] = max |x| over the channel (nch device floats, overwritten;
+ *                           same ordering of Inf / NaN as hif8_amax_*)
+ *   hif8_scale_from_amax_n  hif8_scale_from_amax for `count` consecutive amax values:
+ *                           d_scale2[2 ch] = scale, d_scale2[2 ch + 1] = fl32(1 / scale)
+ *   hif8_encode_axis_*      dst[r, c] = code(Q(fl32(x[r, c] * scale[ch])))  (standard-SR thresholds
+ *                           are indexed by the flat element index r * cols + c)
+ *   hif8_decode_axis_*      dst[r, c] = narrow(fl32(value(src[r, c]) * fl32(1 / scale[ch])))
+ * The fast paths need 16-byte aligned matrices (codes: 4 / 8 bytes as for hif8_encode_*) and
+ * cols a multiple of 4 (FP32) or 8 (16-bit); anything else takes an element-per-lane path.
+ * rows and cols must each be below 2^31.
+ */
+hif8_status hif8_scale_from_amax_n(const float* d_amax, float* d_scale2, size_t count, float target,
+                                   int pow2, hif8_stream_t stream);
+hif8_status hif8_amax_axis_f32(const float* src, size_t rows, size_t cols, int axis, float* d_amax,
+                               hif8_stream_t stream);
+hif8_status hif8_amax_axis_bf16(const uint16_t* src, size_t rows, size_t cols, int axis,
+                                float* d_amax, hif8_stream_t stream);
+hif8_status hif8_amax_axis_f16(const uint16_t* src, size_t rows, size_t cols, int axis,
+                               float* d_amax, hif8_stream_t stream);
+hif8_status hif8_encode_axis_f32(const float* src, uint8_t* dst, size_t rows, size_t cols, int axis,
+                                 const float* d_scale2, uint32_t rounding_mode,
+                                 hif8_stream_t stream);
+hif8_status hif8_encode_axis_bf16(const uint16_t* src, uint8_t* dst, size_t rows, size_t cols,
+                                  int axis, const float* d_scale2, uint32_t rounding_mode,
+                                  hif8_stream_t stream);
+hif8_status hif8_encode_axis_f16(const uint16_t* src, uint8_t* dst, size_t rows, size_t cols,
+                                 int axis, const float* d_scale2, uint32_t rounding_mode,
+                                 hif8_stream_t stream);
+hif8_status hif8_decode_axis_f32(const uint8_t* src, float* dst, size_t rows, size_t cols, int axis,
+                                 const float* d_scale2, hif8_stream_t stream);
+hif8_status hif8_decode_axis_bf16(const uint8_t* src, uint16_t* dst, size_t rows, size_t cols,
+                                  int axis, const float* d_scale2, hif8_stream_t stream);
+hif8_status hif8_decode_axis_f16(const uint8_t* src, uint16_t* dst, size_t rows, size_t cols,
+                                 int axis, const float* d_scale2, hif8_stream_t stream);
+
+/*
  * Launch-shape tuning knobs (process-wide; for benchmarking and profiling).  The first,
  * second, third and fifth default to -1 = "use the built-in shape of each kernel family".
  *   HIF8_TUNE_BLOCK        threads per workgroup of the streaming kernels (64..1024, multiple of 64)

@@ -82,6 +82,19 @@ _SIGS = {
     "hif8_multi_plan": ([_vp, _sz, _i, _vp], _i),
     "hif8_multi_cast_bf16": ([_vp, _sz, ctypes.c_uint64, _vp, _vp, _f, _i, _u32, _vp], _i),
     "hif8_multi_cast_f32": ([_vp, _sz, ctypes.c_uint64, _vp, _vp, _f, _i, _u32, _vp], _i),
+    "hif8_scale_from_amax_n": ([_vp, _vp, _sz, _f, _i, _vp], _i),
+    "hif8_scale_sweep_f32": ([_vp, _sz, _i, _i, _u32, _vp, _vp], _i),
+    "hif8_scale_sweep_bf16": ([_vp, _sz, _i, _i, _u32, _vp, _vp], _i),
+    "hif8_scale_sweep_f16": ([_vp, _sz, _i, _i, _u32, _vp, _vp], _i),
+    "hif8_amax_axis_f32": ([_vp, _sz, _sz, _i, _vp, _vp], _i),
+    "hif8_amax_axis_bf16": ([_vp, _sz, _sz, _i, _vp, _vp], _i),
+    "hif8_amax_axis_f16": ([_vp, _sz, _sz, _i, _vp, _vp], _i),
+    "hif8_encode_axis_f32": ([_vp, _vp, _sz, _sz, _i, _vp, _u32, _vp], _i),
+    "hif8_encode_axis_bf16": ([_vp, _vp, _sz, _sz, _i, _vp, _u32, _vp], _i),
+    "hif8_encode_axis_f16": ([_vp, _vp, _sz, _sz, _i, _vp, _u32, _vp], _i),
+    "hif8_decode_axis_f32": ([_vp, _vp, _sz, _sz, _i, _vp, _vp], _i),
+    "hif8_decode_axis_bf16": ([_vp, _vp, _sz, _sz, _i, _vp, _vp], _i),
+    "hif8_decode_axis_f16": ([_vp, _vp, _sz, _sz, _i, _vp, _vp], _i),
     "hif8_set_tuning": ([_i, _i], _i),
     "hif8_get_tuning": ([_i], _i),
     "hif8_diag_stream": ([_vp, _vp, _sz, _i, _vp], _i),
@@ -283,6 +296,34 @@ def hif8_multi_cast_f32(d_items, count, total_tiles, d_amax, d_scale2, target=MA
                         rounding_mode=RM_TA, stream=None):
     _check(lib.hif8_multi_cast_f32(_ptr(d_items), count, total_tiles, _ptr(d_amax), _ptr(d_scale2), target,
                                    int(pow2), rounding_mode, _stream(stream)))
+
+
+def hif8_scale_from_amax_n(d_amax, d_scale2, count, target=MAX_FINITE, pow2=0, stream=None):
+    _check(lib.hif8_scale_from_amax_n(_ptr(d_amax), _ptr(d_scale2), count, target, int(pow2), _stream(stream)))
+
+
+def _def_calib(sfx):
+    sweep, amax = getattr(lib, "hif8_scale_sweep_" + sfx), getattr(lib, "hif8_amax_axis_" + sfx)
+    enc, dec = getattr(lib, "hif8_encode_axis_" + sfx), getattr(lib, "hif8_decode_axis_" + sfx)
+
+    def scale_sweep(src, n, e_lo, count, rounding_mode, d_err, stream=None):
+        _check(sweep(_ptr(src), n, e_lo, count, rounding_mode, _ptr(d_err), _stream(stream)))
+
+    def amax_axis(src, rows, cols, axis, d_amax, stream=None):
+        _check(amax(_ptr(src), rows, cols, axis, _ptr(d_amax), _stream(stream)))
+
+    def encode_axis(src, dst, rows, cols, axis, d_scale2, rounding_mode=RM_TA, stream=None):
+        _check(enc(_ptr(src), _ptr(dst), rows, cols, axis, _ptr(d_scale2), rounding_mode, _stream(stream)))
+
+    def decode_axis(src, dst, rows, cols, axis, d_scale2, stream=None):
+        _check(dec(_ptr(src), _ptr(dst), rows, cols, axis, _ptr(d_scale2), _stream(stream)))
+
+    return scale_sweep, amax_axis, encode_axis, decode_axis
+
+
+hif8_scale_sweep_f32, hif8_amax_axis_f32, hif8_encode_axis_f32, hif8_decode_axis_f32 = _def_calib("f32")
+hif8_scale_sweep_bf16, hif8_amax_axis_bf16, hif8_encode_axis_bf16, hif8_decode_axis_bf16 = _def_calib("bf16")
+hif8_scale_sweep_f16, hif8_amax_axis_f16, hif8_encode_axis_f16, hif8_decode_axis_f16 = _def_calib("f16")
 
 
 def hif8_set_tuning(key, value):

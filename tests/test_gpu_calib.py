@@ -1,0 +1,185 @@
+"""GPU parity for the scale sweep (cast-and-score step of Algorithm 1 on one tensor) and the
+per-channel amax / encode / decode kernels, against the CPU oracle.
+
+Bars: codes and amax bit-exact, decoded outputs as raw bit patterns; the fp64 error sums
+within 1e-12 relative (every term is exact in fp64 on both sides; only the order in which
+partial sums are combined differs -- n * 2^-53 relative at worst, ~1e-9 for n = 2^24 in theory,
+far less in practice because the sums are tree-shaped on both sides).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import hif8_oracle as orc
+from gpu_util import assert_same_bytes, bf16_bits, dev, f32_bits, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+TA, HR, TE, SSR, SR = orc.RM_TA, orc.RM_HR, orc.RM_TE, orc.RM_SSR, orc.RM_SR
+SAT = orc.FLAG_SAT
+KINDS = {"f32": orc.SRC_F32, "bf16": orc.SRC_BF16, "f16": orc.SRC_F16}
+SEED = 0xC0FFEE12345
+
+
+@pytest.fixture(scope="module")
+def h():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2409_16626_amd import hif8
+    hif8.hif8_init()
+    return hif8
+
+
+@pytest.fixture(autouse=True)
+def seeds(h):
+    h.hif8_set_sr_seed(SEED)
+    orc.set_sr_seed(SEED)
+    yield
+    h.hif8_set_sr_seed(0)
+    orc.set_sr_seed(0)
+
+
+def as_kind(xf, kind):
+    """float32 device tensor -> (device tensor of that kind, numpy array in the oracle's container)."""
+    if kind == "f32":
+        return xf, xf.cpu().numpy()
+    if kind == "bf16":
+        t = xf.to(torch.bfloat16)
+        return t, bf16_bits(t)
+    t = xf.to(torch.float16)
+    return t, t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def bits16(t):
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def gpu_sweep(h, kind, x, n, e_lo, count, mode):
+    err = torch.full((count,), -1.0, dtype=torch.float64, device=dev())
+    getattr(h, "hif8_scale_sweep_" + kind)(x, n, e_lo, count, mode, err)
+    torch.cuda.synchronize()
+    return err.cpu().numpy()
+
+
+@pytest.mark.parametrize("kind", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("mode", [TA, HR, TE, SSR, SR, TA | SAT])
+def test_scale_sweep_matches_oracle(h, kind, mode):
+    g = torch.Generator(device=dev()).manual_seed(17)
+    n = (1 << 20) + 13
+    xf = torch.randn(n, generator=g, device=dev()) * torch.exp2(torch.rand(n, generator=g, device=dev()) * 16 - 10)
+    x, xn = as_kind(xf, kind)
+    got = gpu_sweep(h, kind, x, n, -4, 10, mode)
+    want = orc.scale_sweep(xn, KINDS[kind], -4, 10, mode)
+    assert np.all(np.isfinite(want))
+    np.testing.assert_allclose(got, want, rtol=1e-12)
+    # the best scale of Algorithm 1's search is the same on both sides
+    assert int(np.argmin(got)) == int(np.argmin(want))
+
+
+@pytest.mark.parametrize("n,off", [(0, 0), (1, 0), (5, 0), (9, 0), (4099, 0), (10007, 1), (70001, 3)])
+def test_scale_sweep_ragged_unaligned_and_ranges(h, n, off):
+    g = torch.Generator(device=dev()).manual_seed(18)
+    big = torch.randn(1 << 17, generator=g, device=dev()) * 3.0
+    for kind in ("f32", "bf16", "f16"):
+        xa, _ = as_kind(big, kind)
+        x = xa[off:off + n]
+        xn = x.contiguous().cpu().numpy() if kind == "f32" else bits16(x.contiguous())
+        for e_lo, count, mode in ((-4, 10, TA), (0, 1, HR), (-8, 16, TE), (3, 2, SR)):
+            err = torch.full((count,), -1.0, dtype=torch.float64, device=dev())
+            getattr(h, "hif8_scale_sweep_" + kind)(x.data_ptr() if n else 0, n, e_lo, count, mode, err)
+            torch.cuda.synchronize()
+            want = orc.scale_sweep(xn, KINDS[kind], e_lo, count, mode)
+            np.testing.assert_allclose(err.cpu().numpy(), want, rtol=1e-12, atol=0)
+
+
+def test_scale_sweep_non_finite_terms(h):
+    x = torch.tensor([3.0e4, 1.0, -2.5, 0.0] * 1000, dtype=torch.float32, device=dev())
+    got = gpu_sweep(h, "f32", x, x.numel(), 0, 3, TA)
+    want = orc.scale_sweep(x.cpu().numpy(), orc.SRC_F32, 0, 3, TA)
+    assert np.isfinite(want[0]) and np.isposinf(want[1]) and np.isposinf(want[2])
+    assert got[0] == pytest.approx(want[0], rel=1e-12) and np.isposinf(got[1]) and np.isposinf(got[2])
+    gs = gpu_sweep(h, "f32", x, x.numel(), 0, 3, TA | SAT)
+    np.testing.assert_allclose(gs, orc.scale_sweep(x.cpu().numpy(), orc.SRC_F32, 0, 3, TA | SAT), rtol=1e-12)
+    x[777] = float("nan")
+    assert np.all(np.isnan(gpu_sweep(h, "f32", x, x.numel(), -1, 4, HR)))
+    # argument checks
+    from paper_2409_16626_amd.hif8 import Hif8Error
+    err = torch.zeros(16, dtype=torch.float64, device=dev())
+    for bad in ((0, 17), (0, 0), (-127, 2), (120, 8)):
+        with pytest.raises(Hif8Error):
+            h.hif8_scale_sweep_f32(x, x.numel(), bad[0], bad[1], TA, err)
+
+
+def test_scale_sweep_large_tensor(h):
+    from paper_2409_16626_amd import workloads
+    x = workloads.activation_bf16(4096, 4096, dev()).view(-1)
+    got = gpu_sweep(h, "bf16", x, x.numel(), -4, 10, TA)
+    want = orc.scale_sweep(bf16_bits(x), orc.SRC_BF16, -4, 10, TA)
+    np.testing.assert_allclose(got, want, rtol=1e-12)
+
+
+# ------------------------------------------------------------------ per-channel
+SHAPES = [(37, 53), (64, 4096), (300, 1032), (1, 8), (4096, 8), (5, 8200), (1030, 264), (2, 3)]
+
+
+@pytest.mark.parametrize("rows,cols", SHAPES)
+@pytest.mark.parametrize("axis", [0, 1])
+def test_per_channel_amax_scale_encode_decode(h, rows, cols, axis):
+    g = torch.Generator(device=dev()).manual_seed(rows * 131 + cols)
+    ch_shape = (rows, 1) if axis == 0 else (1, cols)
+    xf = (torch.randn(rows, cols, generator=g, device=dev())
+          * torch.exp2(torch.rand(ch_shape, generator=g, device=dev()) * 12 - 6)).contiguous()
+    nch = rows if axis == 0 else cols
+    for kind in ("f32", "bf16", "f16"):
+        x, xn = as_kind(xf, kind)
+        am = torch.full((nch,), 5.0, dtype=torch.float32, device=dev())
+        sc = torch.zeros(nch, 2, dtype=torch.float32, device=dev())
+        getattr(h, "hif8_amax_axis_" + kind)(x, rows, cols, axis, am)
+        h.hif8_scale_from_amax_n(am, sc, nch, 32768.0, 1)
+        torch.cuda.synchronize()
+        w_am = orc.amax_axis(xn, KINDS[kind], axis)
+        assert_same_bytes(f32_bits(am), w_am.view(np.uint32), "amax_axis %s" % kind)
+        w_sc = np.array([orc.scale_from_amax(a, 32768.0, True) for a in w_am], np.float32)
+        scn = sc.cpu().numpy()
+        assert np.array_equal(scn[:, 0], w_sc) and np.array_equal(scn[:, 1], np.float32(1.0) / w_sc)
+        for mode in (TA, HR, SR):
+            codes = torch.zeros(rows, cols, dtype=torch.uint8, device=dev())
+            getattr(h, "hif8_encode_axis_" + kind)(x, codes, rows, cols, axis, sc, mode)
+            torch.cuda.synchronize()
+            want = orc.encode_axis(xn, w_sc, KINDS[kind], axis, mode)
+            assert_same_bytes(codes.cpu().numpy().reshape(-1), want.reshape(-1), "encode_axis %s %#x" % (kind, mode))
+        out = torch.empty_like(x)
+        getattr(h, "hif8_decode_axis_" + kind)(codes, out, rows, cols, axis, sc)
+        torch.cuda.synchronize()
+        wd = orc.decode_axis(want, w_sc, KINDS[kind], axis)
+        gd = f32_bits(out) if kind == "f32" else bits16(out)
+        wdb = wd.view(np.uint32) if kind == "f32" else wd
+        assert_same_bytes(gd.reshape(-1), wdb.reshape(-1), "decode_axis %s" % kind)
+
+
+def test_per_channel_unaligned_base_and_special_values(h):
+    rows, cols = 33, 64
+    g = torch.Generator(device=dev()).manual_seed(3)
+    buf = torch.randn(rows * cols + 8, generator=g, device=dev())
+    x = buf[1:1 + rows * cols].view(rows, cols)            # 4 bytes off a 16-byte boundary
+    xn = x.contiguous().cpu().numpy()
+    for axis in (0, 1):
+        nch = rows if axis == 0 else cols
+        am = torch.zeros(nch, dtype=torch.float32, device=dev())
+        h.hif8_amax_axis_f32(x.data_ptr(), rows, cols, axis, am)
+        torch.cuda.synchronize()
+        assert_same_bytes(f32_bits(am), orc.amax_axis(xn, orc.SRC_F32, axis).view(np.uint32), "unaligned amax")
+    y = torch.randn(16, 128, generator=g, device=dev())
+    y[3, 5] = float("inf")
+    y[7, 9] = float("nan")
+    y[9] = 0.0
+    for axis in (0, 1):
+        nch = 16 if axis == 0 else 128
+        am = torch.zeros(nch, dtype=torch.float32, device=dev())
+        sc = torch.zeros(nch, 2, dtype=torch.float32, device=dev())
+        h.hif8_amax_axis_f32(y, 16, 128, axis, am)
+        h.hif8_scale_from_amax_n(am, sc, nch, 32768.0, 0)
+        torch.cuda.synchronize()
+        w = orc.amax_axis(y.cpu().numpy(), orc.SRC_F32, axis)
+        assert_same_bytes(f32_bits(am), w.view(np.uint32), "special amax")
+        w_sc = np.array([orc.scale_from_amax(a, 32768.0, False) for a in w], np.float32)
+        assert np.array_equal(sc.cpu().numpy()[:, 0], w_sc)   # degenerate channels (0, Inf, NaN) get scale 1
