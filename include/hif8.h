@@ -309,6 +309,64 @@ hif8_status hif8_decode_axis_f16(const uint8_t* src, uint16_t* dst, size_t rows,
                                  int axis, const float* d_scale2, hif8_stream_t stream);
 
 /*
+ * Per-tensor scaling state for training (Sec. 5.1, PTS): one scale per GEMM input tensor, all 1
+ * at the start; every `interval` iterations (the paper uses 10) the amax of each tensor is
+ * gathered and its scale becomes the largest power of two s with amax * s <= target; in every
+ * iteration the current scale multiplies the tensor before the cast and the GEMM output is
+ * descaled.  The paper leaves the update rule open ("a certain algorithm") apart from the
+ * power-of-two restriction; a tensor whose gathered amax is 0, Inf or NaN keeps its scale.
+ *
+ * The state lives in caller-owned device memory: d_amax (count floats, the accumulators that
+ * the _ds casts fill through d_amax_accum_or_null, or hif8_amax_* / hif8_multi_cast_* write)
+ * and d_scale2 (count {scale, 1/scale} pairs, read by the _ds casts).  The struct itself is
+ * host memory owned by the caller; the library keeps no reference to it.
+ *   hif8_pts_init           scales = 1, accumulators = 0, iteration = 0 (one small launch);
+ *                           target must be a power of two (HiF8's largest finite value 2^15, or
+ *                           lower to leave headroom), interval >= 1
+ *   hif8_pts_collects       1 if the current iteration is one that gathers amax
+ *                           (iteration % interval == 0), else 0: pass the accumulators to the
+ *                           casts only then
+ *   hif8_pts_end_iteration  on a gathering iteration: one launch that refreshes every scale from
+ *                           its accumulator and clears the accumulator; then iteration += 1.
+ *                           The new scales apply from the next cast enqueued on the stream
+ *                           (delayed scaling: no second pass over the tensors).
+ */
+typedef struct hif8_pts_state {
+  float* d_amax;
+  float* d_scale2;
+  uint32_t count;
+  uint32_t interval;
+  float target;
+  uint64_t iteration;
+} hif8_pts_state;
+
+hif8_status hif8_pts_init(hif8_pts_state* st, float* d_amax, float* d_scale2, size_t count,
+                          uint32_t interval, float target, hif8_stream_t stream);
+int hif8_pts_collects(const hif8_pts_state* st);
+hif8_status hif8_pts_end_iteration(hif8_pts_state* st, hif8_stream_t stream);
+
+/*
+ * Adaptive loss scaling (Sec. 5.1, ALS): the dynamic loss scale of mixed-precision training
+ * (halve on an overflow, double after `window` overflow-free iterations) with a window that
+ * moves along {1, 20, 50, 100, 200, 500, 1000}: initial scale 2^32, initial window 20; three
+ * scale increases since the last window change move the window one place up, three decreases
+ * in a row move it one place down.  Host-only state machine (no device work): the caller
+ * reports per iteration whether the gradients overflowed (e.g. hif8_amax_* returned Inf / NaN).
+ * The scale stays within [1, 2^126].
+ */
+typedef struct hif8_als_state {
+  float scale;
+  int32_t window_index;
+  int32_t good_steps;
+  int32_t increases;
+  int32_t decrease_streak;
+} hif8_als_state;
+
+void hif8_als_init(hif8_als_state* st);
+int hif8_als_window(const hif8_als_state* st); /* current window length, -1 on a bad state */
+hif8_status hif8_als_update(hif8_als_state* st, int found_overflow);
+
+/*
  * Launch-shape tuning knobs (process-wide; for benchmarking and profiling).  The first,
  * second, third and fifth default to -1 = "use the built-in shape of each kernel family".
  *   HIF8_TUNE_BLOCK        threads per workgroup of the streaming kernels (64..1024, multiple of 64)

@@ -95,6 +95,12 @@ _SIGS = {
     "hif8_decode_axis_f32": ([_vp, _vp, _sz, _sz, _i, _vp, _vp], _i),
     "hif8_decode_axis_bf16": ([_vp, _vp, _sz, _sz, _i, _vp, _vp], _i),
     "hif8_decode_axis_f16": ([_vp, _vp, _sz, _sz, _i, _vp, _vp], _i),
+    "hif8_pts_init": ([_vp, _vp, _vp, _sz, _u32, _f, _vp], _i),
+    "hif8_pts_collects": ([_vp], _i),
+    "hif8_pts_end_iteration": ([_vp, _vp], _i),
+    "hif8_als_init": ([_vp], None),
+    "hif8_als_window": ([_vp], _i),
+    "hif8_als_update": ([_vp, _i], _i),
     "hif8_set_tuning": ([_i, _i], _i),
     "hif8_get_tuning": ([_i], _i),
     "hif8_diag_stream": ([_vp, _vp, _sz, _i, _vp], _i),
@@ -324,6 +330,43 @@ def _def_calib(sfx):
 hif8_scale_sweep_f32, hif8_amax_axis_f32, hif8_encode_axis_f32, hif8_decode_axis_f32 = _def_calib("f32")
 hif8_scale_sweep_bf16, hif8_amax_axis_bf16, hif8_encode_axis_bf16, hif8_decode_axis_bf16 = _def_calib("bf16")
 hif8_scale_sweep_f16, hif8_amax_axis_f16, hif8_encode_axis_f16, hif8_decode_axis_f16 = _def_calib("f16")
+
+
+class PtsState(ctypes.Structure):
+    """Mirror of hif8_pts_state."""
+    _fields_ = [("d_amax", ctypes.c_void_p), ("d_scale2", ctypes.c_void_p), ("count", ctypes.c_uint32),
+                ("interval", ctypes.c_uint32), ("target", ctypes.c_float), ("iteration", ctypes.c_uint64)]
+
+
+class AlsState(ctypes.Structure):
+    """Mirror of hif8_als_state."""
+    _fields_ = [("scale", ctypes.c_float), ("window_index", ctypes.c_int32), ("good_steps", ctypes.c_int32),
+                ("increases", ctypes.c_int32), ("decrease_streak", ctypes.c_int32)]
+
+
+def hif8_pts_init(state, d_amax, d_scale2, count, interval=10, target=MAX_FINITE, stream=None):
+    _check(lib.hif8_pts_init(ctypes.addressof(state), _ptr(d_amax), _ptr(d_scale2), count, interval, target,
+                             _stream(stream)))
+
+
+def hif8_pts_collects(state):
+    return lib.hif8_pts_collects(ctypes.addressof(state))
+
+
+def hif8_pts_end_iteration(state, stream=None):
+    _check(lib.hif8_pts_end_iteration(ctypes.addressof(state), _stream(stream)))
+
+
+def hif8_als_init(state):
+    lib.hif8_als_init(ctypes.addressof(state))
+
+
+def hif8_als_window(state):
+    return lib.hif8_als_window(ctypes.addressof(state))
+
+
+def hif8_als_update(state, found_overflow):
+    _check(lib.hif8_als_update(ctypes.addressof(state), int(bool(found_overflow))))
 
 
 def hif8_set_tuning(key, value):

@@ -1,0 +1,103 @@
+"""Training-side scale state through the C ABI: the ALS scheduler is host code and is checked
+against the oracle here on the CPU; the PTS state drives device kernels and is checked on the GPU."""
+import ctypes
+import math
+
+import numpy as np
+import pytest
+
+from conftest import golden_lines
+from oracle import pts_oracle as po
+
+
+def test_als_state_machine_matches_oracle_on_cpu():
+    from paper_2409_16626_amd import hif8
+    rng = np.random.default_rng(21)
+    patterns = {
+        "clean": lambda it: False,
+        "storm": lambda it: True,
+        "mixed": lambda it: it in {1, 2, 23, 24, 45, 46, 47},
+        "bursty": None,
+    }
+    bursts = rng.random(6000) < 0.02
+    for name, f in patterns.items():
+        st = hif8.AlsState()
+        hif8.hif8_als_init(st)
+        ref = po.ALS()
+        assert st.scale == ref.scale and hif8.hif8_als_window(st) == ref.window == 20
+        for it in range(1, 6001):
+            ov = bool(bursts[it - 1]) if f is None else f(it)
+            hif8.hif8_als_update(st, ov)
+            scale, window = ref.update(ov)
+            assert st.scale == scale and hif8.hif8_als_window(st) == window, (name, it)
+    # the hand-worked traces, straight through the library
+    for name, ovf in (("clean", set()), ("mixed", {1, 2, 23, 24, 45, 46, 47})):
+        want = {int(it): (int(lg), int(w)) for n, it, lg, w in golden_lines("als_traces.txt") if n == name}
+        st = hif8.AlsState()
+        hif8.hif8_als_init(st)
+        for it in range(1, max(want) + 1):
+            hif8.hif8_als_update(st, it in ovf)
+            if it in want:
+                assert (math.log2(st.scale), hif8.hif8_als_window(st)) == want[it]
+    assert hif8.lib.hif8_als_update(None, 0) == -1
+    bad = hif8.AlsState()
+    bad.window_index = 9
+    assert hif8.lib.hif8_als_update(ctypes.addressof(bad), 0) == -5 and hif8.hif8_als_window(bad) == -1
+
+
+def test_pts_argument_checks_on_cpu():
+    from paper_2409_16626_amd import hif8
+    st = hif8.PtsState()
+    L, a = hif8.lib, ctypes.addressof(st)
+    assert L.hif8_pts_init(None, 0x1000, 0x1000, 4, 10, 32768.0, None) == -1
+    assert L.hif8_pts_init(a, None, 0x1000, 4, 10, 32768.0, None) == -1
+    assert L.hif8_pts_init(a, 0x1000, 0x1000, 4, 0, 32768.0, None) == -5
+    assert L.hif8_pts_init(a, 0x1000, 0x1000, 4, 10, 30000.0, None) == -5      # not a power of two
+    assert L.hif8_pts_init(a, 0x1000, 0x1000, 4, 10, float("inf"), None) == -5
+    assert L.hif8_pts_init(a, None, None, 0, 10, 32768.0, None) == 0           # empty list: nothing enqueued
+    assert st.iteration == 0 and L.hif8_pts_collects(a) == 1
+    assert L.hif8_pts_end_iteration(a, None) == 0 and st.iteration == 1 and L.hif8_pts_collects(a) == 0
+
+
+@pytest.mark.gpu
+def test_pts_delayed_scaling_over_iterations():
+    """Three tensors whose magnitudes drift; amax gathered inside the cast pass on every 10th
+    iteration; scales and codes checked against the oracle at every iteration."""
+    import torch
+    from oracle import hif8_oracle as orc
+    from paper_2409_16626_amd import hif8
+    from gpu_util import assert_same_bytes, bf16_bits, dev
+    hif8.hif8_init()
+    count, n = 3, (1 << 16) + 5
+    am = torch.full((count,), 9.0, dtype=torch.float32, device=dev())
+    sc = torch.full((count, 2), 9.0, dtype=torch.float32, device=dev())
+    st = hif8.PtsState()
+    hif8.hif8_pts_init(st, am, sc, count, 10, 16384.0)
+    ref = po.PTS(count, 10, 16384.0)
+    g = torch.Generator(device=dev()).manual_seed(9)
+    base = [torch.randn(n, generator=g, device=dev()) for _ in range(count)]
+    codes = torch.empty(n, dtype=torch.uint8, device=dev())
+    torch.cuda.synchronize()
+    assert am.cpu().tolist() == [0.0] * count and sc.cpu().tolist() == [[1.0, 1.0]] * count
+    for it in range(32):
+        gains = [2.0 ** (it / 3.0), 1e-3 * (1 + it), 0.0 if it < 15 else 7.0]
+        collects = bool(hif8.hif8_pts_collects(st))
+        assert collects == ref.collects()
+        amaxes = []
+        for t in range(count):
+            x = (base[t] * gains[t]).to(torch.bfloat16)
+            xn = bf16_bits(x)
+            hif8.hif8_encode_bf16_ds(x, codes, n, sc[t], orc.RM_TA,
+                                     d_amax_accum=am[t:t + 1] if collects else None)
+            torch.cuda.synchronize()
+            assert_same_bytes(codes.cpu().numpy(), orc.encode_bf16(xn, np.float32(ref.scale[t]), orc.RM_TA),
+                              "iteration %d tensor %d" % (it, t))
+            amaxes.append(float(orc.amax_bf16(xn)))
+        hif8.hif8_pts_end_iteration(st)
+        want = ref.end_iteration(amaxes if collects else None)
+        torch.cuda.synchronize()
+        got = sc.cpu().numpy()
+        assert got[:, 0].tolist() == want and np.array_equal(got[:, 1], np.float32(1.0) / got[:, 0]), (it, got, want)
+        assert am.cpu().tolist() == [0.0] * count or not collects
+    assert st.iteration == 32
+    assert ref.scale[2] != 1.0 and ref.scale[0] != 1.0          # the drifting tensors moved their scales
