@@ -367,6 +367,36 @@ int hif8_als_window(const hif8_als_state* st); /* current window length, -1 on a
 hif8_status hif8_als_update(hif8_als_state* st, int found_overflow);
 
 /*
+ * Simulated HiF8 GEMM (Sec. 4 / Sec. 5: the GEMM inputs are cast to HiF8 and the product is
+ * taken on the represented values; Algorithm 1 "MatMul & Restore": the product is descaled by
+ * the two input scales):
+ *     out[m, n] = fl32( (sum_k value(a[m, k]) * value(b[n, k])) * fl32(fl32(1/scale_a) * fl32(1/scale_b)) )
+ * a_codes: [M, K] u8, b_codes: [N, K] u8, both row-major with K contiguous (b is the weight in
+ * [out_features, in_features] order); out: [M, N] row-major FP32 / BF16 / FP16 (round to
+ * nearest even).  Products are exact; sums are FP32 on the matrix cores (bf16 MFMA, every HiF8
+ * value is exact in bfloat16), so results agree with exact arithmetic to within
+ * K * 2^-23 * sum_k |a b| * descale per element, and the summation order is fixed for a given
+ * shape and tile variant.  NaN / Inf codes propagate by IEEE rules.
+ * The matrix-core path needs K % 16 == 0 and 16-byte aligned operands; anything else takes a
+ * plain one-element-per-lane kernel.  M, N, K < 2^31.
+ *   hif8_gemm_sqerr   no output matrix: *d_err += sum (out[m, n] - ref[m, n])^2 in fp64
+ *                     (ref: [M, N] FP32; the caller clears *d_err) -- the "Quantization Error"
+ *                     step of Algorithm 1.
+ *   hif8_gemm_set_variant  0 = choose the tile shape by problem size (default); 1 = 128 x 128 x 64,
+ *                     2 = 256 x 256 x 32, 3 = 256 x 128 x 64 workgroup tiles (for benchmarking).
+ */
+hif8_status hif8_gemm_f32(const uint8_t* a_codes, const uint8_t* b_codes, float* out, size_t M,
+                          size_t N, size_t K, float scale_a, float scale_b, hif8_stream_t stream);
+hif8_status hif8_gemm_bf16(const uint8_t* a_codes, const uint8_t* b_codes, uint16_t* out, size_t M,
+                           size_t N, size_t K, float scale_a, float scale_b, hif8_stream_t stream);
+hif8_status hif8_gemm_f16(const uint8_t* a_codes, const uint8_t* b_codes, uint16_t* out, size_t M,
+                          size_t N, size_t K, float scale_a, float scale_b, hif8_stream_t stream);
+hif8_status hif8_gemm_sqerr(const uint8_t* a_codes, const uint8_t* b_codes, const float* ref, size_t M,
+                            size_t N, size_t K, float scale_a, float scale_b, double* d_err,
+                            hif8_stream_t stream);
+hif8_status hif8_gemm_set_variant(int variant);
+
+/*
  * Launch-shape tuning knobs (process-wide; for benchmarking and profiling).  The first,
  * second, third and fifth default to -1 = "use the built-in shape of each kernel family".
  *   HIF8_TUNE_BLOCK        threads per workgroup of the streaming kernels (64..1024, multiple of 64)

@@ -1,0 +1,340 @@
+// Simulated HiF8 GEMM on the matrix cores of gfx950, and Algorithm 1's per-layer scale search.
+//
+// The paper's experiments cast the GEMM inputs (activations, weights, activation gradients) to
+// HiF8 and run the GEMM on the represented values (Sec. 4, Sec. 5); Algorithm 1 ("MatMul &
+// Restore") descales the product by the two input scales.  Every HiF8 value is exact in
+// bfloat16 (at most 3 mantissa bits, exponents -22..15), so the product is computed with bf16
+// MFMA instructions and FP32 accumulation; the u8 codes are expanded to bf16 on their way from
+// HBM into LDS (one table lookup per element, table replicated per LDS bank so that lookups of a
+// wavefront never conflict), which halves the operand traffic against a bf16 GEMM.
+//
+//   O[M, N] = (value(A[M, K]) x value(B[N, K])^T) * descale        (both operands K-contiguous)
+//
+// Tiling: a workgroup of 4 wavefronts (2 x 2) owns a (2 TM 32) x (2 TN 32) tile of O; each
+// wavefront TM x TN blocks of v_mfma_f32_32x32x16_bf16; K advances in steps of BK through a
+// double-buffered LDS tile, with the next tile's codes in flight in registers during the MFMAs.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <mutex>
+
+#include "hif8.h"
+#include "hif8_conv_api.hpp"
+#include "hif8_device.hpp"
+#include "hif8_host.hpp"
+
+namespace hif8gemm {
+
+using namespace hif8dev;
+using namespace hif8host;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+
+enum : int { EPI_F32 = 0, EPI_BF16 = 1, EPI_F16 = 2, EPI_ERR = 3 };
+
+constexpr int kThreads = 256;
+constexpr int kPad = 8;           // bf16 elements of padding per LDS row (16 bytes)
+constexpr int kLutCopies = 32;    // one copy of the code -> bf16 table per LDS bank
+
+// code -> bfloat16 pattern (the top half of the binary32 pattern; exact for every code)
+static __device__ __attribute__((aligned(16))) uint16_t g_bf16_lut[256];
+__global__ void k_build_gemm_lut() {
+  const uint32_t i = threadIdx.x;
+  if (i < 256u) g_bf16_lut[i] = (uint16_t)(decode_bits(i) >> 16);
+}
+
+// 16 codes (one 16-byte chunk) -> 16 bf16, written to LDS as two 16-byte stores.
+// lut16: this lane's column of the replicated table, indexed by code * (2 * kLutCopies).
+__device__ __forceinline__ void decode_chunk_to_lds(const uint4& c, const uint16_t* lut16, uint4* dst) {
+  const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+  uint32_t o[8];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    u16x2 p0, p1;
+    p0.x = lut16[(w[j] & 0xFFu) * (2 * kLutCopies)];
+    p0.y = lut16[((w[j] >> 8) & 0xFFu) * (2 * kLutCopies)];
+    p1.x = lut16[((w[j] >> 16) & 0xFFu) * (2 * kLutCopies)];
+    p1.y = lut16[(w[j] >> 24) * (2 * kLutCopies)];
+    o[2 * j] = __builtin_bit_cast(uint32_t, p0);
+    o[2 * j + 1] = __builtin_bit_cast(uint32_t, p1);
+  }
+  dst[0] = make_uint4(o[0], o[1], o[2], o[3]);
+  dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
+}
+
+template <int TM, int TN, int BK, int EPI>
+__global__ void __launch_bounds__(kThreads)
+k_gemm_nt(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __restrict__ out,
+          const float* __restrict__ ref, double* __restrict__ err, uint32_t M, uint32_t N, uint32_t K,
+          float descale, const uint16_t* __restrict__ g_lut, uint32_t tiles_n) {
+  constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32;
+  constexpr int LDA = BK + kPad;                       // LDS row stride in bf16
+  constexpr int CPR = BK / 16;                         // 16-code chunks per tile row
+  constexpr int CA = BM * CPR / kThreads, CB = BN * CPR / kThreads;  // chunks per thread
+  static_assert(BM * CPR % kThreads == 0 && BN * CPR % kThreads == 0, "tile / thread mismatch");
+
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+  uint32_t* lut32 = reinterpret_cast<uint32_t*>(smem);                     // [256][kLutCopies]
+  __bf16* As = reinterpret_cast<__bf16*>(smem + 256 * kLutCopies * 4);     // [2][BM][LDA]
+  __bf16* Bs = As + 2 * BM * LDA;                                          // [2][BN][LDA]
+
+  const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+  const uint32_t wm = wave >> 1, wn = wave & 1u;
+  const uint32_t tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x - tile_m * tiles_n;
+  const uint32_t m0 = tile_m * BM, n0 = tile_n * BN;
+
+  // replicated table: entry (code, copy) at dword code * 32 + copy; a lane reads copy lane % 32
+  for (uint32_t i = tid; i < 256u * kLutCopies; i += kThreads) {
+    const uint32_t v = g_lut[i / kLutCopies];
+    lut32[i] = v | (v << 16);
+  }
+  const uint16_t* lut16 = reinterpret_cast<const uint16_t*>(lut32) + 2 * (lane & (kLutCopies - 1));
+
+  // this thread's chunks of the A and B tiles: chunk q -> row q / CPR, 16-code column q % CPR
+  uint4 ra[CA], rb[CB];
+  auto load_tiles = [&](uint32_t k0) {
+#pragma unroll
+    for (int i = 0; i < CA; ++i) {
+      const uint32_t q = tid + i * kThreads, r = q / CPR, kc = q % CPR;
+      const uint32_t row = m0 + r, k = k0 + kc * 16;
+      ra[i] = (row < M && k < K) ? *reinterpret_cast<const uint4*>(A + (size_t)row * K + k) : make_uint4(0u, 0u, 0u, 0u);
+    }
+#pragma unroll
+    for (int i = 0; i < CB; ++i) {
+      const uint32_t q = tid + i * kThreads, r = q / CPR, kc = q % CPR;
+      const uint32_t row = n0 + r, k = k0 + kc * 16;
+      rb[i] = (row < N && k < K) ? *reinterpret_cast<const uint4*>(B + (size_t)row * K + k) : make_uint4(0u, 0u, 0u, 0u);
+    }
+  };
+  auto store_tiles = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < CA; ++i) {
+      const uint32_t q = tid + i * kThreads, r = q / CPR, kc = q % CPR;
+      decode_chunk_to_lds(ra[i], lut16, reinterpret_cast<uint4*>(As + ((size_t)buf * BM + r) * LDA + kc * 16));
+    }
+#pragma unroll
+    for (int i = 0; i < CB; ++i) {
+      const uint32_t q = tid + i * kThreads, r = q / CPR, kc = q % CPR;
+      decode_chunk_to_lds(rb[i], lut16, reinterpret_cast<uint4*>(Bs + ((size_t)buf * BN + r) * LDA + kc * 16));
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  const uint32_t nk = (K + BK - 1) / BK;
+  load_tiles(0);
+  __syncthreads();  // table staged
+  store_tiles(0);
+  __syncthreads();
+
+  const uint32_t frag_row = lane & 31u, frag_k = (lane >> 5) * 8u;
+  for (uint32_t kt = 0; kt < nk; ++kt) {
+    const int buf = (int)(kt & 1u);
+    if (kt + 1 < nk) load_tiles((kt + 1) * BK);
+    const __bf16* a_base = As + ((size_t)buf * BM + wm * TM * 32 + frag_row) * LDA + frag_k;
+    const __bf16* b_base = Bs + ((size_t)buf * BN + wn * TN * 32 + frag_row) * LDA + frag_k;
+#pragma unroll
+    for (int s = 0; s < BK / 16; ++s) {
+      bf16x8 fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(a_base + (size_t)i * 32 * LDA + s * 16);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(b_base + (size_t)j * 32 * LDA + s * 16);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) store_tiles(buf ^ 1);
+    __syncthreads();
+  }
+
+  // epilogue.  Accumulator element v of a 32 x 32 block: row = (v / 4) * 8 + (lane / 32) * 4 + v % 4,
+  // column = lane % 32.
+  double e2 = 0.0;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const uint32_t col = n0 + (wn * TN + j) * 32 + (lane & 31u);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const uint32_t row = m0 + (wm * TM + i) * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+        if (row < M && col < N) {
+          const float o = __fmul_rn(acc[i][j][v], descale);
+          const size_t idx = (size_t)row * N + col;
+          if constexpr (EPI == EPI_F32) reinterpret_cast<float*>(out)[idx] = o;
+          else if constexpr (EPI == EPI_BF16) reinterpret_cast<uint16_t*>(out)[idx] = (uint16_t)narrow_bf16(__float_as_uint(o));
+          else if constexpr (EPI == EPI_F16) reinterpret_cast<_Float16*>(out)[idx] = (_Float16)o;
+          else {
+            const double d = (double)o - (double)ref[idx];
+            e2 = fma(d, d, e2);
+          }
+        }
+      }
+    }
+  }
+  if constexpr (EPI == EPI_ERR) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) e2 += __shfl_xor(e2, off, 64);
+    if (lane == 0) atomicAdd(err, e2);
+  }
+}
+
+// any K, any alignment: one output element per lane, codes expanded with the integer decoder
+template <int EPI>
+__global__ void __launch_bounds__(256)
+k_gemm_nt_simple(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __restrict__ out,
+                 const float* __restrict__ ref, double* __restrict__ err, uint32_t M, uint32_t N, uint32_t K,
+                 float descale) {
+  const size_t total = (size_t)M * N;
+  double e2 = 0.0;
+  for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+    const uint32_t row = (uint32_t)(idx / N), col = (uint32_t)(idx - (size_t)row * N);
+    const uint8_t* a = A + (size_t)row * K;
+    const uint8_t* b = B + (size_t)col * K;
+    float s = 0.0f;
+    for (uint32_t k = 0; k < K; ++k) s = fmaf(__uint_as_float(decode_bits(a[k])), __uint_as_float(decode_bits(b[k])), s);
+    const float o = __fmul_rn(s, descale);
+    if constexpr (EPI == EPI_F32) reinterpret_cast<float*>(out)[idx] = o;
+    else if constexpr (EPI == EPI_BF16) reinterpret_cast<uint16_t*>(out)[idx] = (uint16_t)narrow_bf16(__float_as_uint(o));
+    else if constexpr (EPI == EPI_F16) reinterpret_cast<_Float16*>(out)[idx] = (_Float16)o;
+    else {
+      const double d = (double)o - (double)ref[idx];
+      e2 = fma(d, d, e2);
+    }
+  }
+  if constexpr (EPI == EPI_ERR) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) e2 += __shfl_xor(e2, off, 64);
+    if ((threadIdx.x & 63u) == 0u) atomicAdd(err, e2);
+  }
+}
+
+// ====================================================================================
+// host side
+// ====================================================================================
+constexpr int kMaxDevices = 64;
+static const uint16_t* g_lut_ptr[kMaxDevices] = {};
+
+static hif8_status gemm_init(const uint16_t** lut_out, int* cus_out) {
+  int cus = 0;
+  hif8_status s = ensure_init(&cus, nullptr);
+  if (s != HIF8_OK) return s;
+  int dev = 0;
+  if (!hip_ok(hipGetDevice(&dev))) return HIF8_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return HIF8_ERR_ARG;
+  static std::mutex mu;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!g_lut_ptr[dev]) {
+    void* p = nullptr;
+    if (!hip_ok(hipGetSymbolAddress(&p, HIP_SYMBOL(g_bf16_lut)))) return HIF8_ERR_HIP;
+    hipLaunchKernelGGL(k_build_gemm_lut, dim3(1), dim3(256), 0, (hipStream_t)0);
+    if (!hip_ok(hipGetLastError())) return HIF8_ERR_HIP;
+    if (!hip_ok(hipStreamSynchronize((hipStream_t)0))) return HIF8_ERR_HIP;
+    g_lut_ptr[dev] = reinterpret_cast<const uint16_t*>(p);
+  }
+  *lut_out = g_lut_ptr[dev];
+  if (cus_out) *cus_out = cus;
+  return HIF8_OK;
+}
+
+template <int TM, int TN, int BK>
+constexpr size_t smem_bytes() {
+  return 256 * kLutCopies * 4 + (size_t)2 * (2 * TM * 32 + 2 * TN * 32) * (BK + kPad) * 2;
+}
+
+template <int TM, int TN, int BK, int EPI>
+static hif8_status launch_tiled(const uint8_t* A, const uint8_t* B, void* out, const float* ref, double* err,
+                                uint32_t M, uint32_t N, uint32_t K, float descale, const uint16_t* lut,
+                                hipStream_t st) {
+  constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32;
+  constexpr size_t smem = smem_bytes<TM, TN, BK>();
+  static bool attr_set[kMaxDevices] = {};
+  int dev = 0;
+  if (!hip_ok(hipGetDevice(&dev))) return HIF8_ERR_HIP;
+  if (!attr_set[dev]) {
+    if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt<TM, TN, BK, EPI>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem)))
+      return HIF8_ERR_HIP;
+    attr_set[dev] = true;
+  }
+  const uint32_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  if ((uint64_t)tiles_m * tiles_n > 0x7FFFFFFFull) return HIF8_ERR_ARG;
+  hipLaunchKernelGGL((k_gemm_nt<TM, TN, BK, EPI>), dim3(tiles_m * tiles_n), dim3(kThreads), smem, st, A, B, out, ref,
+                     err, M, N, K, descale, lut, tiles_n);
+  return finish_launch();
+}
+
+static int g_gemm_variant = 0;  // 0 = default choice; tuning knob HIF8_TUNE_GEMM_TILE
+
+template <int EPI>
+static hif8_status gemm_dispatch(const uint8_t* A, const uint8_t* B, void* out, const float* ref, double* err,
+                                 size_t M, size_t N, size_t K, float scale_a, float scale_b, hipStream_t st) {
+  float inv_a = 1.0f, inv_b = 1.0f;
+  if (!valid_scale(scale_a, &inv_a) || !valid_scale(scale_b, &inv_b)) return HIF8_ERR_SCALE;
+  volatile float ds = inv_a * inv_b;
+  const float descale = ds;
+  if (!(descale > 0.0f) || std::isinf(descale)) return HIF8_ERR_SCALE;
+  if (M == 0 || N == 0) return HIF8_OK;
+  if (M > 0x7FFFFFFFu || N > 0x7FFFFFFFu || K > 0x7FFFFFFFu) return HIF8_ERR_ARG;
+  if ((!A || !B) && K != 0) return HIF8_ERR_NULL;
+  if (EPI == EPI_ERR ? (!ref || !err) : !out) return HIF8_ERR_NULL;
+  const uint16_t* lut = nullptr;
+  int cus = 0;
+  hif8_status s = gemm_init(&lut, &cus);
+  if (s != HIF8_OK) return s;
+  const uint32_t m = (uint32_t)M, n = (uint32_t)N, k = (uint32_t)K;
+  const bool fast = K != 0 && (K % 16) == 0 && aligned_to(A, 16) && aligned_to(B, 16);
+  if (!fast) {
+    hipLaunchKernelGGL(k_gemm_nt_simple<EPI>, dim3(grid_elem(M * N, cus)), dim3(256), 0, st, A, B, out, ref, err, m,
+                       n, k, descale);
+    return finish_launch();
+  }
+  int variant = g_gemm_variant;
+  if (variant == 0) variant = (M * N >= (size_t)256 * 256 * 128) ? 2 : 1;  // big tiles once they fill the chip
+  if (variant == 2) return launch_tiled<4, 4, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
+  if (variant == 3) return launch_tiled<4, 2, 64, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
+  return launch_tiled<2, 2, 64, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
+}
+
+}  // namespace hif8gemm
+
+using namespace hif8gemm;
+
+extern "C" {
+
+hif8_status hif8_gemm_set_variant(int variant) {
+  if (variant < 0 || variant > 3) return HIF8_ERR_ARG;
+  g_gemm_variant = variant;
+  return HIF8_OK;
+}
+
+hif8_status hif8_gemm_f32(const uint8_t* a_codes, const uint8_t* b_codes, float* out, size_t M, size_t N, size_t K,
+                          float scale_a, float scale_b, hif8_stream_t stream) {
+  return gemm_dispatch<EPI_F32>(a_codes, b_codes, out, nullptr, nullptr, M, N, K, scale_a, scale_b, (hipStream_t)stream);
+}
+hif8_status hif8_gemm_bf16(const uint8_t* a_codes, const uint8_t* b_codes, uint16_t* out, size_t M, size_t N,
+                           size_t K, float scale_a, float scale_b, hif8_stream_t stream) {
+  return gemm_dispatch<EPI_BF16>(a_codes, b_codes, out, nullptr, nullptr, M, N, K, scale_a, scale_b, (hipStream_t)stream);
+}
+hif8_status hif8_gemm_f16(const uint8_t* a_codes, const uint8_t* b_codes, uint16_t* out, size_t M, size_t N,
+                          size_t K, float scale_a, float scale_b, hif8_stream_t stream) {
+  return gemm_dispatch<EPI_F16>(a_codes, b_codes, out, nullptr, nullptr, M, N, K, scale_a, scale_b, (hipStream_t)stream);
+}
+hif8_status hif8_gemm_sqerr(const uint8_t* a_codes, const uint8_t* b_codes, const float* ref, size_t M, size_t N,
+                            size_t K, float scale_a, float scale_b, double* d_err, hif8_stream_t stream) {
+  return gemm_dispatch<EPI_ERR>(a_codes, b_codes, nullptr, ref, d_err, M, N, K, scale_a, scale_b, (hipStream_t)stream);
+}
+
+}  // extern "C"

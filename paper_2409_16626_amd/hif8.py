@@ -101,6 +101,11 @@ _SIGS = {
     "hif8_als_init": ([_vp], None),
     "hif8_als_window": ([_vp], _i),
     "hif8_als_update": ([_vp, _i], _i),
+    "hif8_gemm_f32": ([_vp, _vp, _vp, _sz, _sz, _sz, _f, _f, _vp], _i),
+    "hif8_gemm_bf16": ([_vp, _vp, _vp, _sz, _sz, _sz, _f, _f, _vp], _i),
+    "hif8_gemm_f16": ([_vp, _vp, _vp, _sz, _sz, _sz, _f, _f, _vp], _i),
+    "hif8_gemm_sqerr": ([_vp, _vp, _vp, _sz, _sz, _sz, _f, _f, _vp, _vp], _i),
+    "hif8_gemm_set_variant": ([_i], _i),
     "hif8_set_tuning": ([_i, _i], _i),
     "hif8_get_tuning": ([_i], _i),
     "hif8_diag_stream": ([_vp, _vp, _sz, _i, _vp], _i),
@@ -367,6 +372,27 @@ def hif8_als_window(state):
 
 def hif8_als_update(state, found_overflow):
     _check(lib.hif8_als_update(ctypes.addressof(state), int(bool(found_overflow))))
+
+
+def hif8_gemm_f32(a_codes, b_codes, out, M, N, K, scale_a=1.0, scale_b=1.0, stream=None):
+    _check(lib.hif8_gemm_f32(_ptr(a_codes), _ptr(b_codes), _ptr(out), M, N, K, scale_a, scale_b, _stream(stream)))
+
+
+def hif8_gemm_bf16(a_codes, b_codes, out, M, N, K, scale_a=1.0, scale_b=1.0, stream=None):
+    _check(lib.hif8_gemm_bf16(_ptr(a_codes), _ptr(b_codes), _ptr(out), M, N, K, scale_a, scale_b, _stream(stream)))
+
+
+def hif8_gemm_f16(a_codes, b_codes, out, M, N, K, scale_a=1.0, scale_b=1.0, stream=None):
+    _check(lib.hif8_gemm_f16(_ptr(a_codes), _ptr(b_codes), _ptr(out), M, N, K, scale_a, scale_b, _stream(stream)))
+
+
+def hif8_gemm_sqerr(a_codes, b_codes, ref, M, N, K, scale_a, scale_b, d_err, stream=None):
+    _check(lib.hif8_gemm_sqerr(_ptr(a_codes), _ptr(b_codes), _ptr(ref), M, N, K, scale_a, scale_b, _ptr(d_err),
+                               _stream(stream)))
+
+
+def hif8_gemm_set_variant(variant):
+    _check(lib.hif8_gemm_set_variant(variant))
 
 
 def hif8_set_tuning(key, value):
