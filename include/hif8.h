@@ -382,8 +382,10 @@ hif8_status hif8_als_update(hif8_als_state* st, int found_overflow);
  *   hif8_gemm_sqerr   no output matrix: *d_err += sum (out[m, n] - ref[m, n])^2 in fp64
  *                     (ref: [M, N] FP32; the caller clears *d_err) -- the "Quantization Error"
  *                     step of Algorithm 1.
- *   hif8_gemm_set_variant  0 = choose the tile shape by problem size (default); 1 = 128 x 128 x 64,
- *                     2 = 256 x 256 x 32, 3 = 256 x 128 x 64 workgroup tiles (for benchmarking).
+ *   hif8_gemm_set_variant  0 = choose the tile shape by problem size (default); 1..5 = fixed
+ *                     workgroup tile / wavefront layouts (for benchmarking): 1 = 128 x 128 x 64
+ *                     (4 wavefronts), 2 = 256 x 256 x 32 (4), 3 = 256 x 128 x 64 (4),
+ *                     4 = 256 x 256 x 32 (8), 5 = 128 x 256 x 64 (8).
  */
 hif8_status hif8_gemm_f32(const uint8_t* a_codes, const uint8_t* b_codes, float* out, size_t M,
                           size_t N, size_t K, float scale_a, float scale_b, hif8_stream_t stream);
@@ -395,6 +397,38 @@ hif8_status hif8_gemm_sqerr(const uint8_t* a_codes, const uint8_t* b_codes, cons
                             size_t N, size_t K, float scale_a, float scale_b, double* d_err,
                             hif8_stream_t stream);
 hif8_status hif8_gemm_set_variant(int variant);
+
+/*
+ * Algorithm 1 (HiF8 calibration with per-tensor scaling) for ONE layer: given the layer's
+ * high-precision input a [M, K], weight w [N, K] (K contiguous in both) and high-precision
+ * output o_ref [M, N] (FP32), try every pair of power-of-two scales 2^Ea, 2^Ew with
+ * Ea = ea_lo .. ea_lo + ea_count - 1, Ew likewise (the paper searches [-4, 5] x [-4, 5]):
+ *     A_q = Q(a * 2^Ea),  W_q = Q(w * 2^Ew),  O_q = (A_q x W_q^T) * 2^-(Ea + Ew),
+ *     d_err[i * ew_count + j] = sum (O_q - o_ref)^2          (fp64; MSE = d_err / (M N))
+ * and, if d_best_or_null is given, write the pair with the smallest finite error to it as two
+ * int32 {Ea, Ew}.  The paper casts with TA here; any rounding_mode is accepted.  The model-level
+ * loop (collecting o_ref, feeding O_q through the non-linearities to the next layer) is the
+ * caller's.  Enqueues ea_count + ew_count casts and ea_count * ew_count error GEMMs on `stream`.
+ * workspace: device scratch for the code matrices, at least
+ * hif8_calibrate_workspace_bytes(M, N, K, ea_count, ew_count) bytes, 16-byte aligned, caller-owned.
+ * Counts are limited to 64 each, exponents to [-60, 60].
+ */
+size_t hif8_calibrate_workspace_bytes(size_t M, size_t N, size_t K, int ea_count, int ew_count);
+hif8_status hif8_calibrate_layer_f32(const float* a, const float* w, const float* o_ref, size_t M,
+                                     size_t N, size_t K, int ea_lo, int ea_count, int ew_lo,
+                                     int ew_count, uint32_t rounding_mode, void* workspace,
+                                     size_t workspace_bytes, double* d_err, int32_t* d_best_or_null,
+                                     hif8_stream_t stream);
+hif8_status hif8_calibrate_layer_bf16(const uint16_t* a, const uint16_t* w, const float* o_ref,
+                                      size_t M, size_t N, size_t K, int ea_lo, int ea_count,
+                                      int ew_lo, int ew_count, uint32_t rounding_mode,
+                                      void* workspace, size_t workspace_bytes, double* d_err,
+                                      int32_t* d_best_or_null, hif8_stream_t stream);
+hif8_status hif8_calibrate_layer_f16(const uint16_t* a, const uint16_t* w, const float* o_ref,
+                                     size_t M, size_t N, size_t K, int ea_lo, int ea_count,
+                                     int ew_lo, int ew_count, uint32_t rounding_mode,
+                                     void* workspace, size_t workspace_bytes, double* d_err,
+                                     int32_t* d_best_or_null, hif8_stream_t stream);
 
 /*
  * Launch-shape tuning knobs (process-wide; for benchmarking and profiling).  The first,

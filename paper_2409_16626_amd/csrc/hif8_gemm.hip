@@ -10,7 +10,7 @@
 //
 //   O[M, N] = (value(A[M, K]) x value(B[N, K])^T) * descale        (both operands K-contiguous)
 //
-// Tiling: a workgroup of 4 wavefronts (2 x 2) owns a (2 TM 32) x (2 TN 32) tile of O; each
+// Tiling: a workgroup of WM x WN wavefronts owns a (WM TM 32) x (WN TN 32) tile of O; each
 // wavefront TM x TN blocks of v_mfma_f32_32x32x16_bf16; K advances in steps of BK through a
 // double-buffered LDS tile, with the next tile's codes in flight in registers during the MFMAs.
 #include <hip/hip_runtime.h>
@@ -35,7 +35,6 @@ typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
 
 enum : int { EPI_F32 = 0, EPI_BF16 = 1, EPI_F16 = 2, EPI_ERR = 3 };
 
-constexpr int kThreads = 256;
 constexpr int kPad = 8;           // bf16 elements of padding per LDS row (16 bytes)
 constexpr int kLutCopies = 32;    // one copy of the code -> bf16 table per LDS bank
 
@@ -65,12 +64,22 @@ __device__ __forceinline__ void decode_chunk_to_lds(const uint4& c, const uint16
   dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
 }
 
-template <int TM, int TN, int BK, int EPI>
-__global__ void __launch_bounds__(kThreads)
+// 16 codes of row `row` at column k; rows / columns outside the matrix read as zero codes.  The
+// address is clamped instead of branching so that the loop body stays one basic block.
+__device__ __forceinline__ uint4 load_chunk(const uint8_t* __restrict__ P, uint32_t row, uint32_t rows,
+                                            uint32_t k, uint32_t K) {
+  const bool ok = row < rows && k < K;
+  const uint4 v = *reinterpret_cast<const uint4*>(P + (size_t)(ok ? row : 0u) * K + (ok ? k : 0u));
+  return ok ? v : make_uint4(0u, 0u, 0u, 0u);
+}
+
+template <int WM, int WN, int TM, int TN, int BK, int EPI>
+__global__ void __launch_bounds__(64 * WM * WN)
 k_gemm_nt(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __restrict__ out,
           const float* __restrict__ ref, double* __restrict__ err, uint32_t M, uint32_t N, uint32_t K,
           float descale, const uint16_t* __restrict__ g_lut, uint32_t tiles_n) {
-  constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32;
+  constexpr int kThreads = 64 * WM * WN;
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   constexpr int LDA = BK + kPad;                       // LDS row stride in bf16
   constexpr int CPR = BK / 16;                         // 16-code chunks per tile row
   constexpr int CA = BM * CPR / kThreads, CB = BN * CPR / kThreads;  // chunks per thread
@@ -82,7 +91,7 @@ k_gemm_nt(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __
   __bf16* Bs = As + 2 * BM * LDA;                                          // [2][BN][LDA]
 
   const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-  const uint32_t wm = wave >> 1, wn = wave & 1u;
+  const uint32_t wm = wave / WN, wn = wave % WN;
   const uint32_t tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x - tile_m * tiles_n;
   const uint32_t m0 = tile_m * BM, n0 = tile_n * BN;
 
@@ -100,13 +109,13 @@ k_gemm_nt(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __
     for (int i = 0; i < CA; ++i) {
       const uint32_t q = tid + i * kThreads, r = q / CPR, kc = q % CPR;
       const uint32_t row = m0 + r, k = k0 + kc * 16;
-      ra[i] = (row < M && k < K) ? *reinterpret_cast<const uint4*>(A + (size_t)row * K + k) : make_uint4(0u, 0u, 0u, 0u);
+      ra[i] = load_chunk(A, row, M, k, K);
     }
 #pragma unroll
     for (int i = 0; i < CB; ++i) {
       const uint32_t q = tid + i * kThreads, r = q / CPR, kc = q % CPR;
       const uint32_t row = n0 + r, k = k0 + kc * 16;
-      rb[i] = (row < N && k < K) ? *reinterpret_cast<const uint4*>(B + (size_t)row * K + k) : make_uint4(0u, 0u, 0u, 0u);
+      rb[i] = load_chunk(B, row, N, k, K);
     }
   };
   auto store_tiles = [&](int buf) {
@@ -139,7 +148,7 @@ k_gemm_nt(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __
   const uint32_t frag_row = lane & 31u, frag_k = (lane >> 5) * 8u;
   for (uint32_t kt = 0; kt < nk; ++kt) {
     const int buf = (int)(kt & 1u);
-    if (kt + 1 < nk) load_tiles((kt + 1) * BK);
+    load_tiles((kt + 1) * BK);  // past the last tile this reads zeros (k >= K) and is never used
     const __bf16* a_base = As + ((size_t)buf * BM + wm * TM * 32 + frag_row) * LDA + frag_k;
     const __bf16* b_base = Bs + ((size_t)buf * BN + wn * TN * 32 + frag_row) * LDA + frag_k;
 #pragma unroll
@@ -155,7 +164,7 @@ k_gemm_nt(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) store_tiles(buf ^ 1);
+    store_tiles(buf ^ 1);
     __syncthreads();
   }
 
@@ -249,29 +258,29 @@ static hif8_status gemm_init(const uint16_t** lut_out, int* cus_out) {
   return HIF8_OK;
 }
 
-template <int TM, int TN, int BK>
+template <int WM, int WN, int TM, int TN, int BK>
 constexpr size_t smem_bytes() {
-  return 256 * kLutCopies * 4 + (size_t)2 * (2 * TM * 32 + 2 * TN * 32) * (BK + kPad) * 2;
+  return 256 * kLutCopies * 4 + (size_t)2 * (WM * TM * 32 + WN * TN * 32) * (BK + kPad) * 2;
 }
 
-template <int TM, int TN, int BK, int EPI>
+template <int WM, int WN, int TM, int TN, int BK, int EPI>
 static hif8_status launch_tiled(const uint8_t* A, const uint8_t* B, void* out, const float* ref, double* err,
                                 uint32_t M, uint32_t N, uint32_t K, float descale, const uint16_t* lut,
                                 hipStream_t st) {
-  constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32;
-  constexpr size_t smem = smem_bytes<TM, TN, BK>();
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+  constexpr size_t smem = smem_bytes<WM, WN, TM, TN, BK>();
   static bool attr_set[kMaxDevices] = {};
   int dev = 0;
   if (!hip_ok(hipGetDevice(&dev))) return HIF8_ERR_HIP;
   if (!attr_set[dev]) {
-    if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt<TM, TN, BK, EPI>),
+    if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt<WM, WN, TM, TN, BK, EPI>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem)))
       return HIF8_ERR_HIP;
     attr_set[dev] = true;
   }
   const uint32_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   if ((uint64_t)tiles_m * tiles_n > 0x7FFFFFFFull) return HIF8_ERR_ARG;
-  hipLaunchKernelGGL((k_gemm_nt<TM, TN, BK, EPI>), dim3(tiles_m * tiles_n), dim3(kThreads), smem, st, A, B, out, ref,
+  hipLaunchKernelGGL((k_gemm_nt<WM, WN, TM, TN, BK, EPI>), dim3(tiles_m * tiles_n), dim3(64 * WM * WN), smem, st, A, B, out, ref,
                      err, M, N, K, descale, lut, tiles_n);
   return finish_launch();
 }
@@ -302,10 +311,67 @@ static hif8_status gemm_dispatch(const uint8_t* A, const uint8_t* B, void* out, 
     return finish_launch();
   }
   int variant = g_gemm_variant;
-  if (variant == 0) variant = (M * N >= (size_t)256 * 256 * 128) ? 2 : 1;  // big tiles once they fill the chip
-  if (variant == 2) return launch_tiled<4, 4, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
-  if (variant == 3) return launch_tiled<4, 2, 64, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
-  return launch_tiled<2, 2, 64, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
+  if (variant == 0)  // 256 x 256 tiles once there is one for every compute unit, else 128 x 128
+    variant = (((M + 255) / 256) * ((N + 255) / 256) >= (size_t)cus) ? 4 : 1;
+  if (variant == 2) return launch_tiled<2, 2, 4, 4, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
+  if (variant == 3) return launch_tiled<2, 2, 4, 2, 64, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
+  if (variant == 4) return launch_tiled<2, 4, 4, 2, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
+  if (variant == 5) return launch_tiled<2, 4, 2, 2, 64, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
+  return launch_tiled<2, 2, 2, 2, 64, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
+}
+
+// position of the smallest finite entry of err[rows * cols] -> best[0] = e_row_lo + row,
+// best[1] = e_col_lo + col (first minimum in row-major order; {e_row_lo, e_col_lo} if none is finite)
+__global__ void k_argmin_pair(const double* __restrict__ err, int rows, int cols, int e_row_lo, int e_col_lo,
+                              int32_t* __restrict__ best) {
+  if (blockIdx.x != 0 || threadIdx.x != 0) return;
+  int bi = 0;
+  double bv = INFINITY;
+  for (int i = 0; i < rows * cols; ++i) {
+    const double v = err[i];
+    if (v < bv) { bv = v; bi = i; }  // NaN and +Inf never compare below
+  }
+  best[0] = e_row_lo + bi / cols;
+  best[1] = e_col_lo + bi % cols;
+}
+
+// Algorithm 1 for one layer: casts at every scale of the search square, then one error GEMM per pair.
+template <int SRCK>
+static hif8_status calibrate_layer(const void* a, const void* w, const float* o_ref, size_t M, size_t N, size_t K,
+                                   int ea_lo, int ea_count, int ew_lo, int ew_count, uint32_t mode, void* workspace,
+                                   size_t workspace_bytes, double* d_err, int32_t* d_best, hipStream_t st) {
+  if (!valid_mode(mode)) return HIF8_ERR_MODE;
+  if (ea_count < 1 || ew_count < 1 || ea_count > 64 || ew_count > 64 || ea_lo < -60 || ew_lo < -60 ||
+      ea_lo + ea_count - 1 > 60 || ew_lo + ew_count - 1 > 60)
+    return HIF8_ERR_ARG;
+  if (!a || !w || !o_ref || !workspace || !d_err) return HIF8_ERR_NULL;
+  if (M == 0 || N == 0 || K == 0) return HIF8_ERR_ARG;
+  const size_t a_bytes = (M * K + 15) / 16 * 16, w_bytes = (N * K + 15) / 16 * 16;  // keep every code matrix 16-byte aligned
+  if (workspace_bytes < a_bytes * ea_count + w_bytes * ew_count || !aligned_to(workspace, 16)) return HIF8_ERR_ARG;
+  uint8_t* ws_a = reinterpret_cast<uint8_t*>(workspace);
+  uint8_t* ws_w = ws_a + a_bytes * ea_count;
+  hif8_status s = launch_fill_u32(reinterpret_cast<uint32_t*>(d_err), 0u, 2u * (uint32_t)(ea_count * ew_count), st);
+  if (s != HIF8_OK) return s;
+  for (int i = 0; i < ea_count; ++i) {
+    s = hif8conv::conv_encode<SRCK>(a, ws_a + a_bytes * i, M * K, std::ldexp(1.0f, ea_lo + i), nullptr, nullptr, mode, st);
+    if (s != HIF8_OK) return s;
+  }
+  for (int j = 0; j < ew_count; ++j) {
+    s = hif8conv::conv_encode<SRCK>(w, ws_w + w_bytes * j, N * K, std::ldexp(1.0f, ew_lo + j), nullptr, nullptr, mode, st);
+    if (s != HIF8_OK) return s;
+  }
+  for (int i = 0; i < ea_count; ++i) {
+    for (int j = 0; j < ew_count; ++j) {
+      s = gemm_dispatch<EPI_ERR>(ws_a + a_bytes * i, ws_w + w_bytes * j, nullptr, o_ref, d_err + (size_t)i * ew_count + j,
+                                 M, N, K, std::ldexp(1.0f, ea_lo + i), std::ldexp(1.0f, ew_lo + j), st);
+      if (s != HIF8_OK) return s;
+    }
+  }
+  if (d_best) {
+    hipLaunchKernelGGL(k_argmin_pair, dim3(1), dim3(64), 0, st, d_err, ea_count, ew_count, ea_lo, ew_lo, d_best);
+    return finish_launch();
+  }
+  return HIF8_OK;
 }
 
 }  // namespace hif8gemm
@@ -315,10 +381,28 @@ using namespace hif8gemm;
 extern "C" {
 
 hif8_status hif8_gemm_set_variant(int variant) {
-  if (variant < 0 || variant > 3) return HIF8_ERR_ARG;
+  if (variant < 0 || variant > 5) return HIF8_ERR_ARG;
   g_gemm_variant = variant;
   return HIF8_OK;
 }
+
+size_t hif8_calibrate_workspace_bytes(size_t M, size_t N, size_t K, int ea_count, int ew_count) {
+  if (ea_count < 0 || ew_count < 0) return 0;
+  return (M * K + 15) / 16 * 16 * (size_t)ea_count + (N * K + 15) / 16 * 16 * (size_t)ew_count;
+}
+
+#define HIF8_DEFINE_CALIBRATE(SFX, T, KIND)                                                                       \
+  hif8_status hif8_calibrate_layer_##SFX(const T* a, const T* w, const float* o_ref, size_t M, size_t N,          \
+                                         size_t K, int ea_lo, int ea_count, int ew_lo, int ew_count,              \
+                                         uint32_t mode, void* workspace, size_t workspace_bytes, double* d_err,   \
+                                         int32_t* d_best_or_null, hif8_stream_t stream) {                         \
+    return calibrate_layer<KIND>(a, w, o_ref, M, N, K, ea_lo, ea_count, ew_lo, ew_count, mode, workspace,         \
+                                 workspace_bytes, d_err, d_best_or_null, (hipStream_t)stream);                    \
+  }
+HIF8_DEFINE_CALIBRATE(f32, float, kSrcF32)
+HIF8_DEFINE_CALIBRATE(bf16, uint16_t, kSrcBF16)
+HIF8_DEFINE_CALIBRATE(f16, uint16_t, kSrcF16)
+#undef HIF8_DEFINE_CALIBRATE
 
 hif8_status hif8_gemm_f32(const uint8_t* a_codes, const uint8_t* b_codes, float* out, size_t M, size_t N, size_t K,
                           float scale_a, float scale_b, hif8_stream_t stream) {

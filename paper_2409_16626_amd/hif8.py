@@ -106,6 +106,10 @@ _SIGS = {
     "hif8_gemm_f16": ([_vp, _vp, _vp, _sz, _sz, _sz, _f, _f, _vp], _i),
     "hif8_gemm_sqerr": ([_vp, _vp, _vp, _sz, _sz, _sz, _f, _f, _vp, _vp], _i),
     "hif8_gemm_set_variant": ([_i], _i),
+    "hif8_calibrate_workspace_bytes": ([_sz, _sz, _sz, _i, _i], _sz),
+    "hif8_calibrate_layer_f32": ([_vp, _vp, _vp, _sz, _sz, _sz, _i, _i, _i, _i, _u32, _vp, _sz, _vp, _vp, _vp], _i),
+    "hif8_calibrate_layer_bf16": ([_vp, _vp, _vp, _sz, _sz, _sz, _i, _i, _i, _i, _u32, _vp, _sz, _vp, _vp, _vp], _i),
+    "hif8_calibrate_layer_f16": ([_vp, _vp, _vp, _sz, _sz, _sz, _i, _i, _i, _i, _u32, _vp, _sz, _vp, _vp, _vp], _i),
     "hif8_set_tuning": ([_i, _i], _i),
     "hif8_get_tuning": ([_i], _i),
     "hif8_diag_stream": ([_vp, _vp, _sz, _i, _vp], _i),
@@ -393,6 +397,26 @@ def hif8_gemm_sqerr(a_codes, b_codes, ref, M, N, K, scale_a, scale_b, d_err, str
 
 def hif8_gemm_set_variant(variant):
     _check(lib.hif8_gemm_set_variant(variant))
+
+
+def hif8_calibrate_workspace_bytes(M, N, K, ea_count=10, ew_count=10):
+    return lib.hif8_calibrate_workspace_bytes(M, N, K, ea_count, ew_count)
+
+
+def _def_calibrate(sfx):
+    fn = getattr(lib, "hif8_calibrate_layer_" + sfx)
+
+    def calibrate_layer(a, w, o_ref, M, N, K, ea_lo, ea_count, ew_lo, ew_count, rounding_mode, workspace,
+                        workspace_bytes, d_err, d_best=None, stream=None):
+        _check(fn(_ptr(a), _ptr(w), _ptr(o_ref), M, N, K, ea_lo, ea_count, ew_lo, ew_count, rounding_mode,
+                  _ptr(workspace), workspace_bytes, _ptr(d_err), _ptr(d_best), _stream(stream)))
+
+    return calibrate_layer
+
+
+hif8_calibrate_layer_f32 = _def_calibrate("f32")
+hif8_calibrate_layer_bf16 = _def_calibrate("bf16")
+hif8_calibrate_layer_f16 = _def_calibrate("f16")
 
 
 def hif8_set_tuning(key, value):
