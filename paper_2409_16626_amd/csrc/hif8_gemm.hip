@@ -35,8 +35,11 @@ typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
 
 enum : int { EPI_F32 = 0, EPI_BF16 = 1, EPI_F16 = 2, EPI_ERR = 3 };
 
-constexpr int kPad = 8;           // bf16 elements of padding per LDS row (16 bytes)
-constexpr int kLutCopies = 32;    // one copy of the code -> bf16 table per LDS bank
+#ifndef HIF8_GEMM_PAD
+#define HIF8_GEMM_PAD 8
+#endif
+constexpr int kPad = HIF8_GEMM_PAD;  // bf16 elements of padding per LDS row
+constexpr int kLutCopies = 64;    // one copy of the code -> bf16 table per lane (64 LDS banks)
 
 // code -> bfloat16 pattern (the top half of the binary32 pattern; exact for every code)
 static __device__ __attribute__((aligned(16))) uint16_t g_bf16_lut[256];
@@ -95,39 +98,39 @@ k_gemm_nt(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __
   const uint32_t tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x - tile_m * tiles_n;
   const uint32_t m0 = tile_m * BM, n0 = tile_n * BN;
 
-  // replicated table: entry (code, copy) at dword code * 32 + copy; a lane reads copy lane % 32
+  // replicated table: entry (code, copy) at dword code * 64 + copy; lane l reads copy l
   for (uint32_t i = tid; i < 256u * kLutCopies; i += kThreads) {
     const uint32_t v = g_lut[i / kLutCopies];
     lut32[i] = v | (v << 16);
   }
   const uint16_t* lut16 = reinterpret_cast<const uint16_t*>(lut32) + 2 * (lane & (kLutCopies - 1));
 
-  // this thread's chunks of the A and B tiles: chunk q -> row q / CPR, 16-code column q % CPR
-  uint4 ra[CA], rb[CB];
-  auto load_tiles = [&](uint32_t k0) {
+  // this thread's chunks of the A and B tiles: chunk q -> row q / CPR, 16-code column q % CPR.
+  // Two register sets: one holds the codes of the tile being expanded into LDS during this K step,
+  // the other receives the loads for the tile after it, so a load has a whole K step to arrive.
+  uint4 ra[2][CA], rb[2][CB];
+  auto load_tiles = [&](int set, uint32_t k0) {
 #pragma unroll
     for (int i = 0; i < CA; ++i) {
       const uint32_t q = tid + i * kThreads, r = q / CPR, kc = q % CPR;
-      const uint32_t row = m0 + r, k = k0 + kc * 16;
-      ra[i] = load_chunk(A, row, M, k, K);
+      ra[set][i] = load_chunk(A, m0 + r, M, k0 + kc * 16, K);
     }
 #pragma unroll
     for (int i = 0; i < CB; ++i) {
       const uint32_t q = tid + i * kThreads, r = q / CPR, kc = q % CPR;
-      const uint32_t row = n0 + r, k = k0 + kc * 16;
-      rb[i] = load_chunk(B, row, N, k, K);
+      rb[set][i] = load_chunk(B, n0 + r, N, k0 + kc * 16, K);
     }
   };
-  auto store_tiles = [&](int buf) {
+  auto store_tiles = [&](int set, int buf) {
 #pragma unroll
     for (int i = 0; i < CA; ++i) {
       const uint32_t q = tid + i * kThreads, r = q / CPR, kc = q % CPR;
-      decode_chunk_to_lds(ra[i], lut16, reinterpret_cast<uint4*>(As + ((size_t)buf * BM + r) * LDA + kc * 16));
+      decode_chunk_to_lds(ra[set][i], lut16, reinterpret_cast<uint4*>(As + ((size_t)buf * BM + r) * LDA + kc * 16));
     }
 #pragma unroll
     for (int i = 0; i < CB; ++i) {
       const uint32_t q = tid + i * kThreads, r = q / CPR, kc = q % CPR;
-      decode_chunk_to_lds(rb[i], lut16, reinterpret_cast<uint4*>(Bs + ((size_t)buf * BN + r) * LDA + kc * 16));
+      decode_chunk_to_lds(rb[set][i], lut16, reinterpret_cast<uint4*>(Bs + ((size_t)buf * BN + r) * LDA + kc * 16));
     }
   };
 
@@ -139,16 +142,11 @@ k_gemm_nt(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-  const uint32_t nk = (K + BK - 1) / BK;
-  load_tiles(0);
-  __syncthreads();  // table staged
-  store_tiles(0);
-  __syncthreads();
-
   const uint32_t frag_row = lane & 31u, frag_k = (lane >> 5) * 8u;
-  for (uint32_t kt = 0; kt < nk; ++kt) {
-    const int buf = (int)(kt & 1u);
-    load_tiles((kt + 1) * BK);  // past the last tile this reads zeros (k >= K) and is never used
+  // one K step: MFMAs on LDS buffer `buf` (tile kt) while the codes in register set `set`
+  // (tile kt + 1) are expanded into the other buffer and tile kt + 2 is requested from memory
+  auto k_step = [&](uint32_t kt, int buf, int set) {
+    load_tiles(set ^ 1, (kt + 2) * BK);  // past the last tile this reads zeros (k >= K); never used
     const __bf16* a_base = As + ((size_t)buf * BM + wm * TM * 32 + frag_row) * LDA + frag_k;
     const __bf16* b_base = Bs + ((size_t)buf * BN + wn * TN * 32 + frag_row) * LDA + frag_k;
 #pragma unroll
@@ -164,9 +162,23 @@ k_gemm_nt(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
-    store_tiles(buf ^ 1);
+    store_tiles(set, buf ^ 1);
     __syncthreads();
+  };
+
+  const uint32_t nk = (K + BK - 1) / BK;
+  load_tiles(0, 0);
+  load_tiles(1, BK);
+  __syncthreads();  // table staged
+  store_tiles(0, 0);
+  __syncthreads();
+  // register sets alternate with the LDS buffers: tile kt + 1 sits in set (kt + 1) & 1
+  uint32_t kt = 0;
+  for (; kt + 1 < nk; kt += 2) {
+    k_step(kt, 0, 1);
+    k_step(kt + 1, 1, 0);
   }
+  if (kt < nk) k_step(kt, 0, 1);
 
   // epilogue.  Accumulator element v of a 32 x 32 block: row = (v / 4) * 8 + (lane / 32) * 4 + v % 4,
   // column = lane % 32.
@@ -314,9 +326,9 @@ static hif8_status gemm_dispatch(const uint8_t* A, const uint8_t* B, void* out, 
   if (variant == 0)  // 256 x 256 tiles once there is one for every compute unit, else 128 x 128
     variant = (((M + 255) / 256) * ((N + 255) / 256) >= (size_t)cus) ? 4 : 1;
   if (variant == 2) return launch_tiled<2, 2, 4, 4, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
-  if (variant == 3) return launch_tiled<2, 2, 4, 2, 64, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
+  if (variant == 3) return launch_tiled<2, 2, 4, 2, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
   if (variant == 4) return launch_tiled<2, 4, 4, 2, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
-  if (variant == 5) return launch_tiled<2, 4, 2, 2, 64, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
+  if (variant == 5) return launch_tiled<4, 2, 2, 4, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
   return launch_tiled<2, 2, 2, 2, 64, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
 }
 
