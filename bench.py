@@ -227,7 +227,58 @@ def main():
         del h16
         w_ms, e_ms = timed(lambda i: hif8.hif8_diag_stream(acts[i % R], cds[i % R], m // 8, 8), K, W)
         extra["stream_r16_w8 (ceiling for BF16 encode)"] = rate(3 * m, e_ms)
-        del acts, fq, cds, a0
+        # calibration-side rows: scale sweep (10 power-of-two scales in one pass), per-channel cast
+        errs = torch.zeros(16, dtype=torch.float64, device=dev)
+        w_ms, e_ms = timed(lambda i: hif8.hif8_scale_sweep_bf16(acts[i % R], m, -4, 10, hif8.RM_TA, errs), K, W)
+        # per element and scale: multiply, shift, table byte, NaN fix-up (3), table dword, multiply,
+        # two conversions to fp64, fp64 subtract, fp64 fma (2 issue slots each on this chip) ~ 14 lane-ops
+        ops = 14.0 * 10 * m
+        extra["scale_sweep_bf16 C3 tensor, 10 scales"] = {
+            "ms": round(e_ms, 5), "elements_per_s": round(m / (e_ms * 1e-3), 0), "casts_per_s": round(10 * m / (e_ms * 1e-3), 0),
+            "bound": "alu", "lane_ops_per_s": round(ops / (e_ms * 1e-3), 0), "frac_of_39.3T_lane_ops": round(ops / (e_ms * 1e-3) / 39.3e12, 4)}
+        rows_c, cols_c = 11008, 4096
+        wmat = acts[0][:rows_c * cols_c]
+        for axis in (0, 1):
+            nch = rows_c if axis == 0 else cols_c
+            am_c = torch.zeros(nch, dtype=torch.float32, device=dev)
+            sc_c = torch.zeros(nch, 2, dtype=torch.float32, device=dev)
+
+            def per_channel(i):
+                hif8.hif8_amax_axis_bf16(wmat, rows_c, cols_c, axis, am_c)
+                hif8.hif8_scale_from_amax_n(am_c, sc_c, nch, hif8.MAX_FINITE, 1)
+                hif8.hif8_encode_axis_bf16(wmat, cds[i % R], rows_c, cols_c, axis, sc_c, hif8.RM_TA)
+
+            w_ms, e_ms = timed(per_channel, K, W)
+            extra["per-channel amax+scale+encode_bf16 [11008,4096] axis %d (5 B/elem with amax pass)" % axis] = rate(5 * rows_c * cols_c, e_ms)
+        del acts, fq, cds, a0, wmat
+        torch.cuda.empty_cache()
+
+        # simulated HiF8 GEMM on the matrix cores (codes -> bf16 in LDS -> MFMA), and Algorithm 1 for one layer
+        MFMA_PEAK = 2.5e15
+        for (gm, gn, gk) in ((8192, 8192, 8192), (8192, 11008, 4096)):
+            ca = torch.randint(8, 0x50, (gm, gk), dtype=torch.int32, device=dev).to(torch.uint8)
+            cb = torch.randint(8, 0x50, (gn, gk), dtype=torch.int32, device=dev).to(torch.uint8)
+            go = torch.empty(gm, gn, dtype=torch.bfloat16, device=dev)
+            w_ms, e_ms = timed(lambda i: hif8.hif8_gemm_bf16(ca, cb, go, gm, gn, gk, 1.0, 1.0), 20, 5)
+            fl = 2.0 * gm * gn * gk
+            extra["gemm_bf16 out, HiF8 operands, M=%d N=%d K=%d" % (gm, gn, gk)] = {
+                "ms": round(e_ms, 4), "TFLOP/s": round(fl / (e_ms * 1e-3) / 1e12, 1), "bound": "mfma",
+                "frac_of_2.5PFLOPs_bf16": round(fl / (e_ms * 1e-3) / MFMA_PEAK, 4)}
+            del ca, cb, go
+        lm, ln, lk = 2048, 4096, 4096
+        xa = torch.randn(lm, lk, device=dev).to(torch.bfloat16)
+        xw = (torch.randn(ln, lk, device=dev) * 0.02).to(torch.bfloat16)
+        oref = xa.float() @ xw.float().t()
+        nws = hif8.hif8_calibrate_workspace_bytes(lm, ln, lk, 10, 10)
+        ws = torch.empty(nws, dtype=torch.uint8, device=dev)
+        cerr = torch.zeros(100, dtype=torch.float64, device=dev)
+        best = torch.zeros(2, dtype=torch.int32, device=dev)
+        w_ms, e_ms = timed(lambda i: hif8.hif8_calibrate_layer_bf16(xa, xw, oref, lm, ln, lk, -4, 10, -4, 10, hif8.RM_TA,
+                                                                   ws, nws, cerr, best), 3, 1)
+        extra["calibrate_layer_bf16 (Algorithm 1, 10x10 scales) M=%d N=%d K=%d" % (lm, ln, lk)] = {
+            "ms": round(e_ms, 3), "TFLOP/s over the 100 GEMMs": round(100 * 2.0 * lm * ln * lk / (e_ms * 1e-3) / 1e12, 1),
+            "best_Ea_Ew": best.cpu().tolist()}
+        del xa, xw, oref, ws
         torch.cuda.empty_cache()
 
         # C4: gradient tensor, 2^30 FP32, TA and HR

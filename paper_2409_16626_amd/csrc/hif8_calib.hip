@@ -127,11 +127,14 @@ k_scale_sweep_elem(const void* __restrict__ src, size_t n, int e_lo, int count, 
 // 16-byte vector straddles two rows; otherwise the element kernels below do the same work.
 //
 // axis 0: a workgroup owns one chunk of one row (block index -> row, chunk).
-// axis 1: a workgroup owns a strip of blockDim.x * VE columns and a run of rows; each lane keeps
-//         its VE columns (and their scales) for the whole run, loads stay coalesced along rows.
+// axis 1: a workgroup owns a strip of 64 * VE columns and a run of rows, its wavefronts taking
+//         every fourth row; each lane keeps its VE columns (and their scales) for the whole run,
+//         loads stay coalesced along rows (1 KiB per wavefront and row).
 // ------------------------------------------------------------------------------------
 constexpr int kAxBlock = 256;
 constexpr int kAxUnroll = 4;  // axis 0: 16-byte vectors per lane per chunk
+constexpr int kAxWaves = kAxBlock / 64;
+constexpr int kAxRowsInFlight = 4;  // axis 1: rows loaded per lane before any is used
 
 template <int SRCK>
 __global__ void __launch_bounds__(kAxBlock)
@@ -147,30 +150,55 @@ k_amax_rows(const void* __restrict__ src, uint32_t cols_vec, uint32_t chunks, ui
   block_max_to_global(fold_amax<SRCK>(m), out + row);
 }
 
+// columns: the four wavefronts of a workgroup share a strip of 64 column vectors and take every
+// fourth row of the workgroup's run of rows, four rows in flight per lane; their maxima are
+// combined in LDS so that only one atomic per column leaves the workgroup
+template <int SRCK>
+__device__ __forceinline__ uint4 colmax(const uint4& m, const uint4& v) {
+  uint4 o;
+  if constexpr (SRCK == kSrcF32) {
+    o.x = umax(m.x, v.x & 0x7FFFFFFFu); o.y = umax(m.y, v.y & 0x7FFFFFFFu);
+    o.z = umax(m.z, v.z & 0x7FFFFFFFu); o.w = umax(m.w, v.w & 0x7FFFFFFFu);
+  } else {
+    o.x = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, m.x), __builtin_bit_cast(u16x2_t, v.x & 0x7FFF7FFFu)));
+    o.y = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, m.y), __builtin_bit_cast(u16x2_t, v.y & 0x7FFF7FFFu)));
+    o.z = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, m.z), __builtin_bit_cast(u16x2_t, v.z & 0x7FFF7FFFu)));
+    o.w = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, m.w), __builtin_bit_cast(u16x2_t, v.w & 0x7FFF7FFFu)));
+  }
+  return o;
+}
+
 template <int SRCK>
 __global__ void __launch_bounds__(kAxBlock)
 k_amax_cols(const void* __restrict__ src, uint32_t rows, uint32_t cols_vec, uint32_t strips,
             uint32_t rows_per_wg, uint32_t* __restrict__ out) {
   constexpr int VE = vec_elems<SRCK>();
+  __shared__ uint4 part[kAxWaves][64];
+  const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
   const uint32_t rchunk = blockIdx.x / strips, strip = blockIdx.x - rchunk * strips;
-  const uint32_t cv = strip * kAxBlock + threadIdx.x;
-  if (cv >= cols_vec) return;
+  const uint32_t cv = strip * 64u + lane;
+  const bool active = cv < cols_vec;
   const uint32_t r0 = rchunk * rows_per_wg;
   const uint32_t r1 = min(rows, r0 + rows_per_wg);
   const uint4* __restrict__ p = reinterpret_cast<const uint4*>(src) + cv;
   uint4 m = make_uint4(0u, 0u, 0u, 0u);  // FP32: four magnitudes; 16-bit: eight packed 15-bit magnitudes
-  for (uint32_t r = r0; r < r1; ++r) {
-    const uint4 v = ld_stream(p + (size_t)r * cols_vec);
-    if constexpr (SRCK == kSrcF32) {
-      m.x = umax(m.x, v.x & 0x7FFFFFFFu); m.y = umax(m.y, v.y & 0x7FFFFFFFu);
-      m.z = umax(m.z, v.z & 0x7FFFFFFFu); m.w = umax(m.w, v.w & 0x7FFFFFFFu);
-    } else {
-      m.x = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, m.x), __builtin_bit_cast(u16x2_t, v.x & 0x7FFF7FFFu)));
-      m.y = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, m.y), __builtin_bit_cast(u16x2_t, v.y & 0x7FFF7FFFu)));
-      m.z = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, m.z), __builtin_bit_cast(u16x2_t, v.z & 0x7FFF7FFFu)));
-      m.w = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, m.w), __builtin_bit_cast(u16x2_t, v.w & 0x7FFF7FFFu)));
+  if (active) {
+    for (uint32_t r = r0 + wv; r < r1; r += kAxWaves * kAxRowsInFlight) {
+      uint4 v[kAxRowsInFlight];
+#pragma unroll
+      for (int j = 0; j < kAxRowsInFlight; ++j) {
+        const uint32_t rr = r + j * kAxWaves;
+        v[j] = rr < r1 ? ld_stream(p + (size_t)rr * cols_vec) : make_uint4(0u, 0u, 0u, 0u);
+      }
+#pragma unroll
+      for (int j = 0; j < kAxRowsInFlight; ++j) m = colmax<SRCK>(m, v[j]);
     }
   }
+  part[wv][lane] = m;
+  __syncthreads();
+  if (wv != 0 || !active) return;
+#pragma unroll
+  for (int w = 1; w < kAxWaves; ++w) m = colmax<SRCK>(m, part[w][lane]);  // masks are no-ops on magnitudes
   uint32_t* o = out + (size_t)cv * VE;
   auto put = [&](int j, uint32_t bits) { if (bits) atomicMax(o + j, bits); };
   if constexpr (SRCK == kSrcF32) {
@@ -239,8 +267,9 @@ k_encode_cols(const void* __restrict__ src, uint8_t* __restrict__ dst, uint32_t 
   if (IMPL == IMPL_HR) stage_hr_table(hrt, mode);
   __syncthreads();
   constexpr int VE = vec_elems<SRCK>();
+  const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
   const uint32_t rchunk = blockIdx.x / strips, strip = blockIdx.x - rchunk * strips;
-  const uint32_t cv = strip * kAxBlock + threadIdx.x;
+  const uint32_t cv = strip * 64u + lane;
   if (cv >= cols_vec) return;
   float sc[VE];
 #pragma unroll
@@ -248,9 +277,8 @@ k_encode_cols(const void* __restrict__ src, uint8_t* __restrict__ dst, uint32_t 
   const uint32_t r0 = rchunk * rows_per_wg;
   const uint32_t r1 = min(rows, r0 + rows_per_wg);
   const uint4* __restrict__ p = reinterpret_cast<const uint4*>(src) + cv;
-  for (uint32_t r = r0; r < r1; ++r) {
+  auto encode_row = [&](uint32_t r, const uint4& v) {
     const size_t idx = (size_t)r * cols_vec + cv;
-    const uint4 v = ld_stream(p + (size_t)r * cols_vec);
     const uint64_t e0 = (uint64_t)idx * VE;
     if constexpr (SRCK == kSrcF32) {
       const uint32_t c0 = encode_one<IMPL, SRCK>(scaled_bits(v.x, sc[0]), ctx, e0);
@@ -268,6 +296,19 @@ k_encode_cols(const void* __restrict__ src, uint8_t* __restrict__ dst, uint32_t 
         o[j >> 1] |= (c0 | (c1 << 8)) << (16 * (j & 1));
       }
       st_stream(reinterpret_cast<uint2*>(dst) + idx, make_uint2(o[0], o[1]));
+    }
+  };
+  for (uint32_t r = r0 + wv; r < r1; r += kAxWaves * kAxRowsInFlight) {
+    uint4 v[kAxRowsInFlight];
+#pragma unroll
+    for (int j = 0; j < kAxRowsInFlight; ++j) {
+      const uint32_t rr = r + j * kAxWaves;
+      if (rr < r1) v[j] = ld_stream(p + (size_t)rr * cols_vec);
+    }
+#pragma unroll
+    for (int j = 0; j < kAxRowsInFlight; ++j) {
+      const uint32_t rr = r + j * kAxWaves;
+      if (rr < r1) encode_row(rr, v[j]);
     }
   }
 }
@@ -318,8 +359,9 @@ k_decode_cols(const uint8_t* __restrict__ src, void* __restrict__ dst, uint32_t 
   stage_dec_lut(dec, g_dec);
   __syncthreads();
   constexpr int VE = vec_elems<DSTK>();
+  const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
   const uint32_t rchunk = blockIdx.x / strips, strip = blockIdx.x - rchunk * strips;
-  const uint32_t cv = strip * kAxBlock + threadIdx.x;
+  const uint32_t cv = strip * 64u + lane;
   if (cv >= cols_vec) return;
   float inv[VE];
 #pragma unroll
@@ -327,23 +369,37 @@ k_decode_cols(const uint8_t* __restrict__ src, void* __restrict__ dst, uint32_t 
   const uint32_t r0 = rchunk * rows_per_wg;
   const uint32_t r1 = min(rows, r0 + rows_per_wg);
   uint4* __restrict__ d4 = reinterpret_cast<uint4*>(dst);
-  for (uint32_t r = r0; r < r1; ++r) {
-    const size_t idx = (size_t)r * cols_vec + cv;
-    uint4 o;
-    if constexpr (DSTK == kSrcF32) {
-      const uint32_t w = ld_stream(reinterpret_cast<const uint32_t*>(src) + idx);
-      o.x = descale_bits(w, dec, inv[0]);
-      o.y = descale_bits(w >> 8, dec, inv[1]);
-      o.z = descale_bits(w >> 16, dec, inv[2]);
-      o.w = descale_bits(w >> 24, dec, inv[3]);
-    } else {
-      const uint2 w = ld_stream(reinterpret_cast<const uint2*>(src) + idx);
-      o.x = narrow2<DSTK>(descale_bits(w.x, dec, inv[0]), descale_bits(w.x >> 8, dec, inv[1]));
-      o.y = narrow2<DSTK>(descale_bits(w.x >> 16, dec, inv[2]), descale_bits(w.x >> 24, dec, inv[3]));
-      o.z = narrow2<DSTK>(descale_bits(w.y, dec, inv[4]), descale_bits(w.y >> 8, dec, inv[5]));
-      o.w = narrow2<DSTK>(descale_bits(w.y >> 16, dec, inv[6]), descale_bits(w.y >> 24, dec, inv[7]));
+  for (uint32_t r = r0 + wv; r < r1; r += kAxWaves * kAxRowsInFlight) {
+    uint2 w[kAxRowsInFlight];
+#pragma unroll
+    for (int j = 0; j < kAxRowsInFlight; ++j) {
+      const uint32_t rr = r + j * kAxWaves;
+      if (rr < r1) {
+        const size_t idx = (size_t)rr * cols_vec + cv;
+        if constexpr (DSTK == kSrcF32) w[j] = make_uint2(ld_stream(reinterpret_cast<const uint32_t*>(src) + idx), 0u);
+        else w[j] = ld_stream(reinterpret_cast<const uint2*>(src) + idx);
+      }
     }
-    st_stream(d4 + idx, o);
+#pragma unroll
+    for (int j = 0; j < kAxRowsInFlight; ++j) {
+      const uint32_t rr = r + j * kAxWaves;
+      if (rr < r1) {
+        const size_t idx = (size_t)rr * cols_vec + cv;
+        uint4 o;
+        if constexpr (DSTK == kSrcF32) {
+          o.x = descale_bits(w[j].x, dec, inv[0]);
+          o.y = descale_bits(w[j].x >> 8, dec, inv[1]);
+          o.z = descale_bits(w[j].x >> 16, dec, inv[2]);
+          o.w = descale_bits(w[j].x >> 24, dec, inv[3]);
+        } else {
+          o.x = narrow2<DSTK>(descale_bits(w[j].x, dec, inv[0]), descale_bits(w[j].x >> 8, dec, inv[1]));
+          o.y = narrow2<DSTK>(descale_bits(w[j].x >> 16, dec, inv[2]), descale_bits(w[j].x >> 24, dec, inv[3]));
+          o.z = narrow2<DSTK>(descale_bits(w[j].y, dec, inv[4]), descale_bits(w[j].y >> 8, dec, inv[5]));
+          o.w = narrow2<DSTK>(descale_bits(w[j].y >> 16, dec, inv[6]), descale_bits(w[j].y >> 24, dec, inv[7]));
+        }
+        st_stream(d4 + idx, o);
+      }
+    }
   }
 }
 
@@ -423,12 +479,14 @@ bool plan_axis(size_t rows, size_t cols, int cus, bool aligned, AxisPlan* p) {
   p->cols_vec = (uint32_t)(cols / VE);
   const uint32_t per_chunk = kAxBlock * kAxUnroll;
   p->chunks = (p->cols_vec + per_chunk - 1) / per_chunk;
-  p->strips = (p->cols_vec + kAxBlock - 1) / kAxBlock;
-  // axis 1: enough row chunks to give every CU several workgroups, at least 8 rows each
-  uint32_t want = (uint32_t)((size_t)cus * 8 / (p->strips ? p->strips : 1));
+  p->strips = (p->cols_vec + 63) / 64;
+  // axis 1: enough row chunks to give every CU several workgroups, at least 64 rows each (one
+  // atomic per column and workgroup in amax), in multiples of what the lanes keep in flight
+  uint32_t want = (uint32_t)((size_t)cus * 6 / (p->strips ? p->strips : 1));
   if (want < 1) want = 1;
   uint32_t rpw = (uint32_t)((rows + want - 1) / want);
-  if (rpw < 8) rpw = 8;
+  if (rpw < 64) rpw = 64;
+  rpw = (rpw + kAxWaves * kAxRowsInFlight - 1) / (kAxWaves * kAxRowsInFlight) * (kAxWaves * kAxRowsInFlight);
   p->rows_per_wg = rpw;
   p->row_chunks = (uint32_t)((rows + rpw - 1) / rpw);
   if ((uint64_t)rows * p->chunks > 0x7FFFFFFFull || (uint64_t)p->row_chunks * p->strips > 0x7FFFFFFFull) return false;

@@ -12,7 +12,8 @@
 //                  Simplified SR in every binade is the same kernel with another threshold clamp.
 //   encode, TE   : differs from TA only at exact ties, which need the low 19 bits to be zero;
 //                  a second 8 KiB table holds the TE code of those patterns.
-//   encode, SR   : standard SR (comparison mode): integer encoder with a hashed threshold per element.
+//   encode, SR   : standard SR (comparison mode): a hashed threshold per element is added below the
+//                  kept mantissa bits, the sum truncated, then the same byte lookup.
 //   decode       : 256-entry binary32 table staged in LDS, one multiply by 1/scale.
 //   fake-quant   : encode and decode fused; the value never leaves registers.
 //   amax         : unsigned max of magnitude patterns; DPP reduction inside a wavefront,
@@ -39,7 +40,7 @@ enum : int { IMPL_TA_LUT = 0, IMPL_TA_ALU = 1, IMPL_HR = 2, IMPL_TE = 3, IMPL_SR
 
 template <int IMPL>
 constexpr uint32_t lut_bytes() {
-  return IMPL == IMPL_TE ? 16384u : (IMPL == IMPL_TA_ALU || IMPL == IMPL_SR) ? 16u : 8192u;
+  return IMPL == IMPL_TE ? 16384u : IMPL == IMPL_TA_ALU ? 16u : 8192u;
 }
 template <int SRCK>
 constexpr int vec_elems() { return SRCK == kSrcF32 ? 4 : 8; }  // elements per 16-byte source vector
@@ -77,12 +78,14 @@ template <int IMPL, int SRCK>
 __device__ __forceinline__ uint32_t encode_one(uint32_t ybits, const EncCtx& c, uint64_t elem) {
   if constexpr (IMPL == IMPL_TA_ALU) {
     return encode_alu<false, SRCK>(ybits, c.mode);
-  } else if constexpr (IMPL == IMPL_SR) {
-    return encode_any<SRCK>(ybits, c.mode, sr_threshold(c.seed, elem));
   } else {
     uint32_t code;
     if constexpr (IMPL == IMPL_TA_LUT) {
       code = c.lut[ybits >> 19];
+    } else if constexpr (IMPL == IMPL_SR) {
+      // standard SR: add the hashed threshold bits below the kept part, truncate, then the byte
+      const uint32_t r = sr_round_bits(ybits & 0x7FFFFFFFu, sr_threshold(c.seed, elem)) | (ybits & 0x80000000u);
+      code = c.lut[r >> 19];
     } else if constexpr (IMPL == IMPL_TE) {
       // a tie needs every bit below the rounding bit to be zero; otherwise TE rounds as TA
       code = c.lut[(ybits >> 19) + ((ybits & 0x7FFFFu) ? 0u : 8192u)];
@@ -238,7 +241,7 @@ k_encode(const void* __restrict__ src, uint8_t* __restrict__ dst, size_t n, floa
           st_stream(reinterpret_cast<uint2*>(dst) + idx, encode8_16<IMPL, SRCK>(v, scale, ctx, idx * VE));
       },
       [&]() {
-        if (IMPL != IMPL_TA_ALU && IMPL != IMPL_SR) {
+        if (IMPL != IMPL_TA_ALU) {
           stage_enc_lut<IMPL>(lut, g_lut, mode);
           if (IMPL == IMPL_HR) stage_hr_table(hrt, mode);
           __syncthreads();

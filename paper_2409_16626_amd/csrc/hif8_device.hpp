@@ -214,6 +214,18 @@ __device__ __forceinline__ uint32_t round_mag_any(uint32_t rm, uint32_t a, uint3
   return ((a >> d) + (carry ? 1u : 0u)) << d;
 }
 
+// Standard SR, streaming form: rounded pattern of magnitude `a` (not NaN), to be looked up in
+// the TA table (the result is on the HiF8 grid, where TA is the identity; exponent 104 stands
+// for "carried out of the underflow step" as in round_mag_any() and the TA table reads it as
+// 2^-22).  With d discarded bits the carry rule (t32 >> (32 - d)) < discarded is the carry out
+// of discarded + ((2^d - 1) - (t32 >> (32 - d))), i.e. adding the complemented top threshold
+// bits below the kept part and truncating.
+__device__ __forceinline__ uint32_t sr_round_bits(uint32_t a, uint32_t t32) {
+  if (a < kBitsTwoM22) return round_mag_any<kSrcF32>(kRmSR, a, a, t32);
+  const uint32_t d = 23u - kept_bits(a >> 23);  // 20..23
+  return (a + ((~t32) >> (32u - d))) & ~((1u << d) - 1u);
+}
+
 // Full encode of one binary32 pattern under any rounding method (element-wise paths).
 template <int SRCK>
 __device__ __forceinline__ uint32_t encode_any(uint32_t ybits, uint32_t mode, uint32_t t32) {

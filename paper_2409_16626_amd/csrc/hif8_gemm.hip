@@ -53,6 +53,16 @@ __global__ void k_build_gemm_lut() {
 __device__ __forceinline__ void decode_chunk_to_lds(const uint4& c, const uint16_t* lut16, uint4* dst) {
   const uint32_t w[4] = {c.x, c.y, c.z, c.w};
   uint32_t o[8];
+#ifdef HIF8_GEMM_FAKE_DECODE  // experiment only: skeleton speed without the table lookups (wrong results)
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    o[2 * j] = (w[j] & 0xFFu) | ((w[j] & 0xFF00u) << 8) | 0x3F003F00u;
+    o[2 * j + 1] = ((w[j] >> 16) & 0xFFu) | ((w[j] >> 8) & 0xFF0000u) | 0x3F003F00u;
+  }
+  dst[0] = make_uint4(o[0], o[1], o[2], o[3]);
+  dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
+  return;
+#endif
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     u16x2 p0, p1;
@@ -67,6 +77,14 @@ __device__ __forceinline__ void decode_chunk_to_lds(const uint4& c, const uint16
   dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
 }
 
+// Batched launches: pair p = blockIdx.y uses A + (p / nb) * a_stride, B + (p % nb) * b_stride,
+// err[p], and descale 2^-(e_base + p / nb + p % nb).  nb == 0: a single GEMM.
+struct Batch {
+  uint32_t nb;
+  int e_base;
+  size_t a_stride, b_stride;
+};
+
 // 16 codes of row `row` at column k; rows / columns outside the matrix read as zero codes.  The
 // address is clamped instead of branching so that the loop body stays one basic block.
 __device__ __forceinline__ uint4 load_chunk(const uint8_t* __restrict__ P, uint32_t row, uint32_t rows,
@@ -80,7 +98,15 @@ template <int WM, int WN, int TM, int TN, int BK, int EPI>
 __global__ void __launch_bounds__(64 * WM * WN)
 k_gemm_nt(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __restrict__ out,
           const float* __restrict__ ref, double* __restrict__ err, uint32_t M, uint32_t N, uint32_t K,
-          float descale, const uint16_t* __restrict__ g_lut, uint32_t tiles_n) {
+          float descale, const uint16_t* __restrict__ g_lut, uint32_t tiles_n, Batch batch) {
+  // batched form (the scale search of Algorithm 1): blockIdx.y = pair (i, j) of code matrices
+  if (batch.nb != 0u) {
+    const uint32_t bi = blockIdx.y / batch.nb, bj = blockIdx.y - bi * batch.nb;
+    A += (size_t)bi * batch.a_stride;
+    B += (size_t)bj * batch.b_stride;
+    err += blockIdx.y;
+    descale = pow2f(-(batch.e_base + (int)bi + (int)bj));
+  }
   constexpr int kThreads = 64 * WM * WN;
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   constexpr int LDA = BK + kPad;                       // LDS row stride in bf16
@@ -278,7 +304,7 @@ constexpr size_t smem_bytes() {
 template <int WM, int WN, int TM, int TN, int BK, int EPI>
 static hif8_status launch_tiled(const uint8_t* A, const uint8_t* B, void* out, const float* ref, double* err,
                                 uint32_t M, uint32_t N, uint32_t K, float descale, const uint16_t* lut,
-                                hipStream_t st) {
+                                hipStream_t st, const Batch& batch = Batch{0u, 0, 0, 0}, uint32_t pairs = 1) {
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   constexpr size_t smem = smem_bytes<WM, WN, TM, TN, BK>();
   static bool attr_set[kMaxDevices] = {};
@@ -292,8 +318,8 @@ static hif8_status launch_tiled(const uint8_t* A, const uint8_t* B, void* out, c
   }
   const uint32_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   if ((uint64_t)tiles_m * tiles_n > 0x7FFFFFFFull) return HIF8_ERR_ARG;
-  hipLaunchKernelGGL((k_gemm_nt<WM, WN, TM, TN, BK, EPI>), dim3(tiles_m * tiles_n), dim3(64 * WM * WN), smem, st, A, B, out, ref,
-                     err, M, N, K, descale, lut, tiles_n);
+  hipLaunchKernelGGL((k_gemm_nt<WM, WN, TM, TN, BK, EPI>), dim3(tiles_m * tiles_n, pairs), dim3(64 * WM * WN), smem, st,
+                     A, B, out, ref, err, M, N, K, descale, lut, tiles_n, batch);
   return finish_launch();
 }
 
@@ -372,6 +398,16 @@ static hif8_status calibrate_layer(const void* a, const void* w, const float* o_
     s = hif8conv::conv_encode<SRCK>(w, ws_w + w_bytes * j, N * K, std::ldexp(1.0f, ew_lo + j), nullptr, nullptr, mode, st);
     if (s != HIF8_OK) return s;
   }
+  if ((K % 16) == 0 && M <= 0x7FFFFFFFu && N <= 0x7FFFFFFFu && K <= 0x7FFFFFFFu) {
+    // all pairs in one launch: the grid's second dimension runs over the search square
+    const uint16_t* lut = nullptr;
+    s = gemm_init(&lut, nullptr);
+    if (s != HIF8_OK) return s;
+    const Batch batch{(uint32_t)ew_count, ea_lo + ew_lo, a_bytes, w_bytes};
+    s = launch_tiled<4, 2, 2, 4, 32, EPI_ERR>(ws_a, ws_w, nullptr, o_ref, d_err, (uint32_t)M, (uint32_t)N, (uint32_t)K,
+                                              1.0f, lut, st, batch, (uint32_t)(ea_count * ew_count));
+    if (s != HIF8_OK) return s;
+  } else
   for (int i = 0; i < ea_count; ++i) {
     for (int j = 0; j < ew_count; ++j) {
       s = gemm_dispatch<EPI_ERR>(ws_a + a_bytes * i, ws_w + w_bytes * j, nullptr, o_ref, d_err + (size_t)i * ew_count + j,

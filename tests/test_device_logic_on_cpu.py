@@ -43,6 +43,13 @@ def _enc(lib, ybits, mode, srck, seed=0):
                                        ctypes.c_size_t(ybits.size), ctypes.c_uint32(mode), ctypes.c_int(srck))
         bad = np.nonzero(out != out2)[0]
         assert bad.size == 0, [(hex(ybits[i]), hex(out[i]), hex(out2[i])) for i in bad[:8]]
+    if (mode & 0xF) == orc.RM_SR:
+        # the streaming kernels' add-and-truncate form of standard SR must agree as well
+        out2 = np.empty(ybits.shape, np.uint8)
+        lib.devfn_encode_bits_sr_table(ybits.ctypes.data_as(ctypes.c_void_p), out2.ctypes.data_as(ctypes.c_void_p),
+                                       ctypes.c_size_t(ybits.size), ctypes.c_uint32(mode), ctypes.c_uint64(seed))
+        bad = np.nonzero(out != out2)[0]
+        assert bad.size == 0, [(hex(ybits[i]), hex(out[i]), hex(out2[i])) for i in bad[:8]]
     return out
 
 
