@@ -382,10 +382,11 @@ hif8_status hif8_als_update(hif8_als_state* st, int found_overflow);
  *   hif8_gemm_sqerr   no output matrix: *d_err += sum (out[m, n] - ref[m, n])^2 in fp64
  *                     (ref: [M, N] FP32; the caller clears *d_err) -- the "Quantization Error"
  *                     step of Algorithm 1.
- *   hif8_gemm_set_variant  0 = choose the tile shape by problem size (default); 1..5 = fixed
- *                     workgroup tile / wavefront layouts (for benchmarking): 1 = 128 x 128 x 64
- *                     (4 wavefronts), 2 = 256 x 256 x 32 (4), 3 = 256 x 128 x 32 (4),
- *                     4 = 256 x 256 x 32 (8, as 2 x 4), 5 = 256 x 256 x 32 (8, as 4 x 2).
+ *   hif8_gemm_set_variant  0 = choose the tile shape by problem size (default: 5 when there is a
+ *                     256 x 256 tile for every compute unit, else 6); 1..6 = fixed workgroup tile /
+ *                     wavefront layouts (for benchmarking): 1 = 128 x 128 x 64 (4 wavefronts),
+ *                     2 = 256 x 256 x 32 (4), 3 = 256 x 128 x 32 (4), 4 = 256 x 256 x 32 (8, as 2 x 4),
+ *                     5 = 256 x 256 x 32 (8, as 4 x 2), 6 = 128 x 128 x 32 (4, two workgroups per CU).
  */
 hif8_status hif8_gemm_f32(const uint8_t* a_codes, const uint8_t* b_codes, float* out, size_t M,
                           size_t N, size_t K, float scale_a, float scale_b, hif8_stream_t stream);

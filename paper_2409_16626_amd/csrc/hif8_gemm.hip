@@ -39,7 +39,7 @@ enum : int { EPI_F32 = 0, EPI_BF16 = 1, EPI_F16 = 2, EPI_ERR = 3 };
 #define HIF8_GEMM_PAD 8
 #endif
 constexpr int kPad = HIF8_GEMM_PAD;  // bf16 elements of padding per LDS row
-constexpr int kLutCopies = 64;    // one copy of the code -> bf16 table per lane (64 LDS banks)
+constexpr int kLutCopies = 32;    // one copy of the code -> bf16 table per LDS bank
 
 // code -> bfloat16 pattern (the top half of the binary32 pattern; exact for every code)
 static __device__ __attribute__((aligned(16))) uint16_t g_bf16_lut[256];
@@ -53,16 +53,6 @@ __global__ void k_build_gemm_lut() {
 __device__ __forceinline__ void decode_chunk_to_lds(const uint4& c, const uint16_t* lut16, uint4* dst) {
   const uint32_t w[4] = {c.x, c.y, c.z, c.w};
   uint32_t o[8];
-#ifdef HIF8_GEMM_FAKE_DECODE  // experiment only: skeleton speed without the table lookups (wrong results)
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    o[2 * j] = (w[j] & 0xFFu) | ((w[j] & 0xFF00u) << 8) | 0x3F003F00u;
-    o[2 * j + 1] = ((w[j] >> 16) & 0xFFu) | ((w[j] >> 8) & 0xFF0000u) | 0x3F003F00u;
-  }
-  dst[0] = make_uint4(o[0], o[1], o[2], o[3]);
-  dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
-  return;
-#endif
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     u16x2 p0, p1;
@@ -124,38 +114,43 @@ k_gemm_nt(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __
   const uint32_t tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x - tile_m * tiles_n;
   const uint32_t m0 = tile_m * BM, n0 = tile_n * BN;
 
-  // replicated table: entry (code, copy) at dword code * 64 + copy; lane l reads copy l
+  // replicated table: entry (code, copy) at dword code * 32 + copy; lane l reads copy l % 32
   for (uint32_t i = tid; i < 256u * kLutCopies; i += kThreads) {
     const uint32_t v = g_lut[i / kLutCopies];
     lut32[i] = v | (v << 16);
   }
   const uint16_t* lut16 = reinterpret_cast<const uint16_t*>(lut32) + 2 * (lane & (kLutCopies - 1));
 
-  // this thread's chunks of the A and B tiles: chunk q -> row q / CPR, 16-code column q % CPR.
+  // this thread's chunks of the A and B tiles.  Chunk q -> (row, 16-code column): 8 consecutive
+  // lanes take 8 consecutive rows of the same column, so that their 16-byte LDS stores (row
+  // stride 16 bytes more than a power of two) fall into 8 different groups of 4 banks; the lanes
+  // 8 apart take the neighbouring columns, so a wavefront still loads whole 16 * CPR byte runs.
+  auto chunk_row = [](uint32_t q) { return 8u * (q / (8u * CPR)) + (q & 7u); };
+  auto chunk_col = [](uint32_t q) { return (q >> 3) % CPR; };
   // Two register sets: one holds the codes of the tile being expanded into LDS during this K step,
   // the other receives the loads for the tile after it, so a load has a whole K step to arrive.
   uint4 ra[2][CA], rb[2][CB];
   auto load_tiles = [&](int set, uint32_t k0) {
 #pragma unroll
     for (int i = 0; i < CA; ++i) {
-      const uint32_t q = tid + i * kThreads, r = q / CPR, kc = q % CPR;
+      const uint32_t q = tid + i * kThreads, r = chunk_row(q), kc = chunk_col(q);
       ra[set][i] = load_chunk(A, m0 + r, M, k0 + kc * 16, K);
     }
 #pragma unroll
     for (int i = 0; i < CB; ++i) {
-      const uint32_t q = tid + i * kThreads, r = q / CPR, kc = q % CPR;
+      const uint32_t q = tid + i * kThreads, r = chunk_row(q), kc = chunk_col(q);
       rb[set][i] = load_chunk(B, n0 + r, N, k0 + kc * 16, K);
     }
   };
   auto store_tiles = [&](int set, int buf) {
 #pragma unroll
     for (int i = 0; i < CA; ++i) {
-      const uint32_t q = tid + i * kThreads, r = q / CPR, kc = q % CPR;
+      const uint32_t q = tid + i * kThreads, r = chunk_row(q), kc = chunk_col(q);
       decode_chunk_to_lds(ra[set][i], lut16, reinterpret_cast<uint4*>(As + ((size_t)buf * BM + r) * LDA + kc * 16));
     }
 #pragma unroll
     for (int i = 0; i < CB; ++i) {
-      const uint32_t q = tid + i * kThreads, r = q / CPR, kc = q % CPR;
+      const uint32_t q = tid + i * kThreads, r = chunk_row(q), kc = chunk_col(q);
       decode_chunk_to_lds(rb[set][i], lut16, reinterpret_cast<uint4*>(Bs + ((size_t)buf * BN + r) * LDA + kc * 16));
     }
   };
@@ -349,12 +344,13 @@ static hif8_status gemm_dispatch(const uint8_t* A, const uint8_t* B, void* out, 
     return finish_launch();
   }
   int variant = g_gemm_variant;
-  if (variant == 0)  // 256 x 256 tiles once there is one for every compute unit, else 128 x 128
-    variant = (((M + 255) / 256) * ((N + 255) / 256) >= (size_t)cus) ? 4 : 1;
+  if (variant == 0)  // 256 x 256 tiles once there is one for every compute unit, else 128 x 128 (two workgroups per CU)
+    variant = (((M + 255) / 256) * ((N + 255) / 256) >= (size_t)cus) ? 5 : 6;
   if (variant == 2) return launch_tiled<2, 2, 4, 4, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
   if (variant == 3) return launch_tiled<2, 2, 4, 2, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
   if (variant == 4) return launch_tiled<2, 4, 4, 2, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
   if (variant == 5) return launch_tiled<4, 2, 2, 4, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
+  if (variant == 6) return launch_tiled<2, 2, 2, 2, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
   return launch_tiled<2, 2, 2, 2, 64, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
 }
 
@@ -429,7 +425,7 @@ using namespace hif8gemm;
 extern "C" {
 
 hif8_status hif8_gemm_set_variant(int variant) {
-  if (variant < 0 || variant > 5) return HIF8_ERR_ARG;
+  if (variant < 0 || variant > 6) return HIF8_ERR_ARG;
   g_gemm_variant = variant;
   return HIF8_OK;
 }
