@@ -67,6 +67,8 @@ def main():
     ap.add_argument("--pmc", action="store_true",
                     help="counter-collection mode for rocprofv3 --pmc: 5 plain 16-byte copies of a known "
                          "size, then 5 headline encode launches; no timing, no JSON")
+    ap.add_argument("--gemm-only", action="store_true",
+                    help="profiling mode: only the simulated HiF8 GEMM rows (25 launches of 8192^3), no headline")
     ap.add_argument("--tune", type=str, default="", help="block,wg_per_cu,unroll,ta_impl,tiles_per_wg,amax_nt (prefix allowed)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -86,6 +88,17 @@ def main():
         for k, v in enumerate(int(t) for t in args.tune.split(",")):
             hif8.hif8_set_tuning(k, v)
     tune = [hif8.hif8_get_tuning(k) for k in range(hif8.N_TUNE_KEYS)]
+
+    if args.gemm_only:
+        gm = gn = gk = 8192
+        ca = torch.randint(8, 0x50, (gm, gk), dtype=torch.int32, device=dev).to(torch.uint8)
+        cb = torch.randint(8, 0x50, (gn, gk), dtype=torch.int32, device=dev).to(torch.uint8)
+        go = torch.empty(gm, gn, dtype=torch.bfloat16, device=dev)
+        w_ms, e_ms = timed(lambda i: hif8.hif8_gemm_bf16(ca, cb, go, gm, gn, gk, 1.0, 1.0), 20, 5)
+        fl = 2.0 * gm * gn * gk
+        print(json.dumps({"gemm_bf16 M=N=K=8192": {"ms": round(e_ms, 4), "TFLOP/s": round(fl / (e_ms * 1e-3) / 1e12, 1),
+                                                   "frac_of_2.5PFLOPs_bf16": round(fl / (e_ms * 1e-3) / 2.5e15, 4)}}), flush=True)
+        return
 
     # ---------------- headline: C2 encode_f32, TA, scale 1 ----------------
     n = 1 << 26
