@@ -22,12 +22,36 @@ __device__ __forceinline__ double wave_sum_f64(double v) {
   return v;
 }
 
+// err[k] += the workgroup's sum of acc[k], k < count: wavefront sums by shuffles, across the
+// wavefronts through LDS, then ONE hardware fp64 atomic per scale and workgroup (thousands of
+// wavefronts adding to the same few addresses would otherwise serialise at the L2).
+// Every lane of the workgroup must call it.
+template <int KMAX>
+__device__ __forceinline__ void block_add_f64(const double (&acc)[KMAX], int count, double* __restrict__ err) {
+  __shared__ double part[kSweepBlock / 64][kSweepMax];
+  const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
+#pragma unroll
+  for (int k = 0; k < KMAX; ++k) {
+    if (k < count) {
+      const double w = wave_sum_f64(acc[k]);
+      if (lane == 0u) part[wv][k] = w;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < (uint32_t)count) {
+    double t = part[0][threadIdx.x];
+    for (uint32_t w = 1; w < blockDim.x / 64u; ++w) t += part[w][threadIdx.x];
+    unsafeAtomicAdd(err + threadIdx.x, t);
+  }
+}
+
 // err[k] += sum over this workgroup's elements of (x - value(Q(x * 2^(e_lo+k))) * 2^-(e_lo+k))^2.
 // The differences and squares are taken in fp64 (exact for every finite term), lane sums are
-// fp64, and each wavefront adds its total with one fp64 atomic per scale.
-template <int IMPL, int SRCK>
+// fp64, and each workgroup adds its total with one fp64 atomic per scale.
+// NSC: number of scales fixed at compile time (straight-line code), or 0: `count` at run time.
+template <int IMPL, int SRCK, int NSC>
 __global__ void __launch_bounds__(kSweepBlock)
-k_scale_sweep(const void* __restrict__ src, size_t n, int e_lo, int count, uint32_t mode, uint64_t seed,
+k_scale_sweep(const void* __restrict__ src, size_t n, int e_lo, int count_arg, uint32_t mode, uint64_t seed,
               const uint8_t* __restrict__ g_lut, const uint32_t* __restrict__ g_dec,
               double* __restrict__ err) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
@@ -40,21 +64,42 @@ k_scale_sweep(const void* __restrict__ src, size_t n, int e_lo, int count, uint3
   __syncthreads();
 
   constexpr int VE = vec_elems<SRCK>();
+  constexpr int KMAX = NSC ? NSC : kSweepMax;
+  const int count = NSC ? NSC : count_arg;
   const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(src);
   const size_t nvec = n >> vec_shift<SRCK>();
-  double acc[kSweepMax];
+  double acc[KMAX];
+  float sc[KMAX], isc[KMAX];
 #pragma unroll
-  for (int k = 0; k < kSweepMax; ++k) acc[k] = 0.0;
+  for (int k = 0; k < KMAX; ++k) {
+    acc[k] = 0.0;
+    sc[k] = pow2f(k < count ? e_lo + k : 0);
+    isc[k] = pow2f(k < count ? -(e_lo + k) : 0);
+  }
 
+  // one element at all scales, in stages so that the table reads of the scales are in flight
+  // together: casts, then descaled values, then the fp64 accumulation
   auto score = [&](uint32_t xb, uint64_t elem) {
     const double xd = (double)__uint_as_float(xb);
+    if constexpr (NSC != 0) {
+      uint32_t c[KMAX], q[KMAX];
 #pragma unroll
-    for (int k = 0; k < kSweepMax; ++k) {
-      if (k < count) {  // uniform across the grid
-        const float s = pow2f(e_lo + k), inv = pow2f(-(e_lo + k));
-        const uint32_t c = encode_one<IMPL, SRCK>(scaled_bits(xb, s), ctx, elem);
-        const double d = xd - (double)__uint_as_float(descale_bits(c, dec, inv));
+      for (int k = 0; k < KMAX; ++k) c[k] = encode_one<IMPL, SRCK>(scaled_bits(xb, sc[k]), ctx, elem);
+#pragma unroll
+      for (int k = 0; k < KMAX; ++k) q[k] = descale_bits(c[k], dec, isc[k]);
+#pragma unroll
+      for (int k = 0; k < KMAX; ++k) {
+        const double d = xd - (double)__uint_as_float(q[k]);
         acc[k] = fma(d, d, acc[k]);
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < KMAX; ++k) {
+        if (k < count) {  // uniform across the grid
+          const uint32_t c = encode_one<IMPL, SRCK>(scaled_bits(xb, sc[k]), ctx, elem);
+          const double d = xd - (double)__uint_as_float(descale_bits(c, dec, isc[k]));
+          acc[k] = fma(d, d, acc[k]);
+        }
       }
     }
   };
@@ -81,13 +126,7 @@ k_scale_sweep(const void* __restrict__ src, size_t n, int e_lo, int count, uint3
   const size_t t = nvec * VE + threadIdx.x;  // ragged tail, workgroup 0
   if (blockIdx.x == 0 && t < n) score(load_bits<SRCK>(src, t), t);
 
-#pragma unroll
-  for (int k = 0; k < kSweepMax; ++k) {
-    if (k < count) {
-      const double w = wave_sum_f64(acc[k]);
-      if ((threadIdx.x & 63u) == 0u) atomicAdd(err + k, w);
-    }
-  }
+  block_add_f64<KMAX>(acc, count, err);
 }
 
 // element-per-lane form for sources that are not 16-byte aligned
@@ -112,13 +151,7 @@ k_scale_sweep_elem(const void* __restrict__ src, size_t n, int e_lo, int count, 
       }
     }
   }
-#pragma unroll
-  for (int k = 0; k < kSweepMax; ++k) {
-    if (k < count) {
-      const double w = wave_sum_f64(acc[k]);
-      if ((threadIdx.x & 63u) == 0u) atomicAdd(err + k, w);
-    }
-  }
+  block_add_f64<kSweepMax>(acc, count, err);
 }
 
 // ------------------------------------------------------------------------------------
@@ -454,15 +487,22 @@ hif8_status scale_sweep(const void* src, size_t n, int e_lo, int count, uint32_t
     return finish_launch();
   }
   const size_t nvec = n >> vec_shift<SRCK>();
-  size_t wgs = (nvec + kSweepBlock - 1) / kSweepBlock;
-  const size_t cap = (size_t)cus * 8;
-  if (wgs > cap) wgs = cap;
-  if (wgs == 0) wgs = 1;
+  hif8_status rc = HIF8_OK;
   dispatch_impl_only(impl_no_alu(mode), [&](auto impl_c) {
-    hipLaunchKernelGGL((k_scale_sweep<decltype(impl_c)::value, SRCK>), dim3((unsigned)wgs), dim3(kSweepBlock), 0,
-                       st, src, n, e_lo, count, mode, seed, tb.enc_lut, tb.dec_lut, d_err);
+    constexpr int IMPL = decltype(impl_c)::value;
+    size_t wgs = (nvec + kSweepBlock - 1) / kSweepBlock;
+    const size_t cap = (size_t)cus * 8;  // grid-stride: a few workgroups per CU
+    if (wgs > cap) wgs = cap;
+    if (wgs == 0) wgs = 1;
+    // the paper's search range (10 scales) gets straight-line code; other counts a run-time bound
+    if (count == 10)
+      hipLaunchKernelGGL((k_scale_sweep<IMPL, SRCK, 10>), dim3((unsigned)wgs), dim3(kSweepBlock), 0, st, src, n,
+                         e_lo, count, mode, seed, tb.enc_lut, tb.dec_lut, d_err);
+    else
+      hipLaunchKernelGGL((k_scale_sweep<IMPL, SRCK, 0>), dim3((unsigned)wgs), dim3(kSweepBlock), 0, st, src, n,
+                         e_lo, count, mode, seed, tb.enc_lut, tb.dec_lut, d_err);
   });
-  return finish_launch();
+  return rc != HIF8_OK ? rc : finish_launch();
 }
 
 struct AxisPlan {

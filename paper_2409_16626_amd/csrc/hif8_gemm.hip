@@ -229,7 +229,7 @@ k_gemm_nt(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __
   if constexpr (EPI == EPI_ERR) {
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) e2 += __shfl_xor(e2, off, 64);
-    if (lane == 0) atomicAdd(err, e2);
+    if (lane == 0) unsafeAtomicAdd(err, e2);  // hardware fp64 add at the L2, no compare-and-swap loop
   }
 }
 
@@ -259,7 +259,7 @@ k_gemm_nt_simple(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, v
   if constexpr (EPI == EPI_ERR) {
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) e2 += __shfl_xor(e2, off, 64);
-    if ((threadIdx.x & 63u) == 0u) atomicAdd(err, e2);
+    if ((threadIdx.x & 63u) == 0u) unsafeAtomicAdd(err, e2);
   }
 }
 
