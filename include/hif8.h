@@ -433,7 +433,7 @@ hif8_status hif8_calibrate_layer_f16(const uint16_t* a, const uint16_t* w, const
 
 /*
  * Launch-shape tuning knobs (process-wide; for benchmarking and profiling).  The first,
- * second, third and fifth default to -1 = "use the built-in shape of each kernel family".
+ * second, third, fifth and sixth default to -1 = "use the built-in choice of each kernel family".
  *   HIF8_TUNE_BLOCK        threads per workgroup of the streaming kernels (64..1024, multiple of 64)
  *   HIF8_TUNE_WG_PER_CU    persistent mode: workgroups launched per compute unit (1..64)
  *   HIF8_TUNE_UNROLL       16-byte loads in flight per lane (1, 2, 4 or 8); a tile is
@@ -441,7 +441,10 @@ hif8_status hif8_calibrate_layer_f16(const uint16_t* a, const uint16_t* w, const
  *   HIF8_TUNE_TA_IMPL      0 = TA encode through the LDS lookup table, 1 = TA encode in ALU only
  *   HIF8_TUNE_TILES_PER_WG 0 = persistent grid (grid-stride over tiles); k >= 1 = one-shot grid in
  *                          which every workgroup handles k consecutive tiles (0..4096)
- *   HIF8_TUNE_AMAX_NT      1 = amax reads with non-temporal loads, 0 = ordinary loads
+ *   HIF8_TUNE_AMAX_NT      1 = amax reads with non-temporal loads, 0 = ordinary (cached) loads,
+ *                          -1 (default) = ordinary loads for tensors up to 192 MiB (a cast of the
+ *                          same tensor usually follows and then finds it in the last-level cache),
+ *                          non-temporal loads above
  * Returns HIF8_ERR_ARG for an unknown key or a value outside the stated range.
  */
 enum {

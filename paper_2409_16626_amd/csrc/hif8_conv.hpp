@@ -682,7 +682,11 @@ hif8_status conv_amax(const void* src, size_t n, float* d_amax, hipStream_t st) 
   const Shape shape = shape_for(FAM_AMAX);
   Walk walk;
   const dim3 grid(grid_for(nvec, cus, shape, &walk)), block(shape.block);
-  const bool nt = tune_amax_nt() != 0;
+  // amax is normally followed by a cast of the same tensor: ordinary (cached) loads leave a tensor
+  // that fits the 256 MB last-level cache there for the second pass; larger ones are streamed
+  const size_t bytes = n * (SRCK == kSrcF32 ? 4 : 2);
+  const int nt_knob = tune_amax_nt();
+  const bool nt = nt_knob < 0 ? bytes > ((size_t)192 << 20) : nt_knob != 0;
   dispatch_unroll(shape.unroll, [&](auto u_c) {
     constexpr int U = decltype(u_c)::value;
     if (nt) hipLaunchKernelGGL((k_amax<U, SRCK, true>), grid, block, 0, st, src, n, out, walk);

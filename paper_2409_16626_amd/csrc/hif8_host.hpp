@@ -33,7 +33,7 @@ enum Family { FAM_ENC32_TA, FAM_ENC32_HR, FAM_ENC16, FAM_FQ, FAM_DEC, FAM_AMAX, 
 
 Shape shape_for(Family f);
 int tune_ta_impl();   // 0 = table, 1 = ALU
-int tune_amax_nt();   // 1 = non-temporal loads in amax
+int tune_amax_nt();   // 1 = non-temporal loads in amax, 0 = cached loads, -1 = by tensor size
 uint64_t sr_seed();   // seed of the standard-SR threshold generator in effect now
 
 bool hip_ok(hipError_t e);  // records a failure for hif8_last_hip_error()

@@ -110,7 +110,7 @@ struct Tuning {
   int unroll = -1;
   int ta_impl = 0;
   int tiles_per_wg = -1;
-  int amax_nt = 1;
+  int amax_nt = -1;  // -1: by size
 };
 Tuning g_tune;
 std::atomic<uint64_t> g_sr_seed{0};
@@ -262,7 +262,7 @@ hif8_status hif8_set_tuning(int key, int value) {
       g_tune.tiles_per_wg = value;
       return HIF8_OK;
     case HIF8_TUNE_AMAX_NT:
-      if (value != 0 && value != 1) return HIF8_ERR_ARG;
+      if (value < -1 || value > 1) return HIF8_ERR_ARG;
       g_tune.amax_nt = value;
       return HIF8_OK;
     default:

@@ -78,7 +78,7 @@ def test_tuning_knobs():
     assert L.hif8_set_tuning(0, 100) == -5 and L.hif8_set_tuning(0, 2048) == -5
     assert L.hif8_set_tuning(1, 0) == -5 and L.hif8_set_tuning(2, 3) == -5
     assert L.hif8_set_tuning(3, 2) == -5 and L.hif8_set_tuning(9, 1) == -5
-    assert L.hif8_set_tuning(4, -2) == -5 and L.hif8_set_tuning(4, 5000) == -5 and L.hif8_set_tuning(5, 2) == -5
+    assert L.hif8_set_tuning(4, -2) == -5 and L.hif8_set_tuning(4, 5000) == -5 and L.hif8_set_tuning(5, 2) == -5 and L.hif8_set_tuning(5, -2) == -5
     assert L.hif8_get_tuning(9) == -1
     assert L.hif8_set_tuning(0, 256) == 0 and L.hif8_get_tuning(0) == 256
     for k, v in enumerate(saved):

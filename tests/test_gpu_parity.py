@@ -522,3 +522,4 @@ def test_non_default_stream(h):
         h.hif8_encode_f32(x, dst, x.numel(), 1.0, TA)
     s.synchronize()
     assert_same_bytes(dst.cpu().numpy(), orc.encode_f32(x.cpu().numpy(), 1.0, TA), "stream")
+
