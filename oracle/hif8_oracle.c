@@ -17,8 +17,7 @@
  *            Sec. 3.2 (simplified stochastic rounding SR14 / SR2 and hybrid
  *            rounding, Eq. (3)).
  *
- * Readings taken where the paper is silent or ambiguous (all also listed in
- * the design document of this repository):
+ * Readings taken where the paper is silent or ambiguous:
  *   - Em bit order: Se is the first (most significant) bit, magnitude bits
  *     follow (the only order that reproduces the Table 4 patterns).
  *   - Rounding in the denormal range, at the underflow edge and at the
