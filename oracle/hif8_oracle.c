@@ -243,6 +243,10 @@ uint32_t hif8o_sr_threshold(uint64_t seed, uint64_t index) {
 }
 static uint64_t g_sr_seed = 0;
 void hif8o_set_sr_seed(uint64_t seed) { g_sr_seed = seed; }
+/* index of the first element of the arrays passed to the array functions (so that a slice of a
+ * large tensor can be checked with the thresholds its elements have inside that tensor) */
+static uint64_t g_sr_index_base = 0;
+void hif8o_set_sr_index_base(uint64_t base) { g_sr_index_base = base; }
 
 uint8_t hif8o_encode_one_t(float y, uint32_t mode, int src_kind, uint32_t t32);
 uint8_t hif8o_encode_one(float y, uint32_t mode, int src_kind) {
@@ -428,7 +432,7 @@ void hif8o_encode_f32(const float *src, uint8_t *dst, size_t n, float scale, uin
 #pragma omp parallel for schedule(static)
   for (ptrdiff_t i = 0; i < (ptrdiff_t)n; ++i) {
     volatile float y = src[i] * scale;
-    dst[i] = hif8o_encode_one_t(y, mode, OSRC_F32, hif8o_sr_threshold(g_sr_seed, (uint64_t)i));
+    dst[i] = hif8o_encode_one_t(y, mode, OSRC_F32, hif8o_sr_threshold(g_sr_seed, g_sr_index_base + (uint64_t)i));
   }
 }
 
@@ -437,7 +441,7 @@ void hif8o_encode_bf16(const uint16_t *src, uint8_t *dst, size_t n, float scale,
 #pragma omp parallel for schedule(static)
   for (ptrdiff_t i = 0; i < (ptrdiff_t)n; ++i) {
     volatile float y = bf16_to_f32(src[i]) * scale;
-    dst[i] = hif8o_encode_one_t(y, mode, OSRC_BF16, hif8o_sr_threshold(g_sr_seed, (uint64_t)i));
+    dst[i] = hif8o_encode_one_t(y, mode, OSRC_BF16, hif8o_sr_threshold(g_sr_seed, g_sr_index_base + (uint64_t)i));
   }
 }
 
@@ -446,7 +450,7 @@ void hif8o_encode_f16(const uint16_t *src, uint8_t *dst, size_t n, float scale, 
 #pragma omp parallel for schedule(static)
   for (ptrdiff_t i = 0; i < (ptrdiff_t)n; ++i) {
     volatile float y = f16_to_f32(src[i]) * scale;
-    dst[i] = hif8o_encode_one_t(y, mode, OSRC_F16, hif8o_sr_threshold(g_sr_seed, (uint64_t)i));
+    dst[i] = hif8o_encode_one_t(y, mode, OSRC_F16, hif8o_sr_threshold(g_sr_seed, g_sr_index_base + (uint64_t)i));
   }
 }
 
@@ -472,7 +476,7 @@ void hif8o_fake_quant_f32(const float *src, float *dst, uint8_t *codes_or_null, 
 #pragma omp parallel for schedule(static)
   for (ptrdiff_t i = 0; i < (ptrdiff_t)n; ++i) {
     volatile float y = src[i] * scale;
-    uint8_t c = hif8o_encode_one_t(y, mode, OSRC_F32, hif8o_sr_threshold(g_sr_seed, (uint64_t)i));
+    uint8_t c = hif8o_encode_one_t(y, mode, OSRC_F32, hif8o_sr_threshold(g_sr_seed, g_sr_index_base + (uint64_t)i));
     if (codes_or_null) codes_or_null[i] = c;
     dst[i] = decode_descaled(c, inv);
   }
@@ -485,7 +489,7 @@ void hif8o_fake_quant_bf16(const uint16_t *src, uint16_t *dst, uint8_t *codes_or
 #pragma omp parallel for schedule(static)
   for (ptrdiff_t i = 0; i < (ptrdiff_t)n; ++i) {
     volatile float y = bf16_to_f32(src[i]) * scale;
-    uint8_t c = hif8o_encode_one_t(y, mode, OSRC_BF16, hif8o_sr_threshold(g_sr_seed, (uint64_t)i));
+    uint8_t c = hif8o_encode_one_t(y, mode, OSRC_BF16, hif8o_sr_threshold(g_sr_seed, g_sr_index_base + (uint64_t)i));
     if (codes_or_null) codes_or_null[i] = c;
     dst[i] = f32_to_bf16_rne(decode_descaled(c, inv));
   }
@@ -498,7 +502,7 @@ void hif8o_fake_quant_f16(const uint16_t *src, uint16_t *dst, uint8_t *codes_or_
 #pragma omp parallel for schedule(static)
   for (ptrdiff_t i = 0; i < (ptrdiff_t)n; ++i) {
     volatile float y = f16_to_f32(src[i]) * scale;
-    uint8_t c = hif8o_encode_one_t(y, mode, OSRC_F16, hif8o_sr_threshold(g_sr_seed, (uint64_t)i));
+    uint8_t c = hif8o_encode_one_t(y, mode, OSRC_F16, hif8o_sr_threshold(g_sr_seed, g_sr_index_base + (uint64_t)i));
     if (codes_or_null) codes_or_null[i] = c;
     dst[i] = f32_to_f16_rne(decode_descaled(c, inv));
   }
@@ -585,7 +589,7 @@ void hif8o_scale_sweep(const void *x, size_t n, int src_kind, int e_lo, int coun
     for (ptrdiff_t i = 0; i < (ptrdiff_t)n; ++i) {
       const float xi = load_as_f32(x, (size_t)i, src_kind);
       volatile float y = xi * s;
-      const uint8_t c = hif8o_encode_one_t(y, mode, src_kind, hif8o_sr_threshold(g_sr_seed, (uint64_t)i));
+      const uint8_t c = hif8o_encode_one_t(y, mode, src_kind, hif8o_sr_threshold(g_sr_seed, g_sr_index_base + (uint64_t)i));
       const double q = (double)decode_descaled(c, inv);
       const double d = (double)xi - q;
       acc += d * d;
@@ -623,7 +627,7 @@ void hif8o_encode_axis(const void *x, uint8_t *dst, size_t rows, size_t cols, in
     for (size_t c = 0; c < cols; ++c) {
       const size_t idx = (size_t)r * cols + c;
       volatile float y = load_as_f32(x, idx, src_kind) * scale[axis == 0 ? (size_t)r : c];
-      dst[idx] = hif8o_encode_one_t(y, mode, src_kind, hif8o_sr_threshold(g_sr_seed, (uint64_t)idx));
+      dst[idx] = hif8o_encode_one_t(y, mode, src_kind, hif8o_sr_threshold(g_sr_seed, g_sr_index_base + (uint64_t)idx));
     }
   }
 }

@@ -41,6 +41,7 @@ _lib.hif8o_encode_one_t.argtypes = [ctypes.c_float, ctypes.c_uint32, ctypes.c_in
 _lib.hif8o_sr_threshold.restype = ctypes.c_uint32
 _lib.hif8o_sr_threshold.argtypes = [ctypes.c_uint64, ctypes.c_uint64]
 _lib.hif8o_set_sr_seed.argtypes = [ctypes.c_uint64]
+_lib.hif8o_set_sr_index_base.argtypes = [ctypes.c_uint64]
 _lib.hif8o_widen_f16.argtypes = [_u16p, _f32p, ctypes.c_size_t]
 _lib.hif8o_narrow_f16.argtypes = [_f32p, _u16p, ctypes.c_size_t]
 _lib.hif8o_encode_f16.argtypes = [_u16p, _u8p, ctypes.c_size_t, ctypes.c_float, ctypes.c_uint32]
@@ -116,6 +117,11 @@ def sr_threshold(seed: int, index: int) -> int:
 def set_sr_seed(seed: int) -> None:
     """Seed of the standard-SR threshold generator used by the array functions."""
     _lib.hif8o_set_sr_seed(seed)
+
+
+def set_sr_index_base(base: int) -> None:
+    """Index that element 0 of the arrays passed to the array functions has (default 0)."""
+    _lib.hif8o_set_sr_index_base(base)
 
 
 def widen_f16(src):

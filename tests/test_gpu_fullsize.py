@@ -121,6 +121,36 @@ def test_c4_full(h, mode):
         assert int(codes[:1 << 26][x[:1 << 26] == 0].max().item()) == 0
 
 
+@pytest.mark.parametrize("mode", [orc.RM_TE, orc.RM_SSR, orc.RM_SR])
+def test_c4_full_comparison_modes(h, mode):
+    """The gradient tensor under the rounding methods the paper compares TA / HR with; sampled
+    blocks against the oracle (standard SR: with the thresholds the elements have at their place
+    in the 2^30-element tensor)."""
+    from paper_2409_16626_amd import workloads
+    n = 1 << 30
+    x = workloads.gradient_f32(n, dev())
+    codes = torch.empty(n, dtype=torch.uint8, device=dev())
+    seed = 0x1234ABCD5678
+    h.hif8_set_sr_seed(seed)
+    orc.set_sr_seed(seed)
+    try:
+        h.hif8_encode_f32(x, codes, n, 1.0, mode)
+        torch.cuda.synchronize()
+        for lo, hi in sample_blocks(n, 1024, 8192, 78):
+            orc.set_sr_index_base(lo)
+            want = orc.encode_f32(x[lo:hi].cpu().numpy(), 1.0, mode)
+            assert_same_bytes(codes[lo:hi].cpu().numpy(), want, "C4 block at %d mode %d" % (lo, mode))
+    finally:
+        orc.set_sr_index_base(0)
+        orc.set_sr_seed(0)
+        h.hif8_set_sr_seed(0)
+    # zero stays zero and the code histogram is dominated by the denormal binades, as for TA
+    z = codes[:1 << 26][x[:1 << 26] == 0]
+    assert int(z.max().item()) == 0
+    mag = codes[:1 << 26] & 0x7F
+    assert float(((mag >= 1) & (mag <= 7)).float().mean().item()) > 0.2
+
+
 def test_c5_full(h):
     from paper_2409_16626_amd import workloads
     arena, index = workloads.llm_weights_bf16(dev())
