@@ -69,6 +69,8 @@ def main():
                          "size, then 5 headline encode launches; no timing, no JSON")
     ap.add_argument("--gemm-only", action="store_true",
                     help="profiling mode: only the simulated HiF8 GEMM rows (25 launches of 8192^3), no headline")
+    ap.add_argument("--sweep-only", action="store_true",
+                    help="profiling mode: only the 10-scale sweep over the C3 tensor (25 launches), no headline")
     ap.add_argument("--tune", type=str, default="", help="block,wg_per_cu,unroll,ta_impl,tiles_per_wg,amax_nt (prefix allowed)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -98,6 +100,15 @@ def main():
         fl = 2.0 * gm * gn * gk
         print(json.dumps({"gemm_bf16 M=N=K=8192": {"ms": round(e_ms, 4), "TFLOP/s": round(fl / (e_ms * 1e-3) / 1e12, 1),
                                                    "frac_of_2.5PFLOPs_bf16": round(fl / (e_ms * 1e-3) / 2.5e15, 4)}}), flush=True)
+        return
+
+    if args.sweep_only:
+        a0 = workloads.activation_bf16(8192, 8192, dev).view(-1)
+        errs = torch.zeros(16, dtype=torch.float64, device=dev)
+        w_ms, e_ms = timed(lambda i: hif8.hif8_scale_sweep_bf16(a0, a0.numel(), -4, 10, hif8.RM_TA, errs), 20, 5)
+        print(json.dumps({"scale_sweep_bf16 2^26 elements x 10 scales": {
+            "ms": round(e_ms, 5), "casts_per_s": round(10 * a0.numel() / (e_ms * 1e-3), 0),
+            "mse_per_scale": [round(v / a0.numel(), 8) for v in errs[:10].cpu().tolist()]}}), flush=True)
         return
 
     # ---------------- headline: C2 encode_f32, TA, scale 1 ----------------
