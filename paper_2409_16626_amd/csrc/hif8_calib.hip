@@ -474,6 +474,7 @@ hif8_status scale_sweep(const void* src, size_t n, int e_lo, int count, uint32_t
   if (!valid_mode(mode)) return HIF8_ERR_MODE;
   if (count < 1 || count > kSweepMax || e_lo < -126 || e_lo + count - 1 > 126) return HIF8_ERR_ARG;
   if (!d_err || (!src && n != 0)) return HIF8_ERR_NULL;
+  if (!aligned_to(d_err, 8)) return HIF8_ERR_ARG;  // fp64 atomics need naturally aligned doubles
   int cus = 0;
   DevTables tb;
   hif8_status s = ensure_init(&cus, &tb);

@@ -332,6 +332,7 @@ static hif8_status gemm_dispatch(const uint8_t* A, const uint8_t* B, void* out, 
   if (M > 0x7FFFFFFFu || N > 0x7FFFFFFFu || K > 0x7FFFFFFFu) return HIF8_ERR_ARG;
   if ((!A || !B) && K != 0) return HIF8_ERR_NULL;
   if (EPI == EPI_ERR ? (!ref || !err) : !out) return HIF8_ERR_NULL;
+  if (EPI == EPI_ERR && !aligned_to(err, 8)) return HIF8_ERR_ARG;  // fp64 atomics need naturally aligned doubles
   const uint16_t* lut = nullptr;
   int cus = 0;
   hif8_status s = gemm_init(&lut, &cus);
@@ -379,6 +380,7 @@ static hif8_status calibrate_layer(const void* a, const void* w, const float* o_
       ea_lo + ea_count - 1 > 60 || ew_lo + ew_count - 1 > 60)
     return HIF8_ERR_ARG;
   if (!a || !w || !o_ref || !workspace || !d_err) return HIF8_ERR_NULL;
+  if (!aligned_to(d_err, 8) || (d_best && !aligned_to(d_best, 4))) return HIF8_ERR_ARG;
   if (M == 0 || N == 0 || K == 0) return HIF8_ERR_ARG;
   const size_t a_bytes = (M * K + 15) / 16 * 16, w_bytes = (N * K + 15) / 16 * 16;  // keep every code matrix 16-byte aligned
   if (workspace_bytes < a_bytes * ea_count + w_bytes * ew_count || !aligned_to(workspace, 16)) return HIF8_ERR_ARG;

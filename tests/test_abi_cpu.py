@@ -46,6 +46,18 @@ def test_argument_validation_happens_on_the_host():
     assert L.hif8_amax_f32(p, 16, None, None) == NULL
     assert L.hif8_scale_from_amax(None, p, 1.0, 0, None) == NULL
     assert L.hif8_scale_from_amax(p, p, -1.0, 0, None) == ARG
+    assert L.hif8_scale_sweep_f32(p, 16, -4, 10, 0, p + 4, None) == ARG       # misaligned doubles
+    assert L.hif8_scale_sweep_f32(p, 16, -4, 17, 0, p, None) == ARG
+    assert L.hif8_scale_sweep_bf16(p, 16, -4, 10, 7, p, None) == MODE
+    assert L.hif8_gemm_sqerr(p, p, p, 16, 16, 16, 1.0, 1.0, p + 4, None) == ARG
+    assert L.hif8_gemm_f32(p, p, None, 16, 16, 16, 1.0, 1.0, None) == NULL
+    assert L.hif8_gemm_f32(p, p, p, 16, 16, 16, 0.0, 1.0, None) == SCALE
+    assert L.hif8_gemm_f32(p, p, p, 0, 16, 16, 1.0, 1.0, None) == OK           # empty output: nothing to do
+    assert L.hif8_amax_axis_f32(p, 4, 4, 2, p, None) == ARG
+    assert L.hif8_encode_axis_bf16(p, p, 4, 4, 0, None, 0, None) == NULL
+    assert L.hif8_calibrate_layer_f32(p, p, p, 16, 16, 16, -4, 10, -4, 10, 0, p, 0, p, None, None) == ARG   # workspace too small
+    assert L.hif8_calibrate_layer_f32(p, p, p, 16, 16, 16, -4, 65, -4, 10, 0, p, 1 << 20, p, None, None) == ARG
+    assert L.hif8_calibrate_workspace_bytes(16, 32, 16, 10, 10) == 10 * 256 + 10 * 512
     assert L.hif8_diag_stream(p, p, 16, 5, None) == ARG
     assert L.hif8_diag_stream(p + 4, p, 16, 4, None) == ARG
 
