@@ -98,8 +98,17 @@ def main():
         go = torch.empty(gm, gn, dtype=torch.bfloat16, device=dev)
         w_ms, e_ms = timed(lambda i: hif8.hif8_gemm_bf16(ca, cb, go, gm, gn, gk, 1.0, 1.0), 20, 5)
         fl = 2.0 * gm * gn * gk
-        print(json.dumps({"gemm_bf16 M=N=K=8192": {"ms": round(e_ms, 4), "TFLOP/s": round(fl / (e_ms * 1e-3) / 1e12, 1),
-                                                   "frac_of_2.5PFLOPs_bf16": round(fl / (e_ms * 1e-3) / 2.5e15, 4)}}), flush=True)
+        res = {"gemm_bf16 M=N=K=8192": {"ms": round(e_ms, 4), "TFLOP/s": round(fl / (e_ms * 1e-3) / 1e12, 1),
+                                        "frac_of_2.5PFLOPs_bf16": round(fl / (e_ms * 1e-3) / 2.5e15, 4)}}
+        ld = hif8.hif8_expanded_ld(gk)
+        xa = torch.empty(gm, ld, dtype=torch.bfloat16, device=dev)
+        xb = torch.empty(gn, ld, dtype=torch.bfloat16, device=dev)
+        hif8.hif8_expand_bf16(ca, gm, gk, xa, ld)
+        hif8.hif8_expand_bf16(cb, gn, gk, xb, ld)
+        w_ms, e_ms = timed(lambda i: hif8.hif8_gemm_expanded_bf16(xa, xb, go, gm, gn, gk, ld, 1.0, 1.0), 20, 5)
+        res["gemm_expanded_bf16 M=N=K=8192"] = {"ms": round(e_ms, 4), "TFLOP/s": round(fl / (e_ms * 1e-3) / 1e12, 1),
+                                                "frac_of_2.5PFLOPs_bf16": round(fl / (e_ms * 1e-3) / 2.5e15, 4)}
+        print(json.dumps(res), flush=True)
         return
 
     if args.sweep_only:
@@ -277,7 +286,8 @@ def main():
         del acts, fq, cds, a0, wmat
         torch.cuda.empty_cache()
 
-        # simulated HiF8 GEMM on the matrix cores (codes -> bf16 in LDS -> MFMA), and Algorithm 1 for one layer
+        # simulated HiF8 GEMM on the matrix cores (code operands expanded in the kernel; operands expanded beforehand),
+        # and Algorithm 1 for one layer
         MFMA_PEAK = 2.5e15
         for (gm, gn, gk) in ((8192, 8192, 8192), (8192, 11008, 4096)):
             ca = torch.randint(8, 0x50, (gm, gk), dtype=torch.int32, device=dev).to(torch.uint8)
@@ -288,7 +298,23 @@ def main():
             extra["gemm_bf16 out, HiF8 operands, M=%d N=%d K=%d" % (gm, gn, gk)] = {
                 "ms": round(e_ms, 4), "TFLOP/s": round(fl / (e_ms * 1e-3) / 1e12, 1), "bound": "mfma",
                 "frac_of_2.5PFLOPs_bf16": round(fl / (e_ms * 1e-3) / MFMA_PEAK, 4)}
-            del ca, cb, go
+            # the same product on operands expanded to bfloat16 once (expansion timed separately, and together)
+            ld = hif8.hif8_expanded_ld(gk)
+            xa = torch.empty(gm, ld, dtype=torch.bfloat16, device=dev)
+            xb = torch.empty(gn, ld, dtype=torch.bfloat16, device=dev)
+
+            def expand_both(i):
+                hif8.hif8_expand_bf16(ca, gm, gk, xa, ld)
+                hif8.hif8_expand_bf16(cb, gn, gk, xb, ld)
+
+            w_ms, x_ms = timed(expand_both, 20, 5)
+            w_ms, e_ms = timed(lambda i: hif8.hif8_gemm_expanded_bf16(xa, xb, go, gm, gn, gk, ld, 1.0, 1.0), 20, 5)
+            extra["gemm_expanded_bf16 out, operands expanded to bf16 beforehand, M=%d N=%d K=%d" % (gm, gn, gk)] = {
+                "ms": round(e_ms, 4), "TFLOP/s": round(fl / (e_ms * 1e-3) / 1e12, 1), "bound": "mfma",
+                "frac_of_2.5PFLOPs_bf16": round(fl / (e_ms * 1e-3) / MFMA_PEAK, 4),
+                "expand_both_operands_ms": round(x_ms, 4), "expand_GB/s (3 B/elem)": round(3.0 * (gm + gn) * gk / (x_ms * 1e-3) / 1e9, 1),
+                "TFLOP/s incl. expansion": round(fl / ((e_ms + x_ms) * 1e-3) / 1e12, 1)}
+            del ca, cb, go, xa, xb
         lm, ln, lk = 2048, 4096, 4096
         xa = torch.randn(lm, lk, device=dev).to(torch.bfloat16)
         xw = (torch.randn(ln, lk, device=dev) * 0.02).to(torch.bfloat16)

@@ -400,6 +400,41 @@ hif8_status hif8_gemm_sqerr(const uint8_t* a_codes, const uint8_t* b_codes, cons
 hif8_status hif8_gemm_set_variant(int variant);
 
 /*
+ * The same GEMM on operands expanded to bfloat16 beforehand.  Every HiF8 value is exact in
+ * bfloat16, so a code matrix that takes part in several products (the 10 + 10 casts and 100
+ * products of Algorithm 1's search; a cast weight used by the forward and the backward GEMM of a
+ * training step, Sec. 5) is expanded once and the products then run without the decoder: tiles go
+ * from HBM straight into LDS and the kernel is faster than the code-operand one for
+ * matrix-core-bound shapes, at 2 bytes per operand element instead of 1.
+ *   hif8_expanded_ld(K)   row pitch (elements) of an expanded operand: K rounded up to a multiple of 64
+ *   hif8_expand_bf16      dst[r * ld + k] = bf16 pattern of value(codes[r * K + k]) for k < K and 0 for
+ *                         K <= k < ld.  codes: [rows, K] u8 device; dst: [rows, ld] u16 device, 16-byte
+ *                         aligned, caller-owned; ld a multiple of 64 and >= K.  (NaN / Inf codes expand
+ *                         to NaN / Inf and propagate through the product.)
+ *   hif8_gemm_expanded_*  out[m, n] = fl32( (sum_k a[m, k] * b[n, k]) * fl32(fl32(1/scale_a) * fl32(1/scale_b)) )
+ *                         a: [M, ld], b: [N, ld] u16 bfloat16 patterns as written by hif8_expand_bf16
+ *                         (16-byte aligned; the columns K .. ld-1 must hold zeros); out / ref / d_err as in
+ *                         hif8_gemm_*.  K >= 1; M, N < 2^31.  Same error bound as hif8_gemm_*; the summation
+ *                         order differs from that kernel's, so the two agree to within that bound, and
+ *                         exactly whenever every partial sum is exact in FP32.
+ */
+size_t hif8_expanded_ld(size_t K);
+hif8_status hif8_expand_bf16(const uint8_t* codes, size_t rows, size_t K, uint16_t* dst, size_t ld,
+                             hif8_stream_t stream);
+hif8_status hif8_gemm_expanded_f32(const uint16_t* a, const uint16_t* b, float* out, size_t M, size_t N,
+                                   size_t K, size_t ld, float scale_a, float scale_b,
+                                   hif8_stream_t stream);
+hif8_status hif8_gemm_expanded_bf16(const uint16_t* a, const uint16_t* b, uint16_t* out, size_t M,
+                                    size_t N, size_t K, size_t ld, float scale_a, float scale_b,
+                                    hif8_stream_t stream);
+hif8_status hif8_gemm_expanded_f16(const uint16_t* a, const uint16_t* b, uint16_t* out, size_t M,
+                                   size_t N, size_t K, size_t ld, float scale_a, float scale_b,
+                                   hif8_stream_t stream);
+hif8_status hif8_gemm_expanded_sqerr(const uint16_t* a, const uint16_t* b, const float* ref, size_t M,
+                                     size_t N, size_t K, size_t ld, float scale_a, float scale_b,
+                                     double* d_err, hif8_stream_t stream);
+
+/*
  * Algorithm 1 (HiF8 calibration with per-tensor scaling) for ONE layer: given the layer's
  * high-precision input a [M, K], weight w [N, K] (K contiguous in both) and high-precision
  * output o_ref [M, N] (FP32), try every pair of power-of-two scales 2^Ea, 2^Ew with
@@ -409,8 +444,9 @@ hif8_status hif8_gemm_set_variant(int variant);
  * and, if d_best_or_null is given, write the pair with the smallest finite error to it as two
  * int32 {Ea, Ew}.  The paper casts with TA here; any rounding_mode is accepted.  The model-level
  * loop (collecting o_ref, feeding O_q through the non-linearities to the next layer) is the
- * caller's.  Enqueues ea_count + ew_count casts and ea_count * ew_count error GEMMs on `stream`.
- * workspace: device scratch for the code matrices, at least
+ * caller's.  Enqueues ea_count + ew_count casts (each followed by its expansion to bfloat16) and
+ * ea_count * ew_count error GEMMs (one batched launch) on `stream`.
+ * workspace: device scratch for one code matrix and the expanded operands, at least
  * hif8_calibrate_workspace_bytes(M, N, K, ea_count, ew_count) bytes, 16-byte aligned, caller-owned.
  * Counts are limited to 64 each, exponents to [-60, 60].
  */

@@ -22,6 +22,7 @@
 #include "hif8.h"
 #include "hif8_conv_api.hpp"
 #include "hif8_device.hpp"
+#include "hif8_gemm_common.hpp"
 #include "hif8_host.hpp"
 
 namespace hif8gemm {
@@ -29,11 +30,7 @@ namespace hif8gemm {
 using namespace hif8dev;
 using namespace hif8host;
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
-
-enum : int { EPI_F32 = 0, EPI_BF16 = 1, EPI_F16 = 2, EPI_ERR = 3 };
 
 #ifndef HIF8_GEMM_PAD
 #define HIF8_GEMM_PAD 8
@@ -66,14 +63,6 @@ __device__ __forceinline__ void decode_chunk_to_lds(const uint4& c, const uint16
   dst[0] = make_uint4(o[0], o[1], o[2], o[3]);
   dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
 }
-
-// Batched launches: pair p = blockIdx.y uses A + (p / nb) * a_stride, B + (p % nb) * b_stride,
-// err[p], and descale 2^-(e_base + p / nb + p % nb).  nb == 0: a single GEMM.
-struct Batch {
-  uint32_t nb;
-  int e_base;
-  size_t a_stride, b_stride;
-};
 
 // 16 codes of row `row` at column k; rows / columns outside the matrix read as zero codes.  The
 // address is clamped instead of branching so that the loop body stays one basic block.
@@ -201,36 +190,7 @@ k_gemm_nt(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __
   }
   if (kt < nk) k_step(kt, 0, 1);
 
-  // epilogue.  Accumulator element v of a 32 x 32 block: row = (v / 4) * 8 + (lane / 32) * 4 + v % 4,
-  // column = lane % 32.
-  double e2 = 0.0;
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const uint32_t col = n0 + (wn * TN + j) * 32 + (lane & 31u);
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const uint32_t row = m0 + (wm * TM + i) * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-        if (row < M && col < N) {
-          const float o = __fmul_rn(acc[i][j][v], descale);
-          const size_t idx = (size_t)row * N + col;
-          if constexpr (EPI == EPI_F32) reinterpret_cast<float*>(out)[idx] = o;
-          else if constexpr (EPI == EPI_BF16) reinterpret_cast<uint16_t*>(out)[idx] = (uint16_t)narrow_bf16(__float_as_uint(o));
-          else if constexpr (EPI == EPI_F16) reinterpret_cast<_Float16*>(out)[idx] = (_Float16)o;
-          else {
-            const double d = (double)o - (double)ref[idx];
-            e2 = fma(d, d, e2);
-          }
-        }
-      }
-    }
-  }
-  if constexpr (EPI == EPI_ERR) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) e2 += __shfl_xor(e2, off, 64);
-    if (lane == 0) unsafeAtomicAdd(err, e2);  // hardware fp64 add at the L2, no compare-and-swap loop
-  }
+  epilogue<EPI, TM, TN>(acc, out, ref, err, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, descale);
 }
 
 // any K, any alignment: one output element per lane, codes expanded with the integer decoder
@@ -370,7 +330,13 @@ __global__ void k_argmin_pair(const double* __restrict__ err, int rows, int cols
   best[1] = e_col_lo + bi % cols;
 }
 
-// Algorithm 1 for one layer: casts at every scale of the search square, then one error GEMM per pair.
+static size_t calibrate_bytes(size_t M, size_t N, size_t K, int ea_count, int ew_count) {
+  const size_t ld = expanded_ld(K);
+  return ((M > N ? M : N) * K + 15) / 16 * 16 + 2 * ld * (M * (size_t)ea_count + N * (size_t)ew_count);
+}
+
+// Algorithm 1 for one layer: casts at every scale of the search square (each expanded to bfloat16
+// once), then one error GEMM per pair.
 template <int SRCK>
 static hif8_status calibrate_layer(const void* a, const void* w, const float* o_ref, size_t M, size_t N, size_t K,
                                    int ea_lo, int ea_count, int ew_lo, int ew_count, uint32_t mode, void* workspace,
@@ -382,37 +348,34 @@ static hif8_status calibrate_layer(const void* a, const void* w, const float* o_
   if (!a || !w || !o_ref || !workspace || !d_err) return HIF8_ERR_NULL;
   if (!aligned_to(d_err, 8) || (d_best && !aligned_to(d_best, 4))) return HIF8_ERR_ARG;
   if (M == 0 || N == 0 || K == 0) return HIF8_ERR_ARG;
-  const size_t a_bytes = (M * K + 15) / 16 * 16, w_bytes = (N * K + 15) / 16 * 16;  // keep every code matrix 16-byte aligned
-  if (workspace_bytes < a_bytes * ea_count + w_bytes * ew_count || !aligned_to(workspace, 16)) return HIF8_ERR_ARG;
-  uint8_t* ws_a = reinterpret_cast<uint8_t*>(workspace);
-  uint8_t* ws_w = ws_a + a_bytes * ea_count;
+  if (M > 0x7FFFFFFFu || N > 0x7FFFFFFFu || K > 0x7FFFFF00u) return HIF8_ERR_ARG;
+  // workspace: one code matrix at a time (the stream runs the cast, then the expansion, before the
+  // next cast overwrites it), then every cast operand expanded to bfloat16 for the matrix cores
+  const size_t ld = expanded_ld(K);
+  const size_t code_bytes = ((M > N ? M : N) * K + 15) / 16 * 16;
+  const size_t a_elems = M * ld, w_elems = N * ld;  // multiples of 64 elements: every matrix stays 128-byte aligned
+  if (workspace_bytes < calibrate_bytes(M, N, K, ea_count, ew_count) || !aligned_to(workspace, 16)) return HIF8_ERR_ARG;
+  uint8_t* ws_codes = reinterpret_cast<uint8_t*>(workspace);
+  uint16_t* ws_a = reinterpret_cast<uint16_t*>(ws_codes + code_bytes);
+  uint16_t* ws_w = ws_a + a_elems * ea_count;
   hif8_status s = launch_fill_u32(reinterpret_cast<uint32_t*>(d_err), 0u, 2u * (uint32_t)(ea_count * ew_count), st);
   if (s != HIF8_OK) return s;
   for (int i = 0; i < ea_count; ++i) {
-    s = hif8conv::conv_encode<SRCK>(a, ws_a + a_bytes * i, M * K, std::ldexp(1.0f, ea_lo + i), nullptr, nullptr, mode, st);
+    s = hif8conv::conv_encode<SRCK>(a, ws_codes, M * K, std::ldexp(1.0f, ea_lo + i), nullptr, nullptr, mode, st);
+    if (s != HIF8_OK) return s;
+    s = expand_rows(ws_codes, M, K, ws_a + a_elems * i, ld, st);
     if (s != HIF8_OK) return s;
   }
   for (int j = 0; j < ew_count; ++j) {
-    s = hif8conv::conv_encode<SRCK>(w, ws_w + w_bytes * j, N * K, std::ldexp(1.0f, ew_lo + j), nullptr, nullptr, mode, st);
+    s = hif8conv::conv_encode<SRCK>(w, ws_codes, N * K, std::ldexp(1.0f, ew_lo + j), nullptr, nullptr, mode, st);
+    if (s != HIF8_OK) return s;
+    s = expand_rows(ws_codes, N, K, ws_w + w_elems * j, ld, st);
     if (s != HIF8_OK) return s;
   }
-  if ((K % 16) == 0 && M <= 0x7FFFFFFFu && N <= 0x7FFFFFFFu && K <= 0x7FFFFFFFu) {
-    // all pairs in one launch: the grid's second dimension runs over the search square
-    const uint16_t* lut = nullptr;
-    s = gemm_init(&lut, nullptr);
-    if (s != HIF8_OK) return s;
-    const Batch batch{(uint32_t)ew_count, ea_lo + ew_lo, a_bytes, w_bytes};
-    s = launch_tiled<4, 2, 2, 4, 32, EPI_ERR>(ws_a, ws_w, nullptr, o_ref, d_err, (uint32_t)M, (uint32_t)N, (uint32_t)K,
-                                              1.0f, lut, st, batch, (uint32_t)(ea_count * ew_count));
-    if (s != HIF8_OK) return s;
-  } else
-  for (int i = 0; i < ea_count; ++i) {
-    for (int j = 0; j < ew_count; ++j) {
-      s = gemm_dispatch<EPI_ERR>(ws_a + a_bytes * i, ws_w + w_bytes * j, nullptr, o_ref, d_err + (size_t)i * ew_count + j,
-                                 M, N, K, std::ldexp(1.0f, ea_lo + i), std::ldexp(1.0f, ew_lo + j), st);
-      if (s != HIF8_OK) return s;
-    }
-  }
+  // all pairs in one launch: the grid's second dimension runs over the search square
+  const Batch batch{(uint32_t)ew_count, ea_lo + ew_lo, a_elems, w_elems};
+  s = gemm_expanded<EPI_ERR>(ws_a, ws_w, nullptr, o_ref, d_err, M, N, ld, 1.0f, st, batch, (uint32_t)(ea_count * ew_count));
+  if (s != HIF8_OK) return s;
   if (d_best) {
     hipLaunchKernelGGL(k_argmin_pair, dim3(1), dim3(64), 0, st, d_err, ea_count, ew_count, ea_lo, ew_lo, d_best);
     return finish_launch();
@@ -434,7 +397,7 @@ hif8_status hif8_gemm_set_variant(int variant) {
 
 size_t hif8_calibrate_workspace_bytes(size_t M, size_t N, size_t K, int ea_count, int ew_count) {
   if (ea_count < 0 || ew_count < 0) return 0;
-  return (M * K + 15) / 16 * 16 * (size_t)ea_count + (N * K + 15) / 16 * 16 * (size_t)ew_count;
+  return calibrate_bytes(M, N, K, ea_count, ew_count);
 }
 
 #define HIF8_DEFINE_CALIBRATE(SFX, T, KIND)                                                                       \

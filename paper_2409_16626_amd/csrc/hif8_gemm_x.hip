@@ -1,0 +1,325 @@
+// Simulated HiF8 GEMM on operands that were expanded to bfloat16 beforehand.
+//
+// Every HiF8 value is exact in bfloat16, so a code matrix can be expanded once (3 bytes of HBM
+// traffic per element) and then multiplied any number of times without touching the decoder
+// again -- the shape of Algorithm 1's scale search (10 + 10 casts, 100 products) and of a
+// training step that uses a cast weight in the forward and the backward GEMM (Sec. 5).
+//
+//   expand:  X[r, k] = bf16(value(codes[r, k]))  for k < K,  0 for K <= k < ld,  ld = K rounded up to 64
+//   GEMM:    O[M, N] = (A[M, ld] x B[N, ld]^T) * descale
+//
+// Kernel design (gfx950): a workgroup of WM x WN wavefronts owns a (WM TM 32) x (WN TN 32) tile of O.
+// K advances in steps of 64 through two LDS stages.  Tiles go from global memory straight into LDS
+// (global_load_lds_dwordx4: 64 lanes x 16 bytes land contiguously), so the operands never pass
+// through registers.  A tile row is 128 bytes = 8 chunks of 16 bytes; chunk position p of tile row r
+// holds k-chunk p ^ ((r >> 1) & 7).  LDS has 64 banks of 4 bytes and serves a 16-byte read 16 lanes
+// at a time: the 16 lanes of a fragment read touch 16 consecutive rows of one k-chunk, which the
+// permutation spreads over all 16 chunk slots of two adjacent rows -- no bank conflicts, no padding.
+// Fragments are double-buffered in registers, and the workgroup barrier sits before the last of
+// the four MFMA groups of a K step, so the first fragments of the next step are fetched under it.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+
+#include "hif8.h"
+#include "hif8_device.hpp"
+#include "hif8_gemm_common.hpp"
+#include "hif8_host.hpp"
+
+namespace hif8gemm {
+
+using namespace hif8dev;
+using namespace hif8host;
+
+constexpr int kBK = (int)kExpandK;  // K step
+constexpr int kRowBytes = kBK * 2;  // one tile row in LDS
+constexpr int kRowsPerLoad = 8;     // a wavefront-wide 16-byte load covers 8 tile rows
+
+// s_waitcnt immediates (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[15:14])
+constexpr int kWaitLgkm0 = 0xC07F;        // lgkmcnt(0)
+constexpr int kWaitVm0Lgkm0 = 0x0070;     // vmcnt(0) lgkmcnt(0)
+constexpr int kWaitVm0 = 0x0F70;          // vmcnt(0)
+
+template <int WM, int WN, int TM, int TN, int EPI>
+__global__ void __launch_bounds__(64 * WM * WN)
+k_gemm_x(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, void* __restrict__ out,
+         const float* __restrict__ ref, double* __restrict__ err, uint32_t M, uint32_t N, uint32_t ld,
+         float descale, uint32_t tiles_n, Batch batch) {
+  if (batch.nb != 0u) {
+    const uint32_t bi = blockIdx.y / batch.nb, bj = blockIdx.y - bi * batch.nb;
+    A += (size_t)bi * batch.a_stride;
+    B += (size_t)bj * batch.b_stride;
+    err += blockIdx.y;
+    descale = pow2f(-(batch.e_base + (int)bi + (int)bj));
+  }
+  constexpr int kWaves = WM * WN;
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+  constexpr int IA = BM / kRowsPerLoad / kWaves, IB = BN / kRowsPerLoad / kWaves;  // loads per wavefront and K step
+  static_assert(BM % (kRowsPerLoad * kWaves) == 0 && BN % (kRowsPerLoad * kWaves) == 0, "tile / wavefront mismatch");
+  constexpr int kStageBytes = (BM + BN) * kRowBytes;
+  extern __shared__ __attribute__((aligned(128))) uint8_t smem[];  // [2][BM + BN][128 bytes]
+
+  const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+  const uint32_t wm = wave / WN, wn = wave % WN;
+  const uint32_t tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x - tile_m * tiles_n;
+  const uint32_t m0 = tile_m * BM, n0 = tile_n * BN;
+
+  // Source of this lane in each wavefront-wide load: tile row r = 8 * (load index) + lane / 8, chunk
+  // position lane % 8.  Rows past the matrix read its last row (their products are never stored).
+  const uint32_t lr = lane >> 3, lc = lane & 7u;
+  const uint16_t* a_src[IA];
+  const uint16_t* b_src[IB];
+#pragma unroll
+  for (int i = 0; i < IA; ++i) {
+    const uint32_t r = (wave * IA + i) * kRowsPerLoad + lr;
+    const uint32_t g = min(m0 + r, M - 1u);
+    a_src[i] = A + (size_t)g * ld + ((lc ^ ((r >> 1) & 7u)) * 8u);
+  }
+#pragma unroll
+  for (int i = 0; i < IB; ++i) {
+    const uint32_t r = (wave * IB + i) * kRowsPerLoad + lr;
+    const uint32_t g = min(n0 + r, N - 1u);
+    b_src[i] = B + (size_t)g * ld + ((lc ^ ((r >> 1) & 7u)) * 8u);
+  }
+  auto issue = [&](int stage, uint32_t k0) {
+    uint8_t* sa = smem + stage * kStageBytes + wave * IA * kRowsPerLoad * kRowBytes;
+    uint8_t* sb = smem + stage * kStageBytes + BM * kRowBytes + wave * IB * kRowsPerLoad * kRowBytes;
+#pragma unroll
+    for (int i = 0; i < IA; ++i)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a_src[i] + k0),
+                                       (__attribute__((address_space(3))) void*)(sa + i * kRowsPerLoad * kRowBytes),
+                                       16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < IB; ++i)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(b_src[i] + k0),
+                                       (__attribute__((address_space(3))) void*)(sb + i * kRowsPerLoad * kRowBytes),
+                                       16, 0, 0);
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  // MFMA operand of lane l: row l % 32 of the block, k elements 8 * (l / 32) .. + 7 of the 16-wide step
+  const uint32_t frow = lane & 31u, fk = lane >> 5;
+  const uint32_t swz = (frow >> 1) & 7u;  // block row offsets are multiples of 32: the permutation depends on frow only
+  const uint32_t a_off = (wm * TM * 32 + frow) * kRowBytes;
+  const uint32_t b_off = BM * kRowBytes + (wn * TN * 32 + frow) * kRowBytes;
+  bf16x8 fa[2][TM], fb[2][TN];
+  auto read_frags = [&](int buf, int stage, int s) {
+    const uint8_t* base = smem + stage * kStageBytes + (((uint32_t)(s * 2) + fk) ^ swz) * 16u;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8*>(base + a_off + i * 32 * kRowBytes);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[buf][j] = *reinterpret_cast<const bf16x8*>(base + b_off + j * 32 * kRowBytes);
+  };
+  auto mfmas = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
+  };
+
+  // The scheduling barriers pin "fetch the next fragments, then the MFMAs of the current ones"; each
+  // explicit wait sits where the reads it covers were issued a whole MFMA group earlier.
+  const uint32_t nk = ld / kBK;  // >= 1
+  issue(0, 0);
+  __builtin_amdgcn_s_waitcnt(kWaitVm0);
+  __syncthreads();
+  if (nk > 1) issue(1, kBK);
+  read_frags(0, 0, 0);
+  for (uint32_t kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1;
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+    read_frags(1, cur, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas(0);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+    read_frags(0, cur, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas(1);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+    read_frags(1, cur, 3);
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas(0);
+    __builtin_amdgcn_sched_barrier(0);
+    // this wavefront's part of tile kt + 1 has landed and its last fragments of tile kt are in registers;
+    // after the barrier that holds for the whole workgroup, so stage `cur` may be overwritten
+    __builtin_amdgcn_s_waitcnt(kWaitVm0Lgkm0);
+    __syncthreads();
+    if (kt + 2 < nk) issue(cur, (kt + 2) * kBK);
+    if (kt + 1 < nk) read_frags(0, cur ^ 1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas(1);
+  }
+
+  epilogue<EPI, TM, TN>(acc, out, ref, err, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, descale);
+}
+
+// codes [rows, K] -> bf16 [rows, ld]; one 16-byte output chunk (8 elements) per lane and step
+__global__ void __launch_bounds__(256)
+k_expand_rows(const uint8_t* __restrict__ codes, uint16_t* __restrict__ dst, size_t rows, uint32_t K, uint32_t ld,
+              int vec_ok) {
+  __shared__ uint16_t lut[256];
+  lut[threadIdx.x] = (uint16_t)(decode_bits(threadIdx.x) >> 16);  // blockDim.x == 256
+  __syncthreads();
+  const uint32_t cpr = ld / 8u;  // output chunks per row
+  const size_t total = rows * cpr;
+  for (size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x; q < total; q += (size_t)gridDim.x * blockDim.x) {
+    const size_t row = q / cpr;
+    const uint32_t k = (uint32_t)(q - row * cpr) * 8u;
+    const uint8_t* src = codes + row * K + k;
+    uint32_t c[8];
+    if (vec_ok && k + 8u <= K) {
+      const uint2 v = *reinterpret_cast<const uint2*>(src);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        c[j] = (v.x >> (8 * j)) & 0xFFu;
+        c[4 + j] = (v.y >> (8 * j)) & 0xFFu;
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) c[j] = (k + j < K) ? (uint32_t)src[j] : 0u;  // code 0x00 is +0
+    }
+    uint4 o;
+    o.x = lut[c[0]] | ((uint32_t)lut[c[1]] << 16);
+    o.y = lut[c[2]] | ((uint32_t)lut[c[3]] << 16);
+    o.z = lut[c[4]] | ((uint32_t)lut[c[5]] << 16);
+    o.w = lut[c[6]] | ((uint32_t)lut[c[7]] << 16);
+    *reinterpret_cast<uint4*>(dst + row * ld + k) = o;
+  }
+}
+
+// ====================================================================================
+// host side
+// ====================================================================================
+hif8_status expand_rows(const uint8_t* codes, size_t rows, size_t K, uint16_t* dst, size_t ld, hipStream_t st) {
+  if (rows == 0) return HIF8_OK;
+  if (!dst || (!codes && K != 0)) return HIF8_ERR_NULL;
+  if (ld == 0 || ld % kExpandK != 0 || ld < K || ld > 0x7FFFFFC0u || K > 0x7FFFFFFFu || !aligned_to(dst, 16))
+    return HIF8_ERR_ARG;
+  if (rows > ((size_t)1 << 60) / ld) return HIF8_ERR_ARG;
+  int cus = 0;
+  hif8_status s = ensure_init(&cus, nullptr);
+  if (s != HIF8_OK) return s;
+  const int vec_ok = (K % 8 == 0) && aligned_to(codes, 8);
+  const size_t total = rows * (ld / 8);
+  const size_t want = (total + 255) / 256;
+  const unsigned grid = (unsigned)(want < (size_t)cus * 16 ? want : (size_t)cus * 16);
+  hipLaunchKernelGGL(k_expand_rows, dim3(grid), dim3(256), 0, st, codes, dst, rows, (uint32_t)K, (uint32_t)ld, vec_ok);
+  return finish_launch();
+}
+
+constexpr int kMaxDevices = 64;
+
+template <int WM, int WN, int TM, int TN, int EPI>
+static hif8_status launch_x(const uint16_t* A, const uint16_t* B, void* out, const float* ref, double* err, uint32_t M,
+                            uint32_t N, uint32_t ld, float descale, hipStream_t st, const Batch& batch, uint32_t pairs) {
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+  constexpr size_t smem = (size_t)2 * (BM + BN) * kRowBytes;
+  static bool attr_set[kMaxDevices] = {};
+  int dev = 0;
+  if (!hip_ok(hipGetDevice(&dev))) return HIF8_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return HIF8_ERR_ARG;
+  if (!attr_set[dev]) {
+    if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_x<WM, WN, TM, TN, EPI>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem)))
+      return HIF8_ERR_HIP;
+    attr_set[dev] = true;
+  }
+  const uint32_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  if ((uint64_t)tiles_m * tiles_n > 0x7FFFFFFFull || pairs == 0 || pairs > 65535u) return HIF8_ERR_ARG;
+  hipLaunchKernelGGL((k_gemm_x<WM, WN, TM, TN, EPI>), dim3(tiles_m * tiles_n, pairs), dim3(64 * WM * WN), smem, st, A, B,
+                     out, ref, err, M, N, ld, descale, tiles_n, batch);
+  return finish_launch();
+}
+
+template <int EPI>
+hif8_status gemm_expanded(const uint16_t* A, const uint16_t* B, void* out, const float* ref, double* err, size_t M,
+                          size_t N, size_t ld, float descale, hipStream_t st, const Batch& batch, uint32_t pairs) {
+  if (M == 0 || N == 0) return HIF8_OK;
+  if (M > 0x7FFFFFFFu || N > 0x7FFFFFFFu || ld > 0x7FFFFFC0u || ld == 0 || ld % kExpandK != 0) return HIF8_ERR_ARG;
+  if (!A || !B) return HIF8_ERR_NULL;
+  if (EPI == EPI_ERR ? (!ref || !err) : !out) return HIF8_ERR_NULL;
+  if (!aligned_to(A, 16) || !aligned_to(B, 16)) return HIF8_ERR_ARG;
+  if (EPI == EPI_ERR && !aligned_to(err, 8)) return HIF8_ERR_ARG;
+  if (batch.nb != 0u && ((batch.a_stride % 8) != 0 || (batch.b_stride % 8) != 0)) return HIF8_ERR_ARG;
+  int cus = 0;
+  hif8_status s = ensure_init(&cus, nullptr);
+  if (s != HIF8_OK) return s;
+  // 256 x 256 tiles (8 wavefronts) once the launch has one for every compute unit, else 128 x 128 (4 wavefronts)
+  const size_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256) * (size_t)pairs;
+  if (big_tiles >= (size_t)cus)
+    return launch_x<2, 4, 4, 2, EPI>(A, B, out, ref, err, (uint32_t)M, (uint32_t)N, (uint32_t)ld, descale, st, batch, pairs);
+  return launch_x<2, 2, 2, 2, EPI>(A, B, out, ref, err, (uint32_t)M, (uint32_t)N, (uint32_t)ld, descale, st, batch, pairs);
+}
+
+template hif8_status gemm_expanded<EPI_F32>(const uint16_t*, const uint16_t*, void*, const float*, double*, size_t, size_t,
+                                            size_t, float, hipStream_t, const Batch&, uint32_t);
+template hif8_status gemm_expanded<EPI_BF16>(const uint16_t*, const uint16_t*, void*, const float*, double*, size_t, size_t,
+                                             size_t, float, hipStream_t, const Batch&, uint32_t);
+template hif8_status gemm_expanded<EPI_F16>(const uint16_t*, const uint16_t*, void*, const float*, double*, size_t, size_t,
+                                            size_t, float, hipStream_t, const Batch&, uint32_t);
+template hif8_status gemm_expanded<EPI_ERR>(const uint16_t*, const uint16_t*, void*, const float*, double*, size_t, size_t,
+                                            size_t, float, hipStream_t, const Batch&, uint32_t);
+
+// descale = fl32(fl32(1 / scale_a) * fl32(1 / scale_b)), as in the code-operand GEMM
+static bool descale_of(float scale_a, float scale_b, float* out) {
+  float inv_a = 1.0f, inv_b = 1.0f;
+  if (!valid_scale(scale_a, &inv_a) || !valid_scale(scale_b, &inv_b)) return false;
+  volatile float ds = inv_a * inv_b;
+  *out = ds;
+  return (*out > 0.0f) && !std::isinf(*out);
+}
+
+template <int EPI>
+static hif8_status gemm_expanded_abi(const uint16_t* a, const uint16_t* b, void* out, const float* ref, double* err,
+                                     size_t M, size_t N, size_t K, size_t ld, float scale_a, float scale_b,
+                                     hipStream_t st) {
+  float descale = 1.0f;
+  if (!descale_of(scale_a, scale_b, &descale)) return HIF8_ERR_SCALE;
+  if (K == 0 || ld < K) return HIF8_ERR_ARG;
+  return gemm_expanded<EPI>(a, b, out, ref, err, M, N, ld, descale, st, Batch{0u, 0, 0, 0}, 1u);
+}
+
+}  // namespace hif8gemm
+
+using namespace hif8gemm;
+
+extern "C" {
+
+size_t hif8_expanded_ld(size_t K) { return expanded_ld(K); }
+
+hif8_status hif8_expand_bf16(const uint8_t* codes, size_t rows, size_t K, uint16_t* dst, size_t ld,
+                             hif8_stream_t stream) {
+  return expand_rows(codes, rows, K, dst, ld, (hipStream_t)stream);
+}
+
+hif8_status hif8_gemm_expanded_f32(const uint16_t* a, const uint16_t* b, float* out, size_t M, size_t N, size_t K,
+                                   size_t ld, float scale_a, float scale_b, hif8_stream_t stream) {
+  return gemm_expanded_abi<EPI_F32>(a, b, out, nullptr, nullptr, M, N, K, ld, scale_a, scale_b, (hipStream_t)stream);
+}
+hif8_status hif8_gemm_expanded_bf16(const uint16_t* a, const uint16_t* b, uint16_t* out, size_t M, size_t N, size_t K,
+                                    size_t ld, float scale_a, float scale_b, hif8_stream_t stream) {
+  return gemm_expanded_abi<EPI_BF16>(a, b, out, nullptr, nullptr, M, N, K, ld, scale_a, scale_b, (hipStream_t)stream);
+}
+hif8_status hif8_gemm_expanded_f16(const uint16_t* a, const uint16_t* b, uint16_t* out, size_t M, size_t N, size_t K,
+                                   size_t ld, float scale_a, float scale_b, hif8_stream_t stream) {
+  return gemm_expanded_abi<EPI_F16>(a, b, out, nullptr, nullptr, M, N, K, ld, scale_a, scale_b, (hipStream_t)stream);
+}
+hif8_status hif8_gemm_expanded_sqerr(const uint16_t* a, const uint16_t* b, const float* ref, size_t M, size_t N,
+                                     size_t K, size_t ld, float scale_a, float scale_b, double* d_err,
+                                     hif8_stream_t stream) {
+  return gemm_expanded_abi<EPI_ERR>(a, b, nullptr, ref, d_err, M, N, K, ld, scale_a, scale_b, (hipStream_t)stream);
+}
+
+}  // extern "C"

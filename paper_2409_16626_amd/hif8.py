@@ -107,6 +107,12 @@ _SIGS = {
     "hif8_gemm_sqerr": ([_vp, _vp, _vp, _sz, _sz, _sz, _f, _f, _vp, _vp], _i),
     "hif8_gemm_set_variant": ([_i], _i),
     "hif8_calibrate_workspace_bytes": ([_sz, _sz, _sz, _i, _i], _sz),
+    "hif8_expanded_ld": ([_sz], _sz),
+    "hif8_expand_bf16": ([_vp, _sz, _sz, _vp, _sz, _vp], _i),
+    "hif8_gemm_expanded_f32": ([_vp, _vp, _vp, _sz, _sz, _sz, _sz, _f, _f, _vp], _i),
+    "hif8_gemm_expanded_bf16": ([_vp, _vp, _vp, _sz, _sz, _sz, _sz, _f, _f, _vp], _i),
+    "hif8_gemm_expanded_f16": ([_vp, _vp, _vp, _sz, _sz, _sz, _sz, _f, _f, _vp], _i),
+    "hif8_gemm_expanded_sqerr": ([_vp, _vp, _vp, _sz, _sz, _sz, _sz, _f, _f, _vp, _vp], _i),
     "hif8_calibrate_layer_f32": ([_vp, _vp, _vp, _sz, _sz, _sz, _i, _i, _i, _i, _u32, _vp, _sz, _vp, _vp, _vp], _i),
     "hif8_calibrate_layer_bf16": ([_vp, _vp, _vp, _sz, _sz, _sz, _i, _i, _i, _i, _u32, _vp, _sz, _vp, _vp, _vp], _i),
     "hif8_calibrate_layer_f16": ([_vp, _vp, _vp, _sz, _sz, _sz, _i, _i, _i, _i, _u32, _vp, _sz, _vp, _vp, _vp], _i),
@@ -397,6 +403,31 @@ def hif8_gemm_sqerr(a_codes, b_codes, ref, M, N, K, scale_a, scale_b, d_err, str
 
 def hif8_gemm_set_variant(variant):
     _check(lib.hif8_gemm_set_variant(variant))
+
+
+def hif8_expanded_ld(K):
+    return lib.hif8_expanded_ld(K)
+
+
+def hif8_expand_bf16(codes, rows, K, dst, ld, stream=None):
+    _check(lib.hif8_expand_bf16(_ptr(codes), rows, K, _ptr(dst), ld, _stream(stream)))
+
+
+def hif8_gemm_expanded_f32(a, b, out, M, N, K, ld, scale_a=1.0, scale_b=1.0, stream=None):
+    _check(lib.hif8_gemm_expanded_f32(_ptr(a), _ptr(b), _ptr(out), M, N, K, ld, scale_a, scale_b, _stream(stream)))
+
+
+def hif8_gemm_expanded_bf16(a, b, out, M, N, K, ld, scale_a=1.0, scale_b=1.0, stream=None):
+    _check(lib.hif8_gemm_expanded_bf16(_ptr(a), _ptr(b), _ptr(out), M, N, K, ld, scale_a, scale_b, _stream(stream)))
+
+
+def hif8_gemm_expanded_f16(a, b, out, M, N, K, ld, scale_a=1.0, scale_b=1.0, stream=None):
+    _check(lib.hif8_gemm_expanded_f16(_ptr(a), _ptr(b), _ptr(out), M, N, K, ld, scale_a, scale_b, _stream(stream)))
+
+
+def hif8_gemm_expanded_sqerr(a, b, ref, M, N, K, ld, scale_a, scale_b, d_err, stream=None):
+    _check(lib.hif8_gemm_expanded_sqerr(_ptr(a), _ptr(b), _ptr(ref), M, N, K, ld, scale_a, scale_b, _ptr(d_err),
+                                        _stream(stream)))
 
 
 def hif8_calibrate_workspace_bytes(M, N, K, ea_count=10, ew_count=10):

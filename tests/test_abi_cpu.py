@@ -57,7 +57,22 @@ def test_argument_validation_happens_on_the_host():
     assert L.hif8_encode_axis_bf16(p, p, 4, 4, 0, None, 0, None) == NULL
     assert L.hif8_calibrate_layer_f32(p, p, p, 16, 16, 16, -4, 10, -4, 10, 0, p, 0, p, None, None) == ARG   # workspace too small
     assert L.hif8_calibrate_layer_f32(p, p, p, 16, 16, 16, -4, 65, -4, 10, 0, p, 1 << 20, p, None, None) == ARG
-    assert L.hif8_calibrate_workspace_bytes(16, 32, 16, 10, 10) == 10 * 256 + 10 * 512
+    # one code matrix (the larger operand) + every cast operand as bfloat16 with rows padded to 64 elements
+    assert L.hif8_calibrate_workspace_bytes(16, 32, 16, 10, 10) == 32 * 16 + 2 * 64 * (10 * 16 + 10 * 32)
+    assert [L.hif8_expanded_ld(k) for k in (1, 63, 64, 65, 4096)] == [64, 64, 64, 128, 4096]
+    assert L.hif8_expand_bf16(p, 4, 64, None, 64, None) == NULL
+    assert L.hif8_expand_bf16(p, 4, 64, p, 32, None) == ARG                     # pitch below K
+    assert L.hif8_expand_bf16(p, 4, 64, p, 96, None) == ARG                     # pitch not a multiple of 64
+    assert L.hif8_expand_bf16(p, 4, 64, p + 2, 64, None) == ARG                 # misaligned destination
+    assert L.hif8_expand_bf16(p, 0, 64, p, 64, None) == OK
+    assert L.hif8_gemm_expanded_f32(p, p, p, 16, 16, 0, 64, 1.0, 1.0, None) == ARG
+    assert L.hif8_gemm_expanded_f32(p, p, p, 16, 16, 65, 64, 1.0, 1.0, None) == ARG
+    assert L.hif8_gemm_expanded_bf16(p, p, p, 16, 16, 64, 100, 1.0, 1.0, None) == ARG
+    assert L.hif8_gemm_expanded_f16(p + 2, p, p, 16, 16, 64, 64, 1.0, 1.0, None) == ARG
+    assert L.hif8_gemm_expanded_f32(p, p, None, 16, 16, 64, 64, 1.0, 1.0, None) == NULL
+    assert L.hif8_gemm_expanded_f32(p, p, p, 16, 16, 64, 64, 1.0, float("nan"), None) == SCALE
+    assert L.hif8_gemm_expanded_sqerr(p, p, p, 16, 16, 64, 64, 1.0, 1.0, p + 4, None) == ARG
+    assert L.hif8_gemm_expanded_f32(p, p, p, 16, 0, 64, 64, 1.0, 1.0, None) == OK
     assert L.hif8_diag_stream(p, p, 16, 5, None) == ARG
     assert L.hif8_diag_stream(p + 4, p, 16, 4, None) == ARG
 
