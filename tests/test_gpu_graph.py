@@ -1,0 +1,81 @@
+"""The library under HIP graph capture: every entry point only enqueues kernels on the caller's
+stream (no allocation, no memset, no synchronisation once hif8_init has run), so a whole
+amax -> scale -> cast -> expand -> GEMM sequence can be captured once and replayed.
+
+Each replay, with fresh input written between replays by ordinary eager work, is compared bit
+for bit with the same sequence run eagerly on the same input, and the casts with the oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import hif8_oracle as orc
+from gpu_util import bf16_bits, dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def h():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2409_16626_amd import hif8
+    hif8.hif8_init()
+    return hif8
+
+
+def test_cast_and_gemm_sequence_replays_exactly(h):
+    M, N, K = 192, 160, 200
+    ld = h.hif8_expanded_ld(K)
+    g = torch.Generator(device=dev()).manual_seed(21)
+    x = torch.empty(M, K, dtype=torch.bfloat16, device=dev())
+    w = (torch.randn(N, K, generator=g, device=dev()) * 0.03).to(torch.bfloat16)
+
+    class Bufs:
+        def __init__(self):
+            self.amax = torch.zeros(2, dtype=torch.float32, device=dev())
+            self.scale = torch.zeros(2, 2, dtype=torch.float32, device=dev())
+            self.xq = torch.empty_like(x)
+            self.xc = torch.empty(M, K, dtype=torch.uint8, device=dev())
+            self.wc = torch.empty(N, K, dtype=torch.uint8, device=dev())
+            self.xe = torch.empty(M, ld, dtype=torch.bfloat16, device=dev())
+            self.we = torch.empty(N, ld, dtype=torch.bfloat16, device=dev())
+            self.out = torch.empty(M, N, dtype=torch.float32, device=dev())
+
+    def sequence(b):
+        b.amax.zero_()                                                     # a fill kernel, not a memset node
+        h.hif8_amax_bf16(x, M * K, b.amax[0:1])
+        h.hif8_amax_bf16(w, N * K, b.amax[1:2])
+        h.hif8_scale_from_amax_n(b.amax, b.scale, 2, h.MAX_FINITE, 1)
+        h.hif8_fake_quant_bf16_ds(x, b.xq, b.xc, M * K, b.scale[0], h.RM_TA)
+        h.hif8_encode_bf16_ds(w, b.wc, N * K, b.scale[1], h.RM_HR)
+        h.hif8_expand_bf16(b.xc, M, K, b.xe, ld)
+        h.hif8_expand_bf16(b.wc, N, K, b.we, ld)
+        h.hif8_gemm_expanded_f32(b.xe, b.we, b.out, M, N, K, ld, 1.0, 1.0)
+
+    eager, graphed = Bufs(), Bufs()
+    x.copy_(torch.randn(M, K, generator=g, device=dev()).to(torch.bfloat16))
+    sequence(graphed)                                                      # warm-up outside the capture: one-time setup happens here
+    torch.cuda.synchronize()
+
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sequence(graphed)
+
+    for rep in range(4):
+        x.copy_((torch.randn(M, K, generator=g, device=dev()) * (0.5 + 3.0 * rep)).to(torch.bfloat16))   # eager work between replays
+        torch.cuda.synchronize()
+        for t in (graphed.xq, graphed.xc, graphed.wc, graphed.xe, graphed.out):
+            t.fill_(0)
+        graph.replay()
+        sequence(eager)
+        torch.cuda.synchronize()
+        for name in ("amax", "scale", "xc", "wc", "out"):
+            assert torch.equal(getattr(graphed, name), getattr(eager, name)), (rep, name)
+        assert torch.equal(graphed.xq.view(torch.int16), eager.xq.view(torch.int16)), rep
+        assert torch.equal(graphed.xe.view(torch.int16), eager.xe.view(torch.int16)), rep
+        # and against the oracle: amax, scale and codes of the activation cast
+        xn = bf16_bits(x)
+        w_am = orc.amax_bf16(xn.reshape(-1))
+        w_s = orc.scale_from_amax(w_am, 32768.0, True)
+        assert graphed.amax[0].item() == float(w_am) and graphed.scale[0, 0].item() == float(w_s)
+        assert np.array_equal(graphed.xc.cpu().numpy().reshape(-1), orc.encode_bf16(xn.reshape(-1), w_s, orc.RM_TA))
