@@ -386,7 +386,9 @@ hif8_status hif8_als_update(hif8_als_state* st, int found_overflow);
  *                     256 x 256 tile for every compute unit, else 6); 1..6 = fixed workgroup tile /
  *                     wavefront layouts (for benchmarking): 1 = 128 x 128 x 64 (4 wavefronts),
  *                     2 = 256 x 256 x 32 (4), 3 = 256 x 128 x 32 (4), 4 = 256 x 256 x 32 (8, as 2 x 4),
- *                     5 = 256 x 256 x 32 (8, as 4 x 2), 6 = 128 x 128 x 32 (4, two workgroups per CU).
+ *                     5 = 256 x 256 x 32 (8, as 4 x 2), 6 = 128 x 128 x 32 (4, two workgroups per CU);
+ *                     7..9 = layouts of the expanded-operand kernel below (hif8_gemm_expanded_*): 7 = 256 x 256 x 64
+ *                     (8, as 2 x 4), 8 = the same as 4 x 2, 9 = 128 x 128 x 64 (4).  0 resets both choices.
  */
 hif8_status hif8_gemm_f32(const uint8_t* a_codes, const uint8_t* b_codes, float* out, size_t M,
                           size_t N, size_t K, float scale_a, float scale_b, hif8_stream_t stream);
@@ -414,7 +416,7 @@ hif8_status hif8_gemm_set_variant(int variant);
  *   hif8_gemm_expanded_*  out[m, n] = fl32( (sum_k a[m, k] * b[n, k]) * fl32(fl32(1/scale_a) * fl32(1/scale_b)) )
  *                         a: [M, ld], b: [N, ld] u16 bfloat16 patterns as written by hif8_expand_bf16
  *                         (16-byte aligned; the columns K .. ld-1 must hold zeros); out / ref / d_err as in
- *                         hif8_gemm_*.  K >= 1; M, N < 2^31.  Same error bound as hif8_gemm_*; the summation
+ *                         hif8_gemm_*.  K >= 1, ld <= 2^22; M, N < 2^31.  Same error bound as hif8_gemm_*; the summation
  *                         order differs from that kernel's, so the two agree to within that bound, and
  *                         exactly whenever every partial sum is exact in FP32.
  */
@@ -448,7 +450,7 @@ hif8_status hif8_gemm_expanded_sqerr(const uint16_t* a, const uint16_t* b, const
  * ea_count * ew_count error GEMMs (one batched launch) on `stream`.
  * workspace: device scratch for one code matrix and the expanded operands, at least
  * hif8_calibrate_workspace_bytes(M, N, K, ea_count, ew_count) bytes, 16-byte aligned, caller-owned.
- * Counts are limited to 64 each, exponents to [-60, 60].
+ * Counts are limited to 64 each, exponents to [-60, 60], K to 2^22.
  */
 size_t hif8_calibrate_workspace_bytes(size_t M, size_t N, size_t K, int ea_count, int ew_count);
 hif8_status hif8_calibrate_layer_f32(const float* a, const float* w, const float* o_ref, size_t M,

@@ -348,7 +348,7 @@ static hif8_status calibrate_layer(const void* a, const void* w, const float* o_
   if (!a || !w || !o_ref || !workspace || !d_err) return HIF8_ERR_NULL;
   if (!aligned_to(d_err, 8) || (d_best && !aligned_to(d_best, 4))) return HIF8_ERR_ARG;
   if (M == 0 || N == 0 || K == 0) return HIF8_ERR_ARG;
-  if (M > 0x7FFFFFFFu || N > 0x7FFFFFFFu || K > 0x7FFFFF00u) return HIF8_ERR_ARG;
+  if (M > 0x7FFFFFFFu || N > 0x7FFFFFFFu || K > kMaxLd) return HIF8_ERR_ARG;
   // workspace: one code matrix at a time (the stream runs the cast, then the expansion, before the
   // next cast overwrites it), then every cast operand expanded to bfloat16 for the matrix cores
   const size_t ld = expanded_ld(K);
@@ -390,8 +390,15 @@ using namespace hif8gemm;
 extern "C" {
 
 hif8_status hif8_gemm_set_variant(int variant) {
-  if (variant < 0 || variant > 6) return HIF8_ERR_ARG;
-  g_gemm_variant = variant;
+  if (variant < 0 || variant > 9) return HIF8_ERR_ARG;
+  if (variant == 0) {
+    g_gemm_variant = 0;
+    expanded_variant() = 0;
+  } else if (variant <= 6) {
+    g_gemm_variant = variant;
+  } else {
+    expanded_variant() = variant;
+  }
   return HIF8_OK;
 }
 

@@ -10,7 +10,7 @@
 //
 // Kernel design (gfx950): a workgroup of WM x WN wavefronts owns a (WM TM 32) x (WN TN 32) tile of O.
 // K advances in steps of 64 through two LDS stages.  Tiles go from global memory straight into LDS
-// (global_load_lds_dwordx4: 64 lanes x 16 bytes land contiguously), so the operands never pass
+// (buffer_load_dwordx4 ... lds: 64 lanes x 16 bytes land contiguously), so the operands never pass
 // through registers.  A tile row is 128 bytes = 8 chunks of 16 bytes; chunk position p of tile row r
 // holds k-chunk p ^ ((r >> 1) & 7).  LDS has 64 banks of 4 bytes and serves a 16-byte read 16 lanes
 // at a time: the 16 lanes of a fragment read touch 16 consecutive rows of one k-chunk, which the
@@ -40,6 +40,7 @@ constexpr int kRowsPerLoad = 8;     // a wavefront-wide 16-byte load covers 8 ti
 constexpr int kWaitLgkm0 = 0xC07F;        // lgkmcnt(0)
 constexpr int kWaitVm0Lgkm0 = 0x0070;     // vmcnt(0) lgkmcnt(0)
 constexpr int kWaitVm0 = 0x0F70;          // vmcnt(0)
+constexpr int kRsrcFlags = 0x00020000;    // word 3 of a raw (unstructured, untyped) buffer descriptor on gfx9-family parts
 
 template <int WM, int WN, int TM, int TN, int EPI>
 __global__ void __launch_bounds__(64 * WM * WN)
@@ -58,43 +59,49 @@ k_gemm_x(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, void* _
   constexpr int IA = BM / kRowsPerLoad / kWaves, IB = BN / kRowsPerLoad / kWaves;  // loads per wavefront and K step
   static_assert(BM % (kRowsPerLoad * kWaves) == 0 && BN % (kRowsPerLoad * kWaves) == 0, "tile / wavefront mismatch");
   constexpr int kStageBytes = (BM + BN) * kRowBytes;
+  static_assert(kStageBytes == 65536 || kStageBytes == 32768, "stage size");
   extern __shared__ __attribute__((aligned(128))) uint8_t smem[];  // [2][BM + BN][128 bytes]
 
-  const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+  const uint32_t tid = threadIdx.x, lane = tid & 63u;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: LDS destinations of the loads stay in SGPRs
   const uint32_t wm = wave / WN, wn = wave % WN;
   const uint32_t tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x - tile_m * tiles_n;
   const uint32_t m0 = tile_m * BM, n0 = tile_n * BN;
 
-  // Source of this lane in each wavefront-wide load: tile row r = 8 * (load index) + lane / 8, chunk
-  // position lane % 8.  Rows past the matrix read its last row (their products are never stored).
+  // Tile loads are buffer loads into LDS: one descriptor per operand panel of this workgroup (SGPRs), a
+  // 32-bit byte offset per lane that never changes, and a scalar offset that advances along K -- no vector
+  // ALU work per load.  The descriptor ends with the matrix, so rows past it read as zeros.
+  const size_t bytes_a = ((size_t)M - m0) * ld * 2u, bytes_b = ((size_t)N - n0) * ld * 2u;
+  const __amdgpu_buffer_rsrc_t res_a = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(A + (size_t)m0 * ld), 0, (int)(bytes_a > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)bytes_a), kRsrcFlags);
+  const __amdgpu_buffer_rsrc_t res_b = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(B + (size_t)n0 * ld), 0, (int)(bytes_b > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)bytes_b), kRsrcFlags);
+  // lane -> tile row 8 * (load index) + lane / 8, chunk position lane % 8 (which holds k-chunk position ^ ((row >> 1) & 7))
   const uint32_t lr = lane >> 3, lc = lane & 7u;
-  const uint16_t* a_src[IA];
-  const uint16_t* b_src[IB];
+  uint32_t off_a[IA], off_b[IB];
 #pragma unroll
   for (int i = 0; i < IA; ++i) {
     const uint32_t r = (wave * IA + i) * kRowsPerLoad + lr;
-    const uint32_t g = min(m0 + r, M - 1u);
-    a_src[i] = A + (size_t)g * ld + ((lc ^ ((r >> 1) & 7u)) * 8u);
+    off_a[i] = (r * ld + ((lc ^ ((r >> 1) & 7u)) * 8u)) * 2u;  // < 2^32: the host limits ld
   }
 #pragma unroll
   for (int i = 0; i < IB; ++i) {
     const uint32_t r = (wave * IB + i) * kRowsPerLoad + lr;
-    const uint32_t g = min(n0 + r, N - 1u);
-    b_src[i] = B + (size_t)g * ld + ((lc ^ ((r >> 1) & 7u)) * 8u);
+    off_b[i] = (r * ld + ((lc ^ ((r >> 1) & 7u)) * 8u)) * 2u;
   }
-  auto issue = [&](int stage, uint32_t k0) {
+  uint32_t koff = 0;  // byte offset along K of the next tile to request
+  auto issue = [&](int stage) {
     uint8_t* sa = smem + stage * kStageBytes + wave * IA * kRowsPerLoad * kRowBytes;
     uint8_t* sb = smem + stage * kStageBytes + BM * kRowBytes + wave * IB * kRowsPerLoad * kRowBytes;
 #pragma unroll
     for (int i = 0; i < IA; ++i)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a_src[i] + k0),
-                                       (__attribute__((address_space(3))) void*)(sa + i * kRowsPerLoad * kRowBytes),
-                                       16, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(res_a, (__attribute__((address_space(3))) void*)(sa + i * kRowsPerLoad * kRowBytes),
+                                               16, (int)off_a[i], (int)koff, 0, 0);
 #pragma unroll
     for (int i = 0; i < IB; ++i)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(b_src[i] + k0),
-                                       (__attribute__((address_space(3))) void*)(sb + i * kRowsPerLoad * kRowBytes),
-                                       16, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(res_b, (__attribute__((address_space(3))) void*)(sb + i * kRowsPerLoad * kRowBytes),
+                                               16, (int)off_b[i], (int)koff, 0, 0);
+    koff += kBK * 2;
   };
 
   f32x16 acc[TM][TN];
@@ -105,18 +112,25 @@ k_gemm_x(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, void* _
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-  // MFMA operand of lane l: row l % 32 of the block, k elements 8 * (l / 32) .. + 7 of the 16-wide step
+  // MFMA operand of lane l: row l % 32 of the block, k elements 8 * (l / 32) .. + 7 of the 16-wide step.
+  // LDS address of the lane's A fragment of block row 0 for every (stage, step), computed once; the other
+  // block rows and the B fragments are constant offsets from it.
   const uint32_t frow = lane & 31u, fk = lane >> 5;
   const uint32_t swz = (frow >> 1) & 7u;  // block row offsets are multiples of 32: the permutation depends on frow only
-  const uint32_t a_off = (wm * TM * 32 + frow) * kRowBytes;
-  const uint32_t b_off = BM * kRowBytes + (wn * TN * 32 + frow) * kRowBytes;
+  uint32_t fbase[2][4];
+#pragma unroll
+  for (int st = 0; st < 2; ++st)
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      fbase[st][s] = st * kStageBytes + (wm * TM * 32 + frow) * kRowBytes + ((((uint32_t)(s * 2) + fk) ^ swz) * 16u);
+  const uint32_t b_delta = BM * kRowBytes + (wn * TN * 32) * kRowBytes - (wm * TM * 32) * kRowBytes;  // scalar
   bf16x8 fa[2][TM], fb[2][TN];
   auto read_frags = [&](int buf, int stage, int s) {
-    const uint8_t* base = smem + stage * kStageBytes + (((uint32_t)(s * 2) + fk) ^ swz) * 16u;
+    const uint8_t* base = smem + fbase[stage][s];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8*>(base + a_off + i * 32 * kRowBytes);
+    for (int i = 0; i < TM; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8*>(base + i * 32 * kRowBytes);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) fb[buf][j] = *reinterpret_cast<const bf16x8*>(base + b_off + j * 32 * kRowBytes);
+    for (int j = 0; j < TN; ++j) fb[buf][j] = *reinterpret_cast<const bf16x8*>(base + b_delta + j * 32 * kRowBytes);
   };
   auto mfmas = [&](int buf) {
 #pragma unroll
@@ -126,16 +140,11 @@ k_gemm_x(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, void* _
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
   };
 
-  // The scheduling barriers pin "fetch the next fragments, then the MFMAs of the current ones"; each
-  // explicit wait sits where the reads it covers were issued a whole MFMA group earlier.
+  // One K step on LDS stage `cur` (a compile-time constant at both call sites).  The scheduling barriers
+  // pin "fetch the next fragments, then the MFMAs of the current ones"; each explicit wait sits where the
+  // reads it covers were issued a whole MFMA group earlier.
   const uint32_t nk = ld / kBK;  // >= 1
-  issue(0, 0);
-  __builtin_amdgcn_s_waitcnt(kWaitVm0);
-  __syncthreads();
-  if (nk > 1) issue(1, kBK);
-  read_frags(0, 0, 0);
-  for (uint32_t kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
+  auto k_step = [&](int cur, uint32_t kt) {
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
     read_frags(1, cur, 1);
@@ -156,11 +165,22 @@ k_gemm_x(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, void* _
     // after the barrier that holds for the whole workgroup, so stage `cur` may be overwritten
     __builtin_amdgcn_s_waitcnt(kWaitVm0Lgkm0);
     __syncthreads();
-    if (kt + 2 < nk) issue(cur, (kt + 2) * kBK);
+    if (kt + 2 < nk) issue(cur);
     if (kt + 1 < nk) read_frags(0, cur ^ 1, 0);
     __builtin_amdgcn_sched_barrier(0);
     mfmas(1);
+  };
+  issue(0);
+  __builtin_amdgcn_s_waitcnt(kWaitVm0);
+  __syncthreads();
+  if (nk > 1) issue(1);
+  read_frags(0, 0, 0);
+  uint32_t kt = 0;
+  for (; kt + 1 < nk; kt += 2) {
+    k_step(0, kt);
+    k_step(1, kt + 1);
   }
+  if (kt < nk) k_step(0, kt);
 
   epilogue<EPI, TM, TN>(acc, out, ref, err, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, descale);
 }
@@ -221,6 +241,11 @@ hif8_status expand_rows(const uint8_t* codes, size_t rows, size_t K, uint16_t* d
 
 constexpr int kMaxDevices = 64;
 
+int& expanded_variant() {
+  static int v = 0;
+  return v;
+}
+
 template <int WM, int WN, int TM, int TN, int EPI>
 static hif8_status launch_x(const uint16_t* A, const uint16_t* B, void* out, const float* ref, double* err, uint32_t M,
                             uint32_t N, uint32_t ld, float descale, hipStream_t st, const Batch& batch, uint32_t pairs) {
@@ -247,7 +272,8 @@ template <int EPI>
 hif8_status gemm_expanded(const uint16_t* A, const uint16_t* B, void* out, const float* ref, double* err, size_t M,
                           size_t N, size_t ld, float descale, hipStream_t st, const Batch& batch, uint32_t pairs) {
   if (M == 0 || N == 0) return HIF8_OK;
-  if (M > 0x7FFFFFFFu || N > 0x7FFFFFFFu || ld > 0x7FFFFFC0u || ld == 0 || ld % kExpandK != 0) return HIF8_ERR_ARG;
+  // 256 rows x ld x 2 bytes of a workgroup's operand panel must fit the 32-bit lane offsets of the tile loads
+  if (M > 0x7FFFFFFFu || N > 0x7FFFFFFFu || ld > kMaxLd || ld == 0 || ld % kExpandK != 0) return HIF8_ERR_ARG;
   if (!A || !B) return HIF8_ERR_NULL;
   if (EPI == EPI_ERR ? (!ref || !err) : !out) return HIF8_ERR_NULL;
   if (!aligned_to(A, 16) || !aligned_to(B, 16)) return HIF8_ERR_ARG;
@@ -258,8 +284,12 @@ hif8_status gemm_expanded(const uint16_t* A, const uint16_t* B, void* out, const
   if (s != HIF8_OK) return s;
   // 256 x 256 tiles (8 wavefronts) once the launch has one for every compute unit, else 128 x 128 (4 wavefronts)
   const size_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256) * (size_t)pairs;
-  if (big_tiles >= (size_t)cus)
+  int variant = expanded_variant();
+  if (variant == 0) variant = big_tiles >= (size_t)cus ? 7 : 9;
+  if (variant == 7)
     return launch_x<2, 4, 4, 2, EPI>(A, B, out, ref, err, (uint32_t)M, (uint32_t)N, (uint32_t)ld, descale, st, batch, pairs);
+  if (variant == 8)
+    return launch_x<4, 2, 2, 4, EPI>(A, B, out, ref, err, (uint32_t)M, (uint32_t)N, (uint32_t)ld, descale, st, batch, pairs);
   return launch_x<2, 2, 2, 2, EPI>(A, B, out, ref, err, (uint32_t)M, (uint32_t)N, (uint32_t)ld, descale, st, batch, pairs);
 }
 

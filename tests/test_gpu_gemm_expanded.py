@@ -25,7 +25,8 @@ def h():
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     from paper_2409_16626_amd import hif8
     hif8.hif8_init()
-    return hif8
+    yield hif8
+    hif8.hif8_gemm_set_variant(0)
 
 
 def random_codes(rng, shape, kind):
@@ -95,9 +96,11 @@ SHAPES = [(32, 32, 16), (128, 128, 64), (100, 70, 48), (257, 129, 80), (1, 1, 1)
           (256, 256, 32), (300, 520, 4096), (33, 17, 19), (513, 259, 130), (1100, 1300, 72), (4200, 4100, 64)]
 
 
+@pytest.mark.parametrize("variant", [0, 7, 8, 9])     # by problem size; 256 x 256 as 2 x 4 and 4 x 2 wavefronts; 128 x 128
 @pytest.mark.parametrize("M,N,K", SHAPES)
-def test_gemm_expanded_f32_matches_oracle(h, M, N, K):
+def test_gemm_expanded_f32_matches_oracle(h, variant, M, N, K):
     rng = np.random.default_rng(M * 7 + N * 3 + K)
+    h.hif8_gemm_set_variant(variant)
     for kind in ("cast_normal", "uniform_codes"):
         ca, cb = random_codes(rng, (M, K), kind), random_codes(rng, (N, K), kind)
         a, ld = expand(h, ca)
@@ -120,11 +123,14 @@ def test_gemm_expanded_exact_when_sums_fit_24_bits(h, M, N, K):
     ca, cb = rng.choice(ints, size=(M, K)), rng.choice(ints, size=(N, K))
     a, ld = expand(h, ca)
     b, _ = expand(h, cb)
-    out = torch.zeros(M, N, dtype=torch.float32, device=dev())
-    h.hif8_gemm_expanded_f32(a, b, out, M, N, K, ld, 1.0, 1.0)
-    torch.cuda.synchronize()
     want64 = go.gemm_hif8(ca, cb)
-    assert np.array_equal(out.cpu().numpy().astype(np.float64), want64)
+    out = torch.zeros(M, N, dtype=torch.float32, device=dev())
+    for variant in (7, 8, 9, 0):
+        h.hif8_gemm_set_variant(variant)
+        out.zero_()
+        h.hif8_gemm_expanded_f32(a, b, out, M, N, K, ld, 1.0, 1.0)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy().astype(np.float64), want64), variant
     other = torch.zeros(M, N, dtype=torch.float32, device=dev())
     h.hif8_gemm_f32(torch.from_numpy(ca).to(dev()), torch.from_numpy(cb).to(dev()), other, M, N, K, 1.0, 1.0)
     torch.cuda.synchronize()
