@@ -190,7 +190,9 @@ k_gemm_nt(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __
   }
   if (kt < nk) k_step(kt, 0, 1);
 
-  epilogue<EPI, TM, TN>(acc, out, ref, err, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, descale);
+  // the last K step ended with a barrier: the tile buffers (behind the table) are free for the error sums
+  epilogue<EPI, TM, TN>(acc, out, ref, err, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, descale,
+                        reinterpret_cast<double*>(As), wave, WM * WN);
 }
 
 // any K, any alignment: one output element per lane, codes expanded with the integer decoder

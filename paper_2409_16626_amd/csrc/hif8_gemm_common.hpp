@@ -28,31 +28,55 @@ struct Batch {
 
 // Epilogue of one wavefront: TM x TN accumulator blocks of v_mfma_f32_32x32x16_bf16 whose top-left
 // element is (row0, col0).  Element v of a 32 x 32 block sits at row (v / 4) * 8 + (lane / 32) * 4 + v % 4,
-// column lane % 32.  EPI_ERR adds the squared differences to *err (fp64, one atomic per wavefront).
+// column lane % 32.  EPI_ERR adds the squared differences to *err in fp64: the wavefronts of the workgroup
+// combine through `wg_scratch` (LDS, at least one double per wavefront, free of other use by now; every
+// wavefront of the workgroup must make this call) and issue one atomic per workgroup.
+template <int EPI>
+__device__ __forceinline__ void store_one(void* __restrict__ out, size_t idx, float o) {
+  if constexpr (EPI == EPI_F32) reinterpret_cast<float*>(out)[idx] = o;
+  else if constexpr (EPI == EPI_BF16) reinterpret_cast<uint16_t*>(out)[idx] = (uint16_t)hif8dev::narrow_bf16(__float_as_uint(o));
+  else reinterpret_cast<_Float16*>(out)[idx] = (_Float16)o;
+}
+
 template <int EPI, int TM, int TN>
 __device__ __forceinline__ void epilogue(const f32x16 (&acc)[TM][TN], void* __restrict__ out,
                                          const float* __restrict__ ref, double* __restrict__ err, uint32_t M,
-                                         uint32_t N, uint32_t row0, uint32_t col0, uint32_t lane, float descale) {
+                                         uint32_t N, uint32_t row0, uint32_t col0, uint32_t lane, float descale,
+                                         double* wg_scratch, uint32_t wave, uint32_t n_waves) {
   double e2 = 0.0;
+  // the whole wavefront tile inside the matrix (the usual case): no per-element bounds checks
+  const bool inside = row0 + TM * 32 <= M && col0 + TN * 32 <= N;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const uint32_t col = col0 + j * 32 + (lane & 31u);
+      const uint32_t rbase = row0 + i * 32 + (lane >> 5) * 4;
+      if constexpr (EPI == EPI_ERR) {
+        // all 16 reference values of the block are requested before the first is used; positions
+        // outside the matrix read element 0 and contribute nothing
+        float r[16];
+        bool ok[16];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const uint32_t row = row0 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-        if (row < M && col < N) {
-          const float o = __fmul_rn(acc[i][j][v], descale);
-          const size_t idx = (size_t)row * N + col;
-          if constexpr (EPI == EPI_F32) reinterpret_cast<float*>(out)[idx] = o;
-          else if constexpr (EPI == EPI_BF16)
-            reinterpret_cast<uint16_t*>(out)[idx] = (uint16_t)hif8dev::narrow_bf16(__float_as_uint(o));
-          else if constexpr (EPI == EPI_F16) reinterpret_cast<_Float16*>(out)[idx] = (_Float16)o;
-          else {
-            const double d = (double)o - (double)ref[idx];
-            e2 = fma(d, d, e2);
-          }
+        for (int v = 0; v < 16; ++v) {
+          const uint32_t row = rbase + (v >> 2) * 8 + (v & 3);
+          ok[v] = inside || (row < M && col < N);
+          r[v] = ref[ok[v] ? (size_t)row * N + col : (size_t)0];
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const double d = (double)__fmul_rn(acc[i][j][v], descale) - (double)r[v];
+          e2 = ok[v] ? fma(d, d, e2) : e2;
+        }
+      } else if (inside) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          store_one<EPI>(out, (size_t)(rbase + (v >> 2) * 8 + (v & 3)) * N + col, __fmul_rn(acc[i][j][v], descale));
+      } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const uint32_t row = rbase + (v >> 2) * 8 + (v & 3);
+          if (row < M && col < N) store_one<EPI>(out, (size_t)row * N + col, __fmul_rn(acc[i][j][v], descale));
         }
       }
     }
@@ -60,7 +84,13 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[TM][TN], void* __re
   if constexpr (EPI == EPI_ERR) {
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) e2 += __shfl_xor(e2, off, 64);
-    if (lane == 0) unsafeAtomicAdd(err, e2);  // hardware fp64 add at the L2, no compare-and-swap loop
+    if (lane == 0) wg_scratch[wave] = e2;
+    __syncthreads();
+    if (wave == 0 && lane == 0) {
+      double t = 0.0;
+      for (uint32_t w = 0; w < n_waves; ++w) t += wg_scratch[w];
+      unsafeAtomicAdd(err, t);  // hardware fp64 add at the L2, no compare-and-swap loop
+    }
   }
 }
 

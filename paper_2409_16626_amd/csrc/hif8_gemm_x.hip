@@ -182,7 +182,9 @@ k_gemm_x(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, void* _
   }
   if (kt < nk) k_step(0, kt);
 
-  epilogue<EPI, TM, TN>(acc, out, ref, err, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, descale);
+  // every fragment of the last step was in registers before the last barrier, so the tile LDS is free
+  epilogue<EPI, TM, TN>(acc, out, ref, err, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, descale,
+                        reinterpret_cast<double*>(smem), wave, kWaves);
 }
 
 // codes [rows, K] -> bf16 [rows, ld]; one 16-byte output chunk (8 elements) per lane and step
