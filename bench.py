@@ -308,12 +308,17 @@ def main():
                 hif8.hif8_expand_bf16(cb, gn, gk, xb, ld)
 
             w_ms, x_ms = timed(expand_both, 20, 5)
+            ldt = hif8.hif8_expanded_ld(gn)
+            xt = torch.empty(gk, ldt, dtype=torch.bfloat16, device=dev)
+            w_ms, t_ms = timed(lambda i: hif8.hif8_expand_bf16_t(cb, gn, gk, xt, ldt), 20, 5)
+            del xt
             w_ms, e_ms = timed(lambda i: hif8.hif8_gemm_expanded_bf16(xa, xb, go, gm, gn, gk, ld, 1.0, 1.0), 20, 5)
             extra["gemm_expanded_bf16 out, operands expanded to bf16 beforehand, M=%d N=%d K=%d" % (gm, gn, gk)] = {
                 "ms": round(e_ms, 4), "TFLOP/s": round(fl / (e_ms * 1e-3) / 1e12, 1), "bound": "mfma",
                 "frac_of_2.5PFLOPs_bf16": round(fl / (e_ms * 1e-3) / MFMA_PEAK, 4),
                 "expand_both_operands_ms": round(x_ms, 4), "expand_GB/s (3 B/elem)": round(3.0 * (gm + gn) * gk / (x_ms * 1e-3) / 1e9, 1),
-                "TFLOP/s incl. expansion": round(fl / ((e_ms + x_ms) * 1e-3) / 1e12, 1)}
+                "TFLOP/s incl. expansion": round(fl / ((e_ms + x_ms) * 1e-3) / 1e12, 1),
+                "transposing_expand_of_B_ms": round(t_ms, 4), "transposing_expand_GB/s (3 B/elem)": round(3.0 * gn * gk / (t_ms * 1e-3) / 1e9, 1)}
             del ca, cb, go, xa, xb
         lm, ln, lk = 2048, 4096, 4096
         xa = torch.randn(lm, lk, device=dev).to(torch.bfloat16)

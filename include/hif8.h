@@ -413,6 +413,11 @@ hif8_status hif8_gemm_set_variant(int variant);
  *                         K <= k < ld.  codes: [rows, K] u8 device; dst: [rows, ld] u16 device, 16-byte
  *                         aligned, caller-owned; ld a multiple of 64 and >= K.  (NaN / Inf codes expand
  *                         to NaN / Inf and propagate through the product.)
+ *   hif8_expand_bf16_t    the same with a transposition: dst[c * ld + r] = value(codes[r * cols + c]) for r < rows and 0
+ *                         for rows <= r < ld; dst: [cols, ld], ld a multiple of 64 and >= rows.  With it the three
+ *                         products of a linear layer all run on the one K-contiguous kernel (X: [M, K], W: [N, K], dY: [M, N]):
+ *                         Y = X W^T from expand(X), expand(W); dX = dY W from expand(dY), expand_t(W);
+ *                         dW = dY^T X from expand_t(dY), expand_t(X).
  *   hif8_gemm_expanded_*  out[m, n] = fl32( (sum_k a[m, k] * b[n, k]) * fl32(fl32(1/scale_a) * fl32(1/scale_b)) )
  *                         a: [M, ld], b: [N, ld] u16 bfloat16 patterns as written by hif8_expand_bf16
  *                         (16-byte aligned; the columns K .. ld-1 must hold zeros); out / ref / d_err as in
@@ -423,6 +428,8 @@ hif8_status hif8_gemm_set_variant(int variant);
 size_t hif8_expanded_ld(size_t K);
 hif8_status hif8_expand_bf16(const uint8_t* codes, size_t rows, size_t K, uint16_t* dst, size_t ld,
                              hif8_stream_t stream);
+hif8_status hif8_expand_bf16_t(const uint8_t* codes, size_t rows, size_t cols, uint16_t* dst, size_t ld,
+                               hif8_stream_t stream);
 hif8_status hif8_gemm_expanded_f32(const uint16_t* a, const uint16_t* b, float* out, size_t M, size_t N,
                                    size_t K, size_t ld, float scale_a, float scale_b,
                                    hif8_stream_t stream);

@@ -106,6 +106,7 @@ constexpr size_t kMaxLd = (size_t)1 << 22;
 int& expanded_variant();
 
 hif8_status expand_rows(const uint8_t* codes, size_t rows, size_t K, uint16_t* dst, size_t ld, hipStream_t st);
+hif8_status expand_cols(const uint8_t* codes, size_t rows, size_t cols, uint16_t* dst, size_t ld, hipStream_t st);
 
 // out = (A x B^T) * descale on operands of pitch ld (zero beyond K); batch.nb != 0: `pairs` GEMMs in one launch
 template <int EPI>

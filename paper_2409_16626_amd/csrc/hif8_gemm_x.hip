@@ -221,6 +221,58 @@ k_expand_rows(const uint8_t* __restrict__ codes, uint16_t* __restrict__ dst, siz
   }
 }
 
+// codes [rows, cols] -> bf16 [cols, ld], transposed: dst[c * ld + r] = value(codes[r * cols + c]), zeros for
+// rows <= r < ld.  64 x 64 tiles through LDS: 16 codes per lane on the way in, one 16-byte chunk of an
+// output row per lane on the way out (8 consecutive lanes write 128 contiguous bytes).
+constexpr int kTT = 64;           // tile edge
+constexpr int kTPitch = kTT + 2;  // LDS row pitch in elements (33 dwords: consecutive rows start one bank apart)
+__global__ void __launch_bounds__(256)
+k_expand_cols(const uint8_t* __restrict__ codes, uint16_t* __restrict__ dst, uint32_t rows, uint32_t cols, uint32_t ld,
+              uint32_t tiles_c, uint32_t n_tiles, int vec_ok) {
+  __shared__ uint16_t lut[256];
+  __shared__ __attribute__((aligned(16))) uint16_t tile[kTT * kTPitch];
+  const uint32_t t = threadIdx.x;
+  lut[t] = (uint16_t)(decode_bits(t) >> 16);  // blockDim.x == 256
+  for (uint32_t id = blockIdx.x; id < n_tiles; id += gridDim.x) {
+    const uint32_t tr = id / tiles_c, tc = id - tr * tiles_c;
+    const uint32_t r0 = tr * kTT, c0 = tc * kTT;
+    __syncthreads();  // table written (first pass) / previous tile fully read
+    {
+      const uint32_t r = r0 + (t >> 2), c = c0 + (t & 3u) * 16u;
+      uint32_t w[4] = {0u, 0u, 0u, 0u};  // code 0x00 is +0: everything outside the matrix expands to zero
+      if (r < rows && c < cols) {
+        const uint8_t* src = codes + (size_t)r * cols + c;
+        if (vec_ok && c + 16u <= cols) {
+          const uint4 v = *reinterpret_cast<const uint4*>(src);
+          w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+        } else {
+          for (uint32_t j = 0; j < 16u && c + j < cols; ++j) w[j >> 2] |= (uint32_t)src[j] << (8u * (j & 3u));
+        }
+      }
+      uint32_t* trow = reinterpret_cast<uint32_t*>(tile + (t >> 2) * kTPitch + (t & 3u) * 16u);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        trow[2 * j] = lut[w[j] & 0xFFu] | ((uint32_t)lut[(w[j] >> 8) & 0xFFu] << 16);
+        trow[2 * j + 1] = lut[(w[j] >> 16) & 0xFFu] | ((uint32_t)lut[w[j] >> 24] << 16);
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const uint32_t q = t + k * 256u, c = q >> 3, rc = (q & 7u) * 8u;  // output row c0 + c, elements r0 + rc .. + 7
+      if (c0 + c < cols) {
+        const uint16_t* col = tile + rc * kTPitch + c;
+        uint4 o;
+        o.x = col[0] | ((uint32_t)col[kTPitch] << 16);
+        o.y = col[2 * kTPitch] | ((uint32_t)col[3 * kTPitch] << 16);
+        o.z = col[4 * kTPitch] | ((uint32_t)col[5 * kTPitch] << 16);
+        o.w = col[6 * kTPitch] | ((uint32_t)col[7 * kTPitch] << 16);
+        *reinterpret_cast<uint4*>(dst + (size_t)(c0 + c) * ld + r0 + rc) = o;
+      }
+    }
+  }
+}
+
 // ====================================================================================
 // host side
 // ====================================================================================
@@ -238,6 +290,24 @@ hif8_status expand_rows(const uint8_t* codes, size_t rows, size_t K, uint16_t* d
   const size_t want = (total + 255) / 256;
   const unsigned grid = (unsigned)(want < (size_t)cus * 16 ? want : (size_t)cus * 16);
   hipLaunchKernelGGL(k_expand_rows, dim3(grid), dim3(256), 0, st, codes, dst, rows, (uint32_t)K, (uint32_t)ld, vec_ok);
+  return finish_launch();
+}
+
+hif8_status expand_cols(const uint8_t* codes, size_t rows, size_t cols, uint16_t* dst, size_t ld, hipStream_t st) {
+  if (cols == 0) return HIF8_OK;
+  if (!dst || (!codes && rows != 0)) return HIF8_ERR_NULL;
+  if (ld == 0 || ld % kExpandK != 0 || ld < rows || ld > 0x7FFFFFC0u || cols > 0x7FFFFFFFu || !aligned_to(dst, 16))
+    return HIF8_ERR_ARG;
+  if (cols > ((size_t)1 << 60) / ld) return HIF8_ERR_ARG;
+  int cus = 0;
+  hif8_status s = ensure_init(&cus, nullptr);
+  if (s != HIF8_OK) return s;
+  const int vec_ok = (cols % 16 == 0) && aligned_to(codes, 16);
+  const size_t tiles_c = (cols + kTT - 1) / kTT, n_tiles = (ld / kTT) * tiles_c;
+  if (n_tiles > 0x7FFFFFFFull) return HIF8_ERR_ARG;
+  const unsigned grid = (unsigned)(n_tiles < (size_t)cus * 16 ? n_tiles : (size_t)cus * 16);
+  hipLaunchKernelGGL(k_expand_cols, dim3(grid), dim3(256), 0, st, codes, dst, (uint32_t)rows, (uint32_t)cols, (uint32_t)ld,
+                     (uint32_t)tiles_c, (uint32_t)n_tiles, vec_ok);
   return finish_launch();
 }
 
@@ -334,6 +404,11 @@ size_t hif8_expanded_ld(size_t K) { return expanded_ld(K); }
 hif8_status hif8_expand_bf16(const uint8_t* codes, size_t rows, size_t K, uint16_t* dst, size_t ld,
                              hif8_stream_t stream) {
   return expand_rows(codes, rows, K, dst, ld, (hipStream_t)stream);
+}
+
+hif8_status hif8_expand_bf16_t(const uint8_t* codes, size_t rows, size_t cols, uint16_t* dst, size_t ld,
+                               hif8_stream_t stream) {
+  return expand_cols(codes, rows, cols, dst, ld, (hipStream_t)stream);
 }
 
 hif8_status hif8_gemm_expanded_f32(const uint16_t* a, const uint16_t* b, float* out, size_t M, size_t N, size_t K,

@@ -109,6 +109,7 @@ _SIGS = {
     "hif8_calibrate_workspace_bytes": ([_sz, _sz, _sz, _i, _i], _sz),
     "hif8_expanded_ld": ([_sz], _sz),
     "hif8_expand_bf16": ([_vp, _sz, _sz, _vp, _sz, _vp], _i),
+    "hif8_expand_bf16_t": ([_vp, _sz, _sz, _vp, _sz, _vp], _i),
     "hif8_gemm_expanded_f32": ([_vp, _vp, _vp, _sz, _sz, _sz, _sz, _f, _f, _vp], _i),
     "hif8_gemm_expanded_bf16": ([_vp, _vp, _vp, _sz, _sz, _sz, _sz, _f, _f, _vp], _i),
     "hif8_gemm_expanded_f16": ([_vp, _vp, _vp, _sz, _sz, _sz, _sz, _f, _f, _vp], _i),
@@ -411,6 +412,10 @@ def hif8_expanded_ld(K):
 
 def hif8_expand_bf16(codes, rows, K, dst, ld, stream=None):
     _check(lib.hif8_expand_bf16(_ptr(codes), rows, K, _ptr(dst), ld, _stream(stream)))
+
+
+def hif8_expand_bf16_t(codes, rows, cols, dst, ld, stream=None):
+    _check(lib.hif8_expand_bf16_t(_ptr(codes), rows, cols, _ptr(dst), ld, _stream(stream)))
 
 
 def hif8_gemm_expanded_f32(a, b, out, M, N, K, ld, scale_a=1.0, scale_b=1.0, stream=None):

@@ -65,6 +65,9 @@ def test_argument_validation_happens_on_the_host():
     assert L.hif8_expand_bf16(p, 4, 64, p, 96, None) == ARG                     # pitch not a multiple of 64
     assert L.hif8_expand_bf16(p, 4, 64, p + 2, 64, None) == ARG                 # misaligned destination
     assert L.hif8_expand_bf16(p, 0, 64, p, 64, None) == OK
+    assert L.hif8_expand_bf16_t(p, 100, 8, p, 64, None) == ARG                  # pitch below the row count
+    assert L.hif8_expand_bf16_t(p, 64, 8, None, 64, None) == NULL
+    assert L.hif8_expand_bf16_t(p, 64, 0, p, 64, None) == OK
     assert L.hif8_gemm_expanded_f32(p, p, p, 16, 16, 0, 64, 1.0, 1.0, None) == ARG
     assert L.hif8_gemm_expanded_f32(p, p, p, 16, 16, 65, 64, 1.0, 1.0, None) == ARG
     assert L.hif8_gemm_expanded_bf16(p, p, p, 16, 16, 64, 100, 1.0, 1.0, None) == ARG

@@ -247,3 +247,56 @@ def test_calibrate_layer_any_k(h):
     assert np.array_equal(np.isfinite(got), fin)
     np.testing.assert_allclose(got[fin], want[fin], rtol=2e-4)
     assert tuple(best.cpu().tolist()) == want_best
+
+
+def expand_t(h, codes_np):
+    rows, cols = codes_np.shape
+    ld = h.hif8_expanded_ld(rows)
+    dst = torch.full((cols, ld), 0x7FC1, dtype=torch.int16, device=dev())            # NaN patterns: padding must be written
+    h.hif8_expand_bf16_t(torch.from_numpy(codes_np).to(dev()), rows, cols, dst, ld)
+    return dst, ld
+
+
+@pytest.mark.parametrize("rows,cols", [(1, 1), (3, 70), (64, 64), (65, 63), (100, 257), (1000, 48), (130, 4112), (7, 16)])
+def test_transposing_expand_is_exact_and_pads_with_zeros(h, rows, cols):
+    rng = np.random.default_rng(rows * 77 + cols)
+    codes = rng.integers(0, 256, size=(rows, cols), dtype=np.uint8)
+    dst, ld = expand_t(h, codes)
+    torch.cuda.synchronize()
+    assert np.array_equal(dst.cpu().numpy().view(np.uint16), want_expanded(np.ascontiguousarray(codes.T), ld))
+    # a larger pitch than the minimum is filled with zeros as well; unaligned source
+    ld2 = ld + 128
+    buf = torch.zeros(rows * cols + 8, dtype=torch.uint8, device=dev())
+    buf[5:5 + rows * cols] = torch.from_numpy(codes.reshape(-1)).to(dev())
+    dst2 = torch.full((cols, ld2), -1, dtype=torch.int16, device=dev())
+    h.hif8_expand_bf16_t(buf[5:].data_ptr(), rows, cols, dst2, ld2)
+    torch.cuda.synchronize()
+    assert np.array_equal(dst2.cpu().numpy().view(np.uint16), want_expanded(np.ascontiguousarray(codes.T), ld2))
+
+
+def test_linear_layer_forward_and_backward_products(h):
+    """The three GEMMs of a linear layer in simulated HiF8 (Sec. 5: activations, weights and activation
+    gradients are cast): Y = X W^T, dX = dY W, dW = dY^T X, all on the K-contiguous kernel through plain and
+    transposing expansions; each against the oracle on the correspondingly transposed code matrices."""
+    rng = np.random.default_rng(31)
+    M, N, K = 200, 136, 264
+    cx = random_codes(rng, (M, K), "cast_normal")
+    cw = random_codes(rng, (N, K), "cast_normal")
+    cdy = random_codes(rng, (M, N), "cast_normal")
+    xe, ldk = expand(h, cx)
+    we, _ = expand(h, cw)
+    dye, ldn = expand(h, cdy)
+    wte, ldn2 = expand_t(h, cw)          # [K, ld(N)]
+    dyte, ldm = expand_t(h, cdy)         # [N, ld(M)]
+    xte, ldm2 = expand_t(h, cx)          # [K, ld(M)]
+    assert ldn == ldn2 and ldm == ldm2
+    y = torch.zeros(M, N, dtype=torch.float32, device=dev())
+    dx = torch.zeros(M, K, dtype=torch.float32, device=dev())
+    dw = torch.zeros(N, K, dtype=torch.float32, device=dev())
+    h.hif8_gemm_expanded_f32(xe, we, y, M, N, K, ldk, 8.0, 8.0)
+    h.hif8_gemm_expanded_f32(dye, wte, dx, M, K, N, ldn, 8.0, 8.0)
+    h.hif8_gemm_expanded_f32(dyte, xte, dw, N, K, M, ldm, 8.0, 8.0)
+    torch.cuda.synchronize()
+    check(y.cpu().numpy(), cx, cw, 8.0, 8.0)
+    check(dx.cpu().numpy(), cdy, np.ascontiguousarray(cw.T), 8.0, 8.0)
+    check(dw.cpu().numpy(), np.ascontiguousarray(cdy.T), np.ascontiguousarray(cx.T), 8.0, 8.0)
