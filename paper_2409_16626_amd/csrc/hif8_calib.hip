@@ -55,7 +55,7 @@ k_scale_sweep(const void* __restrict__ src, size_t n, int e_lo, int count_arg, u
               const uint8_t* __restrict__ g_lut, const uint32_t* __restrict__ g_dec,
               double* __restrict__ err) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
-  __shared__ __attribute__((aligned(8))) HrExp hrt[IMPL == IMPL_HR ? 256 : 1];
+  __shared__ __attribute__((aligned(16))) HrEntry<SRCK> hrt[IMPL == IMPL_HR ? 256 : 1];
   __shared__ uint32_t dec[256];
   const EncCtx ctx{lut, hrt, mode, seed};
   stage_enc_lut<IMPL>(lut, g_lut, mode);
@@ -259,7 +259,7 @@ k_encode_rows(const void* __restrict__ src, uint8_t* __restrict__ dst, uint32_t 
               const float* __restrict__ d_scale2, uint32_t mode, uint64_t seed,
               const uint8_t* __restrict__ g_lut) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
-  __shared__ __attribute__((aligned(8))) HrExp hrt[IMPL == IMPL_HR ? 256 : 1];
+  __shared__ __attribute__((aligned(16))) HrEntry<SRCK> hrt[IMPL == IMPL_HR ? 256 : 1];
   const EncCtx ctx{lut, hrt, mode, seed};
   constexpr int VE = vec_elems<SRCK>();
   const uint32_t row = blockIdx.x / chunks, chunk = blockIdx.x - row * chunks;
@@ -294,7 +294,7 @@ k_encode_cols(const void* __restrict__ src, uint8_t* __restrict__ dst, uint32_t 
               uint32_t strips, uint32_t rows_per_wg, const float* __restrict__ d_scale2, uint32_t mode,
               uint64_t seed, const uint8_t* __restrict__ g_lut) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
-  __shared__ __attribute__((aligned(8))) HrExp hrt[IMPL == IMPL_HR ? 256 : 1];
+  __shared__ __attribute__((aligned(16))) HrEntry<SRCK> hrt[IMPL == IMPL_HR ? 256 : 1];
   const EncCtx ctx{lut, hrt, mode, seed};
   stage_enc_lut<IMPL>(lut, g_lut, mode);
   if (IMPL == IMPL_HR) stage_hr_table(hrt, mode);

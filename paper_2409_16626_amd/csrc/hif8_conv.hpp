@@ -50,9 +50,14 @@ constexpr int vec_shift() { return SRCK == kSrcF32 ? 2 : 3; }
 // ------------------------------------------------------------------------------------
 // small device helpers
 // ------------------------------------------------------------------------------------
+// per-exponent parameters of the HR / simplified-SR path: scaled-integer form for binary32 sources (SR14),
+// add-and-mask form for 16-bit sources (SR2)
+template <int SRCK>
+using HrEntry = std::conditional_t<SRCK == kSrcF32, HrExp, HrExp16>;
+
 struct EncCtx {
   const uint8_t* lut;  // staged table(s) in LDS
-  const HrExp* hrt;    // staged per-exponent parameters in LDS (IMPL_HR)
+  const void* hrt;     // staged per-exponent parameters in LDS (IMPL_HR): HrEntry<SRCK>[256]
   uint32_t mode;
   uint64_t seed;       // IMPL_SR
 };
@@ -67,6 +72,10 @@ __device__ __forceinline__ void stage_enc_lut(uint8_t* lut, const uint8_t* __res
 __device__ __forceinline__ void stage_hr_table(HrExp* hrt, uint32_t mode) {
   const bool ssr = (mode & 0xFu) == kRmSSR;
   for (uint32_t i = threadIdx.x; i < 256u; i += blockDim.x) hrt[i] = hr_exp_entry(i, ssr);
+}
+__device__ __forceinline__ void stage_hr_table(HrExp16* hrt, uint32_t mode) {
+  const bool ssr = (mode & 0xFu) == kRmSSR;
+  for (uint32_t i = threadIdx.x; i < 256u; i += blockDim.x) hrt[i] = hr16_exp_entry(i, ssr);
 }
 __device__ __forceinline__ void stage_dec_lut(uint32_t* lut, const uint32_t* __restrict__ g_dec) {
   for (uint32_t i = threadIdx.x; i < 256u; i += blockDim.x) lut[i] = g_dec[i];
@@ -91,7 +100,10 @@ __device__ __forceinline__ uint32_t encode_one(uint32_t ybits, const EncCtx& c, 
       code = c.lut[(ybits >> 19) + ((ybits & 0x7FFFFu) ? 0u : 8192u)];
     } else {
       // HR / SSR: rounding to the grid, then the byte of the (now representable) pattern
-      const uint32_t r = hr_round_bits<SRCK>(ybits, c.hrt[(ybits >> 23) & 0xFFu]);
+      const HrEntry<SRCK>& p = reinterpret_cast<const HrEntry<SRCK>*>(c.hrt)[(ybits >> 23) & 0xFFu];
+      uint32_t r;
+      if constexpr (SRCK == kSrcF32) r = hr_round_bits<SRCK>(ybits, p);
+      else r = hr16_round_bits<SRCK>(ybits, p);
       code = c.lut[r >> 19];
     }
     // NaNs whose payload sits only in the low 19 bits index the Inf entry; fix them here.
@@ -224,7 +236,7 @@ k_encode(const void* __restrict__ src, uint8_t* __restrict__ dst, size_t n, floa
          const float* __restrict__ d_scale2, uint32_t* __restrict__ amax_acc, uint32_t mode,
          uint64_t seed, const uint8_t* __restrict__ g_lut, Walk walk) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
-  __shared__ __attribute__((aligned(8))) HrExp hrt[IMPL == IMPL_HR ? 256 : 1];
+  __shared__ __attribute__((aligned(16))) HrEntry<SRCK> hrt[IMPL == IMPL_HR ? 256 : 1];
   const EncCtx ctx{lut, hrt, mode, seed};
   const float scale = d_scale2 ? d_scale2[0] : scale_arg;
   const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(src);
@@ -296,7 +308,7 @@ k_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, float scale_a
              const float* __restrict__ d_scale2, uint32_t* amax_acc, uint32_t mode, uint64_t seed,
              const uint8_t* __restrict__ g_lut, const uint32_t* __restrict__ g_dec, Walk walk) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
-  __shared__ __attribute__((aligned(8))) HrExp hrt[IMPL == IMPL_HR ? 256 : 1];
+  __shared__ __attribute__((aligned(16))) HrEntry<SRCK> hrt[IMPL == IMPL_HR ? 256 : 1];
   __shared__ uint32_t dec[256];
   const EncCtx ctx{lut, hrt, mode, seed};
   const float scale = d_scale2 ? d_scale2[0] : scale_arg;
@@ -496,7 +508,7 @@ k_multi_encode(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_
                const float* __restrict__ d_scale2, uint32_t mode, uint64_t seed,
                const uint8_t* __restrict__ g_lut) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
-  __shared__ __attribute__((aligned(8))) HrExp hrt[IMPL == IMPL_HR ? 256 : 1];
+  __shared__ __attribute__((aligned(16))) HrEntry<SRCK> hrt[IMPL == IMPL_HR ? 256 : 1];
   const EncCtx ctx{lut, hrt, mode, seed};
   stage_enc_lut<IMPL>(lut, g_lut, mode);
   if (IMPL == IMPL_HR) stage_hr_table(hrt, mode);

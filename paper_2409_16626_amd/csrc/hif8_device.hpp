@@ -319,6 +319,49 @@ __device__ __forceinline__ uint32_t hr_round_bits(uint32_t ybits, const HrExp& p
   return r.u | (ybits & 0x80000000u);
 }
 
+// ------------------------------------------------------------------------------------
+// HR / simplified SR for 16-bit sources (SR2), streaming form.  The two-bit test "top two
+// discarded bits F2 >= T2" with T2 = {source LSB, 1} (Sec. 3.2), or F2 >= 2 where Eq. (3) asks for
+// TA, is the carry out of the discarded field after adding (4 - T2) (resp. 2) at the position of
+// its top two bits, so the rounding is one add and one mask on the binary32 pattern; the carry
+// propagates into the exponent exactly as in TA.  Per exponent the table holds the addend for a
+// source LSB of 0, the addend for an LSB of 1, and the mask.  Below 2^-22 there is one step from 0 to
+// 2^-22 (fraction bits F2 = {1, m22} for E = -23, 01 for E = -24, 00 below): the addends move the
+// pattern to exponent 104 or above when it carries and leave it below otherwise, which the TA table
+// then reads as 2^-22 and 0.  From 2^16 up (and for Inf) nothing is added: overflow whatever the rounding.
+// ------------------------------------------------------------------------------------
+struct HrExp16 {
+  uint32_t add0;  // source LSB 0: T2 = 1
+  uint32_t add1;  // source LSB 1: T2 = 3
+  uint32_t mask;
+  uint32_t pad;
+};
+
+__device__ __forceinline__ HrExp16 hr16_exp_entry(uint32_t e, bool ssr = false) {
+  HrExp16 h;
+  h.add0 = 0u; h.add1 = 0u; h.mask = 0xFFFFFFFFu; h.pad = 0u;
+  if (e >= 143u || e <= 102u) return h;
+  if (e == 104u) { h.add0 = 1u << 22; h.add1 = 0u - (1u << 22); return h; }  // F2 = {1, m22}
+  if (e == 103u) { h.add0 = 1u << 23; return h; }                           // F2 = 01: carries iff T2 = 1
+  const uint32_t k = kept_bits(e), d = 23u - k;
+  const bool ta = (k == 3u) && !ssr;
+  h.add0 = (ta ? 2u : 3u) << (d - 2u);
+  h.add1 = (ta ? 2u : 1u) << (d - 2u);
+  h.mask = 0xFFFFFFFFu << d;
+  return h;
+}
+
+// Rounded binary32 pattern (sign kept) of non-NaN pattern ybits, the scaled value of a 16-bit source
+// element; p = table entry of ybits' exponent.  The source LSB is bit 16 (BF16) or bit 13 (FP16) of ybits.
+template <int SRCK>
+__device__ __forceinline__ uint32_t hr16_round_bits(uint32_t ybits, const HrExp16& p) {
+  static_assert(SRCK != kSrcF32, "16-bit sources only");
+  const uint32_t a = ybits & 0x7FFFFFFFu;
+  const uint32_t m = 0u - ((ybits >> (SRCK == kSrcBF16 ? 16 : 13)) & 1u);  // all ones iff the source LSB is set
+  const uint32_t add = (m & p.add1) | (~m & p.add0);
+  return ((a + add) & p.mask) | (ybits & 0x80000000u);
+}
+
 // binary32 pattern of the value of a code (Eq. (1), Eq. (2), special patterns).
 __device__ __forceinline__ uint32_t decode_bits(uint32_t code) {
   const uint32_t s = (code & 0x80u) << 24;

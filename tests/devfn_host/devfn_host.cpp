@@ -31,11 +31,13 @@ void devfn_encode_bits_hr_table(const uint32_t* ybits, uint8_t* dst, size_t n, u
   for (size_t i = 0; i < n; ++i) {
     const uint32_t y = ybits[i];
     if ((y & 0x7FFFFFFFu) > 0x7F800000u) { dst[i] = (uint8_t)hif8dev::nan_code(mode); continue; }
-    const hif8dev::HrExp p = hif8dev::hr_exp_entry((y >> 23) & 0xFFu, ssr);
     uint32_t r;
-    if (srck == 0) r = hif8dev::hr_round_bits<0>(y, p);
-    else if (srck == 1) r = hif8dev::hr_round_bits<1>(y, p);
-    else r = hif8dev::hr_round_bits<2>(y, p);
+    if (srck == 0) {
+      r = hif8dev::hr_round_bits<0>(y, hif8dev::hr_exp_entry((y >> 23) & 0xFFu, ssr));
+    } else {  // 16-bit sources: add-and-mask form
+      const hif8dev::HrExp16 p = hif8dev::hr16_exp_entry((y >> 23) & 0xFFu, ssr);
+      r = srck == 1 ? hif8dev::hr16_round_bits<1>(y, p) : hif8dev::hr16_round_bits<2>(y, p);
+    }
     dst[i] = (uint8_t)hif8dev::encode_alu<false, 0>(r & 0xFFF80000u, mode);
   }
 }
