@@ -300,3 +300,32 @@ def test_linear_layer_forward_and_backward_products(h):
     check(y.cpu().numpy(), cx, cw, 8.0, 8.0)
     check(dx.cpu().numpy(), cdy, np.ascontiguousarray(cw.T), 8.0, 8.0)
     check(dw.cpu().numpy(), np.ascontiguousarray(cdy.T), np.ascontiguousarray(cx.T), 8.0, 8.0)
+
+
+@pytest.mark.parametrize("M,N,K", [(8192, 8192, 8192), (8192, 11008, 4096)])
+def test_gemm_benchmark_shapes_sampled_outputs(h, M, N, K):
+    """The shapes and the operand recipe bench.py times (codes uniform in 0x08..0x4F), default launch
+    configuration, both kernels: 64 x 64 sampled outputs (first and last rows and columns included)
+    against the oracle's product of the sampled rows."""
+    g = torch.Generator(device=dev()).manual_seed(M + N + K)
+    ca = torch.randint(8, 0x50, (M, K), generator=g, dtype=torch.int32, device=dev()).to(torch.uint8)
+    cb = torch.randint(8, 0x50, (N, K), generator=g, dtype=torch.int32, device=dev()).to(torch.uint8)
+    h.hif8_gemm_set_variant(0)
+    ld = h.hif8_expanded_ld(K)
+    xa = torch.empty(M, ld, dtype=torch.bfloat16, device=dev())
+    xb = torch.empty(N, ld, dtype=torch.bfloat16, device=dev())
+    h.hif8_expand_bf16(ca, M, K, xa, ld)
+    h.hif8_expand_bf16(cb, N, K, xb, ld)
+    out_x = torch.empty(M, N, dtype=torch.float32, device=dev())
+    out_c = torch.empty(M, N, dtype=torch.float32, device=dev())
+    h.hif8_gemm_expanded_f32(xa, xb, out_x, M, N, K, ld, 4.0, 0.5)
+    h.hif8_gemm_f32(ca, cb, out_c, M, N, K, 4.0, 0.5)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(1)
+    rows = np.unique(np.concatenate([[0, 1, 255, 256, M - 1], rng.integers(0, M, 59)]))
+    cols = np.unique(np.concatenate([[0, 31, 32, 257, N - 1], rng.integers(0, N, 59)]))
+    sa, sb = ca[torch.from_numpy(rows).to(dev())].cpu().numpy(), cb[torch.from_numpy(cols).to(dev())].cpu().numpy()
+    for out in (out_x, out_c):
+        got = out[torch.from_numpy(rows).to(dev())][:, torch.from_numpy(cols).to(dev())].cpu().numpy()
+        diff, bound = check(got, sa, sb, 4.0, 0.5)
+        assert np.mean(diff) <= 0.05 * K * 2.0 ** -23 * np.mean(bound)
