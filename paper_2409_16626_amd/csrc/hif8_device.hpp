@@ -362,6 +362,26 @@ __device__ __forceinline__ uint32_t hr16_round_bits(uint32_t ybits, const HrExp1
   return ((a + add) & p.mask) | (ybits & 0x80000000u);
 }
 
+// Per-tensor scale from an amax (Sec. 5): fl32(target / amax), with pow2 the largest power of two not
+// above it; amax zero, Inf or NaN, or a quotient that is not finite and positive, gives 1.
+// The division must be the correctly rounded one (the library is compiled that way).
+__device__ __forceinline__ float scale_from_amax_value(float amax, float target, int pow2) {
+  union { uint32_t u; float f; } a, q, s;
+  a.f = amax;
+  s.f = 1.0f;
+  if (a.u != 0u && a.u < 0x7F800000u) {  // positive, finite, non-zero
+    q.f = target / amax;
+    if (q.u != 0u && q.u < 0x7F800000u) {
+      s.f = q.f;
+      if (pow2) {
+        if ((q.u >> 23) != 0u) s.u = q.u & 0x7F800000u;
+        else s.u = 1u << (31 - __clz((int)q.u));  // subnormal quotient
+      }
+    }
+  }
+  return s.f;
+}
+
 // binary32 pattern of the value of a code (Eq. (1), Eq. (2), special patterns).
 __device__ __forceinline__ uint32_t decode_bits(uint32_t code) {
   const uint32_t s = (code & 0x80u) << 24;

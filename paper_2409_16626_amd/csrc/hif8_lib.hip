@@ -47,20 +47,7 @@ __global__ void k_scale_from_amax(const float* d_amax, float* d_scale2, uint32_t
   if (i >= count) return;
   d_amax += i;
   d_scale2 += 2 * i;
-  const float amax = *d_amax;
-  const uint32_t ab = __float_as_uint(amax);
-  float s = 1.0f;
-  if (ab != 0u && ab < 0x7F800000u) {  // positive, finite, non-zero
-    const float q = target / amax;     // correctly rounded divide
-    const uint32_t qb = __float_as_uint(q);
-    if (qb != 0u && qb < 0x7F800000u) {
-      s = q;
-      if (pow2) {
-        if ((qb >> 23) != 0u) s = __uint_as_float(qb & 0x7F800000u);
-        else s = __uint_as_float(1u << (31 - __clz((int)qb)));  // subnormal quotient
-      }
-    }
-  }
+  const float s = scale_from_amax_value(*d_amax, target, pow2);
   d_scale2[0] = s;
   d_scale2[1] = 1.0f / s;
 }

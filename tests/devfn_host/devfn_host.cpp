@@ -12,6 +12,10 @@ static inline int __clz(int x) { return x == 0 ? 32 : __builtin_clz((unsigned)x)
 #include "../../paper_2409_16626_amd/csrc/hif8_device.hpp"
 
 extern "C" {
+// per-tensor scale from an amax (the arithmetic of the scale kernels)
+void devfn_scale_from_amax(const float* amax, float* out, size_t n, float target, int pow2) {
+  for (size_t i = 0; i < n; ++i) out[i] = hif8dev::scale_from_amax_value(amax[i], target, pow2);
+}
 // generic element-wise form (any rounding method, any source kind)
 void devfn_encode_bits(const uint32_t* ybits, uint8_t* dst, size_t n, uint32_t mode, int srck,
                        uint64_t seed) {

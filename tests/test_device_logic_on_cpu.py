@@ -119,3 +119,27 @@ def test_device_narrow_logic(dev):
     dev.devfn_narrow_bf16(u.ctypes.data_as(ctypes.c_void_p), out.ctypes.data_as(ctypes.c_void_p),
                           ctypes.c_size_t(u.size))
     assert np.array_equal(out, orc.narrow_bf16(u.view(np.float32)))
+
+
+def test_device_scale_from_amax_logic(dev):
+    """The scale arithmetic of the scale kernels (fl32(target / amax), optional floor to a power of two,
+    degenerate amax -> 1) against the oracle, bit for bit, on special values and random patterns."""
+    rng = np.random.default_rng(23)
+    special = np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 1e-45, 1.1754944e-38, 3.4028235e38, 1.0, 32768.0, 32767.99,
+                        5e-39, 2.5e-41, 3.0e33, 6.1e-5], np.float32)
+    rnd = rng.integers(0, 2 ** 31, size=200000, dtype=np.int64).astype(np.uint32).view(np.float32)   # non-negative patterns
+    amax = np.concatenate([special, rnd, np.exp2(rng.uniform(-40, 40, 50000)).astype(np.float32)])
+    out = np.empty(amax.shape, np.float32)
+    for target in (32768.0, 1.0, 448.0, 3.0e38, 1e-30):
+        for pow2 in (0, 1):
+            dev.devfn_scale_from_amax(amax.ctypes.data_as(ctypes.c_void_p), out.ctypes.data_as(ctypes.c_void_p),
+                                      ctypes.c_size_t(amax.size), ctypes.c_float(target), ctypes.c_int(pow2))
+            want = np.array([orc.scale_from_amax(a, target, bool(pow2)) for a in amax[:2000]], np.float32)
+            assert np.array_equal(out[:2000].view(np.uint32), want.view(np.uint32)), (target, pow2)
+            assert np.all(out > 0) and np.all(np.isfinite(out))
+            if pow2:      # a power of two: empty mantissa field, or (subnormal) a single mantissa bit
+                b = out.view(np.uint32)
+                normal = (b >> 23) != 0
+                assert np.all((b[normal] & 0x7FFFFF) == 0)
+                sub = b[~normal]
+                assert np.all((sub & (sub - 1)) == 0)
