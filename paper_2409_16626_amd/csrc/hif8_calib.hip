@@ -55,11 +55,11 @@ k_scale_sweep(const void* __restrict__ src, size_t n, int e_lo, int count_arg, u
               const uint8_t* __restrict__ g_lut, const uint32_t* __restrict__ g_dec,
               double* __restrict__ err) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
-  __shared__ __attribute__((aligned(16))) HrEntry<SRCK> hrt[IMPL == IMPL_HR ? 256 : 1];
+  __shared__ HrLds<IMPL == IMPL_HR> hrt;
   __shared__ uint32_t dec[256];
-  const EncCtx ctx{lut, hrt, mode, seed};
+  const EncCtx ctx{lut, hrt.w, mode, seed};
   stage_enc_lut<IMPL>(lut, g_lut, mode);
-  if (IMPL == IMPL_HR) stage_hr_table(hrt, mode);
+  if (IMPL == IMPL_HR) stage_hr_table<SRCK>(hrt.w, mode);
   stage_dec_lut(dec, g_dec);
   __syncthreads();
 
@@ -259,8 +259,8 @@ k_encode_rows(const void* __restrict__ src, uint8_t* __restrict__ dst, uint32_t 
               const float* __restrict__ d_scale2, uint32_t mode, uint64_t seed,
               const uint8_t* __restrict__ g_lut) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
-  __shared__ __attribute__((aligned(16))) HrEntry<SRCK> hrt[IMPL == IMPL_HR ? 256 : 1];
-  const EncCtx ctx{lut, hrt, mode, seed};
+  __shared__ HrLds<IMPL == IMPL_HR> hrt;
+  const EncCtx ctx{lut, hrt.w, mode, seed};
   constexpr int VE = vec_elems<SRCK>();
   const uint32_t row = blockIdx.x / chunks, chunk = blockIdx.x - row * chunks;
   const size_t rbase = (size_t)row * cols_vec;
@@ -273,7 +273,7 @@ k_encode_rows(const void* __restrict__ src, uint8_t* __restrict__ dst, uint32_t 
   }
   const float scale = d_scale2[2 * (size_t)row];
   stage_enc_lut<IMPL>(lut, g_lut, mode);
-  if (IMPL == IMPL_HR) stage_hr_table(hrt, mode);
+  if (IMPL == IMPL_HR) stage_hr_table<SRCK>(hrt.w, mode);
   __syncthreads();
 #pragma unroll
   for (int j = 0; j < kAxUnroll; ++j) {
@@ -294,10 +294,10 @@ k_encode_cols(const void* __restrict__ src, uint8_t* __restrict__ dst, uint32_t 
               uint32_t strips, uint32_t rows_per_wg, const float* __restrict__ d_scale2, uint32_t mode,
               uint64_t seed, const uint8_t* __restrict__ g_lut) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
-  __shared__ __attribute__((aligned(16))) HrEntry<SRCK> hrt[IMPL == IMPL_HR ? 256 : 1];
-  const EncCtx ctx{lut, hrt, mode, seed};
+  __shared__ HrLds<IMPL == IMPL_HR> hrt;
+  const EncCtx ctx{lut, hrt.w, mode, seed};
   stage_enc_lut<IMPL>(lut, g_lut, mode);
-  if (IMPL == IMPL_HR) stage_hr_table(hrt, mode);
+  if (IMPL == IMPL_HR) stage_hr_table<SRCK>(hrt.w, mode);
   __syncthreads();
   constexpr int VE = vec_elems<SRCK>();
   const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;

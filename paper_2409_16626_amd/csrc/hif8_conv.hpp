@@ -50,14 +50,24 @@ constexpr int vec_shift() { return SRCK == kSrcF32 ? 2 : 3; }
 // ------------------------------------------------------------------------------------
 // small device helpers
 // ------------------------------------------------------------------------------------
-// per-exponent parameters of the HR / simplified-SR path: scaled-integer form for binary32 sources (SR14),
-// add-and-mask form for 16-bit sources (SR2)
-template <int SRCK>
-using HrEntry = std::conditional_t<SRCK == kSrcF32, HrExp, HrExp16>;
+// Per-exponent parameters of the HR / simplified-SR path (add-and-mask forms: SR14 for binary32 sources, SR2
+// for 16-bit sources) in LDS, 4 KiB either way.
+//   binary32 sources: 256 entries of 16 bytes {C, -mult, mask, lo | hi << 16}, one ds_read_b128 per element.
+//     (Measured alternatives: 32-byte entries -- two reads, and entries 32 bytes apart share banks across
+//     exponents: 2.8 TB/s on the wide-range C2 tensor; one dword array per parameter -- conflict-free but five
+//     reads per element, and the LDS takes about four cycles per wavefront instruction: 5.3 TB/s; 16-byte
+//     entries: 6.1-6.2 TB/s.)
+//   16-bit sources: three 256-entry dword arrays add0[], add1[], mask[] -- twice as many elements per byte of
+//     tensor, and with 16-byte entries lanes whose exponents are 16 apart collide: 5.3 TB/s on a narrow
+//     tensor but 3.9 TB/s on a wide-range one; the arrays give 5.2-5.4 TB/s on both.
+template <bool ON>
+struct HrLds {
+  __attribute__((aligned(16))) uint32_t w[ON ? 4 * 256 : 4];
+};
 
 struct EncCtx {
   const uint8_t* lut;  // staged table(s) in LDS
-  const void* hrt;     // staged per-exponent parameters in LDS (IMPL_HR): HrEntry<SRCK>[256]
+  const uint32_t* hrt; // staged per-exponent parameters in LDS (IMPL_HR): HrLds::w
   uint32_t mode;
   uint64_t seed;       // IMPL_SR
 };
@@ -65,17 +75,22 @@ struct EncCtx {
 template <int IMPL>
 __device__ __forceinline__ void stage_enc_lut(uint8_t* lut, const uint8_t* __restrict__ g_lut, uint32_t mode) {
   if (lut_bytes<IMPL>() < 8192u) return;
-  const uint4* g = reinterpret_cast<const uint4*>(g_lut + ((mode & kFlagSat) ? 16384u : 0u));
+  const uint4* g = reinterpret_cast<const uint4*>(g_lut + ((mode & kFlagNan2Zero) ? 32768u : 0u) + ((mode & kFlagSat) ? 16384u : 0u));
   uint4* l = reinterpret_cast<uint4*>(lut);
   for (uint32_t i = threadIdx.x; i < lut_bytes<IMPL>() / 16u; i += blockDim.x) l[i] = g[i];
 }
-__device__ __forceinline__ void stage_hr_table(HrExp* hrt, uint32_t mode) {
+template <int SRCK>
+__device__ __forceinline__ void stage_hr_table(uint32_t* w, uint32_t mode) {
   const bool ssr = (mode & 0xFu) == kRmSSR;
-  for (uint32_t i = threadIdx.x; i < 256u; i += blockDim.x) hrt[i] = hr_exp_entry(i, ssr);
-}
-__device__ __forceinline__ void stage_hr_table(HrExp16* hrt, uint32_t mode) {
-  const bool ssr = (mode & 0xFu) == kRmSSR;
-  for (uint32_t i = threadIdx.x; i < 256u; i += blockDim.x) hrt[i] = hr16_exp_entry(i, ssr);
+  for (uint32_t i = threadIdx.x; i < 256u; i += blockDim.x) {
+    if constexpr (SRCK == kSrcF32) {
+      const HrExp h = hr_exp_entry(i, ssr);
+      reinterpret_cast<uint4*>(w)[i] = make_uint4(h.C, (uint32_t)h.negmult, h.mask, h.lo | (h.hi << 16));
+    } else {
+      const HrExp16 h = hr16_exp_entry(i, ssr);
+      w[i] = h.add0; w[256 + i] = h.add1; w[512 + i] = h.mask;
+    }
+  }
 }
 __device__ __forceinline__ void stage_dec_lut(uint32_t* lut, const uint32_t* __restrict__ g_dec) {
   for (uint32_t i = threadIdx.x; i < 256u; i += blockDim.x) lut[i] = g_dec[i];
@@ -100,14 +115,27 @@ __device__ __forceinline__ uint32_t encode_one(uint32_t ybits, const EncCtx& c, 
       code = c.lut[(ybits >> 19) + ((ybits & 0x7FFFFu) ? 0u : 8192u)];
     } else {
       // HR / SSR: rounding to the grid, then the byte of the (now representable) pattern
-      const HrEntry<SRCK>& p = reinterpret_cast<const HrEntry<SRCK>*>(c.hrt)[(ybits >> 23) & 0xFFu];
       uint32_t r;
-      if constexpr (SRCK == kSrcF32) r = hr_round_bits<SRCK>(ybits, p);
-      else r = hr16_round_bits<SRCK>(ybits, p);
+      if constexpr (SRCK == kSrcF32) {
+        const uint4 q = reinterpret_cast<const uint4*>(c.hrt)[(ybits >> 23) & 0xFFu];
+        HrExp p;
+        p.C = q.x; p.negmult = (int32_t)q.y; p.mask = q.z; p.lo = q.w & 0xFFFFu; p.hi = q.w >> 16;
+        r = hr_round_bits<SRCK>(ybits, p);
+      } else {
+        const uint32_t* t = c.hrt + ((ybits >> 23) & 0xFFu);
+        HrExp16 p;
+        p.add0 = t[0]; p.add1 = t[256]; p.mask = t[512];
+        r = hr16_round_bits<SRCK>(ybits, p);
+      }
       code = c.lut[r >> 19];
     }
-    // NaNs whose payload sits only in the low 19 bits index the Inf entry; fix them here.
-    if ((ybits & 0x7FFFFFFFu) > 0x7F800000u) code = nan_code(c.mode);
+    // NaN: ybits is always the result of the scale multiply, which returns a quiet NaN (bit 22 set) for
+    // any NaN input, so the pattern indexes a NaN entry of the table (which holds the code of the NaN
+    // option in effect); the HR forms pass NaN patterns through unchanged.  Standard SR adds to the pattern
+    // before the lookup and checks for NaN itself.
+    if constexpr (IMPL == IMPL_SR) {
+      if ((ybits & 0x7FFFFFFFu) > 0x7F800000u) code = nan_code(c.mode);
+    }
     return code;
   }
 }
@@ -236,8 +264,8 @@ k_encode(const void* __restrict__ src, uint8_t* __restrict__ dst, size_t n, floa
          const float* __restrict__ d_scale2, uint32_t* __restrict__ amax_acc, uint32_t mode,
          uint64_t seed, const uint8_t* __restrict__ g_lut, Walk walk) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
-  __shared__ __attribute__((aligned(16))) HrEntry<SRCK> hrt[IMPL == IMPL_HR ? 256 : 1];
-  const EncCtx ctx{lut, hrt, mode, seed};
+  __shared__ HrLds<IMPL == IMPL_HR> hrt;
+  const EncCtx ctx{lut, hrt.w, mode, seed};
   const float scale = d_scale2 ? d_scale2[0] : scale_arg;
   const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(src);
   constexpr int VE = vec_elems<SRCK>();
@@ -255,7 +283,7 @@ k_encode(const void* __restrict__ src, uint8_t* __restrict__ dst, size_t n, floa
       [&]() {
         if (IMPL != IMPL_TA_ALU) {
           stage_enc_lut<IMPL>(lut, g_lut, mode);
-          if (IMPL == IMPL_HR) stage_hr_table(hrt, mode);
+          if (IMPL == IMPL_HR) stage_hr_table<SRCK>(hrt.w, mode);
           __syncthreads();
         }
       });
@@ -308,14 +336,14 @@ k_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, float scale_a
              const float* __restrict__ d_scale2, uint32_t* amax_acc, uint32_t mode, uint64_t seed,
              const uint8_t* __restrict__ g_lut, const uint32_t* __restrict__ g_dec, Walk walk) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
-  __shared__ __attribute__((aligned(16))) HrEntry<SRCK> hrt[IMPL == IMPL_HR ? 256 : 1];
+  __shared__ HrLds<IMPL == IMPL_HR> hrt;
   __shared__ uint32_t dec[256];
-  const EncCtx ctx{lut, hrt, mode, seed};
+  const EncCtx ctx{lut, hrt.w, mode, seed};
   const float scale = d_scale2 ? d_scale2[0] : scale_arg;
   const float inv = d_scale2 ? d_scale2[1] : inv_arg;
   auto prologue = [&]() {
     stage_enc_lut<IMPL>(lut, g_lut, mode);
-    if (IMPL == IMPL_HR) stage_hr_table(hrt, mode);
+    if (IMPL == IMPL_HR) stage_hr_table<SRCK>(hrt.w, mode);
     stage_dec_lut(dec, g_dec);
     __syncthreads();
   };
@@ -508,10 +536,10 @@ k_multi_encode(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_
                const float* __restrict__ d_scale2, uint32_t mode, uint64_t seed,
                const uint8_t* __restrict__ g_lut) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
-  __shared__ __attribute__((aligned(16))) HrEntry<SRCK> hrt[IMPL == IMPL_HR ? 256 : 1];
-  const EncCtx ctx{lut, hrt, mode, seed};
+  __shared__ HrLds<IMPL == IMPL_HR> hrt;
+  const EncCtx ctx{lut, hrt.w, mode, seed};
   stage_enc_lut<IMPL>(lut, g_lut, mode);
-  if (IMPL == IMPL_HR) stage_hr_table(hrt, mode);
+  if (IMPL == IMPL_HR) stage_hr_table<SRCK>(hrt.w, mode);
   __syncthreads();
   constexpr int VE = vec_elems<SRCK>();
   for (uint32_t i = 0; i < kMultiTpwEncode; ++i) {

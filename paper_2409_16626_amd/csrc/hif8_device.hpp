@@ -236,21 +236,26 @@ __device__ __forceinline__ uint32_t encode_any(uint32_t ybits, uint32_t mode, ui
 }
 
 // ------------------------------------------------------------------------------------
-// Hybrid rounding, table-driven form for the streaming kernels.
+// Hybrid rounding, table-driven form for the streaming kernels, binary32 sources (SR14).
 //
-// For a value in the binade of biased exponent e the HiF8 grid step is ulp = 2^(E-k)
-// (2^-22 below 2^-22).  Multiplying |y| by c = 2^14 / ulp (exact: a power of two) and
-// truncating to an integer gives Q = n * 2^14 + F with n the kept digits and F the top 14
-// bits of the discarded fraction, which is what both SR14 and SR2 compare with a threshold
-// (SR2's two-bit test F2 >= T2 is F >= T2 * 2^12).  The carry is added as
-// Q - T + 2^14 (bit 14 and up then hold n or n + 1), and n' * ulp is rebuilt by one
-// integer->float conversion and one multiply by 1/c.  Per exponent the table also holds
-// the clamp range of the threshold: [1, 2^14 - 1] where Eq. (3) asks for simplified SR
-// (F = 0 never carries), [2^13, 2^13] where it asks for TA (|E| < 4: carry iff F >= half).
+// With d discarded mantissa bits, "carry iff F14 >= T" (F14 the top 14 discarded bits, Sec. 3.2) is the
+// carry out of the discarded field after adding 2^d - T * 2^(d-14), so the rounding is
+//     r = (a + C - T' * mult) & mask,    C = 2^d,  mult = 2^(d-14),  mask = ~(2^d - 1),
+// on the binary32 pattern a of |y|; the carry propagates into the exponent exactly as in TA.  T' is the
+// threshold T = low 14 bits of the pattern clamped to a per-exponent range: [1, 2^14 - 1] where Eq. (3)
+// asks for simplified SR (so that F = 0 never carries), [2^13, 2^13] where it asks for TA (|E| < 4).
+// Below 2^-22 there is one step from 0 to 2^-22 and F14 = sig >> (10 + j) for exponent 104 - j (sig the
+// 24-bit significand): with C = (j + 1) * 2^23 and mult = 2^(10+j) the sum is 104 * 2^23 + sig - T' * mult,
+// i.e. at or above exponent 104 exactly when it carries; the mask then keeps the exponent only, which
+// the TA table reads as 2^-22 (104, 105) or 0 (below).  T' is clamped to 2^(14-j) there (F14 is smaller
+// than that, and the product stays below 2^24).  Exponents with F14 = 0 (E <= -37), at or above 2^16,
+// Inf and NaN pass unchanged (T' = 0).  The multiply is a 24-bit one (full rate).
 // ------------------------------------------------------------------------------------
 struct HrExp {
-  float c;         // 2^14 / ulp (a power of two; its reciprocal is rebuilt from the bits)
-  uint32_t tpack;  // threshold clamp: low bound in bits [15:0], high bound in bits [31:16]
+  uint32_t C;
+  int32_t negmult;  // -mult
+  uint32_t mask;
+  uint32_t lo, hi;  // clamp range of the threshold
 };
 
 __device__ __forceinline__ float pow2f(int x) {  // 2^x for x in [-126, 127]
@@ -262,61 +267,51 @@ __device__ __forceinline__ float pow2f(int x) {  // 2^x for x in [-126, 127]
 // ssr: simplified SR in every binade (no TA exception for |E| < 4)
 __device__ __forceinline__ HrExp hr_exp_entry(uint32_t e, bool ssr = false) {
   HrExp h;
-  if (e <= 104u) {  // |y| < 2^-22: one step from 0 to 2^-22
-    h.c = pow2f(36);
-    h.tpack = 1u | (0x3FFFu << 16);
+  h.C = 0u; h.negmult = 0; h.mask = 0xFFFFFFFFu; h.lo = 0u; h.hi = 0u;
+  if (e >= 143u || e <= 90u) return h;
+  if (e <= 104u) {
+    const uint32_t j = 104u - e;
+    h.C = (j + 1u) << 23;
+    h.negmult = -(int32_t)(1u << (10u + j));
+    h.mask = 0xFF800000u;
+    h.lo = 1u;
+    h.hi = 1u << (14u - j);
     return h;
   }
-  const int E = (int)e - 127;
-  const int k = (int)kept_bits(e);
-  h.c = pow2f(14 - E + k);
-  h.tpack = (k == 3 && !ssr) ? (0x2000u | (0x2000u << 16)) : (1u | (0x3FFFu << 16));
-  // Inf: the product saturates the integer conversion to 2^32 - 1; a threshold of 2^14
-  // never carries, so Q stays saturated instead of wrapping, and n' * ulp overflows to Inf
-  if (e == 255u) h.tpack = 0x4000u | (0x4000u << 16);
+  const uint32_t k = kept_bits(e), d = 23u - k;
+  const bool ta = (k == 3u) && !ssr;
+  h.C = 1u << d;
+  h.negmult = -(int32_t)(1u << (d - 14u));
+  h.mask = 0xFFFFFFFFu << d;
+  h.lo = ta ? 0x2000u : 1u;
+  h.hi = ta ? 0x2000u : 0x3FFFu;
   return h;
 }
 
 #ifdef HIF8_DEVICE_HOST_SHIM
 // host stand-ins for two hardware instructions (used by the CPU test build only)
-__device__ __forceinline__ uint32_t cvt_u32_trunc_sat(float x) {  // NaN -> 0, saturating
-  if (!(x > 0.0f)) return 0u;
-  if (x >= 4294967296.0f) return 0xFFFFFFFFu;
-  return (uint32_t)x;
-}
 __device__ __forceinline__ uint32_t med3_u32(uint32_t a, uint32_t lo, uint32_t hi) {
   return a < lo ? lo : (a > hi ? hi : a);
 }
+__device__ __forceinline__ int32_t mul_i24(int32_t a, int32_t b) { return a * b; }  // operands fit 24 bits
 #else
-__device__ __forceinline__ uint32_t cvt_u32_trunc_sat(float x) {
-  uint32_t q;
-  asm("v_cvt_u32_f32 %0, %1" : "=v"(q) : "v"(x));  // truncates; saturates; NaN -> 0
-  return q;
-}
 __device__ __forceinline__ uint32_t med3_u32(uint32_t a, uint32_t lo, uint32_t hi) {
   uint32_t r;
   asm("v_med3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(lo), "v"(hi));
   return r;
 }
+__device__ __forceinline__ int32_t mul_i24(int32_t a, int32_t b) { return __mul24(a, b); }
 #endif
 
-// Rounded binary32 pattern (sign kept) of non-NaN pattern ybits under HR; p = table entry
-// of ybits' exponent.  The result is on the HiF8 grid (or at/above 1.5 * 2^15: overflow).
+// Rounded binary32 pattern (sign kept) of pattern ybits under HR; p = table entry of ybits' exponent.
+// The result is on the HiF8 grid (or at/above 1.5 * 2^15: overflow); NaN patterns come back unchanged.
 template <int SRCK>
 __device__ __forceinline__ uint32_t hr_round_bits(uint32_t ybits, const HrExp& p) {
-  union { uint32_t u; float f; } y, r, c, inv;
-  y.u = ybits & 0x7FFFFFFFu;
-  c.f = p.c;
-  inv.u = 0x7F000000u - c.u;  // 1/c for c = 2^x: exponent field 127 - x
-  const uint32_t q = cvt_u32_trunc_sat(y.f * c.f);
-  // SR2: T2 = {source LSB, 1} against the top two fraction bits == T2 * 2^12 against F14
-  uint32_t T = (SRCK == kSrcBF16) ? (((ybits >> 3) & 0x2000u) | 0x1000u)
-             : (SRCK == kSrcF16)  ? ((ybits & 0x2000u) | 0x1000u)
-                                  : (ybits & 0x3FFFu);
-  T = med3_u32(T, p.tpack & 0xFFFFu, p.tpack >> 16);
-  const uint32_t qq = (q - T + 0x4000u) & 0xFFFFC000u;
-  r.f = (float)qq * inv.f;
-  return r.u | (ybits & 0x80000000u);
+  static_assert(SRCK == kSrcF32, "binary32 sources; 16-bit sources use hr16_round_bits");
+  const uint32_t a = ybits & 0x7FFFFFFFu;
+  const uint32_t T = med3_u32(ybits & 0x3FFFu, p.lo, p.hi);
+  const uint32_t r = (a + p.C + (uint32_t)mul_i24((int32_t)T, p.negmult)) & p.mask;
+  return r | (ybits & 0x80000000u);
 }
 
 // ------------------------------------------------------------------------------------
@@ -334,12 +329,11 @@ struct HrExp16 {
   uint32_t add0;  // source LSB 0: T2 = 1
   uint32_t add1;  // source LSB 1: T2 = 3
   uint32_t mask;
-  uint32_t pad;
 };
 
 __device__ __forceinline__ HrExp16 hr16_exp_entry(uint32_t e, bool ssr = false) {
   HrExp16 h;
-  h.add0 = 0u; h.add1 = 0u; h.mask = 0xFFFFFFFFu; h.pad = 0u;
+  h.add0 = 0u; h.add1 = 0u; h.mask = 0xFFFFFFFFu;
   if (e >= 143u || e <= 102u) return h;
   if (e == 104u) { h.add0 = 1u << 22; h.add1 = 0u - (1u << 22); return h; }  // F2 = {1, m22}
   if (e == 103u) { h.add0 = 1u << 23; return h; }                           // F2 = 01: carries iff T2 = 1

@@ -16,8 +16,8 @@ namespace hif8host {
 // Read-only lookup tables in static device memory of one device (addresses of that device's
 // copy, resolved once by ensure_init()).
 struct DevTables {
-  // [sat 0/1][kind 0/1][8192] bytes.  kind 0: TA code of pattern (i << 19); kind 1: TE code of
-  // the same pattern (used only when the low 19 bits of the converted pattern are all zero).
+  // [NaN -> 0 option 0/1][sat 0/1][kind 0/1][8192] bytes.  kind 0: TA code of pattern (i << 19); kind 1: TE
+  // code of the same pattern (used only when the low 19 bits of the converted pattern are all zero).
   const uint8_t* enc_lut;
   const uint32_t* dec_lut;  // [256] code -> binary32 pattern
 };

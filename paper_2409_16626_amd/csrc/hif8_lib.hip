@@ -21,16 +21,20 @@ using namespace hif8dev;
 // ------------------------------------------------------------------------------------
 // static device tables (written once per device by k_build_tables)
 // ------------------------------------------------------------------------------------
-static __device__ __attribute__((aligned(16))) uint8_t g_enc_lut[2][2][8192];  // [sat][TA, TE][pattern >> 19]
+static __device__ __attribute__((aligned(16))) uint8_t g_enc_lut[2][2][2][8192];  // [NaN -> 0][sat][TA, TE][pattern >> 19]
 static __device__ __attribute__((aligned(16))) uint32_t g_dec_lut[256];        // code -> binary32 bits
 
 __global__ void k_build_tables() {
   const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < 8192u) {
-    g_enc_lut[0][0][i] = (uint8_t)encode_alu<false, kSrcF32>(i << 19, 0u);
-    g_enc_lut[1][0][i] = (uint8_t)encode_alu<false, kSrcF32>(i << 19, kFlagSat);
-    g_enc_lut[0][1][i] = (uint8_t)encode_any<kSrcF32>(i << 19, kRmTE, 0u);
-    g_enc_lut[1][1][i] = (uint8_t)encode_any<kSrcF32>(i << 19, kRmTE | kFlagSat, 0u);
+#pragma unroll
+    for (uint32_t z = 0; z < 2u; ++z)
+#pragma unroll
+      for (uint32_t sat = 0; sat < 2u; ++sat) {
+        const uint32_t flags = (z ? kFlagNan2Zero : 0u) | (sat ? kFlagSat : 0u);
+        g_enc_lut[z][sat][0][i] = (uint8_t)encode_alu<false, kSrcF32>(i << 19, flags);
+        g_enc_lut[z][sat][1][i] = (uint8_t)encode_any<kSrcF32>(i << 19, kRmTE | flags, 0u);
+      }
   }
   if (i < 256u) g_dec_lut[i] = decode_bits(i);
 }
