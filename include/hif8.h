@@ -103,9 +103,10 @@ hif8_status hif8_init(void);
 /*
  * Seed of the threshold generator of HIF8_RM_SR (process-wide; default 0).  A call uses the
  * seed in effect when it is enqueued.  The 32-bit threshold of element i (index within the
- * tensor of the call) is two rounds of the 32-bit MurmurHash3 finaliser
+ * tensor of the call) is the 32-bit MurmurHash3 finaliser
  *     fmix(x): x ^= x >> 16; x *= 0x85EBCA6B; x ^= x >> 13; x *= 0xC2B2AE35; x ^= x >> 16
- *     t = fmix( fmix(lo32(i) ^ lo32(seed)) + hi32(i) * 0x9E3779B9 + hi32(seed) )
+ * over the low index word and a key that is constant over 2^32 consecutive elements:
+ *     key = fmix( hi32(seed) + hi32(i) * 0x9E3779B9 ) ^ lo32(seed),    t = fmix( lo32(i) ^ key )
  * so results are reproducible and independent of the launch shape.  Sec. 3.2 notes that
  * standard SR needs a random number per element; a counter-based hash supplies it here.
  */

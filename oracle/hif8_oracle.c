@@ -63,8 +63,9 @@
  *         element from a counter-based generator (below); strict "<" makes the
  *         carry probability exactly F for a discrete uniform T and keeps
  *         representable inputs fixed (the paper writes F >= T for a real-valued T).
- *         Threshold of element i under seed s: two rounds of the 32-bit finaliser
- *         of MurmurHash3 over (low words of i and s), then (high words).
+ *         Threshold of element i under seed s: the 32-bit finaliser of MurmurHash3
+ *         over the low word of i xor a key made from s and the high word of i
+ *         (for i, s < 2^32: fmix(i ^ s)).
  *   - FP16 sources use SR2 with the FP16 LSB (bit 13 of the binary32 pattern
  *     being converted, so that, as for BF16, a scaled product is handled too).
  *
@@ -237,9 +238,8 @@ static uint32_t fmix32(uint32_t x) {
   return x;
 }
 uint32_t hif8o_sr_threshold(uint64_t seed, uint64_t index) {
-  uint32_t x = fmix32((uint32_t)index ^ (uint32_t)seed);
-  x += (uint32_t)(index >> 32) * 0x9E3779B9u + (uint32_t)(seed >> 32);
-  return fmix32(x);
+  const uint32_t key = fmix32((uint32_t)(seed >> 32) + (uint32_t)(index >> 32) * 0x9E3779B9u) ^ (uint32_t)seed;
+  return fmix32((uint32_t)index ^ key);
 }
 static uint64_t g_sr_seed = 0;
 void hif8o_set_sr_seed(uint64_t seed) { g_sr_seed = seed; }

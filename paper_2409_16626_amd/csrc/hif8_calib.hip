@@ -55,11 +55,11 @@ k_scale_sweep(const void* __restrict__ src, size_t n, int e_lo, int count_arg, u
               const uint8_t* __restrict__ g_lut, const uint32_t* __restrict__ g_dec,
               double* __restrict__ err) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
-  __shared__ HrLds<IMPL == IMPL_HR> hrt;
+  __shared__ HrLds<uses_exp_table<IMPL>()> hrt;
   __shared__ uint32_t dec[256];
-  const EncCtx ctx{lut, hrt.w, mode, seed};
+  const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, seed);
   stage_enc_lut<IMPL>(lut, g_lut, mode);
-  if (IMPL == IMPL_HR) stage_hr_table<SRCK>(hrt.w, mode);
+  stage_exp_table<IMPL, SRCK>(hrt.w, mode);
   stage_dec_lut(dec, g_dec);
   __syncthreads();
 
@@ -80,11 +80,12 @@ k_scale_sweep(const void* __restrict__ src, size_t n, int e_lo, int count_arg, u
   // one element at all scales, in stages so that the table reads of the scales are in flight
   // together: casts, then descaled values, then the fp64 accumulation
   auto score = [&](uint32_t xb, uint64_t elem) {
+    const EncCtx kc = keyed<IMPL>(ctx, elem);
     const double xd = (double)__uint_as_float(xb);
     if constexpr (NSC != 0) {
       uint32_t c[KMAX], q[KMAX];
 #pragma unroll
-      for (int k = 0; k < KMAX; ++k) c[k] = encode_one<IMPL, SRCK>(scaled_bits(xb, sc[k]), ctx, elem);
+      for (int k = 0; k < KMAX; ++k) c[k] = encode_one<IMPL, SRCK>(scaled_bits(xb, sc[k]), kc, elem);
 #pragma unroll
       for (int k = 0; k < KMAX; ++k) q[k] = descale_bits(c[k], dec, isc[k]);
 #pragma unroll
@@ -96,7 +97,7 @@ k_scale_sweep(const void* __restrict__ src, size_t n, int e_lo, int count_arg, u
 #pragma unroll
       for (int k = 0; k < KMAX; ++k) {
         if (k < count) {  // uniform across the grid
-          const uint32_t c = encode_one<IMPL, SRCK>(scaled_bits(xb, sc[k]), ctx, elem);
+          const uint32_t c = encode_one<IMPL, SRCK>(scaled_bits(xb, sc[k]), kc, elem);
           const double d = xd - (double)__uint_as_float(descale_bits(c, dec, isc[k]));
           acc[k] = fma(d, d, acc[k]);
         }
@@ -259,8 +260,8 @@ k_encode_rows(const void* __restrict__ src, uint8_t* __restrict__ dst, uint32_t 
               const float* __restrict__ d_scale2, uint32_t mode, uint64_t seed,
               const uint8_t* __restrict__ g_lut) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
-  __shared__ HrLds<IMPL == IMPL_HR> hrt;
-  const EncCtx ctx{lut, hrt.w, mode, seed};
+  __shared__ HrLds<uses_exp_table<IMPL>()> hrt;
+  const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, seed);
   constexpr int VE = vec_elems<SRCK>();
   const uint32_t row = blockIdx.x / chunks, chunk = blockIdx.x - row * chunks;
   const size_t rbase = (size_t)row * cols_vec;
@@ -273,7 +274,7 @@ k_encode_rows(const void* __restrict__ src, uint8_t* __restrict__ dst, uint32_t 
   }
   const float scale = d_scale2[2 * (size_t)row];
   stage_enc_lut<IMPL>(lut, g_lut, mode);
-  if (IMPL == IMPL_HR) stage_hr_table<SRCK>(hrt.w, mode);
+  stage_exp_table<IMPL, SRCK>(hrt.w, mode);
   __syncthreads();
 #pragma unroll
   for (int j = 0; j < kAxUnroll; ++j) {
@@ -294,10 +295,10 @@ k_encode_cols(const void* __restrict__ src, uint8_t* __restrict__ dst, uint32_t 
               uint32_t strips, uint32_t rows_per_wg, const float* __restrict__ d_scale2, uint32_t mode,
               uint64_t seed, const uint8_t* __restrict__ g_lut) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
-  __shared__ HrLds<IMPL == IMPL_HR> hrt;
-  const EncCtx ctx{lut, hrt.w, mode, seed};
+  __shared__ HrLds<uses_exp_table<IMPL>()> hrt;
+  const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, seed);
   stage_enc_lut<IMPL>(lut, g_lut, mode);
-  if (IMPL == IMPL_HR) stage_hr_table<SRCK>(hrt.w, mode);
+  stage_exp_table<IMPL, SRCK>(hrt.w, mode);
   __syncthreads();
   constexpr int VE = vec_elems<SRCK>();
   const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
@@ -313,19 +314,20 @@ k_encode_cols(const void* __restrict__ src, uint8_t* __restrict__ dst, uint32_t 
   auto encode_row = [&](uint32_t r, const uint4& v) {
     const size_t idx = (size_t)r * cols_vec + cv;
     const uint64_t e0 = (uint64_t)idx * VE;
+    const EncCtx kc = keyed<IMPL>(ctx, e0);
     if constexpr (SRCK == kSrcF32) {
-      const uint32_t c0 = encode_one<IMPL, SRCK>(scaled_bits(v.x, sc[0]), ctx, e0);
-      const uint32_t c1 = encode_one<IMPL, SRCK>(scaled_bits(v.y, sc[1]), ctx, e0 + 1);
-      const uint32_t c2 = encode_one<IMPL, SRCK>(scaled_bits(v.z, sc[2]), ctx, e0 + 2);
-      const uint32_t c3 = encode_one<IMPL, SRCK>(scaled_bits(v.w, sc[3]), ctx, e0 + 3);
+      const uint32_t c0 = encode_one<IMPL, SRCK>(scaled_bits(v.x, sc[0]), kc, e0);
+      const uint32_t c1 = encode_one<IMPL, SRCK>(scaled_bits(v.y, sc[1]), kc, e0 + 1);
+      const uint32_t c2 = encode_one<IMPL, SRCK>(scaled_bits(v.z, sc[2]), kc, e0 + 2);
+      const uint32_t c3 = encode_one<IMPL, SRCK>(scaled_bits(v.w, sc[3]), kc, e0 + 3);
       st_stream(reinterpret_cast<uint32_t*>(dst) + idx, c0 | (c1 << 8) | (c2 << 16) | (c3 << 24));
     } else {
       const uint32_t w[4] = {v.x, v.y, v.z, v.w};
       uint32_t o[2] = {0u, 0u};
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const uint32_t c0 = encode_one<IMPL, SRCK>(scaled_bits(widen_lo<SRCK>(w[j]), sc[2 * j]), ctx, e0 + 2 * j);
-        const uint32_t c1 = encode_one<IMPL, SRCK>(scaled_bits(widen_hi<SRCK>(w[j]), sc[2 * j + 1]), ctx, e0 + 2 * j + 1);
+        const uint32_t c0 = encode_one<IMPL, SRCK>(scaled_bits(widen_lo<SRCK>(w[j]), sc[2 * j]), kc, e0 + 2 * j);
+        const uint32_t c1 = encode_one<IMPL, SRCK>(scaled_bits(widen_hi<SRCK>(w[j]), sc[2 * j + 1]), kc, e0 + 2 * j + 1);
         o[j >> 1] |= (c0 | (c1 << 8)) << (16 * (j & 1));
       }
       st_stream(reinterpret_cast<uint2*>(dst) + idx, make_uint2(o[0], o[1]));

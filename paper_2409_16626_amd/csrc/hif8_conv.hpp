@@ -60,6 +60,9 @@ constexpr int vec_shift() { return SRCK == kSrcF32 ? 2 : 3; }
 //   16-bit sources: three 256-entry dword arrays add0[], add1[], mask[] -- twice as many elements per byte of
 //     tensor, and with 16-byte entries lanes whose exponents are 16 apart collide: 5.3 TB/s on a narrow
 //     tensor but 3.9 TB/s on a wide-range one; the arrays give 5.2-5.4 TB/s on both.
+//   standard SR: 256 entries of 16 bytes {offset, width, mask, factor} (sr_exp_entry()).
+template <int IMPL>
+constexpr bool uses_exp_table() { return IMPL == IMPL_HR || IMPL == IMPL_SR; }
 template <bool ON>
 struct HrLds {
   __attribute__((aligned(16))) uint32_t w[ON ? 4 * 256 : 4];
@@ -67,10 +70,33 @@ struct HrLds {
 
 struct EncCtx {
   const uint8_t* lut;  // staged table(s) in LDS
-  const uint32_t* hrt; // staged per-exponent parameters in LDS (IMPL_HR): HrLds::w
+  const uint32_t* hrt; // staged per-exponent parameters in LDS (IMPL_HR, IMPL_SR): HrLds::w
   uint32_t mode;
   uint64_t seed;       // IMPL_SR
+  uint32_t sr_key;     // IMPL_SR: key of the 2^32-element block sr_hi (set by keyed())
+  uint32_t sr_hi;
 };
+
+// Context for encoding elements of the 2^32-element block that holds element `elem` (standard SR draws its
+// thresholds from the low index word and a per-block key; other methods ignore it).  The key is computed
+// only when the block differs from the one the context was last keyed for.
+template <int IMPL>
+__device__ __forceinline__ EncCtx keyed(const EncCtx& c, uint64_t elem) {
+  if constexpr (IMPL != IMPL_SR) return c;
+  const uint32_t hi = (uint32_t)(elem >> 32);
+  if (hi == c.sr_hi) return c;
+  EncCtx k = c;
+  k.sr_key = sr_key(c.seed, hi);
+  k.sr_hi = hi;
+  return k;
+}
+// A context keyed for block 0 (kernel prologue).
+template <int IMPL>
+__device__ __forceinline__ EncCtx make_ctx(const uint8_t* lut, const uint32_t* hrt, uint32_t mode, uint64_t seed) {
+  EncCtx c{lut, hrt, mode, seed, 0u, 0u};
+  if constexpr (IMPL == IMPL_SR) c.sr_key = sr_key(seed, 0u);
+  return c;
+}
 
 template <int IMPL>
 __device__ __forceinline__ void stage_enc_lut(uint8_t* lut, const uint8_t* __restrict__ g_lut, uint32_t mode) {
@@ -79,11 +105,15 @@ __device__ __forceinline__ void stage_enc_lut(uint8_t* lut, const uint8_t* __res
   uint4* l = reinterpret_cast<uint4*>(lut);
   for (uint32_t i = threadIdx.x; i < lut_bytes<IMPL>() / 16u; i += blockDim.x) l[i] = g[i];
 }
-template <int SRCK>
-__device__ __forceinline__ void stage_hr_table(uint32_t* w, uint32_t mode) {
+template <int IMPL, int SRCK>
+__device__ __forceinline__ void stage_exp_table(uint32_t* w, uint32_t mode) {
+  if constexpr (!uses_exp_table<IMPL>()) return;
   const bool ssr = (mode & 0xFu) == kRmSSR;
   for (uint32_t i = threadIdx.x; i < 256u; i += blockDim.x) {
-    if constexpr (SRCK == kSrcF32) {
+    if constexpr (IMPL == IMPL_SR) {
+      const SrExp h = sr_exp_entry(i);
+      reinterpret_cast<uint4*>(w)[i] = make_uint4(h.off, h.width, h.mask, __float_as_uint(h.fmul));
+    } else if constexpr (SRCK == kSrcF32) {
       const HrExp h = hr_exp_entry(i, ssr);
       reinterpret_cast<uint4*>(w)[i] = make_uint4(h.C, (uint32_t)h.negmult, h.mask, h.lo | (h.hi << 16));
     } else {
@@ -97,7 +127,7 @@ __device__ __forceinline__ void stage_dec_lut(uint32_t* lut, const uint32_t* __r
 }
 
 // One element: scaled pattern -> code.  `elem` is the element's index in the tensor (it
-// selects the threshold of standard SR and is unused otherwise).
+// selects the threshold of standard SR and is unused otherwise); c must be keyed() for elem's block.
 template <int IMPL, int SRCK>
 __device__ __forceinline__ uint32_t encode_one(uint32_t ybits, const EncCtx& c, uint64_t elem) {
   if constexpr (IMPL == IMPL_TA_ALU) {
@@ -108,8 +138,10 @@ __device__ __forceinline__ uint32_t encode_one(uint32_t ybits, const EncCtx& c, 
       code = c.lut[ybits >> 19];
     } else if constexpr (IMPL == IMPL_SR) {
       // standard SR: add the hashed threshold bits below the kept part, truncate, then the byte
-      const uint32_t r = sr_round_bits(ybits & 0x7FFFFFFFu, sr_threshold(c.seed, elem)) | (ybits & 0x80000000u);
-      code = c.lut[r >> 19];
+      const uint4 q = reinterpret_cast<const uint4*>(c.hrt)[(ybits >> 23) & 0xFFu];
+      SrExp p;
+      p.off = q.x; p.width = q.y; p.mask = q.z; p.fmul = __uint_as_float(q.w);
+      code = c.lut[sr_round_bits(ybits, fmix32((uint32_t)elem ^ c.sr_key), p) >> 19];
     } else if constexpr (IMPL == IMPL_TE) {
       // a tie needs every bit below the rounding bit to be zero; otherwise TE rounds as TA
       code = c.lut[(ybits >> 19) + ((ybits & 0x7FFFFu) ? 0u : 8192u)];
@@ -131,11 +163,7 @@ __device__ __forceinline__ uint32_t encode_one(uint32_t ybits, const EncCtx& c, 
     }
     // NaN: ybits is always the result of the scale multiply, which returns a quiet NaN (bit 22 set) for
     // any NaN input, so the pattern indexes a NaN entry of the table (which holds the code of the NaN
-    // option in effect); the HR forms pass NaN patterns through unchanged.  Standard SR adds to the pattern
-    // before the lookup and checks for NaN itself.
-    if constexpr (IMPL == IMPL_SR) {
-      if ((ybits & 0x7FFFFFFFu) > 0x7F800000u) code = nan_code(c.mode);
-    }
+    // option in effect); the HR and SR forms pass NaN patterns through unchanged.
     return code;
   }
 }
@@ -164,7 +192,8 @@ __device__ __forceinline__ uint32_t load_bits(const void* src, size_t i) {
 }
 
 template <int IMPL>
-__device__ __forceinline__ uint32_t encode4_f32(const uint4& v, float scale, const EncCtx& c, uint64_t e0) {
+__device__ __forceinline__ uint32_t encode4_f32(const uint4& v, float scale, const EncCtx& c0_, uint64_t e0) {
+  const EncCtx c = keyed<IMPL>(c0_, e0);  // a vector never straddles a multiple of 2^32 elements
   const uint32_t c0 = encode_one<IMPL, kSrcF32>(scaled_bits(v.x, scale), c, e0);
   const uint32_t c1 = encode_one<IMPL, kSrcF32>(scaled_bits(v.y, scale), c, e0 + 1);
   const uint32_t c2 = encode_one<IMPL, kSrcF32>(scaled_bits(v.z, scale), c, e0 + 2);
@@ -180,7 +209,8 @@ __device__ __forceinline__ uint32_t encode2_16(uint32_t w, float scale, const En
   return c0 | (c1 << 8);
 }
 template <int IMPL, int SRCK>
-__device__ __forceinline__ uint2 encode8_16(const uint4& v, float scale, const EncCtx& c, uint64_t e0) {
+__device__ __forceinline__ uint2 encode8_16(const uint4& v, float scale, const EncCtx& c0_, uint64_t e0) {
+  const EncCtx c = keyed<IMPL>(c0_, e0);  // a vector never straddles a multiple of 2^32 elements
   uint2 o;
   o.x = encode2_16<IMPL, SRCK>(v.x, scale, c, e0) | (encode2_16<IMPL, SRCK>(v.y, scale, c, e0 + 2) << 16);
   o.y = encode2_16<IMPL, SRCK>(v.z, scale, c, e0 + 4) | (encode2_16<IMPL, SRCK>(v.w, scale, c, e0 + 6) << 16);
@@ -264,8 +294,8 @@ k_encode(const void* __restrict__ src, uint8_t* __restrict__ dst, size_t n, floa
          const float* __restrict__ d_scale2, uint32_t* __restrict__ amax_acc, uint32_t mode,
          uint64_t seed, const uint8_t* __restrict__ g_lut, Walk walk) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
-  __shared__ HrLds<IMPL == IMPL_HR> hrt;
-  const EncCtx ctx{lut, hrt.w, mode, seed};
+  __shared__ HrLds<uses_exp_table<IMPL>()> hrt;
+  const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, seed);
   const float scale = d_scale2 ? d_scale2[0] : scale_arg;
   const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(src);
   constexpr int VE = vec_elems<SRCK>();
@@ -283,7 +313,7 @@ k_encode(const void* __restrict__ src, uint8_t* __restrict__ dst, size_t n, floa
       [&]() {
         if (IMPL != IMPL_TA_ALU) {
           stage_enc_lut<IMPL>(lut, g_lut, mode);
-          if (IMPL == IMPL_HR) stage_hr_table<SRCK>(hrt.w, mode);
+          stage_exp_table<IMPL, SRCK>(hrt.w, mode);
           __syncthreads();
         }
       });
@@ -292,7 +322,7 @@ k_encode(const void* __restrict__ src, uint8_t* __restrict__ dst, size_t n, floa
   if (blockIdx.x == 0 && t < n) {
     const uint32_t xb = load_bits<SRCK>(src, t);
     m = umax(m, xb & 0x7FFFFFFFu);
-    dst[t] = (uint8_t)encode_one<IMPL, SRCK>(scaled_bits(xb, scale), ctx, t);
+    dst[t] = (uint8_t)encode_one<IMPL, SRCK>(scaled_bits(xb, scale), keyed<IMPL>(ctx, t), t);
   }
   if (amax_acc) block_max_to_global(m, amax_acc);
 }
@@ -336,14 +366,14 @@ k_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, float scale_a
              const float* __restrict__ d_scale2, uint32_t* amax_acc, uint32_t mode, uint64_t seed,
              const uint8_t* __restrict__ g_lut, const uint32_t* __restrict__ g_dec, Walk walk) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
-  __shared__ HrLds<IMPL == IMPL_HR> hrt;
+  __shared__ HrLds<uses_exp_table<IMPL>()> hrt;
   __shared__ uint32_t dec[256];
-  const EncCtx ctx{lut, hrt.w, mode, seed};
+  const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, seed);
   const float scale = d_scale2 ? d_scale2[0] : scale_arg;
   const float inv = d_scale2 ? d_scale2[1] : inv_arg;
   auto prologue = [&]() {
     stage_enc_lut<IMPL>(lut, g_lut, mode);
-    if (IMPL == IMPL_HR) stage_hr_table<SRCK>(hrt.w, mode);
+    stage_exp_table<IMPL, SRCK>(hrt.w, mode);
     stage_dec_lut(dec, g_dec);
     __syncthreads();
   };
@@ -372,7 +402,7 @@ k_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, float scale_a
   if (blockIdx.x == 0 && t < n) {
     const uint32_t xb = load_bits<SRCK>(src, t);
     m = umax(m, xb & 0x7FFFFFFFu);
-    const uint32_t c = encode_one<IMPL, SRCK>(scaled_bits(xb, scale), ctx, t);
+    const uint32_t c = encode_one<IMPL, SRCK>(scaled_bits(xb, scale), keyed<IMPL>(ctx, t), t);
     const uint32_t b = descale_bits(c, dec, inv);
     if constexpr (SRCK == kSrcF32) reinterpret_cast<uint32_t*>(dst)[t] = b;
     else reinterpret_cast<uint16_t*>(dst)[t] = (uint16_t)narrow1<SRCK>(b);
@@ -536,10 +566,10 @@ k_multi_encode(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_
                const float* __restrict__ d_scale2, uint32_t mode, uint64_t seed,
                const uint8_t* __restrict__ g_lut) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
-  __shared__ HrLds<IMPL == IMPL_HR> hrt;
-  const EncCtx ctx{lut, hrt.w, mode, seed};
+  __shared__ HrLds<uses_exp_table<IMPL>()> hrt;
+  const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, seed);
   stage_enc_lut<IMPL>(lut, g_lut, mode);
-  if (IMPL == IMPL_HR) stage_hr_table<SRCK>(hrt.w, mode);
+  stage_exp_table<IMPL, SRCK>(hrt.w, mode);
   __syncthreads();
   constexpr int VE = vec_elems<SRCK>();
   for (uint32_t i = 0; i < kMultiTpwEncode; ++i) {
@@ -572,7 +602,7 @@ k_multi_encode(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_
     if (local + 1 == multi_item_tiles<SRCK>(n)) {
       const uint64_t t = nvec * VE + threadIdx.x;
       if (t < n)
-        dst[t] = (uint8_t)encode_one<IMPL, SRCK>(scaled_bits(load_bits<SRCK>(items[it].src, t), scale), ctx, t);
+        dst[t] = (uint8_t)encode_one<IMPL, SRCK>(scaled_bits(load_bits<SRCK>(items[it].src, t), scale), keyed<IMPL>(ctx, t), t);
     }
   }
 }

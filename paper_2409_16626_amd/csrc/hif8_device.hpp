@@ -138,16 +138,19 @@ __device__ __forceinline__ uint32_t encode_alu(uint32_t ybits, uint32_t mode) {
 // for clarity: these are not on the throughput path.
 // ------------------------------------------------------------------------------------
 
-// 32-bit threshold of element `index` under `seed`: two rounds of MurmurHash3's 32-bit
-// finaliser, first over the low words, then folding in the high words.
+// MurmurHash3's 32-bit finaliser
 __host__ __device__ __forceinline__ uint32_t fmix32(uint32_t x) {
   x ^= x >> 16; x *= 0x85EBCA6Bu; x ^= x >> 13; x *= 0xC2B2AE35u; x ^= x >> 16;
   return x;
 }
+// Threshold of element `index` under `seed`: one finaliser round over the low index word xor a key that
+// depends on the seed and on the high index word only (constant over 2^32 consecutive elements, so the
+// kernels compute it once per vector).
+__host__ __device__ __forceinline__ uint32_t sr_key(uint64_t seed, uint32_t index_hi) {
+  return fmix32((uint32_t)(seed >> 32) + index_hi * 0x9E3779B9u) ^ (uint32_t)seed;
+}
 __host__ __device__ __forceinline__ uint32_t sr_threshold(uint64_t seed, uint64_t index) {
-  uint32_t x = fmix32((uint32_t)index ^ (uint32_t)seed);
-  x += (uint32_t)(index >> 32) * 0x9E3779B9u + (uint32_t)(seed >> 32);
-  return fmix32(x);
+  return fmix32((uint32_t)index ^ sr_key(seed, (uint32_t)(index >> 32)));
 }
 
 // Rounded pattern of magnitude `a` (not NaN) under rounding method rm (any of the five), in
@@ -214,16 +217,70 @@ __device__ __forceinline__ uint32_t round_mag_any(uint32_t rm, uint32_t a, uint3
   return ((a >> d) + (carry ? 1u : 0u)) << d;
 }
 
-// Standard SR, streaming form: rounded pattern of magnitude `a` (not NaN), to be looked up in
-// the TA table (the result is on the HiF8 grid, where TA is the identity; exponent 104 stands
-// for "carried out of the underflow step" as in round_mag_any() and the TA table reads it as
-// 2^-22).  With d discarded bits the carry rule (t32 >> (32 - d)) < discarded is the carry out
-// of discarded + ((2^d - 1) - (t32 >> (32 - d))), i.e. adding the complemented top threshold
-// bits below the kept part and truncating.
-__device__ __forceinline__ uint32_t sr_round_bits(uint32_t a, uint32_t t32) {
-  if (a < kBitsTwoM22) return round_mag_any<kSrcF32>(kRmSR, a, a, t32);
-  const uint32_t d = 23u - kept_bits(a >> 23);  // 20..23
-  return (a + ((~t32) >> (32u - d))) & ~((1u << d) - 1u);
+// Standard SR, table-driven form for the streaming kernels.
+//
+// At or above 2^-22, with d discarded bits, the carry rule (t32 >> (32 - d)) < discarded is the carry out
+// of discarded + ((2^d - 1) - (t32 >> (32 - d))): add the top d bits of the complemented threshold below
+// the kept part and truncate,
+//     r = (y + bfe(~t32, 32 - d, d)) & mask,      mask = ~(2^d - 1),
+// on the whole pattern y (the sum stays below the sign bit: the magnitude is at most Inf's pattern, the
+// addend below 2^23).  The result is on the HiF8 grid, where the TA table is the identity.  Exponent 255
+// (Inf, and NaN, which the table turns into the code of the NaN option) takes a field of width 0: unchanged.
+// Below 2^-22 the rule is t32 < |y| / 2^-22 * 2^32 = |y| * 2^54, a product that binary32 holds exactly
+// (below 2^32; subnormal inputs included, denormals are not flushed), so with X = ceil of it as an integer
+// the value carries to 2^-22 (written as exponent 104, which the TA table reads as 2^-22) iff t32 < X, and
+// is zero otherwise (mask keeps the sign only).  The factor is 2^54 for those exponents and 0 for all others
+// (X = 0: never; Inf * 0 = NaN converts to 0 as well).
+struct SrExp {
+  uint32_t off, width;  // field of ~t32 that is added
+  uint32_t mask;
+  float fmul;
+};
+
+__device__ __forceinline__ SrExp sr_exp_entry(uint32_t e) {
+  SrExp h;
+  h.off = 0u; h.width = 0u; h.mask = 0xFFFFFFFFu; h.fmul = 0.0f;
+  if (e == 255u) return h;
+  if (e <= 104u) {
+    h.mask = 0x80000000u;
+    union { uint32_t u; float f; } v;
+    v.u = (127u + 54u) << 23;
+    h.fmul = v.f;
+    return h;
+  }
+  const uint32_t d = 23u - kept_bits(e);  // 20..23
+  h.off = 32u - d; h.width = d; h.mask = 0xFFFFFFFFu << d;
+  return h;
+}
+
+#ifdef HIF8_DEVICE_HOST_SHIM
+__device__ __forceinline__ uint32_t bfe_u32(uint32_t x, uint32_t off, uint32_t width) {
+  return width ? ((x >> off) & ((1u << width) - 1u)) : 0u;
+}
+__device__ __forceinline__ uint32_t ceil_to_u32(float p) {  // p >= 0 or NaN; NaN -> 0
+  if (!(p == p)) return 0u;
+  const double c = __builtin_ceil((double)p);
+  return c >= 4294967295.0 ? 0xFFFFFFFFu : (uint32_t)c;
+}
+#else
+__device__ __forceinline__ uint32_t bfe_u32(uint32_t x, uint32_t off, uint32_t width) {
+  return __builtin_amdgcn_ubfe(x, off, width);
+}
+__device__ __forceinline__ uint32_t ceil_to_u32(float p) {  // v_cvt_u32_f32: NaN -> 0, saturating
+  uint32_t r;
+  asm("v_cvt_u32_f32 %0, %1" : "=v"(r) : "v"(__builtin_ceilf(p)));
+  return r;
+}
+#endif
+
+// Rounded binary32 pattern (sign kept) of pattern ybits under standard SR with threshold t32;
+// p = table entry of ybits' exponent.  NaN patterns come back unchanged.
+__device__ __forceinline__ uint32_t sr_round_bits(uint32_t ybits, uint32_t t32, const SrExp& p) {
+  union { uint32_t u; float f; } mag;
+  mag.u = ybits & 0x7FFFFFFFu;
+  const uint32_t X = ceil_to_u32(mag.f * p.fmul);
+  const uint32_t small = t32 < X ? (104u << 23) : 0u;
+  return ((ybits + bfe_u32(~t32, p.off, p.width)) & p.mask) | small;
 }
 
 // Full encode of one binary32 pattern under any rounding method (element-wise paths).

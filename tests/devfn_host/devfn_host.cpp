@@ -45,12 +45,13 @@ void devfn_encode_bits_hr_table(const uint32_t* ybits, uint8_t* dst, size_t n, u
     dst[i] = (uint8_t)hif8dev::encode_alu<false, 0>(r & 0xFFF80000u, mode);
   }
 }
-// standard SR, streaming form: add-and-truncate, then the TA code of the (representable) result
+// standard SR, streaming form: per-exponent table entry, add-and-truncate, then the TA code of the
+// (representable) result
 void devfn_encode_bits_sr_table(const uint32_t* ybits, uint8_t* dst, size_t n, uint32_t mode, uint64_t seed) {
   for (size_t i = 0; i < n; ++i) {
     const uint32_t y = ybits[i];
     if ((y & 0x7FFFFFFFu) > 0x7F800000u) { dst[i] = (uint8_t)hif8dev::nan_code(mode); continue; }
-    const uint32_t r = hif8dev::sr_round_bits(y & 0x7FFFFFFFu, hif8dev::sr_threshold(seed, (uint64_t)i)) | (y & 0x80000000u);
+    const uint32_t r = hif8dev::sr_round_bits(y, hif8dev::sr_threshold(seed, (uint64_t)i), hif8dev::sr_exp_entry((y >> 23) & 0xFFu));
     dst[i] = (uint8_t)hif8dev::encode_alu<false, 0>(r & 0xFFF80000u, mode);
   }
 }

@@ -154,10 +154,9 @@ def np_fmix32(x):
 
 def np_threshold(seed, idx):
     idx = np.asarray(idx, np.uint64)
-    lo = (idx & np.uint64(0xFFFFFFFF)) ^ np.uint64(seed & 0xFFFFFFFF)
-    x = np_fmix32(lo)
-    x = (x + (idx >> np.uint64(32)) * np.uint64(0x9E3779B9) + np.uint64(seed >> 32)) & np.uint64(0xFFFFFFFF)
-    return np_fmix32(x).astype(np.uint32)
+    key = np_fmix32((np.uint64(seed >> 32) + (idx >> np.uint64(32)) * np.uint64(0x9E3779B9)) & np.uint64(0xFFFFFFFF)) \
+        ^ np.uint64(seed & 0xFFFFFFFF)
+    return np_fmix32((idx & np.uint64(0xFFFFFFFF)) ^ key).astype(np.uint32)
 
 
 def test_sr_threshold_generator():
