@@ -173,6 +173,32 @@ def test_sr_threshold_generator():
     assert not np.array_equal(np_threshold(7, np.arange(64, dtype=np.uint64)), np_threshold(8, np.arange(64, dtype=np.uint64)))
 
 
+def test_sr_threshold_generator_statistics():
+    """What standard SR needs of its thresholds (Sec. 3.2: a uniform random number per element): every bit
+    balanced, neighbours uncorrelated, streams of different seeds and of different 2^32-element blocks
+    uncorrelated.  Measured on the oracle's own generator (the C function), 2^18 draws per stream."""
+    n = 1 << 18
+    def stream(seed, base):
+        return np.array([orc.sr_threshold(seed, base + i) for i in range(n)], np.uint32)
+    def corr(a, b):
+        a = a.astype(np.float64) - a.mean(); b = b.astype(np.float64) - b.mean()
+        return float((a * b).sum() / np.sqrt((a * a).sum() * (b * b).sum()))
+    bound = 5.0 / np.sqrt(n)                                 # 5 sigma of a sample correlation / of a bit mean * 2
+    s7 = stream(7, 0)
+    for b in range(32):
+        assert abs(((s7 >> np.uint32(b)) & np.uint32(1)).mean() - 0.5) < bound / 2, b
+    for lag in (1, 2, 3, 4, 8, 64, 1024):
+        assert abs(corr(s7[:-lag], s7[lag:])) < bound, lag
+    assert abs(corr(s7, stream(8, 0))) < bound               # neighbouring seeds
+    assert abs(corr(s7, stream(7 + (1 << 32), 0))) < bound   # seeds that differ in the high word only
+    assert abs(corr(s7, stream(7, 1 << 32))) < bound         # the next 2^32-element block
+    assert abs(corr(s7, stream(7, 1 << 33))) < bound
+    # top bits (the ones that decide a carry) of neighbours: all 16 pairs of 2-bit values about equally often
+    top = (s7 >> np.uint32(30)).astype(np.int64)
+    pairs = np.bincount(top[:-1] * 4 + top[1:], minlength=16)
+    assert pairs.min() > 0.95 * (n - 1) / 16 and pairs.max() < 1.05 * (n - 1) / 16
+
+
 def test_sr_matches_bit_level_rule_and_is_unbiased():
     rng = np.random.default_rng(54)
     n = 1 << 20
