@@ -169,6 +169,7 @@ constexpr int kAxBlock = 256;
 constexpr int kAxUnroll = 4;  // axis 0: 16-byte vectors per lane per chunk
 constexpr int kAxWaves = kAxBlock / 64;
 constexpr int kAxRowsInFlight = 4;  // axis 1: rows loaded per lane before any is used
+constexpr int kAmaxColsWaves = 8;   // axis 1 amax: wavefronts per workgroup
 
 template <int SRCK>
 __global__ void __launch_bounds__(kAxBlock)
@@ -184,8 +185,8 @@ k_amax_rows(const void* __restrict__ src, uint32_t cols_vec, uint32_t chunks, ui
   block_max_to_global(fold_amax<SRCK>(m), out + row);
 }
 
-// columns: the four wavefronts of a workgroup share a strip of 64 column vectors and take every
-// fourth row of the workgroup's run of rows, four rows in flight per lane; their maxima are
+// columns: the wavefronts of a workgroup share a strip of 64 column vectors and take every
+// WAVES-th row of the workgroup's run of rows, four rows in flight per lane; their maxima are
 // combined in LDS so that only one atomic per column leaves the workgroup
 template <int SRCK>
 __device__ __forceinline__ uint4 colmax(const uint4& m, const uint4& v) {
@@ -202,12 +203,12 @@ __device__ __forceinline__ uint4 colmax(const uint4& m, const uint4& v) {
   return o;
 }
 
-template <int SRCK>
-__global__ void __launch_bounds__(kAxBlock)
+template <int SRCK, int WAVES>
+__global__ void __launch_bounds__(WAVES * 64)
 k_amax_cols(const void* __restrict__ src, uint32_t rows, uint32_t cols_vec, uint32_t strips,
             uint32_t rows_per_wg, uint32_t* __restrict__ out) {
   constexpr int VE = vec_elems<SRCK>();
-  __shared__ uint4 part[kAxWaves][64];
+  __shared__ uint4 part[WAVES][64];
   const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
   const uint32_t rchunk = blockIdx.x / strips, strip = blockIdx.x - rchunk * strips;
   const uint32_t cv = strip * 64u + lane;
@@ -217,11 +218,11 @@ k_amax_cols(const void* __restrict__ src, uint32_t rows, uint32_t cols_vec, uint
   const uint4* __restrict__ p = reinterpret_cast<const uint4*>(src) + cv;
   uint4 m = make_uint4(0u, 0u, 0u, 0u);  // FP32: four magnitudes; 16-bit: eight packed 15-bit magnitudes
   if (active) {
-    for (uint32_t r = r0 + wv; r < r1; r += kAxWaves * kAxRowsInFlight) {
+    for (uint32_t r = r0 + wv; r < r1; r += WAVES * kAxRowsInFlight) {
       uint4 v[kAxRowsInFlight];
 #pragma unroll
       for (int j = 0; j < kAxRowsInFlight; ++j) {
-        const uint32_t rr = r + j * kAxWaves;
+        const uint32_t rr = r + j * WAVES;
         v[j] = rr < r1 ? ld_stream(p + (size_t)rr * cols_vec) : make_uint4(0u, 0u, 0u, 0u);
       }
 #pragma unroll
@@ -232,7 +233,7 @@ k_amax_cols(const void* __restrict__ src, uint32_t rows, uint32_t cols_vec, uint
   __syncthreads();
   if (wv != 0 || !active) return;
 #pragma unroll
-  for (int w = 1; w < kAxWaves; ++w) m = colmax<SRCK>(m, part[w][lane]);  // masks are no-ops on magnitudes
+  for (int w = 1; w < WAVES; ++w) m = colmax<SRCK>(m, part[w][lane]);  // masks are no-ops on magnitudes
   uint32_t* o = out + (size_t)cv * VE;
   auto put = [&](int j, uint32_t bits) { if (bits) atomicMax(o + j, bits); };
   if constexpr (SRCK == kSrcF32) {
@@ -523,9 +524,10 @@ bool plan_axis(size_t rows, size_t cols, int cus, bool aligned, AxisPlan* p) {
   const uint32_t per_chunk = kAxBlock * kAxUnroll;
   p->chunks = (p->cols_vec + per_chunk - 1) / per_chunk;
   p->strips = (p->cols_vec + 63) / 64;
-  // axis 1: enough row chunks to give every CU several workgroups, at least 64 rows each (one
-  // atomic per column and workgroup in amax), in multiples of what the lanes keep in flight
-  uint32_t want = (uint32_t)((size_t)cus * 6 / (p->strips ? p->strips : 1));
+  // axis 1: enough row chunks to give every CU about three workgroups, at least 64 rows each (every
+  // lane loads the scales of its columns once per workgroup; measured on [11008, 4096] and [32000, 4096]
+  // BF16 and [8192, 8192] FP32: three per CU beat six by 5-12 %), in multiples of what the lanes keep in flight
+  uint32_t want = (uint32_t)((size_t)cus * 3 / (p->strips ? p->strips : 1));
   if (want < 1) want = 1;
   uint32_t rpw = (uint32_t)((rows + want - 1) / want);
   if (rpw < 64) rpw = 64;
@@ -557,16 +559,18 @@ hif8_status amax_axis(const void* src, size_t rows, size_t cols, int axis, float
   } else {
     // longer runs of rows than the casts use -- about one workgroup per CU -- because every
     // workgroup ends with one atomic per column (measured on [11008, 4096] BF16: 50 us with 64-row
-    // runs, 25 us with 384-row runs, 50 us again with 1024-row runs that leave most CUs idle)
-    const uint32_t unit = kAxWaves * kAxRowsInFlight;
+    // runs, 25 us with 384-row runs, 50 us again with 1024-row runs that leave most CUs idle), and
+    // eight wavefronts per workgroup so that a CU still has enough loads in flight (20 us; four
+    // wavefronts 24 us, sixteen no better)
+    const uint32_t unit = kAmaxColsWaves * kAxRowsInFlight;
     uint32_t want_chunks = (uint32_t)cus / (p.strips ? p.strips : 1u);
     if (want_chunks < 1u) want_chunks = 1u;
     uint32_t rpw = (uint32_t)((rows + want_chunks - 1) / want_chunks);
     rpw = (rpw + unit - 1) / unit * unit;
     if (rpw < 64u) rpw = 64u;
     const uint32_t row_chunks = (uint32_t)((rows + rpw - 1) / rpw);
-    hipLaunchKernelGGL(k_amax_cols<SRCK>, dim3(row_chunks * p.strips), dim3(kAxBlock), 0, st, src, (uint32_t)rows,
-                       p.cols_vec, p.strips, rpw, out);
+    hipLaunchKernelGGL((k_amax_cols<SRCK, kAmaxColsWaves>), dim3(row_chunks * p.strips), dim3(kAmaxColsWaves * 64), 0,
+                       st, src, (uint32_t)rows, p.cols_vec, p.strips, rpw, out);
   }
   return finish_launch();
 }
