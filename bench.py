@@ -252,6 +252,10 @@ def main():
         extra["amax_bf16 (2 B/elem)"] = rate(2 * m, e_ms)
         w_ms, e_ms = timed(lambda i: hif8.hif8_encode_bf16_ds(acts[i % R], cds[i % R], m, sc, hif8.RM_TA), K, W)
         extra["encode_bf16 (3 B/elem)"] = rate(3 * m, e_ms)
+        w_ms, e_ms = timed(lambda i: hif8.hif8_encode_bf16_ds(acts[i % R], cds[i % R], m, sc, hif8.RM_HR), K, W)
+        extra["encode_bf16 HR (3 B/elem)"] = rate(3 * m, e_ms)
+        w_ms, e_ms = timed(lambda i: hif8.hif8_encode_bf16_ds(acts[i % R], cds[i % R], m, sc, hif8.RM_SR), K, W)
+        extra["encode_bf16 SR (3 B/elem, comparison mode)"] = rate(3 * m, e_ms)
         h16 = [a.float().to(torch.float16) for a in acts[:2]]
         w_ms, e_ms = timed(lambda i: hif8.hif8_encode_f16(h16[i % 2], cds[i % R], m, 1.0, hif8.RM_TA), K, W)
         extra["encode_f16 (3 B/elem)"] = rate(3 * m, e_ms)

@@ -58,7 +58,7 @@ k_scale_sweep(const void* __restrict__ src, size_t n, int e_lo, int count_arg, u
   __shared__ HrLds<uses_exp_table<IMPL>()> hrt;
   __shared__ uint32_t dec[256];
   const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, seed);
-  stage_enc_lut<IMPL>(lut, g_lut, mode);
+  stage_enc_lut<IMPL, SRCK>(lut, g_lut, mode);
   stage_exp_table<IMPL, SRCK>(hrt.w, mode);
   stage_dec_lut(dec, g_dec);
   __syncthreads();
@@ -274,7 +274,7 @@ k_encode_rows(const void* __restrict__ src, uint8_t* __restrict__ dst, uint32_t 
     if (c < cols_vec) v[j] = ld_stream(p + c);
   }
   const float scale = d_scale2[2 * (size_t)row];
-  stage_enc_lut<IMPL>(lut, g_lut, mode);
+  stage_enc_lut<IMPL, SRCK>(lut, g_lut, mode);
   stage_exp_table<IMPL, SRCK>(hrt.w, mode);
   __syncthreads();
 #pragma unroll
@@ -298,7 +298,7 @@ k_encode_cols(const void* __restrict__ src, uint8_t* __restrict__ dst, uint32_t 
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
   __shared__ HrLds<uses_exp_table<IMPL>()> hrt;
   const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, seed);
-  stage_enc_lut<IMPL>(lut, g_lut, mode);
+  stage_enc_lut<IMPL, SRCK>(lut, g_lut, mode);
   stage_exp_table<IMPL, SRCK>(hrt.w, mode);
   __syncthreads();
   constexpr int VE = vec_elems<SRCK>();
@@ -466,8 +466,10 @@ void dispatch_impl_only(int impl, F&& f) {
     default: f(integral_constant<int, IMPL_TA_LUT>{}); break;
   }
 }
+// the sweep and the per-channel kernels stage their tables for little data per workgroup: they keep the
+// small per-exponent tables for HR whatever the source kind
 inline int impl_no_alu(uint32_t mode) {
-  const int i = impl_for(mode);
+  const int i = impl_for<kSrcF32>(mode);
   return i == IMPL_TA_ALU ? IMPL_TA_LUT : i;
 }
 

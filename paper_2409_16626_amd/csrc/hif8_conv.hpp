@@ -10,6 +10,8 @@
 //                  itself is produced on the device, once, by the integer encoder.
 //   encode, HR   : table-driven rounding to the grid (hr_round_bits), then the same byte lookup.
 //                  Simplified SR in every binade is the same kernel with another threshold clamp.
+//                  On 16-bit sources HR proper is a single lookup in a 16 KiB table indexed by the
+//                  source LSB and the top 13 bits of the scaled pattern (IMPL_HR16).
 //   encode, TE   : differs from TA only at exact ties, which need the low 19 bits to be zero;
 //                  a second 8 KiB table holds the TE code of those patterns.
 //   encode, SR   : standard SR (comparison mode): a hashed threshold per element is added below the
@@ -36,11 +38,11 @@ namespace hif8conv {
 using namespace hif8dev;
 using namespace hif8host;
 
-enum : int { IMPL_TA_LUT = 0, IMPL_TA_ALU = 1, IMPL_HR = 2, IMPL_TE = 3, IMPL_SR = 4 };
+enum : int { IMPL_TA_LUT = 0, IMPL_TA_ALU = 1, IMPL_HR = 2, IMPL_TE = 3, IMPL_SR = 4, IMPL_HR16 = 5 };
 
 template <int IMPL>
 constexpr uint32_t lut_bytes() {
-  return IMPL == IMPL_TE ? 16384u : IMPL == IMPL_TA_ALU ? 16u : 8192u;
+  return (IMPL == IMPL_TE || IMPL == IMPL_HR16) ? 16384u : IMPL == IMPL_TA_ALU ? 16u : 8192u;
 }
 template <int SRCK>
 constexpr int vec_elems() { return SRCK == kSrcF32 ? 4 : 8; }  // elements per 16-byte source vector
@@ -57,10 +59,14 @@ constexpr int vec_shift() { return SRCK == kSrcF32 ? 2 : 3; }
 //     exponents: 2.8 TB/s on the wide-range C2 tensor; one dword array per parameter -- conflict-free but five
 //     reads per element, and the LDS takes about four cycles per wavefront instruction: 5.3 TB/s; 16-byte
 //     entries: 6.1-6.2 TB/s.)
-//   16-bit sources: three 256-entry dword arrays add0[], add1[], mask[] -- twice as many elements per byte of
-//     tensor, and with 16-byte entries lanes whose exponents are 16 apart collide: 5.3 TB/s on a narrow
-//     tensor but 3.9 TB/s on a wide-range one; the arrays give 5.2-5.4 TB/s on both.
+//   16-bit sources: two 256-entry dword arrays add0[], add1[] -- twice as many elements per byte of
+//     tensor, and with 16-byte entries {add0, add1, mask} lanes whose exponents are 16 apart collide: 5.3 TB/s
+//     on a narrow tensor but 3.9 TB/s on a wide-range one; three arrays gave 5.2-5.4 TB/s on both.  The addend
+//     is read from the array the source LSB selects (one read, no select); add1[] starts 32 banks after add0[]
+//     so that lanes with the same exponent and different LSBs do not collide.  The mask is not applied at
+//     all: the sum is looked up in the truncating encode table (one LDS read per element fewer).
 //   standard SR: 256 entries of 16 bytes {offset, width, mask, factor} (sr_exp_entry()).
+constexpr uint32_t kHr16Add1 = 256u + 32u;  // dword offset of add1[] in HrLds::w (16-bit sources)
 template <int IMPL>
 constexpr bool uses_exp_table() { return IMPL == IMPL_HR || IMPL == IMPL_SR; }
 template <bool ON>
@@ -98,10 +104,19 @@ __device__ __forceinline__ EncCtx make_ctx(const uint8_t* lut, const uint32_t* h
   return c;
 }
 
-template <int IMPL>
+// Encode tables of one (NaN option, saturation) pair lie together: TA, TE's ties, truncating (8 KiB each).
+// HR on 16-bit sources looks its sums up in the truncating table, everything else in the TA table (TE in
+// the first two).
+template <int IMPL, int SRCK>
+constexpr bool uses_trunc_lut() { return IMPL == IMPL_HR && SRCK != kSrcF32; }
+template <int IMPL, int SRCK>
 __device__ __forceinline__ void stage_enc_lut(uint8_t* lut, const uint8_t* __restrict__ g_lut, uint32_t mode) {
   if (lut_bytes<IMPL>() < 8192u) return;
-  const uint4* g = reinterpret_cast<const uint4*>(g_lut + ((mode & kFlagNan2Zero) ? 32768u : 0u) + ((mode & kFlagSat) ? 16384u : 0u));
+  // IMPL_HR16 is handed the direct tables [NaN -> 0][sat][source LSB][pattern >> 19] instead
+  const uint32_t off = IMPL == IMPL_HR16 ? ((mode & kFlagNan2Zero) ? 32768u : 0u) + ((mode & kFlagSat) ? 16384u : 0u)
+                                         : ((mode & kFlagNan2Zero) ? 49152u : 0u) + ((mode & kFlagSat) ? 24576u : 0u) +
+                                               (uses_trunc_lut<IMPL, SRCK>() ? 16384u : 0u);
+  const uint4* g = reinterpret_cast<const uint4*>(g_lut + off);
   uint4* l = reinterpret_cast<uint4*>(lut);
   for (uint32_t i = threadIdx.x; i < lut_bytes<IMPL>() / 16u; i += blockDim.x) l[i] = g[i];
 }
@@ -118,7 +133,7 @@ __device__ __forceinline__ void stage_exp_table(uint32_t* w, uint32_t mode) {
       reinterpret_cast<uint4*>(w)[i] = make_uint4(h.C, (uint32_t)h.negmult, h.mask, h.lo | (h.hi << 16));
     } else {
       const HrExp16 h = hr16_exp_entry(i, ssr);
-      w[i] = h.add0; w[256 + i] = h.add1; w[512 + i] = h.mask;
+      w[i] = h.add0; w[kHr16Add1 + i] = h.add1;  // the mask is folded into the truncating encode table
     }
   }
 }
@@ -142,6 +157,12 @@ __device__ __forceinline__ uint32_t encode_one(uint32_t ybits, const EncCtx& c, 
       SrExp p;
       p.off = q.x; p.width = q.y; p.mask = q.z; p.fmul = __uint_as_float(q.w);
       code = c.lut[sr_round_bits(ybits, fmix32((uint32_t)elem ^ c.sr_key), p) >> 19];
+    } else if constexpr (IMPL == IMPL_HR16) {
+      // HR proper on a 16-bit source: kept mantissa, the two fraction bits (bit 19 upwards: where three bits
+      // are kept Eq. (3) asks for TA, which looks at bit 19 only) and the source LSB decide, so the code comes
+      // straight from a table indexed by the LSB and the top 13 bits
+      static_assert(SRCK != kSrcF32, "16-bit sources only");
+      code = c.lut[(ybits >> 19) | (hr16_lsb<SRCK>(ybits) << 13)];
     } else if constexpr (IMPL == IMPL_TE) {
       // a tie needs every bit below the rounding bit to be zero; otherwise TE rounds as TA
       code = c.lut[(ybits >> 19) + ((ybits & 0x7FFFFu) ? 0u : 8192u)];
@@ -155,9 +176,7 @@ __device__ __forceinline__ uint32_t encode_one(uint32_t ybits, const EncCtx& c, 
         r = hr_round_bits<SRCK>(ybits, p);
       } else {
         const uint32_t* t = c.hrt + ((ybits >> 23) & 0xFFu);
-        HrExp16 p;
-        p.add0 = t[0]; p.add1 = t[256]; p.mask = t[512];
-        r = hr16_round_bits<SRCK>(ybits, p);
+        r = hr16_round_sum(ybits, t[hr16_lsb<SRCK>(ybits) * kHr16Add1]);  // no mask: truncating table
       }
       code = c.lut[r >> 19];
     }
@@ -312,7 +331,7 @@ k_encode(const void* __restrict__ src, uint8_t* __restrict__ dst, size_t n, floa
       },
       [&]() {
         if (IMPL != IMPL_TA_ALU) {
-          stage_enc_lut<IMPL>(lut, g_lut, mode);
+          stage_enc_lut<IMPL, SRCK>(lut, g_lut, mode);
           stage_exp_table<IMPL, SRCK>(hrt.w, mode);
           __syncthreads();
         }
@@ -372,7 +391,7 @@ k_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, float scale_a
   const float scale = d_scale2 ? d_scale2[0] : scale_arg;
   const float inv = d_scale2 ? d_scale2[1] : inv_arg;
   auto prologue = [&]() {
-    stage_enc_lut<IMPL>(lut, g_lut, mode);
+    stage_enc_lut<IMPL, SRCK>(lut, g_lut, mode);
     stage_exp_table<IMPL, SRCK>(hrt.w, mode);
     stage_dec_lut(dec, g_dec);
     __syncthreads();
@@ -568,7 +587,7 @@ k_multi_encode(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
   __shared__ HrLds<uses_exp_table<IMPL>()> hrt;
   const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, seed);
-  stage_enc_lut<IMPL>(lut, g_lut, mode);
+  stage_enc_lut<IMPL, SRCK>(lut, g_lut, mode);
   stage_exp_table<IMPL, SRCK>(hrt.w, mode);
   __syncthreads();
   constexpr int VE = vec_elems<SRCK>();
@@ -610,9 +629,14 @@ k_multi_encode(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_
 // ====================================================================================
 // host side
 // ====================================================================================
+// global table a kernel of implementation IMPL stages from
+template <int IMPL>
+inline const uint8_t* enc_table_for(const DevTables& tb) { return IMPL == IMPL_HR16 ? tb.hr16_lut : tb.enc_lut; }
+
+template <int SRCK>
 inline int impl_for(uint32_t mode) {
   switch (mode & HIF8_RM_MASK) {
-    case HIF8_RM_HR:
+    case HIF8_RM_HR: return SRCK != kSrcF32 ? IMPL_HR16 : IMPL_HR;
     case HIF8_RM_SSR: return IMPL_HR;
     case HIF8_RM_TE: return IMPL_TE;
     case HIF8_RM_SR: return IMPL_SR;
@@ -622,10 +646,13 @@ inline int impl_for(uint32_t mode) {
 
 // Calls f(integral_constant IMPL, integral_constant U).  The comparison modes TE and SR are
 // built for one unroll factor only.
-template <typename F>
+template <int SRCK, typename F>
 inline void dispatch_impl(int impl, int unroll, F&& f) {
   using std::integral_constant;
   switch (impl) {
+    case IMPL_HR16:
+      if constexpr (SRCK != kSrcF32) dispatch_unroll(unroll, [&](auto u) { f(integral_constant<int, IMPL_HR16>{}, u); });
+      break;
     case IMPL_TA_ALU: dispatch_unroll(unroll, [&](auto u) { f(integral_constant<int, IMPL_TA_ALU>{}, u); }); break;
     case IMPL_HR: dispatch_unroll(unroll, [&](auto u) { f(integral_constant<int, IMPL_HR>{}, u); }); break;
     case IMPL_TE: f(integral_constant<int, IMPL_TE>{}, integral_constant<int, 2>{}); break;
@@ -655,14 +682,14 @@ hif8_status conv_encode(const void* src, uint8_t* dst, size_t n, float scale, co
     return finish_launch();
   }
   const size_t nvec = n >> vec_shift<SRCK>();
-  const int impl = impl_for(mode);
+  const int impl = impl_for<SRCK>(mode);
   Shape shape = shape_for(SRCK != kSrcF32 ? FAM_ENC16 : (impl == IMPL_HR ? FAM_ENC32_HR : FAM_ENC32_TA));
   if (impl == IMPL_TE || impl == IMPL_SR) shape.unroll = 2;
   Walk walk;
   const dim3 grid(grid_for(nvec, cus, shape, &walk)), block(shape.block);
-  dispatch_impl(impl, shape.unroll, [&](auto impl_c, auto u_c) {
+  dispatch_impl<SRCK>(impl, shape.unroll, [&](auto impl_c, auto u_c) {
     hipLaunchKernelGGL((k_encode<decltype(u_c)::value, decltype(impl_c)::value, SRCK>), grid, block, 0, st, src,
-                       dst, n, scale, d_scale2, amax_acc, mode, seed, tb.enc_lut, walk);
+                       dst, n, scale, d_scale2, amax_acc, mode, seed, enc_table_for<decltype(impl_c)::value>(tb), walk);
   });
   return finish_launch();
 }
@@ -717,19 +744,19 @@ hif8_status conv_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n
     return finish_launch();
   }
   const size_t nvec = n >> vec_shift<SRCK>();
-  const int impl = impl_for(mode);
+  const int impl = impl_for<SRCK>(mode);
   Shape shape = shape_for(FAM_FQ);
   if (impl == IMPL_TE || impl == IMPL_SR) shape.unroll = 2;
   Walk walk;
   const dim3 grid(grid_for(nvec, cus, shape, &walk)), block(shape.block);
-  dispatch_impl(impl, shape.unroll, [&](auto impl_c, auto u_c) {
+  dispatch_impl<SRCK>(impl, shape.unroll, [&](auto impl_c, auto u_c) {
     constexpr int U = decltype(u_c)::value, IMPL = decltype(impl_c)::value;
     if (codes)
       hipLaunchKernelGGL((k_fake_quant<U, IMPL, true, SRCK>), grid, block, 0, st, src, dst, codes, n, scale, inv,
-                         d_scale2, amax_acc, mode, seed, tb.enc_lut, tb.dec_lut, walk);
+                         d_scale2, amax_acc, mode, seed, enc_table_for<IMPL>(tb), tb.dec_lut, walk);
     else
       hipLaunchKernelGGL((k_fake_quant<U, IMPL, false, SRCK>), grid, block, 0, st, src, dst, codes, n, scale, inv,
-                         d_scale2, amax_acc, mode, seed, tb.enc_lut, tb.dec_lut, walk);
+                         d_scale2, amax_acc, mode, seed, enc_table_for<IMPL>(tb), tb.dec_lut, walk);
   });
   return finish_launch();
 }
@@ -790,7 +817,11 @@ hif8_status conv_multi_cast(const hif8_cast_item* d_items, size_t count, uint64_
   if (s != HIF8_OK) return s;
   if (total_tiles != 0) {
     const dim3 g2((unsigned)((total_tiles + kMultiTpwEncode - 1) / kMultiTpwEncode)), blk(kMultiBlock);
-    switch (impl_for(mode)) {
+    switch (impl_for<SRCK>(mode)) {
+      case IMPL_HR16:
+        if constexpr (SRCK != kSrcF32)
+          hipLaunchKernelGGL((k_multi_encode<IMPL_HR16, SRCK>), g2, blk, 0, st, d_items, cnt, total_tiles, d_scale2, mode, seed, tb.hr16_lut);
+        break;
       case IMPL_HR:
         hipLaunchKernelGGL((k_multi_encode<IMPL_HR, SRCK>), g2, blk, 0, st, d_items, cnt, total_tiles, d_scale2, mode, seed, tb.enc_lut);
         break;

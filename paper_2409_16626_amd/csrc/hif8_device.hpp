@@ -365,10 +365,11 @@ __device__ __forceinline__ int32_t mul_i24(int32_t a, int32_t b) { return __mul2
 template <int SRCK>
 __device__ __forceinline__ uint32_t hr_round_bits(uint32_t ybits, const HrExp& p) {
   static_assert(SRCK == kSrcF32, "binary32 sources; 16-bit sources use hr16_round_bits");
-  const uint32_t a = ybits & 0x7FFFFFFFu;
+  // on the whole pattern: the addend C - T' * mult never takes the magnitude below zero or up to the sign
+  // bit (it is at least -2^24 where the magnitude is at least 96 * 2^23, below 2^24 elsewhere, and zero
+  // from exponent 143 up), and every mask keeps the sign bit
   const uint32_t T = med3_u32(ybits & 0x3FFFu, p.lo, p.hi);
-  const uint32_t r = (a + p.C + (uint32_t)mul_i24((int32_t)T, p.negmult)) & p.mask;
-  return r | (ybits & 0x80000000u);
+  return (ybits + p.C + (uint32_t)mul_i24((int32_t)T, p.negmult)) & p.mask;
 }
 
 // ------------------------------------------------------------------------------------
@@ -402,15 +403,39 @@ __device__ __forceinline__ HrExp16 hr16_exp_entry(uint32_t e, bool ssr = false) 
   return h;
 }
 
-// Rounded binary32 pattern (sign kept) of non-NaN pattern ybits, the scaled value of a 16-bit source
-// element; p = table entry of ybits' exponent.  The source LSB is bit 16 (BF16) or bit 13 (FP16) of ybits.
+// The source LSB that selects the addend is bit 16 (BF16) or bit 13 (FP16) of the pattern.
 template <int SRCK>
-__device__ __forceinline__ uint32_t hr16_round_bits(uint32_t ybits, const HrExp16& p) {
+__device__ __forceinline__ uint32_t hr16_lsb(uint32_t ybits) {
   static_assert(SRCK != kSrcF32, "16-bit sources only");
-  const uint32_t a = ybits & 0x7FFFFFFFu;
-  const uint32_t m = 0u - ((ybits >> (SRCK == kSrcBF16 ? 16 : 13)) & 1u);  // all ones iff the source LSB is set
-  const uint32_t add = (m & p.add1) | (~m & p.add0);
-  return ((a + add) & p.mask) | (ybits & 0x80000000u);
+  return (ybits >> (SRCK == kSrcBF16 ? 16 : 13)) & 1u;
+}
+// Rounded binary32 pattern (sign kept) of pattern ybits, the scaled value of a 16-bit source element;
+// add = addend of ybits' exponent and source LSB, mask = mask of its exponent.  The add works on the whole
+// pattern: the magnitude plus the addend stays within [0, 2^31) (the one negative addend, -2^22, belongs to
+// exponent 104), the masks keep the sign bit, and Inf / NaN patterns get a zero addend.
+__device__ __forceinline__ uint32_t hr16_round_bits(uint32_t ybits, uint32_t add, uint32_t mask) {
+  return (ybits + add) & mask;
+}
+
+// The same without the per-exponent mask, for a lookup in the truncating table (trunc_table_pattern()),
+// which clears the bits below the kept mantissa of the exponent it sees.  That is the exponent of the sum:
+// the right one unless the add carried into the next binade, where the result is the start of that binade
+// exactly but the sum still holds what is left of the discarded field (and the next binade may keep one
+// bit more).  Clamping the sum to the start of the next binade removes it; the saturating add keeps
+// negative Inf / NaN patterns (exponent 255, zero addend) from wrapping to zero.
+#ifdef HIF8_DEVICE_HOST_SHIM
+__device__ __forceinline__ uint32_t uadd_sat1(uint32_t x) { return x == 0xFFFFFFFFu ? x : x + 1u; }
+#else
+__device__ __forceinline__ uint32_t uadd_sat1(uint32_t x) { return __builtin_elementwise_add_sat(x, 1u); }
+#endif
+__device__ __forceinline__ uint32_t hr16_round_sum(uint32_t ybits, uint32_t add) {
+  const uint32_t sum = ybits + add;
+  const uint32_t next = uadd_sat1(ybits | 0x007FFFFFu);
+  return sum < next ? sum : next;
+}
+// Pattern whose TA code entry i (= pattern >> 19) of the truncating table holds.
+__device__ __forceinline__ uint32_t trunc_table_pattern(uint32_t i) {
+  return (i << 19) & hr16_exp_entry((i >> 4) & 0xFFu).mask;
 }
 
 // Per-tensor scale from an amax (Sec. 5): fl32(target / amax), with pow2 the largest power of two not

@@ -19,6 +19,7 @@ struct DevTables {
   // [NaN -> 0 option 0/1][sat 0/1][kind 0/1][8192] bytes.  kind 0: TA code of pattern (i << 19); kind 1: TE
   // code of the same pattern (used only when the low 19 bits of the converted pattern are all zero).
   const uint8_t* enc_lut;
+  const uint8_t* hr16_lut;
   const uint32_t* dec_lut;  // [256] code -> binary32 pattern
 };
 

@@ -40,9 +40,22 @@ void devfn_encode_bits_hr_table(const uint32_t* ybits, uint8_t* dst, size_t n, u
       r = hif8dev::hr_round_bits<0>(y, hif8dev::hr_exp_entry((y >> 23) & 0xFFu, ssr));
     } else {  // 16-bit sources: add-and-mask form
       const hif8dev::HrExp16 p = hif8dev::hr16_exp_entry((y >> 23) & 0xFFu, ssr);
-      r = srck == 1 ? hif8dev::hr16_round_bits<1>(y, p) : hif8dev::hr16_round_bits<2>(y, p);
+      const uint32_t lsb = srck == 1 ? hif8dev::hr16_lsb<1>(y) : hif8dev::hr16_lsb<2>(y);
+      r = hif8dev::hr16_round_bits(y, lsb ? p.add1 : p.add0, p.mask);
     }
     dst[i] = (uint8_t)hif8dev::encode_alu<false, 0>(r & 0xFFF80000u, mode);
+  }
+}
+// 16-bit sources, streaming form: clamped sum, then the truncating table's entry (the TA code of
+// trunc_table_pattern())
+void devfn_encode_bits_hr16_stream(const uint32_t* ybits, uint8_t* dst, size_t n, uint32_t mode, int srck) {
+  const bool ssr = (mode & 0xF) == hif8dev::kRmSSR;
+  for (size_t i = 0; i < n; ++i) {
+    const uint32_t y = ybits[i];
+    const hif8dev::HrExp16 p = hif8dev::hr16_exp_entry((y >> 23) & 0xFFu, ssr);
+    const uint32_t lsb = srck == 1 ? hif8dev::hr16_lsb<1>(y) : hif8dev::hr16_lsb<2>(y);
+    const uint32_t r = hif8dev::hr16_round_sum(y, lsb ? p.add1 : p.add0);
+    dst[i] = (uint8_t)hif8dev::encode_alu<false, 0>(hif8dev::trunc_table_pattern(r >> 19), mode);
   }
 }
 // standard SR, streaming form: per-exponent table entry, add-and-truncate, then the TA code of the

@@ -43,6 +43,13 @@ def _enc(lib, ybits, mode, srck, seed=0):
                                        ctypes.c_size_t(ybits.size), ctypes.c_uint32(mode), ctypes.c_int(srck))
         bad = np.nonzero(out != out2)[0]
         assert bad.size == 0, [(hex(ybits[i]), hex(out[i]), hex(out2[i])) for i in bad[:8]]
+        if srck != 0:
+            # 16-bit sources: the clamped sum looked up in the truncating table
+            out3 = np.empty(ybits.shape, np.uint8)
+            lib.devfn_encode_bits_hr16_stream(ybits.ctypes.data_as(ctypes.c_void_p), out3.ctypes.data_as(ctypes.c_void_p),
+                                              ctypes.c_size_t(ybits.size), ctypes.c_uint32(mode), ctypes.c_int(srck))
+            bad = np.nonzero(out != out3)[0]
+            assert bad.size == 0, [(hex(ybits[i]), hex(out[i]), hex(out3[i])) for i in bad[:8]]
     if (mode & 0xF) == orc.RM_SR:
         # the streaming kernels' add-and-truncate form of standard SR must agree as well
         out2 = np.empty(ybits.shape, np.uint8)
