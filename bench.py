@@ -67,6 +67,9 @@ def main():
     ap.add_argument("--pmc", action="store_true",
                     help="counter-collection mode for rocprofv3 --pmc: 5 plain 16-byte copies of a known "
                          "size, then 5 headline encode launches; no timing, no JSON")
+    ap.add_argument("--pmc-modes", action="store_true",
+                    help="counter-collection mode for rocprofv3 --pmc: 5 encode launches per rounding method, on the "
+                         "C2 tensor (binary32) and on the C3 tensor (BF16); no timing, no JSON")
     ap.add_argument("--gemm-only", action="store_true",
                     help="profiling mode: only the simulated HiF8 GEMM rows (25 launches of 8192^3), no headline")
     ap.add_argument("--sweep-only", action="store_true",
@@ -139,6 +142,22 @@ def main():
             step(i)
         torch.cuda.synchronize()
         log("pmc mode: 5 x k_diag_stream<.,16> (%d B read, %d B written each), 5 x k_encode_f32" % (4 * n, 4 * n))
+        return
+
+    if args.pmc_modes:
+        from paper_2409_16626_amd import workloads as wl
+        act = wl.activation_bf16(8192, 8192, dev).view(-1)
+        m = act.numel()
+        cd = torch.empty(m, dtype=torch.uint8, device=dev)
+        for name in ("TA", "HR", "TE", "SSR", "SR"):
+            mode = getattr(hif8, "RM_" + name)
+            for i in range(5):
+                hif8.hif8_encode_f32(xs[i % R], outs[i % R], n, 1.0, mode)
+            for i in range(5):
+                hif8.hif8_encode_bf16(act, cd, m, 91.0, mode)
+        torch.cuda.synchronize()
+        log("pmc-modes: 5 x hif8_encode_f32 (%d elements) and 5 x hif8_encode_bf16 (%d elements) per rounding method "
+            "TA, HR, TE, SSR, SR" % (n, m))
         return
 
     wall_ms, ev_ms = timed(step, args.steps, args.warmup)
