@@ -52,15 +52,15 @@ __device__ __forceinline__ void block_add_f64(const double (&acc)[KMAX], int cou
 template <int IMPL, int SRCK, int NSC>
 __global__ void __launch_bounds__(kSweepBlock)
 k_scale_sweep(const void* __restrict__ src, size_t n, int e_lo, int count_arg, uint32_t mode, uint64_t seed,
-              const uint8_t* __restrict__ g_lut, const uint32_t* __restrict__ g_dec,
-              double* __restrict__ err) {
-  __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
+              const uint16_t* __restrict__ g_val, double* __restrict__ err) {
+  // the sweep needs values, not codes: its table holds the upper half of the binary32 pattern of every
+  // encode-table entry's value (at most four significant bits, Inf and the quiet NaN included), so that a
+  // cast costs one LDS read instead of two
+  __shared__ __attribute__((aligned(16))) uint16_t val[lut_bytes<IMPL>()];
   __shared__ HrLds<uses_exp_table<IMPL>()> hrt;
-  __shared__ uint32_t dec[256];
-  const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, seed);
-  stage_enc_lut<IMPL, SRCK>(lut, g_lut, mode);
+  const EncCtx ctx = make_ctx<IMPL>(nullptr, hrt.w, mode, seed);
+  stage_enc_lut<IMPL, SRCK, uint16_t>(val, g_val, mode);
   stage_exp_table<IMPL, SRCK>(hrt.w, mode);
-  stage_dec_lut(dec, g_dec);
   __syncthreads();
 
   constexpr int VE = vec_elems<SRCK>();
@@ -85,9 +85,9 @@ k_scale_sweep(const void* __restrict__ src, size_t n, int e_lo, int count_arg, u
     if constexpr (NSC != 0) {
       uint32_t c[KMAX], q[KMAX];
 #pragma unroll
-      for (int k = 0; k < KMAX; ++k) c[k] = encode_one<IMPL, SRCK>(scaled_bits(xb, sc[k]), kc, elem);
+      for (int k = 0; k < KMAX; ++k) c[k] = val[table_index<IMPL, SRCK>(scaled_bits(xb, sc[k]), kc, elem)];
 #pragma unroll
-      for (int k = 0; k < KMAX; ++k) q[k] = descale_bits(c[k], dec, isc[k]);
+      for (int k = 0; k < KMAX; ++k) q[k] = scaled_bits(c[k] << 16, isc[k]);
 #pragma unroll
       for (int k = 0; k < KMAX; ++k) {
         const double d = xd - (double)__uint_as_float(q[k]);
@@ -97,8 +97,8 @@ k_scale_sweep(const void* __restrict__ src, size_t n, int e_lo, int count_arg, u
 #pragma unroll
       for (int k = 0; k < KMAX; ++k) {
         if (k < count) {  // uniform across the grid
-          const uint32_t c = encode_one<IMPL, SRCK>(scaled_bits(xb, sc[k]), kc, elem);
-          const double d = xd - (double)__uint_as_float(descale_bits(c, dec, isc[k]));
+          const uint32_t c = val[table_index<IMPL, SRCK>(scaled_bits(xb, sc[k]), kc, elem)];
+          const double d = xd - (double)__uint_as_float(scaled_bits(c << 16, isc[k]));
           acc[k] = fma(d, d, acc[k]);
         }
       }
@@ -503,10 +503,10 @@ hif8_status scale_sweep(const void* src, size_t n, int e_lo, int count, uint32_t
     // the paper's search range (10 scales) gets straight-line code; other counts a run-time bound
     if (count == 10)
       hipLaunchKernelGGL((k_scale_sweep<IMPL, SRCK, 10>), dim3((unsigned)wgs), dim3(kSweepBlock), 0, st, src, n,
-                         e_lo, count, mode, seed, tb.enc_lut, tb.dec_lut, d_err);
+                         e_lo, count, mode, seed, tb.val_lut, d_err);
     else
       hipLaunchKernelGGL((k_scale_sweep<IMPL, SRCK, 0>), dim3((unsigned)wgs), dim3(kSweepBlock), 0, st, src, n,
-                         e_lo, count, mode, seed, tb.enc_lut, tb.dec_lut, d_err);
+                         e_lo, count, mode, seed, tb.val_lut, d_err);
   });
   return rc != HIF8_OK ? rc : finish_launch();
 }

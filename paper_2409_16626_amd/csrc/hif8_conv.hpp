@@ -109,8 +109,10 @@ __device__ __forceinline__ EncCtx make_ctx(const uint8_t* lut, const uint32_t* h
 // the first two).
 template <int IMPL, int SRCK>
 constexpr bool uses_trunc_lut() { return IMPL == IMPL_HR && SRCK != kSrcF32; }
-template <int IMPL, int SRCK>
-__device__ __forceinline__ void stage_enc_lut(uint8_t* lut, const uint8_t* __restrict__ g_lut, uint32_t mode) {
+// T = uint8_t: the code tables; T = uint16_t: the value tables of the same layout (upper half of the
+// binary32 pattern of each entry's value).
+template <int IMPL, int SRCK, typename T = uint8_t>
+__device__ __forceinline__ void stage_enc_lut(T* lut, const T* __restrict__ g_lut, uint32_t mode) {
   if (lut_bytes<IMPL>() < 8192u) return;
   // IMPL_HR16 is handed the direct tables [NaN -> 0][sat][source LSB][pattern >> 19] instead
   const uint32_t off = IMPL == IMPL_HR16 ? ((mode & kFlagNan2Zero) ? 32768u : 0u) + ((mode & kFlagSat) ? 16384u : 0u)
@@ -118,7 +120,7 @@ __device__ __forceinline__ void stage_enc_lut(uint8_t* lut, const uint8_t* __res
                                                (uses_trunc_lut<IMPL, SRCK>() ? 16384u : 0u);
   const uint4* g = reinterpret_cast<const uint4*>(g_lut + off);
   uint4* l = reinterpret_cast<uint4*>(lut);
-  for (uint32_t i = threadIdx.x; i < lut_bytes<IMPL>() / 16u; i += blockDim.x) l[i] = g[i];
+  for (uint32_t i = threadIdx.x; i < lut_bytes<IMPL>() * (uint32_t)sizeof(T) / 16u; i += blockDim.x) l[i] = g[i];
 }
 template <int IMPL, int SRCK>
 __device__ __forceinline__ void stage_exp_table(uint32_t* w, uint32_t mode) {
@@ -141,50 +143,53 @@ __device__ __forceinline__ void stage_dec_lut(uint32_t* lut, const uint32_t* __r
   for (uint32_t i = threadIdx.x; i < 256u; i += blockDim.x) lut[i] = g_dec[i];
 }
 
-// One element: scaled pattern -> code.  `elem` is the element's index in the tensor (it
-// selects the threshold of standard SR and is unused otherwise); c must be keyed() for elem's block.
+// One element: scaled pattern -> index into the staged encode table (every implementation but the ALU one
+// ends in one table lookup).  `elem` is the element's index in the tensor (it selects the threshold of
+// standard SR and is unused otherwise); c must be keyed() for elem's block.
+// NaN: ybits is always the result of the scale multiply, which returns a quiet NaN (bit 22 set) for any NaN
+// input, so the pattern indexes a NaN entry of the table (which holds the code of the NaN option in
+// effect); the HR and SR forms pass NaN patterns through unchanged.
+template <int IMPL, int SRCK>
+__device__ __forceinline__ uint32_t table_index(uint32_t ybits, const EncCtx& c, uint64_t elem) {
+  static_assert(IMPL != IMPL_TA_ALU, "the ALU form has no table");
+  if constexpr (IMPL == IMPL_TA_LUT) {
+    return ybits >> 19;
+  } else if constexpr (IMPL == IMPL_SR) {
+    // standard SR: add the hashed threshold bits below the kept part, truncate
+    const uint4 q = reinterpret_cast<const uint4*>(c.hrt)[(ybits >> 23) & 0xFFu];
+    SrExp p;
+    p.off = q.x; p.width = q.y; p.mask = q.z; p.fmul = __uint_as_float(q.w);
+    return sr_round_bits(ybits, fmix32((uint32_t)elem ^ c.sr_key), p) >> 19;
+  } else if constexpr (IMPL == IMPL_HR16) {
+    // HR proper on a 16-bit source: kept mantissa, the two fraction bits (bit 19 upwards: where three bits
+    // are kept Eq. (3) asks for TA, which looks at bit 19 only) and the source LSB decide, so the code comes
+    // straight from a table indexed by the LSB and the top 13 bits
+    static_assert(SRCK != kSrcF32, "16-bit sources only");
+    return (ybits >> 19) | (hr16_lsb<SRCK>(ybits) << 13);
+  } else if constexpr (IMPL == IMPL_TE) {
+    // a tie needs every bit below the rounding bit to be zero; otherwise TE rounds as TA
+    return (ybits >> 19) + ((ybits & 0x7FFFFu) ? 0u : 8192u);
+  } else {
+    // HR / SSR: rounding to the grid, then the entry of the (now representable) pattern
+    uint32_t r;
+    if constexpr (SRCK == kSrcF32) {
+      const uint4 q = reinterpret_cast<const uint4*>(c.hrt)[(ybits >> 23) & 0xFFu];
+      HrExp p;
+      p.C = q.x; p.negmult = (int32_t)q.y; p.mask = q.z; p.lo = q.w & 0xFFFFu; p.hi = q.w >> 16;
+      r = hr_round_bits<SRCK>(ybits, p);
+    } else {
+      const uint32_t* t = c.hrt + ((ybits >> 23) & 0xFFu);
+      r = hr16_round_sum(ybits, t[hr16_lsb<SRCK>(ybits) * kHr16Add1]);  // no mask: truncating table
+    }
+    return r >> 19;
+  }
+}
+
+// One element: scaled pattern -> code.
 template <int IMPL, int SRCK>
 __device__ __forceinline__ uint32_t encode_one(uint32_t ybits, const EncCtx& c, uint64_t elem) {
-  if constexpr (IMPL == IMPL_TA_ALU) {
-    return encode_alu<false, SRCK>(ybits, c.mode);
-  } else {
-    uint32_t code;
-    if constexpr (IMPL == IMPL_TA_LUT) {
-      code = c.lut[ybits >> 19];
-    } else if constexpr (IMPL == IMPL_SR) {
-      // standard SR: add the hashed threshold bits below the kept part, truncate, then the byte
-      const uint4 q = reinterpret_cast<const uint4*>(c.hrt)[(ybits >> 23) & 0xFFu];
-      SrExp p;
-      p.off = q.x; p.width = q.y; p.mask = q.z; p.fmul = __uint_as_float(q.w);
-      code = c.lut[sr_round_bits(ybits, fmix32((uint32_t)elem ^ c.sr_key), p) >> 19];
-    } else if constexpr (IMPL == IMPL_HR16) {
-      // HR proper on a 16-bit source: kept mantissa, the two fraction bits (bit 19 upwards: where three bits
-      // are kept Eq. (3) asks for TA, which looks at bit 19 only) and the source LSB decide, so the code comes
-      // straight from a table indexed by the LSB and the top 13 bits
-      static_assert(SRCK != kSrcF32, "16-bit sources only");
-      code = c.lut[(ybits >> 19) | (hr16_lsb<SRCK>(ybits) << 13)];
-    } else if constexpr (IMPL == IMPL_TE) {
-      // a tie needs every bit below the rounding bit to be zero; otherwise TE rounds as TA
-      code = c.lut[(ybits >> 19) + ((ybits & 0x7FFFFu) ? 0u : 8192u)];
-    } else {
-      // HR / SSR: rounding to the grid, then the byte of the (now representable) pattern
-      uint32_t r;
-      if constexpr (SRCK == kSrcF32) {
-        const uint4 q = reinterpret_cast<const uint4*>(c.hrt)[(ybits >> 23) & 0xFFu];
-        HrExp p;
-        p.C = q.x; p.negmult = (int32_t)q.y; p.mask = q.z; p.lo = q.w & 0xFFFFu; p.hi = q.w >> 16;
-        r = hr_round_bits<SRCK>(ybits, p);
-      } else {
-        const uint32_t* t = c.hrt + ((ybits >> 23) & 0xFFu);
-        r = hr16_round_sum(ybits, t[hr16_lsb<SRCK>(ybits) * kHr16Add1]);  // no mask: truncating table
-      }
-      code = c.lut[r >> 19];
-    }
-    // NaN: ybits is always the result of the scale multiply, which returns a quiet NaN (bit 22 set) for
-    // any NaN input, so the pattern indexes a NaN entry of the table (which holds the code of the NaN
-    // option in effect); the HR and SR forms pass NaN patterns through unchanged.
-    return code;
-  }
+  if constexpr (IMPL == IMPL_TA_ALU) return encode_alu<false, SRCK>(ybits, c.mode);
+  else return c.lut[table_index<IMPL, SRCK>(ybits, c, elem)];
 }
 
 __device__ __forceinline__ uint32_t scaled_bits(uint32_t xbits, float scale) {

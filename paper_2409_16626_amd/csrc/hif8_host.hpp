@@ -20,6 +20,7 @@ struct DevTables {
   // code of the same pattern (used only when the low 19 bits of the converted pattern are all zero).
   const uint8_t* enc_lut;
   const uint8_t* hr16_lut;
+  const uint16_t* val_lut;  // layout of enc_lut, values instead of codes
   const uint32_t* dec_lut;  // [256] code -> binary32 pattern
 };
 

@@ -22,6 +22,7 @@ using namespace hif8dev;
 // static device tables (written once per device by k_build_tables)
 // ------------------------------------------------------------------------------------
 static __device__ __attribute__((aligned(16))) uint8_t g_enc_lut[2][2][3][8192];  // [NaN -> 0][sat][TA, TE ties, truncating][pattern >> 19]
+static __device__ __attribute__((aligned(16))) uint16_t g_val_lut[2][2][3][8192];  // layout of g_enc_lut: upper half of the binary32 pattern of the entry's value
 static __device__ __attribute__((aligned(16))) uint8_t g_hr16_lut[2][2][2][8192];  // HR, 16-bit sources: [NaN -> 0][sat][source LSB][pattern >> 19]
 static __device__ __attribute__((aligned(16))) uint32_t g_dec_lut[256];        // code -> binary32 bits
 
@@ -40,6 +41,8 @@ __global__ void k_build_tables() {
         g_enc_lut[z][sat][2][i] = (uint8_t)encode_alu<false, kSrcF32>(trunc_table_pattern(i), flags);
         // HR of the pattern as a BF16-sourced value (source LSB = bit 16); the bits below 19 that the
         // index drops do not enter the decision
+#pragma unroll
+        for (uint32_t k = 0; k < 3u; ++k) g_val_lut[z][sat][k][i] = (uint16_t)(decode_bits(g_enc_lut[z][sat][k][i]) >> 16);
         g_hr16_lut[z][sat][0][i] = (uint8_t)encode_any<kSrcBF16>(i << 19, kRmHR | flags, 0u);
         g_hr16_lut[z][sat][1][i] = (uint8_t)encode_any<kSrcBF16>((i << 19) | 0x10000u, kRmHR | flags, 0u);
       }
@@ -155,9 +158,11 @@ hif8_status ensure_init(int* cu_count_out, DevTables* tables_out) {
     void* p_enc = nullptr;
     void* p_dec = nullptr;
     void* p_hr16 = nullptr;
+    void* p_val = nullptr;
     if (!hip_ok(hipGetSymbolAddress(&p_enc, HIP_SYMBOL(g_enc_lut)))) return HIF8_ERR_HIP;
     if (!hip_ok(hipGetSymbolAddress(&p_dec, HIP_SYMBOL(g_dec_lut)))) return HIF8_ERR_HIP;
     if (!hip_ok(hipGetSymbolAddress(&p_hr16, HIP_SYMBOL(g_hr16_lut)))) return HIF8_ERR_HIP;
+    if (!hip_ok(hipGetSymbolAddress(&p_val, HIP_SYMBOL(g_val_lut)))) return HIF8_ERR_HIP;
     hipLaunchKernelGGL(k_build_tables, dim3(8192 / 256), dim3(256), 0, (hipStream_t)0);
     if (!hip_ok(hipGetLastError())) return HIF8_ERR_HIP;
     // the null stream synchronises with every blocking stream; wait on the host as well so
@@ -167,6 +172,7 @@ hif8_status ensure_init(int* cu_count_out, DevTables* tables_out) {
     g_tables[dev].enc_lut = reinterpret_cast<const uint8_t*>(p_enc);
     g_tables[dev].dec_lut = reinterpret_cast<const uint32_t*>(p_dec);
     g_tables[dev].hr16_lut = reinterpret_cast<const uint8_t*>(p_hr16);
+    g_tables[dev].val_lut = reinterpret_cast<const uint16_t*>(p_val);
     g_inited[dev] = true;
   }
   if (cu_count_out) *cu_count_out = g_cu_count[dev];
