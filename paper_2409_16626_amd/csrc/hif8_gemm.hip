@@ -77,7 +77,7 @@ template <int WM, int WN, int TM, int TN, int BK, int EPI>
 __global__ void __launch_bounds__(64 * WM * WN)
 k_gemm_nt(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __restrict__ out,
           const float* __restrict__ ref, double* __restrict__ err, uint32_t M, uint32_t N, uint32_t K,
-          float descale, const uint16_t* __restrict__ g_lut, uint32_t tiles_n, Batch batch) {
+          float descale, const uint16_t* __restrict__ g_lut, uint32_t tiles_n, uint32_t col_begin, Batch batch) {
   // batched form (the scale search of Algorithm 1): blockIdx.y = pair (i, j) of code matrices
   if (batch.nb != 0u) {
     const uint32_t bi = blockIdx.y / batch.nb, bj = blockIdx.y - bi * batch.nb;
@@ -101,7 +101,7 @@ k_gemm_nt(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __
   const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
   const uint32_t wm = wave / WN, wn = wave % WN;
   const uint32_t tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x - tile_m * tiles_n;
-  const uint32_t m0 = tile_m * BM, n0 = tile_n * BN;
+  const uint32_t m0 = tile_m * BM, n0 = col_begin + tile_n * BN;  // the launch covers columns from col_begin on
 
   // replicated table: entry (code, copy) at dword code * 32 + copy; lane l reads copy l % 32
   for (uint32_t i = tid; i < 256u * kLutCopies; i += kThreads) {
@@ -261,7 +261,10 @@ constexpr size_t smem_bytes() {
 template <int WM, int WN, int TM, int TN, int BK, int EPI>
 static hif8_status launch_tiled(const uint8_t* A, const uint8_t* B, void* out, const float* ref, double* err,
                                 uint32_t M, uint32_t N, uint32_t K, float descale, const uint16_t* lut,
-                                hipStream_t st, const Batch& batch = Batch{0u, 0, 0, 0}, uint32_t pairs = 1) {
+                                hipStream_t st, const Batch& batch = Batch{0u, 0, 0, 0}, uint32_t pairs = 1,
+                                uint32_t col_begin = 0, uint32_t col_end = 0xFFFFFFFFu) {
+  if (col_end > N) col_end = N;
+  if (col_begin >= col_end) return HIF8_OK;
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   constexpr size_t smem = smem_bytes<WM, WN, TM, TN, BK>();
   static bool attr_set[kMaxDevices] = {};
@@ -273,10 +276,10 @@ static hif8_status launch_tiled(const uint8_t* A, const uint8_t* B, void* out, c
       return HIF8_ERR_HIP;
     attr_set[dev] = true;
   }
-  const uint32_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  const uint32_t tiles_m = (M + BM - 1) / BM, tiles_n = (col_end - col_begin + BN - 1) / BN;
   if ((uint64_t)tiles_m * tiles_n > 0x7FFFFFFFull) return HIF8_ERR_ARG;
   hipLaunchKernelGGL((k_gemm_nt<WM, WN, TM, TN, BK, EPI>), dim3(tiles_m * tiles_n, pairs), dim3(64 * WM * WN), smem, st,
-                     A, B, out, ref, err, M, N, K, descale, lut, tiles_n, batch);
+                     A, B, out, ref, err, M, N, K, descale, lut, tiles_n, col_begin, batch);
   return finish_launch();
 }
 
@@ -307,6 +310,13 @@ static hif8_status gemm_dispatch(const uint8_t* A, const uint8_t* B, void* out, 
     return finish_launch();
   }
   int variant = g_gemm_variant;
+  uint32_t split = 0;
+  if (variant == 0 && ragged_round_split(M, N, (size_t)cus, &split)) {
+    // complete rounds of 256 x 256 tiles, then the remaining columns in 128 x 128 tiles (second launch)
+    s = launch_tiled<4, 2, 2, 4, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st, Batch{0u, 0, 0, 0}, 1u, 0u, split);
+    if (s != HIF8_OK) return s;
+    return launch_tiled<2, 2, 2, 2, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st, Batch{0u, 0, 0, 0}, 1u, split, n);
+  }
   if (variant == 0)  // 256 x 256 tiles once there is one for every compute unit, else 128 x 128 (two workgroups per CU)
     variant = (((M + 255) / 256) * ((N + 255) / 256) >= (size_t)cus) ? 5 : 6;
   if (variant == 2) return launch_tiled<2, 2, 4, 4, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);

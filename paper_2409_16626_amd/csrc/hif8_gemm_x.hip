@@ -46,7 +46,7 @@ template <int WM, int WN, int TM, int TN, int EPI>
 __global__ void __launch_bounds__(64 * WM * WN)
 k_gemm_x(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, void* __restrict__ out,
          const float* __restrict__ ref, double* __restrict__ err, uint32_t M, uint32_t N, uint32_t ld,
-         float descale, uint32_t tiles_n, Batch batch) {
+         float descale, uint32_t tiles_n, uint32_t col_begin, Batch batch) {
   if (batch.nb != 0u) {
     const uint32_t bi = blockIdx.y / batch.nb, bj = blockIdx.y - bi * batch.nb;
     A += (size_t)bi * batch.a_stride;
@@ -66,7 +66,7 @@ k_gemm_x(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, void* _
   const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: LDS destinations of the loads stay in SGPRs
   const uint32_t wm = wave / WN, wn = wave % WN;
   const uint32_t tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x - tile_m * tiles_n;
-  const uint32_t m0 = tile_m * BM, n0 = tile_n * BN;
+  const uint32_t m0 = tile_m * BM, n0 = col_begin + tile_n * BN;  // the launch covers columns from col_begin on
 
   // Tile loads are buffer loads into LDS: one descriptor per operand panel of this workgroup (SGPRs), a
   // 32-bit byte offset per lane that never changes, and a scalar offset that advances along K -- no vector
@@ -320,7 +320,9 @@ int& expanded_variant() {
 
 template <int WM, int WN, int TM, int TN, int EPI>
 static hif8_status launch_x(const uint16_t* A, const uint16_t* B, void* out, const float* ref, double* err, uint32_t M,
-                            uint32_t N, uint32_t ld, float descale, hipStream_t st, const Batch& batch, uint32_t pairs) {
+                            uint32_t N, uint32_t ld, float descale, hipStream_t st, const Batch& batch, uint32_t pairs,
+                            uint32_t col_begin = 0, uint32_t col_end = 0xFFFFFFFFu) {
+  if (col_end > N) col_end = N;
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   constexpr size_t smem = (size_t)2 * (BM + BN) * kRowBytes;
   static bool attr_set[kMaxDevices] = {};
@@ -333,10 +335,11 @@ static hif8_status launch_x(const uint16_t* A, const uint16_t* B, void* out, con
       return HIF8_ERR_HIP;
     attr_set[dev] = true;
   }
-  const uint32_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  if (col_begin >= col_end) return HIF8_OK;
+  const uint32_t tiles_m = (M + BM - 1) / BM, tiles_n = (col_end - col_begin + BN - 1) / BN;
   if ((uint64_t)tiles_m * tiles_n > 0x7FFFFFFFull || pairs == 0 || pairs > 65535u) return HIF8_ERR_ARG;
   hipLaunchKernelGGL((k_gemm_x<WM, WN, TM, TN, EPI>), dim3(tiles_m * tiles_n, pairs), dim3(64 * WM * WN), smem, st, A, B,
-                     out, ref, err, M, N, ld, descale, tiles_n, batch);
+                     out, ref, err, M, N, ld, descale, tiles_n, col_begin, batch);
   return finish_launch();
 }
 
@@ -357,6 +360,15 @@ hif8_status gemm_expanded(const uint16_t* A, const uint16_t* B, void* out, const
   // 256 x 256 tiles (8 wavefronts) once the launch has one for every compute unit, else 128 x 128 (4 wavefronts)
   const size_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256) * (size_t)pairs;
   int variant = expanded_variant();
+  uint32_t split = 0;
+  if (variant == 0 && pairs == 1 && ragged_round_split(M, N, (size_t)cus, &split)) {
+    // complete rounds of 256 x 256 tiles, then the remaining columns in 128 x 128 tiles (second launch)
+    s = launch_x<2, 4, 4, 2, EPI>(A, B, out, ref, err, (uint32_t)M, (uint32_t)N, (uint32_t)ld, descale, st, batch, pairs,
+                                  0u, split);
+    if (s != HIF8_OK) return s;
+    return launch_x<2, 2, 2, 2, EPI>(A, B, out, ref, err, (uint32_t)M, (uint32_t)N, (uint32_t)ld, descale, st, batch, pairs,
+                                     split, (uint32_t)N);
+  }
   if (variant == 0) variant = big_tiles >= (size_t)cus ? 7 : 9;
   if (variant == 7)
     return launch_x<2, 4, 4, 2, EPI>(A, B, out, ref, err, (uint32_t)M, (uint32_t)N, (uint32_t)ld, descale, st, batch, pairs);
