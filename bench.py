@@ -267,6 +267,12 @@ def main():
         extra["C3 amax+scale+fake_quant_bf16 (7 B/elem with amax pass)"] = rate(7 * m, e_ms)
         w_ms, e_ms = timed(lambda i: hif8.hif8_fake_quant_bf16_ds(acts[i % R], fq[i % R], cds[i % R], m, sc, hif8.RM_TA), K, W)
         extra["fake_quant_bf16 alone (5 B/elem)"] = rate(5 * m, e_ms)
+        # the paper's delayed scaling (Sec. 5): the cast uses the scale on the device and accumulates the amax
+        # of its input for the next update in the same pass -- C3 in one pass over the tensor
+        acc = torch.zeros(1, dtype=torch.float32, device=dev)
+        w_ms, e_ms = timed(lambda i: hif8.hif8_fake_quant_bf16_ds(acts[i % R], fq[i % R], cds[i % R], m, sc, hif8.RM_TA,
+                                                                  d_amax_accum=acc), K, W)
+        extra["C3 with delayed scaling: fake_quant_bf16_ds + amax accumulated in the same pass (5 B/elem)"] = rate(5 * m, e_ms)
         w_ms, e_ms = timed(lambda i: hif8.hif8_amax_bf16(acts[i % R], m, am), K, W)
         extra["amax_bf16 (2 B/elem)"] = rate(2 * m, e_ms)
         w_ms, e_ms = timed(lambda i: hif8.hif8_encode_bf16_ds(acts[i % R], cds[i % R], m, sc, hif8.RM_TA), K, W)
@@ -287,11 +293,15 @@ def main():
         errs = torch.zeros(16, dtype=torch.float64, device=dev)
         w_ms, e_ms = timed(lambda i: hif8.hif8_scale_sweep_bf16(acts[i % R], m, -4, 10, hif8.RM_TA, errs), K, W)
         # per element and scale: multiply, two shifts, 16-bit value-table read, shift, multiply, conversion to
-        # fp64, fp64 subtract, fp64 fma: 8.5 vector instructions per cast by SQ_INSTS_VALU
+        # fp64, fp64 subtract, fp64 fma: 8.5 vector instructions per cast by SQ_INSTS_VALU.  The rate can pass the
+        # 39.3 T lane-ops/s of one instruction per SIMD every four cycles: v_fma_f64 partly overlaps with other
+        # vector instructions on this chip (a probe mixing it with integer and fp32 instructions issues 44 T/s,
+        # any single kind 38 T/s), and it is one instruction in eight here.
         ops = 8.5 * 10 * m
         extra["scale_sweep_bf16 C3 tensor, 10 scales"] = {
             "ms": round(e_ms, 5), "elements_per_s": round(m / (e_ms * 1e-3), 0), "casts_per_s": round(10 * m / (e_ms * 1e-3), 0),
-            "bound": "alu", "lane_ops_per_s": round(ops / (e_ms * 1e-3), 0), "frac_of_39.3T_lane_ops": round(ops / (e_ms * 1e-3) / 39.3e12, 4)}
+            "bound": "alu", "lane_ops_per_s": round(ops / (e_ms * 1e-3), 0), "frac_of_39.3T_lane_ops": round(ops / (e_ms * 1e-3) / 39.3e12, 4),
+            "note": "above 1 where v_fma_f64 overlaps with the other vector instructions"}
         rows_c, cols_c = 11008, 4096
         wmats = [a[:rows_c * cols_c] for a in acts]   # rotate the source as well: one 90 MB matrix would sit in the last-level cache
         for axis in (0, 1):
