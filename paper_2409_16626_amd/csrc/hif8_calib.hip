@@ -182,7 +182,7 @@ k_amax_rows(const void* __restrict__ src, uint32_t cols_vec, uint32_t chunks, ui
     const uint32_t c = (chunk * kAxUnroll + j) * kAxBlock + threadIdx.x;
     if (c < cols_vec) m = vec_amax<SRCK>(m, ld_stream(p + c));
   }
-  block_max_to_global(fold_amax<SRCK>(m), out + row);
+  block_max_to_global<false>(fold_amax<SRCK>(m), out + row);  // a row has few chunks: no contention to avoid
 }
 
 // columns: the wavefronts of a workgroup share a strip of 64 column vectors and take every
