@@ -316,6 +316,11 @@ def main():
 
             w_ms, e_ms = timed(per_channel, K, W)
             extra["per-channel amax+scale+encode_bf16 [11008,4096] axis %d (5 B/elem with amax pass)" % axis] = rate(5 * rows_c * cols_c, e_ms)
+        am_r = torch.zeros(rows_c, dtype=torch.float32, device=dev)
+        sc_r = torch.zeros(rows_c, 2, dtype=torch.float32, device=dev)
+        w_ms, e_ms = timed(lambda i: hif8.hif8_quantize_rows_bf16(wmats[i % R], cds[i % R], rows_c, cols_c, am_r, sc_r,
+                                                                  hif8.MAX_FINITE, 1, hif8.RM_TA), K, W)
+        extra["per-row amax+scale+encode_bf16 [11008,4096] in one pass, hif8_quantize_rows (3 B/elem)"] = rate(3 * rows_c * cols_c, e_ms)
         del acts, fq, cds, a0, wmats
         torch.cuda.empty_cache()
 

@@ -310,6 +310,30 @@ hif8_status hif8_decode_axis_f16(const uint8_t* src, uint16_t* dst, size_t rows,
                                  int axis, const float* d_scale2, hif8_stream_t stream);
 
 /*
+ * Per-row scaling (channels along axis 0, the layout of a weight matrix [out channels, in]; Sec. 4.2
+ * names per-channel scaling of weights as a further method) in one call and, where a row fits the
+ * registers of a workgroup, one pass over the source:
+ *     d_amax[r]  = max_c |src[r, c]|                      (rows device floats, always written)
+ *     d_scale2[2 r], [2 r + 1] = scale, fl32(1 / scale)    as hif8_scale_from_amax(d_amax[r], target, pow2)
+ *     dst[r, c]  = code(Q(fl32(src[r, c] * scale)))
+ * i.e. exactly what hif8_amax_axis_* (axis 0), hif8_scale_from_amax_n and hif8_encode_axis_* (axis 0)
+ * produce in three launches and two reads of the source.  The single-pass form needs the fast-path
+ * alignment of hif8_encode_axis_* and at most 16,384 (FP32) or 32,768 (16-bit) columns; other inputs
+ * are handed to the three separate launches.  All pointers are device pointers owned by the caller;
+ * rows == 0 is a no-op; HIF8_ERR_NULL for a null d_amax or d_scale2 (or null data with rows * cols > 0),
+ * HIF8_ERR_MODE / HIF8_ERR_ARG as for the separate calls.
+ */
+hif8_status hif8_quantize_rows_f32(const float* src, uint8_t* dst, size_t rows, size_t cols, float target,
+                                   int pow2, uint32_t rounding_mode, float* d_amax, float* d_scale2,
+                                   hif8_stream_t stream);
+hif8_status hif8_quantize_rows_bf16(const uint16_t* src, uint8_t* dst, size_t rows, size_t cols, float target,
+                                    int pow2, uint32_t rounding_mode, float* d_amax, float* d_scale2,
+                                    hif8_stream_t stream);
+hif8_status hif8_quantize_rows_f16(const uint16_t* src, uint8_t* dst, size_t rows, size_t cols, float target,
+                                   int pow2, uint32_t rounding_mode, float* d_amax, float* d_scale2,
+                                   hif8_stream_t stream);
+
+/*
  * Per-tensor scaling state for training (Sec. 5.1, PTS): one scale per GEMM input tensor, all 1
  * at the start; every `interval` iterations (the paper uses 10) the amax of each tensor is
  * gathered and its scale becomes the largest power of two s with amax * s <= target; in every

@@ -290,6 +290,76 @@ k_encode_rows(const void* __restrict__ src, uint8_t* __restrict__ dst, uint32_t 
   }
 }
 
+// Per-row scaling in one pass: amax of the row, its scale, and the cast, with the row held in registers
+// between the two (one read of the source instead of two).  A workgroup walks rows blockIdx.x, + gridDim.x, ...;
+// a lane holds VPT 16-byte vectors of the row (vector j * kQrBlock + lane index), the next row is requested
+// before the current one is reduced, and one barrier per row publishes the wavefront maxima (two sets of
+// slots, used alternately).  Same arithmetic as hif8_amax_axis + hif8_scale_from_amax_n + hif8_encode_axis
+// with axis 0: d_amax[row] and d_scale2[2 row], [2 row + 1] receive the same values.
+constexpr int kQrBlock = 512;
+constexpr int kQrWaves = kQrBlock / 64;
+
+template <int IMPL, int SRCK, int VPT>
+__global__ void __launch_bounds__(kQrBlock)
+k_quant_rows(const void* __restrict__ src, uint8_t* __restrict__ dst, uint32_t rows, uint32_t cols_vec, float target,
+             int pow2, uint32_t* __restrict__ d_amax, float* __restrict__ d_scale2, uint32_t mode, uint64_t seed,
+             const uint8_t* __restrict__ g_lut) {
+  __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
+  __shared__ HrLds<uses_exp_table<IMPL>()> hrt;
+  __shared__ uint32_t part[2][kQrWaves];
+  const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, seed);
+  constexpr int VE = vec_elems<SRCK>();
+  const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(src);
+  const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
+  uint4 nxt[VPT];
+  auto request = [&](uint32_t r) {
+    const uint4* __restrict__ p = src4 + (size_t)r * cols_vec;
+#pragma unroll
+    for (int j = 0; j < VPT; ++j) {
+      const uint32_t c = j * kQrBlock + threadIdx.x;
+      nxt[j] = c < cols_vec ? ld_stream(p + c) : make_uint4(0u, 0u, 0u, 0u);
+    }
+  };
+  uint32_t r = blockIdx.x;  // uniform over the workgroup, as is every branch on it
+  if (r < rows) request(r);
+  stage_enc_lut<IMPL, SRCK>(lut, g_lut, mode);
+  stage_exp_table<IMPL, SRCK>(hrt.w, mode);
+  for (uint32_t it = 0; r < rows; r += gridDim.x, ++it) {
+    uint4 cur[VPT];
+    uint32_t m = 0;
+#pragma unroll
+    for (int j = 0; j < VPT; ++j) {
+      cur[j] = nxt[j];
+      m = vec_amax<SRCK>(m, cur[j]);  // vectors past the row are zeros
+    }
+    m = wave_max_u32(fold_amax<SRCK>(m));
+    if (lane == 0u) part[it & 1u][wv] = m;
+    if (r + gridDim.x < rows) request(r + gridDim.x);
+    __syncthreads();  // also orders the table staging before the first row's lookups
+    uint32_t a = part[it & 1u][0];
+#pragma unroll
+    for (int w = 1; w < kQrWaves; ++w) a = umax(a, part[it & 1u][w]);
+    const float scale = scale_from_amax_value(__uint_as_float(a), target, pow2);
+    if (threadIdx.x == 0u) {
+      d_amax[r] = a;
+      d_scale2[2 * (size_t)r] = scale;
+      d_scale2[2 * (size_t)r + 1] = 1.0f / scale;
+    }
+    const size_t rbase = (size_t)r * cols_vec;
+#pragma unroll
+    for (int j = 0; j < VPT; ++j) {
+      const uint32_t c = j * kQrBlock + threadIdx.x;
+      if (c < cols_vec) {
+        const size_t idx = rbase + c;
+        if constexpr (SRCK == kSrcF32)
+          st_stream(reinterpret_cast<uint32_t*>(dst) + idx, encode4_f32<IMPL>(cur[j], scale, ctx, idx * VE));
+        else
+          st_stream(reinterpret_cast<uint2*>(dst) + idx, encode8_16<IMPL, SRCK>(cur[j], scale, ctx, idx * VE));
+      }
+    }
+  }
+}
+
 template <int IMPL, int SRCK>
 __global__ void __launch_bounds__(kAxBlock)
 k_encode_cols(const void* __restrict__ src, uint8_t* __restrict__ dst, uint32_t rows, uint32_t cols_vec,
@@ -609,6 +679,52 @@ hif8_status encode_axis(const void* src, uint8_t* dst, size_t rows, size_t cols,
   return finish_launch();
 }
 
+// Fused per-row path when a row fits the registers of one workgroup and the fast-path alignment holds;
+// otherwise the three separate launches (same results).
+template <int SRCK>
+hif8_status quantize_rows(const void* src, uint8_t* dst, size_t rows, size_t cols, float target, int pow2, uint32_t mode,
+                          float* d_amax, float* d_scale2, hipStream_t st) {
+  if (!valid_mode(mode)) return HIF8_ERR_MODE;
+  if (!(target > 0.0f) || std::isinf(target)) return HIF8_ERR_ARG;
+  if (rows == 0) return HIF8_OK;
+  if (!d_amax || !d_scale2 || (rows * cols != 0 && (!src || !dst))) return HIF8_ERR_NULL;
+  if (rows > 0x7FFFFFFFu || cols > 0x7FFFFFFFu) return HIF8_ERR_ARG;
+  int cus = 0;
+  DevTables tb;
+  hif8_status s = ensure_init(&cus, &tb);
+  if (s != HIF8_OK) return s;
+  constexpr size_t VE = vec_elems<SRCK>();
+  const bool al = aligned_to(src, 16) && aligned_to(dst, SRCK == kSrcF32 ? 4 : 8);
+  const size_t cols_vec = cols / VE;
+  if (!al || cols == 0 || (cols % VE) != 0 || cols_vec > (size_t)kQrBlock * 8) {
+    s = amax_axis<SRCK>(src, rows, cols, 0, d_amax, st);
+    if (s != HIF8_OK) return s;
+    s = hif8host::launch_scale_from_amax(d_amax, d_scale2, (uint32_t)rows, target, pow2, st);
+    if (s != HIF8_OK) return s;
+    return encode_axis<SRCK>(src, dst, rows, cols, 0, d_scale2, mode, st);
+  }
+  const uint64_t seed = sr_seed();
+  // enough workgroups to fill the chip (four of 512 lanes per CU), each walking several rows (measured flat from 3 to 8 per CU)
+  size_t wgs = (size_t)cus * 4;
+  if (wgs > rows) wgs = rows;
+  const int vpt = cols_vec <= (size_t)kQrBlock ? 1 : cols_vec <= (size_t)kQrBlock * 2 ? 2 : cols_vec <= (size_t)kQrBlock * 4 ? 4 : 8;
+  uint32_t* am = reinterpret_cast<uint32_t*>(d_amax);
+  dispatch_impl_only(impl_no_alu(mode), [&](auto impl_c) {
+    constexpr int IMPL = decltype(impl_c)::value;
+    auto go = [&](auto vpt_c) {
+      constexpr int VPT = decltype(vpt_c)::value;
+      hipLaunchKernelGGL((k_quant_rows<IMPL, SRCK, VPT>), dim3((unsigned)wgs), dim3(kQrBlock), 0, st, src, dst, (uint32_t)rows,
+                         (uint32_t)cols_vec, target, pow2, am, d_scale2, mode, seed, tb.enc_lut);
+    };
+    using std::integral_constant;
+    if (vpt == 1) go(integral_constant<int, 1>{});
+    else if (vpt == 2) go(integral_constant<int, 2>{});
+    else if (vpt == 4) go(integral_constant<int, 4>{});
+    else go(integral_constant<int, 8>{});
+  });
+  return finish_launch();
+}
+
 template <int DSTK>
 hif8_status decode_axis(const uint8_t* src, void* dst, size_t rows, size_t cols, int axis, const float* d_scale2,
                         hipStream_t st) {
@@ -668,6 +784,11 @@ hif8_status hif8_scale_from_amax_n(const float* d_amax, float* d_scale2, size_t 
   hif8_status hif8_decode_axis_##SFX(const uint8_t* src, T* dst, size_t rows, size_t cols, int axis,          \
                                      const float* d_scale2, hif8_stream_t stream) {                           \
     return decode_axis<K>(src, dst, rows, cols, axis, d_scale2, (hipStream_t)stream);                         \
+  }                                                                                                           \
+  hif8_status hif8_quantize_rows_##SFX(const T* src, uint8_t* dst, size_t rows, size_t cols, float target,    \
+                                       int pow2, uint32_t mode, float* d_amax, float* d_scale2,               \
+                                       hif8_stream_t stream) {                                                \
+    return quantize_rows<K>(src, dst, rows, cols, target, pow2, mode, d_amax, d_scale2, (hipStream_t)stream); \
   }
 
 HIF8_DEFINE_CALIB(f32, float, kSrcF32)

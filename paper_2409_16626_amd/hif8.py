@@ -95,6 +95,9 @@ _SIGS = {
     "hif8_decode_axis_f32": ([_vp, _vp, _sz, _sz, _i, _vp, _vp], _i),
     "hif8_decode_axis_bf16": ([_vp, _vp, _sz, _sz, _i, _vp, _vp], _i),
     "hif8_decode_axis_f16": ([_vp, _vp, _sz, _sz, _i, _vp, _vp], _i),
+    "hif8_quantize_rows_f32": ([_vp, _vp, _sz, _sz, _f, _i, _u32, _vp, _vp, _vp], _i),
+    "hif8_quantize_rows_bf16": ([_vp, _vp, _sz, _sz, _f, _i, _u32, _vp, _vp, _vp], _i),
+    "hif8_quantize_rows_f16": ([_vp, _vp, _sz, _sz, _f, _i, _u32, _vp, _vp, _vp], _i),
     "hif8_pts_init": ([_vp, _vp, _vp, _sz, _u32, _f, _vp], _i),
     "hif8_pts_collects": ([_vp], _i),
     "hif8_pts_end_iteration": ([_vp, _vp], _i),
@@ -346,6 +349,21 @@ def _def_calib(sfx):
 hif8_scale_sweep_f32, hif8_amax_axis_f32, hif8_encode_axis_f32, hif8_decode_axis_f32 = _def_calib("f32")
 hif8_scale_sweep_bf16, hif8_amax_axis_bf16, hif8_encode_axis_bf16, hif8_decode_axis_bf16 = _def_calib("bf16")
 hif8_scale_sweep_f16, hif8_amax_axis_f16, hif8_encode_axis_f16, hif8_decode_axis_f16 = _def_calib("f16")
+
+
+def _def_quantize_rows(sfx):
+    fn = getattr(lib, "hif8_quantize_rows_" + sfx)
+
+    def quantize_rows(src, dst, rows, cols, d_amax, d_scale2, target=MAX_FINITE, pow2=0, rounding_mode=RM_TA, stream=None):
+        _check(fn(_ptr(src), _ptr(dst), rows, cols, target, int(pow2), rounding_mode, _ptr(d_amax), _ptr(d_scale2),
+                  _stream(stream)))
+
+    return quantize_rows
+
+
+hif8_quantize_rows_f32 = _def_quantize_rows("f32")
+hif8_quantize_rows_bf16 = _def_quantize_rows("bf16")
+hif8_quantize_rows_f16 = _def_quantize_rows("f16")
 
 
 class PtsState(ctypes.Structure):

@@ -55,6 +55,12 @@ def test_argument_validation_happens_on_the_host():
     assert L.hif8_gemm_f32(p, p, p, 0, 16, 16, 1.0, 1.0, None) == OK           # empty output: nothing to do
     assert L.hif8_amax_axis_f32(p, 4, 4, 2, p, None) == ARG
     assert L.hif8_encode_axis_bf16(p, p, 4, 4, 0, None, 0, None) == NULL
+    assert L.hif8_quantize_rows_bf16(p, p, 4, 8, 32768.0, 1, 0, None, p, None) == NULL
+    assert L.hif8_quantize_rows_bf16(p, p, 4, 8, 32768.0, 1, 0, p, None, None) == NULL
+    assert L.hif8_quantize_rows_f32(None, p, 4, 8, 32768.0, 1, 0, p, p, None) == NULL
+    assert L.hif8_quantize_rows_f32(p, p, 4, 8, 32768.0, 1, 9, p, p, None) == MODE
+    assert L.hif8_quantize_rows_f16(p, p, 4, 8, 0.0, 1, 0, p, p, None) == ARG
+    assert L.hif8_quantize_rows_f16(None, None, 0, 8, 32768.0, 1, 0, None, None, None) == OK
     assert L.hif8_calibrate_layer_f32(p, p, p, 16, 16, 16, -4, 10, -4, 10, 0, p, 0, p, None, None) == ARG   # workspace too small
     assert L.hif8_calibrate_layer_f32(p, p, p, 16, 16, 16, -4, 65, -4, 10, 0, p, 1 << 20, p, None, None) == ARG
     # one code matrix (the larger operand) + every cast operand as bfloat16 with rows padded to 64 elements

@@ -156,6 +156,72 @@ def test_per_channel_amax_scale_encode_decode(h, rows, cols, axis):
         assert_same_bytes(gd.reshape(-1), wdb.reshape(-1), "decode_axis %s" % kind)
 
 
+QR_SHAPES = [(37, 56), (64, 4096), (300, 1032), (1, 8), (4096, 8), (5, 8200), (1030, 264), (2, 3), (3, 16392),
+             (700, 4104), (2, 32768), (2, 32776), (9, 2048)]
+
+
+@pytest.mark.parametrize("rows,cols", QR_SHAPES)
+def test_quantize_rows_matches_oracle_composition(h, rows, cols):
+    """The one-call per-row path (one pass where a row fits a workgroup, the three launches otherwise):
+    amax, scale pair and codes bit for bit what the oracle's amax -> scale -> cast composition gives."""
+    g = torch.Generator(device=dev()).manual_seed(rows * 977 + cols)
+    xf = (torch.randn(rows, cols, generator=g, device=dev())
+          * torch.exp2(torch.rand((rows, 1), generator=g, device=dev()) * 14 - 7)).contiguous()
+    if rows > 2:
+        xf[1] = 0.0                                            # an all-zero row: amax 0 -> scale 1
+    for kind in ("f32", "bf16", "f16"):
+        x, xn = as_kind(xf, kind)
+        w_am = orc.amax_axis(xn, KINDS[kind], 0)
+        for mode, pow2, target in ((TA, 1, 32768.0), (HR, 0, 32768.0), (SR | SAT, 1, 16.0), (TE, 0, 1000.0)):
+            am = torch.full((rows,), 5.0, dtype=torch.float32, device=dev())
+            sc = torch.full((rows, 2), -1.0, dtype=torch.float32, device=dev())
+            codes = torch.full((rows, cols), 0xAA, dtype=torch.uint8, device=dev())
+            getattr(h, "hif8_quantize_rows_" + kind)(x, codes, rows, cols, am, sc, target, pow2, mode)
+            torch.cuda.synchronize()
+            assert_same_bytes(f32_bits(am), w_am.view(np.uint32), "quantize_rows amax %s" % kind)
+            w_sc = np.array([orc.scale_from_amax(a, target, bool(pow2)) for a in w_am], np.float32)
+            scn = sc.cpu().numpy()
+            assert np.array_equal(scn[:, 0], w_sc) and np.array_equal(scn[:, 1], np.float32(1.0) / w_sc)
+            want = orc.encode_axis(xn, w_sc, KINDS[kind], 0, mode)
+            assert_same_bytes(codes.cpu().numpy().reshape(-1), want.reshape(-1), "quantize_rows %s %#x" % (kind, mode))
+
+
+def test_quantize_rows_unaligned_special_values_and_arguments(h):
+    from paper_2409_16626_amd.hif8 import Hif8Error
+    rows, cols = 19, 72
+    g = torch.Generator(device=dev()).manual_seed(5)
+    base = torch.randn(rows * cols + 8, generator=g, device=dev())
+    x = base[1:1 + rows * cols]                                # 4-byte aligned only: the separate launches
+    x[5] = float("inf"); x[cols + 3] = float("nan"); x[2 * cols:3 * cols] = 0.0
+    xn = x.cpu().numpy().reshape(rows, cols)
+    am = torch.zeros(rows, dtype=torch.float32, device=dev())
+    sc = torch.zeros(rows, 2, dtype=torch.float32, device=dev())
+    codes = torch.zeros(rows, cols, dtype=torch.uint8, device=dev())
+    h.hif8_quantize_rows_f32(x.data_ptr(), codes, rows, cols, am, sc, 32768.0, 1, TA)
+    torch.cuda.synchronize()
+    w_am = orc.amax_axis(xn, orc.SRC_F32, 0)
+    assert_same_bytes(f32_bits(am), w_am.view(np.uint32), "amax")
+    w_sc = np.array([orc.scale_from_amax(a, 32768.0, True) for a in w_am], np.float32)
+    assert np.array_equal(sc.cpu().numpy()[:, 0], w_sc)
+    assert_same_bytes(codes.cpu().numpy().reshape(-1), orc.encode_axis(xn, w_sc, orc.SRC_F32, 0, TA).reshape(-1), "codes")
+    # the same values through the aligned (single-pass) path
+    xa = x.clone()
+    am2, sc2, codes2 = torch.zeros_like(am), torch.zeros_like(sc), torch.zeros_like(codes)
+    h.hif8_quantize_rows_f32(xa, codes2, rows, cols, am2, sc2, 32768.0, 1, TA)
+    torch.cuda.synchronize()
+    assert torch.equal(am.view(torch.int32), am2.view(torch.int32)) and torch.equal(sc.view(torch.int32), sc2.view(torch.int32))
+    assert torch.equal(codes, codes2)
+    # arguments
+    h.hif8_quantize_rows_f32(0, 0, 0, 64, 0, 0)                # no rows: nothing to do
+    for bad in (dict(target=0.0), dict(target=float("inf")), dict(rounding_mode=7)):
+        with pytest.raises(Hif8Error):
+            h.hif8_quantize_rows_f32(xa, codes2, rows, cols, am2, sc2, **bad)
+    with pytest.raises(Hif8Error):
+        h.hif8_quantize_rows_f32(xa, codes2, rows, cols, 0, sc2)
+    with pytest.raises(Hif8Error):
+        h.hif8_quantize_rows_f32(xa, codes2, rows, cols, am2, 0)
+
+
 def test_per_channel_unaligned_base_and_special_values(h):
     rows, cols = 33, 64
     g = torch.Generator(device=dev()).manual_seed(3)
