@@ -185,3 +185,26 @@ def test_c5_full(h):
         h.hif8_encode_bf16_ds(arena.data_ptr() + 2 * off, c2, m, s2, TA)
         torch.cuda.synchronize()
         assert torch.equal(c2, codes[off:off + m])
+
+
+@pytest.mark.parametrize("mode", [TA, HR])
+def test_quantize_rows_weight_matrix_full(h, mode):
+    """Per-row scaling of a [11008, 4096] BF16 weight matrix (the shape bench.py times) in one pass:
+    every amax, scale pair and code against the oracle's amax -> scale -> cast composition."""
+    rows, cols = 11008, 4096
+    g = torch.Generator(device=dev()).manual_seed(4096)
+    w = (torch.randn(rows, cols, generator=g, device=dev()) * 0.02
+         * torch.exp2(torch.rand((rows, 1), generator=g, device=dev()) * 6 - 3)).to(torch.bfloat16)
+    am = torch.zeros(rows, dtype=torch.float32, device=dev())
+    sc = torch.zeros(rows, 2, dtype=torch.float32, device=dev())
+    codes = torch.zeros(rows, cols, dtype=torch.uint8, device=dev())
+    h.hif8_quantize_rows_bf16(w, codes, rows, cols, am, sc, 32768.0, 1, mode)
+    torch.cuda.synchronize()
+    wn = bf16_bits(w)
+    w_am = orc.amax_axis(wn, orc.SRC_BF16, 0)
+    assert_same_bytes(f32_bits(am), w_am.view(np.uint32), "amax")
+    w_sc = np.array([orc.scale_from_amax(a, 32768.0, True) for a in w_am], np.float32)
+    scn = sc.cpu().numpy()
+    assert np.array_equal(scn[:, 0], w_sc) and np.array_equal(scn[:, 1], np.float32(1.0) / w_sc)
+    want = orc.encode_axis(wn, w_sc, orc.SRC_BF16, 0, mode)
+    assert_same_bytes(codes.cpu().numpy().reshape(-1), want.reshape(-1), "codes")
