@@ -364,7 +364,7 @@ __device__ __forceinline__ int32_t mul_i24(int32_t a, int32_t b) { return __mul2
 // The result is on the HiF8 grid (or at/above 1.5 * 2^15: overflow); NaN patterns come back unchanged.
 template <int SRCK>
 __device__ __forceinline__ uint32_t hr_round_bits(uint32_t ybits, const HrExp& p) {
-  static_assert(SRCK == kSrcF32, "binary32 sources; 16-bit sources use hr16_round_bits");
+  static_assert(SRCK == kSrcF32, "binary32 sources; 16-bit sources use hr16_round_sum");
   // on the whole pattern: the addend C - T' * mult never takes the magnitude below zero or up to the sign
   // bit (it is at least -2^24 where the magnitude is at least 96 * 2^23, below 2^24 elsewhere, and zero
   // from exponent 143 up), and every mask keeps the sign bit
@@ -409,15 +409,13 @@ __device__ __forceinline__ uint32_t hr16_lsb(uint32_t ybits) {
   static_assert(SRCK != kSrcF32, "16-bit sources only");
   return (ybits >> (SRCK == kSrcBF16 ? 16 : 13)) & 1u;
 }
-// Rounded binary32 pattern (sign kept) of pattern ybits, the scaled value of a 16-bit source element;
-// add = addend of ybits' exponent and source LSB, mask = mask of its exponent.  The add works on the whole
-// pattern: the magnitude plus the addend stays within [0, 2^31) (the one negative addend, -2^22, belongs to
-// exponent 104), the masks keep the sign bit, and Inf / NaN patterns get a zero addend.
-__device__ __forceinline__ uint32_t hr16_round_bits(uint32_t ybits, uint32_t add, uint32_t mask) {
-  return (ybits + add) & mask;
-}
-
-// The same without the per-exponent mask, for a lookup in the truncating table (trunc_table_pattern()),
+// Rounding a 16-bit source's scaled pattern ybits: (ybits + add) & mask with the addend of its exponent and
+// source LSB and the mask of its exponent.  The add works on the whole pattern: the magnitude plus the addend
+// stays within [0, 2^31) (the one negative addend, -2^22, belongs to exponent 104), the masks keep the sign
+// bit, and Inf / NaN patterns get a zero addend.  The kernels use the form below, which leaves the mask to
+// the lookup table.
+//
+// Sum without the per-exponent mask, for a lookup in the truncating table (trunc_table_pattern()),
 // which clears the bits below the kept mantissa of the exponent it sees.  That is the exponent of the sum:
 // the right one unless the add carried into the next binade, where the result is the start of that binade
 // exactly but the sum still holds what is left of the discarded field (and the next binade may keep one

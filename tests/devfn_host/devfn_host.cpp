@@ -28,21 +28,14 @@ void devfn_encode_bits(const uint32_t* ybits, uint8_t* dst, size_t n, uint32_t m
     dst[i] = (uint8_t)c;
   }
 }
-// table-driven hybrid rounding (or simplified SR everywhere), then the TA code of the
-// (representable) result
-void devfn_encode_bits_hr_table(const uint32_t* ybits, uint8_t* dst, size_t n, uint32_t mode, int srck) {
+// table-driven hybrid rounding (or simplified SR everywhere) of binary32 sources, then the TA code of
+// the (representable) result
+void devfn_encode_bits_hr_table(const uint32_t* ybits, uint8_t* dst, size_t n, uint32_t mode) {
   const bool ssr = (mode & 0xF) == hif8dev::kRmSSR;
   for (size_t i = 0; i < n; ++i) {
     const uint32_t y = ybits[i];
     if ((y & 0x7FFFFFFFu) > 0x7F800000u) { dst[i] = (uint8_t)hif8dev::nan_code(mode); continue; }
-    uint32_t r;
-    if (srck == 0) {
-      r = hif8dev::hr_round_bits<0>(y, hif8dev::hr_exp_entry((y >> 23) & 0xFFu, ssr));
-    } else {  // 16-bit sources: add-and-mask form
-      const hif8dev::HrExp16 p = hif8dev::hr16_exp_entry((y >> 23) & 0xFFu, ssr);
-      const uint32_t lsb = srck == 1 ? hif8dev::hr16_lsb<1>(y) : hif8dev::hr16_lsb<2>(y);
-      r = hif8dev::hr16_round_bits(y, lsb ? p.add1 : p.add0, p.mask);
-    }
+    const uint32_t r = hif8dev::hr_round_bits<0>(y, hif8dev::hr_exp_entry((y >> 23) & 0xFFu, ssr));
     dst[i] = (uint8_t)hif8dev::encode_alu<false, 0>(r & 0xFFF80000u, mode);
   }
 }

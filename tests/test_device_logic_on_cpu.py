@@ -37,19 +37,17 @@ def _enc(lib, ybits, mode, srck, seed=0):
                           ctypes.c_size_t(ybits.size), ctypes.c_uint32(mode), ctypes.c_int(srck),
                           ctypes.c_uint64(seed))
     if (mode & 0xF) in (orc.RM_HR, orc.RM_SSR):
-        # the streaming kernels' table-driven form must agree with the generic form
+        # the streaming kernels' table-driven forms must agree with the generic form
         out2 = np.empty(ybits.shape, np.uint8)
-        lib.devfn_encode_bits_hr_table(ybits.ctypes.data_as(ctypes.c_void_p), out2.ctypes.data_as(ctypes.c_void_p),
-                                       ctypes.c_size_t(ybits.size), ctypes.c_uint32(mode), ctypes.c_int(srck))
+        if srck == 0:
+            lib.devfn_encode_bits_hr_table(ybits.ctypes.data_as(ctypes.c_void_p), out2.ctypes.data_as(ctypes.c_void_p),
+                                           ctypes.c_size_t(ybits.size), ctypes.c_uint32(mode))
+        else:
+            # 16-bit sources: the clamped sum looked up in the truncating table
+            lib.devfn_encode_bits_hr16_stream(ybits.ctypes.data_as(ctypes.c_void_p), out2.ctypes.data_as(ctypes.c_void_p),
+                                              ctypes.c_size_t(ybits.size), ctypes.c_uint32(mode), ctypes.c_int(srck))
         bad = np.nonzero(out != out2)[0]
         assert bad.size == 0, [(hex(ybits[i]), hex(out[i]), hex(out2[i])) for i in bad[:8]]
-        if srck != 0:
-            # 16-bit sources: the clamped sum looked up in the truncating table
-            out3 = np.empty(ybits.shape, np.uint8)
-            lib.devfn_encode_bits_hr16_stream(ybits.ctypes.data_as(ctypes.c_void_p), out3.ctypes.data_as(ctypes.c_void_p),
-                                              ctypes.c_size_t(ybits.size), ctypes.c_uint32(mode), ctypes.c_int(srck))
-            bad = np.nonzero(out != out3)[0]
-            assert bad.size == 0, [(hex(ybits[i]), hex(out[i]), hex(out3[i])) for i in bad[:8]]
     if (mode & 0xF) == orc.RM_SR:
         # the streaming kernels' add-and-truncate form of standard SR must agree as well
         out2 = np.empty(ybits.shape, np.uint8)
