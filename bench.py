@@ -406,6 +406,19 @@ def main():
         extra["C5 multi-tensor cast, 4 launches (3 B/elem primary)"] = rate(3 * tot, e_ms)
         extra["C5 multi-tensor cast, 4 launches (5 B/elem with amax pass)"] = rate(5 * tot, e_ms)
         extra["C5 multi-tensor cast wall ms"] = round(w_ms, 3)
+        # the paper's delayed scaling (Sec. 5): scales from earlier iterations, the amax of each tensor
+        # accumulated by the cast itself for the next update -- one pass, one launch per tensor
+        accs = torch.zeros(len(index), dtype=torch.float32, device=dev)
+        acp = accs.data_ptr()
+
+        def c5_delayed(i):
+            for t, (_, off, cnt) in enumerate(index):
+                hif8.hif8_encode_bf16_ds(ap + 2 * off, cp + off, cnt, scp + 8 * t, hif8.RM_TA, d_amax_accum=acp + 4 * t)
+
+        w_ms, e_ms = timed(c5_delayed, 5, 1)
+        extra["C5 with delayed scaling: 225 x encode_bf16_ds + amax accumulated in the same pass (3 B/elem)"] = rate(3 * tot, e_ms)
+        w_ms, e_ms = timed(lambda i: hif8.hif8_multi_encode_bf16_ds(d_items, count, tiles, scs, hif8.RM_TA, d_amax_accum=accs), 5, 1)
+        extra["C5 with delayed scaling: multi-tensor encode + amax accumulation, 1 launch (3 B/elem)"] = rate(3 * tot, e_ms)
         result["extra"] = extra
         for k, v in extra.items():
             log("%-64s %s" % (k, v))

@@ -231,6 +231,14 @@ hif8_status hif8_fake_quant_f16_ds(const uint16_t* src, uint16_t* dst, uint8_t* 
  *                    {scale, 1/scale} per tensor, as hif8_scale_from_amax); target, pow2 as in
  *                    hif8_scale_from_amax.  Results equal the per-tensor sequence
  *                    hif8_amax_* -> hif8_scale_from_amax -> hif8_encode_*_ds.
+ *   hif8_multi_encode_{bf16,f16,f32}_ds
+ *                    the cast alone, in ONE launch, with scales that are already on the device
+ *                    (delayed scaling, Sec. 5: scales from earlier iterations): d_scale2: 2*count
+ *                    device floats (input, {scale, 1/scale} per tensor); d_amax_accum_or_null:
+ *                    count device floats, or null; when given, the amax of every tensor's source
+ *                    is accumulated into its entry (max with what the entry holds; the call does
+ *                    not clear it), as the *_ds casts do for one tensor.  Results equal
+ *                    hif8_encode_*_ds per tensor.
  * Misaligned items make hif8_multi_plan return HIF8_ERR_ARG (use the per-tensor calls).
  */
 typedef struct hif8_cast_item {
@@ -248,6 +256,15 @@ hif8_status hif8_multi_cast_bf16(const hif8_cast_item* d_items, size_t count, ui
 hif8_status hif8_multi_cast_f32(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
                                 float* d_amax, float* d_scale2, float target, int pow2,
                                 uint32_t rounding_mode, hif8_stream_t stream);
+hif8_status hif8_multi_encode_bf16_ds(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
+                                      const float* d_scale2, float* d_amax_accum_or_null,
+                                      uint32_t rounding_mode, hif8_stream_t stream);
+hif8_status hif8_multi_encode_f32_ds(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
+                                     const float* d_scale2, float* d_amax_accum_or_null,
+                                     uint32_t rounding_mode, hif8_stream_t stream);
+hif8_status hif8_multi_encode_f16_ds(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
+                                     const float* d_scale2, float* d_amax_accum_or_null,
+                                     uint32_t rounding_mode, hif8_stream_t stream);
 hif8_status hif8_multi_cast_f16(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
                                 float* d_amax, float* d_scale2, float target, int pow2,
                                 uint32_t rounding_mode, hif8_stream_t stream);

@@ -584,10 +584,12 @@ k_multi_amax(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_t 
   if (cur != 0xFFFFFFFFu) block_max_to_global(umax(fold_amax<SRCK>(m), mt), amax_out + cur);
 }
 
-template <int IMPL, int SRCK>
+// ACC: also accumulate the amax of every tensor's source into amax_acc[item] (delayed scaling: the scales
+// in use come from earlier iterations, the accumulators feed the next update).
+template <int IMPL, int SRCK, bool ACC>
 __global__ void __launch_bounds__(kMultiBlock)
 k_multi_encode(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_t total_tiles,
-               const float* __restrict__ d_scale2, uint32_t mode, uint64_t seed,
+               const float* __restrict__ d_scale2, uint32_t* __restrict__ amax_acc, uint32_t mode, uint64_t seed,
                const uint8_t* __restrict__ g_lut) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
   __shared__ HrLds<uses_exp_table<IMPL>()> hrt;
@@ -596,10 +598,20 @@ k_multi_encode(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_
   stage_exp_table<IMPL, SRCK>(hrt.w, mode);
   __syncthreads();
   constexpr int VE = vec_elems<SRCK>();
+  uint32_t m = 0, mt = 0, cur = 0xFFFFFFFFu;  // ACC: as in k_multi_amax
   for (uint32_t i = 0; i < kMultiTpwEncode; ++i) {
     const uint64_t tile = (uint64_t)blockIdx.x * kMultiTpwEncode + i;
     if (tile >= total_tiles) break;
     const uint32_t it = multi_find_item(items, count, tile);
+    if (ACC && it != cur) {
+      if (cur != 0xFFFFFFFFu) {
+        block_max_to_global(umax(fold_amax<SRCK>(m), mt), amax_acc + cur);
+        __syncthreads();
+      }
+      cur = it;
+      m = 0;
+      mt = 0;
+    }
     const uint64_t n = items[it].n;
     const uint64_t nvec = n >> vec_shift<SRCK>();
     const uint64_t local = tile - items[it].first_tile;
@@ -612,10 +624,12 @@ k_multi_encode(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_
     for (int j = 0; j < kMultiUnroll; ++j) {
       const uint64_t idx = first + (uint64_t)j * kMultiBlock;
       if (idx < nvec) v[j] = ld_stream(src4 + idx);
+      else if (ACC) v[j] = make_uint4(0u, 0u, 0u, 0u);
     }
 #pragma unroll
     for (int j = 0; j < kMultiUnroll; ++j) {
       const uint64_t idx = first + (uint64_t)j * kMultiBlock;
+      if (ACC) m = vec_amax<SRCK>(m, v[j]);
       if (idx < nvec) {
         if constexpr (SRCK == kSrcF32)
           st_stream(reinterpret_cast<uint32_t*>(dst) + idx, encode4_f32<IMPL>(v[j], scale, ctx, idx * VE));
@@ -625,10 +639,14 @@ k_multi_encode(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_
     }
     if (local + 1 == multi_item_tiles<SRCK>(n)) {
       const uint64_t t = nvec * VE + threadIdx.x;
-      if (t < n)
-        dst[t] = (uint8_t)encode_one<IMPL, SRCK>(scaled_bits(load_bits<SRCK>(items[it].src, t), scale), keyed<IMPL>(ctx, t), t);
+      if (t < n) {
+        const uint32_t xb = load_bits<SRCK>(items[it].src, t);
+        if (ACC) mt = umax(mt, xb & 0x7FFFFFFFu);
+        dst[t] = (uint8_t)encode_one<IMPL, SRCK>(scaled_bits(xb, scale), keyed<IMPL>(ctx, t), t);
+      }
     }
   }
+  if (ACC && cur != 0xFFFFFFFFu) block_max_to_global(umax(fold_amax<SRCK>(m), mt), amax_acc + cur);
 }
 
 // ====================================================================================
@@ -797,6 +815,45 @@ hif8_status conv_amax(const void* src, size_t n, float* d_amax, hipStream_t st) 
   return finish_launch();
 }
 
+template <int SRCK, bool ACC>
+void launch_multi_encode(const hif8_cast_item* d_items, uint32_t cnt, uint64_t total_tiles, const float* d_scale2,
+                         uint32_t* amax_acc, uint32_t mode, uint64_t seed, const DevTables& tb, hipStream_t st) {
+  const dim3 g2((unsigned)((total_tiles + kMultiTpwEncode - 1) / kMultiTpwEncode)), blk(kMultiBlock);
+  auto go = [&](auto impl_c) {
+    constexpr int IMPL = decltype(impl_c)::value;
+    hipLaunchKernelGGL((k_multi_encode<IMPL, SRCK, ACC>), g2, blk, 0, st, d_items, cnt, total_tiles, d_scale2, amax_acc, mode,
+                       seed, enc_table_for<IMPL>(tb));
+  };
+  using std::integral_constant;
+  switch (impl_for<SRCK>(mode)) {
+    case IMPL_HR16:
+      if constexpr (SRCK != kSrcF32) go(integral_constant<int, IMPL_HR16>{});
+      break;
+    case IMPL_HR: go(integral_constant<int, IMPL_HR>{}); break;
+    case IMPL_TE: go(integral_constant<int, IMPL_TE>{}); break;
+    case IMPL_SR: go(integral_constant<int, IMPL_SR>{}); break;
+    default: go(integral_constant<int, IMPL_TA_LUT>{}); break;
+  }
+}
+
+// Multi-tensor cast with the scales already on the device (delayed scaling): one launch.
+template <int SRCK>
+hif8_status conv_multi_encode_ds(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
+                                 const float* d_scale2, float* d_amax_acc, uint32_t mode, hipStream_t st) {
+  if (!valid_mode(mode)) return HIF8_ERR_MODE;
+  if (count == 0) return HIF8_OK;
+  if (!d_items || !d_scale2) return HIF8_ERR_NULL;
+  if (count > 0xFFFFFFu) return HIF8_ERR_ARG;
+  DevTables tb;
+  hif8_status s = ensure_init(nullptr, &tb);
+  if (s != HIF8_OK) return s;
+  if (total_tiles == 0) return HIF8_OK;
+  uint32_t* acc = reinterpret_cast<uint32_t*>(d_amax_acc);
+  if (acc) launch_multi_encode<SRCK, true>(d_items, (uint32_t)count, total_tiles, d_scale2, acc, mode, sr_seed(), tb, st);
+  else launch_multi_encode<SRCK, false>(d_items, (uint32_t)count, total_tiles, d_scale2, nullptr, mode, sr_seed(), tb, st);
+  return finish_launch();
+}
+
 template <int SRCK>
 hif8_status conv_multi_cast(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
                             float* d_amax, float* d_scale2, float target, int pow2, uint32_t mode,
@@ -820,27 +877,7 @@ hif8_status conv_multi_cast(const hif8_cast_item* d_items, size_t count, uint64_
   }
   s = launch_scale_from_amax(d_amax, d_scale2, cnt, target, pow2, st);
   if (s != HIF8_OK) return s;
-  if (total_tiles != 0) {
-    const dim3 g2((unsigned)((total_tiles + kMultiTpwEncode - 1) / kMultiTpwEncode)), blk(kMultiBlock);
-    switch (impl_for<SRCK>(mode)) {
-      case IMPL_HR16:
-        if constexpr (SRCK != kSrcF32)
-          hipLaunchKernelGGL((k_multi_encode<IMPL_HR16, SRCK>), g2, blk, 0, st, d_items, cnt, total_tiles, d_scale2, mode, seed, tb.hr16_lut);
-        break;
-      case IMPL_HR:
-        hipLaunchKernelGGL((k_multi_encode<IMPL_HR, SRCK>), g2, blk, 0, st, d_items, cnt, total_tiles, d_scale2, mode, seed, tb.enc_lut);
-        break;
-      case IMPL_TE:
-        hipLaunchKernelGGL((k_multi_encode<IMPL_TE, SRCK>), g2, blk, 0, st, d_items, cnt, total_tiles, d_scale2, mode, seed, tb.enc_lut);
-        break;
-      case IMPL_SR:
-        hipLaunchKernelGGL((k_multi_encode<IMPL_SR, SRCK>), g2, blk, 0, st, d_items, cnt, total_tiles, d_scale2, mode, seed, tb.enc_lut);
-        break;
-      default:
-        hipLaunchKernelGGL((k_multi_encode<IMPL_TA_LUT, SRCK>), g2, blk, 0, st, d_items, cnt, total_tiles, d_scale2, mode, seed, tb.enc_lut);
-        break;
-    }
-  }
+  if (total_tiles != 0) launch_multi_encode<SRCK, false>(d_items, cnt, total_tiles, d_scale2, nullptr, mode, seed, tb, st);
   return finish_launch();
 }
 
@@ -857,4 +894,6 @@ hif8_status conv_multi_cast(const hif8_cast_item* d_items, size_t count, uint64_
   template hif8_status conv_amax<K>(const void*, size_t, float*, hipStream_t);                           \
   template hif8_status conv_multi_cast<K>(const hif8_cast_item*, size_t, uint64_t, float*, float*,       \
                                           float, int, uint32_t, hipStream_t);                            \
+  template hif8_status conv_multi_encode_ds<K>(const hif8_cast_item*, size_t, uint64_t, const float*,    \
+                                               float*, uint32_t, hipStream_t);                           \
   }

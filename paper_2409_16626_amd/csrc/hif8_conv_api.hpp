@@ -27,6 +27,9 @@ template <int SRCK>
 hif8_status conv_multi_cast(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
                             float* d_amax, float* d_scale2, float target, int pow2, uint32_t mode,
                             hipStream_t st);
+template <int SRCK>
+hif8_status conv_multi_encode_ds(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
+                                 const float* d_scale2, float* d_amax_acc, uint32_t mode, hipStream_t st);
 
 // vector units per tile of the multi-tensor kernels (shared with hif8_multi_plan)
 constexpr int kMultiBlock = 512;

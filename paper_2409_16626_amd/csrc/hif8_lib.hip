@@ -336,6 +336,12 @@ hif8_status hif8_scale_from_amax(const float* d_amax, float* d_scale2, float tar
                                     uint32_t mode, hif8_stream_t stream) {                               \
     return conv_multi_cast<K>(d_items, count, total_tiles, d_amax, d_scale2, target, pow2, mode,         \
                               (hipStream_t)stream);                                                      \
+  }                                                                                                      \
+  hif8_status hif8_multi_encode_##SFX##_ds(const hif8_cast_item* d_items, size_t count,                  \
+                                           uint64_t total_tiles, const float* d_scale2,                  \
+                                           float* d_amax_acc, uint32_t mode, hif8_stream_t stream) {     \
+    return conv_multi_encode_ds<K>(d_items, count, total_tiles, d_scale2, d_amax_acc, mode,              \
+                                   (hipStream_t)stream);                                                 \
   }
 
 HIF8_DEFINE_KIND(f32, float, kSrcF32)

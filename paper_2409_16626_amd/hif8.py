@@ -81,6 +81,9 @@ _SIGS = {
     "hif8_fake_quant_bf16_ds": ([_vp, _vp, _vp, _sz, _vp, _vp, _u32, _vp], _i),
     "hif8_multi_plan": ([_vp, _sz, _i, _vp], _i),
     "hif8_multi_cast_bf16": ([_vp, _sz, ctypes.c_uint64, _vp, _vp, _f, _i, _u32, _vp], _i),
+    "hif8_multi_encode_bf16_ds": ([_vp, _sz, ctypes.c_uint64, _vp, _vp, _u32, _vp], _i),
+    "hif8_multi_encode_f32_ds": ([_vp, _sz, ctypes.c_uint64, _vp, _vp, _u32, _vp], _i),
+    "hif8_multi_encode_f16_ds": ([_vp, _sz, ctypes.c_uint64, _vp, _vp, _u32, _vp], _i),
     "hif8_multi_cast_f32": ([_vp, _sz, ctypes.c_uint64, _vp, _vp, _f, _i, _u32, _vp], _i),
     "hif8_scale_from_amax_n": ([_vp, _vp, _sz, _f, _i, _vp], _i),
     "hif8_scale_sweep_f32": ([_vp, _sz, _i, _i, _u32, _vp, _vp], _i),
@@ -321,6 +324,20 @@ def hif8_multi_cast_f32(d_items, count, total_tiles, d_amax, d_scale2, target=MA
                         rounding_mode=RM_TA, stream=None):
     _check(lib.hif8_multi_cast_f32(_ptr(d_items), count, total_tiles, _ptr(d_amax), _ptr(d_scale2), target,
                                    int(pow2), rounding_mode, _stream(stream)))
+
+
+def _def_multi_encode_ds(sfx):
+    fn = getattr(lib, "hif8_multi_encode_%s_ds" % sfx)
+
+    def multi_encode_ds(d_items, count, total_tiles, d_scale2, rounding_mode=RM_TA, stream=None, d_amax_accum=None):
+        _check(fn(_ptr(d_items), count, total_tiles, _ptr(d_scale2), _ptr(d_amax_accum), rounding_mode, _stream(stream)))
+
+    return multi_encode_ds
+
+
+hif8_multi_encode_bf16_ds = _def_multi_encode_ds("bf16")
+hif8_multi_encode_f32_ds = _def_multi_encode_ds("f32")
+hif8_multi_encode_f16_ds = _def_multi_encode_ds("f16")
 
 
 def hif8_scale_from_amax_n(d_amax, d_scale2, count, target=MAX_FINITE, pow2=0, stream=None):

@@ -55,6 +55,10 @@ def test_argument_validation_happens_on_the_host():
     assert L.hif8_gemm_f32(p, p, p, 0, 16, 16, 1.0, 1.0, None) == OK           # empty output: nothing to do
     assert L.hif8_amax_axis_f32(p, 4, 4, 2, p, None) == ARG
     assert L.hif8_encode_axis_bf16(p, p, 4, 4, 0, None, 0, None) == NULL
+    assert L.hif8_multi_encode_bf16_ds(p, 3, 1, None, None, 0, None) == NULL
+    assert L.hif8_multi_encode_f32_ds(None, 3, 1, p, None, 0, None) == NULL
+    assert L.hif8_multi_encode_f16_ds(p, 3, 1, p, None, 9, None) == MODE
+    assert L.hif8_multi_encode_f16_ds(None, 0, 0, None, None, 0, None) == OK
     assert L.hif8_quantize_rows_bf16(p, p, 4, 8, 32768.0, 1, 0, None, p, None) == NULL
     assert L.hif8_quantize_rows_bf16(p, p, 4, 8, 32768.0, 1, 0, p, None, None) == NULL
     assert L.hif8_quantize_rows_f32(None, p, 4, 8, 32768.0, 1, 0, p, p, None) == NULL

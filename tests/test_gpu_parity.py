@@ -351,6 +351,45 @@ def test_multi_tensor_cast_matches_per_tensor_oracle(h, mode, pow2):
             assert not cg[o + m:o + pad].any()
 
 
+@pytest.mark.parametrize("mode", [TA, HR, orc.RM_SR | SAT])
+def test_multi_tensor_encode_with_device_scales_and_amax_accumulation(h, mode):
+    """Delayed scaling over a tensor list in one launch: codes under the given scales bit for bit the
+    oracle's, accumulators = max(previous content, amax of the tensor), untouched without the pointer."""
+    rng = np.random.default_rng(43)
+    sizes = [8192 * 3, 0, 1, 7, 8, 8200, 12345, 8192, 100003, 16, 0, 65536 + 24, 3 * 8192 * 8 + 5]
+    for kind in ("bf16", "f32", "f16"):
+        offs, total = [], 0
+        for m in sizes:
+            offs.append(total)
+            total += (m + 15) // 16 * 16
+        xf = torch.from_numpy((rng.standard_normal(total) * np.exp2(rng.uniform(-12, 3, total))).astype(np.float32)).to(dev())
+        x = {"bf16": xf.to(torch.bfloat16), "f16": xf.to(torch.float16), "f32": xf}[kind]
+        codes = torch.zeros(total, dtype=torch.uint8, device=dev())
+        items = [(x[o:o + m].data_ptr() if m else 0, codes[o:o + m].data_ptr() if m else 0, m) for o, m in zip(offs, sizes)]
+        d_items, count, tiles = h.hif8_multi_plan(items, src_is_16bit=kind != "f32")
+        scales = np.exp2(rng.integers(-3, 9, count)).astype(np.float32) * np.float32(1.25)
+        sc = torch.from_numpy(np.stack([scales, np.float32(1.0) / scales], 1).copy()).to(dev())
+        prev = np.where(np.arange(count) % 3 == 0, np.float32(1e9), np.float32(0.0)).astype(np.float32)   # some already above
+        acc = torch.from_numpy(prev.copy()).to(dev())
+        fn = getattr(h, "hif8_multi_encode_%s_ds" % kind)
+        fn(d_items, count, tiles, sc, mode, d_amax_accum=acc)
+        torch.cuda.synchronize()
+        xn = x.cpu().numpy() if kind == "f32" else x.view(torch.int16).cpu().numpy().view(np.uint16)
+        enc = {"bf16": orc.encode_bf16, "f16": orc.encode_f16, "f32": orc.encode_f32}[kind]
+        amx = {"bf16": orc.amax_bf16, "f16": orc.amax_f16, "f32": orc.amax_f32}[kind]
+        cg, ag = codes.cpu().numpy(), acc.cpu().numpy()
+        for i, (o, m) in enumerate(zip(offs, sizes)):
+            part = xn[o:o + m]
+            assert_same_bytes(cg[o:o + m], enc(part, scales[i], mode), "multi ds item %d (n=%d, %s)" % (i, m, kind))
+            assert ag[i] == max(prev[i], np.float32(amx(part))), (i, m, kind)
+        codes2 = torch.zeros_like(codes)
+        items2 = [(x[o:o + m].data_ptr() if m else 0, codes2[o:o + m].data_ptr() if m else 0, m) for o, m in zip(offs, sizes)]
+        d_items2, count2, tiles2 = h.hif8_multi_plan(items2, src_is_16bit=kind != "f32")
+        fn(d_items2, count2, tiles2, sc, mode)                      # no accumulator
+        torch.cuda.synchronize()
+        assert torch.equal(codes, codes2)
+
+
 # ------------------------------------------------------------------ amax semantics, tuning, graphs
 def test_amax_special_values(h):
     x = torch.randn(100003, device=dev())
