@@ -40,6 +40,13 @@ def test_cast_and_gemm_sequence_replays_exactly(h):
             self.xe = torch.empty(M, ld, dtype=torch.bfloat16, device=dev())
             self.we = torch.empty(N, ld, dtype=torch.bfloat16, device=dev())
             self.out = torch.empty(M, N, dtype=torch.float32, device=dev())
+            self.ram = torch.zeros(N, dtype=torch.float32, device=dev())
+            self.rsc = torch.zeros(N, 2, dtype=torch.float32, device=dev())
+            self.rc = torch.empty(N, K, dtype=torch.uint8, device=dev())
+            self.acc = torch.zeros(2, dtype=torch.float32, device=dev())
+            self.mc = torch.empty(M * K + N * K, dtype=torch.uint8, device=dev())
+            self.items = h.hif8_multi_plan([(x.data_ptr(), self.mc.data_ptr(), M * K),
+                                            (w.data_ptr(), self.mc[M * K:].data_ptr(), N * K)], src_is_16bit=True)
 
     def sequence(b):
         b.amax.zero_()                                                     # a fill kernel, not a memset node
@@ -51,6 +58,10 @@ def test_cast_and_gemm_sequence_replays_exactly(h):
         h.hif8_expand_bf16(b.xc, M, K, b.xe, ld)
         h.hif8_expand_bf16(b.wc, N, K, b.we, ld)
         h.hif8_gemm_expanded_f32(b.xe, b.we, b.out, M, N, K, ld, 1.0, 1.0)
+        h.hif8_quantize_rows_bf16(w, b.rc, N, K, b.ram, b.rsc, h.MAX_FINITE, 1, h.RM_TA)      # per-row scaling in one pass
+        b.acc.zero_()
+        d_items, count, tiles = b.items
+        h.hif8_multi_encode_bf16_ds(d_items, count, tiles, b.scale, h.RM_TA, d_amax_accum=b.acc)  # both tensors, one launch
 
     eager, graphed = Bufs(), Bufs()
     x.copy_(torch.randn(M, K, generator=g, device=dev()).to(torch.bfloat16))
@@ -69,7 +80,7 @@ def test_cast_and_gemm_sequence_replays_exactly(h):
         graph.replay()
         sequence(eager)
         torch.cuda.synchronize()
-        for name in ("amax", "scale", "xc", "wc", "out"):
+        for name in ("amax", "scale", "xc", "wc", "out", "ram", "rsc", "rc", "acc", "mc"):
             assert torch.equal(getattr(graphed, name), getattr(eager, name)), (rep, name)
         assert torch.equal(graphed.xq.view(torch.int16), eager.xq.view(torch.int16)), rep
         assert torch.equal(graphed.xe.view(torch.int16), eager.xe.view(torch.int16)), rep
@@ -79,3 +90,5 @@ def test_cast_and_gemm_sequence_replays_exactly(h):
         w_s = orc.scale_from_amax(w_am, 32768.0, True)
         assert graphed.amax[0].item() == float(w_am) and graphed.scale[0, 0].item() == float(w_s)
         assert np.array_equal(graphed.xc.cpu().numpy().reshape(-1), orc.encode_bf16(xn.reshape(-1), w_s, orc.RM_TA))
+        assert np.array_equal(graphed.mc[:M * K].cpu().numpy(), orc.encode_bf16(xn.reshape(-1), w_s, orc.RM_TA))
+        assert graphed.acc[0].item() == float(w_am)
