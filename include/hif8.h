@@ -360,7 +360,9 @@ hif8_status hif8_quantize_rows_f16(const uint16_t* src, uint8_t* dst, size_t row
  *
  * The state lives in caller-owned device memory: d_amax (count floats, the accumulators that
  * the _ds casts fill through d_amax_accum_or_null, or hif8_amax_* / hif8_multi_cast_* write)
- * and d_scale2 (count {scale, 1/scale} pairs, read by the _ds casts).  The struct itself is
+ * and d_scale2 (count {scale, 1/scale} pairs, read by the _ds casts).  Both arrays have the layout
+ * that hif8_multi_encode_*_ds takes, so all tensors of the state can be cast in one launch (pass
+ * d_amax as its accumulators on gathering iterations, null otherwise).  The struct itself is
  * host memory owned by the caller; the library keeps no reference to it.
  *   hif8_pts_init           scales = 1, accumulators = 0, iteration = 0 (one small launch);
  *                           target must be a power of two (HiF8's largest finite value 2^15, or

@@ -101,3 +101,44 @@ def test_pts_delayed_scaling_over_iterations():
         assert am.cpu().tolist() == [0.0] * count or not collects
     assert st.iteration == 32
     assert ref.scale[2] != 1.0 and ref.scale[0] != 1.0          # the drifting tensors moved their scales
+
+
+@pytest.mark.gpu
+def test_pts_with_one_multi_tensor_cast_per_iteration():
+    """The same training loop with all tensors of the state cast by one hif8_multi_encode_bf16_ds launch
+    per iteration (the state's arrays are that call's scale and accumulator arrays)."""
+    import torch
+    from oracle import hif8_oracle as orc
+    from paper_2409_16626_amd import hif8
+    from gpu_util import assert_same_bytes, bf16_bits, dev
+    hif8.hif8_init()
+    count, n = 3, (1 << 16) + 5
+    pad = (n + 15) // 16 * 16
+    am = torch.zeros(count, dtype=torch.float32, device=dev())
+    sc = torch.zeros(count, 2, dtype=torch.float32, device=dev())
+    st = hif8.PtsState()
+    hif8.hif8_pts_init(st, am, sc, count, 10, 16384.0)
+    ref = po.PTS(count, 10, 16384.0)
+    g = torch.Generator(device=dev()).manual_seed(10)
+    base = torch.randn(count, pad, generator=g, device=dev())
+    x = torch.zeros(count, pad, dtype=torch.bfloat16, device=dev())
+    codes = torch.zeros(count, pad, dtype=torch.uint8, device=dev())
+    d_items, cnt, tiles = hif8.hif8_multi_plan([(x[t].data_ptr(), codes[t].data_ptr(), n) for t in range(count)], src_is_16bit=True)
+    for it in range(24):
+        gains = torch.tensor([2.0 ** (it / 3.0), 1e-3 * (1 + it), 0.0 if it < 12 else 7.0], device=dev())
+        x.copy_((base * gains[:, None]).to(torch.bfloat16))
+        collects = bool(hif8.hif8_pts_collects(st))
+        assert collects == ref.collects()
+        hif8.hif8_multi_encode_bf16_ds(d_items, cnt, tiles, sc, orc.RM_TA, d_amax_accum=am if collects else None)
+        torch.cuda.synchronize()
+        xn, cn = bf16_bits(x), codes.cpu().numpy()
+        amaxes = []
+        for t in range(count):
+            assert_same_bytes(cn[t, :n], orc.encode_bf16(xn[t, :n], np.float32(ref.scale[t]), orc.RM_TA),
+                              "iteration %d tensor %d" % (it, t))
+            amaxes.append(float(orc.amax_bf16(xn[t, :n])))
+        hif8.hif8_pts_end_iteration(st)
+        want = ref.end_iteration(amaxes if collects else None)
+        torch.cuda.synchronize()
+        assert sc.cpu().numpy()[:, 0].tolist() == want, (it, want)
+    assert ref.scale[2] != 1.0 and ref.scale[0] != 1.0
