@@ -335,3 +335,41 @@ def test_gemm_benchmark_shapes_sampled_outputs(h, M, N, K):
         got = out[torch.from_numpy(rows).to(dev())][:, torch.from_numpy(cols).to(dev())].cpu().numpy()
         diff, bound = check(got, sa, sb, 4.0, 0.5)
         assert np.mean(diff) <= 0.05 * K * 2.0 ** -23 * np.mean(bound)
+
+
+def test_ragged_round_shape_all_outputs_and_sqerr(h):
+    """A shape whose 256 x 256 tiles leave a ragged last round (two launches: large tiles, then small tiles
+    over the remaining columns), with a short K: every output of both kernels against the fp64 product of the
+    oracle-decoded operands (a torch matmul, not this library), and the squared-error epilogues against the error
+    of those outputs."""
+    M, N, K = 8192, 11008, 64
+    g = torch.Generator(device=dev()).manual_seed(77)
+    ca = torch.randint(8, 0x50, (M, K), generator=g, dtype=torch.int32, device=dev()).to(torch.uint8)
+    cb = torch.randint(8, 0x50, (N, K), generator=g, dtype=torch.int32, device=dev()).to(torch.uint8)
+    h.hif8_gemm_set_variant(0)
+    ld = h.hif8_expanded_ld(K)
+    xa = torch.empty(M, ld, dtype=torch.bfloat16, device=dev())
+    xb = torch.empty(N, ld, dtype=torch.bfloat16, device=dev())
+    h.hif8_expand_bf16(ca, M, K, xa, ld)
+    h.hif8_expand_bf16(cb, N, K, xb, ld)
+    out_x = torch.full((M, N), float("nan"), dtype=torch.float32, device=dev())
+    out_c = torch.full((M, N), float("nan"), dtype=torch.float32, device=dev())
+    h.hif8_gemm_expanded_f32(xa, xb, out_x, M, N, K, ld, 1.0, 1.0)
+    h.hif8_gemm_f32(ca, cb, out_c, M, N, K, 1.0, 1.0)
+    torch.cuda.synchronize()
+    # values of codes 0x08..0x4F lie in a few binades around 1: K = 64 products sum exactly enough for fp64 on the GPU
+    # to serve as the exact product of the decoded operands (decode is pinned against the oracle elsewhere)
+    dec = torch.from_numpy(orc.decode_f32(np.arange(256, dtype=np.uint8), 1.0).astype(np.float64)).to(dev())
+    exact = dec[ca.long()] @ dec[cb.long()].T
+    bound = (dec[ca.long()].abs() @ dec[cb.long()].abs().T) * (K * 2.0 ** -23)
+    for out in (out_x, out_c):
+        assert not bool(torch.isnan(out).any())
+        assert bool(((out.double() - exact).abs() <= bound).all())
+    ref = torch.randn(M, N, generator=g, device=dev())
+    for out, call in ((out_x, lambda e: h.hif8_gemm_expanded_sqerr(xa, xb, ref, M, N, K, ld, 1.0, 1.0, e)),
+                      (out_c, lambda e: h.hif8_gemm_sqerr(ca, cb, ref, M, N, K, 1.0, 1.0, e))):
+        err = torch.zeros(1, dtype=torch.float64, device=dev())
+        call(err)
+        torch.cuda.synchronize()
+        want = float(((out.double() - ref.double()) ** 2).sum())
+        assert abs(err.item() - want) <= 1e-10 * want
