@@ -10,6 +10,7 @@
 #define __forceinline__ inline
 static inline int __clz(int x) { return x == 0 ? 32 : __builtin_clz((unsigned)x); }
 #include "../../paper_2409_16626_amd/csrc/hif8_device.hpp"
+#include "../../paper_2409_16626_amd/csrc/hif8_gemm_split.hpp"
 
 extern "C" {
 // per-tensor scale from an amax (the arithmetic of the scale kernels)
@@ -66,5 +67,10 @@ void devfn_decode_bits(const uint8_t* codes, uint32_t* dst, size_t n) {
 }
 void devfn_narrow_bf16(const uint32_t* bits, uint16_t* dst, size_t n) {
   for (size_t i = 0; i < n; ++i) dst[i] = (uint16_t)hif8dev::narrow_bf16(bits[i]);
+}
+// host-side launch planning of the GEMM kernels: returns the split column, or 0 for a single launch
+uint32_t devfn_ragged_round_split(size_t M, size_t N, size_t cus) {
+  uint32_t split = 0;
+  return hif8gemm::ragged_round_split(M, N, cus, &split) ? split : 0u;
 }
 }

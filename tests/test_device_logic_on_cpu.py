@@ -148,3 +148,33 @@ def test_device_scale_from_amax_logic(dev):
                 assert np.all((b[normal] & 0x7FFFFF) == 0)
                 sub = b[~normal]
                 assert np.all((sub & (sub - 1)) == 0)
+
+
+def test_gemm_ragged_round_split_plan(dev):
+    """Host-side planning of the GEMM launches: a second launch of small tiles only where the last round of
+    256 x 256 tiles would be at most half full and whole tile columns fill the complete rounds; the split
+    column is a multiple of 256 inside the matrix and the large tiles left of it fill whole rounds or less."""
+    dev.devfn_ragged_round_split.restype = ctypes.c_uint32
+    dev.devfn_ragged_round_split.argtypes = [ctypes.c_size_t, ctypes.c_size_t, ctypes.c_size_t]
+    f = dev.devfn_ragged_round_split
+    assert f(8192, 11008, 256) == 40 * 256            # 32 x 43 tiles = 5.375 rounds: 40 tile columns = 5 rounds exactly
+    assert f(8192, 8192, 256) == 0                    # 1024 tiles = 4 whole rounds
+    assert f(4096, 4096, 256) == 0                    # one round exactly
+    assert f(2048, 2048, 256) == 0                    # fewer tiles than compute units
+    assert f(8192, 11008, 0) == 0
+    assert f(8192, 12288, 256) == 0                   # 6 rounds exactly
+    assert f(8192, 12800, 256) == 48 * 256            # 32 x 50 = 6.25 rounds
+    assert f(8192, 14336, 256) == 0                   # 7 rounds exactly
+    assert f(8192, 15000, 256) == 56 * 256            # 32 x 59 = 7.4 rounds: 3 tile columns left = 96 tiles
+    assert f(8192, 16000, 256) == 0                   # 32 x 63 = 7.9 rounds: the last round is nearly full
+    rng = np.random.default_rng(3)
+    for _ in range(2000):
+        M, N, cus = int(rng.integers(1, 40000)), int(rng.integers(1, 40000)), int(rng.choice([64, 120, 256, 304]))
+        s = f(M, N, cus)
+        tm, tn = (M + 255) // 256, (N + 255) // 256
+        if s:
+            assert s % 256 == 0 and 0 < s < N
+            big = tm * (s // 256)
+            assert big <= (tm * tn // cus) * cus                  # the large tiles fit the complete rounds
+            assert (tn - s // 256) * tm * 2 <= cus                # what is left is at most half a round of large tiles
+            assert tm * tn > cus and (tm * tn) % cus != 0
