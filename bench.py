@@ -378,7 +378,7 @@ def main():
         g = workloads.gradient_f32(1 << 30, dev)
         gc = torch.empty(g.numel(), dtype=torch.uint8, device=dev)
         for name, mode in (("TA", hif8.RM_TA), ("HR", hif8.RM_HR)):
-            w_ms, e_ms = timed(lambda i: hif8.hif8_encode_f32(g, gc, g.numel(), 1.0, mode), 10, 2)
+            w_ms, e_ms = timed(lambda i: hif8.hif8_encode_f32(g, gc, g.numel(), 1.0, mode), 20, 20)
             extra["C4 encode_f32 %s 2^30 (5 B/elem)" % name] = rate(5 * g.numel(), e_ms)
         del g, gc
         torch.cuda.empty_cache()

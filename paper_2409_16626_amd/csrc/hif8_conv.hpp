@@ -706,8 +706,10 @@ hif8_status conv_encode(const void* src, uint8_t* dst, size_t n, float scale, co
   }
   const size_t nvec = n >> vec_shift<SRCK>();
   const int impl = impl_for<SRCK>(mode);
-  Shape shape = shape_for(SRCK != kSrcF32 ? FAM_ENC16 : (impl == IMPL_HR ? FAM_ENC32_HR : FAM_ENC32_TA));
-  if (impl == IMPL_TE || impl == IMPL_SR) shape.unroll = 2;
+  // TE and standard SR stage larger tables and are built for one unroll factor: they keep the 512-lane shape
+  const bool one_unroll = impl == IMPL_TE || impl == IMPL_SR;
+  Shape shape = shape_for((SRCK != kSrcF32 || one_unroll) ? FAM_ENC16 : (impl == IMPL_HR ? FAM_ENC32_HR : FAM_ENC32_TA));
+  if (one_unroll) shape.unroll = 2;
   Walk walk;
   const dim3 grid(grid_for(nvec, cus, shape, &walk)), block(shape.block);
   dispatch_impl<SRCK>(impl, shape.unroll, [&](auto impl_c, auto u_c) {

@@ -92,10 +92,12 @@ thread_local int t_last_hip_error = 0;
 
 // Defaults from a sweep on MI355X under sustained load (hundreds of back-to-back launches on
 // 64 Mi-element tensors; short bursts rank the shapes differently): one-shot grids of
-// 512-lane workgroups with 16-32 KiB of source per staged table win for the read+write
+// 256- or 512-lane workgroups with 16-32 KiB of source per staged table win for the read+write
 // kernels, a persistent grid of one 1024-lane workgroup per CU wins for the read-only reduction.
+// FP32 TA encode: 256 lanes x 4 loads, one tile per workgroup (16 KiB of source) -- 6.48 TB/s on 2^26
+// and 6.5 TB/s on 2^30 elements against 6.39 / 6.2 TB/s for 512 lanes x 2 loads x 2 tiles.
 const Shape kDefaultShape[FAM_COUNT] = {
-    {512, 2, 2, 4},   // FP32 encode, TA
+    {256, 4, 1, 4},   // FP32 encode, TA
     {512, 4, 1, 4},   // FP32 encode, HR
     {512, 2, 2, 4},   // 16-bit encode
     {512, 2, 2, 4},   // fake-quant
