@@ -238,7 +238,7 @@ using namespace hif8conv;
 
 extern "C" {
 
-int hif8_version(void) { return 300; }
+int hif8_version(void) { return 400; }
 int hif8_last_hip_error(void) { return t_last_hip_error; }
 hif8_status hif8_init(void) { return ensure_init(nullptr, nullptr); }
 
