@@ -74,6 +74,8 @@ def main():
                     help="profiling mode: only the simulated HiF8 GEMM rows (25 launches of 8192^3), no headline")
     ap.add_argument("--sweep-only", action="store_true",
                     help="profiling mode: only the 10-scale sweep over the C3 tensor (25 launches), no headline")
+    ap.add_argument("--per-channel-only", action="store_true",
+                    help="profiling mode: only the per-channel casts of a [11008, 4096] BF16 matrix (25 rounds), no headline")
     ap.add_argument("--tune", type=str, default="", help="block,wg_per_cu,unroll,ta_impl,tiles_per_wg,amax_nt (prefix allowed)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -112,6 +114,32 @@ def main():
         res["gemm_expanded_bf16 M=N=K=8192"] = {"ms": round(e_ms, 4), "TFLOP/s": round(fl / (e_ms * 1e-3) / 1e12, 1),
                                                 "frac_of_2.5PFLOPs_bf16": round(fl / (e_ms * 1e-3) / 2.5e15, 4)}
         print(json.dumps(res), flush=True)
+        return
+
+    if args.per_channel_only:
+        rows_c, cols_c, Rw = 11008, 4096, 3
+        g = torch.Generator(device=dev).manual_seed(11008)
+        wm = [(torch.randn(rows_c, cols_c, generator=g, device=dev) * 0.02).to(torch.bfloat16) for _ in range(Rw)]   # 270 MB: more than the last-level cache
+        cd = torch.empty(rows_c, cols_c, dtype=torch.uint8, device=dev)
+        out = {}
+        for axis in (0, 1):
+            nch = rows_c if axis == 0 else cols_c
+            am_c = torch.zeros(nch, dtype=torch.float32, device=dev)
+            sc_c = torch.zeros(nch, 2, dtype=torch.float32, device=dev)
+
+            def three(i):
+                hif8.hif8_amax_axis_bf16(wm[i % Rw], rows_c, cols_c, axis, am_c)
+                hif8.hif8_scale_from_amax_n(am_c, sc_c, nch, hif8.MAX_FINITE, 1)
+                hif8.hif8_encode_axis_bf16(wm[i % Rw], cd, rows_c, cols_c, axis, sc_c, hif8.RM_TA)
+
+            w_ms, e_ms = timed(three, 20, 5)
+            out["axis %d, three launches" % axis] = round(e_ms * 1e3, 2)
+        am_r = torch.zeros(rows_c, dtype=torch.float32, device=dev)
+        sc_r = torch.zeros(rows_c, 2, dtype=torch.float32, device=dev)
+        w_ms, e_ms = timed(lambda i: hif8.hif8_quantize_rows_bf16(wm[i % Rw], cd, rows_c, cols_c, am_r, sc_r, hif8.MAX_FINITE, 1,
+                                                                  hif8.RM_TA), 20, 5)
+        out["rows in one pass (hif8_quantize_rows_bf16)"] = round(e_ms * 1e3, 2)
+        print(json.dumps({"per-channel casts of a [11008, 4096] BF16 matrix, us per call sequence": out}), flush=True)
         return
 
     if args.sweep_only:
