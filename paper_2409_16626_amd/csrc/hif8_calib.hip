@@ -174,6 +174,8 @@ constexpr int kAmaxColsWaves = 8;   // axis 1 amax: wavefronts per workgroup
 template <int SRCK>
 __global__ void __launch_bounds__(kAxBlock)
 k_amax_rows(const void* __restrict__ src, uint32_t cols_vec, uint32_t chunks, uint32_t* __restrict__ out) {
+  // chunks == 1: the workgroup owns the whole row and stores its maximum (the array needs no clearing);
+  // otherwise the chunks of a row meet in an atomic max on the cleared array
   const uint32_t row = blockIdx.x / chunks, chunk = blockIdx.x - row * chunks;
   const uint4* __restrict__ p = reinterpret_cast<const uint4*>(src) + (size_t)row * cols_vec;
   uint32_t m = 0;
@@ -182,7 +184,12 @@ k_amax_rows(const void* __restrict__ src, uint32_t cols_vec, uint32_t chunks, ui
     const uint32_t c = (chunk * kAxUnroll + j) * kAxBlock + threadIdx.x;
     if (c < cols_vec) m = vec_amax<SRCK>(m, ld_stream(p + c));
   }
-  block_max_to_global<false>(fold_amax<SRCK>(m), out + row);  // a row has few chunks: no contention to avoid
+  if (chunks == 1u) {
+    const uint32_t r = block_max_thread0(fold_amax<SRCK>(m));
+    if (threadIdx.x == 0u) out[row] = r;
+  } else {
+    block_max_to_global<false>(fold_amax<SRCK>(m), out + row);  // a row has few chunks: no contention to avoid
+  }
 }
 
 // columns: the wavefronts of a workgroup share a strip of 64 column vectors and take every
@@ -622,8 +629,11 @@ hif8_status amax_axis(const void* src, size_t rows, size_t cols, int axis, float
   AxisPlan p;
   if (!plan_axis<SRCK>(rows, cols, cus, aligned_to(src, 16), &p)) return HIF8_ERR_ARG;
   uint32_t* out = reinterpret_cast<uint32_t*>(d_amax);
-  s = launch_fill_u32(out, 0u, (uint32_t)nch, st);
-  if (s != HIF8_OK || rows * cols == 0) return s;
+  const bool stores = p.fast && axis == 0 && p.chunks == 1 && rows * cols != 0;  // k_amax_rows writes every row itself
+  if (!stores) {
+    s = launch_fill_u32(out, 0u, (uint32_t)nch, st);
+    if (s != HIF8_OK || rows * cols == 0) return s;
+  }
   if (!p.fast) {
     hipLaunchKernelGGL(k_amax_axis_elem<SRCK>, dim3(grid_elem(rows * cols, cus)), dim3(256), 0, st, src, rows, cols, axis, out);
   } else if (axis == 0) {

@@ -100,6 +100,21 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
   return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
+// Workgroup maximum of m, valid in thread 0.  Every lane of the workgroup must call it (it contains a barrier).
+__device__ __forceinline__ uint32_t block_max_thread0(uint32_t m) {
+  __shared__ uint32_t wave_m[16];
+  m = wave_max_u32(m);
+  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  if (lane == 0) wave_m[wave] = m;
+  __syncthreads();
+  uint32_t r = 0;
+  if (threadIdx.x == 0) {
+    const uint32_t nw = (blockDim.x + 63u) >> 6;
+    r = wave_m[0];
+    for (uint32_t w = 1; w < nw; ++w) r = umax(r, wave_m[w]);
+  }
+  return r;
+}
 // Workgroup maximum of m, then at most one atomic max into *out: it is skipped when the value read from
 // *out just before is already as large.  Atomics of thousands of workgroups on one address are served one
 // after the other at the L2 (measured: about 6 ns each -- a BF16 cast of 2^26 elements that accumulates the
@@ -109,15 +124,8 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
 // Every lane of the workgroup must call it (it contains a barrier).
 template <bool CHECK = true>
 __device__ __forceinline__ void block_max_to_global(uint32_t m, uint32_t* out) {
-  __shared__ uint32_t wave_m[16];
-  m = wave_max_u32(m);
-  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-  if (lane == 0) wave_m[wave] = m;
-  __syncthreads();
+  const uint32_t r = block_max_thread0(m);
   if (threadIdx.x == 0) {
-    const uint32_t nw = (blockDim.x + 63u) >> 6;
-    uint32_t r = wave_m[0];
-    for (uint32_t w = 1; w < nw; ++w) r = umax(r, wave_m[w]);
     if (CHECK ? r > __hip_atomic_load(out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : r != 0u) atomicMax(out, r);
   }
 }
