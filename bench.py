@@ -293,6 +293,11 @@ def main():
         w_ms, e_ms = timed(c3, K, W)
         extra["C3 amax+scale+fake_quant_bf16 (5 B/elem primary)"] = rate(5 * m, e_ms)
         extra["C3 amax+scale+fake_quant_bf16 (7 B/elem with amax pass)"] = rate(7 * m, e_ms)
+        qws = torch.empty(hif8.hif8_quantize_workspace_bytes(), dtype=torch.uint8, device=dev)
+        w_ms, e_ms = timed(lambda i: hif8.hif8_quantize_tensor_bf16(acts[i % R], fq[i % R], cds[i % R], m, am, sc, qws,
+                                                                    hif8.MAX_FINITE, 0, hif8.RM_TA), K, W)
+        extra["C3 hif8_quantize_tensor_bf16: amax+scale+fake_quant in one call, 2 launches (5 B/elem primary)"] = rate(5 * m, e_ms)
+        extra["C3 hif8_quantize_tensor_bf16 (7 B/elem with amax pass)"] = rate(7 * m, e_ms)
         w_ms, e_ms = timed(lambda i: hif8.hif8_fake_quant_bf16_ds(acts[i % R], fq[i % R], cds[i % R], m, sc, hif8.RM_TA), K, W)
         extra["fake_quant_bf16 alone (5 B/elem)"] = rate(5 * m, e_ms)
         # the paper's delayed scaling (Sec. 5): the cast uses the scale on the device and accumulates the amax
@@ -429,7 +434,12 @@ def main():
         extra["C5 per-tensor calls, 225 x (amax, scale, encode_bf16) (3 B/elem primary)"] = rate(3 * tot, e_ms)
         extra["C5 per-tensor calls (5 B/elem with amax pass)"] = rate(5 * tot, e_ms)
         items = [(ap + 2 * off, cp + off, cnt) for _, off, cnt in index]
-        d_items, count, tiles = hif8.hif8_multi_plan(items, src_is_16bit=True)
+        plan = hif8.hif8_multi_plan(items, src_is_16bit=True)
+        d_items, count, tiles = plan
+        w_ms, e_ms = timed(lambda i: hif8.hif8_multi_cast_bf16(d_items, count, tiles, ams, scs, hif8.MAX_FINITE, 0, hif8.RM_TA,
+                                                               host_items=plan.host_items), 5, 1)
+        extra["C5 multi-tensor cast, group-wise (amax of a group while the previous one is cast) (3 B/elem primary)"] = rate(3 * tot, e_ms)
+        extra["C5 multi-tensor cast, group-wise (5 B/elem with amax pass)"] = rate(5 * tot, e_ms)
         w_ms, e_ms = timed(lambda i: hif8.hif8_multi_cast_bf16(d_items, count, tiles, ams, scs, hif8.MAX_FINITE, 0, hif8.RM_TA), 5, 1)
         extra["C5 multi-tensor cast, 4 launches (3 B/elem primary)"] = rate(3 * tot, e_ms)
         extra["C5 multi-tensor cast, 4 launches (5 B/elem with amax pass)"] = rate(5 * tot, e_ms)

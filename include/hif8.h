@@ -101,18 +101,30 @@ int hif8_last_hip_error(void);
 hif8_status hif8_init(void);
 
 /*
- * Seed of the threshold generator of HIF8_RM_SR (process-wide; default 0).  A call uses the
- * seed in effect when it is enqueued.  The 32-bit threshold of element i (index within the
- * tensor of the call) is the 32-bit MurmurHash3 finaliser
- *     fmix(x): x ^= x >> 16; x *= 0x85EBCA6B; x ^= x >> 13; x *= 0xC2B2AE35; x ^= x >> 16
- * over the low index word and a key that is constant over 2^32 consecutive elements:
- *     key = fmix( hi32(seed) + hi32(i) * 0x9E3779B9 ) ^ lo32(seed),    t = fmix( lo32(i) ^ key )
- * so results are reproducible and independent of the launch shape.  Sec. 3.2 notes that
- * standard SR needs a random number per element; a counter-based hash supplies it here.
+ * Threshold generator of HIF8_RM_SR.  Sec. 3.2 asks for one uniform random number per element and
+ * names no source; a counter-based hash supplies it here, so results are reproducible and
+ * independent of the launch shape.  The 32-bit threshold of the element with index i in the
+ * threshold stream of a 64-bit seed:
+ *     z  = seed + 0x9E3779B97F4A7C15 * (hi32(i) + 1)                         (mod 2^64)
+ *     z  = (z ^ z >> 30) * 0xBF58476D1CE4E5B9;  z = (z ^ z >> 27) * 0x94D049BB133111EB;  z ^= z >> 31
+ *     k1 = lo32(z), k2 = hi32(z)           (splitmix64's output function; constant over 2^32 elements)
+ *     x  = lo32(i) ^ k1;  x ^= x >> 16;  x *= 0x85EBCA6B;  x += k2;  x ^= x >> 13;  x *= 0xC2B2AE35;
+ *     t  = x ^ x >> 16                     (MurmurHash3's 32-bit finaliser, keyed at its input and middle)
+ * The whole seed enters non-linearly: two seeds give two different functions of the index, not one
+ * sequence in another order.
+ *   hif8_set_sr_seed    process-wide default seed (default 0); a call without a seed argument uses
+ *                       the value in effect when it is enqueued, with index base 0
+ *   hif8_sr_threshold   host-side evaluation of t
+ *   *_sr entry points   (below) take the seed and the index base of the call explicitly:
+ *                       element j of the call draws t(seed, index_base + j).  Casting the tensors
+ *                       of one training step with one seed and consecutive index ranges (or one
+ *                       seed per tensor) keeps their thresholds independent; a slice of a tensor
+ *                       cast with its offset as index base gets the thresholds it has inside the
+ *                       whole tensor.
  */
 hif8_status hif8_set_sr_seed(uint64_t seed);
 uint64_t hif8_get_sr_seed(void);
-uint32_t hif8_sr_threshold(uint64_t seed, uint64_t index); /* host-side evaluation of t */
+uint32_t hif8_sr_threshold(uint64_t seed, uint64_t index);
 
 /*
  * Per-tensor amax (Sec. 5, per-tensor scaling): *d_amax = max_i |src[i]|.
@@ -214,9 +226,68 @@ hif8_status hif8_fake_quant_f16_ds(const uint16_t* src, uint16_t* dst, uint8_t* 
                                    uint32_t rounding_mode, hif8_stream_t stream);
 
 /*
- * Multi-tensor cast: per-tensor amax, scale and encode for a whole list of tensors in four
- * launches (clear, amax, scale, encode) instead of four per tensor -- the per-tensor scaling
- * recipe of Sec. 5 applied to every weight (or activation) tensor of a model at once.
+ * Casts with an explicit threshold stream for HIF8_RM_SR (Sec. 3.2: one random number per element):
+ * hif8_encode_* / hif8_fake_quant_* with the seed and the index base of this call as arguments
+ * instead of the process-wide seed (see hif8_set_sr_seed).  Any rounding_mode is accepted; only
+ * HIF8_RM_SR looks at the two values.  index_base + n must not exceed 2^64.
+ */
+hif8_status hif8_encode_f32_sr(const float* src, uint8_t* dst, size_t n, float scale,
+                               uint32_t rounding_mode, uint64_t seed, uint64_t index_base,
+                               hif8_stream_t stream);
+hif8_status hif8_encode_bf16_sr(const uint16_t* src, uint8_t* dst, size_t n, float scale,
+                                uint32_t rounding_mode, uint64_t seed, uint64_t index_base,
+                                hif8_stream_t stream);
+hif8_status hif8_encode_f16_sr(const uint16_t* src, uint8_t* dst, size_t n, float scale,
+                               uint32_t rounding_mode, uint64_t seed, uint64_t index_base,
+                               hif8_stream_t stream);
+hif8_status hif8_fake_quant_f32_sr(const float* src, float* dst, uint8_t* codes_or_null, size_t n,
+                                   float scale, uint32_t rounding_mode, uint64_t seed,
+                                   uint64_t index_base, hif8_stream_t stream);
+hif8_status hif8_fake_quant_bf16_sr(const uint16_t* src, uint16_t* dst, uint8_t* codes_or_null,
+                                    size_t n, float scale, uint32_t rounding_mode, uint64_t seed,
+                                    uint64_t index_base, hif8_stream_t stream);
+hif8_status hif8_fake_quant_f16_sr(const uint16_t* src, uint16_t* dst, uint8_t* codes_or_null,
+                                   size_t n, float scale, uint32_t rounding_mode, uint64_t seed,
+                                   uint64_t index_base, hif8_stream_t stream);
+
+/*
+ * Per-tensor scaling in one call (Sec. 5, per-tensor scaling: amax of the tensor, scale factor
+ * from it, scale and cast):
+ *     d_amax[0]   = max_i |src[i]|                         as hif8_amax_*
+ *     d_scale2[0] = scale, d_scale2[1] = fl32(1 / scale)   as hif8_scale_from_amax(d_amax, target, pow2)
+ *     codes[i]    = code(Q(fl32(widen(src[i]) * scale)))   as hif8_encode_*_ds          (if codes != NULL)
+ *     dst[i]      = decode(codes[i]) descaled              as hif8_fake_quant_*_ds      (if dst != NULL)
+ * i.e. exactly what the three separate calls produce, in two launches instead of four: the first
+ * pass leaves one partial maximum per workgroup in `workspace`, and every workgroup of the cast
+ * reduces those and derives the scale itself (no clearing launch, no atomics, no scale launch).
+ * The first pass reads with ordinary loads, so a tensor that fits the 256 MB last-level cache is
+ * still there when the cast reads it again.
+ * At least one of dst, codes must be given; dst may equal src.  d_amax: one device float,
+ * d_scale2: two device floats, both written.  workspace: device scratch of at least
+ * hif8_quantize_workspace_bytes() bytes (4 KiB), 4-byte aligned, caller-owned; its contents need
+ * not be kept between calls, and calls that share it must not overlap in time.  n == 0 writes
+ * amax 0 and the pair {1, 1}.  Inputs that miss the fast path's alignment (see the general
+ * conventions) are handed to the separate calls.  Errors: HIF8_ERR_MODE, HIF8_ERR_ARG (target not
+ * finite and positive, workspace too small or misaligned), HIF8_ERR_NULL.
+ */
+size_t hif8_quantize_workspace_bytes(void);
+hif8_status hif8_quantize_tensor_f32(const float* src, float* dst_or_null, uint8_t* codes_or_null,
+                                     size_t n, float target, int pow2, uint32_t rounding_mode,
+                                     float* d_amax, float* d_scale2, void* workspace,
+                                     size_t workspace_bytes, hif8_stream_t stream);
+hif8_status hif8_quantize_tensor_bf16(const uint16_t* src, uint16_t* dst_or_null,
+                                      uint8_t* codes_or_null, size_t n, float target, int pow2,
+                                      uint32_t rounding_mode, float* d_amax, float* d_scale2,
+                                      void* workspace, size_t workspace_bytes, hif8_stream_t stream);
+hif8_status hif8_quantize_tensor_f16(const uint16_t* src, uint16_t* dst_or_null,
+                                     uint8_t* codes_or_null, size_t n, float target, int pow2,
+                                     uint32_t rounding_mode, float* d_amax, float* d_scale2,
+                                     void* workspace, size_t workspace_bytes, hif8_stream_t stream);
+
+/*
+ * Multi-tensor cast: per-tensor amax, scale and encode for a whole list of tensors in a few
+ * launches instead of four per tensor -- the per-tensor scaling recipe of Sec. 5 applied to every
+ * weight (or activation) tensor of a model at once.
  *
  *   hif8_cast_item   one tensor: src (device, 16-byte aligned; all items of a list have the
  *                    same type), dst (device, n u8 codes, 8-byte aligned for BF16 / FP16
@@ -226,11 +297,19 @@ hif8_status hif8_fake_quant_f16_ds(const uint16_t* src, uint16_t* dst, uint8_t* 
  *                    returns the total tile count.  The caller then copies the array to
  *                    device memory (it may be reused for any number of casts).
  *   hif8_multi_cast_{bf16,f16,f32}
- *                    d_items: the planned array in DEVICE memory; d_amax: count device floats
- *                    (output, amax per tensor); d_scale2: 2*count device floats (output,
- *                    {scale, 1/scale} per tensor, as hif8_scale_from_amax); target, pow2 as in
- *                    hif8_scale_from_amax.  Results equal the per-tensor sequence
- *                    hif8_amax_* -> hif8_scale_from_amax -> hif8_encode_*_ds.
+ *                    d_items: the planned array in DEVICE memory; host_items_or_null: the same
+ *                    planned array in HOST memory (read during the call only, for the sizes);
+ *                    d_amax: count device floats (output, amax per tensor); d_scale2: 2*count
+ *                    device floats (output, {scale, 1/scale} per tensor, as
+ *                    hif8_scale_from_amax); target, pow2 as in hif8_scale_from_amax.  Results
+ *                    equal the per-tensor sequence hif8_amax_* -> hif8_scale_from_amax ->
+ *                    hif8_encode_*_ds.  With the host copy the list is cut into groups of whole
+ *                    tensors of about 96 MiB of source, and one launch per group gathers the amax
+ *                    of that group while it casts the previous one, whose source is then still in
+ *                    the 256 MB last-level cache: the second read of every tensor is served from
+ *                    there instead of HBM.  Without it (NULL): amax of all tensors, scales, cast of
+ *                    all tensors (four launches, every tensor read from HBM twice).  HIF8_ERR_ARG if
+ *                    the host copy does not match total_tiles.
  *   hif8_multi_encode_{bf16,f16,f32}_ds
  *                    the cast alone, in ONE launch, with scales that are already on the device
  *                    (delayed scaling, Sec. 5: scales from earlier iterations): d_scale2: 2*count
@@ -250,10 +329,12 @@ typedef struct hif8_cast_item {
 
 hif8_status hif8_multi_plan(hif8_cast_item* host_items, size_t count, int src_is_16bit,
                             uint64_t* total_tiles_out);
-hif8_status hif8_multi_cast_bf16(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
+hif8_status hif8_multi_cast_bf16(const hif8_cast_item* host_items_or_null, const hif8_cast_item* d_items,
+                                 size_t count, uint64_t total_tiles,
                                  float* d_amax, float* d_scale2, float target, int pow2,
                                  uint32_t rounding_mode, hif8_stream_t stream);
-hif8_status hif8_multi_cast_f32(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
+hif8_status hif8_multi_cast_f32(const hif8_cast_item* host_items_or_null, const hif8_cast_item* d_items,
+                                 size_t count, uint64_t total_tiles,
                                 float* d_amax, float* d_scale2, float target, int pow2,
                                 uint32_t rounding_mode, hif8_stream_t stream);
 hif8_status hif8_multi_encode_bf16_ds(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
@@ -265,7 +346,8 @@ hif8_status hif8_multi_encode_f32_ds(const hif8_cast_item* d_items, size_t count
 hif8_status hif8_multi_encode_f16_ds(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
                                      const float* d_scale2, float* d_amax_accum_or_null,
                                      uint32_t rounding_mode, hif8_stream_t stream);
-hif8_status hif8_multi_cast_f16(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
+hif8_status hif8_multi_cast_f16(const hif8_cast_item* host_items_or_null, const hif8_cast_item* d_items,
+                                 size_t count, uint64_t total_tiles,
                                 float* d_amax, float* d_scale2, float target, int pow2,
                                 uint32_t rounding_mode, hif8_stream_t stream);
 
@@ -426,13 +508,6 @@ hif8_status hif8_als_update(hif8_als_state* st, int found_overflow);
  *   hif8_gemm_sqerr   no output matrix: *d_err += sum (out[m, n] - ref[m, n])^2 in fp64
  *                     (ref: [M, N] FP32; the caller clears *d_err) -- the "Quantization Error"
  *                     step of Algorithm 1.
- *   hif8_gemm_set_variant  0 = choose the tile shape by problem size (default: 5 when there is a
- *                     256 x 256 tile for every compute unit, else 6); 1..6 = fixed workgroup tile /
- *                     wavefront layouts (for benchmarking): 1 = 128 x 128 x 64 (4 wavefronts),
- *                     2 = 256 x 256 x 32 (4), 3 = 256 x 128 x 32 (4), 4 = 256 x 256 x 32 (8, as 2 x 4),
- *                     5 = 256 x 256 x 32 (8, as 4 x 2), 6 = 128 x 128 x 32 (4, two workgroups per CU);
- *                     7..9 = layouts of the expanded-operand kernel below (hif8_gemm_expanded_*): 7 = 256 x 256 x 64
- *                     (8, as 2 x 4), 8 = the same as 4 x 2, 9 = 128 x 128 x 64 (4).  0 resets both choices.
  */
 hif8_status hif8_gemm_f32(const uint8_t* a_codes, const uint8_t* b_codes, float* out, size_t M,
                           size_t N, size_t K, float scale_a, float scale_b, hif8_stream_t stream);
@@ -443,7 +518,6 @@ hif8_status hif8_gemm_f16(const uint8_t* a_codes, const uint8_t* b_codes, uint16
 hif8_status hif8_gemm_sqerr(const uint8_t* a_codes, const uint8_t* b_codes, const float* ref, size_t M,
                             size_t N, size_t K, float scale_a, float scale_b, double* d_err,
                             hif8_stream_t stream);
-hif8_status hif8_gemm_set_variant(int variant);
 
 /*
  * The same GEMM on operands expanded to bfloat16 beforehand.  Every HiF8 value is exact in
@@ -519,43 +593,6 @@ hif8_status hif8_calibrate_layer_f16(const uint16_t* a, const uint16_t* w, const
                                      int ew_lo, int ew_count, uint32_t rounding_mode,
                                      void* workspace, size_t workspace_bytes, double* d_err,
                                      int32_t* d_best_or_null, hif8_stream_t stream);
-
-/*
- * Launch-shape tuning knobs (process-wide; for benchmarking and profiling).  The first,
- * second, third, fifth and sixth default to -1 = "use the built-in choice of each kernel family".
- *   HIF8_TUNE_BLOCK        threads per workgroup of the streaming kernels (64..1024, multiple of 64)
- *   HIF8_TUNE_WG_PER_CU    persistent mode: workgroups launched per compute unit (1..64)
- *   HIF8_TUNE_UNROLL       16-byte loads in flight per lane (1, 2, 4 or 8); a tile is
- *                          block * unroll lanes' worth of data
- *   HIF8_TUNE_TA_IMPL      0 = TA encode through the LDS lookup table, 1 = TA encode in ALU only
- *   HIF8_TUNE_TILES_PER_WG 0 = persistent grid (grid-stride over tiles); k >= 1 = one-shot grid in
- *                          which every workgroup handles k consecutive tiles (0..4096)
- *   HIF8_TUNE_AMAX_NT      1 = amax reads with non-temporal loads, 0 = ordinary (cached) loads,
- *                          -1 (default) = ordinary loads for tensors up to 192 MiB (a cast of the
- *                          same tensor usually follows and then finds it in the last-level cache),
- *                          non-temporal loads above
- * Returns HIF8_ERR_ARG for an unknown key or a value outside the stated range.
- */
-enum {
-  HIF8_TUNE_BLOCK = 0,
-  HIF8_TUNE_WG_PER_CU = 1,
-  HIF8_TUNE_UNROLL = 2,
-  HIF8_TUNE_TA_IMPL = 3,
-  HIF8_TUNE_TILES_PER_WG = 4,
-  HIF8_TUNE_AMAX_NT = 5
-};
-hif8_status hif8_set_tuning(int key, int value);
-int hif8_get_tuning(int key); /* -1 for an unknown key */
-
-/*
- * Diagnostic stream kernel with the same read:write mix as a conversion
- * (read in_bytes_per_lane = 16 per lane, write out_bytes_per_lane in {4, 8, 16}),
- * used by the benchmark as the practical bandwidth ceiling of the machine.
- * Copies the low bytes of each 16-byte group: dst group g = first out_bytes of src group g.
- * n_groups 16-byte groups are read.  src 16-byte aligned, dst aligned to out_bytes.
- */
-hif8_status hif8_diag_stream(const void* src, void* dst, size_t n_groups, int out_bytes_per_lane,
-                             hif8_stream_t stream);
 
 #ifdef __cplusplus
 }

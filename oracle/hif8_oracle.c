@@ -63,9 +63,14 @@
  *         element from a counter-based generator (below); strict "<" makes the
  *         carry probability exactly F for a discrete uniform T and keeps
  *         representable inputs fixed (the paper writes F >= T for a real-valued T).
- *         Threshold of element i under seed s: the 32-bit finaliser of MurmurHash3
- *         over the low word of i xor a key made from s and the high word of i
- *         (for i, s < 2^32: fmix(i ^ s)).
+ *         Sec. 3.2 asks for one uniform random number per element and names no source,
+ *         so the generator is this build's choice.  Threshold of element i under the
+ *         64-bit seed s: a key pair (k1, k2) = the two halves of the splitmix64 finaliser
+ *         of s + 0x9E3779B97F4A7C15 * (hi32(i) + 1), i.e. a non-linear function of the whole
+ *         seed that is constant over 2^32 consecutive elements; then the 32-bit finaliser
+ *         of MurmurHash3 over lo32(i) ^ k1 with k2 added between its two multiplications.
+ *         Two seeds give two different functions of the index (not one sequence in another
+ *         order), which the pins check.
  *   - FP16 sources use SR2 with the FP16 LSB (bit 13 of the binary32 pattern
  *     being converted, so that, as for BF16, a scaled product is handled too).
  *
@@ -233,13 +238,18 @@ static float bits_f32(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
  * simplified SR the hybrid mode uses (SR2 for 16-bit sources, SR14 for FP32).
  * ---------------------------------------------------------------------- */
 /* counter-based threshold generator for standard SR (see header) */
-static uint32_t fmix32(uint32_t x) {
-  x ^= x >> 16; x *= 0x85EBCA6Bu; x ^= x >> 13; x *= 0xC2B2AE35u; x ^= x >> 16;
-  return x;
-}
 uint32_t hif8o_sr_threshold(uint64_t seed, uint64_t index) {
-  const uint32_t key = fmix32((uint32_t)(seed >> 32) + (uint32_t)(index >> 32) * 0x9E3779B9u) ^ (uint32_t)seed;
-  return fmix32((uint32_t)index ^ key);
+  /* key pair of the 2^32-element block that holds `index`: splitmix64's output function */
+  uint64_t z = seed + 0x9E3779B97F4A7C15ull * ((index >> 32) + 1ull);
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  z = z ^ (z >> 31);
+  const uint32_t k1 = (uint32_t)z, k2 = (uint32_t)(z >> 32);
+  /* MurmurHash3's 32-bit finaliser over the low index word, keyed at its input and in its middle */
+  uint32_t x = (uint32_t)index ^ k1;
+  x ^= x >> 16; x *= 0x85EBCA6Bu; x += k2;
+  x ^= x >> 13; x *= 0xC2B2AE35u; x ^= x >> 16;
+  return x;
 }
 static uint64_t g_sr_seed = 0;
 void hif8o_set_sr_seed(uint64_t seed) { g_sr_seed = seed; }

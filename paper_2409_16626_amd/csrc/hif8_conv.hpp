@@ -26,6 +26,7 @@
 
 #include <cmath>
 #include <cstdint>
+#include <cstring>
 
 #include "hif8.h"
 #include "hif8_conv_api.hpp"
@@ -79,13 +80,13 @@ struct EncCtx {
   const uint32_t* hrt; // staged per-exponent parameters in LDS (IMPL_HR, IMPL_SR): HrLds::w
   uint32_t mode;
   uint64_t seed;       // IMPL_SR
-  uint32_t sr_key;     // IMPL_SR: key of the 2^32-element block sr_hi (set by keyed())
+  SrKey sr_key;        // IMPL_SR: key pair of the 2^32-element block sr_hi (set by keyed())
   uint32_t sr_hi;
 };
 
 // Context for encoding elements of the 2^32-element block that holds element `elem` (standard SR draws its
-// thresholds from the low index word and a per-block key; other methods ignore it).  The key is computed
-// only when the block differs from the one the context was last keyed for.
+// thresholds from the low index word and a per-block key pair; other methods ignore it).  The key is
+// computed only when the block differs from the one the context was last keyed for.
 template <int IMPL>
 __device__ __forceinline__ EncCtx keyed(const EncCtx& c, uint64_t elem) {
   if constexpr (IMPL != IMPL_SR) return c;
@@ -96,11 +97,12 @@ __device__ __forceinline__ EncCtx keyed(const EncCtx& c, uint64_t elem) {
   k.sr_hi = hi;
   return k;
 }
-// A context keyed for block 0 (kernel prologue).
+// A context keyed for the block of element `elem0` (kernel prologue).
 template <int IMPL>
-__device__ __forceinline__ EncCtx make_ctx(const uint8_t* lut, const uint32_t* hrt, uint32_t mode, uint64_t seed) {
-  EncCtx c{lut, hrt, mode, seed, 0u, 0u};
-  if constexpr (IMPL == IMPL_SR) c.sr_key = sr_key(seed, 0u);
+__device__ __forceinline__ EncCtx make_ctx(const uint8_t* lut, const uint32_t* hrt, uint32_t mode, uint64_t seed,
+                                           uint64_t elem0 = 0) {
+  EncCtx c{lut, hrt, mode, seed, SrKey{0u, 0u}, (uint32_t)(elem0 >> 32)};
+  if constexpr (IMPL == IMPL_SR) c.sr_key = sr_key(seed, c.sr_hi);
   return c;
 }
 
@@ -159,7 +161,7 @@ __device__ __forceinline__ uint32_t table_index(uint32_t ybits, const EncCtx& c,
     const uint4 q = reinterpret_cast<const uint4*>(c.hrt)[(ybits >> 23) & 0xFFu];
     SrExp p;
     p.off = q.x; p.width = q.y; p.mask = q.z; p.fmul = __uint_as_float(q.w);
-    return sr_round_bits(ybits, fmix32((uint32_t)elem ^ c.sr_key), p) >> 19;
+    return sr_round_bits(ybits, sr_hash((uint32_t)elem, c.sr_key), p) >> 19;
   } else if constexpr (IMPL == IMPL_HR16) {
     // HR proper on a 16-bit source: kept mantissa, the two fraction bits (bit 19 upwards: where three bits
     // are kept Eq. (3) asks for TA, which looks at bit 19 only) and the source LSB decide, so the code comes
@@ -215,14 +217,27 @@ __device__ __forceinline__ uint32_t load_bits(const void* src, size_t i) {
   else return widen_lo<SRCK>(reinterpret_cast<const uint16_t*>(src)[i]);
 }
 
+// True when the VE elements starting at e0 do not all lie in one 2^32-element block (standard SR only; it can
+// happen only when the call's index base is not a multiple of the vector width).
+template <int IMPL, int VE>
+__device__ __forceinline__ bool straddles_block(uint64_t e0) {
+  if constexpr (IMPL != IMPL_SR) return false;
+  return (uint32_t)e0 > 0xFFFFFFFFu - (uint32_t)(VE - 1);
+}
+
 template <int IMPL>
 __device__ __forceinline__ uint32_t encode4_f32(const uint4& v, float scale, const EncCtx& c0_, uint64_t e0) {
-  const EncCtx c = keyed<IMPL>(c0_, e0);  // a vector never straddles a multiple of 2^32 elements
-  const uint32_t c0 = encode_one<IMPL, kSrcF32>(scaled_bits(v.x, scale), c, e0);
-  const uint32_t c1 = encode_one<IMPL, kSrcF32>(scaled_bits(v.y, scale), c, e0 + 1);
-  const uint32_t c2 = encode_one<IMPL, kSrcF32>(scaled_bits(v.z, scale), c, e0 + 2);
-  const uint32_t c3 = encode_one<IMPL, kSrcF32>(scaled_bits(v.w, scale), c, e0 + 3);
-  return c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
+  const uint32_t y[4] = {scaled_bits(v.x, scale), scaled_bits(v.y, scale), scaled_bits(v.z, scale), scaled_bits(v.w, scale)};
+  uint32_t r = 0;
+  if (straddles_block<IMPL, 4>(e0)) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) r |= encode_one<IMPL, kSrcF32>(y[j], keyed<IMPL>(c0_, e0 + j), e0 + j) << (8 * j);
+    return r;
+  }
+  const EncCtx c = keyed<IMPL>(c0_, e0);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) r |= encode_one<IMPL, kSrcF32>(y[j], c, e0 + j) << (8 * j);
+  return r;
 }
 
 // two 16-bit floats in one dword -> two codes in the low 16 bits
@@ -234,8 +249,21 @@ __device__ __forceinline__ uint32_t encode2_16(uint32_t w, float scale, const En
 }
 template <int IMPL, int SRCK>
 __device__ __forceinline__ uint2 encode8_16(const uint4& v, float scale, const EncCtx& c0_, uint64_t e0) {
-  const EncCtx c = keyed<IMPL>(c0_, e0);  // a vector never straddles a multiple of 2^32 elements
   uint2 o;
+  if (straddles_block<IMPL, 8>(e0)) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t q[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t c0 = encode_one<IMPL, SRCK>(scaled_bits(widen_lo<SRCK>(w[j]), scale), keyed<IMPL>(c0_, e0 + 2 * j), e0 + 2 * j);
+      const uint32_t c1 = encode_one<IMPL, SRCK>(scaled_bits(widen_hi<SRCK>(w[j]), scale), keyed<IMPL>(c0_, e0 + 2 * j + 1), e0 + 2 * j + 1);
+      q[j] = c0 | (c1 << 8);
+    }
+    o.x = q[0] | (q[1] << 16);
+    o.y = q[2] | (q[3] << 16);
+    return o;
+  }
+  const EncCtx c = keyed<IMPL>(c0_, e0);
   o.x = encode2_16<IMPL, SRCK>(v.x, scale, c, e0) | (encode2_16<IMPL, SRCK>(v.y, scale, c, e0 + 2) << 16);
   o.y = encode2_16<IMPL, SRCK>(v.z, scale, c, e0 + 4) | (encode2_16<IMPL, SRCK>(v.w, scale, c, e0 + 6) << 16);
   return o;
@@ -309,18 +337,75 @@ __device__ __forceinline__ uint32_t fold_amax(uint32_t m) {
 }
 
 // ------------------------------------------------------------------------------------
+// Where a cast kernel takes its scale pair {scale, fl32(1/scale)} from:
+//   by value            scale, inv (host-validated)
+//   d_scale2            two floats in device memory, written earlier on the stream
+//   parts               the per-workgroup maxima that k_amax_parts left for this tensor: every workgroup of the
+//                       cast reduces them (a few hundred words, L2-resident) and derives amax, scale and 1/scale
+//                       itself, so that per-tensor scaling needs two launches, no clearing launch and no atomics;
+//                       workgroup 0 publishes amax and the pair to out_amax / out_scale2.
+// ------------------------------------------------------------------------------------
+struct ScaleArg {
+  float scale, inv;
+  const float* d_scale2;
+  const uint32_t* parts;
+  uint32_t nparts;
+  float target;
+  int pow2;
+  float* out_amax;
+  float* out_scale2;
+};
+inline ScaleArg scale_by_value(float scale, float inv) { return ScaleArg{scale, inv, nullptr, nullptr, 0u, 0.0f, 0, nullptr, nullptr}; }
+inline ScaleArg scale_on_device(const float* d_scale2) { return ScaleArg{1.0f, 1.0f, d_scale2, nullptr, 0u, 0.0f, 0, nullptr, nullptr}; }
+
+
+// First half (before the workgroup barrier of the kernel prologue): wavefront maxima of the partial maxima
+// into LDS.  Second half (after that barrier): every lane folds them and derives the pair.
+struct ScaleLds {
+  uint32_t wave_m[16];
+};
+__device__ __forceinline__ void scale_before_barrier(const ScaleArg& a, ScaleLds& l) {
+  if (!a.parts) return;
+  uint32_t m = 0;
+  for (uint32_t i = threadIdx.x; i < a.nparts; i += blockDim.x) m = umax(m, a.parts[i]);
+  m = wave_max_u32(m);
+  if ((threadIdx.x & 63u) == 0u) l.wave_m[threadIdx.x >> 6] = m;
+}
+__device__ __forceinline__ void scale_after_barrier(const ScaleArg& a, const ScaleLds& l, float& scale, float& inv) {
+  if (a.parts) {
+    const uint32_t nw = (blockDim.x + 63u) >> 6;
+    uint32_t r = l.wave_m[0];
+    for (uint32_t w = 1; w < nw; ++w) r = umax(r, l.wave_m[w]);
+    const float amax = __uint_as_float(r);
+    scale = scale_from_amax_value(amax, a.target, a.pow2);
+    inv = 1.0f / scale;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+      *a.out_amax = amax;
+      a.out_scale2[0] = scale;
+      a.out_scale2[1] = inv;
+    }
+  } else if (a.d_scale2) {
+    scale = a.d_scale2[0];
+    inv = a.d_scale2[1];
+  } else {
+    scale = a.scale;
+    inv = a.inv;
+  }
+}
+
+// ------------------------------------------------------------------------------------
 // streaming kernels.  The ragged tail (n modulo the vector width) is done element-wise by
 // workgroup 0.
 // ------------------------------------------------------------------------------------
 template <int U, int IMPL, int SRCK>
 __global__ void __launch_bounds__(1024)
-k_encode(const void* __restrict__ src, uint8_t* __restrict__ dst, size_t n, float scale_arg,
-         const float* __restrict__ d_scale2, uint32_t* __restrict__ amax_acc, uint32_t mode,
-         uint64_t seed, const uint8_t* __restrict__ g_lut, Walk walk) {
+k_encode(const void* __restrict__ src, uint8_t* __restrict__ dst, size_t n, ScaleArg sa,
+         uint32_t* __restrict__ amax_acc, uint32_t mode, SrArg sr, const uint8_t* __restrict__ g_lut, Walk walk) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
   __shared__ HrLds<uses_exp_table<IMPL>()> hrt;
-  const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, seed);
-  const float scale = d_scale2 ? d_scale2[0] : scale_arg;
+  __shared__ ScaleLds sl;
+  const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, sr.seed, sr.base);
+  float scale = 1.0f, inv = 1.0f;
   const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(src);
   constexpr int VE = vec_elems<SRCK>();
   const size_t nvec = n >> vec_shift<SRCK>();
@@ -330,23 +415,25 @@ k_encode(const void* __restrict__ src, uint8_t* __restrict__ dst, size_t n, floa
       [&](size_t idx, const uint4& v) {
         if (amax_acc) m = vec_amax<SRCK>(m, v);
         if constexpr (SRCK == kSrcF32)
-          st_stream(reinterpret_cast<uint32_t*>(dst) + idx, encode4_f32<IMPL>(v, scale, ctx, idx * VE));
+          st_stream(reinterpret_cast<uint32_t*>(dst) + idx, encode4_f32<IMPL>(v, scale, ctx, sr.base + idx * VE));
         else
-          st_stream(reinterpret_cast<uint2*>(dst) + idx, encode8_16<IMPL, SRCK>(v, scale, ctx, idx * VE));
+          st_stream(reinterpret_cast<uint2*>(dst) + idx, encode8_16<IMPL, SRCK>(v, scale, ctx, sr.base + idx * VE));
       },
       [&]() {
         if (IMPL != IMPL_TA_ALU) {
           stage_enc_lut<IMPL, SRCK>(lut, g_lut, mode);
           stage_exp_table<IMPL, SRCK>(hrt.w, mode);
-          __syncthreads();
         }
+        scale_before_barrier(sa, sl);
+        if (IMPL != IMPL_TA_ALU || sa.parts) __syncthreads();
+        scale_after_barrier(sa, sl, scale, inv);
       });
   const size_t t = nvec * VE + threadIdx.x;
   m = fold_amax<SRCK>(m);
   if (blockIdx.x == 0 && t < n) {
     const uint32_t xb = load_bits<SRCK>(src, t);
     m = umax(m, xb & 0x7FFFFFFFu);
-    dst[t] = (uint8_t)encode_one<IMPL, SRCK>(scaled_bits(xb, scale), keyed<IMPL>(ctx, t), t);
+    dst[t] = (uint8_t)encode_one<IMPL, SRCK>(scaled_bits(xb, scale), keyed<IMPL>(ctx, sr.base + t), sr.base + t);
   }
   if (amax_acc) block_max_to_global(m, amax_acc);
 }
@@ -386,20 +473,21 @@ k_decode(const uint8_t* __restrict__ src, void* __restrict__ dst, size_t n, floa
 // fake-quant: src and dst may alias (each lane reads its own vectors before it writes them)
 template <int U, int IMPL, bool CODES, int SRCK>
 __global__ void __launch_bounds__(1024)
-k_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, float scale_arg, float inv_arg,
-             const float* __restrict__ d_scale2, uint32_t* amax_acc, uint32_t mode, uint64_t seed,
-             const uint8_t* __restrict__ g_lut, const uint32_t* __restrict__ g_dec, Walk walk) {
+k_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, ScaleArg sa, uint32_t* amax_acc, uint32_t mode,
+             SrArg sr, const uint8_t* __restrict__ g_lut, const uint32_t* __restrict__ g_dec, Walk walk) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
   __shared__ HrLds<uses_exp_table<IMPL>()> hrt;
   __shared__ uint32_t dec[256];
-  const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, seed);
-  const float scale = d_scale2 ? d_scale2[0] : scale_arg;
-  const float inv = d_scale2 ? d_scale2[1] : inv_arg;
+  __shared__ ScaleLds sl;
+  const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, sr.seed, sr.base);
+  float scale = 1.0f, inv = 1.0f;
   auto prologue = [&]() {
     stage_enc_lut<IMPL, SRCK>(lut, g_lut, mode);
     stage_exp_table<IMPL, SRCK>(hrt.w, mode);
     stage_dec_lut(dec, g_dec);
+    scale_before_barrier(sa, sl);
     __syncthreads();
+    scale_after_barrier(sa, sl, scale, inv);
   };
   const uint4* src4 = reinterpret_cast<const uint4*>(src);
   uint4* dst4 = reinterpret_cast<uint4*>(dst);
@@ -411,11 +499,11 @@ k_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, float scale_a
       [&](size_t idx, const uint4& v) {
         if (amax_acc) m = vec_amax<SRCK>(m, v);
         if constexpr (SRCK == kSrcF32) {
-          const uint32_t w = encode4_f32<IMPL>(v, scale, ctx, idx * VE);
+          const uint32_t w = encode4_f32<IMPL>(v, scale, ctx, sr.base + idx * VE);
           st_stream(dst4 + idx, descale4_f32(w, dec, inv));
           if (CODES) st_stream(reinterpret_cast<uint32_t*>(codes) + idx, w);
         } else {
-          const uint2 w = encode8_16<IMPL, SRCK>(v, scale, ctx, idx * VE);
+          const uint2 w = encode8_16<IMPL, SRCK>(v, scale, ctx, sr.base + idx * VE);
           st_stream(dst4 + idx, descale8_16<SRCK>(w, dec, inv));
           if (CODES) st_stream(reinterpret_cast<uint2*>(codes) + idx, w);
         }
@@ -426,7 +514,7 @@ k_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, float scale_a
   if (blockIdx.x == 0 && t < n) {
     const uint32_t xb = load_bits<SRCK>(src, t);
     m = umax(m, xb & 0x7FFFFFFFu);
-    const uint32_t c = encode_one<IMPL, SRCK>(scaled_bits(xb, scale), keyed<IMPL>(ctx, t), t);
+    const uint32_t c = encode_one<IMPL, SRCK>(scaled_bits(xb, scale), keyed<IMPL>(ctx, sr.base + t), sr.base + t);
     const uint32_t b = descale_bits(c, dec, inv);
     if constexpr (SRCK == kSrcF32) reinterpret_cast<uint32_t*>(dst)[t] = b;
     else reinterpret_cast<uint16_t*>(dst)[t] = (uint16_t)narrow1<SRCK>(b);
@@ -442,14 +530,14 @@ k_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, float scale_a
 template <int SRCK>
 __global__ void __launch_bounds__(256)
 k_encode_elem(const void* src, uint8_t* dst, size_t n, float scale_arg, const float* d_scale2,
-              uint32_t* amax_acc, uint32_t mode, uint64_t seed) {
+              uint32_t* amax_acc, uint32_t mode, SrArg sr) {
   const float scale = d_scale2 ? d_scale2[0] : scale_arg;
   uint32_t m = 0;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
        i += (size_t)gridDim.x * blockDim.x) {
     const uint32_t xb = load_bits<SRCK>(src, i);
     m = umax(m, xb & 0x7FFFFFFFu);
-    dst[i] = (uint8_t)encode_any<SRCK>(scaled_bits(xb, scale), mode, sr_threshold(seed, i));
+    dst[i] = (uint8_t)encode_any<SRCK>(scaled_bits(xb, scale), mode, sr_threshold(sr.seed, sr.base + i));
   }
   if (amax_acc) block_max_to_global(m, amax_acc);
 }
@@ -470,7 +558,7 @@ template <int SRCK>
 __global__ void __launch_bounds__(256)
 k_fake_quant_elem(const void* src, void* dst, uint8_t* codes, size_t n, float scale_arg,
                   float inv_arg, const float* d_scale2, uint32_t* amax_acc, uint32_t mode,
-                  uint64_t seed) {
+                  SrArg sr) {
   const float scale = d_scale2 ? d_scale2[0] : scale_arg;
   const float inv = d_scale2 ? d_scale2[1] : inv_arg;
   uint32_t m = 0;
@@ -478,7 +566,7 @@ k_fake_quant_elem(const void* src, void* dst, uint8_t* codes, size_t n, float sc
        i += (size_t)gridDim.x * blockDim.x) {
     const uint32_t xb = load_bits<SRCK>(src, i);
     m = umax(m, xb & 0x7FFFFFFFu);
-    const uint32_t c = encode_any<SRCK>(scaled_bits(xb, scale), mode, sr_threshold(seed, i));
+    const uint32_t c = encode_any<SRCK>(scaled_bits(xb, scale), mode, sr_threshold(sr.seed, sr.base + i));
     const uint32_t b = __float_as_uint(__fmul_rn(__uint_as_float(decode_bits(c)), inv));
     if constexpr (SRCK == kSrcF32) reinterpret_cast<uint32_t*>(dst)[i] = b;
     else reinterpret_cast<uint16_t*>(dst)[i] = (uint16_t)narrow1<SRCK>(b);
@@ -490,7 +578,10 @@ k_fake_quant_elem(const void* src, void* dst, uint8_t* codes, size_t n, float sc
 // ------------------------------------------------------------------------------------
 // amax (magnitude patterns as binary32 bits)
 // ------------------------------------------------------------------------------------
-template <int U, int SRCK, bool NT>
+// PARTS = false: one atomic max per workgroup into *out (which the host cleared on the stream before).
+// PARTS = true : out[blockIdx.x] = maximum of this workgroup's share, no atomics and nothing to clear; the
+//                cast that follows reduces the array (ScaleArg::parts).
+template <int U, int SRCK, bool NT, bool PARTS>
 __global__ void __launch_bounds__(1024)
 k_amax(const void* __restrict__ src, size_t n, uint32_t* __restrict__ out, Walk walk) {
   const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(src);
@@ -502,7 +593,12 @@ k_amax(const void* __restrict__ src, size_t n, uint32_t* __restrict__ out, Walk 
   m = fold_amax<SRCK>(m);
   const size_t t = nvec * vec_elems<SRCK>() + threadIdx.x;
   if (blockIdx.x == 0 && t < n) m = umax(m, load_bits<SRCK>(src, t) & 0x7FFFFFFFu);
-  block_max_to_global(m, out);
+  if constexpr (PARTS) {
+    const uint32_t r = block_max_thread0(m);
+    if (threadIdx.x == 0) out[blockIdx.x] = r;
+  } else {
+    block_max_to_global(m, out);
+  }
 }
 
 template <int SRCK>
@@ -516,10 +612,9 @@ k_amax_elem(const void* __restrict__ src, size_t n, uint32_t* __restrict__ out) 
 }
 
 // ------------------------------------------------------------------------------------
-// multi-tensor cast: many tensors per launch (amax, then scale, then encode), so that a
-// list of small tensors is not bound by launch gaps.  All tensors share one global tile
-// index space; items[i].first_tile is the prefix sum of tile counts.  A tile is
-// kMultiBlock * kMultiUnroll vector units of one tensor.
+// multi-tensor cast: many tensors per launch, so that a list of small tensors is not bound by
+// launch gaps.  All tensors share one global tile index space; items[i].first_tile is the
+// prefix sum of tile counts.  A tile is kMultiBlock * kMultiUnroll vector units of one tensor.
 // ------------------------------------------------------------------------------------
 constexpr uint32_t kMultiTpwEncode = 2;
 constexpr uint32_t kMultiTpwAmax = 8;
@@ -542,16 +637,18 @@ __device__ __forceinline__ uint64_t multi_item_tiles(uint64_t n) {
   return (t == 0 && n != 0) ? 1 : t;
 }
 
-template <int SRCK>
-__global__ void __launch_bounds__(kMultiBlock)
-k_multi_amax(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_t total_tiles,
-             uint32_t* __restrict__ amax_out) {
+// amax of the tiles [first, first + TPW) below tile_end: one atomic max per tensor touched.
+// NT: non-temporal loads (the tensors are not read again soon); otherwise ordinary loads, which leave the
+// data in the last-level cache for the cast of the same tiles that follows.
+template <int SRCK, bool NT, uint32_t TPW>
+__device__ __forceinline__ void multi_amax_tiles(const hif8_cast_item* __restrict__ items, uint32_t count,
+                                                 uint64_t first, uint64_t tile_end, uint32_t* __restrict__ amax_out) {
   uint32_t m = 0;     // vector part, in the packed form of vec_amax
   uint32_t mt = 0;    // ragged-tail part, binary32 magnitude pattern
   uint32_t cur = 0xFFFFFFFFu;
-  for (uint32_t i = 0; i < kMultiTpwAmax; ++i) {
-    const uint64_t tile = (uint64_t)blockIdx.x * kMultiTpwAmax + i;
-    if (tile >= total_tiles) break;
+  for (uint32_t i = 0; i < TPW; ++i) {
+    const uint64_t tile = first + i;
+    if (tile >= tile_end) break;
     const uint32_t it = multi_find_item(items, count, tile);
     if (it != cur) {
       if (cur != 0xFFFFFFFFu) {
@@ -566,12 +663,12 @@ k_multi_amax(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_t 
     const uint64_t nvec = n >> vec_shift<SRCK>();
     const uint64_t local = tile - items[it].first_tile;
     const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(items[it].src);
-    const uint64_t first = local * kMultiTileVec + threadIdx.x;
+    const uint64_t v0 = local * kMultiTileVec + threadIdx.x;
     uint4 v[kMultiUnroll];
 #pragma unroll
     for (int j = 0; j < kMultiUnroll; ++j) {
-      const uint64_t idx = first + (uint64_t)j * kMultiBlock;
-      v[j] = (idx < nvec) ? ld_stream(src4 + idx) : make_uint4(0u, 0u, 0u, 0u);
+      const uint64_t idx = v0 + (uint64_t)j * kMultiBlock;
+      v[j] = (idx < nvec) ? (NT ? ld_stream(src4 + idx) : src4[idx]) : make_uint4(0u, 0u, 0u, 0u);
     }
 #pragma unroll
     for (int j = 0; j < kMultiUnroll; ++j) m = vec_amax<SRCK>(m, v[j]);
@@ -584,24 +681,29 @@ k_multi_amax(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_t 
   if (cur != 0xFFFFFFFFu) block_max_to_global(umax(fold_amax<SRCK>(m), mt), amax_out + cur);
 }
 
-// ACC: also accumulate the amax of every tensor's source into amax_acc[item] (delayed scaling: the scales
-// in use come from earlier iterations, the accumulators feed the next update).
-template <int IMPL, int SRCK, bool ACC>
-__global__ void __launch_bounds__(kMultiBlock)
-k_multi_encode(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_t total_tiles,
-               const float* __restrict__ d_scale2, uint32_t* __restrict__ amax_acc, uint32_t mode, uint64_t seed,
-               const uint8_t* __restrict__ g_lut) {
-  __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
-  __shared__ HrLds<uses_exp_table<IMPL>()> hrt;
-  const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, seed);
-  stage_enc_lut<IMPL, SRCK>(lut, g_lut, mode);
-  stage_exp_table<IMPL, SRCK>(hrt.w, mode);
-  __syncthreads();
+// Where the multi-tensor cast takes the scale of item `it` from: the pair in d_scale2 (written earlier on the
+// stream), or -- FROM_AMAX -- derived here from the finished amax of the item, in which case the workgroup that
+// casts the item's first tile also publishes the pair to d_scale2.
+struct MultiScale {
+  const float* d_scale2_in;
+  const uint32_t* amax_in;
+  float* d_scale2_out;
+  float target;
+  int pow2;
+};
+
+// Cast of the tiles [first, first + kMultiTpwEncode) below tile_end.  ACC: also accumulate the amax of every
+// tensor's source into amax_acc[item] (delayed scaling: the scales in use come from earlier iterations, the
+// accumulators feed the next update).  The encode tables must be staged (and a barrier passed) before.
+template <int IMPL, int SRCK, bool ACC, bool FROM_AMAX>
+__device__ __forceinline__ void multi_encode_tiles(const hif8_cast_item* __restrict__ items, uint32_t count,
+                                                   uint64_t first, uint64_t tile_end, const MultiScale& ms,
+                                                   uint32_t* __restrict__ amax_acc, const EncCtx& ctx) {
   constexpr int VE = vec_elems<SRCK>();
-  uint32_t m = 0, mt = 0, cur = 0xFFFFFFFFu;  // ACC: as in k_multi_amax
+  uint32_t m = 0, mt = 0, cur = 0xFFFFFFFFu;  // ACC: as in multi_amax_tiles
   for (uint32_t i = 0; i < kMultiTpwEncode; ++i) {
-    const uint64_t tile = (uint64_t)blockIdx.x * kMultiTpwEncode + i;
-    if (tile >= total_tiles) break;
+    const uint64_t tile = first + i;
+    if (tile >= tile_end) break;
     const uint32_t it = multi_find_item(items, count, tile);
     if (ACC && it != cur) {
       if (cur != 0xFFFFFFFFu) {
@@ -615,20 +717,29 @@ k_multi_encode(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_
     const uint64_t n = items[it].n;
     const uint64_t nvec = n >> vec_shift<SRCK>();
     const uint64_t local = tile - items[it].first_tile;
-    const float scale = d_scale2[2 * it];
+    float scale;
+    if constexpr (FROM_AMAX) {
+      scale = scale_from_amax_value(__uint_as_float(ms.amax_in[it]), ms.target, ms.pow2);
+      if (local == 0 && threadIdx.x == 0) {
+        ms.d_scale2_out[2 * it] = scale;
+        ms.d_scale2_out[2 * it + 1] = 1.0f / scale;
+      }
+    } else {
+      scale = ms.d_scale2_in[2 * it];
+    }
     const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(items[it].src);
     uint8_t* __restrict__ dst = items[it].dst;
-    const uint64_t first = local * kMultiTileVec + threadIdx.x;
+    const uint64_t v0 = local * kMultiTileVec + threadIdx.x;
     uint4 v[kMultiUnroll];
 #pragma unroll
     for (int j = 0; j < kMultiUnroll; ++j) {
-      const uint64_t idx = first + (uint64_t)j * kMultiBlock;
+      const uint64_t idx = v0 + (uint64_t)j * kMultiBlock;
       if (idx < nvec) v[j] = ld_stream(src4 + idx);
       else if (ACC) v[j] = make_uint4(0u, 0u, 0u, 0u);
     }
 #pragma unroll
     for (int j = 0; j < kMultiUnroll; ++j) {
-      const uint64_t idx = first + (uint64_t)j * kMultiBlock;
+      const uint64_t idx = v0 + (uint64_t)j * kMultiBlock;
       if (ACC) m = vec_amax<SRCK>(m, v[j]);
       if (idx < nvec) {
         if constexpr (SRCK == kSrcF32)
@@ -647,6 +758,167 @@ k_multi_encode(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_
     }
   }
   if (ACC && cur != 0xFFFFFFFFu) block_max_to_global(umax(fold_amax<SRCK>(m), mt), amax_acc + cur);
+}
+
+template <int SRCK>
+__global__ void __launch_bounds__(kMultiBlock)
+k_multi_amax(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_t total_tiles,
+             uint32_t* __restrict__ amax_out) {
+  multi_amax_tiles<SRCK, true, kMultiTpwAmax>(items, count, (uint64_t)blockIdx.x * kMultiTpwAmax, total_tiles, amax_out);
+}
+
+template <int IMPL, int SRCK, bool ACC>
+__global__ void __launch_bounds__(kMultiBlock)
+k_multi_encode(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_t total_tiles,
+               const float* __restrict__ d_scale2, uint32_t* __restrict__ amax_acc, uint32_t mode, uint64_t seed,
+               const uint8_t* __restrict__ g_lut) {
+  __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
+  __shared__ HrLds<uses_exp_table<IMPL>()> hrt;
+  const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, seed);
+  stage_enc_lut<IMPL, SRCK>(lut, g_lut, mode);
+  stage_exp_table<IMPL, SRCK>(hrt.w, mode);
+  __syncthreads();
+  const MultiScale ms{d_scale2, nullptr, nullptr, 0.0f, 0};
+  multi_encode_tiles<IMPL, SRCK, ACC, false>(items, count, (uint64_t)blockIdx.x * kMultiTpwEncode, total_tiles, ms,
+                                             amax_acc, ctx);
+}
+
+// One stage of the group-wise multi-tensor cast: am_wgs workgroups gather the amax of the tensors am[] of one
+// group while enc_wgs workgroups cast the tensors enc[] of the group before it -- whose amax the previous stage
+// gathered, so that their source now sits in the last-level cache.  One launch per group.  The tensors of a stage
+// travel by value in the kernel arguments (at most kStageItems per role), each with its first position in the
+// role's index space, so a workgroup finds its tensor with a few scalar compares.
+//   cast: a workgroup owns kStageVec consecutive 16-byte vectors of one tensor, requests all of them at once,
+//         and the last workgroup of a tensor also does its ragged tail;
+//   amax: few, long-lived workgroups (at most one per compute unit) walk the chunks of kStageVecAmax vectors of
+//         all tensors of the group with a stride, and end with one atomic max per tensor they touched.  (One
+//         short-lived workgroup per chunk was measured first: a thousand workgroups that start together all
+//         find the accumulator at zero, and their atomics on one address, served one after the other at about
+//         7 ns each, then cost as much as the reads.)
+// The amax workgroups come first in index order: the dispatcher hands workgroups out in that order, so they
+// hold one slot of every compute unit for the whole stage and the short-lived casting workgroups stream
+// through the other slots.
+constexpr int kStageItems = 16;
+constexpr int kStageBlock = 512;
+constexpr int kStageU = 4;       // cast: 16-byte loads per lane
+constexpr int kStageUAmax = 8;   // amax: 16-byte loads per lane
+constexpr uint32_t kStageVec = kStageBlock * kStageU;
+constexpr uint32_t kStageVecAmax = kStageBlock * kStageUAmax;
+struct StageItem {
+  const void* src;
+  uint8_t* dst;
+  uint64_t n;
+  uint32_t wg_first;  // cast: first workgroup of the role that works on this tensor; amax: its first chunk
+  uint32_t index;     // position in the caller's list (its amax / scale pair entries)
+};
+struct StageArgs {
+  StageItem enc[kStageItems];
+  StageItem am[kStageItems];
+  uint32_t n_enc, n_am;
+  uint32_t enc_wgs, am_wgs;
+  uint32_t am_chunks;  // chunks of all tensors of am[]
+};
+template <int SRCK>
+__host__ __device__ inline uint32_t stage_item_wgs(uint64_t n, uint32_t vec_per_wg) {
+  const uint64_t nvec = n >> vec_shift<SRCK>();
+  const uint64_t w = (nvec + vec_per_wg - 1) / vec_per_wg;
+  return (uint32_t)((w == 0 && n != 0) ? 1 : w);
+}
+
+// entry of `items` whose workgroup range holds w (wg_first ascending, items[0].wg_first == 0)
+__device__ __forceinline__ int stage_find(const StageItem* items, uint32_t n_items, uint32_t w) {
+  int j = 0;
+#pragma unroll
+  for (int k = 1; k < kStageItems; ++k)
+    if ((uint32_t)k < n_items && items[k].wg_first <= w) j = k;
+  return j;
+}
+
+template <int IMPL, int SRCK>
+__global__ void __launch_bounds__(kStageBlock)
+k_group_stage(const StageArgs sg, uint32_t* __restrict__ amax, float* __restrict__ d_scale2, float target, int pow2,
+              uint32_t mode, uint64_t seed, const uint8_t* __restrict__ g_lut) {
+  __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
+  __shared__ HrLds<uses_exp_table<IMPL>()> hrt;
+  constexpr int VE = vec_elems<SRCK>();
+  const bool is_amax = blockIdx.x < sg.am_wgs;
+  const uint32_t w = is_amax ? blockIdx.x : blockIdx.x - sg.am_wgs;  // index within the role
+  if (!is_amax) {
+    const int j = stage_find(sg.enc, sg.n_enc, w);
+    const StageItem it = sg.enc[j];
+    const uint64_t nvec = it.n >> vec_shift<SRCK>();
+    const uint32_t local = w - it.wg_first;
+    const uint64_t v0 = (uint64_t)local * kStageVec + threadIdx.x;
+    const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(it.src);
+    uint4 v[kStageU];
+#pragma unroll
+    for (int u = 0; u < kStageU; ++u) {
+      const uint64_t idx = v0 + (uint64_t)u * kStageBlock;
+      if (idx < nvec) v[u] = ld_stream(src4 + idx);
+    }
+    const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, seed);
+    stage_enc_lut<IMPL, SRCK>(lut, g_lut, mode);
+    stage_exp_table<IMPL, SRCK>(hrt.w, mode);
+    const float scale = scale_from_amax_value(__uint_as_float(amax[it.index]), target, pow2);
+    if (local == 0 && threadIdx.x == 0) {
+      d_scale2[2 * it.index] = scale;
+      d_scale2[2 * it.index + 1] = 1.0f / scale;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kStageU; ++u) {
+      const uint64_t idx = v0 + (uint64_t)u * kStageBlock;
+      if (idx < nvec) {
+        if constexpr (SRCK == kSrcF32)
+          st_stream(reinterpret_cast<uint32_t*>(it.dst) + idx, encode4_f32<IMPL>(v[u], scale, ctx, idx * VE));
+        else
+          st_stream(reinterpret_cast<uint2*>(it.dst) + idx, encode8_16<IMPL, SRCK>(v[u], scale, ctx, idx * VE));
+      }
+    }
+    if (local + 1 == stage_item_wgs<SRCK>(it.n, kStageVec)) {  // ragged tail of the tensor
+      const uint64_t t = nvec * VE + threadIdx.x;
+      if (t < it.n)
+        it.dst[t] = (uint8_t)encode_one<IMPL, SRCK>(scaled_bits(load_bits<SRCK>(it.src, t), scale), keyed<IMPL>(ctx, t), t);
+    }
+  } else {
+    uint32_t m = 0, mt = 0;  // vector part (packed form of vec_amax) and ragged-tail part of the current tensor
+    int cur = -1;
+    for (uint32_t c = w; c < sg.am_chunks; c += sg.am_wgs) {
+      const int j = stage_find(sg.am, sg.n_am, c);
+      if (j != cur) {
+        if (cur >= 0) {
+          block_max_to_global(umax(fold_amax<SRCK>(m), mt), amax + sg.am[cur].index);
+          __syncthreads();
+        }
+        cur = j;
+        m = 0;
+        mt = 0;
+      }
+      const StageItem it = sg.am[j];
+      const uint64_t nvec = it.n >> vec_shift<SRCK>();
+      const uint32_t local = c - it.wg_first;
+      const uint64_t v0 = (uint64_t)local * kStageVecAmax + threadIdx.x;
+      const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(it.src);
+      if (nvec != 0) {
+        // unconditional loads (so that all are in flight together): an index past the end reads the last
+        // vector again, which leaves the maximum as it is.  Ordinary loads: the cast of the next stage
+        // re-reads the data from the last-level cache.
+        uint4 v[kStageUAmax];
+#pragma unroll
+        for (int u = 0; u < kStageUAmax; ++u) {
+          const uint64_t idx = v0 + (uint64_t)u * kStageBlock;
+          v[u] = src4[idx < nvec ? idx : nvec - 1];
+        }
+#pragma unroll
+        for (int u = 0; u < kStageUAmax; ++u) m = vec_amax<SRCK>(m, v[u]);
+      }
+      if (local + 1 == stage_item_wgs<SRCK>(it.n, kStageVecAmax)) {
+        const uint64_t t = nvec * VE + threadIdx.x;
+        if (t < it.n) mt = umax(mt, load_bits<SRCK>(it.src, t) & 0x7FFFFFFFu);
+      }
+    }
+    if (cur >= 0) block_max_to_global(umax(fold_amax<SRCK>(m), mt), amax + sg.am[cur].index);
+  }
 }
 
 // ====================================================================================
@@ -684,26 +956,10 @@ inline void dispatch_impl(int impl, int unroll, F&& f) {
   }
 }
 
+// The fast (16-byte vector) form of the cast; the caller has validated the arguments and the alignment.
 template <int SRCK>
-hif8_status conv_encode(const void* src, uint8_t* dst, size_t n, float scale, const float* d_scale2,
-                        float* d_amax_acc, uint32_t mode, hipStream_t st) {
-  uint32_t* amax_acc = reinterpret_cast<uint32_t*>(d_amax_acc);
-  if (!valid_mode(mode)) return HIF8_ERR_MODE;
-  float inv = 1.0f;
-  if (!d_scale2 && !valid_scale(scale, &inv)) return HIF8_ERR_SCALE;
-  if (n == 0) return HIF8_OK;
-  if (!src || !dst) return HIF8_ERR_NULL;
-  int cus = 0;
-  DevTables tb;
-  hif8_status s = ensure_init(&cus, &tb);
-  if (s != HIF8_OK) return s;
-  const uint64_t seed = sr_seed();
-  const bool fast = aligned_to(src, 16) && aligned_to(dst, SRCK == kSrcF32 ? 4 : 8);
-  if (!fast) {
-    hipLaunchKernelGGL(k_encode_elem<SRCK>, dim3(grid_elem(n, cus)), dim3(256), 0, st, src, dst, n,
-                       scale, d_scale2, amax_acc, mode, seed);
-    return finish_launch();
-  }
+void launch_encode_fast(const void* src, uint8_t* dst, size_t n, const ScaleArg& sa, uint32_t* amax_acc, uint32_t mode,
+                        const SrArg& sr, int cus, const DevTables& tb, hipStream_t st) {
   const size_t nvec = n >> vec_shift<SRCK>();
   const int impl = impl_for<SRCK>(mode);
   // TE and standard SR stage larger tables and are built for one unroll factor: they keep the 512-lane shape
@@ -714,8 +970,60 @@ hif8_status conv_encode(const void* src, uint8_t* dst, size_t n, float scale, co
   const dim3 grid(grid_for(nvec, cus, shape, &walk)), block(shape.block);
   dispatch_impl<SRCK>(impl, shape.unroll, [&](auto impl_c, auto u_c) {
     hipLaunchKernelGGL((k_encode<decltype(u_c)::value, decltype(impl_c)::value, SRCK>), grid, block, 0, st, src,
-                       dst, n, scale, d_scale2, amax_acc, mode, seed, enc_table_for<decltype(impl_c)::value>(tb), walk);
+                       dst, n, sa, amax_acc, mode, sr, enc_table_for<decltype(impl_c)::value>(tb), walk);
   });
+}
+
+template <int SRCK>
+void launch_fake_quant_fast(const void* src, void* dst, uint8_t* codes, size_t n, const ScaleArg& sa, uint32_t* amax_acc,
+                            uint32_t mode, const SrArg& sr, int cus, const DevTables& tb, hipStream_t st) {
+  const size_t nvec = n >> vec_shift<SRCK>();
+  const int impl = impl_for<SRCK>(mode);
+  Shape shape = shape_for(FAM_FQ);
+  if (impl == IMPL_TE || impl == IMPL_SR) shape.unroll = 2;
+  Walk walk;
+  const dim3 grid(grid_for(nvec, cus, shape, &walk)), block(shape.block);
+  dispatch_impl<SRCK>(impl, shape.unroll, [&](auto impl_c, auto u_c) {
+    constexpr int U = decltype(u_c)::value, IMPL = decltype(impl_c)::value;
+    if (codes)
+      hipLaunchKernelGGL((k_fake_quant<U, IMPL, true, SRCK>), grid, block, 0, st, src, dst, codes, n, sa, amax_acc, mode,
+                         sr, enc_table_for<IMPL>(tb), tb.dec_lut, walk);
+    else
+      hipLaunchKernelGGL((k_fake_quant<U, IMPL, false, SRCK>), grid, block, 0, st, src, dst, codes, n, sa, amax_acc,
+                         mode, sr, enc_table_for<IMPL>(tb), tb.dec_lut, walk);
+  });
+}
+
+template <int SRCK>
+inline bool encode_fast_ok(const void* src, const uint8_t* dst) {
+  return aligned_to(src, 16) && aligned_to(dst, SRCK == kSrcF32 ? 4 : 8);
+}
+template <int SRCK>
+inline bool fake_quant_fast_ok(const void* src, const void* dst, const uint8_t* codes) {
+  return aligned_to(src, 16) && aligned_to(dst, 16) && (!codes || aligned_to(codes, SRCK == kSrcF32 ? 4 : 8));
+}
+
+template <int SRCK>
+hif8_status conv_encode(const void* src, uint8_t* dst, size_t n, float scale, const float* d_scale2,
+                        float* d_amax_acc, uint32_t mode, const SrArg* sr_or_null, hipStream_t st) {
+  uint32_t* amax_acc = reinterpret_cast<uint32_t*>(d_amax_acc);
+  if (!valid_mode(mode)) return HIF8_ERR_MODE;
+  float inv = 1.0f;
+  if (!d_scale2 && !valid_scale(scale, &inv)) return HIF8_ERR_SCALE;
+  if (n == 0) return HIF8_OK;
+  if (!src || !dst) return HIF8_ERR_NULL;
+  int cus = 0;
+  DevTables tb;
+  hif8_status s = ensure_init(&cus, &tb);
+  if (s != HIF8_OK) return s;
+  const SrArg sr = sr_or_null ? *sr_or_null : SrArg{sr_seed(), 0};
+  if (!encode_fast_ok<SRCK>(src, dst)) {
+    hipLaunchKernelGGL(k_encode_elem<SRCK>, dim3(grid_elem(n, cus)), dim3(256), 0, st, src, dst, n,
+                       scale, d_scale2, amax_acc, mode, sr);
+    return finish_launch();
+  }
+  launch_encode_fast<SRCK>(src, dst, n, d_scale2 ? scale_on_device(d_scale2) : scale_by_value(scale, inv), amax_acc, mode,
+                           sr, cus, tb, st);
   return finish_launch();
 }
 
@@ -749,7 +1057,8 @@ hif8_status conv_decode(const uint8_t* src, void* dst, size_t n, float scale, co
 
 template <int SRCK>
 hif8_status conv_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, float scale,
-                            const float* d_scale2, float* d_amax_acc, uint32_t mode, hipStream_t st) {
+                            const float* d_scale2, float* d_amax_acc, uint32_t mode, const SrArg* sr_or_null,
+                            hipStream_t st) {
   uint32_t* amax_acc = reinterpret_cast<uint32_t*>(d_amax_acc);
   if (!valid_mode(mode)) return HIF8_ERR_MODE;
   float inv = 1.0f;
@@ -760,30 +1069,33 @@ hif8_status conv_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n
   DevTables tb;
   hif8_status s = ensure_init(&cus, &tb);
   if (s != HIF8_OK) return s;
-  const uint64_t seed = sr_seed();
-  const bool fast = aligned_to(src, 16) && aligned_to(dst, 16) &&
-                    (!codes || aligned_to(codes, SRCK == kSrcF32 ? 4 : 8));
-  if (!fast) {
+  const SrArg sr = sr_or_null ? *sr_or_null : SrArg{sr_seed(), 0};
+  if (!fake_quant_fast_ok<SRCK>(src, dst, codes)) {
     hipLaunchKernelGGL(k_fake_quant_elem<SRCK>, dim3(grid_elem(n, cus)), dim3(256), 0, st, src, dst,
-                       codes, n, scale, inv, d_scale2, amax_acc, mode, seed);
+                       codes, n, scale, inv, d_scale2, amax_acc, mode, sr);
     return finish_launch();
   }
-  const size_t nvec = n >> vec_shift<SRCK>();
-  const int impl = impl_for<SRCK>(mode);
-  Shape shape = shape_for(FAM_FQ);
-  if (impl == IMPL_TE || impl == IMPL_SR) shape.unroll = 2;
-  Walk walk;
-  const dim3 grid(grid_for(nvec, cus, shape, &walk)), block(shape.block);
-  dispatch_impl<SRCK>(impl, shape.unroll, [&](auto impl_c, auto u_c) {
-    constexpr int U = decltype(u_c)::value, IMPL = decltype(impl_c)::value;
-    if (codes)
-      hipLaunchKernelGGL((k_fake_quant<U, IMPL, true, SRCK>), grid, block, 0, st, src, dst, codes, n, scale, inv,
-                         d_scale2, amax_acc, mode, seed, enc_table_for<IMPL>(tb), tb.dec_lut, walk);
-    else
-      hipLaunchKernelGGL((k_fake_quant<U, IMPL, false, SRCK>), grid, block, 0, st, src, dst, codes, n, scale, inv,
-                         d_scale2, amax_acc, mode, seed, enc_table_for<IMPL>(tb), tb.dec_lut, walk);
-  });
+  launch_fake_quant_fast<SRCK>(src, dst, codes, n, d_scale2 ? scale_on_device(d_scale2) : scale_by_value(scale, inv),
+                               amax_acc, mode, sr, cus, tb, st);
   return finish_launch();
+}
+
+// amax over the fast path: PARTS = false accumulates into *out (cleared by the caller), PARTS = true writes
+// one partial maximum per workgroup to out[0 .. return value) (at most kMaxParts).
+// cached: ordinary loads, which leave the tensor in the last-level cache for a pass that follows.
+template <int SRCK, bool PARTS>
+uint32_t launch_amax_fast(const void* src, size_t n, uint32_t* out, bool cached, int cus, hipStream_t st) {
+  const size_t nvec = n >> vec_shift<SRCK>();
+  const Shape shape = shape_for(PARTS ? FAM_AMAX_PARTS : FAM_AMAX);
+  Walk walk;
+  const unsigned g = grid_for(nvec, cus, shape, &walk, PARTS ? kMaxParts : 0u);
+  const dim3 grid(g), block(shape.block);
+  dispatch_unroll(shape.unroll, [&](auto u_c) {
+    constexpr int U = decltype(u_c)::value;
+    if (cached) hipLaunchKernelGGL((k_amax<U, SRCK, false, PARTS>), grid, block, 0, st, src, n, out, walk);
+    else hipLaunchKernelGGL((k_amax<U, SRCK, true, PARTS>), grid, block, 0, st, src, n, out, walk);
+  });
+  return g;
 }
 
 template <int SRCK>
@@ -800,32 +1112,52 @@ hif8_status conv_amax(const void* src, size_t n, float* d_amax, hipStream_t st) 
     hipLaunchKernelGGL(k_amax_elem<SRCK>, dim3(grid_elem(n, cus)), dim3(256), 0, st, src, n, out);
     return finish_launch();
   }
-  const size_t nvec = n >> vec_shift<SRCK>();
-  const Shape shape = shape_for(FAM_AMAX);
-  Walk walk;
-  const dim3 grid(grid_for(nvec, cus, shape, &walk)), block(shape.block);
   // amax is normally followed by a cast of the same tensor: ordinary (cached) loads leave a tensor
   // that fits the 256 MB last-level cache there for the second pass; larger ones are streamed
   const size_t bytes = n * (SRCK == kSrcF32 ? 4 : 2);
   const int nt_knob = tune_amax_nt();
   const bool nt = nt_knob < 0 ? bytes > ((size_t)192 << 20) : nt_knob != 0;
-  dispatch_unroll(shape.unroll, [&](auto u_c) {
-    constexpr int U = decltype(u_c)::value;
-    if (nt) hipLaunchKernelGGL((k_amax<U, SRCK, true>), grid, block, 0, st, src, n, out, walk);
-    else hipLaunchKernelGGL((k_amax<U, SRCK, false>), grid, block, 0, st, src, n, out, walk);
-  });
+  launch_amax_fast<SRCK, false>(src, n, out, !nt, cus, st);
   return finish_launch();
 }
 
-template <int SRCK, bool ACC>
-void launch_multi_encode(const hif8_cast_item* d_items, uint32_t cnt, uint64_t total_tiles, const float* d_scale2,
-                         uint32_t* amax_acc, uint32_t mode, uint64_t seed, const DevTables& tb, hipStream_t st) {
-  const dim3 g2((unsigned)((total_tiles + kMultiTpwEncode - 1) / kMultiTpwEncode)), blk(kMultiBlock);
-  auto go = [&](auto impl_c) {
-    constexpr int IMPL = decltype(impl_c)::value;
-    hipLaunchKernelGGL((k_multi_encode<IMPL, SRCK, ACC>), g2, blk, 0, st, d_items, cnt, total_tiles, d_scale2, amax_acc, mode,
-                       seed, enc_table_for<IMPL>(tb));
-  };
+// Per-tensor scaling in one call (Sec. 5: amax, scale factor, cast): pass 1 leaves one partial maximum per
+// workgroup in `parts` (ordinary loads, so a tensor that fits the last-level cache stays there), pass 2 is the
+// cast -- codes only when dst is null, else the fused round trip with optional codes -- whose workgroups reduce
+// the partial maxima and derive the scale themselves.  Two launches; no clearing launch, no atomics, no
+// separate scale launch.  Inputs that miss the fast path's alignment take the separate calls.
+template <int SRCK>
+hif8_status conv_quantize_tensor(const void* src, void* dst, uint8_t* codes, size_t n, float target, int pow2,
+                                 uint32_t mode, float* d_amax, float* d_scale2, uint32_t* parts, const SrArg* sr_or_null,
+                                 hipStream_t st) {
+  if (!valid_mode(mode)) return HIF8_ERR_MODE;
+  if (!(target > 0.0f) || std::isinf(target)) return HIF8_ERR_ARG;
+  if (!d_amax || !d_scale2 || !parts) return HIF8_ERR_NULL;
+  if (n != 0 && (!src || (!dst && !codes))) return HIF8_ERR_NULL;
+  int cus = 0;
+  DevTables tb;
+  hif8_status s = ensure_init(&cus, &tb);
+  if (s != HIF8_OK) return s;
+  const bool fast = n != 0 && (dst ? fake_quant_fast_ok<SRCK>(src, dst, codes) : encode_fast_ok<SRCK>(src, codes));
+  if (!fast) {
+    s = conv_amax<SRCK>(src, n, d_amax, st);
+    if (s != HIF8_OK) return s;
+    s = launch_scale_from_amax(d_amax, d_scale2, 1u, target, pow2, st);
+    if (s != HIF8_OK || n == 0) return s;
+    return dst ? conv_fake_quant<SRCK>(src, dst, codes, n, 1.0f, d_scale2, nullptr, mode, sr_or_null, st)
+               : conv_encode<SRCK>(src, codes, n, 1.0f, d_scale2, nullptr, mode, sr_or_null, st);
+  }
+  const SrArg sr = sr_or_null ? *sr_or_null : SrArg{sr_seed(), 0};
+  const uint32_t nparts = launch_amax_fast<SRCK, true>(src, n, parts, true, cus, st);
+  const ScaleArg sa{1.0f, 1.0f, nullptr, parts, nparts, target, pow2, d_amax, d_scale2};
+  if (dst) launch_fake_quant_fast<SRCK>(src, dst, codes, n, sa, nullptr, mode, sr, cus, tb, st);
+  else launch_encode_fast<SRCK>(src, codes, n, sa, nullptr, mode, sr, cus, tb, st);
+  return finish_launch();
+}
+
+// Calls go(integral_constant IMPL) for the implementation a multi-tensor cast under `mode` uses.
+template <int SRCK, typename F>
+inline void dispatch_multi_impl(uint32_t mode, F&& go) {
   using std::integral_constant;
   switch (impl_for<SRCK>(mode)) {
     case IMPL_HR16:
@@ -836,6 +1168,17 @@ void launch_multi_encode(const hif8_cast_item* d_items, uint32_t cnt, uint64_t t
     case IMPL_SR: go(integral_constant<int, IMPL_SR>{}); break;
     default: go(integral_constant<int, IMPL_TA_LUT>{}); break;
   }
+}
+
+template <int SRCK, bool ACC>
+void launch_multi_encode(const hif8_cast_item* d_items, uint32_t cnt, uint64_t total_tiles, const float* d_scale2,
+                         uint32_t* amax_acc, uint32_t mode, uint64_t seed, const DevTables& tb, hipStream_t st) {
+  const dim3 g2((unsigned)((total_tiles + kMultiTpwEncode - 1) / kMultiTpwEncode)), blk(kMultiBlock);
+  dispatch_multi_impl<SRCK>(mode, [&](auto impl_c) {
+    constexpr int IMPL = decltype(impl_c)::value;
+    hipLaunchKernelGGL((k_multi_encode<IMPL, SRCK, ACC>), g2, blk, 0, st, d_items, cnt, total_tiles, d_scale2, amax_acc, mode,
+                       seed, enc_table_for<IMPL>(tb));
+  });
 }
 
 // Multi-tensor cast with the scales already on the device (delayed scaling): one launch.
@@ -856,30 +1199,111 @@ hif8_status conv_multi_encode_ds(const hif8_cast_item* d_items, size_t count, ui
   return finish_launch();
 }
 
+// Multi-tensor cast with fresh per-tensor scales.  With the planned items also at hand on the host the list is cut
+// into groups of whole tensors of at most `group_bytes` of source each (a larger tensor is a group of its own), and
+// the stages [amax of group g+1 | cast of group g] are enqueued back to back, one launch each: the cast of a group
+// then finds its source in the 256 MB last-level cache instead of reading it from HBM a second time.  Without the
+// host copy: amax of every tensor, then the scales, then the cast of every tensor (four launches).
 template <int SRCK>
-hif8_status conv_multi_cast(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,
-                            float* d_amax, float* d_scale2, float target, int pow2, uint32_t mode,
+hif8_status conv_multi_cast(const hif8_cast_item* host_items_or_null, const hif8_cast_item* d_items, size_t count,
+                            uint64_t total_tiles, float* d_amax, float* d_scale2, float target, int pow2, uint32_t mode,
                             hipStream_t st) {
   if (!valid_mode(mode)) return HIF8_ERR_MODE;
   if (!(target > 0.0f) || std::isinf(target)) return HIF8_ERR_ARG;
   if (count == 0) return HIF8_OK;
   if (!d_items || !d_amax || !d_scale2) return HIF8_ERR_NULL;
   if (count > 0xFFFFFFu) return HIF8_ERR_ARG;
+  if (host_items_or_null) {  // the host copy must be the planned array: tile counts consistent with total_tiles
+    uint64_t tiles = 0;
+    for (size_t i = 0; i < count; ++i) {
+      if (host_items_or_null[i].first_tile != tiles) return HIF8_ERR_ARG;
+      tiles += plan_item_tiles(host_items_or_null[i].n, SRCK != kSrcF32);
+    }
+    if (tiles != total_tiles) return HIF8_ERR_ARG;
+  }
   DevTables tb;
-  hif8_status s = ensure_init(nullptr, &tb);
+  int cus = 0;
+  hif8_status s = ensure_init(&cus, &tb);
   if (s != HIF8_OK) return s;
   const uint64_t seed = sr_seed();
   const uint32_t cnt = (uint32_t)count;
   uint32_t* am = reinterpret_cast<uint32_t*>(d_amax);
   s = launch_fill_u32(am, 0u, cnt, st);
   if (s != HIF8_OK) return s;
-  if (total_tiles != 0) {
-    const unsigned g1 = (unsigned)((total_tiles + kMultiTpwAmax - 1) / kMultiTpwAmax);
-    hipLaunchKernelGGL(k_multi_amax<SRCK>, dim3(g1), dim3(kMultiBlock), 0, st, d_items, cnt, total_tiles, am);
+  if (!host_items_or_null) {
+    if (total_tiles != 0) {
+      const unsigned g1 = (unsigned)((total_tiles + kMultiTpwAmax - 1) / kMultiTpwAmax);
+      hipLaunchKernelGGL(k_multi_amax<SRCK>, dim3(g1), dim3(kMultiBlock), 0, st, d_items, cnt, total_tiles, am);
+    }
+    s = launch_scale_from_amax(d_amax, d_scale2, cnt, target, pow2, st);
+    if (s != HIF8_OK) return s;
+    if (total_tiles != 0) launch_multi_encode<SRCK, false>(d_items, cnt, total_tiles, d_scale2, nullptr, mode, seed, tb, st);
+    return finish_launch();
   }
-  s = launch_scale_from_amax(d_amax, d_scale2, cnt, target, pow2, st);
-  if (s != HIF8_OK) return s;
-  if (total_tiles != 0) launch_multi_encode<SRCK, false>(d_items, cnt, total_tiles, d_scale2, nullptr, mode, seed, tb, st);
+  // tensors without elements own no tile, hence no workgroup that would write their pair: with every amax
+  // still zero, one small launch sets every pair to {1, 1}; the stages overwrite those of the other tensors
+  bool any_empty = false;
+  for (size_t k = 0; k < count; ++k) any_empty = any_empty || host_items_or_null[k].n == 0;
+  if (any_empty) {
+    s = launch_scale_from_amax(d_amax, d_scale2, cnt, target, pow2, st);
+    if (s != HIF8_OK) return s;
+  }
+  // group-wise stages: stage k gathers the amax of group k and casts group k - 1.  A group is a run of whole
+  // tensors (empty ones skipped): at least one, more while they fit group_bytes and kStageItems.
+  const uint64_t group_bytes = multi_group_bytes();
+  const uint64_t esize = SRCK == kSrcF32 ? 4 : 2;
+  StageArgs sg;
+  std::memset(&sg, 0, sizeof(sg));
+  const bool overlap = multi_stage_overlap();
+  const uint32_t am_cap = (uint32_t)cus * (uint32_t)shape_for(FAM_MULTI_STAGE).wg_per_cu;
+  size_t i = 0;
+  for (;;) {
+    // the group gathered by the previous stage is cast by this one
+    sg.n_enc = sg.n_am;
+    sg.enc_wgs = 0;
+    for (uint32_t k = 0; k < sg.n_enc; ++k) {
+      sg.enc[k] = sg.am[k];
+      sg.enc[k].wg_first = sg.enc_wgs;
+      sg.enc_wgs += stage_item_wgs<SRCK>(sg.enc[k].n, kStageVec);
+    }
+    sg.n_am = 0;
+    sg.am_chunks = 0;
+    uint64_t bytes = 0;
+    while (i < count && sg.n_am < (uint32_t)kStageItems) {
+      const hif8_cast_item& h = host_items_or_null[i];
+      if (h.n == 0) { ++i; continue; }
+      if (sg.n_am != 0 && bytes + h.n * esize > group_bytes) break;
+      const uint32_t chunks = stage_item_wgs<SRCK>(h.n, kStageVecAmax);
+      if (stage_item_wgs<SRCK>(h.n, kStageVec) > 0x3FFFFFFFu) return HIF8_ERR_ARG;
+      if (sg.n_am != 0 && (uint64_t)sg.am_chunks + chunks > 0x3FFFFFFFu) break;
+      sg.am[sg.n_am] = StageItem{h.src, h.dst, h.n, sg.am_chunks, (uint32_t)i};
+      sg.am_chunks += chunks;
+      sg.n_am += 1;
+      bytes += h.n * esize;
+      ++i;
+    }
+    sg.am_wgs = sg.am_chunks < am_cap ? sg.am_chunks : am_cap;
+    if (sg.n_enc == 0 && sg.n_am == 0) break;  // nothing left to gather, nothing left to cast
+    if ((uint64_t)sg.enc_wgs + sg.am_wgs > 0x7FFFFFFFull) return HIF8_ERR_ARG;
+    auto launch = [&](const StageArgs& a) {
+      if (a.enc_wgs + a.am_wgs == 0) return;
+      dispatch_multi_impl<SRCK>(mode, [&](auto impl_c) {
+        constexpr int IMPL = decltype(impl_c)::value;
+        hipLaunchKernelGGL((k_group_stage<IMPL, SRCK>), dim3(a.enc_wgs + a.am_wgs), dim3(kStageBlock), 0, st, a, am,
+                           d_scale2, target, pow2, mode, seed, enc_table_for<IMPL>(tb));
+      });
+    };
+    if (!overlap) {  // the cast of a group, then the amax of the next, as two launches
+      StageArgs a = sg;
+      a.n_am = 0; a.am_wgs = 0; a.am_chunks = 0;
+      launch(a);
+      a = sg;
+      a.n_enc = 0; a.enc_wgs = 0;
+      launch(a);
+    } else {
+      launch(sg);
+    }
+  }
   return finish_launch();
 }
 
@@ -889,13 +1313,15 @@ hif8_status conv_multi_cast(const hif8_cast_item* d_items, size_t count, uint64_
 #define HIF8_INSTANTIATE_CONV(K)                                                                         \
   namespace hif8conv {                                                                                   \
   template hif8_status conv_encode<K>(const void*, uint8_t*, size_t, float, const float*, float*,        \
-                                      uint32_t, hipStream_t);                                            \
+                                      uint32_t, const SrArg*, hipStream_t);                              \
   template hif8_status conv_decode<K>(const uint8_t*, void*, size_t, float, const float*, hipStream_t);  \
   template hif8_status conv_fake_quant<K>(const void*, void*, uint8_t*, size_t, float, const float*,     \
-                                          float*, uint32_t, hipStream_t);                                \
+                                          float*, uint32_t, const SrArg*, hipStream_t);                  \
   template hif8_status conv_amax<K>(const void*, size_t, float*, hipStream_t);                           \
-  template hif8_status conv_multi_cast<K>(const hif8_cast_item*, size_t, uint64_t, float*, float*,       \
-                                          float, int, uint32_t, hipStream_t);                            \
+  template hif8_status conv_quantize_tensor<K>(const void*, void*, uint8_t*, size_t, float, int, uint32_t, \
+                                               float*, float*, uint32_t*, const SrArg*, hipStream_t);    \
+  template hif8_status conv_multi_cast<K>(const hif8_cast_item*, const hif8_cast_item*, size_t, uint64_t, \
+                                          float*, float*, float, int, uint32_t, hipStream_t);            \
   template hif8_status conv_multi_encode_ds<K>(const hif8_cast_item*, size_t, uint64_t, const float*,    \
                                                float*, uint32_t, hipStream_t);                           \
   }

@@ -138,19 +138,37 @@ __device__ __forceinline__ uint32_t encode_alu(uint32_t ybits, uint32_t mode) {
 // for clarity: these are not on the throughput path.
 // ------------------------------------------------------------------------------------
 
-// MurmurHash3's 32-bit finaliser
-__host__ __device__ __forceinline__ uint32_t fmix32(uint32_t x) {
-  x ^= x >> 16; x *= 0x85EBCA6Bu; x ^= x >> 13; x *= 0xC2B2AE35u; x ^= x >> 16;
+// Threshold generator of standard SR (Sec. 3.2 asks for one uniform random number per element and names no
+// source; a counter-based hash supplies it: no state, reproducible, independent of the launch shape).
+// Threshold of element `index` under `seed`:
+//   key pair   (k1, k2) = low and high half of splitmix64's output function applied to
+//              seed + 0x9E3779B97F4A7C15 * (hi32(index) + 1): a non-linear function of the whole seed,
+//              constant over 2^32 consecutive elements (the kernels compute it once per workgroup and again
+//              only where a tensor crosses a multiple of 2^32 elements);
+//   threshold  MurmurHash3's 32-bit finaliser over lo32(index) ^ k1, with k2 added between its two
+//              multiplications: ten vector instructions per element.
+// Two seeds give two different functions of the index, not one sequence in another order.
+struct SrKey {
+  uint32_t k1, k2;
+};
+__host__ __device__ __forceinline__ SrKey sr_key(uint64_t seed, uint32_t index_hi) {
+  uint64_t z = seed + 0x9E3779B97F4A7C15ull * ((uint64_t)index_hi + 1ull);
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  z = z ^ (z >> 31);
+  SrKey k;
+  k.k1 = (uint32_t)z;
+  k.k2 = (uint32_t)(z >> 32);
+  return k;
+}
+__host__ __device__ __forceinline__ uint32_t sr_hash(uint32_t index_lo, const SrKey& k) {
+  uint32_t x = index_lo ^ k.k1;
+  x ^= x >> 16; x *= 0x85EBCA6Bu; x += k.k2;
+  x ^= x >> 13; x *= 0xC2B2AE35u; x ^= x >> 16;
   return x;
 }
-// Threshold of element `index` under `seed`: one finaliser round over the low index word xor a key that
-// depends on the seed and on the high index word only (constant over 2^32 consecutive elements, so the
-// kernels compute it once per vector).
-__host__ __device__ __forceinline__ uint32_t sr_key(uint64_t seed, uint32_t index_hi) {
-  return fmix32((uint32_t)(seed >> 32) + index_hi * 0x9E3779B9u) ^ (uint32_t)seed;
-}
 __host__ __device__ __forceinline__ uint32_t sr_threshold(uint64_t seed, uint64_t index) {
-  return fmix32((uint32_t)index ^ sr_key(seed, (uint32_t)(index >> 32)));
+  return sr_hash((uint32_t)index, sr_key(seed, (uint32_t)(index >> 32)));
 }
 
 // Rounded pattern of magnitude `a` (not NaN) under rounding method rm (any of the five), in

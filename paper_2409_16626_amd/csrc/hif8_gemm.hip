@@ -20,6 +20,7 @@
 #include <mutex>
 
 #include "hif8.h"
+#include "hif8_diag.h"
 #include "hif8_conv_api.hpp"
 #include "hif8_device.hpp"
 #include "hif8_gemm_common.hpp"
@@ -373,13 +374,13 @@ static hif8_status calibrate_layer(const void* a, const void* w, const float* o_
   hif8_status s = launch_fill_u32(reinterpret_cast<uint32_t*>(d_err), 0u, 2u * (uint32_t)(ea_count * ew_count), st);
   if (s != HIF8_OK) return s;
   for (int i = 0; i < ea_count; ++i) {
-    s = hif8conv::conv_encode<SRCK>(a, ws_codes, M * K, std::ldexp(1.0f, ea_lo + i), nullptr, nullptr, mode, st);
+    s = hif8conv::conv_encode<SRCK>(a, ws_codes, M * K, std::ldexp(1.0f, ea_lo + i), nullptr, nullptr, mode, nullptr, st);
     if (s != HIF8_OK) return s;
     s = expand_rows(ws_codes, M, K, ws_a + a_elems * i, ld, st);
     if (s != HIF8_OK) return s;
   }
   for (int j = 0; j < ew_count; ++j) {
-    s = hif8conv::conv_encode<SRCK>(w, ws_codes, N * K, std::ldexp(1.0f, ew_lo + j), nullptr, nullptr, mode, st);
+    s = hif8conv::conv_encode<SRCK>(w, ws_codes, N * K, std::ldexp(1.0f, ew_lo + j), nullptr, nullptr, mode, nullptr, st);
     if (s != HIF8_OK) return s;
     s = expand_rows(ws_codes, N, K, ws_w + w_elems * j, ld, st);
     if (s != HIF8_OK) return s;

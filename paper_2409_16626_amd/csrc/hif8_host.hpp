@@ -31,11 +31,13 @@ struct Shape {
   int tiles_per_wg;
   int wg_per_cu;
 };
-enum Family { FAM_ENC32_TA, FAM_ENC32_HR, FAM_ENC16, FAM_FQ, FAM_DEC, FAM_AMAX, FAM_DIAG, FAM_CALIB, FAM_COUNT };
+enum Family { FAM_ENC32_TA, FAM_ENC32_HR, FAM_ENC16, FAM_FQ, FAM_DEC, FAM_AMAX, FAM_DIAG, FAM_CALIB, FAM_AMAX_PARTS, FAM_MULTI_STAGE, FAM_COUNT };
 
 Shape shape_for(Family f);
 int tune_ta_impl();   // 0 = table, 1 = ALU
 int tune_amax_nt();   // 1 = non-temporal loads in amax, 0 = cached loads, -1 = by tensor size
+uint64_t multi_group_bytes();  // source bytes per group of the group-wise multi-tensor cast
+bool multi_stage_overlap();  // true: one launch gathers the amax of a group and casts the previous one
 uint64_t sr_seed();   // seed of the standard-SR threshold generator in effect now
 
 bool hip_ok(hipError_t e);  // records a failure for hif8_last_hip_error()
@@ -46,8 +48,9 @@ inline bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintp
 bool valid_mode(uint32_t mode);
 bool valid_scale(float scale, float* inv_out);  // scale and fl32(1/scale) both finite and positive
 
-// grid size and tile walk for nvec vector units under a launch shape
-unsigned grid_for(size_t nvec, int cus, const Shape& sh, hif8dev::Walk* walk);
+// grid size and tile walk for nvec vector units under a launch shape; max_grid != 0 caps the number of
+// workgroups (a one-shot grid then gives every workgroup more consecutive tiles)
+unsigned grid_for(size_t nvec, int cus, const Shape& sh, hif8dev::Walk* walk, unsigned max_grid = 0);
 unsigned grid_elem(size_t n, int cus);
 
 // small utility launches shared by the translation units

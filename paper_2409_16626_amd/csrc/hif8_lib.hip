@@ -11,6 +11,7 @@
 #include <mutex>
 
 #include "hif8.h"
+#include "hif8_diag.h"
 #include "hif8_conv_api.hpp"
 #include "hif8_device.hpp"
 #include "hif8_host.hpp"
@@ -67,18 +68,21 @@ __global__ void k_scale_from_amax(const float* d_amax, float* d_scale2, uint32_t
   d_scale2[1] = 1.0f / s;
 }
 
-// diagnostic stream kernel: read 16 B per lane, write the first OUT bytes of it
+// diagnostic stream kernel: read 16 B per lane, write the first OUT bytes of it (OUT = 0: read only)
 template <int U, int OUT>
 __global__ void __launch_bounds__(1024)
 k_diag_stream(const uint4* __restrict__ src, void* __restrict__ dst, size_t nvec, Walk walk) {
+  uint32_t acc = 0;
   tile_loop<U, uint4>(
       nvec, walk, [&](size_t idx) { return ld_stream(src + idx); },
       [&](size_t idx, const uint4& v) {
-        if (OUT == 4) st_stream(reinterpret_cast<uint32_t*>(dst) + idx, v.x);
+        if (OUT == 0) acc |= (v.x ^ v.y) & (v.z ^ v.w);
+        else if (OUT == 4) st_stream(reinterpret_cast<uint32_t*>(dst) + idx, v.x);
         else if (OUT == 8) st_stream(reinterpret_cast<uint2*>(dst) + idx, make_uint2(v.x, v.y));
         else st_stream(reinterpret_cast<uint4*>(dst) + idx, v);
       },
       []() {});
+  if (OUT == 0 && dst && acc == 0xFFFFFFFFu && threadIdx.x == 0xFFFFu) *reinterpret_cast<uint32_t*>(dst) = acc;  // keeps the loads alive
 }
 
 // ====================================================================================
@@ -105,6 +109,8 @@ const Shape kDefaultShape[FAM_COUNT] = {
     {1024, 2, 0, 1},  // amax
     {512, 1, 2, 4},   // diagnostic stream
     {512, 2, 2, 4},   // calibration sweeps
+    {1024, 2, 0, 1},  // amax that leaves per-workgroup maxima (hif8_quantize_tensor_*)
+    {512, 8, 0, 1},   // group-wise multi-tensor cast: only wg_per_cu (amax workgroups per CU of a stage) is used
 };
 
 // user overrides; -1 = use the family default
@@ -115,7 +121,11 @@ struct Tuning {
   int ta_impl = 0;
   int tiles_per_wg = -1;
   int amax_nt = -1;  // -1: by size
+  int group_mib = 96;
+  int family = -1;  // kernel family the shape overrides apply to; -1: all
+  int stage_overlap = 1;
 };
+// Process-wide; written only by hif8_set_tuning (a benchmarking call, documented as not thread-safe).
 Tuning g_tune;
 std::atomic<uint64_t> g_sr_seed{0};
 
@@ -129,6 +139,7 @@ DevTables g_tables[kMaxDevices] = {};
 
 Shape shape_for(Family f) {
   Shape s = kDefaultShape[f];
+  if (g_tune.family >= 0 && g_tune.family != (int)f) return s;
   if (g_tune.block >= 0) s.block = g_tune.block;
   if (g_tune.unroll >= 0) s.unroll = g_tune.unroll;
   if (g_tune.tiles_per_wg >= 0) s.tiles_per_wg = g_tune.tiles_per_wg;
@@ -137,6 +148,8 @@ Shape shape_for(Family f) {
 }
 int tune_ta_impl() { return g_tune.ta_impl; }
 int tune_amax_nt() { return g_tune.amax_nt; }
+uint64_t multi_group_bytes() { return (uint64_t)g_tune.group_mib << 20; }
+bool multi_stage_overlap() { return g_tune.stage_overlap != 0; }
 uint64_t sr_seed() { return g_sr_seed.load(std::memory_order_relaxed); }
 
 bool hip_ok(hipError_t e) {
@@ -195,17 +208,19 @@ bool valid_scale(float scale, float* inv_out) {
   return true;
 }
 
-unsigned grid_for(size_t nvec, int cus, const Shape& sh, Walk* walk) {
+unsigned grid_for(size_t nvec, int cus, const Shape& sh, Walk* walk, unsigned max_grid) {
   const size_t tile = (size_t)sh.block * (size_t)sh.unroll;
   size_t tiles = (nvec + tile - 1) / tile;
   if (tiles == 0) tiles = 1;  // block 0 still handles a ragged tail
   size_t grid;
   if (sh.tiles_per_wg > 0) {
-    const size_t tpw = (size_t)sh.tiles_per_wg;
+    size_t tpw = (size_t)sh.tiles_per_wg;
+    if (max_grid != 0 && (tiles + tpw - 1) / tpw > max_grid) tpw = (tiles + max_grid - 1) / max_grid;
     grid = (tiles + tpw - 1) / tpw;
     *walk = Walk{(uint32_t)tpw, 1u, (uint32_t)tpw};
   } else {
-    const size_t cap = (size_t)cus * (size_t)sh.wg_per_cu;
+    size_t cap = (size_t)cus * (size_t)sh.wg_per_cu;
+    if (max_grid != 0 && cap > max_grid) cap = max_grid;
     grid = tiles < cap ? tiles : cap;
     *walk = Walk{1u, (uint32_t)grid, (uint32_t)((tiles + grid - 1) / grid)};
   }
@@ -275,6 +290,18 @@ hif8_status hif8_set_tuning(int key, int value) {
       if (value < -1 || value > 1) return HIF8_ERR_ARG;
       g_tune.amax_nt = value;
       return HIF8_OK;
+    case HIF8_TUNE_GROUP_MIB:
+      if (value < 1 || value > 4096) return HIF8_ERR_ARG;
+      g_tune.group_mib = value;
+      return HIF8_OK;
+    case HIF8_TUNE_FAMILY:
+      if (value < -1 || value >= (int)FAM_COUNT) return HIF8_ERR_ARG;
+      g_tune.family = value;
+      return HIF8_OK;
+    case HIF8_TUNE_STAGE_OVERLAP:
+      if (value != 0 && value != 1) return HIF8_ERR_ARG;
+      g_tune.stage_overlap = value;
+      return HIF8_OK;
     default:
       return HIF8_ERR_ARG;
   }
@@ -288,6 +315,9 @@ int hif8_get_tuning(int key) {
     case HIF8_TUNE_TA_IMPL: return g_tune.ta_impl;
     case HIF8_TUNE_TILES_PER_WG: return g_tune.tiles_per_wg;
     case HIF8_TUNE_AMAX_NT: return g_tune.amax_nt;
+    case HIF8_TUNE_GROUP_MIB: return g_tune.group_mib;
+    case HIF8_TUNE_FAMILY: return g_tune.family;
+    case HIF8_TUNE_STAGE_OVERLAP: return g_tune.stage_overlap;
     default: return -1;
   }
 }
@@ -306,7 +336,7 @@ hif8_status hif8_scale_from_amax(const float* d_amax, float* d_scale2, float tar
   }                                                                                                      \
   hif8_status hif8_encode_##SFX(const T* src, uint8_t* dst, size_t n, float scale, uint32_t mode,        \
                                 hif8_stream_t stream) {                                                  \
-    return conv_encode<K>(src, dst, n, scale, nullptr, nullptr, mode, (hipStream_t)stream);              \
+    return conv_encode<K>(src, dst, n, scale, nullptr, nullptr, mode, nullptr, (hipStream_t)stream);     \
   }                                                                                                      \
   hif8_status hif8_decode_##SFX(const uint8_t* src, T* dst, size_t n, float scale,                       \
                                 hif8_stream_t stream) {                                                  \
@@ -314,12 +344,13 @@ hif8_status hif8_scale_from_amax(const float* d_amax, float* d_scale2, float tar
   }                                                                                                      \
   hif8_status hif8_fake_quant_##SFX(const T* src, T* dst, uint8_t* codes, size_t n, float scale,         \
                                     uint32_t mode, hif8_stream_t stream) {                               \
-    return conv_fake_quant<K>(src, dst, codes, n, scale, nullptr, nullptr, mode, (hipStream_t)stream);   \
+    return conv_fake_quant<K>(src, dst, codes, n, scale, nullptr, nullptr, mode, nullptr,                \
+                              (hipStream_t)stream);                                                      \
   }                                                                                                      \
   hif8_status hif8_encode_##SFX##_ds(const T* src, uint8_t* dst, size_t n, const float* d_scale2,        \
                                      float* d_amax_acc, uint32_t mode, hif8_stream_t stream) {           \
     if (!d_scale2) return HIF8_ERR_NULL;                                                                 \
-    return conv_encode<K>(src, dst, n, 1.0f, d_scale2, d_amax_acc, mode, (hipStream_t)stream);           \
+    return conv_encode<K>(src, dst, n, 1.0f, d_scale2, d_amax_acc, mode, nullptr, (hipStream_t)stream);  \
   }                                                                                                      \
   hif8_status hif8_decode_##SFX##_ds(const uint8_t* src, T* dst, size_t n, const float* d_scale2,        \
                                      hif8_stream_t stream) {                                             \
@@ -330,14 +361,35 @@ hif8_status hif8_scale_from_amax(const float* d_amax, float* d_scale2, float tar
                                          const float* d_scale2, float* d_amax_acc, uint32_t mode,        \
                                          hif8_stream_t stream) {                                         \
     if (!d_scale2) return HIF8_ERR_NULL;                                                                 \
-    return conv_fake_quant<K>(src, dst, codes, n, 1.0f, d_scale2, d_amax_acc, mode,                      \
+    return conv_fake_quant<K>(src, dst, codes, n, 1.0f, d_scale2, d_amax_acc, mode, nullptr,             \
                               (hipStream_t)stream);                                                      \
   }                                                                                                      \
-  hif8_status hif8_multi_cast_##SFX(const hif8_cast_item* d_items, size_t count, uint64_t total_tiles,   \
-                                    float* d_amax, float* d_scale2, float target, int pow2,              \
-                                    uint32_t mode, hif8_stream_t stream) {                               \
-    return conv_multi_cast<K>(d_items, count, total_tiles, d_amax, d_scale2, target, pow2, mode,         \
+  hif8_status hif8_encode_##SFX##_sr(const T* src, uint8_t* dst, size_t n, float scale, uint32_t mode,   \
+                                     uint64_t seed, uint64_t index_base, hif8_stream_t stream) {         \
+    const SrArg sr{seed, index_base};                                                                    \
+    return conv_encode<K>(src, dst, n, scale, nullptr, nullptr, mode, &sr, (hipStream_t)stream);         \
+  }                                                                                                      \
+  hif8_status hif8_fake_quant_##SFX##_sr(const T* src, T* dst, uint8_t* codes, size_t n, float scale,    \
+                                         uint32_t mode, uint64_t seed, uint64_t index_base,              \
+                                         hif8_stream_t stream) {                                         \
+    const SrArg sr{seed, index_base};                                                                    \
+    return conv_fake_quant<K>(src, dst, codes, n, scale, nullptr, nullptr, mode, &sr,                    \
                               (hipStream_t)stream);                                                      \
+  }                                                                                                      \
+  hif8_status hif8_quantize_tensor_##SFX(const T* src, T* dst, uint8_t* codes, size_t n, float target,   \
+                                         int pow2, uint32_t mode, float* d_amax, float* d_scale2,        \
+                                         void* workspace, size_t workspace_bytes,                        \
+                                         hif8_stream_t stream) {                                         \
+    if (workspace && (workspace_bytes < hif8_quantize_workspace_bytes() || !aligned_to(workspace, 4)))   \
+      return HIF8_ERR_ARG;                                                                               \
+    return conv_quantize_tensor<K>(src, dst, codes, n, target, pow2, mode, d_amax, d_scale2,             \
+                                   reinterpret_cast<uint32_t*>(workspace), nullptr, (hipStream_t)stream);\
+  }                                                                                                      \
+  hif8_status hif8_multi_cast_##SFX(const hif8_cast_item* host_items, const hif8_cast_item* d_items,     \
+                                    size_t count, uint64_t total_tiles, float* d_amax, float* d_scale2,  \
+                                    float target, int pow2, uint32_t mode, hif8_stream_t stream) {       \
+    return conv_multi_cast<K>(host_items, d_items, count, total_tiles, d_amax, d_scale2, target, pow2,   \
+                              mode, (hipStream_t)stream);                                                \
   }                                                                                                      \
   hif8_status hif8_multi_encode_##SFX##_ds(const hif8_cast_item* d_items, size_t count,                  \
                                            uint64_t total_tiles, const float* d_scale2,                  \
@@ -351,6 +403,8 @@ HIF8_DEFINE_KIND(bf16, uint16_t, kSrcBF16)
 HIF8_DEFINE_KIND(f16, uint16_t, kSrcF16)
 #undef HIF8_DEFINE_KIND
 
+size_t hif8_quantize_workspace_bytes(void) { return (size_t)kMaxParts * sizeof(uint32_t); }
+
 hif8_status hif8_multi_plan(hif8_cast_item* host_items, size_t count, int src_is_16bit,
                             uint64_t* total_tiles_out) {
   if (!total_tiles_out || (!host_items && count != 0)) return HIF8_ERR_NULL;
@@ -361,10 +415,7 @@ hif8_status hif8_multi_plan(hif8_cast_item* host_items, size_t count, int src_is
     if (it.n != 0 && (!it.src || !it.dst)) return HIF8_ERR_NULL;
     if (!aligned_to(it.src, 16) || !aligned_to(it.dst, src_is_16bit ? 8 : 4)) return HIF8_ERR_ARG;
     it.first_tile = tiles;
-    const uint64_t nvec = src_is_16bit ? (it.n >> 3) : (it.n >> 2);
-    uint64_t t = (nvec + kMultiTileVec - 1) / kMultiTileVec;
-    if (t == 0 && it.n != 0) t = 1;
-    tiles += t;
+    tiles += plan_item_tiles(it.n, src_is_16bit != 0);
   }
   *total_tiles_out = tiles;
   return HIF8_OK;
@@ -372,9 +423,9 @@ hif8_status hif8_multi_plan(hif8_cast_item* host_items, size_t count, int src_is
 
 hif8_status hif8_diag_stream(const void* src, void* dst, size_t n_groups, int out_bytes,
                              hif8_stream_t stream) {
-  if (!src || !dst) return HIF8_ERR_NULL;
-  if (out_bytes != 4 && out_bytes != 8 && out_bytes != 16) return HIF8_ERR_ARG;
-  if (!aligned_to(src, 16) || !aligned_to(dst, (size_t)out_bytes)) return HIF8_ERR_ARG;
+  if (!src || (!dst && out_bytes != 0)) return HIF8_ERR_NULL;
+  if (out_bytes != 0 && out_bytes != 4 && out_bytes != 8 && out_bytes != 16) return HIF8_ERR_ARG;
+  if (!aligned_to(src, 16) || (out_bytes != 0 && !aligned_to(dst, (size_t)out_bytes))) return HIF8_ERR_ARG;
   if (n_groups == 0) return HIF8_OK;
   int cus = 0;
   hif8_status s = ensure_init(&cus, nullptr);
@@ -386,7 +437,8 @@ hif8_status hif8_diag_stream(const void* src, void* dst, size_t n_groups, int ou
   hipStream_t st = (hipStream_t)stream;
   dispatch_unroll(shape.unroll, [&](auto u_c) {
     constexpr int U = decltype(u_c)::value;
-    if (out_bytes == 4) hipLaunchKernelGGL((k_diag_stream<U, 4>), grid, block, 0, st, s4, dst, n_groups, walk);
+    if (out_bytes == 0) hipLaunchKernelGGL((k_diag_stream<U, 0>), grid, block, 0, st, s4, dst, n_groups, walk);
+    else if (out_bytes == 4) hipLaunchKernelGGL((k_diag_stream<U, 4>), grid, block, 0, st, s4, dst, n_groups, walk);
     else if (out_bytes == 8) hipLaunchKernelGGL((k_diag_stream<U, 8>), grid, block, 0, st, s4, dst, n_groups, walk);
     else hipLaunchKernelGGL((k_diag_stream<U, 16>), grid, block, 0, st, s4, dst, n_groups, walk);
   });

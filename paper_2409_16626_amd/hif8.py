@@ -22,8 +22,9 @@ FLAG_SAT = 0x10
 FLAG_NAN2ZERO = 0x20
 MAX_FINITE = 32768.0
 
-TUNE_BLOCK, TUNE_WG_PER_CU, TUNE_UNROLL, TUNE_TA_IMPL, TUNE_TILES_PER_WG, TUNE_AMAX_NT = 0, 1, 2, 3, 4, 5
-N_TUNE_KEYS = 6
+TUNE_BLOCK, TUNE_WG_PER_CU, TUNE_UNROLL, TUNE_TA_IMPL, TUNE_TILES_PER_WG, TUNE_AMAX_NT, TUNE_GROUP_MIB, TUNE_FAMILY, TUNE_STAGE_OVERLAP = 0, 1, 2, 3, 4, 5, 6, 7, 8
+N_TUNE_KEYS = 9
+(FAM_ENC32_TA, FAM_ENC32_HR, FAM_ENC16, FAM_FQ, FAM_DEC, FAM_AMAX, FAM_DIAG, FAM_CALIB, FAM_AMAX_PARTS, FAM_MULTI_STAGE) = range(10)
 
 _STATUS = {0: "HIF8_OK", -1: "HIF8_ERR_NULL", -2: "HIF8_ERR_MODE", -3: "HIF8_ERR_SCALE",
            -4: "HIF8_ERR_HIP", -5: "HIF8_ERR_ARG"}
@@ -63,7 +64,10 @@ _SIGS = {
     "hif8_encode_f16_ds": ([_vp, _vp, _sz, _vp, _vp, _u32, _vp], _i),
     "hif8_decode_f16_ds": ([_vp, _vp, _sz, _vp, _vp], _i),
     "hif8_fake_quant_f16_ds": ([_vp, _vp, _vp, _sz, _vp, _vp, _u32, _vp], _i),
-    "hif8_multi_cast_f16": ([_vp, _sz, ctypes.c_uint64, _vp, _vp, _f, _i, _u32, _vp], _i),
+    "hif8_multi_cast_f16": ([_vp, _vp, _sz, ctypes.c_uint64, _vp, _vp, _f, _i, _u32, _vp], _i),
+    "hif8_encode_f16_sr": ([_vp, _vp, _sz, _f, _u32, _u64, _u64, _vp], _i),
+    "hif8_fake_quant_f16_sr": ([_vp, _vp, _vp, _sz, _f, _u32, _u64, _u64, _vp], _i),
+    "hif8_quantize_tensor_f16": ([_vp, _vp, _vp, _sz, _f, _i, _u32, _vp, _vp, _vp, _sz, _vp], _i),
     "hif8_amax_f32": ([_vp, _sz, _vp, _vp], _i),
     "hif8_amax_bf16": ([_vp, _sz, _vp, _vp], _i),
     "hif8_scale_from_amax": ([_vp, _vp, _f, _i, _vp], _i),
@@ -80,11 +84,18 @@ _SIGS = {
     "hif8_fake_quant_f32_ds": ([_vp, _vp, _vp, _sz, _vp, _vp, _u32, _vp], _i),
     "hif8_fake_quant_bf16_ds": ([_vp, _vp, _vp, _sz, _vp, _vp, _u32, _vp], _i),
     "hif8_multi_plan": ([_vp, _sz, _i, _vp], _i),
-    "hif8_multi_cast_bf16": ([_vp, _sz, ctypes.c_uint64, _vp, _vp, _f, _i, _u32, _vp], _i),
+    "hif8_quantize_workspace_bytes": ([], _sz),
+    "hif8_multi_cast_bf16": ([_vp, _vp, _sz, ctypes.c_uint64, _vp, _vp, _f, _i, _u32, _vp], _i),
+    "hif8_encode_bf16_sr": ([_vp, _vp, _sz, _f, _u32, _u64, _u64, _vp], _i),
+    "hif8_fake_quant_bf16_sr": ([_vp, _vp, _vp, _sz, _f, _u32, _u64, _u64, _vp], _i),
+    "hif8_quantize_tensor_bf16": ([_vp, _vp, _vp, _sz, _f, _i, _u32, _vp, _vp, _vp, _sz, _vp], _i),
     "hif8_multi_encode_bf16_ds": ([_vp, _sz, ctypes.c_uint64, _vp, _vp, _u32, _vp], _i),
     "hif8_multi_encode_f32_ds": ([_vp, _sz, ctypes.c_uint64, _vp, _vp, _u32, _vp], _i),
     "hif8_multi_encode_f16_ds": ([_vp, _sz, ctypes.c_uint64, _vp, _vp, _u32, _vp], _i),
-    "hif8_multi_cast_f32": ([_vp, _sz, ctypes.c_uint64, _vp, _vp, _f, _i, _u32, _vp], _i),
+    "hif8_multi_cast_f32": ([_vp, _vp, _sz, ctypes.c_uint64, _vp, _vp, _f, _i, _u32, _vp], _i),
+    "hif8_encode_f32_sr": ([_vp, _vp, _sz, _f, _u32, _u64, _u64, _vp], _i),
+    "hif8_fake_quant_f32_sr": ([_vp, _vp, _vp, _sz, _f, _u32, _u64, _u64, _vp], _i),
+    "hif8_quantize_tensor_f32": ([_vp, _vp, _vp, _sz, _f, _i, _u32, _vp, _vp, _vp, _sz, _vp], _i),
     "hif8_scale_from_amax_n": ([_vp, _vp, _sz, _f, _i, _vp], _i),
     "hif8_scale_sweep_f32": ([_vp, _sz, _i, _i, _u32, _vp, _vp], _i),
     "hif8_scale_sweep_bf16": ([_vp, _sz, _i, _i, _u32, _vp, _vp], _i),
@@ -217,12 +228,6 @@ def hif8_fake_quant_f16_ds(src, dst, codes_or_none, n, d_scale2, rounding_mode=R
                                       _ptr(d_amax_accum), rounding_mode, _stream(stream)))
 
 
-def hif8_multi_cast_f16(d_items, count, total_tiles, d_amax, d_scale2, target=MAX_FINITE, pow2=0,
-                        rounding_mode=RM_TA, stream=None):
-    _check(lib.hif8_multi_cast_f16(_ptr(d_items), count, total_tiles, _ptr(d_amax), _ptr(d_scale2), target,
-                                   int(pow2), rounding_mode, _stream(stream)))
-
-
 def hif8_amax_f32(src, n, d_amax, stream=None):
     _check(lib.hif8_amax_f32(_ptr(src), n, _ptr(d_amax), _stream(stream)))
 
@@ -297,9 +302,19 @@ class CastItem(ctypes.Structure):
                 ("first_tile", ctypes.c_uint64)]
 
 
+class MultiPlan:
+    """A planned list of tensors: the hif8_cast_item array on the host (ctypes) and its device copy."""
+
+    def __init__(self, host_items, d_items, count, total_tiles):
+        self.host_items, self.d_items, self.count, self.total_tiles = host_items, d_items, count, total_tiles
+
+    def __iter__(self):   # (d_items, count, total_tiles), the arguments the launches take
+        return iter((self.d_items, self.count, self.total_tiles))
+
+
 def hif8_multi_plan(items, src_is_16bit=True):
-    """items: list of (src_ptr_or_tensor, dst_ptr_or_tensor, n).  Returns (device uint8 tensor
-    holding the planned hif8_cast_item array, count, total_tiles)."""
+    """items: list of (src_ptr_or_tensor, dst_ptr_or_tensor, n).  Returns a MultiPlan (it unpacks into
+    (device uint8 tensor holding the planned hif8_cast_item array, count, total_tiles))."""
     count = len(items)
     arr = (CastItem * max(count, 1))()
     for i, (src, dst, n) in enumerate(items):
@@ -311,19 +326,54 @@ def hif8_multi_plan(items, src_is_16bit=True):
                                ctypes.cast(ctypes.byref(total), ctypes.c_void_p)))
     raw = bytes(arr)[:count * ctypes.sizeof(CastItem)]
     d_items = torch.frombuffer(bytearray(raw), dtype=torch.uint8).cuda() if count else torch.empty(0, dtype=torch.uint8, device="cuda")
-    return d_items, count, total.value
+    return MultiPlan(arr, d_items, count, total.value)
 
 
-def hif8_multi_cast_bf16(d_items, count, total_tiles, d_amax, d_scale2, target=MAX_FINITE, pow2=0,
-                         rounding_mode=RM_TA, stream=None):
-    _check(lib.hif8_multi_cast_bf16(_ptr(d_items), count, total_tiles, _ptr(d_amax), _ptr(d_scale2), target,
-                                    int(pow2), rounding_mode, _stream(stream)))
+def _def_multi_cast(sfx):
+    fn = getattr(lib, "hif8_multi_cast_" + sfx)
+
+    def multi_cast(d_items, count, total_tiles, d_amax, d_scale2, target=MAX_FINITE, pow2=0, rounding_mode=RM_TA,
+                   stream=None, host_items=None):
+        """host_items: the planned array on the host (MultiPlan.host_items) -> group-wise schedule."""
+        hp = ctypes.cast(host_items, ctypes.c_void_p) if host_items is not None else None
+        _check(fn(hp, _ptr(d_items), count, total_tiles, _ptr(d_amax), _ptr(d_scale2), target, int(pow2), rounding_mode,
+                  _stream(stream)))
+
+    return multi_cast
 
 
-def hif8_multi_cast_f32(d_items, count, total_tiles, d_amax, d_scale2, target=MAX_FINITE, pow2=0,
-                        rounding_mode=RM_TA, stream=None):
-    _check(lib.hif8_multi_cast_f32(_ptr(d_items), count, total_tiles, _ptr(d_amax), _ptr(d_scale2), target,
-                                   int(pow2), rounding_mode, _stream(stream)))
+hif8_multi_cast_bf16 = _def_multi_cast("bf16")
+hif8_multi_cast_f32 = _def_multi_cast("f32")
+hif8_multi_cast_f16 = _def_multi_cast("f16")
+
+
+def hif8_quantize_workspace_bytes():
+    return lib.hif8_quantize_workspace_bytes()
+
+
+def _def_tensor_calls(sfx):
+    enc_sr, fq_sr = getattr(lib, "hif8_encode_%s_sr" % sfx), getattr(lib, "hif8_fake_quant_%s_sr" % sfx)
+    qt = getattr(lib, "hif8_quantize_tensor_" + sfx)
+
+    def encode_sr(src, dst, n, scale, rounding_mode, seed, index_base=0, stream=None):
+        _check(enc_sr(_ptr(src), _ptr(dst), n, scale, rounding_mode, seed, index_base, _stream(stream)))
+
+    def fake_quant_sr(src, dst, codes_or_none, n, scale, rounding_mode, seed, index_base=0, stream=None):
+        _check(fq_sr(_ptr(src), _ptr(dst), _ptr(codes_or_none), n, scale, rounding_mode, seed, index_base, _stream(stream)))
+
+    def quantize_tensor(src, dst_or_none, codes_or_none, n, d_amax, d_scale2, workspace, target=MAX_FINITE, pow2=0,
+                        rounding_mode=RM_TA, stream=None, workspace_bytes=None):
+        if workspace_bytes is None:
+            workspace_bytes = 0 if workspace is None or isinstance(workspace, int) else workspace.numel() * workspace.element_size()
+        _check(qt(_ptr(src), _ptr(dst_or_none), _ptr(codes_or_none), n, target, int(pow2), rounding_mode, _ptr(d_amax),
+                  _ptr(d_scale2), _ptr(workspace), workspace_bytes, _stream(stream)))
+
+    return encode_sr, fake_quant_sr, quantize_tensor
+
+
+hif8_encode_f32_sr, hif8_fake_quant_f32_sr, hif8_quantize_tensor_f32 = _def_tensor_calls("f32")
+hif8_encode_bf16_sr, hif8_fake_quant_bf16_sr, hif8_quantize_tensor_bf16 = _def_tensor_calls("bf16")
+hif8_encode_f16_sr, hif8_fake_quant_f16_sr, hif8_quantize_tensor_f16 = _def_tensor_calls("f16")
 
 
 def _def_multi_encode_ds(sfx):

@@ -6,10 +6,17 @@ import re
 from conftest import ROOT
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "hif8.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(hif8_[a-z0-9_]+)\s*\(", text)))
+def declared_symbols(header=None):
+    """Function names declared in include/*.h (or in one of the headers)."""
+    inc = os.path.join(ROOT, "include")
+    names = set()
+    for h in sorted(os.listdir(inc)) if header is None else [header]:
+        if not h.endswith(".h"):
+            continue
+        text = open(os.path.join(inc, h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names.update(re.findall(r"\b(hif8_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
@@ -21,6 +28,10 @@ def test_library_exports_every_declared_symbol():
         assert n in hif8.EXPORTED_SYMBOLS, "binding has no wrapper for " + n
         assert callable(getattr(hif8, n)), n
     assert hif8.hif8_version() >= 100
+    # the benchmarking surface lives in its own header, the method's calls in hif8.h
+    diag = set(declared_symbols("hif8_diag.h"))
+    assert diag == {"hif8_set_tuning", "hif8_get_tuning", "hif8_gemm_set_variant", "hif8_diag_stream"}
+    assert not diag & set(declared_symbols("hif8.h"))
 
 
 def test_argument_validation_happens_on_the_host():
@@ -88,6 +99,23 @@ def test_argument_validation_happens_on_the_host():
     assert L.hif8_gemm_expanded_f32(p, p, p, 16, 0, 64, 64, 1.0, 1.0, None) == OK
     assert L.hif8_diag_stream(p, p, 16, 5, None) == ARG
     assert L.hif8_diag_stream(p + 4, p, 16, 4, None) == ARG
+    assert L.hif8_diag_stream(p, None, 16, 4, None) == NULL
+    # casts with an explicit threshold stream
+    assert L.hif8_encode_f32_sr(p, p, 16, 1.0, 9, 1, 0, None) == MODE
+    assert L.hif8_encode_bf16_sr(None, p, 16, 1.0, 4, 1, 0, None) == NULL
+    assert L.hif8_fake_quant_f16_sr(p, p, None, 16, 0.0, 4, 1, 0, None) == SCALE
+    assert L.hif8_fake_quant_f32_sr(p, p, None, 0, 1.0, 4, 1, 1 << 40, None) == OK
+    # per-tensor scaling in one call
+    ws = L.hif8_quantize_workspace_bytes()
+    assert ws == 4096
+    assert L.hif8_quantize_tensor_bf16(p, p, p, 16, 32768.0, 0, 9, p, p, p, ws, None) == MODE
+    assert L.hif8_quantize_tensor_bf16(p, p, p, 16, 0.0, 0, 0, p, p, p, ws, None) == ARG
+    assert L.hif8_quantize_tensor_bf16(p, p, p, 16, 32768.0, 0, 0, p, p, p, ws - 1, None) == ARG     # workspace too small
+    assert L.hif8_quantize_tensor_f32(p, p, p, 16, 32768.0, 0, 0, p, p, p + 2, ws, None) == ARG      # misaligned workspace
+    assert L.hif8_quantize_tensor_f32(p, p, p, 16, 32768.0, 0, 0, p, p, None, 0, None) == NULL
+    assert L.hif8_quantize_tensor_f32(p, p, p, 16, 32768.0, 0, 0, None, p, p, ws, None) == NULL
+    assert L.hif8_quantize_tensor_f16(p, None, None, 16, 32768.0, 0, 0, p, p, p, ws, None) == NULL    # nothing to write
+    assert L.hif8_quantize_tensor_f16(None, p, p, 16, 32768.0, 0, 0, p, p, p, ws, None) == NULL
 
 
 def test_multi_plan_is_host_only():
@@ -107,8 +135,15 @@ def test_multi_plan_is_host_only():
     assert hif8.lib.hif8_multi_plan(p, 3, 1, tp) == -5
     arr[2].src = None
     assert hif8.lib.hif8_multi_plan(p, 3, 1, tp) == -1
-    assert hif8.lib.hif8_multi_cast_bf16(p, 0, 0, None, None, 32768.0, 0, 0, None) == 0
-    assert hif8.lib.hif8_multi_cast_bf16(p, 3, 4, None, None, 32768.0, 0, 9, None) == -2
+    assert hif8.lib.hif8_multi_cast_bf16(None, p, 0, 0, None, None, 32768.0, 0, 0, None) == 0
+    assert hif8.lib.hif8_multi_cast_bf16(None, p, 3, 4, None, None, 32768.0, 0, 9, None) == -2
+    # a host copy of the plan that does not match the tile count is refused before anything is enqueued
+    arr[2].src = 0x30000
+    assert hif8.lib.hif8_multi_plan(p, 3, 1, tp) == 0 and total.value == 3
+    d = 0x1000   # never dereferenced
+    assert hif8.lib.hif8_multi_cast_bf16(p, d, 3, 4, d, d, 32768.0, 0, 0, None) == -5
+    arr[1].first_tile = 1
+    assert hif8.lib.hif8_multi_cast_bf16(p, d, 3, 3, d, d, 32768.0, 0, 0, None) == -5
 
 
 def test_tuning_knobs():
@@ -119,7 +154,8 @@ def test_tuning_knobs():
     assert L.hif8_set_tuning(1, 0) == -5 and L.hif8_set_tuning(2, 3) == -5
     assert L.hif8_set_tuning(3, 2) == -5 and L.hif8_set_tuning(9, 1) == -5
     assert L.hif8_set_tuning(4, -2) == -5 and L.hif8_set_tuning(4, 5000) == -5 and L.hif8_set_tuning(5, 2) == -5 and L.hif8_set_tuning(5, -2) == -5
-    assert L.hif8_get_tuning(9) == -1
+    assert L.hif8_get_tuning(9) == -1 and L.hif8_set_tuning(8, 2) == -5 and L.hif8_set_tuning(7, 10) == -5 and L.hif8_set_tuning(7, -2) == -5
+    assert L.hif8_set_tuning(6, 0) == -5 and L.hif8_set_tuning(6, 5000) == -5 and L.hif8_get_tuning(6) == 96
     assert L.hif8_set_tuning(0, 256) == 0 and L.hif8_get_tuning(0) == 256
     for k, v in enumerate(saved):
         assert L.hif8_set_tuning(k, v) == 0

@@ -153,10 +153,22 @@ def np_fmix32(x):
 
 
 def np_threshold(seed, idx):
+    """The generator as the oracle's header states it, typed again in numpy (so that whole arrays of
+    thresholds can be formed quickly; test_sr_threshold_generator compares it with the C function)."""
     idx = np.asarray(idx, np.uint64)
-    key = np_fmix32((np.uint64(seed >> 32) + (idx >> np.uint64(32)) * np.uint64(0x9E3779B9)) & np.uint64(0xFFFFFFFF)) \
-        ^ np.uint64(seed & 0xFFFFFFFF)
-    return np_fmix32((idx & np.uint64(0xFFFFFFFF)) ^ key).astype(np.uint32)
+    m32 = np.uint64(0xFFFFFFFF)
+    with np.errstate(over="ignore"):
+        z = np.uint64(seed) + np.uint64(0x9E3779B97F4A7C15) * ((idx >> np.uint64(32)) + np.uint64(1))
+        z = (z ^ (z >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
+        z = (z ^ (z >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
+        z = z ^ (z >> np.uint64(31))
+    k1, k2 = z & m32, z >> np.uint64(32)
+    x = (idx & m32) ^ k1
+    x ^= x >> np.uint64(16); x = (x * np.uint64(0x85EBCA6B)) & m32
+    x = (x + k2) & m32
+    x ^= x >> np.uint64(13); x = (x * np.uint64(0xC2B2AE35)) & m32
+    x ^= x >> np.uint64(16)
+    return x.astype(np.uint32)
 
 
 def test_sr_threshold_generator():
@@ -198,6 +210,69 @@ def test_sr_threshold_generator_statistics():
     pairs = np.bincount(top[:-1] * 4 + top[1:], minlength=16)
     assert pairs.min() > 0.95 * (n - 1) / 16 and pairs.max() < 1.05 * (n - 1) / 16
 
+
+
+def _oracle_thresholds(seed, n, base=0):
+    return np.array([orc.sr_threshold(seed, base + i) for i in range(n)], np.uint32)
+
+
+def test_sr_seeds_are_different_draws_not_permutations():
+    """Sec. 3.2: standard SR draws one uniform random number per element.  Two seeds must therefore give
+    two draws, not one draw in another order: (a) the thresholds that fall into one aligned 16-element block
+    must differ as a multiset between seeds, (b) the number of carries over a constant tensor (a binomial
+    count) must vary from seed to seed with about the binomial spread, (c) no small index displacement d maps
+    the stream of seed s onto the stream of seed s ^ d."""
+    n = 1 << 12
+    base_seeds = (0, 7, 1234, 1 << 40)
+    for s in base_seeds:
+        a = np.sort(_oracle_thresholds(s, n).reshape(-1, 16), axis=1)
+        for s2 in (s + 1, s ^ 5, s + (1 << 32), s + (1 << 33) + 1):
+            b = np.sort(_oracle_thresholds(s2, n).reshape(-1, 16), axis=1)
+            same = int((a == b).all(axis=1).sum())
+            assert same == 0, (s, s2, same)
+    # (c) t(s, i) == t(s ^ d, i ^ d) would make seeds permutations of each other
+    for s in base_seeds:
+        t0 = _oracle_thresholds(s, 256)
+        for d in range(1, 64):
+            t1 = _oracle_thresholds(s ^ d, 256)
+            idx = np.arange(256) ^ d
+            assert int((t0 == t1[idx]).sum()) <= 1, (s, d)
+    # (b) 2^16 copies of 20.5 (between 20 and 24: discarded fraction 1/8): carries ~ Binomial(2^16, 1/8)
+    m = 1 << 16
+    x = np.full(m, 20.5, np.float32)
+    v = all_values()
+    sums = []
+    try:
+        for seed in range(16):
+            orc.set_sr_seed(seed)
+            sums.append(float(v[orc.encode_f32(x, 1.0, SR)].sum()))
+    finally:
+        orc.set_sr_seed(0)
+    carries = (np.array(sums) - 20.0 * m) / 4.0
+    sd = np.sqrt(m * 0.125 * 0.875)                      # 84.7
+    assert len(set(sums)) >= 14                           # not one value for every seed
+    assert np.all(np.abs(carries - m / 8) < 5 * sd)
+    assert 0.4 * sd < carries.std(ddof=1) < 2.0 * sd      # chi-square bounds for 15 degrees of freedom, wide
+
+
+def test_sr_index_base_continues_the_stream():
+    """A slice of a tensor cast with index base b uses the thresholds its elements have inside the tensor."""
+    rng = np.random.default_rng(7)
+    x = (rng.standard_normal(5000) * 3).astype(np.float32)
+    try:
+        orc.set_sr_seed(11)
+        whole = orc.encode_f32(x, 1.0, SR)
+        orc.set_sr_index_base(1234)
+        part = orc.encode_f32(x[1234:], 1.0, SR)
+        orc.set_sr_index_base((1 << 32) - 100)
+        hi = orc.encode_f32(x[:200], 1.0, SR)
+        t = np.array([orc.sr_threshold(11, (1 << 32) - 100 + i) for i in range(200)], np.uint32)
+        want = [orc.encode_one(float(x[i]), SR, 0, int(t[i])) for i in range(200)]
+    finally:
+        orc.set_sr_seed(0)
+        orc.set_sr_index_base(0)
+    assert np.array_equal(part, whole[1234:])
+    assert hi.tolist() == want
 
 def test_sr_matches_bit_level_rule_and_is_unbiased():
     rng = np.random.default_rng(54)
