@@ -285,6 +285,26 @@ hif8_status hif8_quantize_tensor_f16(const uint16_t* src, uint16_t* dst_or_null,
                                      void* workspace, size_t workspace_bytes, hif8_stream_t stream);
 
 /*
+ * hif8_quantize_tensor_* for callers that cannot provide (or allocate) a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same results as
+ * hif8_quantize_tensor_{f32,bf16,f16} (src_kind selects which); the partial maxima live in a 4 KiB
+ * array in static device memory of the library instead (one copy per GPU, held until the process
+ * ends).  The call allocates nothing and frees nothing.  Every call on a GPU shares that GPU's
+ * array: calls that overlap in time on one GPU (two streams, two threads) race and give wrong
+ * results -- serialise them, or use the workspace form.  n above HIF8_STATIC_MAX_ELEMENTS (2^32) is
+ * refused with HIF8_ERR_ARG, as is an unknown src_kind; other errors as hif8_quantize_tensor_*.
+ * src, dst_or_null: tensors of the kind src_kind names.
+ */
+#define HIF8_KIND_F32 0
+#define HIF8_KIND_BF16 1
+#define HIF8_KIND_F16 2
+#define HIF8_STATIC_MAX_ELEMENTS ((size_t)1 << 32)
+hif8_status hif8_quantize_tensor_static(const void* src, void* dst_or_null, uint8_t* codes_or_null,
+                                        size_t n, int src_kind, float target, int pow2,
+                                        uint32_t rounding_mode, float* d_amax, float* d_scale2,
+                                        hif8_stream_t stream);
+
+/*
  * Multi-tensor cast: per-tensor amax, scale and encode for a whole list of tensors in a few
  * launches instead of four per tensor -- the per-tensor scaling recipe of Sec. 5 applied to every
  * weight (or activation) tensor of a model at once.

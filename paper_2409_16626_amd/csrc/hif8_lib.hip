@@ -27,6 +27,12 @@ static __device__ __attribute__((aligned(16))) uint16_t g_val_lut[2][2][3][8192]
 static __device__ __attribute__((aligned(16))) uint8_t g_hr16_lut[2][2][2][8192];  // HR, 16-bit sources: [NaN -> 0][sat][source LSB][pattern >> 19]
 static __device__ __attribute__((aligned(16))) uint32_t g_dec_lut[256];        // code -> binary32 bits
 
+// Scratch of hif8_quantize_tensor_static: the per-workgroup partial maxima that hif8_quantize_tensor_* keeps in a
+// caller's workspace.  One copy per GPU, held until the process ends.  In host code this name is only a handle
+// for hipGetSymbolAddress: ensure_init() resolves the address of the current device's copy once and every
+// launch is given that pointer.
+static __device__ __align__(256) uint32_t scratch[hif8conv::kMaxParts];
+
 __global__ void k_build_tables() {
   const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < 8192u) {
@@ -134,6 +140,7 @@ std::mutex g_init_mutex;
 bool g_inited[kMaxDevices] = {};
 int g_cu_count[kMaxDevices] = {};
 DevTables g_tables[kMaxDevices] = {};
+uint32_t* g_scratch[kMaxDevices] = {};  // device address of `scratch` on each device
 
 }  // namespace
 
@@ -178,6 +185,8 @@ hif8_status ensure_init(int* cu_count_out, DevTables* tables_out) {
     if (!hip_ok(hipGetSymbolAddress(&p_dec, HIP_SYMBOL(g_dec_lut)))) return HIF8_ERR_HIP;
     if (!hip_ok(hipGetSymbolAddress(&p_hr16, HIP_SYMBOL(g_hr16_lut)))) return HIF8_ERR_HIP;
     if (!hip_ok(hipGetSymbolAddress(&p_val, HIP_SYMBOL(g_val_lut)))) return HIF8_ERR_HIP;
+    void* p_scratch = nullptr;
+    if (!hip_ok(hipGetSymbolAddress(&p_scratch, HIP_SYMBOL(scratch))) || !p_scratch) return HIF8_ERR_HIP;
     hipLaunchKernelGGL(k_build_tables, dim3(8192 / 256), dim3(256), 0, (hipStream_t)0);
     if (!hip_ok(hipGetLastError())) return HIF8_ERR_HIP;
     // the null stream synchronises with every blocking stream; wait on the host as well so
@@ -188,11 +197,20 @@ hif8_status ensure_init(int* cu_count_out, DevTables* tables_out) {
     g_tables[dev].dec_lut = reinterpret_cast<const uint32_t*>(p_dec);
     g_tables[dev].hr16_lut = reinterpret_cast<const uint8_t*>(p_hr16);
     g_tables[dev].val_lut = reinterpret_cast<const uint16_t*>(p_val);
+    g_scratch[dev] = reinterpret_cast<uint32_t*>(p_scratch);
     g_inited[dev] = true;
   }
   if (cu_count_out) *cu_count_out = g_cu_count[dev];
   if (tables_out) *tables_out = g_tables[dev];
   return HIF8_OK;
+}
+
+// device address of the static scratch array on the current device (after ensure_init)
+static uint32_t* static_scratch() {
+  int dev = 0;
+  if (!hip_ok(hipGetDevice(&dev)) || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_init_mutex);
+  return g_inited[dev] ? g_scratch[dev] : nullptr;
 }
 
 bool valid_mode(uint32_t mode) {
@@ -404,6 +422,25 @@ HIF8_DEFINE_KIND(f16, uint16_t, kSrcF16)
 #undef HIF8_DEFINE_KIND
 
 size_t hif8_quantize_workspace_bytes(void) { return (size_t)kMaxParts * sizeof(uint32_t); }
+
+hif8_status hif8_quantize_tensor_static(const void* src, void* dst, uint8_t* codes, size_t n, int src_kind, float target,
+                                        int pow2, uint32_t mode, float* d_amax, float* d_scale2, hif8_stream_t stream) {
+  if (src_kind != HIF8_KIND_F32 && src_kind != HIF8_KIND_BF16 && src_kind != HIF8_KIND_F16) return HIF8_ERR_ARG;
+  if (n > HIF8_STATIC_MAX_ELEMENTS) return HIF8_ERR_ARG;
+  if (!valid_mode(mode)) return HIF8_ERR_MODE;
+  if (!(target > 0.0f) || std::isinf(target)) return HIF8_ERR_ARG;
+  if (!d_amax || !d_scale2 || (n != 0 && (!src || (!dst && !codes)))) return HIF8_ERR_NULL;
+  hif8_status s = ensure_init(nullptr, nullptr);  // resolves the scratch address of this device on first use
+  if (s != HIF8_OK) return s;
+  uint32_t* parts = hif8host::static_scratch();
+  if (!parts) return HIF8_ERR_HIP;
+  hipStream_t st = (hipStream_t)stream;
+  switch (src_kind) {
+    case HIF8_KIND_F32: return conv_quantize_tensor<kSrcF32>(src, dst, codes, n, target, pow2, mode, d_amax, d_scale2, parts, nullptr, st);
+    case HIF8_KIND_BF16: return conv_quantize_tensor<kSrcBF16>(src, dst, codes, n, target, pow2, mode, d_amax, d_scale2, parts, nullptr, st);
+    default: return conv_quantize_tensor<kSrcF16>(src, dst, codes, n, target, pow2, mode, d_amax, d_scale2, parts, nullptr, st);
+  }
+}
 
 hif8_status hif8_multi_plan(hif8_cast_item* host_items, size_t count, int src_is_16bit,
                             uint64_t* total_tiles_out) {

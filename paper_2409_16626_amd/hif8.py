@@ -85,6 +85,7 @@ _SIGS = {
     "hif8_fake_quant_bf16_ds": ([_vp, _vp, _vp, _sz, _vp, _vp, _u32, _vp], _i),
     "hif8_multi_plan": ([_vp, _sz, _i, _vp], _i),
     "hif8_quantize_workspace_bytes": ([], _sz),
+    "hif8_quantize_tensor_static": ([_vp, _vp, _vp, _sz, _i, _f, _i, _u32, _vp, _vp, _vp], _i),
     "hif8_multi_cast_bf16": ([_vp, _vp, _sz, ctypes.c_uint64, _vp, _vp, _f, _i, _u32, _vp], _i),
     "hif8_encode_bf16_sr": ([_vp, _vp, _sz, _f, _u32, _u64, _u64, _vp], _i),
     "hif8_fake_quant_bf16_sr": ([_vp, _vp, _vp, _sz, _f, _u32, _u64, _u64, _vp], _i),
@@ -349,6 +350,16 @@ hif8_multi_cast_f16 = _def_multi_cast("f16")
 
 def hif8_quantize_workspace_bytes():
     return lib.hif8_quantize_workspace_bytes()
+
+
+KIND_F32, KIND_BF16, KIND_F16 = 0, 1, 2
+STATIC_MAX_ELEMENTS = 1 << 32
+
+
+def hif8_quantize_tensor_static(src, dst_or_none, codes_or_none, n, src_kind, d_amax, d_scale2, target=MAX_FINITE, pow2=0,
+                                rounding_mode=RM_TA, stream=None):
+    _check(lib.hif8_quantize_tensor_static(_ptr(src), _ptr(dst_or_none), _ptr(codes_or_none), n, src_kind, target, int(pow2),
+                                           rounding_mode, _ptr(d_amax), _ptr(d_scale2), _stream(stream)))
 
 
 def _def_tensor_calls(sfx):
