@@ -527,18 +527,20 @@ void hif8o_decode_f16(const uint8_t *src, uint16_t *dst, size_t n, float scale) 
 }
 
 float hif8o_amax_f16(const uint16_t *src, size_t n) {
-  uint16_t m = 0;                     /* magnitude patterns of binary16 order like the values */
-  for (size_t i = 0; i < n; ++i) {
-    uint16_t a = src[i] & 0x7FFF;
+  uint32_t m = 0;                     /* magnitude patterns of binary16 order like the values */
+#pragma omp parallel for schedule(static) reduction(max : m)
+  for (ptrdiff_t i = 0; i < (ptrdiff_t)n; ++i) {
+    uint32_t a = src[i] & 0x7FFFu;
     if (a > m) m = a;
   }
-  return f16_to_f32(m);
+  return f16_to_f32((uint16_t)m);
 }
 
 /* amax: maximum magnitude pattern, compared as unsigned integers */
 float hif8o_amax_f32(const float *src, size_t n) {
   uint32_t m = 0;
-  for (size_t i = 0; i < n; ++i) {
+#pragma omp parallel for schedule(static) reduction(max : m)
+  for (ptrdiff_t i = 0; i < (ptrdiff_t)n; ++i) {
     uint32_t a = f32_bits(src[i]) & 0x7FFFFFFFu;
     if (a > m) m = a;
   }
@@ -547,7 +549,8 @@ float hif8o_amax_f32(const float *src, size_t n) {
 
 float hif8o_amax_bf16(const uint16_t *src, size_t n) {
   uint32_t m = 0;
-  for (size_t i = 0; i < n; ++i) {
+#pragma omp parallel for schedule(static) reduction(max : m)
+  for (ptrdiff_t i = 0; i < (ptrdiff_t)n; ++i) {
     uint32_t a = ((uint32_t)src[i] << 16) & 0x7FFFFFFFu;
     if (a > m) m = a;
   }

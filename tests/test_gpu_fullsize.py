@@ -1,13 +1,12 @@
 """GPU parity at the baseline's full sizes, in the launch configuration bench.py times.
 
-Every element is checked where the oracle can afford it:
-  * FP32, TA  : the oracle encodes the whole tensor (config 2), or -- for 2^30 elements --
-                the oracle's table over the top 13 bits of a pattern (the TA code depends on
-                nothing else; that lemma is pinned in the oracle's own tests) is compared with
-                every element, plus direct oracle calls on sampled blocks;
-  * FP32, HR  : direct oracle calls on sampled blocks (first, last, and seeded random blocks);
+Every element of every configuration is checked:
+  * FP32      : the oracle encodes the whole tensor, in slices of 2^26 elements for the 2^30-element
+                gradient tensor (under standard SR each slice with the index base its elements have
+                inside the tensor), under every rounding method;
   * BF16      : the oracle evaluates all 65,536 source patterns at the tensor's scale and every
-                element is compared through that table (exhaustive, the op is element-wise).
+                element is compared through that table (exhaustive, the op is element-wise); amax
+                comes from the oracle's own reduction over the tensor.
 """
 import numpy as np
 import pytest
@@ -55,8 +54,8 @@ def test_c2_full(h):
         h.hif8_encode_f32(x, codes, n, 1.0, mode)
         torch.cuda.synchronize()
         assert_same_bytes(codes.cpu().numpy(), orc.encode_f32(xn, 1.0, mode), "C2 full mode %#x" % mode)
-    # the tie positions really are ties: a visible share of inputs has <= 4 fractional mantissa bits
-    assert np.mean((xn.view(np.uint32) & 0x7FFFF) == 0) > 0.005
+    # the tie positions really are ties: about 1 % of the inputs have no bit below the rounding position
+    assert np.mean((xn.view(np.uint32) & 0x7FFFF) == 0) > 0.009
 
 
 def test_c3_full(h):
@@ -80,12 +79,29 @@ def test_c3_full(h):
     assert torch.equal(codes, gather_bf16(t_codes, xi))
     assert torch.equal(out.view(torch.int16), gather_bf16(t_out, xi))
     assert w_am > 100.0          # the x100 outliers set the scale
+    # the same recipe as one call (two launches): identical outputs
+    ws = torch.empty(h.hif8_quantize_workspace_bytes(), dtype=torch.uint8, device=dev())
+    am2 = torch.zeros_like(am); sc2 = torch.zeros_like(sc)
+    out2 = torch.empty_like(x); codes2 = torch.empty_like(codes)
+    h.hif8_quantize_tensor_bf16(x, out2, codes2, n, am2, sc2, ws, 32768.0, 0, TA)
+    torch.cuda.synchronize()
+    assert torch.equal(am, am2) and torch.equal(sc, sc2) and torch.equal(codes, codes2)
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
 
 
-def sample_blocks(n, n_blocks, block, seed):
-    rng = np.random.default_rng(seed)
-    starts = np.unique(np.concatenate([[0, n - block], rng.integers(0, n - block, n_blocks)]))
-    return [(int(s), int(s) + block) for s in starts]
+SLICE = 1 << 26
+
+
+def check_c4_against_oracle(x, codes, mode, what):
+    """Every element of the 2^30-element tensor: the oracle encodes slice after slice on the host."""
+    n = x.numel()
+    try:
+        for lo in range(0, n, SLICE):
+            orc.set_sr_index_base(lo)
+            want = orc.encode_f32(x[lo:lo + SLICE].cpu().numpy(), 1.0, mode)
+            assert_same_bytes(codes[lo:lo + SLICE].cpu().numpy(), want, "%s, slice at %d" % (what, lo))
+    finally:
+        orc.set_sr_index_base(0)
 
 
 @pytest.mark.parametrize("mode", [TA, HR])
@@ -96,36 +112,19 @@ def test_c4_full(h, mode):
     codes = torch.empty(n, dtype=torch.uint8, device=dev())
     h.hif8_encode_f32(x, codes, n, 1.0, mode)
     torch.cuda.synchronize()
-    for lo, hi in sample_blocks(n, 2048, 8192, 77):
-        want = orc.encode_f32(x[lo:hi].cpu().numpy(), 1.0, mode)
-        assert_same_bytes(codes[lo:hi].cpu().numpy(), want, "C4 block at %d" % lo)
-    if mode == TA:
-        top = (np.arange(1 << 13, dtype=np.uint32) << 19)
-        tbl = orc.encode_f32(top.view(np.float32), 1.0, TA)     # NaN rows are never indexed: no NaNs in C4
-        t = torch.from_numpy(tbl.copy()).to(dev())
-        xi = x.view(torch.int32)
-        bad = 0
-        for lo in range(0, n, 1 << 27):
-            idx = ((xi[lo:lo + (1 << 27)] >> 19) & 0x1FFF).to(torch.int64)
-            bad += int((t[idx] != codes[lo:lo + (1 << 27)]).sum().item())
-        assert bad == 0
-        assert not torch.isnan(x).any()
-    else:
-        # properties that hold everywhere: HR equals TA where |E| < 4; zero stays zero
-        ta = torch.empty(1 << 26, dtype=torch.uint8, device=dev())
-        h.hif8_encode_f32(x[:1 << 26], ta, 1 << 26, 1.0, TA)
-        torch.cuda.synchronize()
-        e = (x[:1 << 26].view(torch.int32) >> 23) & 0xFF
-        inside = (e >= 124) & (e <= 130)
-        assert torch.equal(codes[:1 << 26][inside], ta[inside])
-        assert int(codes[:1 << 26][x[:1 << 26] == 0].max().item()) == 0
+    check_c4_against_oracle(x, codes, mode, "C4 mode %d" % mode)
+    assert not torch.isnan(x).any()
+    # the bulk of the data sits in the denormal binades 2^-22 .. 2^-16 and a visible share underflows
+    mag = codes[:SLICE] & 0x7F
+    assert float(((mag >= 1) & (mag <= 7)).float().mean().item()) > 0.3
+    assert 0.08 < float((codes[:SLICE] == 0).float().mean().item()) < 0.25
 
 
 @pytest.mark.parametrize("mode", [orc.RM_TE, orc.RM_SSR, orc.RM_SR])
 def test_c4_full_comparison_modes(h, mode):
-    """The gradient tensor under the rounding methods the paper compares TA / HR with; sampled
-    blocks against the oracle (standard SR: with the thresholds the elements have at their place
-    in the 2^30-element tensor)."""
+    """The gradient tensor under the rounding methods the paper compares TA / HR with, every element
+    against the oracle (standard SR: with the thresholds the elements have at their place in the
+    2^30-element tensor)."""
     from paper_2409_16626_amd import workloads
     n = 1 << 30
     x = workloads.gradient_f32(n, dev())
@@ -136,19 +135,12 @@ def test_c4_full_comparison_modes(h, mode):
     try:
         h.hif8_encode_f32(x, codes, n, 1.0, mode)
         torch.cuda.synchronize()
-        for lo, hi in sample_blocks(n, 1024, 8192, 78):
-            orc.set_sr_index_base(lo)
-            want = orc.encode_f32(x[lo:hi].cpu().numpy(), 1.0, mode)
-            assert_same_bytes(codes[lo:hi].cpu().numpy(), want, "C4 block at %d mode %d" % (lo, mode))
+        check_c4_against_oracle(x, codes, mode, "C4 mode %d" % mode)
     finally:
-        orc.set_sr_index_base(0)
         orc.set_sr_seed(0)
         h.hif8_set_sr_seed(0)
-    # zero stays zero and the code histogram is dominated by the denormal binades, as for TA
-    z = codes[:1 << 26][x[:1 << 26] == 0]
+    z = codes[:SLICE][x[:SLICE] == 0]
     assert int(z.max().item()) == 0
-    mag = codes[:1 << 26] & 0x7F
-    assert float(((mag >= 1) & (mag <= 7)).float().mean().item()) > 0.2
 
 
 def test_c5_full(h):
@@ -157,23 +149,31 @@ def test_c5_full(h):
     assert len(index) == 225 and arena.numel() == 6607077376
     codes = torch.empty(arena.numel(), dtype=torch.uint8, device=dev())
     items = [(arena.data_ptr() + 2 * off, codes.data_ptr() + off, m) for _, off, m in index]
-    d_items, count, tiles = h.hif8_multi_plan(items, src_is_16bit=True)
+    plan = h.hif8_multi_plan(items, src_is_16bit=True)
+    d_items, count, tiles = plan
     am = torch.zeros(count, dtype=torch.float32, device=dev())
     sc = torch.zeros(count, 2, dtype=torch.float32, device=dev())
-    h.hif8_multi_cast_bf16(d_items, count, tiles, am, sc, 32768.0, 0, TA)
+    h.hif8_multi_cast_bf16(d_items, count, tiles, am, sc, 32768.0, 0, TA, host_items=plan.host_items)   # group-wise schedule
     torch.cuda.synchronize()
     amn, scn = am.cpu().numpy(), sc.cpu().numpy()
     ai = arena.view(torch.int16)
     for i, (name, off, m) in enumerate(index):
         part = ai[off:off + m]
-        # amax through torch on the bit patterns (max of magnitude bits), as a second route
-        w_am_bits = int((part.to(torch.int32) & 0x7FFF).max().item()) << 16
-        w_am = np.array([w_am_bits], np.uint32).view(np.float32)[0]
+        w_am = orc.amax_bf16(part.cpu().numpy().view(np.uint16))
         assert amn[i] == w_am, name
         w_s = orc.scale_from_amax(w_am, 32768.0, False)
         assert scn[i, 0] == w_s, name
         t_codes, _ = bf16_tables(w_s, TA)
         assert torch.equal(codes[off:off + m], gather_bf16(t_codes, part)), name
+    # the four-launch form (no host copy of the plan) gives the same bytes
+    codes4 = torch.empty_like(codes)
+    items4 = [(arena.data_ptr() + 2 * off, codes4.data_ptr() + off, m) for _, off, m in index]
+    plan4 = h.hif8_multi_plan(items4, src_is_16bit=True)
+    am4 = torch.zeros_like(am); sc4 = torch.zeros_like(sc)
+    h.hif8_multi_cast_bf16(plan4.d_items, plan4.count, plan4.total_tiles, am4, sc4, 32768.0, 0, TA)
+    torch.cuda.synchronize()
+    assert torch.equal(codes, codes4) and torch.equal(am, am4) and torch.equal(sc, sc4)
+    del codes4
     # the per-tensor call sequence gives the same bytes (checked on the first and last tensors)
     for i in (0, 4, 224):
         _, off, m = index[i]
