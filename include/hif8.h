@@ -324,12 +324,12 @@ hif8_status hif8_quantize_tensor_static(const void* src, void* dst_or_null, uint
  *                    hif8_scale_from_amax); target, pow2 as in hif8_scale_from_amax.  Results
  *                    equal the per-tensor sequence hif8_amax_* -> hif8_scale_from_amax ->
  *                    hif8_encode_*_ds.  With the host copy the list is cut into groups of whole
- *                    tensors of about 96 MiB of source, and one launch per group gathers the amax
- *                    of that group while it casts the previous one, whose source is then still in
- *                    the 256 MB last-level cache: the second read of every tensor is served from
- *                    there instead of HBM.  Without it (NULL): amax of all tensors, scales, cast of
- *                    all tensors (four launches, every tensor read from HBM twice).  HIF8_ERR_ARG if
- *                    the host copy does not match total_tiles.
+ *                    tensors of about 192 MiB of source (at most 16 tensors), and one launch per group
+ *                    gathers the amax of that group while it casts the previous one, whose source was
+ *                    read a moment before: the two passes overlap and no launch has to wait for
+ *                    the whole list.  Without it (NULL): amax of all tensors, scales, cast of all
+ *                    tensors (four launches).  HIF8_ERR_ARG if the host copy does not match
+ *                    total_tiles.
  *   hif8_multi_encode_{bf16,f16,f32}_ds
  *                    the cast alone, in ONE launch, with scales that are already on the device
  *                    (delayed scaling, Sec. 5: scales from earlier iterations): d_scale2: 2*count

@@ -28,8 +28,7 @@ extern "C" {
  *                          loads, -1 (default) = ordinary loads for tensors up to 192 MiB (a cast of
  *                          the same tensor usually follows and then finds it in the last-level
  *                          cache), non-temporal loads above
- *   HIF8_TUNE_GROUP_MIB    source MiB per group of the group-wise hif8_multi_cast_* (1..4096,
- *                          default 96: two groups fit the 256 MB last-level cache)
+ *   HIF8_TUNE_GROUP_MIB    source MiB per group of the group-wise hif8_multi_cast_* (1..4096, default 192)
  *   HIF8_TUNE_FAMILY       kernel family the four shape knobs (block, workgroups per CU, unroll, tiles
  *                          per workgroup) apply to; -1 (default) = all.  0 = FP32 encode TA, 1 = FP32
  *                          encode HR, 2 = 16-bit encode, 3 = fake-quant, 4 = decode, 5 = amax,

@@ -359,53 +359,60 @@ inline ScaleArg scale_by_value(float scale, float inv) { return ScaleArg{scale, 
 inline ScaleArg scale_on_device(const float* d_scale2) { return ScaleArg{1.0f, 1.0f, d_scale2, nullptr, 0u, 0.0f, 0, nullptr, nullptr}; }
 
 
-// First half (before the workgroup barrier of the kernel prologue): wavefront maxima of the partial maxima
-// into LDS.  Second half (after that barrier): every lane folds them and derives the pair.
+// Scale pair of the plain forms (uniform over the grid: scalar loads).
+__device__ __forceinline__ float plain_scale(const ScaleArg& a) { return a.d_scale2 ? a.d_scale2[0] : a.scale; }
+__device__ __forceinline__ float plain_inv(const ScaleArg& a) { return a.d_scale2 ? a.d_scale2[1] : a.inv; }
+
+// The parts form.  First half (before the workgroup barrier of the kernel prologue): wavefront maxima of the
+// partial maxima into LDS.  Second half (after that barrier): every lane folds them and derives the pair;
+// workgroup 0 publishes amax and the pair.
 struct ScaleLds {
   uint32_t wave_m[16];
 };
-__device__ __forceinline__ void scale_before_barrier(const ScaleArg& a, ScaleLds& l) {
-  if (!a.parts) return;
+__device__ __forceinline__ void parts_before_barrier(const ScaleArg& a, ScaleLds& l) {
   uint32_t m = 0;
   for (uint32_t i = threadIdx.x; i < a.nparts; i += blockDim.x) m = umax(m, a.parts[i]);
   m = wave_max_u32(m);
   if ((threadIdx.x & 63u) == 0u) l.wave_m[threadIdx.x >> 6] = m;
 }
-__device__ __forceinline__ void scale_after_barrier(const ScaleArg& a, const ScaleLds& l, float& scale, float& inv) {
-  if (a.parts) {
-    const uint32_t nw = (blockDim.x + 63u) >> 6;
-    uint32_t r = l.wave_m[0];
-    for (uint32_t w = 1; w < nw; ++w) r = umax(r, l.wave_m[w]);
-    const float amax = __uint_as_float(r);
-    scale = scale_from_amax_value(amax, a.target, a.pow2);
-    inv = 1.0f / scale;
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-      *a.out_amax = amax;
-      a.out_scale2[0] = scale;
-      a.out_scale2[1] = inv;
-    }
-  } else if (a.d_scale2) {
-    scale = a.d_scale2[0];
-    inv = a.d_scale2[1];
-  } else {
-    scale = a.scale;
-    inv = a.inv;
+__device__ __forceinline__ void parts_after_barrier(const ScaleArg& a, const ScaleLds& l, float& scale, float& inv) {
+  const uint32_t nw = (blockDim.x + 63u) >> 6;
+  uint32_t r = l.wave_m[0];
+  for (uint32_t w = 1; w < nw; ++w) r = umax(r, l.wave_m[w]);
+  const float amax = __uint_as_float(r);
+  scale = scale_from_amax_value(amax, a.target, a.pow2);
+  inv = 1.0f / scale;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    *a.out_amax = amax;
+    a.out_scale2[0] = scale;
+    a.out_scale2[1] = inv;
   }
+}
+
+// Index of the element a kernel's position `local` has in the threshold stream of standard SR; other rounding
+// methods never look at it, so their kernels carry no base.
+template <int IMPL>
+__device__ __forceinline__ uint64_t stream_index(const SrArg& sr, uint64_t local) {
+  if constexpr (IMPL == IMPL_SR) return sr.base + local;
+  else return local;
 }
 
 // ------------------------------------------------------------------------------------
 // streaming kernels.  The ragged tail (n modulo the vector width) is done element-wise by
 // workgroup 0.
 // ------------------------------------------------------------------------------------
-template <int U, int IMPL, int SRCK>
+// PARTS: the scale comes from the partial maxima of k_amax<.., PARTS> (ScaleArg::parts); otherwise by value or
+// from d_scale2.
+template <int U, int IMPL, int SRCK, bool PARTS>
 __global__ void __launch_bounds__(1024)
 k_encode(const void* __restrict__ src, uint8_t* __restrict__ dst, size_t n, ScaleArg sa,
          uint32_t* __restrict__ amax_acc, uint32_t mode, SrArg sr, const uint8_t* __restrict__ g_lut, Walk walk) {
   __shared__ __attribute__((aligned(16))) uint8_t lut[lut_bytes<IMPL>()];
   __shared__ HrLds<uses_exp_table<IMPL>()> hrt;
   __shared__ ScaleLds sl;
-  const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, sr.seed, sr.base);
+  const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, sr.seed, stream_index<IMPL>(sr, 0));
   float scale = 1.0f, inv = 1.0f;
+  if constexpr (!PARTS) scale = plain_scale(sa);
   const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(src);
   constexpr int VE = vec_elems<SRCK>();
   const size_t nvec = n >> vec_shift<SRCK>();
@@ -415,25 +422,26 @@ k_encode(const void* __restrict__ src, uint8_t* __restrict__ dst, size_t n, Scal
       [&](size_t idx, const uint4& v) {
         if (amax_acc) m = vec_amax<SRCK>(m, v);
         if constexpr (SRCK == kSrcF32)
-          st_stream(reinterpret_cast<uint32_t*>(dst) + idx, encode4_f32<IMPL>(v, scale, ctx, sr.base + idx * VE));
+          st_stream(reinterpret_cast<uint32_t*>(dst) + idx, encode4_f32<IMPL>(v, scale, ctx, stream_index<IMPL>(sr, idx * VE)));
         else
-          st_stream(reinterpret_cast<uint2*>(dst) + idx, encode8_16<IMPL, SRCK>(v, scale, ctx, sr.base + idx * VE));
+          st_stream(reinterpret_cast<uint2*>(dst) + idx, encode8_16<IMPL, SRCK>(v, scale, ctx, stream_index<IMPL>(sr, idx * VE)));
       },
       [&]() {
         if (IMPL != IMPL_TA_ALU) {
           stage_enc_lut<IMPL, SRCK>(lut, g_lut, mode);
           stage_exp_table<IMPL, SRCK>(hrt.w, mode);
         }
-        scale_before_barrier(sa, sl);
-        if (IMPL != IMPL_TA_ALU || sa.parts) __syncthreads();
-        scale_after_barrier(sa, sl, scale, inv);
+        if constexpr (PARTS) parts_before_barrier(sa, sl);
+        if (IMPL != IMPL_TA_ALU || PARTS) __syncthreads();
+        if constexpr (PARTS) parts_after_barrier(sa, sl, scale, inv);
       });
   const size_t t = nvec * VE + threadIdx.x;
   m = fold_amax<SRCK>(m);
   if (blockIdx.x == 0 && t < n) {
     const uint32_t xb = load_bits<SRCK>(src, t);
     m = umax(m, xb & 0x7FFFFFFFu);
-    dst[t] = (uint8_t)encode_one<IMPL, SRCK>(scaled_bits(xb, scale), keyed<IMPL>(ctx, sr.base + t), sr.base + t);
+    const uint64_t e = stream_index<IMPL>(sr, t);
+    dst[t] = (uint8_t)encode_one<IMPL, SRCK>(scaled_bits(xb, scale), keyed<IMPL>(ctx, e), e);
   }
   if (amax_acc) block_max_to_global(m, amax_acc);
 }
@@ -471,7 +479,7 @@ k_decode(const uint8_t* __restrict__ src, void* __restrict__ dst, size_t n, floa
 }
 
 // fake-quant: src and dst may alias (each lane reads its own vectors before it writes them)
-template <int U, int IMPL, bool CODES, int SRCK>
+template <int U, int IMPL, bool CODES, int SRCK, bool PARTS>
 __global__ void __launch_bounds__(1024)
 k_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, ScaleArg sa, uint32_t* amax_acc, uint32_t mode,
              SrArg sr, const uint8_t* __restrict__ g_lut, const uint32_t* __restrict__ g_dec, Walk walk) {
@@ -479,15 +487,19 @@ k_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, ScaleArg sa, 
   __shared__ HrLds<uses_exp_table<IMPL>()> hrt;
   __shared__ uint32_t dec[256];
   __shared__ ScaleLds sl;
-  const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, sr.seed, sr.base);
+  const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, sr.seed, stream_index<IMPL>(sr, 0));
   float scale = 1.0f, inv = 1.0f;
+  if constexpr (!PARTS) {
+    scale = plain_scale(sa);
+    inv = plain_inv(sa);
+  }
   auto prologue = [&]() {
     stage_enc_lut<IMPL, SRCK>(lut, g_lut, mode);
     stage_exp_table<IMPL, SRCK>(hrt.w, mode);
     stage_dec_lut(dec, g_dec);
-    scale_before_barrier(sa, sl);
+    if constexpr (PARTS) parts_before_barrier(sa, sl);
     __syncthreads();
-    scale_after_barrier(sa, sl, scale, inv);
+    if constexpr (PARTS) parts_after_barrier(sa, sl, scale, inv);
   };
   const uint4* src4 = reinterpret_cast<const uint4*>(src);
   uint4* dst4 = reinterpret_cast<uint4*>(dst);
@@ -499,11 +511,11 @@ k_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, ScaleArg sa, 
       [&](size_t idx, const uint4& v) {
         if (amax_acc) m = vec_amax<SRCK>(m, v);
         if constexpr (SRCK == kSrcF32) {
-          const uint32_t w = encode4_f32<IMPL>(v, scale, ctx, sr.base + idx * VE);
+          const uint32_t w = encode4_f32<IMPL>(v, scale, ctx, stream_index<IMPL>(sr, idx * VE));
           st_stream(dst4 + idx, descale4_f32(w, dec, inv));
           if (CODES) st_stream(reinterpret_cast<uint32_t*>(codes) + idx, w);
         } else {
-          const uint2 w = encode8_16<IMPL, SRCK>(v, scale, ctx, sr.base + idx * VE);
+          const uint2 w = encode8_16<IMPL, SRCK>(v, scale, ctx, stream_index<IMPL>(sr, idx * VE));
           st_stream(dst4 + idx, descale8_16<SRCK>(w, dec, inv));
           if (CODES) st_stream(reinterpret_cast<uint2*>(codes) + idx, w);
         }
@@ -514,7 +526,8 @@ k_fake_quant(const void* src, void* dst, uint8_t* codes, size_t n, ScaleArg sa, 
   if (blockIdx.x == 0 && t < n) {
     const uint32_t xb = load_bits<SRCK>(src, t);
     m = umax(m, xb & 0x7FFFFFFFu);
-    const uint32_t c = encode_one<IMPL, SRCK>(scaled_bits(xb, scale), keyed<IMPL>(ctx, sr.base + t), sr.base + t);
+    const uint64_t e = stream_index<IMPL>(sr, t);
+    const uint32_t c = encode_one<IMPL, SRCK>(scaled_bits(xb, scale), keyed<IMPL>(ctx, e), e);
     const uint32_t b = descale_bits(c, dec, inv);
     if constexpr (SRCK == kSrcF32) reinterpret_cast<uint32_t*>(dst)[t] = b;
     else reinterpret_cast<uint16_t*>(dst)[t] = (uint16_t)narrow1<SRCK>(b);
@@ -969,8 +982,13 @@ void launch_encode_fast(const void* src, uint8_t* dst, size_t n, const ScaleArg&
   Walk walk;
   const dim3 grid(grid_for(nvec, cus, shape, &walk)), block(shape.block);
   dispatch_impl<SRCK>(impl, shape.unroll, [&](auto impl_c, auto u_c) {
-    hipLaunchKernelGGL((k_encode<decltype(u_c)::value, decltype(impl_c)::value, SRCK>), grid, block, 0, st, src,
-                       dst, n, sa, amax_acc, mode, sr, enc_table_for<decltype(impl_c)::value>(tb), walk);
+    constexpr int U = decltype(u_c)::value, IMPL = decltype(impl_c)::value;
+    if (sa.parts)
+      hipLaunchKernelGGL((k_encode<U, IMPL, SRCK, true>), grid, block, 0, st, src, dst, n, sa, amax_acc, mode, sr,
+                         enc_table_for<IMPL>(tb), walk);
+    else
+      hipLaunchKernelGGL((k_encode<U, IMPL, SRCK, false>), grid, block, 0, st, src, dst, n, sa, amax_acc, mode, sr,
+                         enc_table_for<IMPL>(tb), walk);
   });
 }
 
@@ -985,12 +1003,14 @@ void launch_fake_quant_fast(const void* src, void* dst, uint8_t* codes, size_t n
   const dim3 grid(grid_for(nvec, cus, shape, &walk)), block(shape.block);
   dispatch_impl<SRCK>(impl, shape.unroll, [&](auto impl_c, auto u_c) {
     constexpr int U = decltype(u_c)::value, IMPL = decltype(impl_c)::value;
-    if (codes)
-      hipLaunchKernelGGL((k_fake_quant<U, IMPL, true, SRCK>), grid, block, 0, st, src, dst, codes, n, sa, amax_acc, mode,
-                         sr, enc_table_for<IMPL>(tb), tb.dec_lut, walk);
-    else
-      hipLaunchKernelGGL((k_fake_quant<U, IMPL, false, SRCK>), grid, block, 0, st, src, dst, codes, n, sa, amax_acc,
-                         mode, sr, enc_table_for<IMPL>(tb), tb.dec_lut, walk);
+    auto go = [&](auto codes_c, auto parts_c) {
+      hipLaunchKernelGGL((k_fake_quant<U, IMPL, decltype(codes_c)::value, SRCK, decltype(parts_c)::value>), grid, block, 0, st,
+                         src, dst, codes, n, sa, amax_acc, mode, sr, enc_table_for<IMPL>(tb), tb.dec_lut, walk);
+    };
+    using std::true_type;
+    using std::false_type;
+    if (codes) { if (sa.parts) go(true_type{}, true_type{}); else go(true_type{}, false_type{}); }
+    else { if (sa.parts) go(false_type{}, true_type{}); else go(false_type{}, false_type{}); }
   });
 }
 

@@ -88,7 +88,7 @@ k_diag_stream(const uint4* __restrict__ src, void* __restrict__ dst, size_t nvec
         else st_stream(reinterpret_cast<uint4*>(dst) + idx, v);
       },
       []() {});
-  if (OUT == 0 && dst && acc == 0xFFFFFFFFu && threadIdx.x == 0xFFFFu) *reinterpret_cast<uint32_t*>(dst) = acc;  // keeps the loads alive
+  if (OUT == 0 && dst && acc == 0x9E3779B9u) *reinterpret_cast<uint32_t*>(dst) = acc;  // keeps the loads alive (dst is null in practice)
 }
 
 // ====================================================================================
@@ -127,7 +127,7 @@ struct Tuning {
   int ta_impl = 0;
   int tiles_per_wg = -1;
   int amax_nt = -1;  // -1: by size
-  int group_mib = 96;
+  int group_mib = 192;
   int family = -1;  // kernel family the shape overrides apply to; -1: all
   int stage_overlap = 1;
 };

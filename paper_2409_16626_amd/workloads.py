@@ -100,7 +100,11 @@ def _pattern_view(bits):
     return b.to(torch.int32).view(torch.float32)
 
 
-def _chunks(n, chunk):
+def _chunks(n, chunk, device="cpu"):
+    """(start, length) pieces of [0, n).  The default piece is 2^26 elements on a GPU (few launches; the int64
+    temporaries take a few GiB) and 2^22 on the CPU; the bytes generated do not depend on it."""
+    if chunk is None:
+        chunk = 1 << 22 if torch.device(device).type == "cpu" else 1 << 26
     for lo in range(0, n, chunk):
         yield lo, min(chunk, n - lo)
 
@@ -126,15 +130,15 @@ def all_bf16(device="cpu"):
     return bits.view(torch.bfloat16)
 
 
-def normal_f32(n=1 << 20, device="cpu", chunk=1 << 24):
+def normal_f32(n=1 << 20, device="cpu", chunk=None):
     """C1(iii): FP32 ~ N(0, 1)."""
     out = torch.empty(n, device=device, dtype=torch.float32)
-    for lo, m in _chunks(n, chunk):
+    for lo, m in _chunks(n, chunk, device):
         out[lo:lo + m] = _normal_f32(1, 0, _index(lo, m, device))
     return out
 
 
-def dynamic_range_sweep(n=1 << 26, device="cpu", tie_fraction=0.01, chunk=1 << 24):
+def dynamic_range_sweep(n=1 << 26, device="cpu", tie_fraction=0.01, chunk=None):
     """C2: random sign * 2^E * (1 + m / 2^23) with E uniform over the integers -30 .. 19 and all 23 mantissa bits
     random (every binade from far below the smallest HiF8 denormal to above its largest value, every rounding
     position), and about 1 % of the positions overwritten with exact rounding ties: midpoints between two adjacent
@@ -144,7 +148,7 @@ def dynamic_range_sweep(n=1 << 26, device="cpu", tie_fraction=0.01, chunk=1 << 2
     E = -22 .. -16, Eq. (2)): a midpoint has one more mantissa bit than its binade keeps, and that bit is set."""
     out = torch.empty(n, device=device, dtype=torch.float32)
     thr = int(tie_fraction * 65536)
-    for lo, m in _chunks(n, chunk):
+    for lo, m in _chunks(n, chunk, device):
         idx = _index(lo, m, device)
         h0 = hash_words(2, 0, idx)
         e = -30 + ((_u16(h0, 0) * 50) >> 16)                       # -30 .. 19
@@ -165,12 +169,12 @@ def dynamic_range_sweep(n=1 << 26, device="cpu", tie_fraction=0.01, chunk=1 << 2
     return out
 
 
-def activation_bf16(rows=8192, cols=8192, device="cpu", outlier_fraction=0.001, outlier_gain=100.0, chunk=1 << 24):
+def activation_bf16(rows=8192, cols=8192, device="cpu", outlier_fraction=0.001, outlier_gain=100.0, chunk=None):
     """C3: BF16 [rows, cols] ~ N(0, 1) with a fraction of hash-selected positions multiplied by 100."""
     n = rows * cols
     out = torch.empty(n, device=device, dtype=torch.bfloat16)
     thr = int(outlier_fraction * (1 << 32))
-    for lo, m in _chunks(n, chunk):
+    for lo, m in _chunks(n, chunk, device):
         idx = _index(lo, m, device)
         x = _normal_f32(3, 0, idx)
         sel = (hash_words(3, 4, idx) & 0xFFFFFFFF) < thr
@@ -179,7 +183,7 @@ def activation_bf16(rows=8192, cols=8192, device="cpu", outlier_fraction=0.001, 
     return out.view(rows, cols)
 
 
-def gradient_f32(n=1 << 30, device="cpu", zero_fraction=0.05, chunk=1 << 24):
+def gradient_f32(n=1 << 30, device="cpu", zero_fraction=0.05, chunk=None):
     """C4: log-normal magnitudes, ln|x| ~ Normal(mean -12, std 3), random sign, 5 % exact zeros.
     Built in the binary logarithm, in fixed point: log2|x| = (-12 + 3 z) / ln 2 with z the Irwin-Hall normal; its
     integer part is the exponent, its fraction the top 16 mantissa bits (linear within a binade), and the low 7
@@ -188,7 +192,7 @@ def gradient_f32(n=1 << 30, device="cpu", zero_fraction=0.05, chunk=1 << 24):
     a_fix = -1134566      # round(-12 / ln 2 * 2^16)
     b_fix = 283645        # round(3 / ln 2 * 2^16)
     zthr = int(zero_fraction * 65536)
-    for lo, m in _chunks(n, chunk):
+    for lo, m in _chunks(n, chunk, device):
         idx = _index(lo, m, device)
         d = _irwin_hall(4, 0, idx)                                # z = d * 2^-17
         t = a_fix + ((b_fix * d) >> 17)                            # log2|x| in Q16 (floor)
@@ -215,13 +219,13 @@ def llm_weight_shapes(layers=32, hidden=4096, ffn=11008, vocab=32000):
     return shapes
 
 
-def llm_weights_bf16(device="cpu", layers=32, hidden=4096, ffn=11008, vocab=32000, std=0.02, chunk=1 << 24):
+def llm_weights_bf16(device="cpu", layers=32, hidden=4096, ffn=11008, vocab=32000, std=0.02, chunk=None):
     """C5: one flat BF16 arena ~ N(0, 0.02) plus (name, offset, numel) per tensor (element i of the arena is a
     function of i alone).  Every tensor size is a multiple of 16 elements, so each slice stays 16-byte aligned."""
     shapes = llm_weight_shapes(layers, hidden, ffn, vocab)
     total = sum(a * b for _, (a, b) in shapes)
     arena = torch.empty(total, device=device, dtype=torch.bfloat16)
-    for lo, m in _chunks(total, chunk):
+    for lo, m in _chunks(total, chunk, device):
         arena[lo:lo + m] = (_normal_f32(5, 0, _index(lo, m, device)) * std).to(torch.bfloat16)
     index = []
     off = 0

@@ -155,7 +155,7 @@ def test_tuning_knobs():
     assert L.hif8_set_tuning(3, 2) == -5 and L.hif8_set_tuning(9, 1) == -5
     assert L.hif8_set_tuning(4, -2) == -5 and L.hif8_set_tuning(4, 5000) == -5 and L.hif8_set_tuning(5, 2) == -5 and L.hif8_set_tuning(5, -2) == -5
     assert L.hif8_get_tuning(9) == -1 and L.hif8_set_tuning(8, 2) == -5 and L.hif8_set_tuning(7, 10) == -5 and L.hif8_set_tuning(7, -2) == -5
-    assert L.hif8_set_tuning(6, 0) == -5 and L.hif8_set_tuning(6, 5000) == -5 and L.hif8_get_tuning(6) == 96
+    assert L.hif8_set_tuning(6, 0) == -5 and L.hif8_set_tuning(6, 5000) == -5 and L.hif8_get_tuning(6) == 192
     assert L.hif8_set_tuning(0, 256) == 0 and L.hif8_get_tuning(0) == 256
     for k, v in enumerate(saved):
         assert L.hif8_set_tuning(k, v) == 0

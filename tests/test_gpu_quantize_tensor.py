@@ -132,7 +132,7 @@ def test_quantize_tensor_special_inputs(h):
     assert_same_bytes(host_view(out.contiguous()), wo, "unaligned fake-quant")
 
 
-@pytest.mark.parametrize("group_mib", [1, 2, 96])
+@pytest.mark.parametrize("group_mib", [1, 2, 192])
 @pytest.mark.parametrize("mode,pow2", [(TA, 0), (HR | SAT, 1)])
 def test_group_wise_multi_cast_matches_oracle_and_the_four_launch_form(h, group_mib, mode, pow2):
     """A tensor list with tiny, empty, ragged and large members, cut into groups of 1 MiB / 2 MiB / all in one:
@@ -175,7 +175,7 @@ def test_group_wise_multi_cast_matches_oracle_and_the_four_launch_form(h, group_
             torch.cuda.synchronize()
             assert torch.equal(codes, codes2) and torch.equal(am, am2) and torch.equal(sc, sc2)
     finally:
-        h.hif8_set_tuning(h.TUNE_GROUP_MIB, 96)
+        h.hif8_set_tuning(h.TUNE_GROUP_MIB, 192)
 
 
 @pytest.mark.parametrize("kind", ["f32", "bf16", "f16"])
