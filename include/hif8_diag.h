@@ -54,14 +54,13 @@ hif8_status hif8_set_tuning(int key, int value);
 int hif8_get_tuning(int key); /* -1 for an unknown key */
 
 /*
- * Tile shape of the simulated HiF8 GEMMs (hif8_gemm_*, hif8_gemm_expanded_*):
- *   0 = choose the tile shape by problem size (default: 5 when there is a
- *                     256 x 256 tile for every compute unit, else 6); 1..6 = fixed workgroup tile /
- *                     wavefront layouts (for benchmarking): 1 = 128 x 128 x 64 (4 wavefronts),
- *                     2 = 256 x 256 x 32 (4), 3 = 256 x 128 x 32 (4), 4 = 256 x 256 x 32 (8, as 2 x 4),
- *                     5 = 256 x 256 x 32 (8, as 4 x 2), 6 = 128 x 128 x 32 (4, two workgroups per CU);
- *                     7..9 = layouts of the expanded-operand kernel below (hif8_gemm_expanded_*): 7 = 256 x 256 x 64
- *                     (8, as 2 x 4), 8 = the same as 4 x 2, 9 = 128 x 128 x 64 (4).  0 resets both choices.
+ * Tile shape of the simulated HiF8 GEMMs, for benchmarking (default 0 = chosen by problem size).
+ *   code-operand kernel (hif8_gemm_*):         5 = 256 x 256 x 32 workgroup tile, 8 wavefronts as 4 x 2 (the
+ *                                              choice when there is such a tile for every compute unit);
+ *                                              6 = 128 x 128 x 32, 4 wavefronts, two workgroups per CU
+ *   expanded-operand kernel (hif8_gemm_expanded_*): 7 = 256 x 256 x 64, 8 wavefronts as 2 x 4; 8 = the same as
+ *                                              4 x 2; 9 = 128 x 128 x 64, 4 wavefronts
+ * 0 resets both choices.  Other values: HIF8_ERR_ARG.
  */
 hif8_status hif8_gemm_set_variant(int variant);
 

@@ -44,7 +44,6 @@ def build(force: bool = True, verbose: bool = False, jobs: int = 8) -> str:
     if not force and not is_stale():
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    extra = os.environ.get("HIF8_EXTRA_HIPCC_FLAGS", "").split()   # e.g. -D switches for experiments
     os.makedirs(OBJDIR, exist_ok=True)
     inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
     hdr_time = max(os.path.getmtime(h) for h in headers())
@@ -55,7 +54,7 @@ def build(force: bool = True, verbose: bool = False, jobs: int = 8) -> str:
                 and os.path.getmtime(obj) >= max(os.path.getmtime(src), hdr_time)):
             return obj
         lang = ["-x", "hip"] if src.endswith(".hip") else []
-        cmd = [hipcc] + HIPCC_FLAGS + extra + inc + ["-c"] + lang + [src, "-o", obj]
+        cmd = [hipcc] + HIPCC_FLAGS + inc + ["-c"] + lang + [src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

@@ -677,14 +677,19 @@ __device__ __forceinline__ void multi_amax_tiles(const hif8_cast_item* __restric
     const uint64_t local = tile - items[it].first_tile;
     const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(items[it].src);
     const uint64_t v0 = local * kMultiTileVec + threadIdx.x;
-    uint4 v[kMultiUnroll];
+    if (nvec != 0) {
+      // unconditional loads, so that all are in flight together: an index past the end reads the last vector
+      // again, which leaves the maximum as it is
+      uint4 v[kMultiUnroll];
 #pragma unroll
-    for (int j = 0; j < kMultiUnroll; ++j) {
-      const uint64_t idx = v0 + (uint64_t)j * kMultiBlock;
-      v[j] = (idx < nvec) ? (NT ? ld_stream(src4 + idx) : src4[idx]) : make_uint4(0u, 0u, 0u, 0u);
+      for (int j = 0; j < kMultiUnroll; ++j) {
+        const uint64_t idx = v0 + (uint64_t)j * kMultiBlock;
+        const uint4* q = src4 + (idx < nvec ? idx : nvec - 1);
+        v[j] = NT ? ld_stream(q) : *q;
+      }
+#pragma unroll
+      for (int j = 0; j < kMultiUnroll; ++j) m = vec_amax<SRCK>(m, v[j]);
     }
-#pragma unroll
-    for (int j = 0; j < kMultiUnroll; ++j) m = vec_amax<SRCK>(m, v[j]);
     // ragged tail of the tensor, done with its last tile
     if (local + 1 == multi_item_tiles<SRCK>(n)) {
       const uint64_t t = nvec * vec_elems<SRCK>() + threadIdx.x;
@@ -743,22 +748,30 @@ __device__ __forceinline__ void multi_encode_tiles(const hif8_cast_item* __restr
     const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(items[it].src);
     uint8_t* __restrict__ dst = items[it].dst;
     const uint64_t v0 = local * kMultiTileVec + threadIdx.x;
-    uint4 v[kMultiUnroll];
+    if (nvec != 0) {
+      // Loads without a guard (an index past the end reads the last vector again: harmless for the amax, and its
+      // cast is not stored), so that all are in flight together; stores without a guard where the whole tile
+      // lies inside the tensor -- a guarded store makes the compiler wait for every earlier store of the lane.
+      const bool full = (local + 1) * kMultiTileVec <= nvec;
+      uint4 v[kMultiUnroll];
 #pragma unroll
-    for (int j = 0; j < kMultiUnroll; ++j) {
-      const uint64_t idx = v0 + (uint64_t)j * kMultiBlock;
-      if (idx < nvec) v[j] = ld_stream(src4 + idx);
-      else if (ACC) v[j] = make_uint4(0u, 0u, 0u, 0u);
-    }
+      for (int j = 0; j < kMultiUnroll; ++j) {
+        const uint64_t idx = v0 + (uint64_t)j * kMultiBlock;
+        v[j] = ld_stream(src4 + (idx < nvec ? idx : nvec - 1));
+      }
 #pragma unroll
-    for (int j = 0; j < kMultiUnroll; ++j) {
-      const uint64_t idx = v0 + (uint64_t)j * kMultiBlock;
-      if (ACC) m = vec_amax<SRCK>(m, v[j]);
-      if (idx < nvec) {
-        if constexpr (SRCK == kSrcF32)
-          st_stream(reinterpret_cast<uint32_t*>(dst) + idx, encode4_f32<IMPL>(v[j], scale, ctx, idx * VE));
-        else
-          st_stream(reinterpret_cast<uint2*>(dst) + idx, encode8_16<IMPL, SRCK>(v[j], scale, ctx, idx * VE));
+      for (int j = 0; j < kMultiUnroll; ++j) {
+        const uint64_t idx = v0 + (uint64_t)j * kMultiBlock;
+        if (ACC) m = vec_amax<SRCK>(m, v[j]);
+        if constexpr (SRCK == kSrcF32) {
+          const uint32_t c = encode4_f32<IMPL>(v[j], scale, ctx, idx * VE);
+          if (full) st_stream(reinterpret_cast<uint32_t*>(dst) + idx, c);
+          else if (idx < nvec) st_stream(reinterpret_cast<uint32_t*>(dst) + idx, c);
+        } else {
+          const uint2 c = encode8_16<IMPL, SRCK>(v[j], scale, ctx, idx * VE);
+          if (full) st_stream(reinterpret_cast<uint2*>(dst) + idx, c);
+          else if (idx < nvec) st_stream(reinterpret_cast<uint2*>(dst) + idx, c);
+        }
       }
     }
     if (local + 1 == multi_item_tiles<SRCK>(n)) {
@@ -863,11 +876,14 @@ k_group_stage(const StageArgs sg, uint32_t* __restrict__ amax, float* __restrict
     const uint32_t local = w - it.wg_first;
     const uint64_t v0 = (uint64_t)local * kStageVec + threadIdx.x;
     const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(it.src);
+    const bool full = (uint64_t)(local + 1) * kStageVec <= nvec;  // whole chunk inside the tensor: no guards
     uint4 v[kStageU];
+    if (nvec != 0) {  // (a tensor shorter than one vector has only its ragged tail)
 #pragma unroll
-    for (int u = 0; u < kStageU; ++u) {
-      const uint64_t idx = v0 + (uint64_t)u * kStageBlock;
-      if (idx < nvec) v[u] = ld_stream(src4 + idx);
+      for (int u = 0; u < kStageU; ++u) {
+        const uint64_t idx = v0 + (uint64_t)u * kStageBlock;
+        v[u] = ld_stream(src4 + ((full || idx < nvec) ? idx : nvec - 1));  // past the end: the last vector again, not stored
+      }
     }
     const EncCtx ctx = make_ctx<IMPL>(lut, hrt.w, mode, seed);
     stage_enc_lut<IMPL, SRCK>(lut, g_lut, mode);
@@ -881,11 +897,14 @@ k_group_stage(const StageArgs sg, uint32_t* __restrict__ amax, float* __restrict
 #pragma unroll
     for (int u = 0; u < kStageU; ++u) {
       const uint64_t idx = v0 + (uint64_t)u * kStageBlock;
-      if (idx < nvec) {
-        if constexpr (SRCK == kSrcF32)
-          st_stream(reinterpret_cast<uint32_t*>(it.dst) + idx, encode4_f32<IMPL>(v[u], scale, ctx, idx * VE));
-        else
-          st_stream(reinterpret_cast<uint2*>(it.dst) + idx, encode8_16<IMPL, SRCK>(v[u], scale, ctx, idx * VE));
+      if constexpr (SRCK == kSrcF32) {
+        const uint32_t c = encode4_f32<IMPL>(v[u], scale, ctx, idx * VE);
+        if (full) st_stream(reinterpret_cast<uint32_t*>(it.dst) + idx, c);
+        else if (idx < nvec) st_stream(reinterpret_cast<uint32_t*>(it.dst) + idx, c);
+      } else {
+        const uint2 c = encode8_16<IMPL, SRCK>(v[u], scale, ctx, idx * VE);
+        if (full) st_stream(reinterpret_cast<uint2*>(it.dst) + idx, c);
+        else if (idx < nvec) st_stream(reinterpret_cast<uint2*>(it.dst) + idx, c);
       }
     }
     if (local + 1 == stage_item_wgs<SRCK>(it.n, kStageVec)) {  // ragged tail of the tensor

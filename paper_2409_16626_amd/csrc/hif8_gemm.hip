@@ -320,12 +320,8 @@ static hif8_status gemm_dispatch(const uint8_t* A, const uint8_t* B, void* out, 
   }
   if (variant == 0)  // 256 x 256 tiles once there is one for every compute unit, else 128 x 128 (two workgroups per CU)
     variant = (((M + 255) / 256) * ((N + 255) / 256) >= (size_t)cus) ? 5 : 6;
-  if (variant == 2) return launch_tiled<2, 2, 4, 4, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
-  if (variant == 3) return launch_tiled<2, 2, 4, 2, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
-  if (variant == 4) return launch_tiled<2, 4, 4, 2, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
   if (variant == 5) return launch_tiled<4, 2, 2, 4, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
-  if (variant == 6) return launch_tiled<2, 2, 2, 2, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
-  return launch_tiled<2, 2, 2, 2, 64, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
+  return launch_tiled<2, 2, 2, 2, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
 }
 
 // position of the smallest finite entry of err[rows * cols] -> best[0] = e_row_lo + row,
@@ -403,7 +399,7 @@ using namespace hif8gemm;
 extern "C" {
 
 hif8_status hif8_gemm_set_variant(int variant) {
-  if (variant < 0 || variant > 9) return HIF8_ERR_ARG;
+  if (variant != 0 && (variant < 5 || variant > 9)) return HIF8_ERR_ARG;
   if (variant == 0) {
     g_gemm_variant = 0;
     expanded_variant() = 0;

@@ -52,7 +52,7 @@ SHAPES = [(32, 32, 16), (128, 128, 64), (100, 70, 48), (257, 129, 80), (1, 1, 16
           (256, 256, 32), (300, 520, 4096), (33, 17, 16)]
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("variant", [5, 6])
 @pytest.mark.parametrize("M,N,K", SHAPES)
 def test_gemm_f32_matches_oracle(h, variant, M, N, K):
     rng = np.random.default_rng(M * 7 + N * 3 + K)
@@ -78,7 +78,7 @@ def test_gemm_exact_when_sums_fit_24_bits(h):
     assert [orc.decode_value(int(c)) for c in ints] == [0, 1, 2, 3, 4, -1, -2, -3, -4]
     ca, cb = rng.choice(ints, size=(M, K)), rng.choice(ints, size=(N, K))
     a, b = torch.from_numpy(ca).to(dev()), torch.from_numpy(cb).to(dev())
-    for variant in (1, 2, 3, 4, 5, 6):
+    for variant in (5, 6):
         h.hif8_gemm_set_variant(variant)
         out = torch.zeros(M, N, dtype=torch.float32, device=dev())
         h.hif8_gemm_f32(a, b, out, M, N, K, 1.0, 1.0)
@@ -120,7 +120,7 @@ def test_gemm_special_codes_follow_ieee(h):
     ca[20, 7] = 0xEF      # -Inf, meeting a zero below: Inf * 0 = NaN
     cb[11, 7] = 0x00
     a, b = torch.from_numpy(ca).to(dev()), torch.from_numpy(cb).to(dev())
-    for variant in (1, 2):
+    for variant in (5, 6):
         h.hif8_gemm_set_variant(variant)
         out = torch.zeros(M, N, dtype=torch.float32, device=dev())
         h.hif8_gemm_f32(a, b, out, M, N, K, 1.0, 1.0)
@@ -159,7 +159,7 @@ def test_gemm_sqerr_epilogue(h):
     S = np.sum((want_o - ref.astype(np.float64)) ** 2)
     e = K * 2.0 ** -23 * go.gemm_abs_bound(ca, cb, 4.0, 64.0)
     tol = 2 * np.sqrt(S * np.sum(e ** 2)) + np.sum(e ** 2)
-    for variant in (1, 2, 3, 4, 5, 6):
+    for variant in (5, 6):
         h.hif8_gemm_set_variant(variant)
         err = torch.zeros(2, dtype=torch.float64, device=dev())
         h.hif8_gemm_sqerr(a, b, r, M, N, K, 4.0, 64.0, err)
