@@ -588,6 +588,15 @@ def main():
         tm = timed(c5, 5, 1)
         extra["C5 per-tensor calls, 225 x (amax, scale, encode_bf16) (3 B/elem primary)"] = rate(3 * tot, tm)
         extra["C5 per-tensor calls (5 B/elem with amax pass)"] = rate(5 * tot, tm)
+        ws = torch.zeros(hif8.hif8_quantize_workspace_bytes(), dtype=torch.uint8, device=dev)
+
+        def c5_qt(i):
+            for t, (_, off, cnt) in enumerate(index):
+                hif8.hif8_quantize_tensor_bf16(ap + 2 * off, None, cp + off, cnt, amp + 4 * t, scp + 8 * t, ws,
+                                               hif8.MAX_FINITE, 0, hif8.RM_TA)
+
+        tm = timed(c5_qt, 5, 1)
+        extra["C5 per-tensor calls, 225 x hif8_quantize_tensor_bf16 (2 launches each) (3 B/elem primary)"] = rate(3 * tot, tm)
         items = [(ap + 2 * off, cp + off, cnt) for _, off, cnt in index]
         plan = hif8.hif8_multi_plan(items, src_is_16bit=True)
         d_items, count, tiles = plan

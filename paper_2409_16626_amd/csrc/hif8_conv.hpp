@@ -629,7 +629,11 @@ k_amax_elem(const void* __restrict__ src, size_t n, uint32_t* __restrict__ out) 
 // launch gaps.  All tensors share one global tile index space; items[i].first_tile is the
 // prefix sum of tile counts.  A tile is kMultiBlock * kMultiUnroll vector units of one tensor.
 // ------------------------------------------------------------------------------------
-constexpr uint32_t kMultiTpwEncode = 2;
+// Tiles per workgroup of the multi-tensor cast.  Two keep the most workgroups in flight, which is what the plain
+// TA cast wants; with the amax accumulation (one atomic per workgroup and tensor) or a larger table to stage per
+// workgroup (every implementation but TA), four measured 3-16 % faster on the 225-tensor LLM weight list.
+template <int IMPL, bool ACC>
+__host__ __device__ constexpr uint32_t multi_tpw_encode() { return (ACC || IMPL != IMPL_TA_LUT) ? 4u : 2u; }
 constexpr uint32_t kMultiTpwAmax = 8;
 
 // largest i with items[i].first_tile <= tile (zero-size items are skipped by construction)
@@ -699,27 +703,17 @@ __device__ __forceinline__ void multi_amax_tiles(const hif8_cast_item* __restric
   if (cur != 0xFFFFFFFFu) block_max_to_global(umax(fold_amax<SRCK>(m), mt), amax_out + cur);
 }
 
-// Where the multi-tensor cast takes the scale of item `it` from: the pair in d_scale2 (written earlier on the
-// stream), or -- FROM_AMAX -- derived here from the finished amax of the item, in which case the workgroup that
-// casts the item's first tile also publishes the pair to d_scale2.
-struct MultiScale {
-  const float* d_scale2_in;
-  const uint32_t* amax_in;
-  float* d_scale2_out;
-  float target;
-  int pow2;
-};
-
-// Cast of the tiles [first, first + kMultiTpwEncode) below tile_end.  ACC: also accumulate the amax of every
-// tensor's source into amax_acc[item] (delayed scaling: the scales in use come from earlier iterations, the
-// accumulators feed the next update).  The encode tables must be staged (and a barrier passed) before.
-template <int IMPL, int SRCK, bool ACC, bool FROM_AMAX>
+// Cast of the tiles [first, first + multi_tpw_encode()) below tile_end, each tensor with the scale d_scale2[2 * item]
+// (written earlier on the stream).  ACC: also accumulate the amax of every tensor's source into amax_acc[item]
+// (delayed scaling: the scales in use come from earlier iterations, the accumulators feed the next update).
+// The encode tables must be staged (and a barrier passed) before.
+template <int IMPL, int SRCK, bool ACC>
 __device__ __forceinline__ void multi_encode_tiles(const hif8_cast_item* __restrict__ items, uint32_t count,
-                                                   uint64_t first, uint64_t tile_end, const MultiScale& ms,
+                                                   uint64_t first, uint64_t tile_end, const float* __restrict__ d_scale2,
                                                    uint32_t* __restrict__ amax_acc, const EncCtx& ctx) {
   constexpr int VE = vec_elems<SRCK>();
   uint32_t m = 0, mt = 0, cur = 0xFFFFFFFFu;  // ACC: as in multi_amax_tiles
-  for (uint32_t i = 0; i < kMultiTpwEncode; ++i) {
+  for (uint32_t i = 0; i < multi_tpw_encode<IMPL, ACC>(); ++i) {
     const uint64_t tile = first + i;
     if (tile >= tile_end) break;
     const uint32_t it = multi_find_item(items, count, tile);
@@ -735,42 +729,27 @@ __device__ __forceinline__ void multi_encode_tiles(const hif8_cast_item* __restr
     const uint64_t n = items[it].n;
     const uint64_t nvec = n >> vec_shift<SRCK>();
     const uint64_t local = tile - items[it].first_tile;
-    float scale;
-    if constexpr (FROM_AMAX) {
-      scale = scale_from_amax_value(__uint_as_float(ms.amax_in[it]), ms.target, ms.pow2);
-      if (local == 0 && threadIdx.x == 0) {
-        ms.d_scale2_out[2 * it] = scale;
-        ms.d_scale2_out[2 * it + 1] = 1.0f / scale;
-      }
-    } else {
-      scale = ms.d_scale2_in[2 * it];
-    }
+    const float scale = d_scale2[2 * it];
     const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(items[it].src);
     uint8_t* __restrict__ dst = items[it].dst;
     const uint64_t v0 = local * kMultiTileVec + threadIdx.x;
     if (nvec != 0) {
-      // Loads without a guard (an index past the end reads the last vector again: harmless for the amax, and its
-      // cast is not stored), so that all are in flight together; stores without a guard where the whole tile
-      // lies inside the tensor -- a guarded store makes the compiler wait for every earlier store of the lane.
-      const bool full = (local + 1) * kMultiTileVec <= nvec;
       uint4 v[kMultiUnroll];
 #pragma unroll
       for (int j = 0; j < kMultiUnroll; ++j) {
         const uint64_t idx = v0 + (uint64_t)j * kMultiBlock;
-        v[j] = ld_stream(src4 + (idx < nvec ? idx : nvec - 1));
+        if (idx < nvec) v[j] = ld_stream(src4 + idx);
+        else if (ACC) v[j] = make_uint4(0u, 0u, 0u, 0u);
       }
 #pragma unroll
       for (int j = 0; j < kMultiUnroll; ++j) {
         const uint64_t idx = v0 + (uint64_t)j * kMultiBlock;
         if (ACC) m = vec_amax<SRCK>(m, v[j]);
-        if constexpr (SRCK == kSrcF32) {
-          const uint32_t c = encode4_f32<IMPL>(v[j], scale, ctx, idx * VE);
-          if (full) st_stream(reinterpret_cast<uint32_t*>(dst) + idx, c);
-          else if (idx < nvec) st_stream(reinterpret_cast<uint32_t*>(dst) + idx, c);
-        } else {
-          const uint2 c = encode8_16<IMPL, SRCK>(v[j], scale, ctx, idx * VE);
-          if (full) st_stream(reinterpret_cast<uint2*>(dst) + idx, c);
-          else if (idx < nvec) st_stream(reinterpret_cast<uint2*>(dst) + idx, c);
+        if (idx < nvec) {
+          if constexpr (SRCK == kSrcF32)
+            st_stream(reinterpret_cast<uint32_t*>(dst) + idx, encode4_f32<IMPL>(v[j], scale, ctx, idx * VE));
+          else
+            st_stream(reinterpret_cast<uint2*>(dst) + idx, encode8_16<IMPL, SRCK>(v[j], scale, ctx, idx * VE));
         }
       }
     }
@@ -804,9 +783,8 @@ k_multi_encode(const hif8_cast_item* __restrict__ items, uint32_t count, uint64_
   stage_enc_lut<IMPL, SRCK>(lut, g_lut, mode);
   stage_exp_table<IMPL, SRCK>(hrt.w, mode);
   __syncthreads();
-  const MultiScale ms{d_scale2, nullptr, nullptr, 0.0f, 0};
-  multi_encode_tiles<IMPL, SRCK, ACC, false>(items, count, (uint64_t)blockIdx.x * kMultiTpwEncode, total_tiles, ms,
-                                             amax_acc, ctx);
+  multi_encode_tiles<IMPL, SRCK, ACC>(items, count, (uint64_t)blockIdx.x * multi_tpw_encode<IMPL, ACC>(), total_tiles, d_scale2,
+                                      amax_acc, ctx);
 }
 
 // One stage of the group-wise multi-tensor cast: am_wgs workgroups gather the amax of the tensors am[] of one
@@ -1212,9 +1190,11 @@ inline void dispatch_multi_impl(uint32_t mode, F&& go) {
 template <int SRCK, bool ACC>
 void launch_multi_encode(const hif8_cast_item* d_items, uint32_t cnt, uint64_t total_tiles, const float* d_scale2,
                          uint32_t* amax_acc, uint32_t mode, uint64_t seed, const DevTables& tb, hipStream_t st) {
-  const dim3 g2((unsigned)((total_tiles + kMultiTpwEncode - 1) / kMultiTpwEncode)), blk(kMultiBlock);
+  const dim3 blk(kMultiBlock);
   dispatch_multi_impl<SRCK>(mode, [&](auto impl_c) {
     constexpr int IMPL = decltype(impl_c)::value;
+    constexpr uint32_t tpw = multi_tpw_encode<IMPL, ACC>();
+    const dim3 g2((unsigned)((total_tiles + tpw - 1) / tpw));
     hipLaunchKernelGGL((k_multi_encode<IMPL, SRCK, ACC>), g2, blk, 0, st, d_items, cnt, total_tiles, d_scale2, amax_acc, mode,
                        seed, enc_table_for<IMPL>(tb));
   });

@@ -92,3 +92,71 @@ def test_cast_and_gemm_sequence_replays_exactly(h):
         assert np.array_equal(graphed.xc.cpu().numpy().reshape(-1), orc.encode_bf16(xn.reshape(-1), w_s, orc.RM_TA))
         assert np.array_equal(graphed.mc[:M * K].cpu().numpy(), orc.encode_bf16(xn.reshape(-1), w_s, orc.RM_TA))
         assert graphed.acc[0].item() == float(w_am)
+
+
+def test_one_call_entry_points_replay_exactly(h):
+    """Per-tensor scaling in one call (workspace and static-scratch forms) and the group-wise
+    multi-tensor cast under capture: they enqueue kernels only, so a captured sequence replays
+    bit for bit on fresh inputs, and matches the oracle."""
+    n0, n1 = 70001 * 16, 4099 * 16            # both multiples of 16 elements: slices stay 16-byte aligned
+    n = n0 + n1
+    g = torch.Generator(device=dev()).manual_seed(77)
+    x = torch.empty(n, dtype=torch.bfloat16, device=dev())
+    xf = torch.empty(n1, dtype=torch.float32, device=dev())
+
+    class Bufs:
+        def __init__(self):
+            self.ws = torch.zeros(h.hif8_quantize_workspace_bytes(), dtype=torch.uint8, device=dev())
+            self.am = torch.zeros(4, dtype=torch.float32, device=dev())
+            self.sc = torch.zeros(4, 2, dtype=torch.float32, device=dev())
+            self.c_ws = torch.empty(n, dtype=torch.uint8, device=dev())
+            self.q_ws = torch.empty(n, dtype=torch.bfloat16, device=dev())
+            self.c_st = torch.empty(n1, dtype=torch.uint8, device=dev())
+            self.c_mc = torch.empty(n, dtype=torch.uint8, device=dev())
+            self.plan = h.hif8_multi_plan([(x.data_ptr(), self.c_mc.data_ptr(), n0),
+                                           (x[n0:].data_ptr(), self.c_mc[n0:].data_ptr(), n1)], src_is_16bit=True)
+
+    def sequence(b):
+        h.hif8_quantize_tensor_bf16(x, b.q_ws, b.c_ws, n, b.am[0:1], b.sc[0], b.ws, h.MAX_FINITE, 1, h.RM_TA)
+        h.hif8_quantize_tensor_static(xf, None, b.c_st, n1, h.KIND_F32, b.am[1:2], b.sc[1], h.MAX_FINITE, 0, h.RM_HR)
+        d_items, count, tiles = b.plan
+        h.hif8_multi_cast_bf16(d_items, count, tiles, b.am[2:4], b.sc[2:4], h.MAX_FINITE, 1, h.RM_TA,
+                               host_items=b.plan.host_items)
+
+    eager, graphed = Bufs(), Bufs()
+    x.copy_(torch.randn(n, generator=g, device=dev()).to(torch.bfloat16))
+    xf.copy_(torch.randn(n1, generator=g, device=dev()))
+    sequence(graphed)
+    torch.cuda.synchronize()
+
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sequence(graphed)
+
+    for rep in range(4):
+        gain = 0.25 + 5.0 * (3 - rep)                                          # amax shrinks from replay to replay
+        x.copy_((torch.randn(n, generator=g, device=dev()) * gain).to(torch.bfloat16))
+        xf.copy_(torch.randn(n1, generator=g, device=dev()) * gain)
+        torch.cuda.synchronize()
+        for t in (graphed.c_ws, graphed.c_st, graphed.c_mc):
+            t.fill_(0)
+        graph.replay()
+        sequence(eager)
+        torch.cuda.synchronize()
+        for name in ("am", "sc", "c_ws", "c_st", "c_mc"):
+            assert torch.equal(getattr(graphed, name), getattr(eager, name)), (rep, name)
+        assert torch.equal(graphed.q_ws.view(torch.int16), eager.q_ws.view(torch.int16)), rep
+        xn, fn = bf16_bits(x), xf.cpu().numpy()
+        am = orc.amax_bf16(xn)
+        s = orc.scale_from_amax(am, 32768.0, True)
+        assert graphed.am[0].item() == float(am) and graphed.sc[0, 0].item() == float(s)
+        assert np.array_equal(graphed.c_ws.cpu().numpy(), orc.encode_bf16(xn, s, orc.RM_TA))
+        amf = orc.amax_f32(fn)
+        sf = orc.scale_from_amax(amf, 32768.0, False)
+        assert graphed.am[1].item() == float(amf) and graphed.sc[1, 0].item() == float(sf)
+        assert np.array_equal(graphed.c_st.cpu().numpy(), orc.encode_f32(fn, sf, orc.RM_HR))
+        for k, (lo, m) in enumerate(((0, n0), (n0, n1))):
+            amk = orc.amax_bf16(xn[lo:lo + m])
+            sk = orc.scale_from_amax(amk, 32768.0, True)
+            assert graphed.am[2 + k].item() == float(amk)
+            assert np.array_equal(graphed.c_mc[lo:lo + m].cpu().numpy(), orc.encode_bf16(xn[lo:lo + m], sk, orc.RM_TA)), (rep, k)
