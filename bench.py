@@ -127,10 +127,22 @@ def main():
             hif8.hif8_set_tuning(k, v)
     tune = [hif8.hif8_get_tuning(k) for k in range(hif8.N_TUNE_KEYS)]
 
+    def gemm_operands(gm, gn, gk):
+        ws = torch.zeros(hif8.hif8_quantize_workspace_bytes(), dtype=torch.uint8, device=dev)
+        am = torch.zeros(2, dtype=torch.float32, device=dev)
+        sc = torch.zeros(2, 2, dtype=torch.float32, device=dev)
+        act = workloads.activation_bf16(gm, gk, dev)
+        wgt = (workloads.normal_f32(gn * gk, dev) * 0.02).to(torch.bfloat16)
+        ca = torch.empty(gm, gk, dtype=torch.uint8, device=dev)
+        cb = torch.empty(gn, gk, dtype=torch.uint8, device=dev)
+        hif8.hif8_quantize_tensor_bf16(act, None, ca, gm * gk, am[0:1], sc[0], ws, hif8.MAX_FINITE, 1, hif8.RM_TA)
+        hif8.hif8_quantize_tensor_bf16(wgt, None, cb, gn * gk, am[1:2], sc[1], ws, hif8.MAX_FINITE, 1, hif8.RM_TA)
+        torch.cuda.synchronize()
+        return ca, cb
+
     if args.gemm_only:
         gm = gn = gk = 8192
-        ca = torch.randint(8, 0x50, (gm, gk), dtype=torch.int32, device=dev).to(torch.uint8)
-        cb = torch.randint(8, 0x50, (gn, gk), dtype=torch.int32, device=dev).to(torch.uint8)
+        ca, cb = gemm_operands(gm, gn, gk)
         go = torch.empty(gm, gn, dtype=torch.bfloat16, device=dev)
         tm = timed(lambda i: hif8.hif8_gemm_bf16(ca, cb, go, gm, gn, gk, 1.0, 1.0), 20, 5)
         fl = 2.0 * gm * gn * gk
@@ -516,8 +528,10 @@ def main():
         # and Algorithm 1 for one layer
         MFMA_PEAK = 2.5e15
         for (gm, gn, gk) in ((8192, 8192, 8192), (8192, 11008, 4096)):
-            ca = torch.randint(8, 0x50, (gm, gk), dtype=torch.int32, device=dev).to(torch.uint8)
-            cb = torch.randint(8, 0x50, (gn, gk), dtype=torch.int32, device=dev).to(torch.uint8)
+            # operands as a training step has them: the per-tensor-scaled HiF8 cast of an activation tensor with
+            # outliers (the C3 recipe) and of N(0, 0.02) weights (the C5 recipe); the matrix-core clock under
+            # load, and with it the rate, follows the operand values
+            ca, cb = gemm_operands(gm, gn, gk)
             go = torch.empty(gm, gn, dtype=torch.bfloat16, device=dev)
             tm = timed(lambda i: hif8.hif8_gemm_bf16(ca, cb, go, gm, gn, gk, 1.0, 1.0), 20, 5)
             fl = 2.0 * gm * gn * gk
@@ -545,6 +559,11 @@ def main():
                 "expand_both_operands_ms": round(tmx.ms, 4), "expand_GB/s (3 B/elem)": round(3.0 * (gm + gn) * gk / (tmx.ms * 1e-3) / 1e9, 1),
                 "TFLOP/s incl. expansion": round(fl / ((tm.ms + tmx.ms) * 1e-3) / 1e12, 1),
                 "transposing_expand_of_B_ms": round(tmt.ms, 4), "transposing_expand_GB/s (3 B/elem)": round(3.0 * gn * gk / (tmt.ms * 1e-3) / 1e9, 1)}
+            # comparison, not part of the path: the vendor library's bf16 GEMM (torch.matmul) on the same expanded operands
+            tmv = timed(lambda i: torch.matmul(xa, xb.t(), out=go), 20, 5)
+            extra["comparison: torch.matmul bf16 on the same expanded operands, M=%d N=%d K=%d" % (gm, gn, gk)] = {
+                "ms": round(tmv.ms, 4), "TFLOP/s": round(fl / (tmv.ms * 1e-3) / 1e12, 1),
+                "frac_of_2.5PFLOPs_bf16": round(fl / (tmv.ms * 1e-3) / MFMA_PEAK, 4)}
             del ca, cb, go, xa, xb
         lm, ln, lk = 2048, 4096, 4096
         xa = torch.randn(lm, lk, device=dev).to(torch.bfloat16)
