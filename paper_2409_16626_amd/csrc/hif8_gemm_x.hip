@@ -44,7 +44,7 @@ constexpr int kRsrcFlags = 0x00020000;    // word 3 of a raw (unstructured, unty
 constexpr uint32_t kXcds = 8;             // accelerator dies, each with an L2 of its own
 constexpr uint32_t kGroupM = 8;           // tile rows per group of the tile order
 
-template <int WM, int WN, int TM, int TN, int EPI>
+template <int WM, int WN, int TM, int TN, int EPI, int FINE = 0>
 __global__ void __launch_bounds__(64 * WM * WN)
 k_gemm_x(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, void* __restrict__ out,
          const float* __restrict__ ref, double* __restrict__ err, uint32_t M, uint32_t N, uint32_t ld,
@@ -183,17 +183,79 @@ k_gemm_x(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, void* _
     __builtin_amdgcn_sched_barrier(0);
     mfmas(1);
   };
+  // The same K step with every instruction placed by hand (FINE): one fragment read behind each of the first
+  // TM + TN MFMAs of a group, and the tile loads of the step after next spread over the last group, so that a
+  // wavefront that has its SIMD to itself never leaves the matrix core waiting behind a burst of memory
+  // instructions.  Used while two more tiles follow; the last steps run k_step.
+  auto read_one = [&](int buf, int stage, int s, int r) {
+    const uint8_t* base = smem + fbase[stage][s];
+    if (r < TM) fa[buf][r] = *reinterpret_cast<const bf16x8*>(base + r * 32 * kRowBytes);
+    else fb[buf][r - TM] = *reinterpret_cast<const bf16x8*>(base + b_delta + (r - TM) * 32 * kRowBytes);
+  };
+  auto issue_one = [&](int stage, int i) {
+    uint8_t* sa = smem + stage * kStageBytes + wave * IA * kRowsPerLoad * kRowBytes;
+    uint8_t* sb = smem + stage * kStageBytes + BM * kRowBytes + wave * IB * kRowsPerLoad * kRowBytes;
+    if (i < IA)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(res_a, (__attribute__((address_space(3))) void*)(sa + i * kRowsPerLoad * kRowBytes),
+                                               16, (int)off_a[i], (int)koff, 0, 0);
+    else
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(res_b, (__attribute__((address_space(3))) void*)(sb + (i - IA) * kRowsPerLoad * kRowBytes),
+                                               16, (int)off_b[i - IA], (int)koff, 0, 0);
+  };
+  auto fine_step = [&](int cur) {
+    constexpr int NM = TM * TN, NR = TM + TN, NL = IA + IB;
+    static_assert(NR <= NM, "one fragment read per MFMA");
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int buf = s & 1;
+      __builtin_amdgcn_sched_barrier(0);
+      if (s == 3) {
+        // tile kt + 1 has landed and the last fragments of tile kt are in registers, for the whole workgroup
+        __builtin_amdgcn_s_waitcnt(kWaitVm0Lgkm0);
+        __syncthreads();
+      } else {
+        __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int idx = 0; idx < NM; ++idx) {
+        const int i = idx / TN, j = idx % TN;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
+        if (idx < NR) {
+          if (s < 3) read_one(buf ^ 1, cur, s + 1, idx);
+          else read_one(buf ^ 1, cur ^ 1, 0, idx);
+        }
+        if (s == 3) {
+#pragma unroll
+          for (int l = idx * NL / NM; l < (idx + 1) * NL / NM; ++l) issue_one(cur, l);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    koff += kBK * 2;
+  };
   issue(0);
   __builtin_amdgcn_s_waitcnt(kWaitVm0);
   __syncthreads();
   if (nk > 1) issue(1);
   read_frags(0, 0, 0);
   uint32_t kt = 0;
-  for (; kt + 1 < nk; kt += 2) {
-    k_step(0, kt);
-    k_step(1, kt + 1);
+  if constexpr (FINE != 0) {
+    for (; kt + 3 < nk; kt += 2) {
+      fine_step(0);
+      fine_step(1);
+    }
+    // at most three steps are left, and kt is even
+    if (kt < nk) k_step(0, kt);
+    if (kt + 1 < nk) k_step(1, kt + 1);
+    if (kt + 2 < nk) k_step(0, kt + 2);
+  } else {
+    for (; kt + 1 < nk; kt += 2) {
+      k_step(0, kt);
+      k_step(1, kt + 1);
+    }
+    if (kt < nk) k_step(0, kt);
   }
-  if (kt < nk) k_step(0, kt);
 
   // every fragment of the last step was in registers before the last barrier, so the tile LDS is free
   epilogue<EPI, TM, TN>(acc, out, ref, err, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, descale,
@@ -331,7 +393,7 @@ int& expanded_variant() {
   return v;
 }
 
-template <int WM, int WN, int TM, int TN, int EPI>
+template <int WM, int WN, int TM, int TN, int EPI, int FINE = 0>
 static hif8_status launch_x(const uint16_t* A, const uint16_t* B, void* out, const float* ref, double* err, uint32_t M,
                             uint32_t N, uint32_t ld, float descale, hipStream_t st, const Batch& batch, uint32_t pairs,
                             uint32_t col_begin = 0, uint32_t col_end = 0xFFFFFFFFu) {
@@ -343,7 +405,7 @@ static hif8_status launch_x(const uint16_t* A, const uint16_t* B, void* out, con
   if (!hip_ok(hipGetDevice(&dev))) return HIF8_ERR_HIP;
   if (dev < 0 || dev >= kMaxDevices) return HIF8_ERR_ARG;
   if (!attr_set[dev]) {
-    if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_x<WM, WN, TM, TN, EPI>),
+    if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_x<WM, WN, TM, TN, EPI, FINE>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem)))
       return HIF8_ERR_HIP;
     attr_set[dev] = true;
@@ -352,7 +414,7 @@ static hif8_status launch_x(const uint16_t* A, const uint16_t* B, void* out, con
   const uint32_t tiles_m = (M + BM - 1) / BM, tiles_n = (col_end - col_begin + BN - 1) / BN;
   if ((uint64_t)tiles_m * tiles_n > 0x7FFFFFFFull || pairs == 0 || pairs > 65535u) return HIF8_ERR_ARG;
   const uint32_t grid_x = (tiles_m * tiles_n + kXcds - 1u) / kXcds * kXcds;  // a whole number of workgroups per die
-  hipLaunchKernelGGL((k_gemm_x<WM, WN, TM, TN, EPI>), dim3(grid_x, pairs), dim3(64 * WM * WN), smem, st, A, B,
+  hipLaunchKernelGGL((k_gemm_x<WM, WN, TM, TN, EPI, FINE>), dim3(grid_x, pairs), dim3(64 * WM * WN), smem, st, A, B,
                      out, ref, err, M, N, ld, descale, tiles_n, col_begin, batch);
   return finish_launch();
 }
@@ -371,19 +433,26 @@ hif8_status gemm_expanded(const uint16_t* A, const uint16_t* B, void* out, const
   int cus = 0;
   hif8_status s = ensure_init(&cus, nullptr);
   if (s != HIF8_OK) return s;
-  // 256 x 256 tiles (8 wavefronts) once the launch has one for every compute unit, else 128 x 128 (4 wavefronts)
+  // 256 x 256 tiles once the launch has one for every compute unit, else 128 x 128 (4 wavefronts, two workgroups
+  // per compute unit).  The large tile runs the hand-placed K step: as 2 x 2 wavefronts of 128 x 128 each (a third
+  // fewer fragment reads per MFMA) when the launch lasts several rounds, as 2 x 4 wavefronts of 128 x 64 when it is
+  // a single round, where the second wavefront per SIMD covers the start and the end of the tile.
   const size_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256) * (size_t)pairs;
   int variant = expanded_variant();
   uint32_t split = 0;
   if (variant == 0 && pairs == 1 && ragged_round_split(M, N, (size_t)cus, &split)) {
     // complete rounds of 256 x 256 tiles, then the remaining columns in 128 x 128 tiles (second launch)
-    s = launch_x<2, 4, 4, 2, EPI>(A, B, out, ref, err, (uint32_t)M, (uint32_t)N, (uint32_t)ld, descale, st, batch, pairs,
-                                  0u, split);
+    s = launch_x<2, 2, 4, 4, EPI, 1>(A, B, out, ref, err, (uint32_t)M, (uint32_t)N, (uint32_t)ld, descale, st, batch, pairs,
+                                     0u, split);
     if (s != HIF8_OK) return s;
     return launch_x<2, 2, 2, 2, EPI>(A, B, out, ref, err, (uint32_t)M, (uint32_t)N, (uint32_t)ld, descale, st, batch, pairs,
                                      split, (uint32_t)N);
   }
-  if (variant == 0) variant = big_tiles >= (size_t)cus ? 7 : 9;
+  if (variant == 0) variant = big_tiles >= 2 * (size_t)cus ? 10 : big_tiles >= (size_t)cus ? 11 : 9;
+  if (variant == 10)
+    return launch_x<2, 2, 4, 4, EPI, 1>(A, B, out, ref, err, (uint32_t)M, (uint32_t)N, (uint32_t)ld, descale, st, batch, pairs);
+  if (variant == 11)
+    return launch_x<2, 4, 4, 2, EPI, 1>(A, B, out, ref, err, (uint32_t)M, (uint32_t)N, (uint32_t)ld, descale, st, batch, pairs);
   if (variant == 7)
     return launch_x<2, 4, 4, 2, EPI>(A, B, out, ref, err, (uint32_t)M, (uint32_t)N, (uint32_t)ld, descale, st, batch, pairs);
   if (variant == 8)
