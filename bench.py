@@ -156,6 +156,9 @@ def main():
         tm = timed(lambda i: hif8.hif8_gemm_expanded_bf16(xa, xb, go, gm, gn, gk, ld, 1.0, 1.0), 20, 5)
         res["gemm_expanded_bf16 M=N=K=8192"] = {"ms": round(tm.ms, 4), "TFLOP/s": round(fl / (tm.ms * 1e-3) / 1e12, 1),
                                                 "frac_of_2.5PFLOPs_bf16": round(fl / (tm.ms * 1e-3) / 2.5e15, 4)}
+        tm = timed(lambda i: torch.matmul(xa, xb.t(), out=go), 20, 5)   # comparison: the vendor library on the same operands
+        res["comparison: torch.matmul bf16 M=N=K=8192"] = {"ms": round(tm.ms, 4), "TFLOP/s": round(fl / (tm.ms * 1e-3) / 1e12, 1),
+                                                           "frac_of_2.5PFLOPs_bf16": round(fl / (tm.ms * 1e-3) / 2.5e15, 4)}
         print(json.dumps(res), flush=True)
         return
 
