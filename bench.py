@@ -541,6 +541,13 @@ def main():
             extra["gemm_bf16 out, HiF8 operands, M=%d N=%d K=%d" % (gm, gn, gk)] = {
                 "ms": round(tm.ms, 4), "TFLOP/s": round(fl / (tm.ms * 1e-3) / 1e12, 1), "bound": "mfma",
                 "frac_of_2.5PFLOPs_bf16": round(fl / (tm.ms * 1e-3) / MFMA_PEAK, 4)}
+            # code operands through a workspace: both expansions and the expanded-operand kernel in one call
+            wsg = torch.empty(hif8.hif8_gemm_workspace_bytes(gm, gn, gk), dtype=torch.uint8, device=dev)
+            tm = timed(lambda i: hif8.hif8_gemm_ws_bf16(ca, cb, go, gm, gn, gk, wsg, 1.0, 1.0), 20, 5)
+            extra["gemm_ws_bf16 out, HiF8 operands expanded into a workspace, M=%d N=%d K=%d" % (gm, gn, gk)] = {
+                "ms": round(tm.ms, 4), "TFLOP/s": round(fl / (tm.ms * 1e-3) / 1e12, 1), "bound": "mfma",
+                "frac_of_2.5PFLOPs_bf16": round(fl / (tm.ms * 1e-3) / MFMA_PEAK, 4)}
+            del wsg
             # the same product on operands expanded to bfloat16 once (expansion timed separately, and together)
             ld = hif8.hif8_expanded_ld(gk)
             xa = torch.empty(gm, ld, dtype=torch.bfloat16, device=dev)

@@ -582,6 +582,32 @@ hif8_status hif8_gemm_expanded_sqerr(const uint16_t* a, const uint16_t* b, const
                                      double* d_err, hif8_stream_t stream);
 
 /*
+ * hif8_gemm_* on code operands with a workspace: both code matrices are expanded to bfloat16 into the
+ * workspace (hif8_expand_bf16) and multiplied by the expanded-operand kernel -- three launches on `stream`, and
+ * for matrix-core-bound shapes about two thirds of the time of hif8_gemm_* (whose kernel expands the codes on
+ * their way into LDS and is bound by that work).  Arguments, result and error bound as for hif8_gemm_* (the
+ * result equals that of hif8_gemm_expanded_* on the expanded operands bit for bit); any K and any alignment of
+ * the code matrices.
+ * workspace: device memory, 16-byte aligned, at least hif8_gemm_workspace_bytes(M, N, K) bytes
+ * (= 2 (M + N) hif8_expanded_ld(K), 0 when M, N or K is 0), caller-owned, free for other use once the
+ * work enqueued here has run; a smaller workspace_bytes is HIF8_ERR_ARG.  K beyond 2^22 (the expanded-operand
+ * kernel's limit) falls back to the hif8_gemm_* kernel and leaves the workspace unused.
+ */
+size_t hif8_gemm_workspace_bytes(size_t M, size_t N, size_t K);
+hif8_status hif8_gemm_ws_f32(const uint8_t* a_codes, const uint8_t* b_codes, float* out, size_t M, size_t N,
+                             size_t K, float scale_a, float scale_b, void* workspace, size_t workspace_bytes,
+                             hif8_stream_t stream);
+hif8_status hif8_gemm_ws_bf16(const uint8_t* a_codes, const uint8_t* b_codes, uint16_t* out, size_t M, size_t N,
+                              size_t K, float scale_a, float scale_b, void* workspace, size_t workspace_bytes,
+                              hif8_stream_t stream);
+hif8_status hif8_gemm_ws_f16(const uint8_t* a_codes, const uint8_t* b_codes, uint16_t* out, size_t M, size_t N,
+                             size_t K, float scale_a, float scale_b, void* workspace, size_t workspace_bytes,
+                             hif8_stream_t stream);
+hif8_status hif8_gemm_ws_sqerr(const uint8_t* a_codes, const uint8_t* b_codes, const float* ref, size_t M, size_t N,
+                               size_t K, float scale_a, float scale_b, double* d_err, void* workspace,
+                               size_t workspace_bytes, hif8_stream_t stream);
+
+/*
  * Algorithm 1 (HiF8 calibration with per-tensor scaling) for ONE layer: given the layer's
  * high-precision input a [M, K], weight w [N, K] (K contiguous in both) and high-precision
  * output o_ref [M, N] (FP32), try every pair of power-of-two scales 2^Ea, 2^Ew with

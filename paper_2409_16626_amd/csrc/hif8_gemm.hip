@@ -324,6 +324,39 @@ static hif8_status gemm_dispatch(const uint8_t* A, const uint8_t* B, void* out, 
   return launch_tiled<2, 2, 2, 2, 32, EPI>(A, B, out, ref, err, m, n, k, descale, lut, st);
 }
 
+// hif8_gemm_* through a workspace: expand both operands, then the expanded-operand kernel.
+static size_t gemm_ws_bytes(size_t M, size_t N, size_t K) {
+  if (M == 0 || N == 0 || K == 0) return 0;
+  const size_t ld = expanded_ld(K);
+  if (ld > kMaxLd || M > 0x7FFFFFFFu || N > 0x7FFFFFFFu) return 0;
+  return 2 * (M + N) * ld;
+}
+
+template <int EPI>
+static hif8_status gemm_ws(const uint8_t* A, const uint8_t* B, void* out, const float* ref, double* err, size_t M,
+                           size_t N, size_t K, float scale_a, float scale_b, void* ws, size_t ws_bytes, hipStream_t st) {
+  const size_t need = gemm_ws_bytes(M, N, K);
+  if (need == 0)  // nothing to expand, or a shape beyond the expanded-operand kernel's limits
+    return gemm_dispatch<EPI>(A, B, out, ref, err, M, N, K, scale_a, scale_b, st);
+  float inv_a = 1.0f, inv_b = 1.0f;
+  if (!valid_scale(scale_a, &inv_a) || !valid_scale(scale_b, &inv_b)) return HIF8_ERR_SCALE;
+  volatile float ds = inv_a * inv_b;
+  const float descale = ds;
+  if (!(descale > 0.0f) || std::isinf(descale)) return HIF8_ERR_SCALE;
+  if (!A || !B || !ws) return HIF8_ERR_NULL;
+  if (EPI == EPI_ERR ? (!ref || !err) : !out) return HIF8_ERR_NULL;
+  if (ws_bytes < need || !aligned_to(ws, 16)) return HIF8_ERR_ARG;
+  if (EPI == EPI_ERR && !aligned_to(err, 8)) return HIF8_ERR_ARG;
+  const size_t ld = expanded_ld(K);
+  uint16_t* xa = reinterpret_cast<uint16_t*>(ws);
+  uint16_t* xb = xa + M * ld;  // M * ld * 2 bytes is a multiple of 128: still 16-byte aligned
+  hif8_status s = expand_rows(A, M, K, xa, ld, st);
+  if (s != HIF8_OK) return s;
+  s = expand_rows(B, N, K, xb, ld, st);
+  if (s != HIF8_OK) return s;
+  return gemm_expanded<EPI>(xa, xb, out, ref, err, M, N, ld, descale, st, Batch{0u, 0, 0, 0}, 1u);
+}
+
 // position of the smallest finite entry of err[rows * cols] -> best[0] = e_row_lo + row,
 // best[1] = e_col_lo + col (first minimum in row-major order; {e_row_lo, e_col_lo} if none is finite)
 __global__ void k_argmin_pair(const double* __restrict__ err, int rows, int cols, int e_row_lo, int e_col_lo,
@@ -428,6 +461,29 @@ HIF8_DEFINE_CALIBRATE(f32, float, kSrcF32)
 HIF8_DEFINE_CALIBRATE(bf16, uint16_t, kSrcBF16)
 HIF8_DEFINE_CALIBRATE(f16, uint16_t, kSrcF16)
 #undef HIF8_DEFINE_CALIBRATE
+
+size_t hif8_gemm_workspace_bytes(size_t M, size_t N, size_t K) { return gemm_ws_bytes(M, N, K); }
+hif8_status hif8_gemm_ws_f32(const uint8_t* a_codes, const uint8_t* b_codes, float* out, size_t M, size_t N, size_t K,
+                             float scale_a, float scale_b, void* workspace, size_t workspace_bytes, hif8_stream_t stream) {
+  return gemm_ws<EPI_F32>(a_codes, b_codes, out, nullptr, nullptr, M, N, K, scale_a, scale_b, workspace, workspace_bytes,
+                          (hipStream_t)stream);
+}
+hif8_status hif8_gemm_ws_bf16(const uint8_t* a_codes, const uint8_t* b_codes, uint16_t* out, size_t M, size_t N, size_t K,
+                              float scale_a, float scale_b, void* workspace, size_t workspace_bytes, hif8_stream_t stream) {
+  return gemm_ws<EPI_BF16>(a_codes, b_codes, out, nullptr, nullptr, M, N, K, scale_a, scale_b, workspace, workspace_bytes,
+                           (hipStream_t)stream);
+}
+hif8_status hif8_gemm_ws_f16(const uint8_t* a_codes, const uint8_t* b_codes, uint16_t* out, size_t M, size_t N, size_t K,
+                             float scale_a, float scale_b, void* workspace, size_t workspace_bytes, hif8_stream_t stream) {
+  return gemm_ws<EPI_F16>(a_codes, b_codes, out, nullptr, nullptr, M, N, K, scale_a, scale_b, workspace, workspace_bytes,
+                          (hipStream_t)stream);
+}
+hif8_status hif8_gemm_ws_sqerr(const uint8_t* a_codes, const uint8_t* b_codes, const float* ref, size_t M, size_t N,
+                               size_t K, float scale_a, float scale_b, double* d_err, void* workspace,
+                               size_t workspace_bytes, hif8_stream_t stream) {
+  return gemm_ws<EPI_ERR>(a_codes, b_codes, nullptr, ref, d_err, M, N, K, scale_a, scale_b, workspace, workspace_bytes,
+                          (hipStream_t)stream);
+}
 
 hif8_status hif8_gemm_f32(const uint8_t* a_codes, const uint8_t* b_codes, float* out, size_t M, size_t N, size_t K,
                           float scale_a, float scale_b, hif8_stream_t stream) {

@@ -123,6 +123,11 @@ _SIGS = {
     "hif8_gemm_bf16": ([_vp, _vp, _vp, _sz, _sz, _sz, _f, _f, _vp], _i),
     "hif8_gemm_f16": ([_vp, _vp, _vp, _sz, _sz, _sz, _f, _f, _vp], _i),
     "hif8_gemm_sqerr": ([_vp, _vp, _vp, _sz, _sz, _sz, _f, _f, _vp, _vp], _i),
+    "hif8_gemm_workspace_bytes": ([_sz, _sz, _sz], _sz),
+    "hif8_gemm_ws_f32": ([_vp, _vp, _vp, _sz, _sz, _sz, _f, _f, _vp, _sz, _vp], _i),
+    "hif8_gemm_ws_bf16": ([_vp, _vp, _vp, _sz, _sz, _sz, _f, _f, _vp, _sz, _vp], _i),
+    "hif8_gemm_ws_f16": ([_vp, _vp, _vp, _sz, _sz, _sz, _f, _f, _vp, _sz, _vp], _i),
+    "hif8_gemm_ws_sqerr": ([_vp, _vp, _vp, _sz, _sz, _sz, _f, _f, _vp, _vp, _sz, _vp], _i),
     "hif8_gemm_set_variant": ([_i], _i),
     "hif8_calibrate_workspace_bytes": ([_sz, _sz, _sz, _i, _i], _sz),
     "hif8_expanded_ld": ([_sz], _sz),
@@ -491,6 +496,34 @@ def hif8_gemm_bf16(a_codes, b_codes, out, M, N, K, scale_a=1.0, scale_b=1.0, str
 
 def hif8_gemm_f16(a_codes, b_codes, out, M, N, K, scale_a=1.0, scale_b=1.0, stream=None):
     _check(lib.hif8_gemm_f16(_ptr(a_codes), _ptr(b_codes), _ptr(out), M, N, K, scale_a, scale_b, _stream(stream)))
+
+
+def hif8_gemm_workspace_bytes(M, N, K):
+    return lib.hif8_gemm_workspace_bytes(M, N, K)
+
+
+def _ws_bytes(workspace, workspace_bytes):
+    if workspace_bytes is not None:
+        return workspace_bytes
+    return 0 if workspace is None or isinstance(workspace, int) else workspace.numel() * workspace.element_size()
+
+
+def _def_gemm_ws(sfx):
+    fn = getattr(lib, "hif8_gemm_ws_" + sfx)
+
+    def gemm_ws(a_codes, b_codes, out, M, N, K, workspace, scale_a=1.0, scale_b=1.0, stream=None, workspace_bytes=None):
+        _check(fn(_ptr(a_codes), _ptr(b_codes), _ptr(out), M, N, K, scale_a, scale_b, _ptr(workspace),
+                  _ws_bytes(workspace, workspace_bytes), _stream(stream)))
+
+    return gemm_ws
+
+
+hif8_gemm_ws_f32, hif8_gemm_ws_bf16, hif8_gemm_ws_f16 = _def_gemm_ws("f32"), _def_gemm_ws("bf16"), _def_gemm_ws("f16")
+
+
+def hif8_gemm_ws_sqerr(a_codes, b_codes, ref, M, N, K, scale_a, scale_b, d_err, workspace, stream=None, workspace_bytes=None):
+    _check(lib.hif8_gemm_ws_sqerr(_ptr(a_codes), _ptr(b_codes), _ptr(ref), M, N, K, scale_a, scale_b, _ptr(d_err),
+                                  _ptr(workspace), _ws_bytes(workspace, workspace_bytes), _stream(stream)))
 
 
 def hif8_gemm_sqerr(a_codes, b_codes, ref, M, N, K, scale_a, scale_b, d_err, stream=None):

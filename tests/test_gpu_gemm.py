@@ -212,3 +212,68 @@ def test_calibrate_layer_matches_algorithm_1_oracle(h, kind):
     with pytest.raises(Hif8Error):
         getattr(h, "hif8_calibrate_layer_" + kind)(tx, tw, torch.from_numpy(o_ref).to(dev()), M, N, K, -4, 10, -4, 10,
                                                    orc.RM_TA, ws, nbytes - 1, err, best)
+
+
+@pytest.mark.parametrize("M,N,K", [(100, 70, 50), (257, 129, 80), (300, 520, 4096), (512, 768, 200), (33, 17, 1)])
+def test_gemm_with_workspace_matches_oracle_and_expanded_kernel(h, M, N, K):
+    """hif8_gemm_ws_*: expand into the workspace, then the expanded-operand kernel.  Any K and alignment; the
+    result is that of hif8_gemm_expanded_* bit for bit, and within the summation bound of the oracle."""
+    rng = np.random.default_rng(M + 3 * N + 7 * K)
+    ca, cb = random_codes(rng, (M, K), "cast_normal"), random_codes(rng, (N, K), "cast_normal")
+    pad = torch.zeros(M * K + 1, dtype=torch.uint8, device=dev())
+    a = pad[1:]                                              # a code matrix that is not 16-byte aligned
+    a.copy_(torch.from_numpy(ca).reshape(-1).to(dev()))
+    b = torch.from_numpy(cb).to(dev())
+    need = h.hif8_gemm_workspace_bytes(M, N, K)
+    ld = h.hif8_expanded_ld(K)
+    assert need == 2 * (M + N) * ld
+    ws = torch.empty(need, dtype=torch.uint8, device=dev())
+    out = torch.full((M, N), 7.0, dtype=torch.float32, device=dev())
+    h.hif8_gemm_ws_f32(a, b, out, M, N, K, ws, 8.0, 0.5)
+    torch.cuda.synchronize()
+    check(out.cpu().numpy(), ca, cb, 8.0, 0.5)
+    xa = torch.empty(M, ld, dtype=torch.bfloat16, device=dev())
+    xb = torch.empty(N, ld, dtype=torch.bfloat16, device=dev())
+    h.hif8_expand_bf16(torch.from_numpy(ca).to(dev()), M, K, xa, ld)
+    h.hif8_expand_bf16(b, N, K, xb, ld)
+    ref = torch.empty_like(out)
+    h.hif8_gemm_expanded_f32(xa, xb, ref, M, N, K, ld, 8.0, 0.5)
+    assert torch.equal(out.view(torch.int32), ref.view(torch.int32))
+    # the narrower outputs and the error epilogue
+    ob = torch.empty(M, N, dtype=torch.bfloat16, device=dev())
+    rb = torch.empty_like(ob)
+    h.hif8_gemm_ws_bf16(a, b, ob, M, N, K, ws, 8.0, 0.5)
+    h.hif8_gemm_expanded_bf16(xa, xb, rb, M, N, K, ld, 8.0, 0.5)
+    assert torch.equal(ob.view(torch.int16), rb.view(torch.int16))
+    oh = torch.empty(M, N, dtype=torch.float16, device=dev())
+    rh = torch.empty_like(oh)
+    h.hif8_gemm_ws_f16(a, b, oh, M, N, K, ws, 8.0, 0.5)
+    h.hif8_gemm_expanded_f16(xa, xb, rh, M, N, K, ld, 8.0, 0.5)
+    assert torch.equal(oh.view(torch.int16), rh.view(torch.int16))
+    target = (out * 1.01).contiguous()
+    e1 = torch.zeros(1, dtype=torch.float64, device=dev())
+    e2 = torch.zeros(1, dtype=torch.float64, device=dev())
+    h.hif8_gemm_ws_sqerr(a, b, target, M, N, K, 8.0, 0.5, e1, ws)
+    h.hif8_gemm_expanded_sqerr(xa, xb, target, M, N, K, ld, 8.0, 0.5, e2)
+    want = float(((out.double() - target.double()) ** 2).sum())
+    assert abs(e1.item() - want) <= 1e-9 * want and abs(e1.item() - e2.item()) <= 1e-12 * want
+
+
+def test_gemm_with_workspace_argument_checks(h):
+    M, N, K = 64, 48, 32
+    a = torch.zeros(M, K, dtype=torch.uint8, device=dev())
+    b = torch.zeros(N, K, dtype=torch.uint8, device=dev())
+    out = torch.full((M, N), 3.0, dtype=torch.float32, device=dev())
+    need = h.hif8_gemm_workspace_bytes(M, N, K)
+    ws = torch.empty(need + 16, dtype=torch.uint8, device=dev())
+    assert h.lib.hif8_gemm_ws_f32(a.data_ptr(), b.data_ptr(), out.data_ptr(), M, N, K, 1.0, 1.0, ws.data_ptr(), need - 1, None) == -5
+    assert h.lib.hif8_gemm_ws_f32(a.data_ptr(), b.data_ptr(), out.data_ptr(), M, N, K, 1.0, 1.0, None, need, None) == -1
+    assert h.lib.hif8_gemm_ws_f32(a.data_ptr(), b.data_ptr(), out.data_ptr(), M, N, K, 1.0, 1.0, ws.data_ptr() + 8, need, None) == -5
+    assert h.lib.hif8_gemm_ws_f32(a.data_ptr(), b.data_ptr(), out.data_ptr(), M, N, K, 0.0, 1.0, ws.data_ptr(), need, None) == -3
+    torch.cuda.synchronize()
+    assert torch.all(out == 3.0)                             # nothing was enqueued by the refused calls
+    # K = 0: no workspace needed, the product is a matrix of zeros
+    assert h.hif8_gemm_workspace_bytes(M, N, 0) == 0
+    h.hif8_gemm_ws_f32(a, b, out, M, N, 0, None)
+    torch.cuda.synchronize()
+    assert torch.all(out == 0.0)
