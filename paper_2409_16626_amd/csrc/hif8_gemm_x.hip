@@ -41,8 +41,6 @@ constexpr int kWaitLgkm0 = 0xC07F;        // lgkmcnt(0)
 constexpr int kWaitVm0Lgkm0 = 0x0070;     // vmcnt(0) lgkmcnt(0)
 constexpr int kWaitVm0 = 0x0F70;          // vmcnt(0)
 constexpr int kRsrcFlags = 0x00020000;    // word 3 of a raw (unstructured, untyped) buffer descriptor on gfx9-family parts
-constexpr uint32_t kXcds = 8;             // accelerator dies, each with an L2 of its own
-constexpr uint32_t kGroupM = 8;           // tile rows per group of the tile order
 
 template <int WM, int WN, int TM, int TN, int EPI, int FINE = 0>
 __global__ void __launch_bounds__(64 * WM * WN)
@@ -67,18 +65,8 @@ k_gemm_x(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, void* _
   const uint32_t tid = threadIdx.x, lane = tid & 63u;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: LDS destinations of the loads stay in SGPRs
   const uint32_t wm = wave / WN, wn = wave % WN;
-  // Workgroup -> tile.  The hardware deals consecutive workgroups round-robin over the 8 accelerator dies (XCDs),
-  // each with its own L2.  Workgroup b therefore takes tile number (b % 8) * per_xcd + b / 8 of a tile order that
-  // walks groups of kGroupM tile rows column by column: the workgroups resident on one die at a time then cover a
-  // compact kGroupM x (a few) block of tiles and share their operand panels in that die's L2, whatever tiles_n is.
-  const uint32_t tiles_m = (M - 1u) / BM + 1u;
-  const uint32_t n_tiles = tiles_m * tiles_n, per_xcd = (n_tiles + kXcds - 1u) / kXcds;
-  const uint32_t t_id = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
-  if (t_id >= n_tiles) return;  // grid = kXcds * per_xcd: the last die's share may be short (whole workgroup leaves)
-  const uint32_t grp = t_id / (kGroupM * tiles_n), first_m = grp * kGroupM;
-  const uint32_t grp_rows = tiles_m - first_m < kGroupM ? tiles_m - first_m : kGroupM;
-  const uint32_t in_grp = t_id - grp * (kGroupM * tiles_n);
-  const uint32_t tile_n = in_grp / grp_rows, tile_m = first_m + (in_grp - tile_n * grp_rows);
+  uint32_t tile_m, tile_n;  // in an order that keeps the workgroups of one die on neighbouring tiles
+  if (!tile_order(blockIdx.x, (M - 1u) / BM + 1u, tiles_n, &tile_m, &tile_n)) return;  // the whole workgroup leaves
   const uint32_t m0 = tile_m * BM, n0 = col_begin + tile_n * BN;  // the launch covers columns from col_begin on
 
   // Tile loads are buffer loads into LDS: one descriptor per operand panel of this workgroup (SGPRs), a
@@ -413,7 +401,7 @@ static hif8_status launch_x(const uint16_t* A, const uint16_t* B, void* out, con
   if (col_begin >= col_end) return HIF8_OK;
   const uint32_t tiles_m = (M + BM - 1) / BM, tiles_n = (col_end - col_begin + BN - 1) / BN;
   if ((uint64_t)tiles_m * tiles_n > 0x7FFFFFFFull || pairs == 0 || pairs > 65535u) return HIF8_ERR_ARG;
-  const uint32_t grid_x = (tiles_m * tiles_n + kXcds - 1u) / kXcds * kXcds;  // a whole number of workgroups per die
+  const uint32_t grid_x = tile_order_grid(tiles_m * tiles_n);  // a whole number of workgroups per die
   hipLaunchKernelGGL((k_gemm_x<WM, WN, TM, TN, EPI, FINE>), dim3(grid_x, pairs), dim3(64 * WM * WN), smem, st, A, B,
                      out, ref, err, M, N, ld, descale, tiles_n, col_begin, batch);
   return finish_launch();

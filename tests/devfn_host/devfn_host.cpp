@@ -68,6 +68,12 @@ void devfn_decode_bits(const uint8_t* codes, uint32_t* dst, size_t n) {
 void devfn_narrow_bf16(const uint32_t* bits, uint16_t* dst, size_t n) {
   for (size_t i = 0; i < n; ++i) dst[i] = (uint16_t)hif8dev::narrow_bf16(bits[i]);
 }
+// workgroup -> tile of the expanded-operand GEMM: tile_m * tiles_n + tile_n, or 0xFFFFFFFF for a workgroup without a tile
+uint32_t devfn_tile_order(uint32_t b, uint32_t tiles_m, uint32_t tiles_n) {
+  uint32_t tm = 0, tn = 0;
+  return hif8gemm::tile_order(b, tiles_m, tiles_n, &tm, &tn) ? tm * tiles_n + tn : 0xFFFFFFFFu;
+}
+uint32_t devfn_tile_order_grid(uint32_t n_tiles) { return hif8gemm::tile_order_grid(n_tiles); }
 // host-side launch planning of the GEMM kernels: returns the split column, or 0 for a single launch
 uint32_t devfn_ragged_round_split(size_t M, size_t N, size_t cus) {
   uint32_t split = 0;

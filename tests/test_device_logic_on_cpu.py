@@ -18,12 +18,13 @@ from oracle import hif8_oracle as orc
 HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "devfn_host", "devfn_host.cpp")
 HDR = os.path.join(HERE, "..", "paper_2409_16626_amd", "csrc", "hif8_device.hpp")
+HDR2 = os.path.join(HERE, "..", "paper_2409_16626_amd", "csrc", "hif8_gemm_split.hpp")
 LIB = os.path.join(HERE, "devfn_host", "libdevfn_host.so")
 
 
 @pytest.fixture(scope="module")
 def dev():
-    newest = max(os.path.getmtime(SRC), os.path.getmtime(HDR))
+    newest = max(os.path.getmtime(SRC), os.path.getmtime(HDR), os.path.getmtime(HDR2))
     if not os.path.exists(LIB) or os.path.getmtime(LIB) < newest:
         subprocess.run(["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-o", LIB, SRC], check=True)
     lib = ctypes.CDLL(LIB)
@@ -178,3 +179,28 @@ def test_gemm_ragged_round_split_plan(dev):
             assert big <= (tm * tn // cus) * cus                  # the large tiles fit the complete rounds
             assert (tn - s // 256) * tm * 2 <= cus                # what is left is at most half a round of large tiles
             assert tm * tn > cus and (tm * tn) % cus != 0
+
+
+def test_gemm_tile_order_is_a_bijection_and_compact_per_die(dev):
+    """Workgroup -> tile of the expanded-operand GEMM: every tile is taken exactly once, only workgroups at the
+    end of the grid go without one, and the 32 workgroups that run together on one die (b = die + 8 s for 32
+    consecutive s) touch few operand panels: at most 8 tile rows and, for full groups, 4 to 5 tile columns."""
+    dev.devfn_tile_order.restype = ctypes.c_uint32
+    dev.devfn_tile_order.argtypes = [ctypes.c_uint32] * 3
+    dev.devfn_tile_order_grid.restype = ctypes.c_uint32
+    dev.devfn_tile_order_grid.argtypes = [ctypes.c_uint32]
+    for tm, tn in [(1, 1), (1, 7), (3, 5), (8, 4), (32, 32), (32, 43), (16, 16), (9, 100), (100, 9), (13, 1), (64, 3)]:
+        n = tm * tn
+        grid = dev.devfn_tile_order_grid(n)
+        assert grid % 8 == 0 and n <= grid < n + 8
+        got = np.array([dev.devfn_tile_order(b, tm, tn) for b in range(grid)], np.int64)
+        have = got[got != 0xFFFFFFFF]
+        assert np.array_equal(np.sort(have), np.arange(n))
+        assert len(have) == n
+    # one round of 256 workgroups on the 32 x 43 tiles of the 8192 x 11008 product: panels per die
+    tm, tn = 32, 43
+    for die in range(8):
+        tiles = [dev.devfn_tile_order(die + 8 * s, tm, tn) for s in range(32)]
+        rows = {t // tn for t in tiles}
+        cols = {t % tn for t in tiles}
+        assert len(rows) <= 8 and len(cols) <= 5, (die, sorted(rows), sorted(cols))
