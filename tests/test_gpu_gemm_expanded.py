@@ -93,7 +93,8 @@ def check(got, ca, cb, sa, sb, extra_rel=0.0):
 
 # several tiles of both tile shapes, ragged edges in M, N and K, K below one K step, single elements
 SHAPES = [(32, 32, 16), (128, 128, 64), (100, 70, 48), (257, 129, 80), (1, 1, 1), (64, 300, 1040),
-          (256, 256, 32), (300, 520, 4096), (33, 17, 19), (513, 259, 130), (1100, 1300, 72), (4200, 4100, 64)]
+          (256, 256, 32), (300, 520, 4096), (33, 17, 19), (513, 259, 130), (1100, 1300, 72), (4200, 4100, 64),
+          (300, 300, 256), (260, 140, 320), (270, 520, 448)]   # 4, 5 and 7 K steps: every length of the loop's tail
 
 
 @pytest.mark.parametrize("variant", [0, 7, 8, 9, 10, 11])     # by problem size; 256 x 256 as 2 x 4 and 4 x 2 wavefronts; 128 x 128; hand-placed 2 x 2 and 2 x 4
