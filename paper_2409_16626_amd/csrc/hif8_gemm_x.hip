@@ -209,6 +209,7 @@ k_gemm_x(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, void* _
       for (int idx = 0; idx < NM; ++idx) {
         const int i = idx / TN, j = idx % TN;
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);  // the MFMA first: the memory instructions issue while it runs
         if (idx < NR) {
           if (s < 3) read_one(buf ^ 1, cur, s + 1, idx);
           else read_one(buf ^ 1, cur ^ 1, 0, idx);
