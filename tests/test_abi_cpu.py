@@ -97,6 +97,18 @@ def test_argument_validation_happens_on_the_host():
     assert L.hif8_gemm_expanded_f32(p, p, p, 16, 16, 64, 64, 1.0, float("nan"), None) == SCALE
     assert L.hif8_gemm_expanded_sqerr(p, p, p, 16, 16, 64, 64, 1.0, 1.0, p + 4, None) == ARG
     assert L.hif8_gemm_expanded_f32(p, p, p, 16, 0, 64, 64, 1.0, 1.0, None) == OK
+    # the code-operand GEMM through a workspace: both operands as bfloat16 with rows padded to 64 elements
+    assert L.hif8_gemm_workspace_bytes(16, 32, 100) == 2 * (16 + 32) * 128
+    assert [L.hif8_gemm_workspace_bytes(*mnk) for mnk in ((0, 32, 64), (16, 0, 64), (16, 32, 0))] == [0, 0, 0]
+    assert L.hif8_gemm_workspace_bytes(16, 16, (1 << 22) + 1) == 0               # beyond the expanded kernel's K: falls back, no workspace
+    gw = L.hif8_gemm_workspace_bytes(16, 16, 64)
+    assert L.hif8_gemm_ws_f32(p, p, p, 16, 16, 64, 1.0, 1.0, p, gw - 1, None) == ARG        # workspace too small
+    assert L.hif8_gemm_ws_bf16(p, p, p, 16, 16, 64, 1.0, 1.0, p + 4, gw, None) == ARG       # misaligned workspace
+    assert L.hif8_gemm_ws_f16(p, p, p, 16, 16, 64, 1.0, 1.0, None, gw, None) == NULL
+    assert L.hif8_gemm_ws_f32(p, p, None, 16, 16, 64, 1.0, 1.0, p, gw, None) == NULL
+    assert L.hif8_gemm_ws_f32(p, p, p, 16, 16, 64, -1.0, 1.0, p, gw, None) == SCALE
+    assert L.hif8_gemm_ws_sqerr(p, p, p, 16, 16, 64, 1.0, 1.0, p + 4, p, gw, None) == ARG   # misaligned fp64 accumulator
+    assert L.hif8_gemm_ws_f32(p, p, p, 0, 16, 64, 1.0, 1.0, None, 0, None) == OK
     assert L.hif8_diag_stream(p, p, 16, 5, None) == ARG
     assert L.hif8_diag_stream(p + 4, p, 16, 4, None) == ARG
     assert L.hif8_diag_stream(p, None, 16, 4, None) == NULL
