@@ -58,8 +58,7 @@ int hif8_get_tuning(int key); /* -1 for an unknown key */
  *   code-operand kernel (hif8_gemm_*):         5 = 256 x 256 x 32 workgroup tile, 8 wavefronts as 4 x 2 (the
  *                                              choice when there is such a tile for every compute unit);
  *                                              6 = 128 x 128 x 32, 4 wavefronts, two workgroups per CU
- *   expanded-operand kernel (hif8_gemm_expanded_*): 7 = 256 x 256 x 64, 8 wavefronts as 2 x 4; 8 = the same as
- *                                              4 x 2; 9 = 128 x 128 x 64, 4 wavefronts (the choice below one large
+ *   expanded-operand kernel (hif8_gemm_expanded_*): 9 = 128 x 128 x 64, 4 wavefronts (the choice below one large
  *                                              tile per compute unit); 10 = 256 x 256 x 64, 4 wavefronts as 2 x 2,
  *                                              memory instructions placed one by one between the MFMAs (the choice
  *                                              from two rounds of tiles on); 11 = the same placement with 8

@@ -432,7 +432,7 @@ using namespace hif8gemm;
 extern "C" {
 
 hif8_status hif8_gemm_set_variant(int variant) {
-  if (variant != 0 && (variant < 5 || variant > 11)) return HIF8_ERR_ARG;
+  if (variant != 0 && variant != 5 && variant != 6 && (variant < 9 || variant > 11)) return HIF8_ERR_ARG;
   if (variant == 0) {
     g_gemm_variant = 0;
     expanded_variant() = 0;

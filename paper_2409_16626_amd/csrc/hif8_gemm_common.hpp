@@ -102,9 +102,8 @@ inline size_t expanded_ld(size_t K) { return (K + kExpandK - 1) / kExpandK * kEx
 // Largest pitch the GEMM accepts: 256 rows x pitch x 2 bytes must fit the 32-bit lane offsets of its tile loads.
 constexpr size_t kMaxLd = (size_t)1 << 22;
 
-// tile layout of the expanded-operand kernel: 0 = by problem size, 7 = 256 x 256 with 8 wavefronts as 2 x 4,
-// 8 = the same as 4 x 2, 9 = 128 x 128 with 4 wavefronts, 10 / 11 = 256 x 256 as 2 x 2 / 2 x 4 wavefronts with the
-// hand-placed K step (set through hif8_gemm_set_variant)
+// tile layout of the expanded-operand kernel: 0 = by problem size, 9 = 128 x 128 with 4 wavefronts,
+// 10 / 11 = 256 x 256 as 2 x 2 / 2 x 4 wavefronts with the hand-placed K step (set through hif8_gemm_set_variant)
 int& expanded_variant();
 
 hif8_status expand_rows(const uint8_t* codes, size_t rows, size_t K, uint16_t* dst, size_t ld, hipStream_t st);

@@ -442,10 +442,6 @@ hif8_status gemm_expanded(const uint16_t* A, const uint16_t* B, void* out, const
     return launch_x<2, 2, 4, 4, EPI, 1>(A, B, out, ref, err, (uint32_t)M, (uint32_t)N, (uint32_t)ld, descale, st, batch, pairs);
   if (variant == 11)
     return launch_x<2, 4, 4, 2, EPI, 1>(A, B, out, ref, err, (uint32_t)M, (uint32_t)N, (uint32_t)ld, descale, st, batch, pairs);
-  if (variant == 7)
-    return launch_x<2, 4, 4, 2, EPI>(A, B, out, ref, err, (uint32_t)M, (uint32_t)N, (uint32_t)ld, descale, st, batch, pairs);
-  if (variant == 8)
-    return launch_x<4, 2, 2, 4, EPI>(A, B, out, ref, err, (uint32_t)M, (uint32_t)N, (uint32_t)ld, descale, st, batch, pairs);
   return launch_x<2, 2, 2, 2, EPI>(A, B, out, ref, err, (uint32_t)M, (uint32_t)N, (uint32_t)ld, descale, st, batch, pairs);
 }
 

@@ -97,7 +97,7 @@ SHAPES = [(32, 32, 16), (128, 128, 64), (100, 70, 48), (257, 129, 80), (1, 1, 1)
           (300, 300, 256), (260, 140, 320), (270, 520, 448)]   # 4, 5 and 7 K steps: every length of the loop's tail
 
 
-@pytest.mark.parametrize("variant", [0, 7, 8, 9, 10, 11])     # by problem size; 256 x 256 as 2 x 4 and 4 x 2 wavefronts; 128 x 128; hand-placed 2 x 2 and 2 x 4
+@pytest.mark.parametrize("variant", [0, 9, 10, 11])     # by problem size; 128 x 128; 256 x 256 as 2 x 2 and as 2 x 4 wavefronts
 @pytest.mark.parametrize("M,N,K", SHAPES)
 def test_gemm_expanded_f32_matches_oracle(h, variant, M, N, K):
     rng = np.random.default_rng(M * 7 + N * 3 + K)
@@ -126,7 +126,7 @@ def test_gemm_expanded_exact_when_sums_fit_24_bits(h, M, N, K):
     b, _ = expand(h, cb)
     want64 = go.gemm_hif8(ca, cb)
     out = torch.zeros(M, N, dtype=torch.float32, device=dev())
-    for variant in (7, 8, 9, 10, 11, 0):
+    for variant in (9, 10, 11, 0):
         h.hif8_gemm_set_variant(variant)
         out.zero_()
         h.hif8_gemm_expanded_f32(a, b, out, M, N, K, ld, 1.0, 1.0)
