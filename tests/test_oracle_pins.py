@@ -458,6 +458,22 @@ def test_encode_is_odd_symmetric_except_zero():
         assert np.all(cn[~nz] == 0) and np.all(cp[~nz] == 0)
 
 
+def test_deterministic_rounding_is_monotone():
+    """Round-to-nearest cannot reorder values: for x <= y the TA (and saturating TA) results satisfy Q(x) <= Q(y),
+    on random inputs over every binade and on a fine sweep across every boundary between two bands of the format
+    (powers of two where the mantissa width changes, the denormal range, underflow and overflow).  A misplaced band
+    boundary, a wrong mantissa width for one exponent or a carry that lands in the wrong exponent breaks it."""
+    rng = np.random.default_rng(61)
+    x = (rng.standard_normal(1 << 17) * np.exp2(rng.uniform(-30, 20, 1 << 17))).astype(np.float32)
+    edges = np.array([2.0 ** e for e in range(-26, 18)], np.float32)
+    fine = (edges[:, None] * np.linspace(0.75, 1.5, 193, dtype=np.float32)[None, :]).reshape(-1)
+    allx = np.sort(np.concatenate([x, fine, -fine, np.array([0.0], np.float32)]))
+    for mode in (TA, TA | SAT):
+        v = orc.decode_f32(orc.encode_f32(allx, 1.0, mode), 1.0).astype(np.float64)
+        assert not np.any(np.isnan(v))
+        assert np.all(v[1:] >= v[:-1]), mode
+
+
 def test_fake_quant_is_composition_and_idempotent():
     rng = np.random.default_rng(6)
     x = (rng.standard_normal(1 << 16) * np.exp2(rng.uniform(-25, 16, 1 << 16))).astype(np.float32)
